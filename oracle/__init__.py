@@ -1,0 +1,222 @@
+"""ctypes access to the CPU oracle in ``lmkan_oracle.c``.
+
+TEST INFRASTRUCTURE ONLY: the tests, the smoke check and the benchmark's
+CPU-baseline leg may import this package; the GPU library never does.  This
+file only marshals numpy arrays into the C functions; every piece of the
+method's arithmetic lives in the C file.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+import subprocess
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "lmkan_oracle.c")
+
+F32, F16, BF16 = 0, 1, 2
+
+
+def _lib_path(variant: str) -> str:
+    return os.path.join(_HERE, f"liblmkan_oracle{variant}.so")
+
+
+def build(variant: str = "", force: bool = False) -> str:
+    """Compile the oracle with gcc.  ``variant='_clip'`` builds the rejected
+    edge-cell reading (-DORACLE_CLIP_EDGE) that one test uses as a foil."""
+    out = _lib_path(variant)
+    if not force and os.path.exists(out) and os.path.getmtime(out) >= os.path.getmtime(_SRC):
+        return out
+    cmd = ["gcc", "-O2", "-std=c11", "-fPIC", "-shared", "-fopenmp", "-ffp-contract=off",
+           "-Wall", "-Wextra", "-o", out, _SRC, "-lm"]
+    if variant == "_clip":
+        cmd.insert(1, "-DORACLE_CLIP_EDGE")
+    elif variant != "":
+        raise ValueError(variant)
+    subprocess.run(cmd, check=True)
+    return out
+
+
+_dp = C.POINTER(C.c_double)
+_fp = C.POINTER(C.c_float)
+_ip = C.POINTER(C.c_int32)
+
+
+def _ptr(a: np.ndarray, t):
+    return a.ctypes.data_as(t)
+
+
+def _f32(a) -> np.ndarray:
+    return np.ascontiguousarray(a, dtype=np.float32)
+
+
+def _f64(a) -> np.ndarray:
+    return np.ascontiguousarray(a, dtype=np.float64)
+
+
+class Oracle:
+    """One loaded build of the oracle."""
+
+    def __init__(self, variant: str = ""):
+        self.lib = C.CDLL(build(variant))
+        L = self.lib
+        L.oracle_sigma.restype = C.c_double
+        L.oracle_sigma.argtypes = [C.c_double]
+        L.oracle_grid.argtypes = [C.c_int, _dp]
+        L.oracle_grid_f32.argtypes = [C.c_int, _fp]
+        L.oracle_locate.argtypes = [C.c_int, _fp, C.c_float]
+        L.oracle_locate_sigma.argtypes = [C.c_int, C.c_double]
+        L.oracle_basis.restype = C.c_double
+        L.oracle_basis.argtypes = [C.c_int, _dp, C.c_int, C.c_double]
+        L.oracle_eval2d_def.restype = C.c_double
+        L.oracle_eval2d_def.argtypes = [C.c_int, _dp, _dp, C.c_double, C.c_double]
+        L.oracle_preamble.argtypes = [C.c_int, _fp, C.c_float, C.c_float, _dp]
+        L.oracle_eval2d.restype = C.c_double
+        L.oracle_eval2d.argtypes = [C.c_int, _fp, _dp, C.c_float, C.c_float]
+        L.oracle_half_bits_to_double.restype = C.c_double
+        L.oracle_half_bits_to_double.argtypes = [C.c_uint16]
+        L.oracle_bf16_bits_to_double.restype = C.c_double
+        L.oracle_bf16_bits_to_double.argtypes = [C.c_uint16]
+        L.oracle_forward.argtypes = [C.c_int64, C.c_int, C.c_int, C.c_int, _fp, C.c_void_p,
+                                     C.c_int, _dp, C.c_int]
+        L.oracle_forward_def.argtypes = [C.c_int64, C.c_int, C.c_int, C.c_int, _fp, C.c_void_p,
+                                         C.c_int, _dp]
+        L.oracle_locate_batch.argtypes = [C.c_int64, C.c_int, C.c_int, _fp, _ip]
+        L.oracle_backward_input.argtypes = [C.c_int64, C.c_int, C.c_int, C.c_int, _fp, C.c_void_p,
+                                            C.c_int, _fp, _dp, C.c_int]
+        L.oracle_backward_coef_pair.argtypes = [C.c_int64, C.c_int, C.c_int, C.c_int, C.c_int,
+                                                _fp, _fp, _dp]
+
+    # ---- scalars and small pieces -------------------------------------
+    def sigma(self, x: float) -> float:
+        return self.lib.oracle_sigma(float(x))
+
+    def grid(self, G: int) -> np.ndarray:
+        E = np.empty(G + 1, dtype=np.float64)
+        if self.lib.oracle_grid(G, _ptr(E, _dp)):
+            raise ValueError("oracle_grid rejected G=%d" % G)
+        return E
+
+    def grid_f32(self, G: int) -> np.ndarray:
+        E = np.empty(G + 1, dtype=np.float32)
+        if self.lib.oracle_grid_f32(G, _ptr(E, _fp)):
+            raise ValueError("oracle_grid_f32 rejected G=%d" % G)
+        return E
+
+    def locate(self, G: int, E32: np.ndarray, x: float) -> int:
+        E32 = _f32(E32)
+        return self.lib.oracle_locate(G, _ptr(E32, _fp), float(np.float32(x)))
+
+    def locate_sigma(self, G: int, x: float) -> int:
+        return self.lib.oracle_locate_sigma(G, float(x))
+
+    def basis(self, G: int, E: np.ndarray, a: int, x: float) -> float:
+        E = _f64(E)
+        return self.lib.oracle_basis(G, _ptr(E, _dp), a, float(x))
+
+    def eval2d_def(self, G: int, E: np.ndarray, P2: np.ndarray, x1: float, x2: float) -> float:
+        E, P2 = _f64(E), _f64(P2)
+        assert P2.shape == (G + 1, G + 1)
+        return self.lib.oracle_eval2d_def(G, _ptr(E, _dp), _ptr(P2, _dp), float(x1), float(x2))
+
+    def preamble(self, G: int, E32: np.ndarray, x1: float, x2: float):
+        E32 = _f32(E32)
+        out = np.empty(4, dtype=np.float64)
+        cell = self.lib.oracle_preamble(G, _ptr(E32, _fp), float(np.float32(x1)),
+                                        float(np.float32(x2)), _ptr(out, _dp))
+        return cell, out
+
+    def eval2d(self, G: int, E32: np.ndarray, P2: np.ndarray, x1: float, x2: float) -> float:
+        E32, P2 = _f32(E32), _f64(P2)
+        assert P2.shape == (G + 1, G + 1)
+        return self.lib.oracle_eval2d(G, _ptr(E32, _fp), _ptr(P2, _dp), float(np.float32(x1)),
+                                      float(np.float32(x2)))
+
+    def half_bits_to_double(self, h: int) -> float:
+        return self.lib.oracle_half_bits_to_double(h)
+
+    def bf16_bits_to_double(self, b: int) -> float:
+        return self.lib.oracle_bf16_bits_to_double(b)
+
+    # ---- layer --------------------------------------------------------
+    @staticmethod
+    def _coef(P: np.ndarray, dtype: int, G: int, K: int, N_out: int) -> np.ndarray:
+        want = {F32: np.float32, F16: np.uint16, BF16: np.uint16}[dtype]
+        if dtype == F16 and P.dtype == np.float16:
+            P = P.view(np.uint16)
+        P = np.ascontiguousarray(P)
+        assert P.dtype == want, (P.dtype, want)
+        assert P.shape == (G + 1, G + 1, K, N_out), P.shape
+        return P
+
+    def forward(self, x, P, G: int, dtype: int = F32, threads: int = 1) -> np.ndarray:
+        x = _f32(x)
+        B, N_in = x.shape
+        N_out = P.shape[-1]
+        P = self._coef(P, dtype, G, N_in // 2, N_out)
+        y = np.empty((B, N_out), dtype=np.float64)
+        if self.lib.oracle_forward(B, N_in, N_out, G, _ptr(x, _fp), P.ctypes.data, dtype,
+                                   _ptr(y, _dp), threads):
+            raise ValueError("oracle_forward rejected its arguments")
+        return y
+
+    def forward_def(self, x, P, G: int, dtype: int = F32) -> np.ndarray:
+        x = _f32(x)
+        B, N_in = x.shape
+        N_out = P.shape[-1]
+        P = self._coef(P, dtype, G, N_in // 2, N_out)
+        y = np.empty((B, N_out), dtype=np.float64)
+        if self.lib.oracle_forward_def(B, N_in, N_out, G, _ptr(x, _fp), P.ctypes.data, dtype,
+                                       _ptr(y, _dp)):
+            raise ValueError("oracle_forward_def rejected its arguments")
+        return y
+
+    def locate_batch(self, x, G: int) -> np.ndarray:
+        x = _f32(x)
+        B, N_in = x.shape
+        cell = np.empty((B, N_in // 2), dtype=np.int32)
+        if self.lib.oracle_locate_batch(B, N_in, G, _ptr(x, _fp), _ptr(cell, _ip)):
+            raise ValueError("oracle_locate_batch rejected its arguments")
+        return cell
+
+    def backward_input(self, x, P, gy, G: int, dtype: int = F32, threads: int = 1) -> np.ndarray:
+        x, gy = _f32(x), _f32(gy)
+        B, N_in = x.shape
+        N_out = P.shape[-1]
+        assert gy.shape == (B, N_out)
+        P = self._coef(P, dtype, G, N_in // 2, N_out)
+        gx = np.empty((B, N_in), dtype=np.float64)
+        if self.lib.oracle_backward_input(B, N_in, N_out, G, _ptr(x, _fp), P.ctypes.data, dtype,
+                                          _ptr(gy, _fp), _ptr(gx, _dp), threads):
+            raise ValueError("oracle_backward_input rejected its arguments")
+        return gx
+
+    def backward_coef_pair(self, x, gy, G: int, k: int) -> np.ndarray:
+        x, gy = _f32(x), _f32(gy)
+        B, N_in = x.shape
+        N_out = gy.shape[1]
+        assert gy.shape[0] == B
+        gPk = np.empty((G + 1, G + 1, N_out), dtype=np.float64)
+        if self.lib.oracle_backward_coef_pair(B, N_in, N_out, G, k, _ptr(x, _fp), _ptr(gy, _fp),
+                                              _ptr(gPk, _dp)):
+            raise ValueError("oracle_backward_coef_pair rejected its arguments")
+        return gPk
+
+    def backward_coef(self, x, gy, G: int) -> np.ndarray:
+        """All pairs, assembled into the layout of Alg. 1: [G+1][G+1][K][N_out]."""
+        x = _f32(x)
+        K = x.shape[1] // 2
+        slabs = [self.backward_coef_pair(x, gy, G, k) for k in range(K)]
+        return np.stack(slabs, axis=2)
+
+
+_default = None
+
+
+def get() -> Oracle:
+    global _default
+    if _default is None:
+        _default = Oracle("")
+    return _default

@@ -1,0 +1,512 @@
+/*
+ * CPU oracle for the 2-D lmKAN layer ("Lookup multivariate Kolmogorov-Arnold
+ * Networks", arXiv 2509.07103).
+ *
+ * THIS IS TEST INFRASTRUCTURE.  It is a plain, slow, double-precision
+ * restatement of what the paper defines, kept deliberately free of blocking,
+ * fusion, SIMD or any other optimisation so that it can be checked against
+ * the paper by eye.  It shares no code with the GPU library and must only be
+ * used by the tests, the smoke check and the benchmark's CPU-baseline leg.
+ *
+ * Parity status: every function below is pinned by CPU tests against facts
+ * the paper or the mathematics fix (grid = percentile levels of sigma, weights
+ * summing to one, node interpolation, exact bilinear / ReLU reproduction,
+ * brute-force evaluation of every basis function, finite differences, a
+ * hand-worked example).  Nothing here is "parity unpinned".
+ *
+ * Conventions (Sec. 3.1, Alg. 1, App. B):
+ *   G        number of grid intervals per axis (G >= 3)
+ *   E[0..G]  extended grid: E[1..G-1] are the G-1 real grid points, E[0] and
+ *            E[G] are the left and right ghost points of App. B.
+ *   cell i   (0 <= i <= G-1) is [E[i], E[i+1]); cell 0 also holds everything
+ *            left of the left ghost, cell G-1 everything right of the right
+ *            ghost.
+ *   P        coefficient tensor [G+1][G+1][K][N_out], K = N_in/2, last index
+ *            fastest (Alg. 1 "Require").  P[a][b][k][j] multiplies
+ *            B_a(x_{2k}) * B_b(x_{2k+1}) in output j (Eq. 2, Eq. 3).
+ *
+ * Readings of the paper taken here:
+ *   - Edge intervals.  Alg. 1 / Alg. 3 leave them out "for brevity".  The same
+ *     two formulas are used in the edge cells, with the ghost point as the
+ *     outer grid value and no clipping, so every function is linear on the
+ *     two infinite intervals (App. B, last paragraph of "Edge cases" and the
+ *     paragraph on linear asymptotes) and w*ReLU(x) is reproduced exactly for
+ *     even G (App. F.1).  Compiling with -DORACLE_CLIP_EDGE selects the other
+ *     reading (edge hat functions cut to zero beyond the ghost); it exists
+ *     only so a test can show that it breaks the ReLU statement.
+ *   - The cell index is defined on the float32-rounded grid: i = number of
+ *     real grid points E32[k] (k = 1..G-1) that are <= x.  In exact
+ *     arithmetic this equals floor(sigma(x) * G) (Sec. 3.1 "Sigma grid");
+ *     defining it by comparison makes it an exact integer function of the
+ *     float32 input.  A point on a grid point belongs to the cell on its right.
+ *   - Weights use the float32-rounded grid promoted to double, so that this
+ *     file and a float32 implementation evaluate the same function.
+ */
+#include <math.h>
+#include <stddef.h>
+#include <stdint.h>
+#include <stdlib.h>
+#include <string.h>
+
+/* ------------------------------------------------------------------------ */
+/* sigma(x) and the grid                                                     */
+/* ------------------------------------------------------------------------ */
+
+/* App. B, Eq. 5 evaluated the way Alg. 2 does it: one exponential of -|x|. */
+double oracle_sigma(double x)
+{
+    double t = exp(-fabs(x));
+    if (x > 0.0)
+        return 1.0 - 0.5 * t;
+    return 0.5 * t;
+}
+
+/* Solve sigma(x) = p for 0 < p < 1 by inverting the two branches of Eq. 5. */
+static double sigma_inverse(double p)
+{
+    if (p <= 0.5)
+        return log(2.0 * p);
+    return -log(2.0 * (1.0 - p));
+}
+
+/*
+ * Extended grid in double (Sec. 3.1 "Sigma grid" + App. B "Edge cases").
+ * Real points: where sigma crosses the G-1 equispaced levels k/G.
+ * Ghost points: mirror the second real point about the first one on each side.
+ * The level is formed from integers so that the left and right halves are
+ * exact mirror images (2k <= G uses k, otherwise G-k).
+ */
+int oracle_grid(int G, double *E)
+{
+    if (G < 3 || E == NULL)
+        return 1;
+    for (int k = 1; k <= G - 1; ++k) {
+        if (2 * k <= G)
+            E[k] = sigma_inverse((double)k / (double)G);
+        else
+            E[k] = -sigma_inverse((double)(G - k) / (double)G);
+    }
+    E[0] = E[1] - (E[2] - E[1]);
+    E[G] = E[G - 1] + (E[G - 1] - E[G - 2]);
+    return 0;
+}
+
+/* The grid table as a float32 implementation sees it: round each entry once. */
+int oracle_grid_f32(int G, float *E32)
+{
+    double *E = (double *)malloc((size_t)(G + 1) * sizeof(double));
+    if (E == NULL || oracle_grid(G, E) != 0) {
+        free(E);
+        return 1;
+    }
+    for (int k = 0; k <= G; ++k)
+        E32[k] = (float)E[k];
+    free(E);
+    return 0;
+}
+
+/* Cell index by comparison against the real grid points (see header). */
+int oracle_locate(int G, const float *E32, float x)
+{
+    int i = 0;
+    for (int k = 1; k <= G - 1; ++k)
+        if (E32[k] <= x)
+            ++i;
+    return i;
+}
+
+/* Cell index the way Sec. 3.1 states it, in double: floor(sigma(x) G), kept in range. */
+int oracle_locate_sigma(int G, double x)
+{
+    int i = (int)floor(oracle_sigma(x) * (double)G);
+    if (i < 0)
+        i = 0;
+    if (i > G - 1)
+        i = G - 1;
+    return i;
+}
+
+/* ------------------------------------------------------------------------ */
+/* Basis functions from their description (no cell lookup)                   */
+/* ------------------------------------------------------------------------ */
+
+/*
+ * Value of the a-th one-dimensional basis function (0 <= a <= G) at x, on an
+ * arbitrary extended grid E, written from Sec. 3.1 "B-splines" and App. B
+ * "Edge cases":
+ *   a = 0, a = G : linear functions on the infinite intervals, zero at the
+ *                  outermost real grid point, one at the ghost point, same
+ *                  slope all the way to infinity, zero on the other side.
+ *   1 <= a <= G-1: hat centred on real point E[a]: rises 0 -> 1 from E[a-1]
+ *                  to E[a], falls 1 -> 0 from E[a] to E[a+1], zero elsewhere.
+ *                  For a = 1 the left neighbour is the left ghost, for
+ *                  a = G-1 the right neighbour is the right ghost, and under
+ *                  the reading taken here the outer branch keeps its slope
+ *                  past the ghost.
+ */
+double oracle_basis(int G, const double *E, int a, double x)
+{
+    if (a == 0)
+        return (x < E[1]) ? (E[1] - x) / (E[1] - E[0]) : 0.0;
+    if (a == G)
+        return (x >= E[G - 1]) ? (x - E[G - 1]) / (E[G] - E[G - 1]) : 0.0;
+
+    if (x < E[a]) {
+        /* rising branch */
+        int unbounded = (a == 1);
+#ifdef ORACLE_CLIP_EDGE
+        unbounded = 0;
+#endif
+        if (!unbounded && x < E[a - 1])
+            return 0.0;
+        return (x - E[a - 1]) / (E[a] - E[a - 1]);
+    } else {
+        /* falling branch */
+        int unbounded = (a == G - 1);
+#ifdef ORACLE_CLIP_EDGE
+        unbounded = 0;
+#endif
+        if (!unbounded && x >= E[a + 1])
+            return 0.0;
+        return (E[a + 1] - x) / (E[a + 1] - E[a]);
+    }
+}
+
+/*
+ * One two-dimensional function straight from Eq. 3: the full double sum over
+ * all (G+1)^2 products of one-dimensional basis functions.
+ * P2 is [G+1][G+1] row-major, first index belongs to x1.
+ */
+double oracle_eval2d_def(int G, const double *E, const double *P2, double x1, double x2)
+{
+    double f = 0.0;
+    for (int a = 0; a <= G; ++a) {
+        double Ba = oracle_basis(G, E, a, x1);
+        for (int b = 0; b <= G; ++b) {
+            double Bb = oracle_basis(G, E, b, x2);
+            f += P2[a * (G + 1) + b] * Ba * Bb;
+        }
+    }
+    return f;
+}
+
+/* ------------------------------------------------------------------------ */
+/* Preamble of Alg. 1 and the O(1) evaluation of Alg. 3                      */
+/* ------------------------------------------------------------------------ */
+
+typedef struct {
+    int i1, i2;         /* cell indices                                    */
+    double B00;         /* B_{i1,   i2  }(x1, x2)                           */
+    double B10;         /* B_{i1+1, i2  }(x1, x2)                           */
+    double B01;         /* B_{i1,   i2+1}(x1, x2)                           */
+    double B11;         /* B_{i1+1, i2+1}(x1, x2)                           */
+} preamble_t;
+
+#ifdef ORACLE_CLIP_EDGE
+/* Other reading of the edge cells: the hat of the outermost real point is cut
+ * at the ghost, so beyond a ghost only the linear edge function survives.   */
+static void clip_axis(int G, const float *E32, int i, double x, double *lo, double *hi)
+{
+    if (i == 0 && x < (double)E32[0])
+        *hi = 0.0;
+    if (i == G - 1 && x > (double)E32[G])
+        *lo = 0.0;
+}
+#endif
+
+/* Alg. 1 "Preamble": two cell indices and the four non-zero 2-D B-splines. */
+static preamble_t preamble(int G, const float *E32, float x1f, float x2f)
+{
+    preamble_t r;
+    double x1 = (double)x1f, x2 = (double)x2f;
+    r.i1 = oracle_locate(G, E32, x1f);
+    r.i2 = oracle_locate(G, E32, x2f);
+    double g1lo = (double)E32[r.i1], g1hi = (double)E32[r.i1 + 1];
+    double g2lo = (double)E32[r.i2], g2hi = (double)E32[r.i2 + 1];
+    double Ainv = 1.0 / ((g1hi - g1lo) * (g2hi - g2lo));
+    double a_lo = g1hi - x1, a_hi = x1 - g1lo; /* factors of B_{i1}, B_{i1+1} */
+    double b_lo = g2hi - x2, b_hi = x2 - g2lo; /* factors of B_{i2}, B_{i2+1} */
+#ifdef ORACLE_CLIP_EDGE
+    clip_axis(G, E32, r.i1, x1, &a_lo, &a_hi);
+    clip_axis(G, E32, r.i2, x2, &b_lo, &b_hi);
+#endif
+    r.B00 = a_lo * b_lo * Ainv;
+    r.B10 = a_hi * b_lo * Ainv;
+    r.B01 = a_lo * b_hi * Ainv;
+    r.B11 = a_hi * b_hi * Ainv;
+    return r;
+}
+
+/* Expose the preamble to tests: out = {B00, B10, B01, B11}, returns i1*G+i2. */
+int oracle_preamble(int G, const float *E32, float x1, float x2, double *out)
+{
+    preamble_t r = preamble(G, E32, x1, x2);
+    out[0] = r.B00;
+    out[1] = r.B10;
+    out[2] = r.B01;
+    out[3] = r.B11;
+    return r.i1 * G + r.i2;
+}
+
+/* Alg. 3: one standalone 2-D function with four terms.  P2 is [G+1][G+1]. */
+double oracle_eval2d(int G, const float *E32, const double *P2, float x1, float x2)
+{
+    preamble_t r = preamble(G, E32, x1, x2);
+    int W = G + 1;
+    double y = 0.0;
+    y += r.B00 * P2[r.i1 * W + r.i2];
+    y += r.B10 * P2[(r.i1 + 1) * W + r.i2];
+    y += r.B01 * P2[r.i1 * W + (r.i2 + 1)];
+    y += r.B11 * P2[(r.i1 + 1) * W + (r.i2 + 1)];
+    return y;
+}
+
+/* ------------------------------------------------------------------------ */
+/* Stored coefficient formats                                                */
+/* ------------------------------------------------------------------------ */
+
+enum { ORACLE_F32 = 0, ORACLE_F16 = 1, ORACLE_BF16 = 2 };
+
+/* IEEE binary16 bit pattern -> double, exactly. */
+double oracle_half_bits_to_double(uint16_t h)
+{
+    int sign = (h >> 15) & 1;
+    int e = (h >> 10) & 0x1f;
+    int m = h & 0x3ff;
+    double v;
+    if (e == 0)
+        v = ldexp((double)m, -24);                 /* zero and subnormals */
+    else if (e == 31)
+        v = (m == 0) ? INFINITY : NAN;
+    else
+        v = ldexp((double)(m + 1024), e - 25);     /* (1 + m/1024) 2^(e-15) */
+    return sign ? -v : v;
+}
+
+/* bfloat16 bit pattern -> double: it is the upper half of a float32. */
+double oracle_bf16_bits_to_double(uint16_t b)
+{
+    uint32_t u = (uint32_t)b << 16;
+    float f;
+    memcpy(&f, &u, sizeof f);
+    return (double)f;
+}
+
+static double coef_at(const void *P, int dtype, size_t idx)
+{
+    if (dtype == ORACLE_F32)
+        return (double)((const float *)P)[idx];
+    if (dtype == ORACLE_F16)
+        return oracle_half_bits_to_double(((const uint16_t *)P)[idx]);
+    return oracle_bf16_bits_to_double(((const uint16_t *)P)[idx]);
+}
+
+/* Offset of P[a][b][k][j] in the layout of Alg. 1. */
+static size_t p_index(int G, int K, int N_out, int a, int b, int k, int j)
+{
+    return (((size_t)a * (size_t)(G + 1) + (size_t)b) * (size_t)K + (size_t)k) * (size_t)N_out +
+           (size_t)j;
+}
+
+/* ------------------------------------------------------------------------ */
+/* Layer forward                                                             */
+/* ------------------------------------------------------------------------ */
+
+/*
+ * Alg. 1 for a batch: for every row, for every input pair run the preamble
+ * once, then four multiply-adds per output.
+ *   x  [B][N_in]  float32 (the same bits a GPU run reads)
+ *   P  [G+1][G+1][N_in/2][N_out] in `dtype` storage, decoded exactly
+ *   y  [B][N_out] double
+ * `threads` > 1 splits the rows over OpenMP threads (rows are independent).
+ */
+int oracle_forward(int64_t B, int N_in, int N_out, int G, const float *x, const void *P, int dtype,
+                   double *y, int threads)
+{
+    if (N_in < 2 || (N_in & 1) || N_out < 1 || G < 3)
+        return 1;
+    int K = N_in / 2;
+    float *E32 = (float *)malloc((size_t)(G + 1) * sizeof(float));
+    if (E32 == NULL || oracle_grid_f32(G, E32) != 0) {
+        free(E32);
+        return 1;
+    }
+    if (threads < 1)
+        threads = 1;
+#pragma omp parallel for num_threads(threads) schedule(static)
+    for (int64_t n = 0; n < B; ++n) {
+        const float *xr = x + n * N_in;
+        double *yr = y + n * N_out;
+        for (int j = 0; j < N_out; ++j)
+            yr[j] = 0.0;
+        for (int k = 0; k < K; ++k) {
+            preamble_t r = preamble(G, E32, xr[2 * k], xr[2 * k + 1]);
+            for (int j = 0; j < N_out; ++j) {
+                yr[j] += r.B00 * coef_at(P, dtype, p_index(G, K, N_out, r.i1, r.i2, k, j));
+                yr[j] += r.B10 * coef_at(P, dtype, p_index(G, K, N_out, r.i1 + 1, r.i2, k, j));
+                yr[j] += r.B01 * coef_at(P, dtype, p_index(G, K, N_out, r.i1, r.i2 + 1, k, j));
+                yr[j] += r.B11 * coef_at(P, dtype, p_index(G, K, N_out, r.i1 + 1, r.i2 + 1, k, j));
+            }
+        }
+    }
+    free(E32);
+    return 0;
+}
+
+/*
+ * The same layer straight from its definition (Eq. 2 with Eq. 3 for every
+ * f_qp): all (G+1)^2 basis products per function, no cell lookup.  Uses the
+ * float32-rounded grid promoted to double so it describes the same function
+ * as oracle_forward.  Meant for tiny layers only.
+ */
+int oracle_forward_def(int64_t B, int N_in, int N_out, int G, const float *x, const void *P,
+                       int dtype, double *y)
+{
+    if (N_in < 2 || (N_in & 1) || N_out < 1 || G < 3)
+        return 1;
+    int K = N_in / 2;
+    float *E32 = (float *)malloc((size_t)(G + 1) * sizeof(float));
+    double *E = (double *)malloc((size_t)(G + 1) * sizeof(double));
+    double *P2 = (double *)malloc((size_t)(G + 1) * (size_t)(G + 1) * sizeof(double));
+    if (!E32 || !E || !P2 || oracle_grid_f32(G, E32) != 0) {
+        free(E32);
+        free(E);
+        free(P2);
+        return 1;
+    }
+    for (int a = 0; a <= G; ++a)
+        E[a] = (double)E32[a];
+    for (int64_t n = 0; n < B; ++n) {
+        for (int q = 0; q < N_out; ++q) {
+            double acc = 0.0;
+            for (int p = 0; p < K; ++p) {
+                for (int a = 0; a <= G; ++a)
+                    for (int b = 0; b <= G; ++b)
+                        P2[a * (G + 1) + b] = coef_at(P, dtype, p_index(G, K, N_out, a, b, p, q));
+                acc += oracle_eval2d_def(G, E, P2, (double)x[n * N_in + 2 * p],
+                                         (double)x[n * N_in + 2 * p + 1]);
+            }
+            y[n * N_out + q] = acc;
+        }
+    }
+    free(E32);
+    free(E);
+    free(P2);
+    return 0;
+}
+
+/* Cell index of every (row, pair): cell[n][k] = i1 * G + i2. */
+int oracle_locate_batch(int64_t B, int N_in, int G, const float *x, int32_t *cell)
+{
+    if (N_in < 2 || (N_in & 1) || G < 3)
+        return 1;
+    int K = N_in / 2;
+    float *E32 = (float *)malloc((size_t)(G + 1) * sizeof(float));
+    if (E32 == NULL || oracle_grid_f32(G, E32) != 0) {
+        free(E32);
+        return 1;
+    }
+    for (int64_t n = 0; n < B; ++n)
+        for (int k = 0; k < K; ++k) {
+            int i1 = oracle_locate(G, E32, x[n * N_in + 2 * k]);
+            int i2 = oracle_locate(G, E32, x[n * N_in + 2 * k + 1]);
+            cell[n * K + k] = i1 * G + i2;
+        }
+    free(E32);
+    return 0;
+}
+
+/* ------------------------------------------------------------------------ */
+/* Layer backward (the paper trains with its kernels but prints no formulas; */
+/* these are the derivatives of Alg. 1's four-term sum)                      */
+/* ------------------------------------------------------------------------ */
+
+/*
+ * Gradient with respect to the inputs for a batch.
+ * Inside a cell the four weights are products of one factor in x1 and one in
+ * x2, each linear, so
+ *   dB00/dx1 = -(E[i2+1]-x2) Ainv,  dB10/dx1 = +(E[i2+1]-x2) Ainv,
+ *   dB01/dx1 = -(x2-E[i2])  Ainv,  dB11/dx1 = +(x2-E[i2])  Ainv,
+ * and symmetrically for x2.  On a grid point the derivative of the cell chosen
+ * by the locate rule (the one on the right) is returned.
+ *   gy [B][N_out] float32, gx [B][N_in] double.
+ */
+int oracle_backward_input(int64_t B, int N_in, int N_out, int G, const float *x, const void *P,
+                          int dtype, const float *gy, double *gx, int threads)
+{
+    if (N_in < 2 || (N_in & 1) || N_out < 1 || G < 3)
+        return 1;
+    int K = N_in / 2;
+    float *E32 = (float *)malloc((size_t)(G + 1) * sizeof(float));
+    if (E32 == NULL || oracle_grid_f32(G, E32) != 0) {
+        free(E32);
+        return 1;
+    }
+    if (threads < 1)
+        threads = 1;
+#pragma omp parallel for num_threads(threads) schedule(static)
+    for (int64_t n = 0; n < B; ++n) {
+        const float *xr = x + n * N_in;
+        const float *gyr = gy + n * N_out;
+        for (int k = 0; k < K; ++k) {
+            double x1 = (double)xr[2 * k], x2 = (double)xr[2 * k + 1];
+            int i1 = oracle_locate(G, E32, xr[2 * k]);
+            int i2 = oracle_locate(G, E32, xr[2 * k + 1]);
+            double g1lo = (double)E32[i1], g1hi = (double)E32[i1 + 1];
+            double g2lo = (double)E32[i2], g2hi = (double)E32[i2 + 1];
+            double Ainv = 1.0 / ((g1hi - g1lo) * (g2hi - g2lo));
+            double d1 = 0.0, d2 = 0.0;
+            for (int j = 0; j < N_out; ++j) {
+                double c00 = coef_at(P, dtype, p_index(G, K, N_out, i1, i2, k, j));
+                double c10 = coef_at(P, dtype, p_index(G, K, N_out, i1 + 1, i2, k, j));
+                double c01 = coef_at(P, dtype, p_index(G, K, N_out, i1, i2 + 1, k, j));
+                double c11 = coef_at(P, dtype, p_index(G, K, N_out, i1 + 1, i2 + 1, k, j));
+                double g = (double)gyr[j];
+                d1 += g * ((c10 - c00) * (g2hi - x2) + (c11 - c01) * (x2 - g2lo)) * Ainv;
+                d2 += g * ((c01 - c00) * (g1hi - x1) + (c11 - c10) * (x1 - g1lo)) * Ainv;
+            }
+            gx[n * N_in + 2 * k] = d1;
+            gx[n * N_in + 2 * k + 1] = d2;
+        }
+    }
+    free(E32);
+    return 0;
+}
+
+/*
+ * Gradient with respect to the coefficients of ONE input pair k:
+ *   gPk[a][b][j] = sum_n B_{ab}(x_n) gy[n][j]  over the four (a,b) of row n's cell.
+ * y is linear in P, so this is exact; nodes no row touches stay exactly zero
+ * (Sec. 3.5 notes that only active B-splines receive gradient).
+ * gPk is [G+1][G+1][N_out] double and is overwritten.
+ */
+int oracle_backward_coef_pair(int64_t B, int N_in, int N_out, int G, int k, const float *x,
+                              const float *gy, double *gPk)
+{
+    if (N_in < 2 || (N_in & 1) || N_out < 1 || G < 3 || k < 0 || k >= N_in / 2)
+        return 1;
+    float *E32 = (float *)malloc((size_t)(G + 1) * sizeof(float));
+    if (E32 == NULL || oracle_grid_f32(G, E32) != 0) {
+        free(E32);
+        return 1;
+    }
+    int W = G + 1;
+    memset(gPk, 0, (size_t)W * (size_t)W * (size_t)N_out * sizeof(double));
+    for (int64_t n = 0; n < B; ++n) {
+        preamble_t r = preamble(G, E32, x[n * N_in + 2 * k], x[n * N_in + 2 * k + 1]);
+        const float *gyr = gy + n * N_out;
+        double *r00 = gPk + ((size_t)r.i1 * W + r.i2) * N_out;
+        double *r10 = gPk + ((size_t)(r.i1 + 1) * W + r.i2) * N_out;
+        double *r01 = gPk + ((size_t)r.i1 * W + (r.i2 + 1)) * N_out;
+        double *r11 = gPk + ((size_t)(r.i1 + 1) * W + (r.i2 + 1)) * N_out;
+        for (int j = 0; j < N_out; ++j) {
+            double g = (double)gyr[j];
+            r00[j] += r.B00 * g;
+            r10[j] += r.B10 * g;
+            r01[j] += r.B01 * g;
+            r11[j] += r.B11 * g;
+        }
+    }
+    free(E32);
+    return 0;
+}
