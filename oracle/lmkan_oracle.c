@@ -61,20 +61,19 @@ double oracle_sigma(double x)
     return 0.5 * t;
 }
 
-/* Solve sigma(x) = p for 0 < p < 1 by inverting the two branches of Eq. 5. */
-static double sigma_inverse(double p)
+/* Solve sigma(x) = p on the lower branch of Eq. 5 (0 < p <= 1/2): 0.5 e^x = p. */
+static double sigma_inverse_lower(double p)
 {
-    if (p <= 0.5)
-        return log(2.0 * p);
-    return -log(2.0 * (1.0 - p));
+    return log(2.0 * p);
 }
 
 /*
  * Extended grid in double (Sec. 3.1 "Sigma grid" + App. B "Edge cases").
  * Real points: where sigma crosses the G-1 equispaced levels k/G.
  * Ghost points: mirror the second real point about the first one on each side.
- * The level is formed from integers so that the left and right halves are
- * exact mirror images (2k <= G uses k, otherwise G-k).
+ * Levels above 1/2 use sigma(-x) = 1 - sigma(x): the point for level k/G is
+ * minus the point for level (G-k)/G, which keeps the two halves exact mirror
+ * images of each other.
  */
 int oracle_grid(int G, double *E)
 {
@@ -82,9 +81,9 @@ int oracle_grid(int G, double *E)
         return 1;
     for (int k = 1; k <= G - 1; ++k) {
         if (2 * k <= G)
-            E[k] = sigma_inverse((double)k / (double)G);
+            E[k] = sigma_inverse_lower((double)k / (double)G);
         else
-            E[k] = -sigma_inverse((double)(G - k) / (double)G);
+            E[k] = -sigma_inverse_lower((double)(G - k) / (double)G);
     }
     E[0] = E[1] - (E[2] - E[1]);
     E[G] = E[G - 1] + (E[G - 1] - E[G - 2]);
