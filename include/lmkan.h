@@ -1,0 +1,166 @@
+/*
+ * lmkan.h - C ABI of the MI355X (gfx950) implementation of the 2-D lmKAN layer
+ * from "Lookup multivariate Kolmogorov-Arnold Networks" (arXiv 2509.07103).
+ *
+ * The layer (Sec. 3, Eq. 2; Alg. 1): inputs are taken in pairs; every
+ * (pair k, output j) owns a bilinear spline table on the sigma grid, and
+ *     y[n][j] = sum_k f_{kj}(x[n][2k], x[n][2k+1]).
+ * Each f is parametrised by (G+1)^2 coefficients on second-order (piecewise
+ * linear) B-splines (Sec. 3.1, Eq. 3); evaluating it needs one cell lookup per
+ * pair, shared by all outputs, and four multiply-adds per output (Sec. 3.2).
+ *
+ * General rules for every entry point
+ *   - Pointers whose name ends in _dev are device pointers on the current HIP
+ *     device; pointers ending in _host are host pointers.  The caller owns all
+ *     of them.  The library allocates no device memory, never synchronises and
+ *     enqueues work only on the stream it is given.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).
+ *   - Every function that can fail returns an lmkan_status.  Argument errors
+ *     are found on the host before anything is launched, so nothing has been
+ *     written when a status other than LMKAN_OK or LMKAN_ERR_HIP comes back.
+ *   - batch == 0 is legal: nothing is read, and only lmkan_backward writes
+ *     (an overwritten grad_coef becomes all zeros).
+ *   - Alignment: x_dev and grad_x_dev 8 bytes (a pair of float32 is read at
+ *     once), every other tensor its element size.  Faster kernels are chosen
+ *     at run time when pointers and widths allow 16-byte accesses.
+ *   - Non-finite inputs are memory-safe: cell indices are always clamped to
+ *     [0, G-1]; the affected outputs are whatever IEEE arithmetic gives.
+ */
+#ifndef LMKAN_H
+#define LMKAN_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define LMKAN_VERSION 1
+
+/* Largest number of grid intervals per axis.  The grid table travels to the
+ * kernels by value; the paper's own experiments use G <= 40 (Sec. 3.4). */
+#define LMKAN_MAX_GRID 64
+
+/* Outputs per tile of the packed coefficient layout (see lmkan_pack). */
+#define LMKAN_PACK_TILE 64
+
+typedef enum {
+    LMKAN_OK = 0,
+    LMKAN_ERR_NULL = 1,        /* a required pointer is NULL                       */
+    LMKAN_ERR_SHAPE = 2,       /* n_in odd or < 2, n_out < 1, G out of range, batch < 0 */
+    LMKAN_ERR_UNSUPPORTED = 3, /* spline order, dtype, layout or flag not implemented  */
+    LMKAN_ERR_WORKSPACE = 4,   /* workspace smaller than lmkan_workspace_bytes()   */
+    LMKAN_ERR_ALIGN = 5,       /* a pointer is not aligned to its element size     */
+    LMKAN_ERR_HIP = 6          /* the HIP runtime reported an error at launch      */
+} lmkan_status;
+
+/* Storage type of the coefficient tensor.  Half formats are storage only:
+ * values are widened to float32 on load and all arithmetic, accumulation and
+ * gradients are float32 (the paper's kernels are float32, Sec. 3.4). */
+typedef enum { LMKAN_F32 = 0, LMKAN_F16 = 1, LMKAN_BF16 = 2 } lmkan_dtype;
+
+typedef enum {
+    LMKAN_LAYOUT_PAPER = 0, /* [G+1][G+1][n_in/2][n_out], last index fastest (Alg. 1) */
+    LMKAN_LAYOUT_PACKED = 1 /* produced by lmkan_pack                                 */
+} lmkan_layout;
+
+#define LMKAN_FLAG_ACCUMULATE_GRAD_COEF 1 /* backward adds into grad_coef instead of overwriting */
+
+/* Description of one layer (Alg. 1 "Require"). */
+typedef struct {
+    int32_t n_in;         /* input width, even, >= 2 (Eq. 2 with d = 2)                  */
+    int32_t n_out;        /* output width, >= 1                                          */
+    int32_t grid;         /* G: grid intervals per axis, 3 <= G <= LMKAN_MAX_GRID.
+                             G-1 real grid points plus two ghost points (App. B)        */
+    int32_t spline_order; /* must be 2: the paper's second-order (piecewise linear)
+                             B-splines, two non-zero per axis (Sec. 3.1)                 */
+    int32_t coef_dtype;   /* lmkan_dtype of the coefficient tensor                       */
+    int32_t coef_layout;  /* lmkan_layout of the coefficient tensor                      */
+    int32_t flags;        /* LMKAN_FLAG_* or 0                                           */
+} lmkan_desc;
+
+/* Library version (LMKAN_VERSION it was built with). */
+int lmkan_version(void);
+
+/* Static, human-readable name of a status code. */
+const char *lmkan_status_string(lmkan_status status);
+
+/*
+ * The extended grid of Sec. 3.1 / App. B as the kernels use it, on the host.
+ *   nodes_host [G+1]: nodes[1..G-1] are the real grid points, where
+ *       sigma(x) = k/G with sigma from App. B Eq. 5; nodes[0] and nodes[G] are
+ *       the ghost points first-(second-first) and its mirror image.  Computed
+ *       in double and rounded once to float32.
+ *   inv_h_host [G]: 1 / (nodes[i+1] - nodes[i]) of the float32 nodes, rounded to
+ *       float32.  Either pointer may be NULL to skip that output.
+ * The cell of an input x is defined on this table: i = number of real grid
+ * points <= x, which is floor(sigma(x) G) of Sec. 3.1 in exact arithmetic.
+ */
+lmkan_status lmkan_grid(int32_t grid, float *nodes_host, float *inv_h_host);
+
+/*
+ * Bytes of the packed coefficient tensor for this layer: n_out is padded to a
+ * multiple of LMKAN_PACK_TILE and the tensor is stored as
+ * [n_out_tiles][n_in/2][(G+1)^2][LMKAN_PACK_TILE] in desc->coef_dtype, so the
+ * table rows one workgroup needs for one pair are contiguous.  0 on bad desc.
+ */
+size_t lmkan_packed_bytes(const lmkan_desc *desc);
+
+/*
+ * Repack a coefficient tensor from the layout of Alg. 1 into the packed
+ * layout (same dtype; padding columns are zero).  desc->coef_layout is
+ * ignored.  src and dst must not overlap.
+ */
+lmkan_status lmkan_pack(const lmkan_desc *desc, const void *coef_paper_dev, void *coef_packed_dev,
+                        void *stream);
+
+/*
+ * Device scratch memory lmkan_forward (pass = 0) or lmkan_backward (pass = 1)
+ * needs for this batch size; may be 0.
+ */
+size_t lmkan_workspace_bytes(const lmkan_desc *desc, int64_t batch, int32_t pass);
+
+/*
+ * Cell lookup alone (the first two lines of Alg. 1's preamble):
+ *   cell_dev[n][k] = i1 * G + i2 for the pair (x[n][2k], x[n][2k+1]),
+ * int32, [batch][n_in/2] row-major, overwritten.  Only n_in and grid of the
+ * descriptor are used.
+ */
+lmkan_status lmkan_locate(const lmkan_desc *desc, int64_t batch, const float *x_dev,
+                          int32_t *cell_dev, void *stream);
+
+/*
+ * Layer forward (Alg. 1) for a batch.
+ *   x_dev    [batch][n_in]  float32 row-major
+ *   coef_dev coefficient tensor in desc->coef_dtype / desc->coef_layout
+ *   y_dev    [batch][n_out] float32 row-major, overwritten
+ *   workspace_dev / workspace_bytes: at least lmkan_workspace_bytes(desc, batch, 0)
+ *            bytes of device memory, 256-byte aligned (NULL allowed when 0)
+ */
+lmkan_status lmkan_forward(const lmkan_desc *desc, int64_t batch, const float *x_dev,
+                           const void *coef_dev, float *y_dev, void *workspace_dev,
+                           size_t workspace_bytes, void *stream);
+
+/*
+ * Layer backward: derivatives of Alg. 1's four-term sum.
+ *   grad_y_dev    [batch][n_out] float32, gradient of the loss w.r.t. y
+ *   grad_x_dev    [batch][n_in]  float32, overwritten; NULL skips it.  On a grid
+ *                 point the derivative of the cell on its right is returned.
+ *   grad_coef_dev float32 in the layout of Alg. 1, [G+1][G+1][n_in/2][n_out],
+ *                 whatever the storage type and layout of coef_dev; overwritten
+ *                 (entries no sample touches become exactly 0, cf. Sec. 3.5)
+ *                 unless LMKAN_FLAG_ACCUMULATE_GRAD_COEF is set; NULL skips it.
+ *   coef_dev      may be NULL when grad_x_dev is NULL.
+ * The coefficient gradient is summed with float32 atomics, so its last bits
+ * can differ from run to run.
+ */
+lmkan_status lmkan_backward(const lmkan_desc *desc, int64_t batch, const float *x_dev,
+                            const void *coef_dev, const float *grad_y_dev, float *grad_x_dev,
+                            float *grad_coef_dev, void *workspace_dev, size_t workspace_bytes,
+                            void *stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* LMKAN_H */

@@ -1,0 +1,222 @@
+"""Thin ctypes binding of the C ABI in include/lmkan.h.
+
+Argument marshalling only: every step of the layer runs in the HIP kernels of
+liblmkan.so.  PyTorch appears here only as the owner of device memory and of
+the current stream.  There is no CPU fallback: if the library is missing or a
+call fails, an exception is raised.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from dataclasses import dataclass
+
+import numpy as np
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "liblmkan.so")
+
+LMKAN_F32, LMKAN_F16, LMKAN_BF16 = 0, 1, 2
+LMKAN_LAYOUT_PAPER, LMKAN_LAYOUT_PACKED = 0, 1
+LMKAN_FLAG_ACCUMULATE_GRAD_COEF = 1
+LMKAN_PACK_TILE = 64
+LMKAN_MAX_GRID = 64
+
+_TORCH_DTYPE = {LMKAN_F32: torch.float32, LMKAN_F16: torch.float16, LMKAN_BF16: torch.bfloat16}
+_DTYPE_CODE = {v: k for k, v in _TORCH_DTYPE.items()}
+
+
+class LmkanError(RuntimeError):
+    def __init__(self, status: int, where: str):
+        self.status = status
+        msg = lib().lmkan_status_string(status).decode()
+        super().__init__(f"{where}: {msg} (status {status})")
+
+
+class _Desc(C.Structure):
+    _fields_ = [("n_in", C.c_int32), ("n_out", C.c_int32), ("grid", C.c_int32),
+                ("spline_order", C.c_int32), ("coef_dtype", C.c_int32),
+                ("coef_layout", C.c_int32), ("flags", C.c_int32)]
+
+
+@dataclass
+class LayerDesc:
+    """Mirror of ``lmkan_desc``."""
+    n_in: int
+    n_out: int
+    grid: int
+    spline_order: int = 2
+    coef_dtype: int = LMKAN_F32
+    coef_layout: int = LMKAN_LAYOUT_PAPER
+    flags: int = 0
+
+    def c(self) -> _Desc:
+        return _Desc(self.n_in, self.n_out, self.grid, self.spline_order, self.coef_dtype,
+                     self.coef_layout, self.flags)
+
+    @property
+    def pairs(self) -> int:
+        return self.n_in // 2
+
+    def coef_shape(self):
+        return (self.grid + 1, self.grid + 1, self.pairs, self.n_out)
+
+
+_lib = None
+
+
+def lib() -> C.CDLL:
+    """Load liblmkan.so (built in-tree by ``build.py``); fail loudly if it is absent."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(LIB_PATH):
+        raise ImportError(f"{LIB_PATH} is missing: run `python -m paper_2509_07103_amd.build` "
+                          "(the layer has no fallback implementation)")
+    L = C.CDLL(LIB_PATH)
+    dp = C.POINTER(_Desc)
+    L.lmkan_version.restype = C.c_int
+    L.lmkan_version.argtypes = []
+    L.lmkan_status_string.restype = C.c_char_p
+    L.lmkan_status_string.argtypes = [C.c_int]
+    L.lmkan_grid.restype = C.c_int
+    L.lmkan_grid.argtypes = [C.c_int32, C.c_void_p, C.c_void_p]
+    L.lmkan_packed_bytes.restype = C.c_size_t
+    L.lmkan_packed_bytes.argtypes = [dp]
+    L.lmkan_workspace_bytes.restype = C.c_size_t
+    L.lmkan_workspace_bytes.argtypes = [dp, C.c_int64, C.c_int32]
+    L.lmkan_pack.restype = C.c_int
+    L.lmkan_pack.argtypes = [dp, C.c_void_p, C.c_void_p, C.c_void_p]
+    L.lmkan_locate.restype = C.c_int
+    L.lmkan_locate.argtypes = [dp, C.c_int64, C.c_void_p, C.c_void_p, C.c_void_p]
+    L.lmkan_forward.restype = C.c_int
+    L.lmkan_forward.argtypes = [dp, C.c_int64, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p,
+                                C.c_size_t, C.c_void_p]
+    L.lmkan_backward.restype = C.c_int
+    L.lmkan_backward.argtypes = [dp, C.c_int64, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p,
+                                 C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]
+    _lib = L
+    return L
+
+
+def _check(status: int, where: str) -> None:
+    if status != 0:
+        raise LmkanError(status, where)
+
+
+def _stream(stream) -> int:
+    if stream is None:
+        return torch.cuda.current_stream().cuda_stream
+    return stream.cuda_stream if hasattr(stream, "cuda_stream") else int(stream)
+
+
+def _dev(t: torch.Tensor | None, dtype, shape, name: str) -> int | None:
+    if t is None:
+        return None
+    if not t.is_cuda or not t.is_contiguous() or t.dtype != dtype or tuple(t.shape) != tuple(shape):
+        raise ValueError(f"{name}: expected contiguous device tensor {dtype} {tuple(shape)}, got "
+                         f"{t.dtype} {tuple(t.shape)} on {t.device}")
+    return t.data_ptr()
+
+
+def lmkan_version() -> int:
+    return lib().lmkan_version()
+
+
+def lmkan_status_string(status: int) -> str:
+    return lib().lmkan_status_string(status).decode()
+
+
+def lmkan_grid(grid: int):
+    """(nodes[G+1], inv_h[G]) as float32 numpy arrays."""
+    n = max(int(grid), 0)
+    nodes = np.zeros(n + 1, dtype=np.float32)
+    inv_h = np.zeros(n, dtype=np.float32)
+    _check(lib().lmkan_grid(grid, nodes.ctypes.data, inv_h.ctypes.data), "lmkan_grid")
+    return nodes, inv_h
+
+
+def lmkan_packed_bytes(desc: LayerDesc) -> int:
+    return lib().lmkan_packed_bytes(C.byref(desc.c()))
+
+
+def lmkan_workspace_bytes(desc: LayerDesc, batch: int, backward: bool) -> int:
+    return lib().lmkan_workspace_bytes(C.byref(desc.c()), batch, 1 if backward else 0)
+
+
+def _workspace(desc: LayerDesc, batch: int, backward: bool, device):
+    need = lmkan_workspace_bytes(desc, batch, backward)
+    if need == 0:
+        return None, 0
+    ws = torch.empty(need, dtype=torch.uint8, device=device)
+    return ws, need
+
+
+def lmkan_pack(desc: LayerDesc, coef: torch.Tensor, stream=None) -> torch.Tensor:
+    """Coefficients [G+1][G+1][K][n_out] -> packed tensor (flat, same dtype)."""
+    dt = _TORCH_DTYPE[desc.coef_dtype]
+    src = _dev(coef, dt, desc.coef_shape(), "coef")
+    nbytes = lmkan_packed_bytes(desc)
+    out = torch.empty(nbytes // coef.element_size(), dtype=dt, device=coef.device)
+    _check(lib().lmkan_pack(C.byref(desc.c()), src, out.data_ptr(), _stream(stream)), "lmkan_pack")
+    return out
+
+
+def _coef_ptr(desc: LayerDesc, coef: torch.Tensor | None) -> int | None:
+    if coef is None:
+        return None
+    dt = _TORCH_DTYPE[desc.coef_dtype]
+    if desc.coef_layout == LMKAN_LAYOUT_PACKED:
+        shape = (lmkan_packed_bytes(desc) // (4 if desc.coef_dtype == LMKAN_F32 else 2),)
+    else:
+        shape = desc.coef_shape()
+    return _dev(coef, dt, shape, "coef")
+
+
+def lmkan_locate(desc: LayerDesc, x: torch.Tensor, stream=None) -> torch.Tensor:
+    batch = x.shape[0]
+    xp = _dev(x, torch.float32, (batch, desc.n_in), "x")
+    cell = torch.empty((batch, desc.pairs), dtype=torch.int32, device=x.device)
+    _check(lib().lmkan_locate(C.byref(desc.c()), batch, xp, cell.data_ptr(), _stream(stream)),
+           "lmkan_locate")
+    return cell
+
+
+def lmkan_forward(desc: LayerDesc, x: torch.Tensor, coef: torch.Tensor, y: torch.Tensor | None = None,
+                  stream=None) -> torch.Tensor:
+    batch = x.shape[0]
+    xp = _dev(x, torch.float32, (batch, desc.n_in), "x")
+    cp = _coef_ptr(desc, coef)
+    if y is None:
+        y = torch.empty((batch, desc.n_out), dtype=torch.float32, device=x.device)
+    yp = _dev(y, torch.float32, (batch, desc.n_out), "y")
+    ws, wsz = _workspace(desc, batch, False, x.device)
+    _check(lib().lmkan_forward(C.byref(desc.c()), batch, xp, cp, yp,
+                               ws.data_ptr() if ws is not None else None, wsz, _stream(stream)),
+           "lmkan_forward")
+    return y
+
+
+def lmkan_backward(desc: LayerDesc, x: torch.Tensor, coef: torch.Tensor | None, grad_y: torch.Tensor,
+                   need_grad_x: bool = True, need_grad_coef: bool = True,
+                   grad_x: torch.Tensor | None = None, grad_coef: torch.Tensor | None = None,
+                   stream=None):
+    """Returns (grad_x or None, grad_coef or None); grad_coef is float32 in the layout of Alg. 1."""
+    batch = x.shape[0]
+    xp = _dev(x, torch.float32, (batch, desc.n_in), "x")
+    cp = _coef_ptr(desc, coef)
+    gyp = _dev(grad_y, torch.float32, (batch, desc.n_out), "grad_y")
+    if need_grad_x and grad_x is None:
+        grad_x = torch.empty((batch, desc.n_in), dtype=torch.float32, device=x.device)
+    if need_grad_coef and grad_coef is None:
+        if desc.flags & LMKAN_FLAG_ACCUMULATE_GRAD_COEF:
+            raise ValueError("accumulating into grad_coef needs an existing grad_coef tensor")
+        grad_coef = torch.empty(desc.coef_shape(), dtype=torch.float32, device=x.device)
+    gxp = _dev(grad_x, torch.float32, (batch, desc.n_in), "grad_x") if need_grad_x else None
+    gcp = _dev(grad_coef, torch.float32, desc.coef_shape(), "grad_coef") if need_grad_coef else None
+    ws, wsz = _workspace(desc, batch, True, x.device)
+    _check(lib().lmkan_backward(C.byref(desc.c()), batch, xp, cp, gyp, gxp, gcp,
+                                ws.data_ptr() if ws is not None else None, wsz, _stream(stream)),
+           "lmkan_backward")
+    return (grad_x if need_grad_x else None), (grad_coef if need_grad_coef else None)

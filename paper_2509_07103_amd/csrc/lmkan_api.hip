@@ -1,0 +1,201 @@
+// Host side of the C ABI declared in include/lmkan.h: argument validation, the
+// grid table, kernel selection.  No entry point allocates or synchronises.
+#include <math.h>
+#include <string.h>
+
+#include "lmkan.h"
+#include "lmkan_kernels.h"
+
+using namespace lmkan;
+
+namespace {
+
+size_t dtype_size(int dtype) { return dtype == LMKAN_F32 ? 4 : 2; }
+
+bool aligned(const void *p, size_t a) { return (reinterpret_cast<uintptr_t>(p) % a) == 0; }
+
+// Sec. 3.1 "Sigma grid" + App. B: real points where sigma crosses the levels k/G, with
+// sigma from Eq. 5 (0.5 e^x on the left half, mirrored on the right), then the two ghost
+// points.  Double precision, each entry rounded once to float32; the spacings are taken
+// from the rounded points.
+lmkan_status build_grid(int G, GridTab *tab)
+{
+    if (G < 3 || G > LMKAN_MAX_GRID) return LMKAN_ERR_SHAPE;
+    double e[LMKAN_MAX_GRID + 1];
+    for (int k = 1; k <= G - 1; ++k) {
+        const int m = (2 * k <= G) ? k : G - k;
+        const double left = log(2.0 * (double)m / (double)G);
+        e[k] = (2 * k <= G) ? left : -left;
+    }
+    e[0] = e[1] - (e[2] - e[1]);
+    e[G] = e[G - 1] + (e[G - 1] - e[G - 2]);
+    memset(tab, 0, sizeof(*tab));
+    tab->G = G;
+    for (int k = 0; k <= G; ++k) tab->node[k] = (float)e[k];
+    for (int i = 0; i < G; ++i)
+        tab->inv_h[i] = (float)(1.0 / ((double)tab->node[i + 1] - (double)tab->node[i]));
+    return LMKAN_OK;
+}
+
+lmkan_status check_desc(const lmkan_desc *d)
+{
+    if (d == nullptr) return LMKAN_ERR_NULL;
+    if (d->n_in < 2 || (d->n_in & 1) || d->n_out < 1) return LMKAN_ERR_SHAPE;
+    if (d->grid < 3 || d->grid > LMKAN_MAX_GRID) return LMKAN_ERR_SHAPE;
+    if (d->spline_order != 2) return LMKAN_ERR_UNSUPPORTED;
+    if (d->coef_dtype != LMKAN_F32 && d->coef_dtype != LMKAN_F16 && d->coef_dtype != LMKAN_BF16)
+        return LMKAN_ERR_UNSUPPORTED;
+    if (d->coef_layout != LMKAN_LAYOUT_PAPER && d->coef_layout != LMKAN_LAYOUT_PACKED)
+        return LMKAN_ERR_UNSUPPORTED;
+    if (d->flags & ~LMKAN_FLAG_ACCUMULATE_GRAD_COEF) return LMKAN_ERR_UNSUPPORTED;
+    return LMKAN_OK;
+}
+
+LayerShape shape_of(const lmkan_desc *d, int64_t batch)
+{
+    LayerShape s;
+    s.batch = batch;
+    s.n_in = d->n_in;
+    s.n_out = d->n_out;
+    s.G = d->grid;
+    s.dtype = d->coef_dtype;
+    s.layout = d->coef_layout;
+    return s;
+}
+
+lmkan_status launch_status()
+{
+    return hipGetLastError() == hipSuccess ? LMKAN_OK : LMKAN_ERR_HIP;
+}
+
+}  // namespace
+
+extern "C" {
+
+int lmkan_version(void) { return LMKAN_VERSION; }
+
+const char *lmkan_status_string(lmkan_status status)
+{
+    switch (status) {
+    case LMKAN_OK: return "ok";
+    case LMKAN_ERR_NULL: return "required pointer is NULL";
+    case LMKAN_ERR_SHAPE: return "invalid shape (n_in, n_out, grid or batch)";
+    case LMKAN_ERR_UNSUPPORTED: return "unsupported spline order, dtype, layout or flag";
+    case LMKAN_ERR_WORKSPACE: return "workspace too small";
+    case LMKAN_ERR_ALIGN: return "misaligned pointer";
+    case LMKAN_ERR_HIP: return "HIP runtime error at launch";
+    }
+    return "unknown status";
+}
+
+lmkan_status lmkan_grid(int32_t grid, float *nodes_host, float *inv_h_host)
+{
+    GridTab tab;
+    const lmkan_status st = build_grid(grid, &tab);
+    if (st != LMKAN_OK) return st;
+    if (nodes_host) memcpy(nodes_host, tab.node, sizeof(float) * (size_t)(grid + 1));
+    if (inv_h_host) memcpy(inv_h_host, tab.inv_h, sizeof(float) * (size_t)grid);
+    return LMKAN_OK;
+}
+
+size_t lmkan_packed_bytes(const lmkan_desc *desc)
+{
+    if (check_desc(desc) != LMKAN_OK) return 0;
+    const LayerShape s = shape_of(desc, 0);
+    return (size_t)s.out_tiles() * (size_t)s.pairs() * (size_t)s.nodes() * LMKAN_PACK_TILE *
+           dtype_size(s.dtype);
+}
+
+size_t lmkan_workspace_bytes(const lmkan_desc *desc, int64_t batch, int32_t pass)
+{
+    (void)batch;
+    (void)pass;
+    if (check_desc(desc) != LMKAN_OK) return 0;
+    return 0;
+}
+
+lmkan_status lmkan_pack(const lmkan_desc *desc, const void *coef_paper_dev, void *coef_packed_dev,
+                        void *stream)
+{
+    const lmkan_status st = check_desc(desc);
+    if (st != LMKAN_OK) return st;
+    if (!coef_paper_dev || !coef_packed_dev) return LMKAN_ERR_NULL;
+    const size_t es = dtype_size(desc->coef_dtype);
+    if (!aligned(coef_paper_dev, es) || !aligned(coef_packed_dev, es)) return LMKAN_ERR_ALIGN;
+    launch_pack(shape_of(desc, 0), coef_paper_dev, coef_packed_dev, static_cast<hipStream_t>(stream));
+    return launch_status();
+}
+
+lmkan_status lmkan_locate(const lmkan_desc *desc, int64_t batch, const float *x_dev,
+                          int32_t *cell_dev, void *stream)
+{
+    const lmkan_status st = check_desc(desc);
+    if (st != LMKAN_OK) return st;
+    if (batch < 0) return LMKAN_ERR_SHAPE;
+    if (batch == 0) return LMKAN_OK;
+    if (!x_dev || !cell_dev) return LMKAN_ERR_NULL;
+    if (!aligned(x_dev, 8) || !aligned(cell_dev, 4)) return LMKAN_ERR_ALIGN;
+    GridTab tab;
+    build_grid(desc->grid, &tab);
+    launch_locate(shape_of(desc, batch), tab, x_dev, cell_dev, static_cast<hipStream_t>(stream));
+    return launch_status();
+}
+
+lmkan_status lmkan_forward(const lmkan_desc *desc, int64_t batch, const float *x_dev,
+                           const void *coef_dev, float *y_dev, void *workspace_dev,
+                           size_t workspace_bytes, void *stream)
+{
+    const lmkan_status st = check_desc(desc);
+    if (st != LMKAN_OK) return st;
+    if (batch < 0) return LMKAN_ERR_SHAPE;
+    if (batch == 0) return LMKAN_OK;
+    if (!x_dev || !coef_dev || !y_dev) return LMKAN_ERR_NULL;
+    if (!aligned(x_dev, 8) || !aligned(y_dev, 4) || !aligned(coef_dev, dtype_size(desc->coef_dtype)))
+        return LMKAN_ERR_ALIGN;
+    const size_t need = lmkan_workspace_bytes(desc, batch, 0);
+    if (need > 0 && (!workspace_dev || workspace_bytes < need)) return LMKAN_ERR_WORKSPACE;
+    GridTab tab;
+    build_grid(desc->grid, &tab);
+    launch_forward_generic(shape_of(desc, batch), tab, x_dev, coef_dev, y_dev,
+                           static_cast<hipStream_t>(stream));
+    return launch_status();
+}
+
+lmkan_status lmkan_backward(const lmkan_desc *desc, int64_t batch, const float *x_dev,
+                            const void *coef_dev, const float *grad_y_dev, float *grad_x_dev,
+                            float *grad_coef_dev, void *workspace_dev, size_t workspace_bytes,
+                            void *stream)
+{
+    const lmkan_status st = check_desc(desc);
+    if (st != LMKAN_OK) return st;
+    if (batch < 0) return LMKAN_ERR_SHAPE;
+    if (!grad_x_dev && !grad_coef_dev) return LMKAN_OK;
+    const LayerShape s = shape_of(desc, batch);
+    hipStream_t hs = static_cast<hipStream_t>(stream);
+    const bool overwrite = !(desc->flags & LMKAN_FLAG_ACCUMULATE_GRAD_COEF);
+    if (batch == 0) {
+        // an empty batch still defines the coefficient gradient: all zeros
+        if (grad_coef_dev && overwrite) {
+            if (!aligned(grad_coef_dev, 4)) return LMKAN_ERR_ALIGN;
+            launch_fill_zero(grad_coef_dev, (size_t)s.nodes() * s.pairs() * s.n_out, hs);
+            return launch_status();
+        }
+        return LMKAN_OK;
+    }
+    if (!x_dev || !grad_y_dev) return LMKAN_ERR_NULL;
+    if (grad_x_dev && !coef_dev) return LMKAN_ERR_NULL;
+    if (!aligned(x_dev, 8) || !aligned(grad_y_dev, 4) || (grad_x_dev && !aligned(grad_x_dev, 8)) ||
+        (grad_coef_dev && !aligned(grad_coef_dev, 4)) ||
+        (coef_dev && !aligned(coef_dev, dtype_size(desc->coef_dtype))))
+        return LMKAN_ERR_ALIGN;
+    const size_t need = lmkan_workspace_bytes(desc, batch, 1);
+    if (need > 0 && (!workspace_dev || workspace_bytes < need)) return LMKAN_ERR_WORKSPACE;
+    GridTab tab;
+    build_grid(desc->grid, &tab);
+    if (grad_coef_dev && overwrite)
+        launch_fill_zero(grad_coef_dev, (size_t)s.nodes() * s.pairs() * s.n_out, hs);
+    launch_backward_generic(s, tab, x_dev, coef_dev, grad_y_dev, grad_x_dev, grad_coef_dev, hs);
+    return launch_status();
+}
+
+}  // extern "C"

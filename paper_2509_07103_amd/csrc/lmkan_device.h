@@ -1,0 +1,87 @@
+// Device-side pieces shared by every lmKAN kernel: the grid table, the cell
+// lookup and the four weights of Alg. 1's preamble, and coefficient decoding.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "lmkan.h"
+
+namespace lmkan {
+
+// Extended grid (Sec. 3.1, App. B "Edge cases") as float32, passed to kernels by value.
+// node[1..G-1] are the real grid points, node[0] / node[G] the ghost points;
+// inv_h[i] = 1 / (node[i+1] - node[i]).
+struct GridTab {
+    float node[LMKAN_MAX_GRID + 1];
+    float inv_h[LMKAN_MAX_GRID];
+    int G;
+};
+
+// Where coefficient (node, pair k, output tile jt, column jl) lives, in elements:
+//   node * s_node + k * s_pair + jt * s_tile + jl,
+// and moving one node along the second axis adds s_node, along the first (G+1) * s_node.
+// Covers both the layout of Alg. 1 and the packed layout.
+struct CoefMap {
+    int64_t s_node;
+    int64_t s_pair;
+    int64_t s_tile;
+};
+
+// One record per (sample, pair): Alg. 1's preamble output.
+struct Preamble {
+    int node;    // i1 * (G+1) + i2 : table node of the cell's lower-left corner
+    int cell;    // i1 * G + i2
+    float a_lo;  // (node[i1+1] - x1) / h1 : factor of B_{i1}
+    float a_hi;  // (x1 - node[i1]) / h1   : factor of B_{i1+1}
+    float b_lo;  // same along the second axis
+    float b_hi;
+    float rh1;   // 1 / h1, 1 / h2 : needed by the input gradient
+    float rh2;
+};
+
+// App. B Eq. 5 the way Alg. 2 evaluates it: one exponential of -|x|.
+__device__ __forceinline__ float sigma(float x)
+{
+    float t = __expf(-fabsf(x));
+    return x > 0.0f ? 1.0f - 0.5f * t : 0.5f * t;
+}
+
+// Cell index.  The candidate floor(sigma(x) G) of Sec. 3.1 is corrected against the
+// float32 grid table so that the result is exactly "number of real grid points <= x"
+// whatever the accuracy of the exponential.  node points to LDS or kernel arguments.
+__device__ __forceinline__ int locate(const float *node, int G, float x)
+{
+    int i = (int)(sigma(x) * (float)G);
+    i = min(max(i, 0), G - 1);
+    while (i > 0 && x < node[i]) --i;
+    while (i < G - 1 && x >= node[i + 1]) ++i;
+    return i;
+}
+
+__device__ __forceinline__ Preamble preamble(const float *node, const float *inv_h, int G, float x1,
+                                             float x2)
+{
+    Preamble r;
+    int i1 = locate(node, G, x1);
+    int i2 = locate(node, G, x2);
+    r.node = i1 * (G + 1) + i2;
+    r.cell = i1 * G + i2;
+    r.rh1 = inv_h[i1];
+    r.rh2 = inv_h[i2];
+    r.a_lo = (node[i1 + 1] - x1) * r.rh1;
+    r.a_hi = (x1 - node[i1]) * r.rh1;
+    r.b_lo = (node[i2 + 1] - x2) * r.rh2;
+    r.b_hi = (x2 - node[i2]) * r.rh2;
+    return r;
+}
+
+// Stored coefficient -> float32.
+__device__ __forceinline__ float widen(float v) { return v; }
+__device__ __forceinline__ float widen(_Float16 v) { return (float)v; }
+struct bf16_t {
+    uint16_t bits;
+};
+__device__ __forceinline__ float widen(bf16_t v) { return __uint_as_float((uint32_t)v.bits << 16); }
+
+}  // namespace lmkan

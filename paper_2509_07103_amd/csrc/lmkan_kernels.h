@@ -1,0 +1,38 @@
+// Host-callable launchers of the lmKAN kernels.  Every launcher enqueues on the given
+// stream and returns; shapes have been validated by the caller (lmkan_api.hip).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "lmkan_device.h"
+
+namespace lmkan {
+
+struct LayerShape {
+    int64_t batch;
+    int n_in;
+    int n_out;
+    int G;
+    int dtype;   // lmkan_dtype
+    int layout;  // lmkan_layout
+    int pairs() const { return n_in / 2; }
+    int nodes() const { return (G + 1) * (G + 1); }
+    int out_tiles() const { return (n_out + LMKAN_PACK_TILE - 1) / LMKAN_PACK_TILE; }
+};
+
+CoefMap coef_map(const LayerShape &s);
+
+// Generic kernels: any shape, any dtype, both layouts; coefficient rows are read
+// straight from global memory.
+void launch_forward_generic(const LayerShape &s, const GridTab &tab, const float *x, const void *coef,
+                            float *y, hipStream_t stream);
+void launch_backward_generic(const LayerShape &s, const GridTab &tab, const float *x,
+                             const void *coef, const float *gy, float *gx, float *gcoef,
+                             hipStream_t stream);
+void launch_locate(const LayerShape &s, const GridTab &tab, const float *x, int32_t *cell,
+                   hipStream_t stream);
+void launch_pack(const LayerShape &s, const void *src, void *dst, hipStream_t stream);
+void launch_fill_zero(float *p, size_t n, hipStream_t stream);
+
+}  // namespace lmkan

@@ -1,0 +1,122 @@
+"""Host-side checks of the C ABI that need no GPU: the library loads, exports every
+symbol the header declares, and turns bad arguments into status codes."""
+import ctypes as C
+import os
+import re
+
+import numpy as np
+import pytest
+
+import paper_2509_07103_amd as pkg
+from paper_2509_07103_amd import binding
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def _declared_functions():
+    names = set()
+    for fn in os.listdir(os.path.join(ROOT, "include")):
+        if fn.endswith(".h"):
+            text = open(os.path.join(ROOT, "include", fn)).read()
+            text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+            names |= set(re.findall(r"\b(lmkan_[a-z_0-9]+)\s*\(", text))
+    return names
+
+
+def test_library_exports_every_declared_symbol():
+    L = pkg.lib()
+    declared = _declared_functions()
+    assert {"lmkan_forward", "lmkan_backward", "lmkan_locate", "lmkan_pack", "lmkan_grid",
+            "lmkan_version", "lmkan_status_string", "lmkan_packed_bytes",
+            "lmkan_workspace_bytes"} <= declared
+    for name in declared:
+        assert hasattr(L, name), name
+        assert hasattr(pkg, name), f"python binding lacks {name}"
+
+
+def test_version_and_status_strings():
+    assert pkg.lmkan_version() == 1
+    seen = {pkg.lmkan_status_string(s) for s in range(7)}
+    assert len(seen) == 7 and "ok" in seen
+    assert pkg.lmkan_status_string(99) == "unknown status"
+
+
+@pytest.mark.parametrize("G", [3, 4, 8, 16, 32, 64])
+def test_grid_table_matches_oracle_bit_for_bit(oracle, G):
+    nodes, inv_h = pkg.lmkan_grid(G)
+    E32 = oracle.grid_f32(G)
+    np.testing.assert_array_equal(nodes, E32)
+    want = (1.0 / (E32[1:].astype(np.float64) - E32[:-1].astype(np.float64))).astype(np.float32)
+    np.testing.assert_array_equal(inv_h, want)
+
+
+def test_grid_rejects_bad_sizes():
+    for G in (-3, 0, 2, 65, 1000):
+        with pytest.raises(pkg.LmkanError) as e:
+            pkg.lmkan_grid(G)
+        assert e.value.status == 2
+
+
+def _desc(**kw):
+    d = dict(n_in=8, n_out=4, grid=8)
+    d.update(kw)
+    return pkg.LayerDesc(**d)
+
+
+BAD_DESCS = [
+    (dict(n_in=7), 2), (dict(n_in=0), 2), (dict(n_out=0), 2), (dict(grid=2), 2), (dict(grid=65), 2),
+    (dict(spline_order=3), 3), (dict(coef_dtype=7), 3), (dict(coef_layout=2), 3), (dict(flags=2), 3),
+]
+
+
+@pytest.mark.parametrize("kw,status", BAD_DESCS)
+def test_bad_descriptors_are_rejected_before_any_launch(kw, status):
+    L = pkg.lib()
+    d = _desc(**kw).c()
+    fake = C.c_void_p(0x1000)   # never dereferenced: validation comes first
+    assert L.lmkan_forward(C.byref(d), 4, fake, fake, fake, None, 0, None) == status
+    assert L.lmkan_backward(C.byref(d), 4, fake, fake, fake, fake, fake, None, 0, None) == status
+    assert L.lmkan_locate(C.byref(d), 4, fake, fake, None) == status
+    assert L.lmkan_pack(C.byref(d), fake, fake, None) == status
+    assert L.lmkan_packed_bytes(C.byref(d)) == 0
+
+
+def test_null_misaligned_and_negative_arguments():
+    L = pkg.lib()
+    d = _desc().c()
+    ok = C.c_void_p(0x1000)
+    odd = C.c_void_p(0x1002)
+    assert L.lmkan_forward(None, 4, ok, ok, ok, None, 0, None) == 1
+    assert L.lmkan_forward(C.byref(d), 4, None, ok, ok, None, 0, None) == 1
+    assert L.lmkan_forward(C.byref(d), 4, ok, None, ok, None, 0, None) == 1
+    assert L.lmkan_forward(C.byref(d), 4, ok, ok, None, None, 0, None) == 1
+    assert L.lmkan_forward(C.byref(d), -1, ok, ok, ok, None, 0, None) == 2
+    assert L.lmkan_forward(C.byref(d), 4, odd, ok, ok, None, 0, None) == 5
+    assert L.lmkan_forward(C.byref(d), 4, C.c_void_p(0x1004), ok, ok, None, 0, None) == 5
+    assert L.lmkan_forward(C.byref(d), 4, ok, odd, ok, None, 0, None) == 5
+    assert L.lmkan_backward(C.byref(d), 4, ok, None, ok, ok, None, None, 0, None) == 1
+    assert L.lmkan_backward(C.byref(d), 4, ok, ok, None, ok, ok, None, 0, None) == 1
+    assert L.lmkan_backward(C.byref(d), -5, ok, ok, ok, ok, ok, None, 0, None) == 2
+    assert L.lmkan_backward(C.byref(d), 4, ok, ok, ok, odd, ok, None, 0, None) == 5
+    assert L.lmkan_locate(C.byref(d), 4, None, ok, None) == 1
+    assert L.lmkan_pack(C.byref(d), None, ok, None) == 1
+    # nothing to do: empty batch, or no gradient requested
+    assert L.lmkan_forward(C.byref(d), 0, None, None, None, None, 0, None) == 0
+    assert L.lmkan_locate(C.byref(d), 0, None, None, None) == 0
+    assert L.lmkan_backward(C.byref(d), 4, ok, ok, ok, None, None, None, 0, None) == 0
+
+
+def test_packed_size_pads_outputs_to_the_tile():
+    for n_out, tiles in ((1, 1), (64, 1), (65, 2), (1024, 16)):
+        for dt, sz in ((binding.LMKAN_F32, 4), (binding.LMKAN_F16, 2), (binding.LMKAN_BF16, 2)):
+            d = _desc(n_in=10, n_out=n_out, grid=5, coef_dtype=dt)
+            assert pkg.lmkan_packed_bytes(d) == tiles * 5 * 36 * 64 * sz
+
+
+def test_binding_refuses_host_tensors():
+    import torch
+    d = _desc()
+    x = torch.zeros((4, 8))
+    P = torch.zeros(d.coef_shape())
+    with pytest.raises(ValueError):
+        pkg.lmkan_forward(d, x, P)

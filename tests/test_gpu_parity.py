@@ -1,0 +1,210 @@
+"""GPU parity: the HIP library (through its C ABI) against the CPU oracle, element by
+element on the same seeded inputs.  Cell indices must agree bit for bit; values within
+1e-5 (float32 tables, and half tables against the oracle reading the stored bits) and
+2e-2 (half tables against the oracle on the float32 master), in the row-wise max norm."""
+import numpy as np
+import pytest
+import torch
+
+import paper_2509_07103_amd as pkg
+from paper_2509_07103_amd import workloads as wl
+from parity_util import (ORACLE_DTYPE, TOL_F32, TOL_HALF, bits, pair_slice_rel_err,
+                         rowwise_rel_err)
+
+pytestmark = pytest.mark.gpu
+
+DT_CODE = {"f32": pkg.LMKAN_F32, "f16": pkg.LMKAN_F16, "bf16": pkg.LMKAN_BF16}
+
+
+@pytest.fixture(scope="module")
+def dev():
+    assert torch.cuda.is_available(), "GPU tests need a GPU"
+    pkg.lib()   # fails loudly if liblmkan.so was not built
+    return torch.device("cuda:0")
+
+
+def _inputs(B, n_in, n_out, G, seed, dev, heavy=False, std=0.1):
+    g = torch.Generator(device="cpu").manual_seed(seed)
+    x = torch.randn((B, n_in), generator=g)
+    if heavy:
+        x = x * (1.0 + 4.0 * torch.rand((B, n_in), generator=g) ** 4)
+    P = torch.randn((G + 1, G + 1, n_in // 2, n_out), generator=g) * std
+    gy = torch.randn((B, n_out), generator=g)
+    return x.to(dev), P.to(dev), gy.to(dev)
+
+
+def _desc(n_in, n_out, G, storage="f32", layout=pkg.LMKAN_LAYOUT_PAPER, flags=0):
+    return pkg.LayerDesc(n_in, n_out, G, coef_dtype=DT_CODE[storage], coef_layout=layout, flags=flags)
+
+
+def _stored(P, storage, desc, layout):
+    Ps = wl.store(P, storage).contiguous()
+    if layout == pkg.LMKAN_LAYOUT_PACKED:
+        return Ps, pkg.lmkan_pack(desc, Ps)
+    return Ps, Ps
+
+
+SHAPES = [
+    # B, n_in, n_out, G
+    (1, 2, 1, 3),
+    (7, 4, 3, 4),
+    (33, 6, 65, 5),
+    (256, 16, 16, 8),
+    (257, 18, 100, 8),
+    (130, 34, 64, 16),
+    (513, 130, 129, 12),
+    (100, 260, 256, 16),
+    (64, 8, 200, 33),
+    (40, 6, 70, 64),
+]
+
+
+@pytest.mark.parametrize("shape", SHAPES)
+def test_cell_indices_are_bit_exact(dev, oracle, shape):
+    B, n_in, n_out, G = shape
+    x, _, _ = _inputs(B, n_in, n_out, G, 11, dev, heavy=True)
+    nodes = torch.from_numpy(oracle.grid_f32(G))
+    flat = x.flatten().cpu()
+    # plant every grid point, its float neighbours, and non-finite / huge values
+    special = torch.cat([nodes, torch.nextafter(nodes, torch.tensor(-1e30)),
+                         torch.nextafter(nodes, torch.tensor(1e30)),
+                         torch.tensor([float("inf"), float("-inf"), float("nan"), 3e38, -3e38,
+                                       0.0, -0.0, 1e-45, 17.0, -17.0, 88.0, -104.0])])
+    m = min(len(special), flat.numel())
+    flat[:m] = special[:m]
+    x = flat.reshape(B, n_in).to(dev)
+    cell = pkg.lmkan_locate(_desc(n_in, n_out, G), x)
+    torch.cuda.synchronize()
+    want = oracle.locate_batch(x.cpu().numpy(), G)
+    np.testing.assert_array_equal(cell.cpu().numpy(), want)
+
+
+@pytest.mark.parametrize("layout", [pkg.LMKAN_LAYOUT_PAPER, pkg.LMKAN_LAYOUT_PACKED])
+@pytest.mark.parametrize("storage", ["f32", "f16", "bf16"])
+@pytest.mark.parametrize("shape", SHAPES)
+def test_forward_matches_oracle(dev, oracle, shape, storage, layout):
+    B, n_in, n_out, G = shape
+    x, P, _ = _inputs(B, n_in, n_out, G, 21, dev, heavy=True)
+    desc = _desc(n_in, n_out, G, storage, layout)
+    Ps, Pdev = _stored(P, storage, desc, layout)
+    y = pkg.lmkan_forward(desc, x, Pdev)
+    torch.cuda.synchronize()
+    xh = x.cpu().numpy()
+    want = oracle.forward(xh, bits(Ps), G, dtype=ORACLE_DTYPE[storage])
+    assert rowwise_rel_err(y.cpu().numpy(), want) <= TOL_F32
+    if storage != "f32":
+        master = oracle.forward(xh, P.cpu().numpy(), G)
+        assert rowwise_rel_err(y.cpu().numpy(), master) <= TOL_HALF
+
+
+@pytest.mark.parametrize("layout", [pkg.LMKAN_LAYOUT_PAPER, pkg.LMKAN_LAYOUT_PACKED])
+@pytest.mark.parametrize("storage", ["f32", "f16", "bf16"])
+@pytest.mark.parametrize("shape", SHAPES)
+def test_backward_matches_oracle(dev, oracle, shape, storage, layout):
+    B, n_in, n_out, G = shape
+    x, P, gy = _inputs(B, n_in, n_out, G, 31, dev, heavy=True)
+    desc = _desc(n_in, n_out, G, storage, layout)
+    Ps, Pdev = _stored(P, storage, desc, layout)
+    gx, gP = pkg.lmkan_backward(desc, x, Pdev, gy)
+    torch.cuda.synchronize()
+    xh, gyh = x.cpu().numpy(), gy.cpu().numpy()
+    want_gx = oracle.backward_input(xh, bits(Ps), gyh, G, dtype=ORACLE_DTYPE[storage])
+    assert rowwise_rel_err(gx.cpu().numpy(), want_gx) <= TOL_F32
+    gPh = gP.cpu().numpy()
+    assert gPh.shape == (G + 1, G + 1, n_in // 2, n_out)
+    for k in range(n_in // 2):
+        want = oracle.backward_coef_pair(xh, gyh, G, k)
+        assert pair_slice_rel_err(gPh[:, :, k, :], want) <= TOL_F32
+        # entries no sample touches must be exactly zero (Sec. 3.5)
+        assert np.all(gPh[:, :, k, :][want == 0.0] == 0.0)
+    if storage != "f32":
+        master = oracle.backward_input(xh, P.cpu().numpy(), gyh, G)
+        assert rowwise_rel_err(gx.cpu().numpy(), master) <= TOL_HALF
+
+
+def test_backward_pieces_and_accumulate_flag(dev, oracle):
+    B, n_in, n_out, G = 90, 12, 70, 8
+    x, P, gy = _inputs(B, n_in, n_out, G, 41, dev)
+    desc = _desc(n_in, n_out, G)
+    gx_only, none = pkg.lmkan_backward(desc, x, P, gy, need_grad_coef=False)
+    assert none is None
+    none, gP_only = pkg.lmkan_backward(desc, x, None, gy, need_grad_x=False)
+    assert none is None
+    gx, gP = pkg.lmkan_backward(desc, x, P, gy)
+    torch.cuda.synchronize()
+    assert torch.equal(gx, gx_only)
+    want = oracle.backward_coef(x.cpu().numpy(), gy.cpu().numpy(), G)
+    for got in (gP, gP_only):
+        assert np.abs(got.cpu().numpy() - want).max() <= TOL_F32 * np.abs(want).max()
+    # accumulate: start from a known tensor, expect tensor + gradient
+    acc = torch.full_like(gP, 0.5)
+    dacc = _desc(n_in, n_out, G, flags=pkg.LMKAN_FLAG_ACCUMULATE_GRAD_COEF)
+    pkg.lmkan_backward(dacc, x, P, gy, need_grad_x=False, grad_coef=acc)
+    torch.cuda.synchronize()
+    assert np.abs(acc.cpu().numpy() - (want + 0.5)).max() <= 2e-5 * max(1.0, np.abs(want).max())
+    # overwrite really overwrites stale contents
+    stale = torch.full_like(gP, 123.0)
+    pkg.lmkan_backward(desc, x, P, gy, need_grad_x=False, grad_coef=stale)
+    torch.cuda.synchronize()
+    assert np.abs(stale.cpu().numpy() - want).max() <= TOL_F32 * np.abs(want).max()
+
+
+def test_empty_batch(dev):
+    desc = _desc(8, 5, 4)
+    x = torch.empty((0, 8), device=dev)
+    P = torch.randn(desc.coef_shape(), device=dev)
+    y = pkg.lmkan_forward(desc, x, P)
+    assert y.shape == (0, 5)
+    gy = torch.empty((0, 5), device=dev)
+    gP = torch.full(desc.coef_shape(), 7.0, device=dev)
+    gx, gP = pkg.lmkan_backward(desc, x, P, gy, grad_coef=gP)
+    torch.cuda.synchronize()
+    assert gx.shape == (0, 8) and torch.all(gP == 0)
+    assert pkg.lmkan_locate(desc, x).shape == (0, 4)
+
+
+def test_pack_layout(dev):
+    n_in, n_out, G = 6, 70, 4
+    desc = _desc(n_in, n_out, G)
+    P = torch.randn(desc.coef_shape(), device=dev)
+    packed = pkg.lmkan_pack(desc, P).cpu().reshape(2, 3, 25, 64)
+    Ph = P.cpu().reshape(25, 3, n_out)
+    for jt in range(2):
+        for k in range(3):
+            cols = min(64, n_out - jt * 64)
+            assert torch.equal(packed[jt, k, :, :cols], Ph[:, k, jt * 64: jt * 64 + cols])
+            assert torch.all(packed[jt, k, :, cols:] == 0)
+
+
+def test_nonfinite_inputs_stay_memory_safe(dev, oracle):
+    B, n_in, n_out, G = 16, 8, 10, 8
+    x, P, gy = _inputs(B, n_in, n_out, G, 51, dev)
+    x[0, 0] = float("nan")
+    x[1, 3] = float("inf")
+    x[2, 4] = float("-inf")
+    x[3, 5] = 1e30
+    desc = _desc(n_in, n_out, G)
+    y = pkg.lmkan_forward(desc, x, P)
+    gx, gP = pkg.lmkan_backward(desc, x, P, gy)
+    torch.cuda.synchronize()
+    # rows without a non-finite input are unaffected
+    want = oracle.forward(x[4:].cpu().numpy(), P.cpu().numpy(), G)
+    assert rowwise_rel_err(y[4:].cpu().numpy(), want) <= TOL_F32
+    assert torch.isnan(y[0]).all()
+    # the huge but finite input is a valid far extrapolation
+    want3 = oracle.forward(x[3:4].cpu().numpy(), P.cpu().numpy(), G)
+    assert rowwise_rel_err(y[3:4].cpu().numpy(), want3) <= TOL_F32
+
+
+def test_results_do_not_depend_on_the_stream(dev, oracle):
+    B, n_in, n_out, G = 300, 20, 96, 8
+    x, P, _ = _inputs(B, n_in, n_out, G, 61, dev)
+    desc = _desc(n_in, n_out, G)
+    y0 = pkg.lmkan_forward(desc, x, P)
+    s = torch.cuda.Stream()
+    s.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(s):
+        y1 = pkg.lmkan_forward(desc, x, P)
+    s.synchronize()
+    torch.cuda.synchronize()
+    assert torch.equal(y0, y1)
