@@ -108,9 +108,9 @@ size_t lmkan_packed_bytes(const lmkan_desc *desc)
 
 size_t lmkan_workspace_bytes(const lmkan_desc *desc, int64_t batch, int32_t pass)
 {
-    (void)batch;
-    (void)pass;
-    if (check_desc(desc) != LMKAN_OK) return 0;
+    if (check_desc(desc) != LMKAN_OK || batch <= 0) return 0;
+    const LayerShape s = shape_of(desc, batch);
+    if (pass == 0 && slab_forward_shape_ok(s)) return records_bytes(s);
     return 0;
 }
 
@@ -154,10 +154,17 @@ lmkan_status lmkan_forward(const lmkan_desc *desc, int64_t batch, const float *x
         return LMKAN_ERR_ALIGN;
     const size_t need = lmkan_workspace_bytes(desc, batch, 0);
     if (need > 0 && (!workspace_dev || workspace_bytes < need)) return LMKAN_ERR_WORKSPACE;
+    if (need > 0 && !aligned(workspace_dev, 256)) return LMKAN_ERR_ALIGN;
     GridTab tab;
     build_grid(desc->grid, &tab);
-    launch_forward_generic(shape_of(desc, batch), tab, x_dev, coef_dev, y_dev,
-                           static_cast<hipStream_t>(stream));
+    const LayerShape s = shape_of(desc, batch);
+    hipStream_t hs = static_cast<hipStream_t>(stream);
+    if (slab_forward_applicable(s, coef_dev, y_dev)) {
+        launch_preamble_records(s, tab, x_dev, workspace_dev, hs);
+        launch_forward_slab(s, coef_dev, y_dev, workspace_dev, hs);
+    } else {
+        launch_forward_generic(s, tab, x_dev, coef_dev, y_dev, hs);
+    }
     return launch_status();
 }
 

@@ -35,4 +35,15 @@ void launch_locate(const LayerShape &s, const GridTab &tab, const float *x, int3
 void launch_pack(const LayerShape &s, const void *src, void *dst, hipStream_t stream);
 void launch_fill_zero(float *p, size_t n, hipStream_t stream);
 
+// Tuned float32 forward (lmkan_slab.hip): preamble records in a workspace, coefficient
+// slabs streamed through LDS.
+size_t records_bytes(const LayerShape &s);
+size_t slab_forward_lds_bytes(const LayerShape &s);
+bool slab_forward_shape_ok(const LayerShape &s);
+bool slab_forward_applicable(const LayerShape &s, const void *coef, const float *y);
+void launch_preamble_records(const LayerShape &s, const GridTab &tab, const float *x, void *records,
+                             hipStream_t stream);
+void launch_forward_slab(const LayerShape &s, const void *coef, float *y, const void *records,
+                         hipStream_t stream);
+
 }  // namespace lmkan

@@ -1,0 +1,421 @@
+// Tuned float32 forward for layers whose table slab fits LDS twice.
+//
+// Work decomposition.  One workgroup owns a tile of samples x 64 outputs and
+// walks over (a range of) the input pairs.  For pair k the (G+1)^2 x 64
+// coefficient "slab" is streamed from global memory straight into LDS
+// (double buffered, LDS-direct 16-byte loads), while the accumulators
+// y[sample][output] stay in registers for the whole walk.
+//
+// Inside a wave the 64 lanes are 4 groups of 16; a group reads one 256-byte
+// table row with one ds_read_b128 per lane (conflict-free, full LDS rate), so a
+// wave processes 4 samples per step and each lane accumulates 4 outputs per
+// sample.  The preamble of Alg. 1 (cell + weights) is computed once per
+// (sample, pair) by a separate pass and stored as records; lane l of a wave
+// fetches the record of sample l, and the group that processes that sample takes
+// the weights directly from that lane's registers through the DPP row broadcast
+// of v_fmac_f32, so the four multiply-adds of Alg. 1 cost exactly four VALU
+// instructions per output quadruple.
+#include "lmkan_kernels.h"
+
+namespace lmkan {
+
+namespace {
+
+constexpr int kTile = LMKAN_PACK_TILE;  // 64 outputs per workgroup tile
+constexpr int kRowBytes = kTile * 4;    // one table row of a float32 slab in LDS
+
+// ---------------------------------------------------------------------------
+// Preamble pass (Alg. 1 "Preamble"): records[field][pair][sample]
+//   field 0: node = i1 (G+1) + i2 (int32), field 1: u, field 2: v  with
+//   u = (x1 - node[i1]) / h1, v likewise; the four B-spline products are
+//   (1-u)(1-v), u(1-v), (1-u)v, uv.
+// A 64 x 64 (sample x pair) tile is read along the rows of x, transposed
+// through LDS and written along the sample axis.
+// ---------------------------------------------------------------------------
+constexpr int kRecTile = 64;
+
+__global__ __launch_bounds__(256) void preamble_records_kernel(GridTab tab, const float *__restrict__ x,
+                                                              int32_t *__restrict__ rec_node,
+                                                              float *__restrict__ rec_u,
+                                                              float *__restrict__ rec_v, int64_t B,
+                                                              int n_in)
+{
+    __shared__ float s_node[LMKAN_MAX_GRID + 1];
+    __shared__ float s_invh[LMKAN_MAX_GRID];
+    __shared__ int s_n[kRecTile][kRecTile + 1];
+    __shared__ float s_u[kRecTile][kRecTile + 1];
+    __shared__ float s_v[kRecTile][kRecTile + 1];
+    for (int i = threadIdx.x; i <= tab.G; i += blockDim.x) s_node[i] = tab.node[i];
+    for (int i = threadIdx.x; i < tab.G; i += blockDim.x) s_invh[i] = tab.inv_h[i];
+    __syncthreads();
+
+    const int K = n_in / 2;
+    const int64_t n0 = (int64_t)blockIdx.x * kRecTile;
+    const int k0 = blockIdx.y * kRecTile;
+    const int p = threadIdx.x & 63;  // pair within tile (fast axis of the read)
+    const int r0 = threadIdx.x >> 6;
+#pragma unroll 4
+    for (int r = r0; r < kRecTile; r += 4) {
+        const int64_t n = n0 + r;
+        int node = 0;
+        float u = 0.f, v = 0.f;
+        if (n < B && k0 + p < K) {
+            const float2 xv = *reinterpret_cast<const float2 *>(x + n * n_in + 2 * (k0 + p));
+            const Preamble pr = preamble(s_node, s_invh, tab.G, xv.x, xv.y);
+            node = pr.node;
+            u = pr.a_hi;
+            v = pr.b_hi;
+        }
+        s_n[p][r] = node;
+        s_u[p][r] = u;
+        s_v[p][r] = v;
+    }
+    __syncthreads();
+    const int r = threadIdx.x & 63;  // sample within tile (fast axis of the write)
+    const int q0 = threadIdx.x >> 6;
+    const int64_t n = n0 + r;
+    if (n < B) {
+        for (int q = q0; q < kRecTile; q += 4) {
+            if (k0 + q < K) {
+                const int64_t o = (int64_t)(k0 + q) * B + n;
+                rec_node[o] = s_n[q][r];
+                rec_u[o] = s_u[q][r];
+                rec_v[o] = s_v[q][r];
+            }
+        }
+    }
+}
+
+// ---------------------------------------------------------------------------
+// DPP helpers.  row_newbcast:S makes every lane of a 16-lane row read lane S of
+// that row.
+// ---------------------------------------------------------------------------
+template <int S>
+__device__ __forceinline__ int row_bcast(int v)
+{
+    return __builtin_amdgcn_update_dpp(0, v, 0x150 + S, 0xf, 0xf, false);
+}
+
+// acc += (w of lane S of this row) * c
+template <int S>
+__device__ __forceinline__ void fmac_row_bcast(float &acc, float w, float c)
+{
+    asm("v_fmac_f32_dpp %0, %1, %2 row_newbcast:%3 row_mask:0xf bank_mask:0xf"
+        : "+v"(acc)
+        : "v"(w), "v"(c), "n"(S));
+}
+
+struct SlabArgs {
+    const float *x_unused;
+    const float *P;
+    float *y;
+    const int32_t *rec_node;
+    const float *rec_u;
+    const float *rec_v;
+    CoefMap map;
+    int64_t B;
+    int n_out;
+    int K;
+    int W;             // G + 1
+    int nodes;         // W * W
+    int pairs_per_split;
+    int n_btiles;
+    int n_jt;
+    int n_split;
+    int atomic_out;    // 1: add into y with atomics (split over pairs), 0: plain store
+};
+
+// 16 bytes per lane from global memory straight into LDS at lds_base + lane * 16
+// (lds_base wave-uniform).  Written as inline assembly on purpose: the compiler does not
+// track it, so it cannot make every later LDS read wait for loads that fill the *other*
+// buffer; completion is awaited explicitly with s_waitcnt vmcnt(0) before the barrier.
+__device__ __forceinline__ void lds_dma16(const void *gptr, unsigned lds_base)
+{
+    asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off"
+                 :
+                 : "v"(gptr), "s"(lds_base)
+                 : "memory");
+}
+
+__device__ __forceinline__ unsigned lds_address(const void *p)
+{
+    return (unsigned)(size_t)(__attribute__((address_space(3))) const void *)p;
+}
+
+// Stream the slab of (pair k, output tile jt) into LDS.  A wave instruction moves
+// 4 table rows (one per 16-lane group, 16 bytes per lane); the 1 KiB it writes is
+// contiguous in LDS.  Chunks are dealt round-robin to the waves.
+template <int WAVES>
+__device__ __forceinline__ void issue_slab_load(const SlabArgs &a, float *slab, int k, int jt, int wave,
+                                                int lane)
+{
+    const int g = lane >> 4, l16 = lane & 15;
+    const float *src = a.P + (int64_t)k * a.map.s_pair + (int64_t)jt * a.map.s_tile + l16 * 4;
+    const int chunks = (a.nodes + 3) >> 2;
+    const unsigned base = __builtin_amdgcn_readfirstlane(lds_address(slab));
+    for (int c = wave; c < chunks; c += WAVES) {
+        const int node = c * 4 + g;
+        if (node < a.nodes)
+            lds_dma16(src + (int64_t)node * a.map.s_node,
+                      __builtin_amdgcn_readfirstlane(base + c * (4 * kRowBytes)));
+    }
+}
+
+// The four table rows of one step: corners (i1,i2), (i1,i2+1), (i1+1,i2), (i1+1,i2+1).
+struct Corners {
+    float4 c00, c01, c10, c11;
+};
+
+template <int S>
+__device__ __forceinline__ void load_corners(Corners &c, const float *slab, int off_bytes, int lane_bytes,
+                                             int W)
+{
+    const float *rowp =
+        reinterpret_cast<const float *>(reinterpret_cast<const char *>(slab) + row_bcast<S>(off_bytes) + lane_bytes);
+    c.c00 = *reinterpret_cast<const float4 *>(rowp);
+    c.c01 = *reinterpret_cast<const float4 *>(rowp + kTile);
+    c.c10 = *reinterpret_cast<const float4 *>(rowp + W * kTile);
+    c.c11 = *reinterpret_cast<const float4 *>(rowp + W * kTile + kTile);
+}
+
+template <int S>
+__device__ __forceinline__ void fma_corners(float *acc, const Corners &c, float w00, float w10, float w01,
+                                            float w11)
+{
+    fmac_row_bcast<S>(acc[0], w00, c.c00.x);
+    fmac_row_bcast<S>(acc[1], w00, c.c00.y);
+    fmac_row_bcast<S>(acc[2], w00, c.c00.z);
+    fmac_row_bcast<S>(acc[3], w00, c.c00.w);
+    fmac_row_bcast<S>(acc[0], w10, c.c10.x);
+    fmac_row_bcast<S>(acc[1], w10, c.c10.y);
+    fmac_row_bcast<S>(acc[2], w10, c.c10.z);
+    fmac_row_bcast<S>(acc[3], w10, c.c10.w);
+    fmac_row_bcast<S>(acc[0], w01, c.c01.x);
+    fmac_row_bcast<S>(acc[1], w01, c.c01.y);
+    fmac_row_bcast<S>(acc[2], w01, c.c01.z);
+    fmac_row_bcast<S>(acc[3], w01, c.c01.w);
+    fmac_row_bcast<S>(acc[0], w11, c.c11.x);
+    fmac_row_bcast<S>(acc[1], w11, c.c11.y);
+    fmac_row_bcast<S>(acc[2], w11, c.c11.z);
+    fmac_row_bcast<S>(acc[3], w11, c.c11.w);
+}
+
+// Software pipeline over the SETS * 16 steps of one pair: the rows of step T + kAhead are
+// requested from LDS before the multiply-adds of step T are issued.
+constexpr int kAhead = 2;
+
+template <int T, int TOTAL>
+__device__ __forceinline__ void slab_pipeline(float *acc, Corners (&ring)[kAhead + 1], const float *slab,
+                                              const int *off, const float *w00, const float *w10,
+                                              const float *w01, const float *w11, int lane_bytes, int W)
+{
+    if constexpr (T < TOTAL) {
+        if constexpr (T + kAhead < TOTAL)
+            load_corners<(T + kAhead) % 16>(ring[(T + kAhead) % (kAhead + 1)], slab, off[(T + kAhead) / 16],
+                                            lane_bytes, W);
+        fma_corners<T % 16>(acc + 4 * T, ring[T % (kAhead + 1)], w00[T / 16], w10[T / 16], w01[T / 16],
+                            w11[T / 16]);
+        slab_pipeline<T + 1, TOTAL>(acc, ring, slab, off, w00, w10, w01, w11, lane_bytes, W);
+    }
+}
+
+// WAVES waves per workgroup, SETS x 64 samples per wave.
+// Two waves per SIMD by construction (one workgroup per CU); telling the compiler lets
+// it spend registers on keeping several LDS reads in flight.
+template <int WAVES, int SETS>
+__global__ __launch_bounds__(WAVES * 64) __attribute__((amdgpu_waves_per_eu(2, 2))) void forward_slab_kernel(SlabArgs a)
+{
+    extern __shared__ __align__(16) float smem[];
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);  // wave-uniform by construction
+    const int l16 = lane & 15, g = lane >> 4;
+    constexpr int kTileB = WAVES * SETS * 64;
+
+    // Workgroup -> (output tile, pair split, sample tile).  Consecutive ids go round-robin
+    // over the 8 XCDs, each with its own L2; workgroups that stream the same slabs
+    // (same output tile and pair range, different sample tile) are placed on one XCD.
+    int id = blockIdx.x;
+    const int total = gridDim.x;
+    if ((total & 7) == 0) id = (id & 7) * (total >> 3) + (id >> 3);
+    const int btile = id % a.n_btiles;
+    const int rest = id / a.n_btiles;
+    const int ks = rest % a.n_split;
+    const int jt = rest / a.n_split;
+
+    const int k_begin = ks * a.pairs_per_split;
+    const int k_end = min(a.K, k_begin + a.pairs_per_split);
+    const int slab_floats = a.nodes * kTile;
+    float *slab0 = smem;
+    float *slab1 = smem + slab_floats;
+
+    const int64_t n_wave = (int64_t)btile * kTileB + (int64_t)wave * (SETS * 64);
+
+    float acc[SETS * 64];
+#pragma unroll
+    for (int i = 0; i < SETS * 64; ++i) acc[i] = 0.0f;
+
+    // record of (sample n_wave + set*64 + lane, pair k), fetched one pair ahead
+    int nx_node[SETS];
+    float nx_u[SETS], nx_v[SETS];
+    auto fetch_records = [&](int k) {
+#pragma unroll
+        for (int s = 0; s < SETS; ++s) {
+            const int64_t n = n_wave + s * 64 + lane;
+            nx_node[s] = 0;
+            nx_u[s] = 0.f;
+            nx_v[s] = 0.f;
+            if (n < a.B) {
+                const int64_t o = (int64_t)k * a.B + n;
+                nx_node[s] = a.rec_node[o];
+                nx_u[s] = a.rec_u[o];
+                nx_v[s] = a.rec_v[o];
+            }
+        }
+    };
+
+    if (k_begin < k_end) {
+        issue_slab_load<WAVES>(a, slab0, k_begin, jt, wave, lane);
+        fetch_records(k_begin);
+    }
+    const int lane_bytes = l16 * 16;
+    for (int k = k_begin; k < k_end; ++k) {
+        const float *slab = ((k - k_begin) & 1) ? slab1 : slab0;
+        float *slab_next = ((k - k_begin) & 1) ? slab0 : slab1;
+
+        int off[SETS];
+        float w00[SETS], w10[SETS], w01[SETS], w11[SETS];
+#pragma unroll
+        for (int s = 0; s < SETS; ++s) {
+            const float u = nx_u[s], v = nx_v[s];
+            const float a_lo = 1.0f - u, b_lo = 1.0f - v;
+            off[s] = nx_node[s] * kRowBytes;
+            w00[s] = a_lo * b_lo;
+            w10[s] = u * b_lo;
+            w01[s] = a_lo * v;
+            w11[s] = u * v;
+        }
+        // this wave's slab loads for pair k have landed; after the barrier everybody's have,
+        // and everybody has finished reading the other buffer (pair k-1)
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        __syncthreads();
+        if (k + 1 < k_end) {
+            issue_slab_load<WAVES>(a, slab_next, k + 1, jt, wave, lane);
+            fetch_records(k + 1);
+        }
+#pragma unroll
+        for (int s = 0; s < SETS; ++s) {
+            // VALU results must not be read through DPP in the next two issue slots
+            asm volatile("s_nop 1" : "+v"(w00[s]), "+v"(w10[s]), "+v"(w01[s]), "+v"(w11[s]));
+        }
+        Corners ring[kAhead + 1];
+#pragma unroll
+        for (int t = 0; t < kAhead; ++t) {
+            if (t == 0) load_corners<0>(ring[0], slab, off[0], lane_bytes, a.W);
+            if (t == 1) load_corners<1>(ring[1], slab, off[0], lane_bytes, a.W);
+        }
+        slab_pipeline<0, SETS * 16>(acc, ring, slab, off, w00, w10, w01, w11, lane_bytes, a.W);
+    }
+
+    // lane (g, l16) holds outputs jt*64 + 4*l16 .. +3 of samples n_wave + set*64 + 16*g + step
+    const int col = jt * kTile + l16 * 4;
+    if (col < a.n_out) {
+#pragma unroll
+        for (int s = 0; s < SETS; ++s) {
+#pragma unroll
+            for (int st = 0; st < 16; ++st) {
+                const int64_t n = n_wave + s * 64 + g * 16 + st;
+                if (n < a.B) {
+                    float *dst = a.y + n * a.n_out + col;
+                    const float *v = acc + s * 64 + st * 4;
+                    if (a.atomic_out) {
+                        unsafeAtomicAdd(dst + 0, v[0]);
+                        unsafeAtomicAdd(dst + 1, v[1]);
+                        unsafeAtomicAdd(dst + 2, v[2]);
+                        unsafeAtomicAdd(dst + 3, v[3]);
+                    } else {
+                        *reinterpret_cast<float4 *>(dst) = make_float4(v[0], v[1], v[2], v[3]);
+                    }
+                }
+            }
+        }
+    }
+}
+
+}  // namespace
+
+size_t slab_forward_lds_bytes(const LayerShape &s)
+{
+    return (size_t)2 * s.nodes() * kRowBytes;
+}
+
+size_t records_bytes(const LayerShape &s)
+{
+    return (size_t)3 * (size_t)s.pairs() * (size_t)s.batch * 4;
+}
+
+void launch_preamble_records(const LayerShape &s, const GridTab &tab, const float *x, void *records,
+                             hipStream_t stream)
+{
+    const size_t n = (size_t)s.pairs() * (size_t)s.batch;
+    int32_t *rec_node = static_cast<int32_t *>(records);
+    float *rec_u = reinterpret_cast<float *>(rec_node + n);
+    float *rec_v = rec_u + n;
+    const dim3 grid((unsigned)((s.batch + kRecTile - 1) / kRecTile),
+                    (unsigned)((s.pairs() + kRecTile - 1) / kRecTile));
+    preamble_records_kernel<<<grid, 256, 0, stream>>>(tab, x, rec_node, rec_u, rec_v, s.batch, s.n_in);
+}
+
+bool slab_forward_shape_ok(const LayerShape &s)
+{
+    if (s.dtype != LMKAN_F32) return false;
+    if (s.n_out % 4 != 0) return false;
+    if (slab_forward_lds_bytes(s) > 160 * 1024) return false;
+    if (s.batch < 256) return false;  // too little work to pay for the slab streaming
+    return true;
+}
+
+bool slab_forward_applicable(const LayerShape &s, const void *coef, const float *y)
+{
+    if (!slab_forward_shape_ok(s)) return false;
+    return ((reinterpret_cast<uintptr_t>(coef) | reinterpret_cast<uintptr_t>(y)) & 15) == 0;
+}
+
+void launch_forward_slab(const LayerShape &s, const void *coef, float *y, const void *records,
+                         hipStream_t stream)
+{
+    constexpr int WAVES = 8, SETS = 2;
+    constexpr int kTileB = WAVES * SETS * 64;
+    static bool attr_set = false;
+    if (!attr_set) {
+        (void)hipFuncSetAttribute(reinterpret_cast<const void *>(forward_slab_kernel<WAVES, SETS>),
+                                  hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
+        attr_set = true;
+    }
+    const size_t n = (size_t)s.pairs() * (size_t)s.batch;
+    SlabArgs a;
+    a.x_unused = nullptr;
+    a.P = static_cast<const float *>(coef);
+    a.y = y;
+    a.rec_node = static_cast<const int32_t *>(records);
+    a.rec_u = reinterpret_cast<const float *>(a.rec_node + n);
+    a.rec_v = a.rec_u + n;
+    a.map = coef_map(s);
+    a.B = s.batch;
+    a.n_out = s.n_out;
+    a.K = s.pairs();
+    a.W = s.G + 1;
+    a.nodes = s.nodes();
+    a.n_btiles = (int)((s.batch + kTileB - 1) / kTileB);
+    a.n_jt = s.out_tiles();
+    // split the pairs over several workgroups when the tiles alone cannot fill 256 CUs
+    const int tiles = a.n_btiles * a.n_jt;
+    int split = 1;
+    while (tiles * split < 256 && a.K / (split * 2) >= 32) split *= 2;
+    a.n_split = split;
+    a.pairs_per_split = (a.K + split - 1) / split;
+    a.atomic_out = split > 1;
+    if (a.atomic_out) launch_fill_zero(y, (size_t)s.batch * s.n_out, stream);
+    forward_slab_kernel<WAVES, SETS><<<tiles * split, WAVES * 64, slab_forward_lds_bytes(s), stream>>>(a);
+}
+
+}  // namespace lmkan

@@ -56,6 +56,10 @@ SHAPES = [
     (100, 260, 256, 16),
     (64, 8, 200, 33),
     (40, 6, 70, 64),
+    # large enough for the LDS-slab forward: ragged sample tile, ragged output tile, pair split
+    (1100, 140, 132, 16),
+    (2053, 64, 64, 12),
+    (300, 10, 260, 3),
 ]
 
 
