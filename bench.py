@@ -1,0 +1,183 @@
+#!/usr/bin/env python3
+"""Benchmark of the lmKAN layer hot path on one MI355X.
+
+A step is one forward + one backward (gradients w.r.t. inputs and coefficients) of the
+headline layer: 1024 -> 1024, G = 16, batch 8192, float32 coefficients, synthetic seeded
+inputs already resident in HBM.  Prints ONE JSON line.
+"""
+from __future__ import annotations
+
+import argparse
+import ctypes as C
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+PEAK_FP32_VECTOR_TFLOPS = 157.3     # MI355X: 256 CU x 128 FMA/clk x 2 flop x 2.4 GHz
+PEAK_HBM_GBS = 8000.0
+
+
+def parse():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)      # the paper's protocol: 10 warm-up + 20 timed
+    ap.add_argument("--warmup", type=int, default=10)
+    ap.add_argument("--storage", default="f32", choices=["f32", "f16", "bf16"])
+    ap.add_argument("--workload", default="cfg3_1024x1024_G16")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-rows", type=int, default=8192)
+    return ap.parse_args()
+
+
+def main():
+    args = parse()
+    if args.gpus != 1:
+        print("bench.py measures one GPU only: this build has no multi-GPU path (--gpus must be 1)",
+              file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+
+    import paper_2509_07103_amd as pkg
+    from paper_2509_07103_amd import workloads as wl
+
+    if not torch.cuda.is_available():
+        print("bench.py needs a GPU", file=sys.stderr)
+        sys.exit(2)
+    dev = torch.device("cuda:0")
+    L = pkg.lib()
+    w = wl.BY_NAME[args.workload]
+    dt_code = {"f32": pkg.LMKAN_F32, "f16": pkg.LMKAN_F16, "bf16": pkg.LMKAN_BF16}[args.storage]
+    B, K, n_out = w.batch, w.n_in // 2, w.n_out
+
+    # ---- inputs, resident in HBM before anything is timed -------------------------------
+    x = wl.make_x(w, dev)
+    gy = wl.make_grad_y(w, dev)
+    P_master = wl.make_coef(w, dev)
+    P_stored = wl.store(P_master, args.storage).contiguous()
+    if args.storage != "f32":
+        del P_master
+    paper = pkg.LayerDesc(w.n_in, n_out, w.grid, coef_dtype=dt_code)
+    t0 = time.perf_counter()
+    P_packed = pkg.lmkan_pack(paper, P_stored)
+    torch.cuda.synchronize()
+    pack_ms = (time.perf_counter() - t0) * 1e3
+    desc = pkg.LayerDesc(w.n_in, n_out, w.grid, coef_dtype=dt_code, coef_layout=pkg.LMKAN_LAYOUT_PACKED)
+    desc_acc = pkg.LayerDesc(w.n_in, n_out, w.grid, coef_dtype=dt_code,
+                             coef_layout=pkg.LMKAN_LAYOUT_PACKED,
+                             flags=pkg.LMKAN_FLAG_ACCUMULATE_GRAD_COEF)
+
+    y = torch.empty((B, n_out), dtype=torch.float32, device=dev)
+    gx = torch.empty((B, w.n_in), dtype=torch.float32, device=dev)
+    gP = torch.empty(paper.coef_shape(), dtype=torch.float32, device=dev)
+    need = max(pkg.lmkan_workspace_bytes(desc, B, False), pkg.lmkan_workspace_bytes(desc, B, True), 256)
+    ws = torch.empty(need, dtype=torch.uint8, device=dev)
+    stream = torch.cuda.current_stream().cuda_stream
+    d, d_acc = desc.c(), desc_acc.c()
+
+    def forward():
+        st = L.lmkan_forward(C.byref(d), B, x.data_ptr(), P_packed.data_ptr(), y.data_ptr(),
+                             ws.data_ptr(), need, stream)
+        assert st == 0, pkg.lmkan_status_string(st)
+
+    def backward(dd=d):
+        st = L.lmkan_backward(C.byref(dd), B, x.data_ptr(), P_packed.data_ptr(), gy.data_ptr(),
+                              gx.data_ptr(), gP.data_ptr(), ws.data_ptr(), need, stream)
+        assert st == 0, pkg.lmkan_status_string(st)
+
+    def step():
+        forward()
+        backward()
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    ms_per_step = (time.perf_counter() - t0) * 1e3 / args.steps
+
+    # ---- per-call durations with events on the launch stream ------------------------------
+    def event_ms(fn, reps):
+        e0 = [torch.cuda.Event(enable_timing=True) for _ in range(reps)]
+        e1 = [torch.cuda.Event(enable_timing=True) for _ in range(reps)]
+        for i in range(reps):
+            e0[i].record()
+            fn()
+            e1[i].record()
+        torch.cuda.synchronize()
+        return float(np.mean([a.elapsed_time(b) for a, b in zip(e0, e1)]))
+
+    reps = max(3, min(args.steps, 20))
+    fwd_ms = event_ms(forward, reps)
+    bwd_ms = event_ms(backward, reps)
+    # the backward kernel alone: with the accumulate flag the call launches nothing else
+    bwd_kernel_ms = event_ms(lambda: backward(d_acc), reps)
+
+    fma_fwd = 4.0 * B * K * n_out                 # Alg. 1: four multiply-adds per (sample, pair, output)
+    fma_bwd = 2.0 * fma_fwd                       # the same four for grad_x and again for grad_coef
+    s_bytes = 4 if args.storage == "f32" else 2
+    if bwd_kernel_ms >= fwd_ms:
+        dom = {"kernel": "backward_generic_kernel", "flops": 2.0 * fma_bwd, "ms": bwd_kernel_ms}
+    else:
+        dom = {"kernel": "forward_slab_kernel (+preamble records, zero fill)", "flops": 2.0 * fma_fwd,
+               "ms": fwd_ms}
+    achieved = dom["flops"] / (dom["ms"] * 1e-3) / 1e12
+    roofline = {"bound": "alu", "achieved": round(achieved, 3), "peak": PEAK_FP32_VECTOR_TFLOPS,
+                "unit": "TFLOP/s", "frac": round(achieved / PEAK_FP32_VECTOR_TFLOPS, 4),
+                "traffic": None, "kernel": dom["kernel"], "kernel_ms": round(dom["ms"], 4)}
+
+    out = {
+        "metric": "lmKAN layer samples/sec (forward + backward, 1024->1024, 1 GPU)",
+        "value": round(B / (ms_per_step * 1e-3), 1),
+        "unit": "samples/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(ms_per_step, 4),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f32", "data": "synthetic",
+        "config": {"workload": f"{w.name}: n_in={w.n_in} n_out={n_out} G={w.grid} batch={B} "
+                               f"coef_storage={args.storage} x~{w.x_kind} coef~N(0,{w.coef_std})",
+                   "pass": "forward+backward(grad_x,grad_coef)", "coef_layout": "packed",
+                   "pack_ms_once": round(pack_ms, 3)},
+        "forward": {"ms": round(fwd_ms, 4), "samples_per_s": round(B / (fwd_ms * 1e-3), 1),
+                    "gather_GBps": round(fma_fwd * s_bytes / (fwd_ms * 1e-3) / 1e9, 1),
+                    "gather_vs_hbm_peak": round(fma_fwd * s_bytes / (fwd_ms * 1e-3) / 1e9 / PEAK_HBM_GBS, 3),
+                    "tflops": round(2 * fma_fwd / (fwd_ms * 1e-3) / 1e12, 3)},
+        "backward": {"ms": round(bwd_ms, 4), "samples_per_s": round(B / (bwd_ms * 1e-3), 1),
+                     "tflops": round(2 * fma_bwd / (bwd_ms * 1e-3) / 1e12, 3)},
+        "roofline": roofline,
+    }
+
+    # ---- CPU baseline: the oracle as it stands, on a bounded row sample ---------------------
+    if not args.no_cpu_baseline:
+        import oracle
+        o = oracle.get()
+        rows = min(args.cpu_rows, B)
+        xh = x[:rows].cpu().numpy()
+        gyh = gy[:rows].cpu().numpy()
+        Pc = P_stored.cpu().contiguous()
+        Ph = Pc.numpy() if args.storage == "f32" else Pc.view(torch.int16).numpy().view(np.uint16)
+        code = {"f32": 0, "f16": 1, "bf16": 2}[args.storage]
+        t0 = time.perf_counter()
+        o.forward(xh, Ph, w.grid, dtype=code, threads=1)
+        o.backward_input(xh, Ph, gyh, w.grid, dtype=code, threads=1)
+        for k in range(K):
+            o.backward_coef_pair(xh, gyh, w.grid, k)
+        cpu_s = time.perf_counter() - t0
+        out["cpu_baseline"] = {"value": round(rows / cpu_s, 3), "unit": "samples/s", "cores": 1,
+                               "kind": "oracle",
+                               "sample": f"first {rows} rows of the same batch through oracle forward, "
+                                         f"backward_input and backward_coef_pair for all {K} pairs "
+                                         f"(full-size table), {cpu_s:.1f} s"}
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()
