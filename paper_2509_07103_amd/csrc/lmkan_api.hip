@@ -12,6 +12,8 @@ namespace {
 
 size_t dtype_size(int dtype) { return dtype == LMKAN_F32 ? 4 : 2; }
 
+size_t align256(size_t n) { return (n + 255) & ~(size_t)255; }
+
 bool aligned(const void *p, size_t a) { return (reinterpret_cast<uintptr_t>(p) % a) == 0; }
 
 // Sec. 3.1 "Sigma grid" + App. B: real points where sigma crosses the levels k/G, with
@@ -110,8 +112,9 @@ size_t lmkan_workspace_bytes(const lmkan_desc *desc, int64_t batch, int32_t pass
 {
     if (check_desc(desc) != LMKAN_OK || batch <= 0) return 0;
     const LayerShape s = shape_of(desc, batch);
-    if (pass == 0 && slab_forward_shape_ok(s)) return records_bytes(s);
-    return 0;
+    if (pass == 0) return slab_forward_shape_ok(s) ? records_bytes(s) : 0;
+    // backward: preamble records, then the cell-sorted copy used by the coefficient gradient
+    return align256(records_bytes(s)) + sorted_records_bytes(s);
 }
 
 lmkan_status lmkan_pack(const lmkan_desc *desc, const void *coef_paper_dev, void *coef_packed_dev,
@@ -195,13 +198,19 @@ lmkan_status lmkan_backward(const lmkan_desc *desc, int64_t batch, const float *
         (grad_coef_dev && !aligned(grad_coef_dev, 4)) ||
         (coef_dev && !aligned(coef_dev, dtype_size(desc->coef_dtype))))
         return LMKAN_ERR_ALIGN;
-    const size_t need = lmkan_workspace_bytes(desc, batch, 1);
+    const size_t need = grad_coef_dev ? lmkan_workspace_bytes(desc, batch, 1) : 0;
     if (need > 0 && (!workspace_dev || workspace_bytes < need)) return LMKAN_ERR_WORKSPACE;
+    if (need > 0 && !aligned(workspace_dev, 256)) return LMKAN_ERR_ALIGN;
     GridTab tab;
     build_grid(desc->grid, &tab);
-    if (grad_coef_dev && overwrite)
-        launch_fill_zero(grad_coef_dev, (size_t)s.nodes() * s.pairs() * s.n_out, hs);
-    launch_backward_generic(s, tab, x_dev, coef_dev, grad_y_dev, grad_x_dev, grad_coef_dev, hs);
+    if (grad_coef_dev) {
+        char *ws = static_cast<char *>(workspace_dev);
+        launch_preamble_records(s, tab, x_dev, ws, hs);
+        launch_backward_coef_sorted(s, ws, ws + align256(records_bytes(s)), grad_y_dev, grad_coef_dev,
+                                    !overwrite, hs);
+    }
+    if (grad_x_dev)
+        launch_backward_generic(s, tab, x_dev, coef_dev, grad_y_dev, grad_x_dev, nullptr, hs);
     return launch_status();
 }
 

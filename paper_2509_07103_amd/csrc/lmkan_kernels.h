@@ -46,4 +46,10 @@ void launch_preamble_records(const LayerShape &s, const GridTab &tab, const floa
 void launch_forward_slab(const LayerShape &s, const void *coef, float *y, const void *records,
                          hipStream_t stream);
 
+// Coefficient gradient by cell-sorted samples (lmkan_backward.hip).  `records` is the output
+// of launch_preamble_records; `sorted` is scratch of sorted_records_bytes().
+size_t sorted_records_bytes(const LayerShape &s);
+void launch_backward_coef_sorted(const LayerShape &s, const void *records, void *sorted, const float *gy,
+                                 float *gcoef, bool accumulate, hipStream_t stream);
+
 }  // namespace lmkan
