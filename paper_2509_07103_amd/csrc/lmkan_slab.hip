@@ -15,6 +15,8 @@
 // the weights directly from that lane's registers through the DPP row broadcast
 // of v_fmac_f32, so the four multiply-adds of Alg. 1 cost exactly four VALU
 // instructions per output quadruple.
+#include <utility>
+
 #include "lmkan_kernels.h"
 
 namespace lmkan {
@@ -105,6 +107,12 @@ __device__ __forceinline__ void fmac_row_bcast(float &acc, float w, float c)
         : "v"(w), "v"(c), "n"(S));
 }
 
+template <int... Ts, class F>
+__device__ __forceinline__ void static_for(std::integer_sequence<int, Ts...>, F &&f)
+{
+    (f(std::integral_constant<int, Ts>{}), ...);
+}
+
 struct SlabArgs {
     const float *x_unused;
     const float *P;
@@ -118,6 +126,7 @@ struct SlabArgs {
     int K;
     int W;             // G + 1
     int nodes;         // W * W
+    int col_limit;     // columns >= col_limit do not exist in the coefficient tensor
     int pairs_per_split;
     int n_btiles;
     int n_jt;
@@ -153,9 +162,10 @@ __device__ __forceinline__ void issue_slab_load(const SlabArgs &a, float *slab, 
     const float *src = a.P + (int64_t)k * a.map.s_pair + (int64_t)jt * a.map.s_tile + l16 * 4;
     const int chunks = (a.nodes + 3) >> 2;
     const unsigned base = __builtin_amdgcn_readfirstlane(lds_address(slab));
+    const bool col_ok = jt * kTile + l16 * 4 < a.col_limit;  // never read past a table row
     for (int c = wave; c < chunks; c += WAVES) {
         const int node = c * 4 + g;
-        if (node < a.nodes)
+        if (node < a.nodes && col_ok)
             lds_dma16(src + (int64_t)node * a.map.s_node,
                       __builtin_amdgcn_readfirstlane(base + c * (4 * kRowBytes)));
     }
@@ -341,6 +351,202 @@ __global__ __launch_bounds__(WAVES * 64) __attribute__((amdgpu_waves_per_eu(2, 2
     }
 }
 
+// ---------------------------------------------------------------------------
+// Input gradient with the same slab streaming.
+//   s_ab(n,k) = sum_j gy[n][j] P[corner ab][k][j]
+//   d/dx1 = (1/h1) ((s10 - s00)(1 - v) + (s11 - s01) v),  d/dx2 = (1/h2) ((s01 - s00)(1 - u) + (s11 - s10) u)
+// The roles of the forward kernel are mirrored: gy[sample][4 outputs] stays in registers, a
+// step forms the four partial dot products of its lane, combines them with the weights of
+// the owning lane (DPP row broadcast) and sums over the 16 lanes that share the sample with
+// DPP row operations.  The two derivatives travel together through the reduction: lanes
+// 0-7 of a row end up with d/dx1, lanes 8-15 with d/dx2.  Results of eight steps are
+// collected across the lanes and added into grad_x with one atomic instruction (the
+// output tiles of a sample are spread over several workgroups).
+// ---------------------------------------------------------------------------
+struct GradInArgs {
+    const float *P;
+    const float *gy;
+    float *gx;
+    const int32_t *rec_node;
+    const float *rec_u;
+    const float *rec_v;
+    CoefMap map;
+    GridTab tab;
+    int64_t B;
+    int n_in;
+    int n_out;
+    int K;
+    int W;
+    int nodes;
+    int pairs_per_split;
+    int n_btiles;
+    int n_jt;
+    int n_split;
+    int col_limit;
+};
+
+template <int CTRL>
+__device__ __forceinline__ float dpp_move(float v)
+{
+    return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), CTRL, 0xf, 0xf, false));
+}
+
+// d = (w of lane S of this row) * x
+template <int S>
+__device__ __forceinline__ float mul_row_bcast(float w, float x)
+{
+    float d;
+    asm("v_mul_f32_dpp %0, %1, %2 row_newbcast:%3 row_mask:0xf bank_mask:0xf" : "=v"(d) : "v"(w), "v"(x), "n"(S));
+    return d;
+}
+
+struct GradRecord {
+    int off;
+    float b_lo, b_hi;  // (1 - v) / h1, v / h1
+    float a_lo, a_hi;  // (1 - u) / h2, u / h2
+};
+
+// returns, in lanes 0-7 of each row, the row's d/dx1 and, in lanes 8-15, its d/dx2
+template <int S>
+__device__ __forceinline__ float grad_step(const float4 g, const Corners &c, const GradRecord &r, bool upper)
+{
+    const float s00 = fmaf(g.w, c.c00.w, fmaf(g.z, c.c00.z, fmaf(g.y, c.c00.y, g.x * c.c00.x)));
+    const float s10 = fmaf(g.w, c.c10.w, fmaf(g.z, c.c10.z, fmaf(g.y, c.c10.y, g.x * c.c10.x)));
+    const float s01 = fmaf(g.w, c.c01.w, fmaf(g.z, c.c01.z, fmaf(g.y, c.c01.y, g.x * c.c01.x)));
+    const float s11 = fmaf(g.w, c.c11.w, fmaf(g.z, c.c11.z, fmaf(g.y, c.c11.y, g.x * c.c11.x)));
+    float t1 = mul_row_bcast<S>(r.b_lo, s10 - s00);
+    fmac_row_bcast<S>(t1, r.b_hi, s11 - s01);
+    float t2 = mul_row_bcast<S>(r.a_lo, s01 - s00);
+    fmac_row_bcast<S>(t2, r.a_hi, s11 - s10);
+    // lanes 0-7 collect t1 of all 16 lanes, lanes 8-15 collect t2
+    const float keep = upper ? t2 : t1;
+    const float send = upper ? t1 : t2;
+    float v = keep + dpp_move<0x128>(send);  // row_ror:8
+    v += dpp_move<0xB1>(v);                  // quad_perm [1,0,3,2]
+    v += dpp_move<0x4E>(v);                  // quad_perm [2,3,0,1]
+    v += dpp_move<0x141>(v);                 // row_half_mirror
+    return v;
+}
+
+template <int WAVES, int SETS>
+__global__ __launch_bounds__(WAVES * 64) __attribute__((amdgpu_waves_per_eu(2, 2))) void backward_input_slab_kernel(
+    GradInArgs a)
+{
+    extern __shared__ __align__(16) float smem[];  // two slab buffers, then 1/h of the grid
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int l16 = lane & 15, g = lane >> 4;
+    constexpr int kTileB = WAVES * SETS * 64;
+    constexpr int TOTAL = SETS * 16;
+    int id = blockIdx.x;
+    const int total = gridDim.x;
+    if ((total & 7) == 0) id = (id & 7) * (total >> 3) + (id >> 3);
+    const int btile = id % a.n_btiles;
+    const int rest = id / a.n_btiles;
+    const int ks = rest % a.n_split;
+    const int jt = rest / a.n_split;
+
+    const int k_begin = ks * a.pairs_per_split;
+    const int k_end = min(a.K, k_begin + a.pairs_per_split);
+    const int slab_floats = a.nodes * kTile;
+    float *slab0 = smem;
+    float *slab1 = smem + slab_floats;
+    float *s_invh = smem + 2 * slab_floats;
+    for (int i = threadIdx.x; i < a.tab.G; i += blockDim.x) s_invh[i] = a.tab.inv_h[i];
+    SlabArgs sa;  // only the fields issue_slab_load reads
+    sa.P = a.P;
+    sa.map = a.map;
+    sa.nodes = a.nodes;
+    sa.col_limit = a.col_limit;
+
+    const int64_t n_wave = (int64_t)btile * kTileB + (int64_t)wave * (SETS * 64);
+    const int col = jt * kTile + l16 * 4;
+    const bool upper = (l16 & 8) != 0;
+
+    // gy of (sample n_wave + set*64 + 16 g + step, outputs col .. col+3), resident for the walk
+    float4 gyr[TOTAL];
+#pragma unroll
+    for (int t = 0; t < TOTAL; ++t) {
+        const int64_t n = n_wave + (t / 16) * 64 + g * 16 + (t % 16);
+        gyr[t] = make_float4(0.f, 0.f, 0.f, 0.f);
+        if (n < a.B && col < a.n_out) gyr[t] = *reinterpret_cast<const float4 *>(a.gy + n * a.n_out + col);
+    }
+
+    int nx_node[SETS];
+    float nx_u[SETS], nx_v[SETS];
+    auto fetch_records = [&](int k) {
+#pragma unroll
+        for (int s = 0; s < SETS; ++s) {
+            const int64_t n = n_wave + s * 64 + lane;
+            nx_node[s] = 0;
+            nx_u[s] = 0.f;
+            nx_v[s] = 0.f;
+            if (n < a.B) {
+                const int64_t o = (int64_t)k * a.B + n;
+                nx_node[s] = a.rec_node[o];
+                nx_u[s] = a.rec_u[o];
+                nx_v[s] = a.rec_v[o];
+            }
+        }
+    };
+
+    // columns past the end of a ragged output tile are never loaded: make them read as zero
+    for (int i = threadIdx.x; i < 2 * slab_floats; i += blockDim.x) smem[i] = 0.0f;
+    __syncthreads();  // zeros and s_invh in place before any slab load lands
+    if (k_begin < k_end) {
+        issue_slab_load<WAVES>(sa, slab0, k_begin, jt, wave, lane);
+        fetch_records(k_begin);
+    }
+    const int lane_bytes = l16 * 16;
+    // where this lane's collected results go: sample 16 g + (l16 & 7) of each block of 8 steps,
+    // input 2k (lanes 0-7) or 2k+1 (lanes 8-15)
+    const int64_t n_lane = n_wave + g * 16 + (l16 & 7);
+    float *gx_lane = a.gx + n_lane * a.n_in + (l16 >> 3);
+
+    for (int k = k_begin; k < k_end; ++k) {
+        const float *slab = ((k - k_begin) & 1) ? slab1 : slab0;
+        float *slab_next = ((k - k_begin) & 1) ? slab0 : slab1;
+
+        GradRecord rec[SETS];
+#pragma unroll
+        for (int s = 0; s < SETS; ++s) {
+            const int node = nx_node[s];
+            const float rh1 = s_invh[node / a.W], rh2 = s_invh[node % a.W];
+            rec[s].off = node * kRowBytes;
+            rec[s].b_lo = (1.0f - nx_v[s]) * rh1;
+            rec[s].b_hi = nx_v[s] * rh1;
+            rec[s].a_lo = (1.0f - nx_u[s]) * rh2;
+            rec[s].a_hi = nx_u[s] * rh2;
+        }
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        __syncthreads();
+        if (k + 1 < k_end) {
+            issue_slab_load<WAVES>(sa, slab_next, k + 1, jt, wave, lane);
+            fetch_records(k + 1);
+        }
+#pragma unroll
+        for (int s = 0; s < SETS; ++s)
+            asm volatile("s_nop 1" : "+v"(rec[s].b_lo), "+v"(rec[s].b_hi), "+v"(rec[s].a_lo), "+v"(rec[s].a_hi));
+
+        Corners ring[kAhead + 1];
+        load_corners<0>(ring[0], slab, rec[0].off, lane_bytes, a.W);
+        load_corners<1>(ring[1], slab, rec[0].off, lane_bytes, a.W);
+        float stash = 0.0f;
+        static_for(std::make_integer_sequence<int, TOTAL>{}, [&](auto tc) {
+            constexpr int T = decltype(tc)::value;
+            if constexpr (T + kAhead < TOTAL)
+                load_corners<(T + kAhead) % 16>(ring[(T + kAhead) % (kAhead + 1)], slab,
+                                                rec[(T + kAhead) / 16].off, lane_bytes, a.W);
+            const float v = grad_step<T % 16>(gyr[T], ring[T % (kAhead + 1)], rec[T / 16], upper);
+            if ((l16 & 7) == (T & 7)) stash = v;
+            if constexpr ((T & 7) == 7) {
+                const int64_t n = n_lane + (T / 16) * 64 + ((T % 16) & ~7);
+                if (n < a.B) unsafeAtomicAdd(gx_lane + (int64_t)((T / 16) * 64 + ((T % 16) & ~7)) * a.n_in + 2 * k, stash);
+            }
+        });
+    }
+}
+
 }  // namespace
 
 size_t slab_forward_lds_bytes(const LayerShape &s)
@@ -405,6 +611,7 @@ void launch_forward_slab(const LayerShape &s, const void *coef, float *y, const 
     a.K = s.pairs();
     a.W = s.G + 1;
     a.nodes = s.nodes();
+    a.col_limit = s.layout == LMKAN_LAYOUT_PACKED ? s.out_tiles() * kTile : s.n_out;
     a.n_btiles = (int)((s.batch + kTileB - 1) / kTileB);
     a.n_jt = s.out_tiles();
     // split the pairs over several workgroups when the tiles alone cannot fill 256 CUs
@@ -416,6 +623,57 @@ void launch_forward_slab(const LayerShape &s, const void *coef, float *y, const 
     a.atomic_out = split > 1;
     if (a.atomic_out) launch_fill_zero(y, (size_t)s.batch * s.n_out, stream);
     forward_slab_kernel<WAVES, SETS><<<tiles * split, WAVES * 64, slab_forward_lds_bytes(s), stream>>>(a);
+}
+
+}  // namespace lmkan
+
+namespace lmkan {
+
+bool slab_backward_input_applicable(const LayerShape &s, const void *coef, const float *gy, const float *gx)
+{
+    if (!slab_forward_shape_ok(s)) return false;
+    return ((reinterpret_cast<uintptr_t>(coef) | reinterpret_cast<uintptr_t>(gy)) & 15) == 0 &&
+           (reinterpret_cast<uintptr_t>(gx) & 3) == 0;
+}
+
+void launch_backward_input_slab(const LayerShape &s, const GridTab &tab, const void *coef, const float *gy,
+                                float *gx, const void *records, hipStream_t stream)
+{
+    constexpr int WAVES = 8, SETS = 2;
+    constexpr int kTileB = WAVES * SETS * 64;
+    auto kernel = backward_input_slab_kernel<WAVES, SETS>;
+    static bool attr_set = false;
+    if (!attr_set) {
+        (void)hipFuncSetAttribute(reinterpret_cast<const void *>(kernel),
+                                  hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
+        attr_set = true;
+    }
+    const size_t n = (size_t)s.pairs() * (size_t)s.batch;
+    GradInArgs a;
+    a.P = static_cast<const float *>(coef);
+    a.gy = gy;
+    a.gx = gx;
+    a.rec_node = static_cast<const int32_t *>(records);
+    a.rec_u = reinterpret_cast<const float *>(a.rec_node + n);
+    a.rec_v = a.rec_u + n;
+    a.map = coef_map(s);
+    a.tab = tab;
+    a.B = s.batch;
+    a.n_in = s.n_in;
+    a.n_out = s.n_out;
+    a.K = s.pairs();
+    a.W = s.G + 1;
+    a.nodes = s.nodes();
+    a.col_limit = s.layout == LMKAN_LAYOUT_PACKED ? s.out_tiles() * kTile : s.n_out;
+    a.n_btiles = (int)((s.batch + kTileB - 1) / kTileB);
+    a.n_jt = s.out_tiles();
+    const int tiles = a.n_btiles * a.n_jt;
+    int split = 1;
+    while (tiles * split < 256 && a.K / (split * 2) >= 32) split *= 2;
+    a.n_split = split;
+    a.pairs_per_split = (a.K + split - 1) / split;
+    launch_fill_zero(gx, (size_t)s.batch * s.n_in, stream);
+    kernel<<<tiles * split, WAVES * 64, slab_forward_lds_bytes(s) + LMKAN_MAX_GRID * sizeof(float), stream>>>(a);
 }
 
 }  // namespace lmkan
