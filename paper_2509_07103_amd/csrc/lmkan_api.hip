@@ -113,8 +113,10 @@ size_t lmkan_workspace_bytes(const lmkan_desc *desc, int64_t batch, int32_t pass
     if (check_desc(desc) != LMKAN_OK || batch <= 0) return 0;
     const LayerShape s = shape_of(desc, batch);
     if (pass == 0) return slab_forward_shape_ok(s) ? records_bytes(s) : 0;
-    // backward: preamble records, then the cell-sorted copy used by the coefficient gradient
-    return align256(records_bytes(s)) + sorted_records_bytes(s);
+    // backward: preamble records, the cell-sorted copy used by the coefficient gradient, and the
+    // transposed scratch of the input gradient
+    return align256(records_bytes(s)) + sorted_records_bytes(s) +
+           (slab_forward_shape_ok(s) ? slab_backward_input_scratch_bytes(s) : 0);
 }
 
 lmkan_status lmkan_pack(const lmkan_desc *desc, const void *coef_paper_dev, void *coef_packed_dev,
@@ -199,8 +201,7 @@ lmkan_status lmkan_backward(const lmkan_desc *desc, int64_t batch, const float *
         (coef_dev && !aligned(coef_dev, dtype_size(desc->coef_dtype))))
         return LMKAN_ERR_ALIGN;
     const bool gx_slab = grad_x_dev && slab_backward_input_applicable(s, coef_dev, grad_y_dev, grad_x_dev);
-    const size_t need = grad_coef_dev ? lmkan_workspace_bytes(desc, batch, 1)
-                                      : (gx_slab ? records_bytes(s) : 0);
+    const size_t need = (grad_coef_dev || gx_slab) ? lmkan_workspace_bytes(desc, batch, 1) : 0;
     if (need > 0 && (!workspace_dev || workspace_bytes < need)) return LMKAN_ERR_WORKSPACE;
     if (need > 0 && !aligned(workspace_dev, 256)) return LMKAN_ERR_ALIGN;
     GridTab tab;
@@ -212,7 +213,8 @@ lmkan_status lmkan_backward(const lmkan_desc *desc, int64_t batch, const float *
                                     !overwrite, hs);
     }
     if (gx_slab)
-        launch_backward_input_slab(s, tab, coef_dev, grad_y_dev, grad_x_dev, ws, hs);
+        launch_backward_input_slab(s, tab, coef_dev, grad_y_dev, grad_x_dev, ws,
+                                   ws + align256(records_bytes(s)) + sorted_records_bytes(s), hs);
     else if (grad_x_dev)
         launch_backward_generic(s, tab, x_dev, coef_dev, grad_y_dev, grad_x_dev, nullptr, hs);
     return launch_status();

@@ -47,8 +47,9 @@ void launch_forward_slab(const LayerShape &s, const void *coef, float *y, const 
                          hipStream_t stream);
 
 bool slab_backward_input_applicable(const LayerShape &s, const void *coef, const float *gy, const float *gx);
+size_t slab_backward_input_scratch_bytes(const LayerShape &s);
 void launch_backward_input_slab(const LayerShape &s, const GridTab &tab, const void *coef, const float *gy,
-                                float *gx, const void *records, hipStream_t stream);
+                                float *gx, const void *records, void *scratch, hipStream_t stream);
 
 // Coefficient gradient by cell-sorted samples (lmkan_backward.hip).  `records` is the output
 // of launch_preamble_records; `sorted` is scratch of sorted_records_bytes().

@@ -366,7 +366,7 @@ __global__ __launch_bounds__(WAVES * 64) __attribute__((amdgpu_waves_per_eu(2, 2
 struct GradInArgs {
     const float *P;
     const float *gy;
-    float *gx;
+    float *gx;  // transposed scratch [n_in][B], zero on entry
     const int32_t *rec_node;
     const float *rec_u;
     const float *rec_v;
@@ -384,6 +384,21 @@ struct GradInArgs {
     int n_split;
     int col_limit;
 };
+
+// out[B][n_in] = in[n_in][B]
+__global__ __launch_bounds__(256) void transpose_kernel(const float *__restrict__ in, float *__restrict__ out,
+                                                       int64_t B, int n_in)
+{
+    __shared__ float tile[64][65];
+    const int64_t n0 = (int64_t)blockIdx.x * 64;
+    const int c0 = blockIdx.y * 64;
+    const int tx = threadIdx.x & 63, ty = threadIdx.x >> 6;
+    for (int r = ty; r < 64; r += 4)
+        if (c0 + r < n_in && n0 + tx < B) tile[r][tx] = in[(int64_t)(c0 + r) * B + n0 + tx];
+    __syncthreads();
+    for (int r = ty; r < 64; r += 4)
+        if (n0 + r < B && c0 + tx < n_in) out[(n0 + r) * n_in + c0 + tx] = tile[tx][r];
+}
 
 template <int CTRL>
 __device__ __forceinline__ float dpp_move(float v)
@@ -499,9 +514,10 @@ __global__ __launch_bounds__(WAVES * 64) __attribute__((amdgpu_waves_per_eu(2, 2
     }
     const int lane_bytes = l16 * 16;
     // where this lane's collected results go: sample 16 g + (l16 & 7) of each block of 8 steps,
-    // input 2k (lanes 0-7) or 2k+1 (lanes 8-15)
+    // input 2k (lanes 0-7) or 2k+1 (lanes 8-15).  The scratch gradient is stored transposed,
+    // [n_in][B], so that the eight lanes of a block hit 32 contiguous bytes.
     const int64_t n_lane = n_wave + g * 16 + (l16 & 7);
-    float *gx_lane = a.gx + n_lane * a.n_in + (l16 >> 3);
+    float *gx_lane = a.gx + (int64_t)(l16 >> 3) * a.B + n_lane;
 
     for (int k = k_begin; k < k_end; ++k) {
         const float *slab = ((k - k_begin) & 1) ? slab1 : slab0;
@@ -541,7 +557,7 @@ __global__ __launch_bounds__(WAVES * 64) __attribute__((amdgpu_waves_per_eu(2, 2
             if ((l16 & 7) == (T & 7)) stash = v;
             if constexpr ((T & 7) == 7) {
                 const int64_t n = n_lane + (T / 16) * 64 + ((T % 16) & ~7);
-                if (n < a.B) unsafeAtomicAdd(gx_lane + (int64_t)((T / 16) * 64 + ((T % 16) & ~7)) * a.n_in + 2 * k, stash);
+                if (n < a.B) unsafeAtomicAdd(gx_lane + (int64_t)(2 * k) * a.B + ((T / 16) * 64 + ((T % 16) & ~7)), stash);
             }
         });
     }
@@ -636,8 +652,13 @@ bool slab_backward_input_applicable(const LayerShape &s, const void *coef, const
            (reinterpret_cast<uintptr_t>(gx) & 3) == 0;
 }
 
+size_t slab_backward_input_scratch_bytes(const LayerShape &s)
+{
+    return ((size_t)s.batch * s.n_in * sizeof(float) + 255) & ~(size_t)255;
+}
+
 void launch_backward_input_slab(const LayerShape &s, const GridTab &tab, const void *coef, const float *gy,
-                                float *gx, const void *records, hipStream_t stream)
+                                float *gx, const void *records, void *scratch, hipStream_t stream)
 {
     constexpr int WAVES = 8, SETS = 2;
     constexpr int kTileB = WAVES * SETS * 64;
@@ -652,7 +673,7 @@ void launch_backward_input_slab(const LayerShape &s, const GridTab &tab, const v
     GradInArgs a;
     a.P = static_cast<const float *>(coef);
     a.gy = gy;
-    a.gx = gx;
+    a.gx = static_cast<float *>(scratch);
     a.rec_node = static_cast<const int32_t *>(records);
     a.rec_u = reinterpret_cast<const float *>(a.rec_node + n);
     a.rec_v = a.rec_u + n;
@@ -672,8 +693,10 @@ void launch_backward_input_slab(const LayerShape &s, const GridTab &tab, const v
     while (tiles * split < 256 && a.K / (split * 2) >= 32) split *= 2;
     a.n_split = split;
     a.pairs_per_split = (a.K + split - 1) / split;
-    launch_fill_zero(gx, (size_t)s.batch * s.n_in, stream);
+    launch_fill_zero(a.gx, (size_t)s.batch * s.n_in, stream);
     kernel<<<tiles * split, WAVES * 64, slab_forward_lds_bytes(s) + LMKAN_MAX_GRID * sizeof(float), stream>>>(a);
+    const dim3 tgrid((unsigned)((s.batch + 63) / 64), (unsigned)((s.n_in + 63) / 64));
+    transpose_kernel<<<tgrid, 256, 0, stream>>>(a.gx, gx, s.batch, s.n_in);
 }
 
 }  // namespace lmkan
