@@ -4,7 +4,8 @@
 //                    B_ab(x_n) * gy[n][j]                  (derivative of Alg. 1's sum)
 //
 // Pass 1 (sort_records_kernel): for every pair k the samples are grouped by cell with a
-// counting sort, and the four B-spline products are stored next to the sample index.
+// counting sort, each cell padded to whole chunks of four samples, and the four B-spline
+// products are stored next to the sample index.
 // Pass 2 (backward_coef_sorted_kernel): one wave owns (pair k, 64 outputs) and walks the
 // sorted samples, cell after cell.  Inside a cell the four corner sums live in registers (lanes = outputs,
 // weights are wave-uniform scalars), so a value of gy feeds four multiply-adds.  Finished
@@ -23,38 +24,61 @@ constexpr int kSortThreads = 1024;
 
 typedef float f4v __attribute__((ext_vector_type(4)));
 
-// records_in: [3][K][B] (node, u, v) from the preamble pass.
-// sorted_n / sorted_cell: [K][B] sample index and i1 << 8 | i2, grouped by cell in increasing
-//             order of i1 * G + i2;  sorted_w: [K][B] the four products (w00, w10, w01, w11).
+constexpr int kChunk = 4;  // samples per chunk; a chunk never straddles two cells
+constexpr int kDepth = 6;  // chunks of gy values in flight
+
+// Samples per pair in the sorted stream: every non-empty cell is padded to whole chunks with
+// zero-weight entries, and the end is padded so that the pipeline below can run (and
+// prefetch) over whole groups of kDepth chunks without bounds checks.
+__host__ __device__ inline int64_t stream_stride(int64_t B, int G)
+{
+    const int64_t body = (B + (int64_t)(kChunk - 1) * G * G + kChunk - 1) / kChunk * kChunk;
+    return body + (int64_t)kChunk * (2 * kDepth + 2);
+}
+
+// records_in: [3][K][B] (node, u, v) from the preamble pass.  Per pair k, with S = stream_stride:
+//   sorted_n [K][S]      sample index (0 in padding entries)
+//   sorted_w [K][S]      the four products (w00, w10, w01, w11), zero in padding entries
+//   chunk_cell [K][S/4]  i1 << 8 | i2 of the cell each chunk belongs to, non-decreasing
+//   n_chunks [K]         chunks to process, a multiple of kDepth
 __global__ __launch_bounds__(kSortThreads) void sort_records_kernel(const int32_t *__restrict__ rec_node,
                                                                    const float *__restrict__ rec_u,
                                                                    const float *__restrict__ rec_v,
                                                                    int32_t *__restrict__ sorted_n,
-                                                                   int32_t *__restrict__ sorted_cell,
-                                                                   f4v *__restrict__ sorted_w, int64_t B,
+                                                                   f4v *__restrict__ sorted_w,
+                                                                   int32_t *__restrict__ chunk_cell,
+                                                                   int32_t *__restrict__ n_chunks, int64_t B,
                                                                    int G)
 {
-    __shared__ int s_count[LMKAN_MAX_GRID * LMKAN_MAX_GRID + 1];
+    __shared__ int s_count[LMKAN_MAX_GRID * LMKAN_MAX_GRID];  // population, then scatter cursor
+    __shared__ int s_start[LMKAN_MAX_GRID * LMKAN_MAX_GRID];  // first stream position of the cell
     __shared__ int s_wave_total[kSortThreads / 64];
+    __shared__ int s_last_cell;
     const int k = blockIdx.x;
     const int cells = G * G, W = G + 1;
+    const int64_t S = stream_stride(B, G);
     const int32_t *node_k = rec_node + (int64_t)k * B;
     const float *u_k = rec_u + (int64_t)k * B;
     const float *v_k = rec_v + (int64_t)k * B;
+    int32_t *out_n = sorted_n + (int64_t)k * S;
+    f4v *out_w = sorted_w + (int64_t)k * S;
+    int32_t *out_cell = chunk_cell + (int64_t)k * (S / kChunk);
 
-    for (int c = threadIdx.x; c <= cells; c += blockDim.x) s_count[c] = 0;
+    for (int c = threadIdx.x; c < cells; c += blockDim.x) s_count[c] = 0;
+    if (threadIdx.x == 0) s_last_cell = 0;
     __syncthreads();
     for (int64_t n = threadIdx.x; n < B; n += blockDim.x) {
         const int node = node_k[n];
         atomicAdd(&s_count[(node / W) * G + node % W], 1);
     }
     __syncthreads();
-    // exclusive scan of s_count[0..cells) in chunks of blockDim.x; the result is the running
-    // cursor of the scatter below
+    // exclusive scan of the padded populations, in pieces of blockDim.x cells
     int carry = 0;
     for (int base = 0; base < cells; base += blockDim.x) {
         const int c = base + threadIdx.x;
-        const int v = c < cells ? s_count[c] : 0;
+        const int cnt = c < cells ? s_count[c] : 0;
+        const int v = (cnt + kChunk - 1) / kChunk * kChunk;
+        if (cnt > 0) atomicMax(&s_last_cell, c);
         int incl = v;
 #pragma unroll
         for (int d = 1; d < 64; d <<= 1) {
@@ -65,48 +89,75 @@ __global__ __launch_bounds__(kSortThreads) void sort_records_kernel(const int32_
         __syncthreads();
         int wave_off = 0;
         for (int w = 0; w < (int)(threadIdx.x >> 6); ++w) wave_off += s_wave_total[w];
-        int chunk_total = 0;
-        for (int w = 0; w < (int)(blockDim.x >> 6); ++w) chunk_total += s_wave_total[w];
-        const int excl = carry + wave_off + incl - v;
+        int piece_total = 0;
+        for (int w = 0; w < (int)(blockDim.x >> 6); ++w) piece_total += s_wave_total[w];
+        if (c < cells) s_start[c] = carry + wave_off + incl - v;
+        carry += piece_total;
         __syncthreads();
-        if (c < cells) s_count[c] = excl;
-        carry += chunk_total;
     }
+    const int total = carry;  // padded samples of all cells, a multiple of kChunk
+    // padding entries and the cell of every chunk
+    for (int c = threadIdx.x; c < cells; c += blockDim.x) {
+        const int cnt = s_count[c];
+        if (cnt == 0) continue;
+        const int first = s_start[c], padded = (cnt + kChunk - 1) / kChunk * kChunk;
+        const f4v zero = {0.f, 0.f, 0.f, 0.f};
+        for (int i = cnt; i < padded; ++i) {
+            out_n[first + i] = 0;
+            out_w[first + i] = zero;
+        }
+        const int code = ((c / G) << 8) | (c % G);
+        for (int q = first / kChunk; q < (first + padded) / kChunk; ++q) out_cell[q] = code;
+    }
+    // tail: whole dummy chunks that belong to the last non-empty cell
+    const int real_chunks = total / kChunk;
+    const int run_chunks = (real_chunks + kDepth - 1) / kDepth * kDepth;
+    const int tail_end = run_chunks + kDepth + 2;  // chunks the pipeline may touch
+    {
+        const int last = s_last_cell;
+        const int code = ((last / G) << 8) | (last % G);
+        const f4v zero = {0.f, 0.f, 0.f, 0.f};
+        for (int i = total + threadIdx.x; i < tail_end * kChunk; i += blockDim.x) {
+            out_n[i] = 0;
+            out_w[i] = zero;
+        }
+        for (int q = real_chunks + threadIdx.x; q < tail_end; q += blockDim.x) out_cell[q] = code;
+        if (threadIdx.x == 0) n_chunks[k] = run_chunks;
+    }
+    __syncthreads();
+    for (int c = threadIdx.x; c < cells; c += blockDim.x) s_count[c] = 0;
     __syncthreads();
     for (int64_t n = threadIdx.x; n < B; n += blockDim.x) {
         const int node = node_k[n];
         const float u = u_k[n], v = v_k[n];
-        const int i1 = node / W, i2 = node % W;
-        const int pos = atomicAdd(&s_count[i1 * G + i2], 1);
-        const int64_t o = (int64_t)k * B + pos;
+        const int c = (node / W) * G + node % W;
+        const int pos = s_start[c] + atomicAdd(&s_count[c], 1);
         const float a_lo = 1.0f - u, b_lo = 1.0f - v;
-        sorted_n[o] = (int32_t)n;
-        sorted_cell[o] = (i1 << 8) | i2;
+        out_n[pos] = (int32_t)n;
         f4v w;
         w.x = a_lo * b_lo;
         w.y = u * b_lo;
         w.z = a_lo * v;
         w.w = u * v;
-        sorted_w[o] = w;
+        out_w[pos] = w;
     }
 }
 
 struct CoefGradArgs {
     const int32_t *sorted_n;
-    const int32_t *sorted_cell;
     const f4v *sorted_w;
+    const int32_t *chunk_cell;
+    const int32_t *n_chunks;
     const float *gy;
     float *gP;
     CoefMap gmap;  // layout of Alg. 1
     int64_t B;
+    int64_t S;     // stream_stride
     int n_out;
     int K;
     int G;
     int accumulate;
 };
-
-constexpr int kChunk = 4;  // samples per pipeline stage
-constexpr int kDepth = 6;  // chunks of gy values in flight
 
 __global__ __launch_bounds__(64) void backward_coef_sorted_kernel(CoefGradArgs a)
 {
@@ -128,9 +179,10 @@ __global__ __launch_bounds__(64) void backward_coef_sorted_kernel(CoefGradArgs a
     // weights are the same for all 64 outputs, so they belong in SGPRs.
     typedef __attribute__((address_space(4))) const int32_t *ScalarIntPtr;
     typedef __attribute__((address_space(4))) const f4v *ScalarWPtr;
-    ScalarIntPtr sn = (ScalarIntPtr)(a.sorted_n + (int64_t)k * a.B);
-    ScalarIntPtr sc = (ScalarIntPtr)(a.sorted_cell + (int64_t)k * a.B);
-    ScalarWPtr sw = (ScalarWPtr)(a.sorted_w + (int64_t)k * a.B);
+    ScalarIntPtr sn = (ScalarIntPtr)(a.sorted_n + (int64_t)k * a.S);
+    ScalarWPtr sw = (ScalarWPtr)(a.sorted_w + (int64_t)k * a.S);
+    ScalarIntPtr cc = (ScalarIntPtr)(a.chunk_cell + (int64_t)k * (a.S / kChunk));
+    const int nch = ((ScalarIntPtr)a.n_chunks)[k];
     const float *gy_col = a.gy + (col_ok ? col : 0);
     float *out = a.gP + (int64_t)k * a.gmap.s_pair + col;
 
@@ -165,26 +217,13 @@ __global__ __launch_bounds__(64) void backward_coef_sorted_kernel(CoefGradArgs a
             }
         }
     };
-    auto consume = [&](int cell, f4v w, float g) {
-        if (cell != cur_cell) {
-            if (cur_cell >= 0) flush();
-            retire_rows(cell >> 8);
-            cur_cell = cell;
-        }
-        a00 = fmaf(w.x, g, a00);
-        a10 = fmaf(w.y, g, a10);
-        a01 = fmaf(w.z, g, a01);
-        a11 = fmaf(w.w, g, a11);
-    };
 
-    // Software pipeline over chunks of kChunk samples.  The address of a gy value depends on
-    // the sample index, so indices run kDepth+1 chunks ahead of the multiply-adds, the gy
-    // loads kDepth chunks ahead (a register ring), weights and cell ids one chunk ahead.
-    const int n_chunks = (int)(a.B / kChunk);
-    int done = 0;  // chunks consumed
-    if (n_chunks >= 2 * kDepth) {
+    // Software pipeline over the chunks.  The address of a gy value depends on the sample
+    // index, so indices run kDepth+1 chunks ahead of the multiply-adds, the gy loads kDepth
+    // chunks ahead (a register ring), weights and the chunk's cell one chunk ahead.
+    if (nch > 0) {
         float g[kDepth][kChunk];
-        int n_use[kChunk], cell_cur[kChunk];
+        int n_use[kChunk];
         f4v w_cur[kChunk];
 #pragma unroll
         for (int d = 0; d < kDepth; ++d) {
@@ -194,47 +233,43 @@ __global__ __launch_bounds__(64) void backward_coef_sorted_kernel(CoefGradArgs a
 #pragma unroll
         for (int u = 0; u < kChunk; ++u) {
             n_use[u] = sn[kDepth * kChunk + u];
-            cell_cur[u] = sc[u];
             w_cur[u] = sw[u];
         }
-        // chunks [0, limit) are consumed here; every load below stays inside [0, n_chunks)
-        const int limit = ((n_chunks - kDepth - 1) / kDepth) * kDepth;
-        for (int c = 0; c < limit; c += kDepth) {
+        int cell_cur = cc[0];
+        for (int c = 0; c < nch; c += kDepth) {
 #pragma unroll
             for (int p = 0; p < kDepth; ++p) {
-                const int j = c + p;  // chunk consumed in this step; j + kDepth + 1 < n_chunks
-                int n_load[kChunk], cell_nxt[kChunk];
+                const int j = c + p;
+                int n_load[kChunk];
                 f4v w_nxt[kChunk];
 #pragma unroll
                 for (int u = 0; u < kChunk; ++u) {
                     n_load[u] = sn[(j + kDepth + 1) * kChunk + u];
-                    cell_nxt[u] = sc[(j + 1) * kChunk + u];
                     w_nxt[u] = sw[(j + 1) * kChunk + u];
                 }
+                const int cell_nxt = cc[j + 1];
+                if (cell_cur != cur_cell) {
+                    if (cur_cell >= 0) flush();
+                    retire_rows(cell_cur >> 8);
+                    cur_cell = cell_cur;
+                }
 #pragma unroll
-                for (int u = 0; u < kChunk; ++u) consume(cell_cur[u], w_cur[u], g[p][u]);
+                for (int u = 0; u < kChunk; ++u) {
+                    a00 = fmaf(w_cur[u].x, g[p][u], a00);
+                    a10 = fmaf(w_cur[u].y, g[p][u], a10);
+                    a01 = fmaf(w_cur[u].z, g[p][u], a01);
+                    a11 = fmaf(w_cur[u].w, g[p][u], a11);
+                }
 #pragma unroll
                 for (int u = 0; u < kChunk; ++u) {
                     g[p][u] = gy_col[(int64_t)n_use[u] * a.n_out];  // chunk j + kDepth
                     n_use[u] = n_load[u];
-                    cell_cur[u] = cell_nxt[u];
                     w_cur[u] = w_nxt[u];
                 }
+                cell_cur = cell_nxt;
             }
         }
-        // drain: the ring holds chunks limit .. limit + kDepth - 1, w_cur / cell_cur chunk `limit`
-#pragma unroll
-        for (int p = 0; p < kDepth; ++p) {
-#pragma unroll
-            for (int u = 0; u < kChunk; ++u) {
-                const int pos = (limit + p) * kChunk + u;
-                consume(p == 0 ? cell_cur[u] : sc[pos], p == 0 ? w_cur[u] : sw[pos], g[p][u]);
-            }
-        }
-        done = limit + kDepth;
     }
-    for (int64_t pos = (int64_t)done * kChunk; pos < a.B; ++pos)
-        consume(sc[pos], sw[pos], gy_col[(int64_t)sn[pos] * a.n_out]);
     if (cur_cell >= 0) flush();
     retire_rows(W);
 }
@@ -243,32 +278,38 @@ __global__ __launch_bounds__(64) void backward_coef_sorted_kernel(CoefGradArgs a
 
 size_t sorted_records_bytes(const LayerShape &s)
 {
-    const size_t bytes = (size_t)s.pairs() * (size_t)s.batch * (2 * sizeof(int32_t) + sizeof(f4v));
-    return (bytes + 255) & ~(size_t)255;
+    const size_t S = (size_t)stream_stride(s.batch, s.G);
+    const size_t per_pair = S * (sizeof(f4v) + sizeof(int32_t)) + (S / kChunk) * sizeof(int32_t) + sizeof(int32_t);
+    return ((size_t)s.pairs() * per_pair + 255) & ~(size_t)255;
 }
 
 void launch_backward_coef_sorted(const LayerShape &s, const void *records, void *sorted, const float *gy,
                                  float *gcoef, bool accumulate, hipStream_t stream)
 {
     const size_t n = (size_t)s.pairs() * (size_t)s.batch;
+    const size_t S = (size_t)stream_stride(s.batch, s.G);
+    const size_t K = (size_t)s.pairs();
     const int32_t *rec_node = static_cast<const int32_t *>(records);
     const float *rec_u = reinterpret_cast<const float *>(rec_node + n);
     const float *rec_v = rec_u + n;
-    f4v *sorted_w = static_cast<f4v *>(sorted);  // 16-byte items first, then the 8-byte ones
-    int32_t *sorted_n = reinterpret_cast<int32_t *>(sorted_w + n);
-    int32_t *sorted_cell = sorted_n + n;
-    sort_records_kernel<<<s.pairs(), kSortThreads, 0, stream>>>(rec_node, rec_u, rec_v, sorted_n, sorted_cell,
-                                                               sorted_w, s.batch, s.G);
+    f4v *sorted_w = static_cast<f4v *>(sorted);  // 16-byte items first, then the 4-byte ones
+    int32_t *sorted_n = reinterpret_cast<int32_t *>(sorted_w + K * S);
+    int32_t *chunk_cell = sorted_n + K * S;
+    int32_t *n_chunks = chunk_cell + K * (S / kChunk);
+    sort_records_kernel<<<s.pairs(), kSortThreads, 0, stream>>>(rec_node, rec_u, rec_v, sorted_n, sorted_w,
+                                                               chunk_cell, n_chunks, s.batch, s.G);
     CoefGradArgs a;
     a.sorted_n = sorted_n;
-    a.sorted_cell = sorted_cell;
     a.sorted_w = sorted_w;
+    a.chunk_cell = chunk_cell;
+    a.n_chunks = n_chunks;
     a.gy = gy;
     a.gP = gcoef;
     LayerShape g = s;
     g.layout = LMKAN_LAYOUT_PAPER;
     a.gmap = coef_map(g);
     a.B = s.batch;
+    a.S = (int64_t)S;
     a.n_out = s.n_out;
     a.K = s.pairs();
     a.G = s.G;
