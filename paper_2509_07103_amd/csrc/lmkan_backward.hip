@@ -33,7 +33,7 @@ constexpr int kDepth = 6;  // chunks of gy values in flight
 __host__ __device__ inline int64_t stream_stride(int64_t B, int G)
 {
     const int64_t body = (B + (int64_t)(kChunk - 1) * G * G + kChunk - 1) / kChunk * kChunk;
-    return body + (int64_t)kChunk * (2 * kDepth + 2);
+    return body + (int64_t)kChunk * (3 * kDepth + 2);
 }
 
 // records_in: [3][K][B] (node, u, v) from the preamble pass.  Per pair k, with S = stream_stride:
@@ -112,7 +112,7 @@ __global__ __launch_bounds__(kSortThreads) void sort_records_kernel(const int32_
     // tail: whole dummy chunks that belong to the last non-empty cell
     const int real_chunks = total / kChunk;
     const int run_chunks = (real_chunks + kDepth - 1) / kDepth * kDepth;
-    const int tail_end = run_chunks + kDepth + 2;  // chunks the pipeline may touch
+    const int tail_end = run_chunks + 2 * kDepth + 2;  // chunks the pipelines may touch
     {
         const int last = s_last_cell;
         const int code = ((last / G) << 8) | (last % G);
@@ -274,6 +274,127 @@ __global__ __launch_bounds__(64) void backward_coef_sorted_kernel(CoefGradArgs a
     retire_rows(W);
 }
 
+// Wide variant (n_out a multiple of 4, 16-byte aligned gy and gP): the wave works on the four
+// samples of a chunk at once, one per 16-lane group, and a lane covers four adjacent outputs,
+// so gy is read with 16-byte loads (the texture path moves 256-byte row pieces four times
+// faster that way than as single dwords).  Weights and sample indices are per group and
+// therefore come from vector loads.  When a cell ends, the four groups' partial sums are
+// combined across the wave and group 0 adds them into the LDS window.
+constexpr int kWideDepth = kDepth;  // chunks of gy values and weights in flight; indices run twice as far ahead
+
+__global__ __launch_bounds__(64) void backward_coef_wide_kernel(CoefGradArgs a)
+{
+    extern __shared__ __align__(16) float win[];  // [2][G+1][64]
+    const int lane = threadIdx.x;
+    const int g = lane >> 4, l16 = lane & 15;
+    const int G = a.G, W = G + 1;
+
+    int id = blockIdx.x;
+    const int total = gridDim.x;
+    if ((total & 7) == 0) id = (id & 7) * (total >> 3) + (id >> 3);
+    const int jt = id / a.K;
+    const int k = id % a.K;
+
+    const int col = jt * kTile + l16 * 4;
+    const bool col_ok = col < a.n_out;
+    typedef __attribute__((address_space(4))) const int32_t *ScalarIntPtr;
+    const int32_t *sn = a.sorted_n + (int64_t)k * a.S + g;  // this group's sample of each chunk
+    const f4v *sw = a.sorted_w + (int64_t)k * a.S + g;
+    ScalarIntPtr cc = (ScalarIntPtr)(a.chunk_cell + (int64_t)k * (a.S / kChunk));
+    const int nch = ((ScalarIntPtr)a.n_chunks)[k];
+    const float *gy_col = a.gy + (col_ok ? col : 0);
+    float *out = a.gP + (int64_t)k * a.gmap.s_pair + col;
+
+    for (int i = lane; i < 2 * W * kTile; i += 64) win[i] = 0.0f;
+
+    f4v acc00 = {0.f, 0.f, 0.f, 0.f}, acc10 = acc00, acc01 = acc00, acc11 = acc00;
+    int cur_cell = -1;
+    int rows_done = 0;
+
+    auto wave_sum = [&](f4v v) {
+        f4v r;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            float t = v[i];
+            t += __shfl_xor(t, 16, 64);
+            t += __shfl_xor(t, 32, 64);
+            r[i] = t;
+        }
+        return r;
+    };
+    auto flush = [&]() {
+        const int i1 = cur_cell >> 8, i2 = cur_cell & 255;
+        const f4v s00 = wave_sum(acc00), s10 = wave_sum(acc10), s01 = wave_sum(acc01), s11 = wave_sum(acc11);
+        if (g == 0) {
+            f4v *cur = reinterpret_cast<f4v *>(win + (i1 & 1) * W * kTile + i2 * kTile) + l16;
+            f4v *nxt = reinterpret_cast<f4v *>(win + ((i1 + 1) & 1) * W * kTile + i2 * kTile) + l16;
+            cur[0] += s00;
+            cur[kTile / 4] += s01;
+            nxt[0] += s10;
+            nxt[kTile / 4] += s11;
+        }
+        acc00 = acc10 = acc01 = acc11 = f4v{0.f, 0.f, 0.f, 0.f};
+    };
+    // four table rows entries per store instruction: group g takes b = 4 i + g
+    auto retire_rows = [&](int upto) {
+        for (; rows_done < upto; ++rows_done) {
+            f4v *row = reinterpret_cast<f4v *>(win + (rows_done & 1) * W * kTile) + l16;
+            for (int b = g; b < W; b += 4) {
+                if (col_ok) {
+                    f4v *dst = reinterpret_cast<f4v *>(out + (int64_t)(rows_done * W + b) * a.gmap.s_node);
+                    const f4v v = row[b * (kTile / 4)];
+                    *dst = a.accumulate ? *dst + v : v;
+                }
+                row[b * (kTile / 4)] = f4v{0.f, 0.f, 0.f, 0.f};
+            }
+        }
+    };
+
+    if (nch > 0) {
+        // three-stage pipeline, all through in-order vector loads: at step j the sample index of
+        // chunk j + 2 depth is requested, the index of chunk j + depth (requested depth steps ago)
+        // addresses the gy and weight loads of that chunk, and chunk j is consumed
+        f4v gq[kWideDepth], wq[kWideDepth];
+        int nq[kWideDepth];
+#pragma unroll
+        for (int d = 0; d < kWideDepth; ++d) {
+            gq[d] = *reinterpret_cast<const f4v *>(gy_col + (int64_t)sn[d * kChunk] * a.n_out);
+            wq[d] = sw[d * kChunk];
+            nq[d] = sn[(kWideDepth + d) * kChunk];
+        }
+        // cells of a whole group of chunks are fetched one group ahead (scalar loads return out
+        // of order, so every use waits for all of them: keep them few and early)
+        int cells_now[kWideDepth], cells_nxt[kWideDepth];
+#pragma unroll
+        for (int p = 0; p < kWideDepth; ++p) cells_now[p] = cc[p];
+        for (int c = 0; c < nch; c += kWideDepth) {
+#pragma unroll
+            for (int p = 0; p < kWideDepth; ++p) cells_nxt[p] = cc[c + kWideDepth + p];
+#pragma unroll
+            for (int p = 0; p < kWideDepth; ++p) {
+                const int j = c + p;
+                const int cell_cur = cells_now[p];
+                if (cell_cur != cur_cell) {
+                    if (cur_cell >= 0) flush();
+                    retire_rows(cell_cur >> 8);
+                    cur_cell = cell_cur;
+                }
+                acc00 += wq[p].x * gq[p];
+                acc10 += wq[p].y * gq[p];
+                acc01 += wq[p].z * gq[p];
+                acc11 += wq[p].w * gq[p];
+                gq[p] = *reinterpret_cast<const f4v *>(gy_col + (int64_t)nq[p] * a.n_out);
+                wq[p] = sw[(j + kWideDepth) * kChunk];
+                nq[p] = sn[(j + 2 * kWideDepth) * kChunk];
+            }
+#pragma unroll
+            for (int p = 0; p < kWideDepth; ++p) cells_now[p] = cells_nxt[p];
+        }
+    }
+    if (cur_cell >= 0) flush();
+    retire_rows(W);
+}
+
 }  // namespace
 
 size_t sorted_records_bytes(const LayerShape &s)
@@ -315,7 +436,12 @@ void launch_backward_coef_sorted(const LayerShape &s, const void *records, void 
     a.G = s.G;
     a.accumulate = accumulate ? 1 : 0;
     const unsigned lds = (unsigned)(2 * (s.G + 1) * kTile * sizeof(float));
-    backward_coef_sorted_kernel<<<s.pairs() * s.out_tiles(), 64, lds, stream>>>(a);
+    const bool wide = s.n_out % 4 == 0 &&
+                      ((reinterpret_cast<uintptr_t>(gy) | reinterpret_cast<uintptr_t>(gcoef)) & 15) == 0;
+    if (wide)
+        backward_coef_wide_kernel<<<s.pairs() * s.out_tiles(), 64, lds, stream>>>(a);
+    else
+        backward_coef_sorted_kernel<<<s.pairs() * s.out_tiles(), 64, lds, stream>>>(a);
 }
 
 }  // namespace lmkan

@@ -5,6 +5,8 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include <utility>
+
 #include "lmkan.h"
 
 namespace lmkan {
@@ -83,5 +85,30 @@ struct bf16_t {
     uint16_t bits;
 };
 __device__ __forceinline__ float widen(bf16_t v) { return __uint_as_float((uint32_t)v.bits << 16); }
+
+// ---------------------------------------------------------------------------
+// DPP helpers.  row_newbcast:S makes every lane of a 16-lane row read lane S of
+// that row.
+// ---------------------------------------------------------------------------
+template <int S>
+__device__ __forceinline__ int row_bcast(int v)
+{
+    return __builtin_amdgcn_update_dpp(0, v, 0x150 + S, 0xf, 0xf, false);
+}
+
+// acc += (w of lane S of this row) * c
+template <int S>
+__device__ __forceinline__ void fmac_row_bcast(float &acc, float w, float c)
+{
+    asm("v_fmac_f32_dpp %0, %1, %2 row_newbcast:%3 row_mask:0xf bank_mask:0xf"
+        : "+v"(acc)
+        : "v"(w), "v"(c), "n"(S));
+}
+
+template <int... Ts, class F>
+__device__ __forceinline__ void static_for(std::integer_sequence<int, Ts...>, F &&f)
+{
+    (f(std::integral_constant<int, Ts>{}), ...);
+}
 
 }  // namespace lmkan
