@@ -201,16 +201,21 @@ lmkan_status lmkan_backward(const lmkan_desc *desc, int64_t batch, const float *
         (coef_dev && !aligned(coef_dev, dtype_size(desc->coef_dtype))))
         return LMKAN_ERR_ALIGN;
     const bool gx_slab = grad_x_dev && slab_backward_input_applicable(s, coef_dev, grad_y_dev, grad_x_dev);
-    const size_t need = (grad_coef_dev || gx_slab) ? lmkan_workspace_bytes(desc, batch, 1) : 0;
+    const bool gp_sorted = grad_coef_dev && coef_sorted_applicable(s, grad_y_dev, grad_coef_dev);
+    const size_t need = (gp_sorted || gx_slab) ? lmkan_workspace_bytes(desc, batch, 1) : 0;
     if (need > 0 && (!workspace_dev || workspace_bytes < need)) return LMKAN_ERR_WORKSPACE;
     if (need > 0 && !aligned(workspace_dev, 256)) return LMKAN_ERR_ALIGN;
     GridTab tab;
     build_grid(desc->grid, &tab);
     char *ws = static_cast<char *>(workspace_dev);
-    if (grad_coef_dev || gx_slab) launch_preamble_records(s, tab, x_dev, ws, hs);
-    if (grad_coef_dev) {
+    if (gp_sorted || gx_slab) launch_preamble_records(s, tab, x_dev, ws, hs);
+    if (gp_sorted) {
         launch_backward_coef_sorted(s, ws, ws + align256(records_bytes(s)), grad_y_dev, grad_coef_dev,
                                     !overwrite, hs);
+    } else if (grad_coef_dev) {
+        // odd output counts or unaligned buffers: atomics on a gradient that starts at zero
+        if (overwrite) launch_fill_zero(grad_coef_dev, (size_t)s.nodes() * s.pairs() * s.n_out, hs);
+        launch_backward_generic(s, tab, x_dev, coef_dev, grad_y_dev, nullptr, grad_coef_dev, hs);
     }
     if (gx_slab)
         launch_backward_input_slab(s, tab, coef_dev, grad_y_dev, grad_x_dev, ws,

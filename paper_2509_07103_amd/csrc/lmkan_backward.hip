@@ -5,14 +5,17 @@
 //
 // Pass 1 (sort_records_kernel): for every pair k the samples are grouped by cell with a
 // counting sort, each cell padded to whole chunks of four samples, and the four B-spline
-// products are stored next to the sample index.
-// Pass 2 (backward_coef_sorted_kernel): one wave owns (pair k, 64 outputs) and walks the
-// sorted samples, cell after cell.  Inside a cell the four corner sums live in registers (lanes = outputs,
-// weights are wave-uniform scalars), so a value of gy feeds four multiply-adds.  Finished
-// cells are added into a two-row window of the table kept in LDS (each lane only ever
-// touches its own column, so no synchronisation is needed); a table row is written to
-// global memory exactly once, when the walk has passed it.  Rows no sample touches are
-// written as exact zeros, so no separate zero fill is needed.
+// products are stored together with the sample index as one five-word record.
+// Pass 2 (backward_coef_stream_kernel): one wave owns (pair k, 64 outputs) and walks the
+// sorted chunks, cell after cell.  The four samples of a chunk go to the four 16-lane
+// groups of the wave and a lane covers four adjacent outputs, so gy is read with 16-byte
+// loads.  A group's record sits in lanes of that group and reaches the multiply-adds as a
+// DPP row broadcast, so the only vector loads are one record word per three chunks and
+// the gy values themselves.  Inside a cell the 16 partial sums (4 corners x 4 outputs) live
+// in registers.  When the cell ends they are combined across the groups and added into a
+// two-row window of the table kept in LDS; a table row is written to global memory exactly
+// once, when the walk has passed it.  Rows no sample touches are written as exact zeros, so
+// no separate zero fill is needed.
 #include "lmkan_kernels.h"
 
 namespace lmkan {
@@ -23,29 +26,37 @@ constexpr int kTile = LMKAN_PACK_TILE;
 constexpr int kSortThreads = 1024;
 
 typedef float f4v __attribute__((ext_vector_type(4)));
+typedef unsigned u2v __attribute__((ext_vector_type(2)));
 
-constexpr int kChunk = 4;  // samples per chunk; a chunk never straddles two cells
-constexpr int kDepth = 6;  // chunks of gy values in flight
+constexpr int kChunk = 4;        // samples per chunk; a chunk never straddles two cells
+constexpr int kRecord = 5;       // words per sorted sample: w00, w10, w01, w11, sample index
+constexpr int kDepth = 6;        // chunks of gy values in flight
+constexpr int kPerLoad = 3;      // chunks whose records one load instruction brings in
+constexpr int kRecRegs = 6;      // record registers in the ring
+constexpr int kUnroll = kPerLoad * kRecRegs;  // chunks per trip of the main loop
+static_assert(kUnroll % kDepth == 0, "the gy ring must divide the unrolled trip");
+static_assert(kPerLoad * kRecord <= 16, "the records of one load must fit a 16-lane group");
 
-// Samples per pair in the sorted stream: every non-empty cell is padded to whole chunks with
-// zero-weight entries, and the end is padded so that the pipeline below can run (and
-// prefetch) over whole groups of kDepth chunks without bounds checks.
+// Samples per pair in the sorted stream: every non-empty cell is padded to whole chunks, and
+// the end is padded so that the pipeline below can run (and prefetch) over whole trips of
+// kUnroll chunks without bounds checks.
 __host__ __device__ inline int64_t stream_stride(int64_t B, int G)
 {
     const int64_t body = (B + (int64_t)(kChunk - 1) * G * G + kChunk - 1) / kChunk * kChunk;
-    return body + (int64_t)kChunk * (3 * kDepth + 2);
+    return body + (int64_t)kChunk * (3 * kUnroll);
 }
 
 // records_in: [3][K][B] (node, u, v) from the preamble pass.  Per pair k, with S = stream_stride:
-//   sorted_n [K][S]      sample index (0 in padding entries)
-//   sorted_w [K][S]      the four products (w00, w10, w01, w11), zero in padding entries
+//   sorted [K][S][5]     the four products (w00, w10, w01, w11) and the sample index (as bits).
+//                        Padding entries have zero products and repeat the index of a sample
+//                        of the same cell, so that what they multiply is a value the cell
+//                        sees anyway.
 //   chunk_cell [K][S/4]  i1 << 8 | i2 of the cell each chunk belongs to, non-decreasing
-//   n_chunks [K]         chunks to process, a multiple of kDepth
+//   n_chunks [K]         chunks to process, a multiple of kUnroll
 __global__ __launch_bounds__(kSortThreads) void sort_records_kernel(const int32_t *__restrict__ rec_node,
                                                                    const float *__restrict__ rec_u,
                                                                    const float *__restrict__ rec_v,
-                                                                   int32_t *__restrict__ sorted_n,
-                                                                   f4v *__restrict__ sorted_w,
+                                                                   float *__restrict__ sorted,
                                                                    int32_t *__restrict__ chunk_cell,
                                                                    int32_t *__restrict__ n_chunks, int64_t B,
                                                                    int G)
@@ -60,9 +71,17 @@ __global__ __launch_bounds__(kSortThreads) void sort_records_kernel(const int32_
     const int32_t *node_k = rec_node + (int64_t)k * B;
     const float *u_k = rec_u + (int64_t)k * B;
     const float *v_k = rec_v + (int64_t)k * B;
-    int32_t *out_n = sorted_n + (int64_t)k * S;
-    f4v *out_w = sorted_w + (int64_t)k * S;
+    float *out = sorted + (int64_t)k * S * kRecord;
     int32_t *out_cell = chunk_cell + (int64_t)k * (S / kChunk);
+
+    auto put = [&](int64_t pos, float w00, float w10, float w01, float w11, int32_t n) {
+        float *r = out + pos * kRecord;
+        r[0] = w00;
+        r[1] = w10;
+        r[2] = w01;
+        r[3] = w11;
+        r[4] = __int_as_float(n);
+    };
 
     for (int c = threadIdx.x; c < cells; c += blockDim.x) s_count[c] = 0;
     if (threadIdx.x == 0) s_last_cell = 0;
@@ -96,35 +115,25 @@ __global__ __launch_bounds__(kSortThreads) void sort_records_kernel(const int32_
         __syncthreads();
     }
     const int total = carry;  // padded samples of all cells, a multiple of kChunk
-    // padding entries and the cell of every chunk
+    // the cell of every chunk
     for (int c = threadIdx.x; c < cells; c += blockDim.x) {
         const int cnt = s_count[c];
         if (cnt == 0) continue;
         const int first = s_start[c], padded = (cnt + kChunk - 1) / kChunk * kChunk;
-        const f4v zero = {0.f, 0.f, 0.f, 0.f};
-        for (int i = cnt; i < padded; ++i) {
-            out_n[first + i] = 0;
-            out_w[first + i] = zero;
-        }
         const int code = ((c / G) << 8) | (c % G);
         for (int q = first / kChunk; q < (first + padded) / kChunk; ++q) out_cell[q] = code;
     }
-    // tail: whole dummy chunks that belong to the last non-empty cell
     const int real_chunks = total / kChunk;
-    const int run_chunks = (real_chunks + kDepth - 1) / kDepth * kDepth;
-    const int tail_end = run_chunks + 2 * kDepth + 2;  // chunks the pipelines may touch
+    const int run_chunks = (real_chunks + kUnroll - 1) / kUnroll * kUnroll;
+    const int tail_end = run_chunks + 2 * kUnroll;  // chunks the pipelines may touch
     {
         const int last = s_last_cell;
         const int code = ((last / G) << 8) | (last % G);
-        const f4v zero = {0.f, 0.f, 0.f, 0.f};
-        for (int i = total + threadIdx.x; i < tail_end * kChunk; i += blockDim.x) {
-            out_n[i] = 0;
-            out_w[i] = zero;
-        }
         for (int q = real_chunks + threadIdx.x; q < tail_end; q += blockDim.x) out_cell[q] = code;
         if (threadIdx.x == 0) n_chunks[k] = run_chunks;
     }
     __syncthreads();
+    // scatter; s_count becomes the cursor and ends equal to the population again
     for (int c = threadIdx.x; c < cells; c += blockDim.x) s_count[c] = 0;
     __syncthreads();
     for (int64_t n = threadIdx.x; n < B; n += blockDim.x) {
@@ -133,19 +142,26 @@ __global__ __launch_bounds__(kSortThreads) void sort_records_kernel(const int32_
         const int c = (node / W) * G + node % W;
         const int pos = s_start[c] + atomicAdd(&s_count[c], 1);
         const float a_lo = 1.0f - u, b_lo = 1.0f - v;
-        out_n[pos] = (int32_t)n;
-        f4v w;
-        w.x = a_lo * b_lo;
-        w.y = u * b_lo;
-        w.z = a_lo * v;
-        w.w = u * v;
-        out_w[pos] = w;
+        put(pos, a_lo * b_lo, u * b_lo, a_lo * v, u * v, (int32_t)n);
+    }
+    __syncthreads();  // also makes the scattered records visible to the whole block
+    // padding entries: zero products, the index of the cell's first sample
+    for (int c = threadIdx.x; c < cells; c += blockDim.x) {
+        const int cnt = s_count[c];
+        if (cnt == 0) continue;
+        const int first = s_start[c], padded = (cnt + kChunk - 1) / kChunk * kChunk;
+        const int32_t n0 = __float_as_int(out[(int64_t)first * kRecord + 4]);
+        for (int i = cnt; i < padded; ++i) put(first + i, 0.f, 0.f, 0.f, 0.f, n0);
+    }
+    // tail: whole dummy chunks that belong to the last non-empty cell
+    {
+        const int32_t n0 = __float_as_int(out[(int64_t)s_start[s_last_cell] * kRecord + 4]);
+        for (int i = total + threadIdx.x; i < tail_end * kChunk; i += blockDim.x) put(i, 0.f, 0.f, 0.f, 0.f, n0);
     }
 }
 
 struct CoefGradArgs {
-    const int32_t *sorted_n;
-    const f4v *sorted_w;
+    const float *sorted;
     const int32_t *chunk_cell;
     const int32_t *n_chunks;
     const float *gy;
@@ -159,10 +175,64 @@ struct CoefGradArgs {
     int accumulate;
 };
 
-__global__ __launch_bounds__(64) void backward_coef_sorted_kernel(CoefGradArgs a)
+// acc[4 q + i] += (product q of this group's sample) * gy[i].  The record of chunk SUB of a
+// load sits in lanes 5 SUB .. 5 SUB + 4 of the group.
+template <int SUB>
+__device__ __forceinline__ void chunk_fma(float (&acc)[16], float rec, const f4v &g)
 {
-    extern __shared__ float win[];  // [2][G+1][64]: table rows r and r+1 of this wave's columns
+    static_for(std::make_integer_sequence<int, 4>{}, [&](auto qc) {
+        constexpr int q = decltype(qc)::value;
+        fmac_row_bcast<kRecord * SUB + q>(acc[4 * q + 0], rec, g.x);
+        fmac_row_bcast<kRecord * SUB + q>(acc[4 * q + 1], rec, g.y);
+        fmac_row_bcast<kRecord * SUB + q>(acc[4 * q + 2], rec, g.z);
+        fmac_row_bcast<kRecord * SUB + q>(acc[4 * q + 3], rec, g.w);
+    });
+}
+
+// The four groups' partial sums of 16 accumulators -> f[i] of group r = total of corner r,
+// output i.  Two rounds of "swap halves of two registers, add": the first pairs corner q
+// with corner q + 2 across the 32-lane halves, the second pairs the results across odd and
+// even 16-lane rows.
+__device__ __forceinline__ void combine_groups(const float (&acc)[16], float (&f)[4])
+{
+#if defined(LMKAN_COMBINE_BPERMUTE)
+    const int g = (threadIdx.x >> 4) & 3;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        float keep = 0.f;
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            float t = acc[4 * q + i];
+            t += __shfl_xor(t, 16, 64);
+            t += __shfl_xor(t, 32, 64);
+            keep = (g == q) ? t : keep;
+        }
+        f[i] = keep;
+    }
+#else
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        float z[2];
+#pragma unroll
+        for (int q = 0; q < 2; ++q) {
+            // upper half of acc[q] <-> lower half of acc[q + 2]
+            const u2v s = __builtin_amdgcn_permlane32_swap(__float_as_uint(acc[4 * q + i]),
+                                                           __float_as_uint(acc[4 * (q + 2) + i]), false, false);
+            z[q] = __uint_as_float(s.x) + __uint_as_float(s.y);  // rows 0,1: corner q; rows 2,3: corner q + 2
+        }
+        // odd rows of z[0] <-> even rows of z[1]
+        const u2v s = __builtin_amdgcn_permlane16_swap(__float_as_uint(z[0]), __float_as_uint(z[1]), false, false);
+        f[i] = __uint_as_float(s.x) + __uint_as_float(s.y);
+    }
+#endif
+}
+
+template <bool kOffset32>
+__global__ __launch_bounds__(64) void backward_coef_stream_kernel(CoefGradArgs a)
+{
+    extern __shared__ __align__(16) float win[];  // [2][G+1][64]: table rows r and r+1 of this wave's columns
     const int lane = threadIdx.x;
+    const int g = lane >> 4, l16 = lane & 15;
     const int G = a.G, W = G + 1;
 
     // Waves that run together on one XCD (ids congruent mod 8) take the same output tile, so
@@ -173,169 +243,61 @@ __global__ __launch_bounds__(64) void backward_coef_sorted_kernel(CoefGradArgs a
     const int jt = id / a.K;
     const int k = id % a.K;
 
-    const int col = jt * kTile + lane;
-    const bool col_ok = col < a.n_out;
-    // The sorted records are read through the scalar unit: positions are wave-uniform and the
-    // weights are the same for all 64 outputs, so they belong in SGPRs.
-    typedef __attribute__((address_space(4))) const int32_t *ScalarIntPtr;
-    typedef __attribute__((address_space(4))) const f4v *ScalarWPtr;
-    ScalarIntPtr sn = (ScalarIntPtr)(a.sorted_n + (int64_t)k * a.S);
-    ScalarWPtr sw = (ScalarWPtr)(a.sorted_w + (int64_t)k * a.S);
-    ScalarIntPtr cc = (ScalarIntPtr)(a.chunk_cell + (int64_t)k * (a.S / kChunk));
-    const int nch = ((ScalarIntPtr)a.n_chunks)[k];
-    const float *gy_col = a.gy + (col_ok ? col : 0);
-    float *out = a.gP + (int64_t)k * a.gmap.s_pair + col;
-
-    for (int i = 0; i < 2 * W; ++i) win[i * kTile + lane] = 0.0f;
-
-    float a00 = 0.f, a10 = 0.f, a01 = 0.f, a11 = 0.f;
-    int cur_cell = -1;    // (i1 << 8 | i2) of the cell the accumulators belong to
-    int rows_done = 0;    // table rows [0, rows_done) have been written out
-
-    // add the accumulators of the finished cell into the two-row window
-    auto flush = [&]() {
-        const int i1 = cur_cell >> 8, i2 = cur_cell & 255;
-        float *cur = win + (i1 & 1) * W * kTile + i2 * kTile + lane;
-        float *nxt = win + ((i1 + 1) & 1) * W * kTile + i2 * kTile + lane;
-        cur[0] += a00;
-        cur[kTile] += a01;
-        nxt[0] += a10;
-        nxt[kTile] += a11;
-        a00 = a10 = a01 = a11 = 0.f;
-    };
-    // table rows below `upto` can receive nothing more: write them and recycle their buffers
-    auto retire_rows = [&](int upto) {
-        for (; rows_done < upto; ++rows_done) {
-            float *row = win + (rows_done & 1) * W * kTile + lane;
-            for (int b = 0; b < W; ++b) {
-                if (col_ok) {
-                    float *dst = out + (int64_t)(rows_done * W + b) * a.gmap.s_node;
-                    const float v = row[b * kTile];
-                    *dst = a.accumulate ? *dst + v : v;
-                }
-                row[b * kTile] = 0.0f;
-            }
-        }
-    };
-
-    // Software pipeline over the chunks.  The address of a gy value depends on the sample
-    // index, so indices run kDepth+1 chunks ahead of the multiply-adds, the gy loads kDepth
-    // chunks ahead (a register ring), weights and the chunk's cell one chunk ahead.
-    if (nch > 0) {
-        float g[kDepth][kChunk];
-        int n_use[kChunk];
-        f4v w_cur[kChunk];
-#pragma unroll
-        for (int d = 0; d < kDepth; ++d) {
-#pragma unroll
-            for (int u = 0; u < kChunk; ++u) g[d][u] = gy_col[(int64_t)sn[d * kChunk + u] * a.n_out];
-        }
-#pragma unroll
-        for (int u = 0; u < kChunk; ++u) {
-            n_use[u] = sn[kDepth * kChunk + u];
-            w_cur[u] = sw[u];
-        }
-        int cell_cur = cc[0];
-        for (int c = 0; c < nch; c += kDepth) {
-#pragma unroll
-            for (int p = 0; p < kDepth; ++p) {
-                const int j = c + p;
-                int n_load[kChunk];
-                f4v w_nxt[kChunk];
-#pragma unroll
-                for (int u = 0; u < kChunk; ++u) {
-                    n_load[u] = sn[(j + kDepth + 1) * kChunk + u];
-                    w_nxt[u] = sw[(j + 1) * kChunk + u];
-                }
-                const int cell_nxt = cc[j + 1];
-                if (cell_cur != cur_cell) {
-                    if (cur_cell >= 0) flush();
-                    retire_rows(cell_cur >> 8);
-                    cur_cell = cell_cur;
-                }
-#pragma unroll
-                for (int u = 0; u < kChunk; ++u) {
-                    a00 = fmaf(w_cur[u].x, g[p][u], a00);
-                    a10 = fmaf(w_cur[u].y, g[p][u], a10);
-                    a01 = fmaf(w_cur[u].z, g[p][u], a01);
-                    a11 = fmaf(w_cur[u].w, g[p][u], a11);
-                }
-#pragma unroll
-                for (int u = 0; u < kChunk; ++u) {
-                    g[p][u] = gy_col[(int64_t)n_use[u] * a.n_out];  // chunk j + kDepth
-                    n_use[u] = n_load[u];
-                    w_cur[u] = w_nxt[u];
-                }
-                cell_cur = cell_nxt;
-            }
-        }
-    }
-    if (cur_cell >= 0) flush();
-    retire_rows(W);
-}
-
-// Wide variant (n_out a multiple of 4, 16-byte aligned gy and gP): the wave works on the four
-// samples of a chunk at once, one per 16-lane group, and a lane covers four adjacent outputs,
-// so gy is read with 16-byte loads (the texture path moves 256-byte row pieces four times
-// faster that way than as single dwords).  Weights and sample indices are per group and
-// therefore come from vector loads.  When a cell ends, the four groups' partial sums are
-// combined across the wave and group 0 adds them into the LDS window.
-constexpr int kWideDepth = kDepth;  // chunks of gy values and weights in flight; indices run twice as far ahead
-
-__global__ __launch_bounds__(64) void backward_coef_wide_kernel(CoefGradArgs a)
-{
-    extern __shared__ __align__(16) float win[];  // [2][G+1][64]
-    const int lane = threadIdx.x;
-    const int g = lane >> 4, l16 = lane & 15;
-    const int G = a.G, W = G + 1;
-
-    int id = blockIdx.x;
-    const int total = gridDim.x;
-    if ((total & 7) == 0) id = (id & 7) * (total >> 3) + (id >> 3);
-    const int jt = id / a.K;
-    const int k = id % a.K;
-
     const int col = jt * kTile + l16 * 4;
     const bool col_ok = col < a.n_out;
     typedef __attribute__((address_space(4))) const int32_t *ScalarIntPtr;
-    const int32_t *sn = a.sorted_n + (int64_t)k * a.S + g;  // this group's sample of each chunk
-    const f4v *sw = a.sorted_w + (int64_t)k * a.S + g;
     ScalarIntPtr cc = (ScalarIntPtr)(a.chunk_cell + (int64_t)k * (a.S / kChunk));
     const int nch = ((ScalarIntPtr)a.n_chunks)[k];
-    const float *gy_col = a.gy + (col_ok ? col : 0);
     float *out = a.gP + (int64_t)k * a.gmap.s_pair + col;
+
+    // record word this lane fetches: chunk sub = l16 / 5 of the load, word l16 % 5 of the
+    // record of this group's sample (lane 15 repeats lane 14's word)
+    const int sub = min(l16 / kRecord, kPerLoad - 1);
+    const int word = min(l16 - sub * kRecord, kRecord - 1);
+    const float *rec_ptr = a.sorted + (int64_t)k * a.S * kRecord + (sub * kChunk + g) * kRecord + word;
+    auto load_record = [&](int chunk) { return rec_ptr[(int64_t)chunk * (kChunk * kRecord)]; };
+
+    const unsigned col_bytes = (unsigned)(col_ok ? col : 0) * 4u;
+    const unsigned row_bytes = (unsigned)a.n_out * 4u;
+    auto load_gy = [&](auto subc, float rec) {
+        constexpr int SUB = decltype(subc)::value;
+        const int n = row_bcast<kRecord * SUB + 4>(__float_as_int(rec));
+        if constexpr (kOffset32) {
+            const unsigned off = __umul24((unsigned)n, row_bytes) + col_bytes;
+            return *reinterpret_cast<const f4v *>(reinterpret_cast<const char *>(a.gy) + off);
+        } else {
+            return *reinterpret_cast<const f4v *>(reinterpret_cast<const char *>(a.gy) +
+                                                  ((int64_t)n * row_bytes + col_bytes));
+        }
+    };
 
     for (int i = lane; i < 2 * W * kTile; i += 64) win[i] = 0.0f;
 
-    f4v acc00 = {0.f, 0.f, 0.f, 0.f}, acc10 = acc00, acc01 = acc00, acc11 = acc00;
-    int cur_cell = -1;
-    int rows_done = 0;
-
-    auto wave_sum = [&](f4v v) {
-        f4v r;
+    float acc[16];
 #pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            float t = v[i];
-            t += __shfl_xor(t, 16, 64);
-            t += __shfl_xor(t, 32, 64);
-            r[i] = t;
-        }
-        return r;
-    };
+    for (int i = 0; i < 16; ++i) acc[i] = 0.f;
+    int cur_cell = -1;  // (i1 << 8 | i2) of the cell the accumulators belong to
+    int rows_done = 0;  // table rows [0, rows_done) have been written out
+
+    // add the sums of the finished cell into the two-row window: group 0 holds corner
+    // (i1, i2), group 1 (i1 + 1, i2), group 2 (i1, i2 + 1), group 3 (i1 + 1, i2 + 1)
     auto flush = [&]() {
         const int i1 = cur_cell >> 8, i2 = cur_cell & 255;
-        const f4v s00 = wave_sum(acc00), s10 = wave_sum(acc10), s01 = wave_sum(acc01), s11 = wave_sum(acc11);
-        if (g == 0) {
-            f4v *cur = reinterpret_cast<f4v *>(win + (i1 & 1) * W * kTile + i2 * kTile) + l16;
-            f4v *nxt = reinterpret_cast<f4v *>(win + ((i1 + 1) & 1) * W * kTile + i2 * kTile) + l16;
-            cur[0] += s00;
-            cur[kTile / 4] += s01;
-            nxt[0] += s10;
-            nxt[kTile / 4] += s11;
-        }
-        acc00 = acc10 = acc01 = acc11 = f4v{0.f, 0.f, 0.f, 0.f};
+        float f[4];
+        combine_groups(acc, f);
+        const int row = (i1 + (g & 1)) & 1, b = i2 + (g >> 1);
+        f4v *p = reinterpret_cast<f4v *>(win + (row * W + b) * kTile) + l16;
+        f4v v = *p;
+        v.x += f[0];
+        v.y += f[1];
+        v.z += f[2];
+        v.w += f[3];
+        *p = v;
+#pragma unroll
+        for (int i = 0; i < 16; ++i) acc[i] = 0.f;
     };
-    // four table rows entries per store instruction: group g takes b = 4 i + g
+    // table rows below `upto` can receive nothing more: write them and recycle their buffers;
+    // four table entries per store instruction, group g takes b = 4 i + g
     auto retire_rows = [&](int upto) {
         for (; rows_done < upto; ++rows_done) {
             f4v *row = reinterpret_cast<f4v *>(win + (rows_done & 1) * W * kTile) + l16;
@@ -351,44 +313,55 @@ __global__ __launch_bounds__(64) void backward_coef_wide_kernel(CoefGradArgs a)
     };
 
     if (nch > 0) {
-        // three-stage pipeline, all through in-order vector loads: at step j the sample index of
-        // chunk j + 2 depth is requested, the index of chunk j + depth (requested depth steps ago)
-        // addresses the gy and weight loads of that chunk, and chunk j is consumed
-        f4v gq[kWideDepth], wq[kWideDepth];
-        int nq[kWideDepth];
+        // Software pipeline, all through in-order vector loads: at step P of a trip the chunk
+        // c + P is consumed, the gy values of chunk c + P + kDepth are requested (their sample
+        // index comes from a record register loaded long before), and after the last chunk of a
+        // record register has been consumed the register is refilled for the next trip.
+        float rq[kRecRegs];
+        f4v gq[kDepth];
+        // The fill is issued in the order the steady state leaves the loads in at the top of a
+        // trip, so that the wait counts of the first steps are those of every other trip.
+        static_for(std::make_integer_sequence<int, kUnroll>{}, [&](auto pc) {
+            constexpr int P = decltype(pc)::value;
+            if constexpr (P < kDepth / kPerLoad + 2) {
+                rq[P] = load_record(P * kPerLoad);
+                __builtin_amdgcn_sched_barrier(0);
+            }
+        });
+        static_for(std::make_integer_sequence<int, kDepth>{}, [&](auto dc) {
+            constexpr int d = decltype(dc)::value;
+            constexpr int P = kUnroll - kDepth + d;  // the step that requests this chunk in later trips
+            gq[d] = load_gy(std::integral_constant<int, d % kPerLoad>{}, rq[d / kPerLoad]);
+            __builtin_amdgcn_sched_barrier(0);
+            if constexpr (P % kPerLoad == kPerLoad - 1) {
+                rq[P / kPerLoad] = load_record((P / kPerLoad) * kPerLoad);
+                __builtin_amdgcn_sched_barrier(0);
+            }
+        });
+        // cells of a whole trip are fetched one trip ahead (scalar loads return out of order, so
+        // every use waits for all of them: keep them few and early)
+        int cells_now[kUnroll], cells_nxt[kUnroll];
 #pragma unroll
-        for (int d = 0; d < kWideDepth; ++d) {
-            gq[d] = *reinterpret_cast<const f4v *>(gy_col + (int64_t)sn[d * kChunk] * a.n_out);
-            wq[d] = sw[d * kChunk];
-            nq[d] = sn[(kWideDepth + d) * kChunk];
-        }
-        // cells of a whole group of chunks are fetched one group ahead (scalar loads return out
-        // of order, so every use waits for all of them: keep them few and early)
-        int cells_now[kWideDepth], cells_nxt[kWideDepth];
+        for (int p = 0; p < kUnroll; ++p) cells_now[p] = cc[p];
+        for (int c = 0; c < nch; c += kUnroll) {
 #pragma unroll
-        for (int p = 0; p < kWideDepth; ++p) cells_now[p] = cc[p];
-        for (int c = 0; c < nch; c += kWideDepth) {
-#pragma unroll
-            for (int p = 0; p < kWideDepth; ++p) cells_nxt[p] = cc[c + kWideDepth + p];
-#pragma unroll
-            for (int p = 0; p < kWideDepth; ++p) {
-                const int j = c + p;
-                const int cell_cur = cells_now[p];
+            for (int p = 0; p < kUnroll; ++p) cells_nxt[p] = cc[c + kUnroll + p];
+            static_for(std::make_integer_sequence<int, kUnroll>{}, [&](auto pc) {
+                constexpr int P = decltype(pc)::value;
+                const int cell_cur = cells_now[P];
                 if (cell_cur != cur_cell) {
                     if (cur_cell >= 0) flush();
                     retire_rows(cell_cur >> 8);
                     cur_cell = cell_cur;
                 }
-                acc00 += wq[p].x * gq[p];
-                acc10 += wq[p].y * gq[p];
-                acc01 += wq[p].z * gq[p];
-                acc11 += wq[p].w * gq[p];
-                gq[p] = *reinterpret_cast<const f4v *>(gy_col + (int64_t)nq[p] * a.n_out);
-                wq[p] = sw[(j + kWideDepth) * kChunk];
-                nq[p] = sn[(j + 2 * kWideDepth) * kChunk];
-            }
+                chunk_fma<P % kPerLoad>(acc, rq[P / kPerLoad], gq[P % kDepth]);
+                gq[P % kDepth] = load_gy(std::integral_constant<int, (P + kDepth) % kPerLoad>{},
+                                         rq[((P + kDepth) / kPerLoad) % kRecRegs]);
+                if constexpr (P % kPerLoad == kPerLoad - 1)
+                    rq[P / kPerLoad] = load_record(c + kUnroll + (P / kPerLoad) * kPerLoad);
+            });
 #pragma unroll
-            for (int p = 0; p < kWideDepth; ++p) cells_now[p] = cells_nxt[p];
+            for (int p = 0; p < kUnroll; ++p) cells_now[p] = cells_nxt[p];
         }
     }
     if (cur_cell >= 0) flush();
@@ -400,8 +373,14 @@ __global__ __launch_bounds__(64) void backward_coef_wide_kernel(CoefGradArgs a)
 size_t sorted_records_bytes(const LayerShape &s)
 {
     const size_t S = (size_t)stream_stride(s.batch, s.G);
-    const size_t per_pair = S * (sizeof(f4v) + sizeof(int32_t)) + (S / kChunk) * sizeof(int32_t) + sizeof(int32_t);
+    const size_t per_pair = S * kRecord * sizeof(float) + (S / kChunk) * sizeof(int32_t) + sizeof(int32_t);
     return ((size_t)s.pairs() * per_pair + 255) & ~(size_t)255;
+}
+
+bool coef_sorted_applicable(const LayerShape &s, const float *gy, const float *gcoef)
+{
+    return s.n_out % 4 == 0 &&
+           ((reinterpret_cast<uintptr_t>(gy) | reinterpret_cast<uintptr_t>(gcoef)) & 15) == 0;
 }
 
 void launch_backward_coef_sorted(const LayerShape &s, const void *records, void *sorted, const float *gy,
@@ -413,15 +392,13 @@ void launch_backward_coef_sorted(const LayerShape &s, const void *records, void 
     const int32_t *rec_node = static_cast<const int32_t *>(records);
     const float *rec_u = reinterpret_cast<const float *>(rec_node + n);
     const float *rec_v = rec_u + n;
-    f4v *sorted_w = static_cast<f4v *>(sorted);  // 16-byte items first, then the 4-byte ones
-    int32_t *sorted_n = reinterpret_cast<int32_t *>(sorted_w + K * S);
-    int32_t *chunk_cell = sorted_n + K * S;
+    float *sorted_rec = static_cast<float *>(sorted);
+    int32_t *chunk_cell = reinterpret_cast<int32_t *>(sorted_rec + K * S * kRecord);
     int32_t *n_chunks = chunk_cell + K * (S / kChunk);
-    sort_records_kernel<<<s.pairs(), kSortThreads, 0, stream>>>(rec_node, rec_u, rec_v, sorted_n, sorted_w,
-                                                               chunk_cell, n_chunks, s.batch, s.G);
+    sort_records_kernel<<<s.pairs(), kSortThreads, 0, stream>>>(rec_node, rec_u, rec_v, sorted_rec, chunk_cell,
+                                                               n_chunks, s.batch, s.G);
     CoefGradArgs a;
-    a.sorted_n = sorted_n;
-    a.sorted_w = sorted_w;
+    a.sorted = sorted_rec;
     a.chunk_cell = chunk_cell;
     a.n_chunks = n_chunks;
     a.gy = gy;
@@ -436,12 +413,14 @@ void launch_backward_coef_sorted(const LayerShape &s, const void *records, void 
     a.G = s.G;
     a.accumulate = accumulate ? 1 : 0;
     const unsigned lds = (unsigned)(2 * (s.G + 1) * kTile * sizeof(float));
-    const bool wide = s.n_out % 4 == 0 &&
-                      ((reinterpret_cast<uintptr_t>(gy) | reinterpret_cast<uintptr_t>(gcoef)) & 15) == 0;
-    if (wide)
-        backward_coef_wide_kernel<<<s.pairs() * s.out_tiles(), 64, lds, stream>>>(a);
+    const unsigned grid = (unsigned)(s.pairs() * s.out_tiles());
+    // 24-bit multiply and 32-bit byte offsets into gy when the tensor is small enough
+    const bool offset32 = s.batch < (1 << 24) && (int64_t)s.n_out * 4 < (1 << 24) &&
+                          (int64_t)s.batch * s.n_out * 4 < ((int64_t)1 << 32);
+    if (offset32)
+        backward_coef_stream_kernel<true><<<grid, 64, lds, stream>>>(a);
     else
-        backward_coef_sorted_kernel<<<s.pairs() * s.out_tiles(), 64, lds, stream>>>(a);
+        backward_coef_stream_kernel<false><<<grid, 64, lds, stream>>>(a);
 }
 
 }  // namespace lmkan

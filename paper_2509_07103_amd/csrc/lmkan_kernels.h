@@ -52,8 +52,11 @@ void launch_backward_input_slab(const LayerShape &s, const GridTab &tab, const v
                                 float *gx, const void *records, void *scratch, hipStream_t stream);
 
 // Coefficient gradient by cell-sorted samples (lmkan_backward.hip).  `records` is the output
-// of launch_preamble_records; `sorted` is scratch of sorted_records_bytes().
+// of launch_preamble_records; `sorted` is scratch of sorted_records_bytes().  Needs n_out to be a
+// multiple of 4 and 16-byte aligned gy and gcoef (coef_sorted_applicable); other shapes take the
+// generic kernel with atomics on a zeroed gradient.
 size_t sorted_records_bytes(const LayerShape &s);
+bool coef_sorted_applicable(const LayerShape &s, const float *gy, const float *gcoef);
 void launch_backward_coef_sorted(const LayerShape &s, const void *records, void *sorted, const float *gy,
                                  float *gcoef, bool accumulate, hipStream_t stream);
 
