@@ -134,7 +134,7 @@ def main():
     s_bytes = 4 if args.storage == "f32" else 2
     # each call = its main kernel plus the small preamble-record / zero-fill / sort launches
     calls = {"forward_slab_kernel": fwd_ms, "backward_input_slab_kernel": gx_ms,
-             "backward_coef_sorted_kernel": gp_ms}
+             "backward_coef_stream_kernel": gp_ms}
     dom_name = max(calls, key=calls.get)
     dom_ms = calls[dom_name]
     achieved = 2.0 * fma / (dom_ms * 1e-3) / 1e12

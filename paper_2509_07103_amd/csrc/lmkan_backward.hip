@@ -9,10 +9,12 @@
 // Pass 2 (backward_coef_stream_kernel): one wave owns (pair k, 64 outputs) and walks the
 // sorted chunks, cell after cell.  The four samples of a chunk go to the four 16-lane
 // groups of the wave and a lane covers four adjacent outputs, so gy is read with 16-byte
-// loads.  A group's record sits in lanes of that group and reaches the multiply-adds as a
-// DPP row broadcast, so the only vector loads are one record word per three chunks and
-// the gy values themselves.  Inside a cell the 16 partial sums (4 corners x 4 outputs) live
-// in registers.  When the cell ends they are combined across the groups and added into a
+// loads.  Within a cell the update is a small dense contraction, (4 corners x samples) times
+// (samples x outputs), and runs on the matrix cores: one 4x4x1 float32 MFMA (16 blocks)
+// multiplies the four products of each group's sample with one gy value per lane, the
+// block-broadcast control handing every block of a group the products of that group's sample.
+// The 16 partial sums (4 corners x 4 outputs) live in the MFMA accumulators.  When the cell
+// ends they are combined across the groups and added into a
 // two-row window of the table kept in LDS; a table row is written to global memory exactly
 // once, when the walk has passed it.  Rows no sample touches are written as exact zeros, so
 // no separate zero fill is needed.
@@ -28,14 +30,11 @@ constexpr int kSortThreads = 1024;
 typedef float f4v __attribute__((ext_vector_type(4)));
 typedef unsigned u2v __attribute__((ext_vector_type(2)));
 
-constexpr int kChunk = 4;        // samples per chunk; a chunk never straddles two cells
-constexpr int kRecord = 5;       // words per sorted sample: w00, w10, w01, w11, sample index
-constexpr int kDepth = 6;        // chunks of gy values in flight
-constexpr int kPerLoad = 3;      // chunks whose records one load instruction brings in
-constexpr int kRecRegs = 6;      // record registers in the ring
-constexpr int kUnroll = kPerLoad * kRecRegs;  // chunks per trip of the main loop
+constexpr int kChunk = 4;    // samples per chunk; a chunk never straddles two cells
+constexpr int kDepth = 8;    // chunks of gy values in flight
+constexpr int kUnroll = 16;  // chunks per trip of the main loop: one load of sample indices
+constexpr int kPerW = 4;     // chunks whose products one load instruction brings in
 static_assert(kUnroll % kDepth == 0, "the gy ring must divide the unrolled trip");
-static_assert(kPerLoad * kRecord <= 16, "the records of one load must fit a 16-lane group");
 
 // Samples per pair in the sorted stream: every non-empty cell is padded to whole chunks, and
 // the end is padded so that the pipeline below can run (and prefetch) over whole trips of
@@ -43,20 +42,21 @@ static_assert(kPerLoad * kRecord <= 16, "the records of one load must fit a 16-l
 __host__ __device__ inline int64_t stream_stride(int64_t B, int G)
 {
     const int64_t body = (B + (int64_t)(kChunk - 1) * G * G + kChunk - 1) / kChunk * kChunk;
-    return body + (int64_t)kChunk * (3 * kUnroll);
+    return body + (int64_t)kChunk * (2 * kUnroll);
 }
 
 // records_in: [3][K][B] (node, u, v) from the preamble pass.  Per pair k, with S = stream_stride:
-//   sorted [K][S][5]     the four products (w00, w10, w01, w11) and the sample index (as bits).
-//                        Padding entries have zero products and repeat the index of a sample
-//                        of the same cell, so that what they multiply is a value the cell
-//                        sees anyway.
+//   sorted_w [K][S]      the four products (w00, w10, w01, w11) of a sample, 16 bytes
+//   sorted_n [K][S]      its index.  Padding entries have zero products and repeat the index
+//                        of a sample of the same cell, so that what they multiply is a value
+//                        the cell sees anyway.
 //   chunk_cell [K][S/4]  i1 << 8 | i2 of the cell each chunk belongs to, non-decreasing
 //   n_chunks [K]         chunks to process, a multiple of kUnroll
 __global__ __launch_bounds__(kSortThreads) void sort_records_kernel(const int32_t *__restrict__ rec_node,
                                                                    const float *__restrict__ rec_u,
                                                                    const float *__restrict__ rec_v,
-                                                                   float *__restrict__ sorted,
+                                                                   f4v *__restrict__ sorted_w,
+                                                                   int32_t *__restrict__ sorted_n,
                                                                    int32_t *__restrict__ chunk_cell,
                                                                    int32_t *__restrict__ n_chunks, int64_t B,
                                                                    int G)
@@ -71,16 +71,13 @@ __global__ __launch_bounds__(kSortThreads) void sort_records_kernel(const int32_
     const int32_t *node_k = rec_node + (int64_t)k * B;
     const float *u_k = rec_u + (int64_t)k * B;
     const float *v_k = rec_v + (int64_t)k * B;
-    float *out = sorted + (int64_t)k * S * kRecord;
+    f4v *out_w = sorted_w + (int64_t)k * S;
+    int32_t *out_n = sorted_n + (int64_t)k * S;
     int32_t *out_cell = chunk_cell + (int64_t)k * (S / kChunk);
 
     auto put = [&](int64_t pos, float w00, float w10, float w01, float w11, int32_t n) {
-        float *r = out + pos * kRecord;
-        r[0] = w00;
-        r[1] = w10;
-        r[2] = w01;
-        r[3] = w11;
-        r[4] = __int_as_float(n);
+        out_w[pos] = f4v{w00, w10, w01, w11};
+        out_n[pos] = n;
     };
 
     for (int c = threadIdx.x; c < cells; c += blockDim.x) s_count[c] = 0;
@@ -125,7 +122,7 @@ __global__ __launch_bounds__(kSortThreads) void sort_records_kernel(const int32_
     }
     const int real_chunks = total / kChunk;
     const int run_chunks = (real_chunks + kUnroll - 1) / kUnroll * kUnroll;
-    const int tail_end = run_chunks + 2 * kUnroll;  // chunks the pipelines may touch
+    const int tail_end = run_chunks + kUnroll;  // chunks the pipelines may touch
     {
         const int last = s_last_cell;
         const int code = ((last / G) << 8) | (last % G);
@@ -150,18 +147,19 @@ __global__ __launch_bounds__(kSortThreads) void sort_records_kernel(const int32_
         const int cnt = s_count[c];
         if (cnt == 0) continue;
         const int first = s_start[c], padded = (cnt + kChunk - 1) / kChunk * kChunk;
-        const int32_t n0 = __float_as_int(out[(int64_t)first * kRecord + 4]);
+        const int32_t n0 = out_n[first];
         for (int i = cnt; i < padded; ++i) put(first + i, 0.f, 0.f, 0.f, 0.f, n0);
     }
     // tail: whole dummy chunks that belong to the last non-empty cell
     {
-        const int32_t n0 = __float_as_int(out[(int64_t)s_start[s_last_cell] * kRecord + 4]);
+        const int32_t n0 = out_n[s_start[s_last_cell]];
         for (int i = total + threadIdx.x; i < tail_end * kChunk; i += blockDim.x) put(i, 0.f, 0.f, 0.f, 0.f, n0);
     }
 }
 
 struct CoefGradArgs {
-    const float *sorted;
+    const f4v *sorted_w;
+    const int32_t *sorted_n;
     const int32_t *chunk_cell;
     const int32_t *n_chunks;
     const float *gy;
@@ -175,25 +173,26 @@ struct CoefGradArgs {
     int accumulate;
 };
 
-// acc[4 q + i] += (product q of this group's sample) * gy[i].  The record of chunk SUB of a
-// load sits in lanes 5 SUB .. 5 SUB + 4 of the group.
+// acc[i][q] += (product q of this group's sample) * gy[i] for the chunk whose products sit in
+// quad SUB of every group of `w` (lane 16 g + 4 SUB + q holds product q of group g's sample).
+// One MFMA is 16 independent 4x4 outer products, block b = lanes 4b .. 4b+3: the A operand of
+// the four blocks of a group is taken from the group's block SUB (broadcast size 4 blocks),
+// the B operand is the lane's own gy value, and row q of the result lands in register q of
+// the same lane.
 template <int SUB>
-__device__ __forceinline__ void chunk_fma(float (&acc)[16], float rec, const f4v &g)
+__device__ __forceinline__ void chunk_fma(f4v (&acc)[4], float w, const f4v &g)
 {
-    static_for(std::make_integer_sequence<int, 4>{}, [&](auto qc) {
-        constexpr int q = decltype(qc)::value;
-        fmac_row_bcast<kRecord * SUB + q>(acc[4 * q + 0], rec, g.x);
-        fmac_row_bcast<kRecord * SUB + q>(acc[4 * q + 1], rec, g.y);
-        fmac_row_bcast<kRecord * SUB + q>(acc[4 * q + 2], rec, g.z);
-        fmac_row_bcast<kRecord * SUB + q>(acc[4 * q + 3], rec, g.w);
-    });
+    acc[0] = __builtin_amdgcn_mfma_f32_4x4x1f32(w, g.x, acc[0], 2, SUB, 0);
+    acc[1] = __builtin_amdgcn_mfma_f32_4x4x1f32(w, g.y, acc[1], 2, SUB, 0);
+    acc[2] = __builtin_amdgcn_mfma_f32_4x4x1f32(w, g.z, acc[2], 2, SUB, 0);
+    acc[3] = __builtin_amdgcn_mfma_f32_4x4x1f32(w, g.w, acc[3], 2, SUB, 0);
 }
 
-// The four groups' partial sums of 16 accumulators -> f[i] of group r = total of corner r,
+// The four groups' partial sums acc[output i][corner q] -> f[i] of group r = total of corner r,
 // output i.  Two rounds of "swap halves of two registers, add": the first pairs corner q
 // with corner q + 2 across the 32-lane halves, the second pairs the results across odd and
 // even 16-lane rows.
-__device__ __forceinline__ void combine_groups(const float (&acc)[16], float (&f)[4])
+__device__ __forceinline__ void combine_groups(const f4v (&acc)[4], float (&f)[4])
 {
 #if defined(LMKAN_COMBINE_BPERMUTE)
     const int g = (threadIdx.x >> 4) & 3;
@@ -202,7 +201,7 @@ __device__ __forceinline__ void combine_groups(const float (&acc)[16], float (&f
         float keep = 0.f;
 #pragma unroll
         for (int q = 0; q < 4; ++q) {
-            float t = acc[4 * q + i];
+            float t = acc[i][q];
             t += __shfl_xor(t, 16, 64);
             t += __shfl_xor(t, 32, 64);
             keep = (g == q) ? t : keep;
@@ -216,8 +215,8 @@ __device__ __forceinline__ void combine_groups(const float (&acc)[16], float (&f
 #pragma unroll
         for (int q = 0; q < 2; ++q) {
             // upper half of acc[q] <-> lower half of acc[q + 2]
-            const u2v s = __builtin_amdgcn_permlane32_swap(__float_as_uint(acc[4 * q + i]),
-                                                           __float_as_uint(acc[4 * (q + 2) + i]), false, false);
+            const u2v s = __builtin_amdgcn_permlane32_swap(__float_as_uint(acc[i][q]),
+                                                           __float_as_uint(acc[i][q + 2]), false, false);
             z[q] = __uint_as_float(s.x) + __uint_as_float(s.y);  // rows 0,1: corner q; rows 2,3: corner q + 2
         }
         // odd rows of z[0] <-> even rows of z[1]
@@ -250,18 +249,20 @@ __global__ __launch_bounds__(64) void backward_coef_stream_kernel(CoefGradArgs a
     const int nch = ((ScalarIntPtr)a.n_chunks)[k];
     float *out = a.gP + (int64_t)k * a.gmap.s_pair + col;
 
-    // record word this lane fetches: chunk sub = l16 / 5 of the load, word l16 % 5 of the
-    // record of this group's sample (lane 15 repeats lane 14's word)
-    const int sub = min(l16 / kRecord, kPerLoad - 1);
-    const int word = min(l16 - sub * kRecord, kRecord - 1);
-    const float *rec_ptr = a.sorted + (int64_t)k * a.S * kRecord + (sub * kChunk + g) * kRecord + word;
-    auto load_record = [&](int chunk) { return rec_ptr[(int64_t)chunk * (kChunk * kRecord)]; };
+    // products: lane (g, 4 j + q) fetches product q of group g's sample of chunk c + j, so one
+    // load brings in four chunks (256 contiguous bytes); sample indices: lane (g, j) fetches the
+    // index of group g's sample of chunk c + j, sixteen chunks per load
+    const float *w_ptr = reinterpret_cast<const float *>(a.sorted_w + (int64_t)k * a.S) +
+                         ((l16 >> 2) * kChunk + g) * 4 + (l16 & 3);
+    const int32_t *n_ptr = a.sorted_n + (int64_t)k * a.S + l16 * kChunk + g;
+    auto load_w = [&](int chunk) { return w_ptr[(int64_t)chunk * (kChunk * 4)]; };
+    auto load_n = [&](int chunk) { return n_ptr[(int64_t)chunk * kChunk]; };
 
     const unsigned col_bytes = (unsigned)(col_ok ? col : 0) * 4u;
     const unsigned row_bytes = (unsigned)a.n_out * 4u;
-    auto load_gy = [&](auto subc, float rec) {
+    auto load_gy = [&](auto subc, int n16) {
         constexpr int SUB = decltype(subc)::value;
-        const int n = row_bcast<kRecord * SUB + 4>(__float_as_int(rec));
+        const int n = row_bcast<SUB>(n16);
         if constexpr (kOffset32) {
             const unsigned off = __umul24((unsigned)n, row_bytes) + col_bytes;
             return *reinterpret_cast<const f4v *>(reinterpret_cast<const char *>(a.gy) + off);
@@ -273,9 +274,9 @@ __global__ __launch_bounds__(64) void backward_coef_stream_kernel(CoefGradArgs a
 
     for (int i = lane; i < 2 * W * kTile; i += 64) win[i] = 0.0f;
 
-    float acc[16];
+    f4v acc[4];  // [output i of the lane][corner q]
 #pragma unroll
-    for (int i = 0; i < 16; ++i) acc[i] = 0.f;
+    for (int i = 0; i < 4; ++i) acc[i] = f4v{0.f, 0.f, 0.f, 0.f};
     int cur_cell = -1;  // (i1 << 8 | i2) of the cell the accumulators belong to
     int rows_done = 0;  // table rows [0, rows_done) have been written out
 
@@ -294,7 +295,7 @@ __global__ __launch_bounds__(64) void backward_coef_stream_kernel(CoefGradArgs a
         v.w += f[3];
         *p = v;
 #pragma unroll
-        for (int i = 0; i < 16; ++i) acc[i] = 0.f;
+        for (int i = 0; i < 4; ++i) acc[i] = f4v{0.f, 0.f, 0.f, 0.f};
     };
     // table rows below `upto` can receive nothing more: write them and recycle their buffers;
     // four table entries per store instruction, group g takes b = 4 i + g
@@ -314,27 +315,29 @@ __global__ __launch_bounds__(64) void backward_coef_stream_kernel(CoefGradArgs a
 
     if (nch > 0) {
         // Software pipeline, all through in-order vector loads: at step P of a trip the chunk
-        // c + P is consumed, the gy values of chunk c + P + kDepth are requested (their sample
-        // index comes from a record register loaded long before), and after the last chunk of a
-        // record register has been consumed the register is refilled for the next trip.
-        float rq[kRecRegs];
+        // c + P is consumed and the gy values of chunk c + P + kDepth are requested (their sample
+        // indices were loaded a trip earlier); a register of products is refilled for the next
+        // trip as soon as its fourth chunk has been consumed.
+        float wq[kUnroll / kPerW];
         f4v gq[kDepth];
+        int n_now, n_nxt;
         // The fill is issued in the order the steady state leaves the loads in at the top of a
         // trip, so that the wait counts of the first steps are those of every other trip.
-        static_for(std::make_integer_sequence<int, kUnroll>{}, [&](auto pc) {
-            constexpr int P = decltype(pc)::value;
-            if constexpr (P < kDepth / kPerLoad + 2) {
-                rq[P] = load_record(P * kPerLoad);
+        n_now = load_n(0);
+        static_for(std::make_integer_sequence<int, kUnroll / kPerW>{}, [&](auto rc) {
+            constexpr int r = decltype(rc)::value;
+            if constexpr (r * kPerW < kUnroll - kDepth) {
+                wq[r] = load_w(r * kPerW);
                 __builtin_amdgcn_sched_barrier(0);
             }
         });
         static_for(std::make_integer_sequence<int, kDepth>{}, [&](auto dc) {
             constexpr int d = decltype(dc)::value;
             constexpr int P = kUnroll - kDepth + d;  // the step that requests this chunk in later trips
-            gq[d] = load_gy(std::integral_constant<int, d % kPerLoad>{}, rq[d / kPerLoad]);
+            gq[d] = load_gy(std::integral_constant<int, d>{}, n_now);
             __builtin_amdgcn_sched_barrier(0);
-            if constexpr (P % kPerLoad == kPerLoad - 1) {
-                rq[P / kPerLoad] = load_record((P / kPerLoad) * kPerLoad);
+            if constexpr (P % kPerW == kPerW - 1) {
+                wq[P / kPerW] = load_w((P / kPerW) * kPerW);
                 __builtin_amdgcn_sched_barrier(0);
             }
         });
@@ -346,6 +349,7 @@ __global__ __launch_bounds__(64) void backward_coef_stream_kernel(CoefGradArgs a
         for (int c = 0; c < nch; c += kUnroll) {
 #pragma unroll
             for (int p = 0; p < kUnroll; ++p) cells_nxt[p] = cc[c + kUnroll + p];
+            n_nxt = load_n(c + kUnroll);
             static_for(std::make_integer_sequence<int, kUnroll>{}, [&](auto pc) {
                 constexpr int P = decltype(pc)::value;
                 const int cell_cur = cells_now[P];
@@ -354,12 +358,12 @@ __global__ __launch_bounds__(64) void backward_coef_stream_kernel(CoefGradArgs a
                     retire_rows(cell_cur >> 8);
                     cur_cell = cell_cur;
                 }
-                chunk_fma<P % kPerLoad>(acc, rq[P / kPerLoad], gq[P % kDepth]);
-                gq[P % kDepth] = load_gy(std::integral_constant<int, (P + kDepth) % kPerLoad>{},
-                                         rq[((P + kDepth) / kPerLoad) % kRecRegs]);
-                if constexpr (P % kPerLoad == kPerLoad - 1)
-                    rq[P / kPerLoad] = load_record(c + kUnroll + (P / kPerLoad) * kPerLoad);
+                chunk_fma<P % kPerW>(acc, wq[P / kPerW], gq[P % kDepth]);
+                gq[P % kDepth] = load_gy(std::integral_constant<int, (P + kDepth) % kUnroll>{},
+                                         P + kDepth < kUnroll ? n_now : n_nxt);
+                if constexpr (P % kPerW == kPerW - 1) wq[P / kPerW] = load_w(c + kUnroll + (P / kPerW) * kPerW);
             });
+            n_now = n_nxt;
 #pragma unroll
             for (int p = 0; p < kUnroll; ++p) cells_now[p] = cells_nxt[p];
         }
@@ -373,7 +377,7 @@ __global__ __launch_bounds__(64) void backward_coef_stream_kernel(CoefGradArgs a
 size_t sorted_records_bytes(const LayerShape &s)
 {
     const size_t S = (size_t)stream_stride(s.batch, s.G);
-    const size_t per_pair = S * kRecord * sizeof(float) + (S / kChunk) * sizeof(int32_t) + sizeof(int32_t);
+    const size_t per_pair = S * (sizeof(f4v) + sizeof(int32_t)) + (S / kChunk) * sizeof(int32_t) + sizeof(int32_t);
     return ((size_t)s.pairs() * per_pair + 255) & ~(size_t)255;
 }
 
@@ -392,13 +396,15 @@ void launch_backward_coef_sorted(const LayerShape &s, const void *records, void 
     const int32_t *rec_node = static_cast<const int32_t *>(records);
     const float *rec_u = reinterpret_cast<const float *>(rec_node + n);
     const float *rec_v = rec_u + n;
-    float *sorted_rec = static_cast<float *>(sorted);
-    int32_t *chunk_cell = reinterpret_cast<int32_t *>(sorted_rec + K * S * kRecord);
+    f4v *sorted_w = static_cast<f4v *>(sorted);  // 16-byte items first, then the 4-byte ones
+    int32_t *sorted_n = reinterpret_cast<int32_t *>(sorted_w + K * S);
+    int32_t *chunk_cell = sorted_n + K * S;
     int32_t *n_chunks = chunk_cell + K * (S / kChunk);
-    sort_records_kernel<<<s.pairs(), kSortThreads, 0, stream>>>(rec_node, rec_u, rec_v, sorted_rec, chunk_cell,
-                                                               n_chunks, s.batch, s.G);
+    sort_records_kernel<<<s.pairs(), kSortThreads, 0, stream>>>(rec_node, rec_u, rec_v, sorted_w, sorted_n,
+                                                               chunk_cell, n_chunks, s.batch, s.G);
     CoefGradArgs a;
-    a.sorted = sorted_rec;
+    a.sorted_w = sorted_w;
+    a.sorted_n = sorted_n;
     a.chunk_cell = chunk_cell;
     a.n_chunks = n_chunks;
     a.gy = gy;
