@@ -93,7 +93,7 @@ __device__ __forceinline__ float widen(bf16_t v) { return __uint_as_float((uint3
 template <int S>
 __device__ __forceinline__ int row_bcast(int v)
 {
-    return __builtin_amdgcn_update_dpp(0, v, 0x150 + S, 0xf, 0xf, false);
+    return __builtin_amdgcn_update_dpp(0, v, 0x150 + S, 0xf, 0xf, true);
 }
 
 // acc += (w of lane S of this row) * c
