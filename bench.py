@@ -21,6 +21,16 @@ if ROOT not in sys.path:
 PEAK_FP32_VECTOR_TFLOPS = 157.3     # MI355X: 256 CU x 128 FMA/clk x 2 flop x 2.4 GHz
 PEAK_HBM_GBS = 8000.0
 
+# HBM bytes per launch of the dominant kernel from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this
+# file (profiles/bench_cfg3_f32_hbm_counters.md: counters scaled by what a plain 1 GiB copy reads,
+# x2.000 and x1.000).  Counters cannot be read from inside the timed process, so the figure is stored
+# here per (workload, storage, kernel); anything not measured reports null.
+MEASURED_TRAFFIC_BYTES = {
+    ("cfg3_1024x1024_G16", "f32", "backward_input_slab_kernel"): 1.579e9,
+    ("cfg3_1024x1024_G16", "f32", "forward_slab_kernel"): 1.278e9,
+    ("cfg3_1024x1024_G16", "f32", "backward_coef_stream_kernel"): 2.977e9,
+}
+
 
 def parse():
     ap = argparse.ArgumentParser()
@@ -31,6 +41,9 @@ def parse():
     ap.add_argument("--workload", default="cfg3_1024x1024_G16")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-rows", type=int, default=8192)
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="after the timed region run one plain device copy of 1 GiB (torch's copy kernel): "
+                         "the known-size reference that scales rocprofv3's FETCH_SIZE / WRITE_SIZE counters")
     return ap.parse_args()
 
 
@@ -140,7 +153,8 @@ def main():
     achieved = 2.0 * fma / (dom_ms * 1e-3) / 1e12
     roofline = {"bound": "alu", "achieved": round(achieved, 3), "peak": PEAK_FP32_VECTOR_TFLOPS,
                 "unit": "TFLOP/s", "frac": round(achieved / PEAK_FP32_VECTOR_TFLOPS, 4),
-                "traffic": None, "kernel": dom_name, "kernel_ms": round(dom_ms, 4),
+                "traffic": MEASURED_TRAFFIC_BYTES.get((w.name, args.storage, dom_name)),
+                "traffic_unit": "bytes per launch (HBM read + write)", "kernel": dom_name, "kernel_ms": round(dom_ms, 4),
                 "all_ms": {k: round(v, 4) for k, v in calls.items()}}
 
     out = {
@@ -163,6 +177,14 @@ def main():
                      "tflops": round(2 * fma_bwd / (bwd_ms * 1e-3) / 1e12, 3)},
         "roofline": roofline,
     }
+
+    if args.calibrate_copy:
+        src = torch.empty(1 << 28, dtype=torch.float32, device=dev).normal_()
+        dst = torch.empty_like(src)
+        torch.cuda.synchronize()
+        dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
 
     # ---- CPU baseline: the oracle as it stands, on a bounded row sample ---------------------
     if not args.no_cpu_baseline:
