@@ -3,9 +3,9 @@
 //   gP[a][b][k][j] = sum over samples n whose cell for pair k has (a,b) as a corner of
 //                    B_ab(x_n) * gy[n][j]                  (derivative of Alg. 1's sum)
 //
-// Pass 1 (sort_records_kernel): for every pair k the samples are grouped by cell with a
-// counting sort, each cell padded to whole chunks of four samples, and the four B-spline
-// products are stored together with the sample index as one five-word record.
+// Pass 1 (sort_count / sort_layout / sort_scatter kernels): for every pair k the samples are
+// grouped by cell with a counting sort, each cell padded to whole chunks of four samples, and
+// the four B-spline products are stored next to the sample index.
 // Pass 2 (backward_coef_stream_kernel): one wave owns (pair k, 64 outputs) and walks the
 // sorted chunks, cell after cell.  The four samples of a chunk go to the four 16-lane
 // groups of the wave and a lane covers four adjacent outputs, so gy is read with 16-byte
@@ -45,47 +45,89 @@ __host__ __device__ inline int64_t stream_stride(int64_t B, int G)
     return body + (int64_t)kChunk * (2 * kUnroll);
 }
 
-// records_in: [3][K][B] (node, u, v) from the preamble pass.  Per pair k, with S = stream_stride:
+// Counting sort of the samples of every pair by cell, in three launches so that long batches
+// are spread over many workgroups.  records_in: [3][K][B] (node, u, v) from the preamble
+// pass.  Per pair k, with S = stream_stride:
 //   sorted_w [K][S]      the four products (w00, w10, w01, w11) of a sample, 16 bytes
 //   sorted_n [K][S]      its index.  Padding entries have zero products and repeat the index
 //                        of a sample of the same cell, so that what they multiply is a value
 //                        the cell sees anyway.
 //   chunk_cell [K][S/4]  i1 << 8 | i2 of the cell each chunk belongs to, non-decreasing
 //   n_chunks [K]         chunks to process, a multiple of kUnroll
-__global__ __launch_bounds__(kSortThreads) void sort_records_kernel(const int32_t *__restrict__ rec_node,
-                                                                   const float *__restrict__ rec_u,
-                                                                   const float *__restrict__ rec_v,
-                                                                   f4v *__restrict__ sorted_w,
-                                                                   int32_t *__restrict__ sorted_n,
-                                                                   int32_t *__restrict__ chunk_cell,
-                                                                   int32_t *__restrict__ n_chunks, int64_t B,
-                                                                   int G)
+// and as scratch between the launches, with nblk = ceil(B / kSortSeg) batch segments:
+//   seg_count [K][nblk][G*G]  population of a cell inside a segment, then the offset of the
+//                             segment's first sample of that cell within the cell
+//   cell_start [K][G*G]       first stream position of the cell
+//   cell_rep [K][G*G]         index of some sample of the cell (any one)
+constexpr int kSortSeg = 4096;     // samples per workgroup in the count and scatter passes
+constexpr int kSortSegThreads = 256;
+constexpr int kMaxCells = LMKAN_MAX_GRID * LMKAN_MAX_GRID;
+
+__device__ __forceinline__ int cell_of_node(int node, int G) { return (node / (G + 1)) * G + node % (G + 1); }
+
+// 1: histogram of one batch segment
+__global__ __launch_bounds__(kSortSegThreads) void sort_count_kernel(const int32_t *__restrict__ rec_node,
+                                                                    int32_t *__restrict__ seg_count,
+                                                                    int32_t *__restrict__ cell_rep, int64_t B, int G)
 {
-    __shared__ int s_count[LMKAN_MAX_GRID * LMKAN_MAX_GRID];  // population, then scatter cursor
-    __shared__ int s_start[LMKAN_MAX_GRID * LMKAN_MAX_GRID];  // first stream position of the cell
+    __shared__ int s_count[kMaxCells];
+    __shared__ int s_rep[kMaxCells];
+    const int blk = blockIdx.x, nblk = gridDim.x, k = blockIdx.y;
+    const int cells = G * G;
+    for (int c = threadIdx.x; c < cells; c += blockDim.x) s_count[c] = 0;
+    __syncthreads();
+    const int64_t n0 = (int64_t)blk * kSortSeg;
+    const int64_t n1 = n0 + kSortSeg < B ? n0 + kSortSeg : B;
+    const int32_t *node_k = rec_node + (int64_t)k * B;
+    for (int64_t n = n0 + threadIdx.x; n < n1; n += blockDim.x) {
+        const int c = cell_of_node(node_k[n], G);
+        atomicAdd(&s_count[c], 1);
+        s_rep[c] = (int)n;  // any writer wins
+    }
+    __syncthreads();
+    int32_t *out = seg_count + ((int64_t)k * nblk + blk) * cells;
+    for (int c = threadIdx.x; c < cells; c += blockDim.x) {
+        const int cnt = s_count[c];
+        out[c] = cnt;
+        if (cnt > 0) cell_rep[(int64_t)k * cells + c] = s_rep[c];  // any segment wins
+    }
+}
+
+// 2: per pair, positions of the cells (each padded to whole chunks), the cell of every chunk,
+// padding entries and the tail
+__global__ __launch_bounds__(kSortThreads) void sort_layout_kernel(int32_t *__restrict__ seg_count,
+                                                                  int32_t *__restrict__ cell_start,
+                                                                  const int32_t *__restrict__ cell_rep,
+                                                                  f4v *__restrict__ sorted_w,
+                                                                  int32_t *__restrict__ sorted_n,
+                                                                  int32_t *__restrict__ chunk_cell,
+                                                                  int32_t *__restrict__ n_chunks, int64_t B,
+                                                                  int G, int nblk)
+{
+    __shared__ int s_count[kMaxCells];      // population of the cell
+    __shared__ int s_start[kMaxCells + 1];  // first stream position of the cell; [cells] = total
     __shared__ int s_wave_total[kSortThreads / 64];
     __shared__ int s_last_cell;
     const int k = blockIdx.x;
-    const int cells = G * G, W = G + 1;
+    const int cells = G * G;
     const int64_t S = stream_stride(B, G);
-    const int32_t *node_k = rec_node + (int64_t)k * B;
-    const float *u_k = rec_u + (int64_t)k * B;
-    const float *v_k = rec_v + (int64_t)k * B;
     f4v *out_w = sorted_w + (int64_t)k * S;
     int32_t *out_n = sorted_n + (int64_t)k * S;
     int32_t *out_cell = chunk_cell + (int64_t)k * (S / kChunk);
+    int32_t *cnt_k = seg_count + (int64_t)k * nblk * cells;
+    const int32_t *rep_k = cell_rep + (int64_t)k * cells;
+    const f4v zero = {0.f, 0.f, 0.f, 0.f};
 
-    auto put = [&](int64_t pos, float w00, float w10, float w01, float w11, int32_t n) {
-        out_w[pos] = f4v{w00, w10, w01, w11};
-        out_n[pos] = n;
-    };
-
-    for (int c = threadIdx.x; c < cells; c += blockDim.x) s_count[c] = 0;
     if (threadIdx.x == 0) s_last_cell = 0;
-    __syncthreads();
-    for (int64_t n = threadIdx.x; n < B; n += blockDim.x) {
-        const int node = node_k[n];
-        atomicAdd(&s_count[(node / W) * G + node % W], 1);
+    // populations; the per-segment counts become offsets inside the cell
+    for (int c = threadIdx.x; c < cells; c += blockDim.x) {
+        int run = 0;
+        for (int b = 0; b < nblk; ++b) {
+            const int v = cnt_k[(int64_t)b * cells + c];
+            cnt_k[(int64_t)b * cells + c] = run;
+            run += v;
+        }
+        s_count[c] = run;
     }
     __syncthreads();
     // exclusive scan of the padded populations, in pieces of blockDim.x cells
@@ -112,48 +154,80 @@ __global__ __launch_bounds__(kSortThreads) void sort_records_kernel(const int32_
         __syncthreads();
     }
     const int total = carry;  // padded samples of all cells, a multiple of kChunk
-    // the cell of every chunk
-    for (int c = threadIdx.x; c < cells; c += blockDim.x) {
-        const int cnt = s_count[c];
-        if (cnt == 0) continue;
-        const int first = s_start[c], padded = (cnt + kChunk - 1) / kChunk * kChunk;
-        const int code = ((c / G) << 8) | (c % G);
-        for (int q = first / kChunk; q < (first + padded) / kChunk; ++q) out_cell[q] = code;
-    }
+    if (threadIdx.x == 0) s_start[cells] = total;
+    __syncthreads();
+    for (int c = threadIdx.x; c < cells; c += blockDim.x) cell_start[(int64_t)k * cells + c] = s_start[c];
     const int real_chunks = total / kChunk;
     const int run_chunks = (real_chunks + kUnroll - 1) / kUnroll * kUnroll;
     const int tail_end = run_chunks + kUnroll;  // chunks the pipelines may touch
-    {
-        const int last = s_last_cell;
-        const int code = ((last / G) << 8) | (last % G);
-        for (int q = real_chunks + threadIdx.x; q < tail_end; q += blockDim.x) out_cell[q] = code;
-        if (threadIdx.x == 0) n_chunks[k] = run_chunks;
+    const int last = s_last_cell;
+    // the cell of every chunk: the highest cell whose start is <= the chunk's first position
+    // (an empty cell shares its start with the next one, so the highest such cell is never empty)
+    for (int q = threadIdx.x; q < tail_end; q += blockDim.x) {
+        int c = last;
+        if (q < real_chunks) {
+            const int pos = q * kChunk;
+            int lo = 0, hi = cells - 1;
+            while (lo < hi) {
+                const int mid = (lo + hi + 1) >> 1;
+                if (s_start[mid] <= pos) lo = mid; else hi = mid - 1;
+            }
+            c = lo;
+        }
+        out_cell[q] = ((c / G) << 8) | (c % G);
     }
-    __syncthreads();
-    // scatter; s_count becomes the cursor and ends equal to the population again
-    for (int c = threadIdx.x; c < cells; c += blockDim.x) s_count[c] = 0;
-    __syncthreads();
-    for (int64_t n = threadIdx.x; n < B; n += blockDim.x) {
-        const int node = node_k[n];
-        const float u = u_k[n], v = v_k[n];
-        const int c = (node / W) * G + node % W;
-        const int pos = s_start[c] + atomicAdd(&s_count[c], 1);
-        const float a_lo = 1.0f - u, b_lo = 1.0f - v;
-        put(pos, a_lo * b_lo, u * b_lo, a_lo * v, u * v, (int32_t)n);
-    }
-    __syncthreads();  // also makes the scattered records visible to the whole block
-    // padding entries: zero products, the index of the cell's first sample
+    // padding entries of every cell, then the tail: zero products, a sample of that cell
     for (int c = threadIdx.x; c < cells; c += blockDim.x) {
         const int cnt = s_count[c];
         if (cnt == 0) continue;
         const int first = s_start[c], padded = (cnt + kChunk - 1) / kChunk * kChunk;
-        const int32_t n0 = out_n[first];
-        for (int i = cnt; i < padded; ++i) put(first + i, 0.f, 0.f, 0.f, 0.f, n0);
+        const int32_t n0 = rep_k[c];
+        for (int i = cnt; i < padded; ++i) {
+            out_w[first + i] = zero;
+            out_n[first + i] = n0;
+        }
     }
-    // tail: whole dummy chunks that belong to the last non-empty cell
     {
-        const int32_t n0 = out_n[s_start[s_last_cell]];
-        for (int i = total + threadIdx.x; i < tail_end * kChunk; i += blockDim.x) put(i, 0.f, 0.f, 0.f, 0.f, n0);
+        const int32_t n0 = rep_k[last];
+        for (int i = total + threadIdx.x; i < tail_end * kChunk; i += blockDim.x) {
+            out_w[i] = zero;
+            out_n[i] = n0;
+        }
+        if (threadIdx.x == 0) n_chunks[k] = run_chunks;
+    }
+}
+
+// 3: scatter of one batch segment
+__global__ __launch_bounds__(kSortSegThreads) void sort_scatter_kernel(const int32_t *__restrict__ rec_node,
+                                                                      const float *__restrict__ rec_u,
+                                                                      const float *__restrict__ rec_v,
+                                                                      const int32_t *__restrict__ seg_count,
+                                                                      const int32_t *__restrict__ cell_start,
+                                                                      f4v *__restrict__ sorted_w,
+                                                                      int32_t *__restrict__ sorted_n, int64_t B,
+                                                                      int G)
+{
+    __shared__ int s_cursor[kMaxCells];
+    const int blk = blockIdx.x, nblk = gridDim.x, k = blockIdx.y;
+    const int cells = G * G;
+    const int64_t S = stream_stride(B, G);
+    const int32_t *off = seg_count + ((int64_t)k * nblk + blk) * cells;
+    for (int c = threadIdx.x; c < cells; c += blockDim.x)
+        s_cursor[c] = cell_start[(int64_t)k * cells + c] + off[c];
+    __syncthreads();
+    const int64_t n0 = (int64_t)blk * kSortSeg;
+    const int64_t n1 = n0 + kSortSeg < B ? n0 + kSortSeg : B;
+    const int32_t *node_k = rec_node + (int64_t)k * B;
+    const float *u_k = rec_u + (int64_t)k * B;
+    const float *v_k = rec_v + (int64_t)k * B;
+    f4v *out_w = sorted_w + (int64_t)k * S;
+    int32_t *out_n = sorted_n + (int64_t)k * S;
+    for (int64_t n = n0 + threadIdx.x; n < n1; n += blockDim.x) {
+        const float u = u_k[n], v = v_k[n];
+        const int pos = atomicAdd(&s_cursor[cell_of_node(node_k[n], G)], 1);
+        const float a_lo = 1.0f - u, b_lo = 1.0f - v;
+        out_w[pos] = f4v{a_lo * b_lo, u * b_lo, a_lo * v, u * v};
+        out_n[pos] = (int32_t)n;
     }
 }
 
@@ -171,6 +245,7 @@ struct CoefGradArgs {
     int K;
     int G;
     int accumulate;
+    int n_seg;  // waves per (pair, output tile)
 };
 
 // acc[i][q] += (product q of this group's sample) * gy[i] for the chunk whose products sit in
@@ -239,22 +314,36 @@ __global__ __launch_bounds__(64) void backward_coef_stream_kernel(CoefGradArgs a
     int id = blockIdx.x;
     const int total = gridDim.x;
     if ((total & 7) == 0) id = (id & 7) * (total >> 3) + (id >> 3);
+    const int seg = id % a.n_seg;
+    id /= a.n_seg;
     const int jt = id / a.K;
     const int k = id % a.K;
 
     const int col = jt * kTile + l16 * 4;
     const bool col_ok = col < a.n_out;
     typedef __attribute__((address_space(4))) const int32_t *ScalarIntPtr;
-    ScalarIntPtr cc = (ScalarIntPtr)(a.chunk_cell + (int64_t)k * (a.S / kChunk));
-    const int nch = ((ScalarIntPtr)a.n_chunks)[k];
+    // When (pairs x output tiles) alone cannot fill the chip, the stream of a pair is cut into
+    // n_seg runs of whole trips, one wave each.  A run may begin and end anywhere, even inside
+    // a cell: every wave then adds what it has into a gradient that starts at zero (atomics).
+    const bool split = a.n_seg > 1;
+    int c_begin = 0;
+    int nch = ((ScalarIntPtr)a.n_chunks)[k];
+    if (split) {
+        const int trips = nch / kUnroll;
+        const int per = (trips + a.n_seg - 1) / a.n_seg * kUnroll;
+        c_begin = min(seg * per, nch);
+        nch = min(per, nch - c_begin);
+        if (nch == 0) return;
+    }
+    ScalarIntPtr cc = (ScalarIntPtr)(a.chunk_cell + (int64_t)k * (a.S / kChunk) + c_begin);
     float *out = a.gP + (int64_t)k * a.gmap.s_pair + col;
 
     // products: lane (g, 4 j + q) fetches product q of group g's sample of chunk c + j, so one
     // load brings in four chunks (256 contiguous bytes); sample indices: lane (g, j) fetches the
     // index of group g's sample of chunk c + j, sixteen chunks per load
-    const float *w_ptr = reinterpret_cast<const float *>(a.sorted_w + (int64_t)k * a.S) +
+    const float *w_ptr = reinterpret_cast<const float *>(a.sorted_w + (int64_t)k * a.S + (int64_t)c_begin * kChunk) +
                          ((l16 >> 2) * kChunk + g) * 4 + (l16 & 3);
-    const int32_t *n_ptr = a.sorted_n + (int64_t)k * a.S + l16 * kChunk + g;
+    const int32_t *n_ptr = a.sorted_n + (int64_t)k * a.S + (int64_t)c_begin * kChunk + l16 * kChunk + g;
     auto load_w = [&](int chunk) { return w_ptr[(int64_t)chunk * (kChunk * 4)]; };
     auto load_n = [&](int chunk) { return n_ptr[(int64_t)chunk * kChunk]; };
 
@@ -306,7 +395,15 @@ __global__ __launch_bounds__(64) void backward_coef_stream_kernel(CoefGradArgs a
                 if (col_ok) {
                     f4v *dst = reinterpret_cast<f4v *>(out + (int64_t)(rows_done * W + b) * a.gmap.s_node);
                     const f4v v = row[b * (kTile / 4)];
-                    *dst = a.accumulate ? *dst + v : v;
+                    if (split) {
+                        float *d = reinterpret_cast<float *>(dst);
+                        unsafeAtomicAdd(d + 0, v.x);
+                        unsafeAtomicAdd(d + 1, v.y);
+                        unsafeAtomicAdd(d + 2, v.z);
+                        unsafeAtomicAdd(d + 3, v.w);
+                    } else {
+                        *dst = a.accumulate ? *dst + v : v;
+                    }
                 }
                 row[b * (kTile / 4)] = f4v{0.f, 0.f, 0.f, 0.f};
             }
@@ -346,6 +443,7 @@ __global__ __launch_bounds__(64) void backward_coef_stream_kernel(CoefGradArgs a
         int cells_now[kUnroll], cells_nxt[kUnroll];
 #pragma unroll
         for (int p = 0; p < kUnroll; ++p) cells_now[p] = cc[p];
+        if (split) rows_done = cells_now[0] >> 8;  // rows before the run's first cell are not this wave's
         for (int c = 0; c < nch; c += kUnroll) {
 #pragma unroll
             for (int p = 0; p < kUnroll; ++p) cells_nxt[p] = cc[c + kUnroll + p];
@@ -369,7 +467,7 @@ __global__ __launch_bounds__(64) void backward_coef_stream_kernel(CoefGradArgs a
         }
     }
     if (cur_cell >= 0) flush();
-    retire_rows(W);
+    retire_rows(split ? min(W, (cur_cell >> 8) + 2) : W);
 }
 
 }  // namespace
@@ -377,7 +475,10 @@ __global__ __launch_bounds__(64) void backward_coef_stream_kernel(CoefGradArgs a
 size_t sorted_records_bytes(const LayerShape &s)
 {
     const size_t S = (size_t)stream_stride(s.batch, s.G);
-    const size_t per_pair = S * (sizeof(f4v) + sizeof(int32_t)) + (S / kChunk) * sizeof(int32_t) + sizeof(int32_t);
+    const size_t nblk = ((size_t)s.batch + kSortSeg - 1) / kSortSeg;
+    const size_t cells = (size_t)s.G * s.G;
+    const size_t per_pair = S * (sizeof(f4v) + sizeof(int32_t)) + (S / kChunk) * sizeof(int32_t) + sizeof(int32_t) +
+                            (nblk + 2) * cells * sizeof(int32_t);
     return ((size_t)s.pairs() * per_pair + 255) & ~(size_t)255;
 }
 
@@ -400,8 +501,17 @@ void launch_backward_coef_sorted(const LayerShape &s, const void *records, void 
     int32_t *sorted_n = reinterpret_cast<int32_t *>(sorted_w + K * S);
     int32_t *chunk_cell = sorted_n + K * S;
     int32_t *n_chunks = chunk_cell + K * (S / kChunk);
-    sort_records_kernel<<<s.pairs(), kSortThreads, 0, stream>>>(rec_node, rec_u, rec_v, sorted_w, sorted_n,
-                                                               chunk_cell, n_chunks, s.batch, s.G);
+    const size_t nblk = ((size_t)s.batch + kSortSeg - 1) / kSortSeg;
+    const size_t cells = (size_t)s.G * s.G;
+    int32_t *seg_count = n_chunks + K;
+    int32_t *cell_start = seg_count + K * nblk * cells;
+    int32_t *cell_rep = cell_start + K * cells;
+    const dim3 seg_grid((unsigned)nblk, (unsigned)K);
+    sort_count_kernel<<<seg_grid, kSortSegThreads, 0, stream>>>(rec_node, seg_count, cell_rep, s.batch, s.G);
+    sort_layout_kernel<<<(unsigned)K, kSortThreads, 0, stream>>>(seg_count, cell_start, cell_rep, sorted_w, sorted_n,
+                                                               chunk_cell, n_chunks, s.batch, s.G, (int)nblk);
+    sort_scatter_kernel<<<seg_grid, kSortSegThreads, 0, stream>>>(rec_node, rec_u, rec_v, seg_count, cell_start,
+                                                                 sorted_w, sorted_n, s.batch, s.G);
     CoefGradArgs a;
     a.sorted_w = sorted_w;
     a.sorted_n = sorted_n;
@@ -419,7 +529,16 @@ void launch_backward_coef_sorted(const LayerShape &s, const void *records, void 
     a.G = s.G;
     a.accumulate = accumulate ? 1 : 0;
     const unsigned lds = (unsigned)(2 * (s.G + 1) * kTile * sizeof(float));
-    const unsigned grid = (unsigned)(s.pairs() * s.out_tiles());
+    // cut the streams when there are too few of them to fill 256 CUs x 16 waves, keeping at
+    // least four trips per wave
+    const int64_t streams = (int64_t)s.pairs() * s.out_tiles();
+    const int64_t trips = (int64_t)S / (kChunk * kUnroll);
+    int n_seg = 1;
+    while (streams * n_seg < 4096 && trips / (n_seg * 2) >= 4 && n_seg < 64) n_seg *= 2;
+    a.n_seg = n_seg;
+    if (n_seg > 1 && !accumulate)
+        launch_fill_zero(gcoef, (size_t)s.nodes() * (size_t)s.pairs() * (size_t)s.n_out, stream);
+    const unsigned grid = (unsigned)(streams * n_seg);
     // 24-bit multiply and 32-bit byte offsets into gy when the tensor is small enough
     const bool offset32 = s.batch < (1 << 24) && (int64_t)s.n_out * 4 < (1 << 24) &&
                           (int64_t)s.batch * s.n_out * 4 < ((int64_t)1 << 32);

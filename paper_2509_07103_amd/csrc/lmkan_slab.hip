@@ -102,6 +102,7 @@ struct SlabArgs {
     int W;             // G + 1
     int nodes;         // W * W
     int col_limit;     // columns >= col_limit do not exist in the coefficient tensor
+    int packed;        // 1: packed layout, the slab of (pair, tile) is contiguous
     int pairs_per_split;
     int n_btiles;
     int n_jt;
@@ -126,6 +127,16 @@ __device__ __forceinline__ unsigned lds_address(const void *p)
     return (unsigned)(size_t)(__attribute__((address_space(3))) const void *)p;
 }
 
+// Same, with the global address given as a wave-uniform base (scalar registers) plus a 32-bit
+// per-lane byte offset: stepping through a contiguous slab then costs scalar instructions only.
+__device__ __forceinline__ void lds_dma16_uniform(const void *gbase, unsigned lane_off, unsigned lds_base)
+{
+    asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1"
+                 :
+                 : "v"(lane_off), "s"(gbase), "s"(lds_base)
+                 : "memory");
+}
+
 // Stream the slab of (pair k, output tile jt) into LDS.  A wave instruction moves
 // 4 table rows (one per 16-lane group, 16 bytes per lane); the 1 KiB it writes is
 // contiguous in LDS.  Chunks are dealt round-robin to the waves.
@@ -134,9 +145,21 @@ __device__ __forceinline__ void issue_slab_load(const SlabArgs &a, float *slab, 
                                                 int lane)
 {
     const int g = lane >> 4, l16 = lane & 15;
+    const unsigned base = __builtin_amdgcn_readfirstlane(lds_address(slab));
+    if (a.packed) {
+        // the slab is one contiguous run of nodes x 256 bytes: chunk c sits at byte c * 1024
+        const char *src = reinterpret_cast<const char *>(a.P + (int64_t)k * a.map.s_pair + (int64_t)jt * a.map.s_tile);
+        const int full = a.nodes >> 2;  // chunks made of four rows
+        const unsigned lane_off = (unsigned)lane * 16u;
+        for (int c = wave; c < full; c += WAVES)
+            lds_dma16_uniform(src + (size_t)c * (4 * kRowBytes), lane_off, base + c * (4 * kRowBytes));
+        const int rest = a.nodes & 3;  // rows of the last, partial chunk
+        if (rest != 0 && full % WAVES == wave && g < rest)
+            lds_dma16_uniform(src + (size_t)full * (4 * kRowBytes), lane_off, base + full * (4 * kRowBytes));
+        return;
+    }
     const float *src = a.P + (int64_t)k * a.map.s_pair + (int64_t)jt * a.map.s_tile + l16 * 4;
     const int chunks = (a.nodes + 3) >> 2;
-    const unsigned base = __builtin_amdgcn_readfirstlane(lds_address(slab));
     const bool col_ok = jt * kTile + l16 * 4 < a.col_limit;  // never read past a table row
     for (int c = wave; c < chunks; c += WAVES) {
         const int node = c * 4 + g;
@@ -358,6 +381,7 @@ struct GradInArgs {
     int n_jt;
     int n_split;
     int col_limit;
+    int packed;
 };
 
 // out[B][n_in] = in[n_in][B]
@@ -448,6 +472,7 @@ __global__ __launch_bounds__(WAVES * 64) __attribute__((amdgpu_waves_per_eu(2, 2
     sa.map = a.map;
     sa.nodes = a.nodes;
     sa.col_limit = a.col_limit;
+    sa.packed = a.packed;
 
     const int64_t n_wave = (int64_t)btile * kTileB + (int64_t)wave * (SETS * 64);
     const int col = jt * kTile + l16 * 4;
@@ -603,6 +628,7 @@ void launch_forward_slab(const LayerShape &s, const void *coef, float *y, const 
     a.W = s.G + 1;
     a.nodes = s.nodes();
     a.col_limit = s.layout == LMKAN_LAYOUT_PACKED ? s.out_tiles() * kTile : s.n_out;
+    a.packed = s.layout == LMKAN_LAYOUT_PACKED;
     a.n_btiles = (int)((s.batch + kTileB - 1) / kTileB);
     a.n_jt = s.out_tiles();
     // split the pairs over several workgroups when the tiles alone cannot fill 256 CUs
@@ -661,6 +687,7 @@ void launch_backward_input_slab(const LayerShape &s, const GridTab &tab, const v
     a.W = s.G + 1;
     a.nodes = s.nodes();
     a.col_limit = s.layout == LMKAN_LAYOUT_PACKED ? s.out_tiles() * kTile : s.n_out;
+    a.packed = s.layout == LMKAN_LAYOUT_PACKED;
     a.n_btiles = (int)((s.batch + kTileB - 1) / kTileB);
     a.n_jt = s.out_tiles();
     const int tiles = a.n_btiles * a.n_jt;
