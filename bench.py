@@ -150,7 +150,7 @@ def main():
     s_bytes = 4 if args.storage == "f32" else 2
     # each call = its main kernel plus the small preamble-record / zero-fill / sort / transpose
     # launches; which kernel serves a call follows the library's own dispatch rules
-    slab = args.storage == "f32" and n_out % 4 == 0 and w.grid <= 16 and B >= 256
+    slab = n_out % 4 == 0 and w.grid <= 16 and B >= 256
     calls = {("forward_slab_kernel" if slab else "forward_generic_kernel"): fwd_ms,
              ("backward_input_slab_kernel" if slab else "backward_generic_kernel(grad_x)"): gx_ms,
              ("backward_coef_stream_kernel" if n_out % 4 == 0 else "backward_generic_kernel(grad_coef)"): gp_ms}

@@ -26,6 +26,15 @@ namespace {
 constexpr int kTile = LMKAN_PACK_TILE;  // 64 outputs per workgroup tile
 constexpr int kRowBytes = kTile * 4;    // one table row of a float32 slab in LDS
 
+template <typename T>
+struct is_bf16 {
+    static constexpr bool value = false;
+};
+template <>
+struct is_bf16<bf16_t> {
+    static constexpr bool value = true;
+};
+
 // ---------------------------------------------------------------------------
 // Preamble pass (Alg. 1 "Preamble"): records[field][pair][sample]
 //   field 0: node = i1 (G+1) + i2 (int32), field 1: u, field 2: v  with
@@ -90,7 +99,7 @@ __global__ __launch_bounds__(256) void preamble_records_kernel(GridTab tab, cons
 
 struct SlabArgs {
     const float *x_unused;
-    const float *P;
+    const void *P;     // float32, or 16-bit storage converted while the slab is filled
     float *y;
     const int32_t *rec_node;
     const float *rec_u;
@@ -148,7 +157,8 @@ __device__ __forceinline__ void issue_slab_load(const SlabArgs &a, float *slab, 
     const unsigned base = __builtin_amdgcn_readfirstlane(lds_address(slab));
     if (a.packed) {
         // the slab is one contiguous run of nodes x 256 bytes: chunk c sits at byte c * 1024
-        const char *src = reinterpret_cast<const char *>(a.P + (int64_t)k * a.map.s_pair + (int64_t)jt * a.map.s_tile);
+        const char *src = reinterpret_cast<const char *>(static_cast<const float *>(a.P) + (int64_t)k * a.map.s_pair +
+                                                         (int64_t)jt * a.map.s_tile);
         const int full = a.nodes >> 2;  // chunks made of four rows
         const unsigned lane_off = (unsigned)lane * 16u;
         for (int c = wave; c < full; c += WAVES)
@@ -158,7 +168,7 @@ __device__ __forceinline__ void issue_slab_load(const SlabArgs &a, float *slab, 
             lds_dma16_uniform(src + (size_t)full * (4 * kRowBytes), lane_off, base + full * (4 * kRowBytes));
         return;
     }
-    const float *src = a.P + (int64_t)k * a.map.s_pair + (int64_t)jt * a.map.s_tile + l16 * 4;
+    const float *src = static_cast<const float *>(a.P) + (int64_t)k * a.map.s_pair + (int64_t)jt * a.map.s_tile + l16 * 4;
     const int chunks = (a.nodes + 3) >> 2;
     const bool col_ok = jt * kTile + l16 * 4 < a.col_limit;  // never read past a table row
     for (int c = wave; c < chunks; c += WAVES) {
@@ -168,6 +178,69 @@ __device__ __forceinline__ void issue_slab_load(const SlabArgs &a, float *slab, 
                       __builtin_amdgcn_readfirstlane(base + c * (4 * kRowBytes)));
     }
 }
+
+// Filling a slab from 16-bit storage: the values travel through registers, are widened to
+// float32 and written with ds_write_b128, so the slab in LDS and everything that reads it
+// are those of the float32 path while the table costs half the bytes in HBM and L2.
+// issue() requests the wave's chunks (8 bytes per lane: the lane's four outputs of one
+// row), commit() converts and stores them; between the two the wave computes on the other
+// buffer.  For float32 storage issue() is the LDS-direct load above and commit() is empty.
+constexpr int kMaxSlabNodes = 17 * 17;  // slabs fit LDS twice up to G = 16
+
+template <typename CT, int WAVES>
+struct SlabFill {
+    static constexpr int kChunksPerWave = ((kMaxSlabNodes + 3) / 4 + WAVES - 1) / WAVES;
+    static constexpr int kPerPhase = (kChunksPerWave + 1) / 2;  // two phases keep the staging registers few
+    uint2 v[kPerPhase];
+
+    template <int PHASE>
+    __device__ __forceinline__ void issue(const SlabArgs &a, float *, int k, int jt, int wave, int lane)
+    {
+        const int g = lane >> 4, l16 = lane & 15;
+        const CT *src = static_cast<const CT *>(a.P) + (int64_t)k * a.map.s_pair + (int64_t)jt * a.map.s_tile + l16 * 4;
+        const bool col_ok = jt * kTile + l16 * 4 < a.col_limit;
+#pragma unroll
+        for (int i = 0; i < kPerPhase; ++i) {
+            const int node = (wave + (PHASE * kPerPhase + i) * WAVES) * 4 + g;
+            v[i] = make_uint2(0u, 0u);
+            if (node < a.nodes && col_ok) v[i] = *reinterpret_cast<const uint2 *>(src + (int64_t)node * a.map.s_node);
+        }
+    }
+    template <int PHASE>
+    __device__ __forceinline__ void commit(const SlabArgs &a, float *slab, int wave, int lane)
+    {
+        const int g = lane >> 4;
+#pragma unroll
+        for (int i = 0; i < kPerPhase; ++i) {
+            const int c = wave + (PHASE * kPerPhase + i) * WAVES;
+            if (c * 4 + g < a.nodes) {
+                float4 f;
+                if constexpr (!is_bf16<CT>::value) {
+                    typedef _Float16 h2v __attribute__((ext_vector_type(2)));
+                    const h2v lo = __builtin_bit_cast(h2v, v[i].x), hi = __builtin_bit_cast(h2v, v[i].y);
+                    f = make_float4((float)lo.x, (float)lo.y, (float)hi.x, (float)hi.y);
+                } else {
+                    f = make_float4(__uint_as_float(v[i].x << 16), __uint_as_float(v[i].x & 0xffff0000u),
+                                    __uint_as_float(v[i].y << 16), __uint_as_float(v[i].y & 0xffff0000u));
+                }
+                *reinterpret_cast<float4 *>(slab + c * (4 * kTile) + lane * 4) = f;
+            }
+        }
+    }
+};
+
+template <int WAVES>
+struct SlabFill<float, WAVES> {
+    template <int PHASE>
+    __device__ __forceinline__ void issue(const SlabArgs &a, float *slab, int k, int jt, int wave, int lane)
+    {
+        if constexpr (PHASE == 0) issue_slab_load<WAVES>(a, slab, k, jt, wave, lane);
+    }
+    template <int PHASE>
+    __device__ __forceinline__ void commit(const SlabArgs &, float *, int, int)
+    {
+    }
+};
 
 // The four table rows of one step: corners (i1,i2), (i1,i2+1), (i1+1,i2), (i1+1,i2+1).
 struct Corners {
@@ -212,25 +285,25 @@ __device__ __forceinline__ void fma_corners(float *acc, const Corners &c, float 
 // requested from LDS before the multiply-adds of step T are issued.
 constexpr int kAhead = 2;
 
-template <int T, int TOTAL>
+template <int T, int END, int TOTAL>
 __device__ __forceinline__ void slab_pipeline(float *acc, Corners (&ring)[kAhead + 1], const float *slab,
                                               const int *off, const float *w00, const float *w10,
                                               const float *w01, const float *w11, int lane_bytes, int W)
 {
-    if constexpr (T < TOTAL) {
+    if constexpr (T < END) {
         if constexpr (T + kAhead < TOTAL)
             load_corners<(T + kAhead) % 16>(ring[(T + kAhead) % (kAhead + 1)], slab, off[(T + kAhead) / 16],
                                             lane_bytes, W);
         fma_corners<T % 16>(acc + 4 * T, ring[T % (kAhead + 1)], w00[T / 16], w10[T / 16], w01[T / 16],
                             w11[T / 16]);
-        slab_pipeline<T + 1, TOTAL>(acc, ring, slab, off, w00, w10, w01, w11, lane_bytes, W);
+        slab_pipeline<T + 1, END, TOTAL>(acc, ring, slab, off, w00, w10, w01, w11, lane_bytes, W);
     }
 }
 
 // WAVES waves per workgroup, SETS x 64 samples per wave.
 // Two waves per SIMD by construction (one workgroup per CU); telling the compiler lets
 // it spend registers on keeping several LDS reads in flight.
-template <int WAVES, int SETS>
+template <typename CT, int WAVES, int SETS>
 __global__ __launch_bounds__(WAVES * 64) __attribute__((amdgpu_waves_per_eu(2, 2))) void forward_slab_kernel(SlabArgs a)
 {
     extern __shared__ __align__(16) float smem[];
@@ -281,8 +354,12 @@ __global__ __launch_bounds__(WAVES * 64) __attribute__((amdgpu_waves_per_eu(2, 2
         }
     };
 
+    SlabFill<CT, WAVES> fill;
     if (k_begin < k_end) {
-        issue_slab_load<WAVES>(a, slab0, k_begin, jt, wave, lane);
+        fill.template issue<0>(a, slab0, k_begin, jt, wave, lane);
+        fill.template commit<0>(a, slab0, wave, lane);
+        fill.template issue<1>(a, slab0, k_begin, jt, wave, lane);
+        fill.template commit<1>(a, slab0, wave, lane);
         fetch_records(k_begin);
     }
     const int lane_bytes = l16 * 16;
@@ -307,7 +384,7 @@ __global__ __launch_bounds__(WAVES * 64) __attribute__((amdgpu_waves_per_eu(2, 2
         asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
         __syncthreads();
         if (k + 1 < k_end) {
-            issue_slab_load<WAVES>(a, slab_next, k + 1, jt, wave, lane);
+            fill.template issue<0>(a, slab_next, k + 1, jt, wave, lane);
             fetch_records(k + 1);
         }
 #pragma unroll
@@ -321,7 +398,15 @@ __global__ __launch_bounds__(WAVES * 64) __attribute__((amdgpu_waves_per_eu(2, 2
             if (t == 0) load_corners<0>(ring[0], slab, off[0], lane_bytes, a.W);
             if (t == 1) load_corners<1>(ring[1], slab, off[0], lane_bytes, a.W);
         }
-        slab_pipeline<0, SETS * 16>(acc, ring, slab, off, w00, w10, w01, w11, lane_bytes, a.W);
+        // the steps of the pair in two halves; a 16-bit table is staged half a slab at a time
+        constexpr int kHalf = SETS * 8;
+        slab_pipeline<0, kHalf, SETS * 16>(acc, ring, slab, off, w00, w10, w01, w11, lane_bytes, a.W);
+        if (k + 1 < k_end) {
+            fill.template commit<0>(a, slab_next, wave, lane);
+            fill.template issue<1>(a, slab_next, k + 1, jt, wave, lane);
+        }
+        slab_pipeline<kHalf, SETS * 16, SETS * 16>(acc, ring, slab, off, w00, w10, w01, w11, lane_bytes, a.W);
+        if (k + 1 < k_end) fill.template commit<1>(a, slab_next, wave, lane);
     }
 
     // lane (g, l16) holds outputs jt*64 + 4*l16 .. +3 of samples n_wave + set*64 + 16*g + step
@@ -362,7 +447,7 @@ __global__ __launch_bounds__(WAVES * 64) __attribute__((amdgpu_waves_per_eu(2, 2
 // output tiles of a sample are spread over several workgroups).
 // ---------------------------------------------------------------------------
 struct GradInArgs {
-    const float *P;
+    const void *P;     // float32, or 16-bit storage converted while the slab is filled
     const float *gy;
     float *gx;  // transposed scratch [n_in][B], zero on entry
     const int32_t *rec_node;
@@ -442,7 +527,7 @@ __device__ __forceinline__ float grad_step(const float4 g, const Corners &c, con
     return v;
 }
 
-template <int WAVES, int SETS>
+template <typename CT, int WAVES, int SETS>
 __global__ __launch_bounds__(WAVES * 64) __attribute__((amdgpu_waves_per_eu(2, 2))) void backward_input_slab_kernel(
     GradInArgs a)
 {
@@ -508,8 +593,12 @@ __global__ __launch_bounds__(WAVES * 64) __attribute__((amdgpu_waves_per_eu(2, 2
     // columns past the end of a ragged output tile are never loaded: make them read as zero
     for (int i = threadIdx.x; i < 2 * slab_floats; i += blockDim.x) smem[i] = 0.0f;
     __syncthreads();  // zeros and s_invh in place before any slab load lands
+    SlabFill<CT, WAVES> fill;
     if (k_begin < k_end) {
-        issue_slab_load<WAVES>(sa, slab0, k_begin, jt, wave, lane);
+        fill.template issue<0>(sa, slab0, k_begin, jt, wave, lane);
+        fill.template commit<0>(sa, slab0, wave, lane);
+        fill.template issue<1>(sa, slab0, k_begin, jt, wave, lane);
+        fill.template commit<1>(sa, slab0, wave, lane);
         fetch_records(k_begin);
     }
     const int lane_bytes = l16 * 16;
@@ -537,7 +626,7 @@ __global__ __launch_bounds__(WAVES * 64) __attribute__((amdgpu_waves_per_eu(2, 2
         asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
         __syncthreads();
         if (k + 1 < k_end) {
-            issue_slab_load<WAVES>(sa, slab_next, k + 1, jt, wave, lane);
+            fill.template issue<0>(sa, slab_next, k + 1, jt, wave, lane);
             fetch_records(k + 1);
         }
 #pragma unroll
@@ -553,6 +642,12 @@ __global__ __launch_bounds__(WAVES * 64) __attribute__((amdgpu_waves_per_eu(2, 2
             if constexpr (T + kAhead < TOTAL)
                 load_corners<(T + kAhead) % 16>(ring[(T + kAhead) % (kAhead + 1)], slab,
                                                 rec[(T + kAhead) / 16].off, lane_bytes, a.W);
+            if constexpr (T == TOTAL / 2) {
+                if (k + 1 < k_end) {
+                    fill.template commit<0>(sa, slab_next, wave, lane);
+                    fill.template issue<1>(sa, slab_next, k + 1, jt, wave, lane);
+                }
+            }
             const float v = grad_step<T % 16>(gyr[T], ring[T % (kAhead + 1)], rec[T / 16], upper);
             if ((l16 & 7) == (T & 7)) stash = v;
             if constexpr ((T & 7) == 7) {
@@ -560,6 +655,7 @@ __global__ __launch_bounds__(WAVES * 64) __attribute__((amdgpu_waves_per_eu(2, 2
                 if (n < a.B) unsafeAtomicAdd(gx_lane + (int64_t)(2 * k) * a.B + ((T / 16) * 64 + ((T % 16) & ~7)), stash);
             }
         });
+        if (k + 1 < k_end) fill.template commit<1>(sa, slab_next, wave, lane);
     }
 }
 
@@ -589,7 +685,6 @@ void launch_preamble_records(const LayerShape &s, const GridTab &tab, const floa
 
 bool slab_forward_shape_ok(const LayerShape &s)
 {
-    if (s.dtype != LMKAN_F32) return false;
     if (s.n_out % 4 != 0) return false;
     if (slab_forward_lds_bytes(s) > 160 * 1024) return false;
     if (s.batch < 256) return false;  // too little work to pay for the slab streaming
@@ -607,16 +702,20 @@ void launch_forward_slab(const LayerShape &s, const void *coef, float *y, const 
 {
     constexpr int WAVES = 8, SETS = 2;
     constexpr int kTileB = WAVES * SETS * 64;
-    static bool attr_set = false;
-    if (!attr_set) {
-        (void)hipFuncSetAttribute(reinterpret_cast<const void *>(forward_slab_kernel<WAVES, SETS>),
-                                  hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
-        attr_set = true;
+    typedef void (*Kernel)(SlabArgs);
+    const Kernel kernels[3] = {forward_slab_kernel<float, WAVES, SETS>, forward_slab_kernel<_Float16, WAVES, SETS>,
+                               forward_slab_kernel<bf16_t, WAVES, SETS>};
+    const Kernel kernel = kernels[s.dtype];
+    static bool attr_set[3] = {false, false, false};
+    if (!attr_set[s.dtype]) {
+        (void)hipFuncSetAttribute(reinterpret_cast<const void *>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize,
+                                  160 * 1024);
+        attr_set[s.dtype] = true;
     }
     const size_t n = (size_t)s.pairs() * (size_t)s.batch;
     SlabArgs a;
     a.x_unused = nullptr;
-    a.P = static_cast<const float *>(coef);
+    a.P = coef;
     a.y = y;
     a.rec_node = static_cast<const int32_t *>(records);
     a.rec_u = reinterpret_cast<const float *>(a.rec_node + n);
@@ -639,7 +738,7 @@ void launch_forward_slab(const LayerShape &s, const void *coef, float *y, const 
     a.pairs_per_split = (a.K + split - 1) / split;
     a.atomic_out = split > 1;
     if (a.atomic_out) launch_fill_zero(y, (size_t)s.batch * s.n_out, stream);
-    forward_slab_kernel<WAVES, SETS><<<tiles * split, WAVES * 64, slab_forward_lds_bytes(s), stream>>>(a);
+    kernel<<<tiles * split, WAVES * 64, slab_forward_lds_bytes(s), stream>>>(a);
 }
 
 }  // namespace lmkan
@@ -663,16 +762,20 @@ void launch_backward_input_slab(const LayerShape &s, const GridTab &tab, const v
 {
     constexpr int WAVES = 8, SETS = 2;
     constexpr int kTileB = WAVES * SETS * 64;
-    auto kernel = backward_input_slab_kernel<WAVES, SETS>;
-    static bool attr_set = false;
-    if (!attr_set) {
-        (void)hipFuncSetAttribute(reinterpret_cast<const void *>(kernel),
-                                  hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
-        attr_set = true;
+    typedef void (*Kernel)(GradInArgs);
+    const Kernel kernels[3] = {backward_input_slab_kernel<float, WAVES, SETS>,
+                               backward_input_slab_kernel<_Float16, WAVES, SETS>,
+                               backward_input_slab_kernel<bf16_t, WAVES, SETS>};
+    const Kernel kernel = kernels[s.dtype];
+    static bool attr_set[3] = {false, false, false};
+    if (!attr_set[s.dtype]) {
+        (void)hipFuncSetAttribute(reinterpret_cast<const void *>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize,
+                                  160 * 1024);
+        attr_set[s.dtype] = true;
     }
     const size_t n = (size_t)s.pairs() * (size_t)s.batch;
     GradInArgs a;
-    a.P = static_cast<const float *>(coef);
+    a.P = coef;
     a.gy = gy;
     a.gx = static_cast<float *>(scratch);
     a.rec_node = static_cast<const int32_t *>(records);
