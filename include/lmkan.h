@@ -117,7 +117,12 @@ lmkan_status lmkan_pack(const lmkan_desc *desc, const void *coef_paper_dev, void
 
 /*
  * Device scratch memory lmkan_forward (pass = 0) or lmkan_backward (pass = 1)
- * needs for this batch size; may be 0.
+ * needs for this batch size; may be 0.  Forward: the preamble records of Alg. 1
+ * (cell and local coordinates per (sample, pair), 12 bytes each).  Backward:
+ * the same records, their copy sorted by cell for the coefficient gradient
+ * (about 21 bytes per (sample, pair) plus per-pair tables), and a transposed
+ * float32 copy of grad_x.  The contents are scratch: nothing is kept between
+ * calls, and two calls that share a workspace must not overlap in time.
  */
 size_t lmkan_workspace_bytes(const lmkan_desc *desc, int64_t batch, int32_t pass);
 
@@ -152,8 +157,12 @@ lmkan_status lmkan_forward(const lmkan_desc *desc, int64_t batch, const float *x
  *                 (entries no sample touches become exactly 0, cf. Sec. 3.5)
  *                 unless LMKAN_FLAG_ACCUMULATE_GRAD_COEF is set; NULL skips it.
  *   coef_dev      may be NULL when grad_x_dev is NULL.
- * The coefficient gradient is summed with float32 atomics, so its last bits
- * can differ from run to run.
+ *   workspace_dev / workspace_bytes: at least lmkan_workspace_bytes(desc, batch, 1),
+ *                 256-byte aligned.
+ * Sums are float32 and their order is not fixed (samples of one cell are taken
+ * in the order a parallel counting sort leaves them; partial sums of grad_x and,
+ * for some shapes, of grad_coef meet through float32 atomics), so the last bits
+ * of both gradients can differ from run to run.
  */
 lmkan_status lmkan_backward(const lmkan_desc *desc, int64_t batch, const float *x_dev,
                             const void *coef_dev, const float *grad_y_dev, float *grad_x_dev,
