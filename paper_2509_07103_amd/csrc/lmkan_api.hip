@@ -116,7 +116,7 @@ size_t lmkan_workspace_bytes(const lmkan_desc *desc, int64_t batch, int32_t pass
     // backward: preamble records, the cell-sorted copy used by the coefficient gradient, and the
     // transposed scratch of the input gradient
     return align256(records_bytes(s)) + sorted_records_bytes(s) +
-           (slab_forward_shape_ok(s) ? slab_backward_input_scratch_bytes(s) : 0);
+           (slab_backward_input_shape_ok(s) ? slab_backward_input_scratch_bytes(s) : 0);
 }
 
 lmkan_status lmkan_pack(const lmkan_desc *desc, const void *coef_paper_dev, void *coef_packed_dev,

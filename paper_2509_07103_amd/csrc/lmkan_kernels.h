@@ -46,6 +46,7 @@ void launch_preamble_records(const LayerShape &s, const GridTab &tab, const floa
 void launch_forward_slab(const LayerShape &s, const void *coef, float *y, const void *records,
                          hipStream_t stream);
 
+bool slab_backward_input_shape_ok(const LayerShape &s);
 bool slab_backward_input_applicable(const LayerShape &s, const void *coef, const float *gy, const float *gx);
 size_t slab_backward_input_scratch_bytes(const LayerShape &s);
 void launch_backward_input_slab(const LayerShape &s, const GridTab &tab, const void *coef, const float *gy,

@@ -149,13 +149,16 @@ __device__ __forceinline__ void lds_dma16_uniform(const void *gbase, unsigned la
 // Stream the slab of (pair k, output tile jt) into LDS.  A wave instruction moves
 // 4 table rows (one per 16-lane group, 16 bytes per lane); the 1 KiB it writes is
 // contiguous in LDS.  Chunks are dealt round-robin to the waves.
-template <int WAVES>
+// LPS = lanes per table row: 16 for 64-output tiles, 4 for 16-output tiles (a 1 KiB chunk is
+// then 16 rows).
+template <int WAVES, int LPS = 16>
 __device__ __forceinline__ void issue_slab_load(const SlabArgs &a, float *slab, int k, int jt, int wave,
                                                 int lane)
 {
-    const int g = lane >> 4, l16 = lane & 15;
+    constexpr int NG = 64 / LPS;  // rows per chunk
+    const int g = lane / LPS, l16 = lane % LPS;
     const unsigned base = __builtin_amdgcn_readfirstlane(lds_address(slab));
-    if (a.packed) {
+    if (LPS == 16 && a.packed) {
         // the slab is one contiguous run of nodes x 256 bytes: chunk c sits at byte c * 1024
         const char *src = reinterpret_cast<const char *>(static_cast<const float *>(a.P) + (int64_t)k * a.map.s_pair +
                                                          (int64_t)jt * a.map.s_tile);
@@ -168,11 +171,13 @@ __device__ __forceinline__ void issue_slab_load(const SlabArgs &a, float *slab, 
             lds_dma16_uniform(src + (size_t)full * (4 * kRowBytes), lane_off, base + full * (4 * kRowBytes));
         return;
     }
-    const float *src = static_cast<const float *>(a.P) + (int64_t)k * a.map.s_pair + (int64_t)jt * a.map.s_tile + l16 * 4;
-    const int chunks = (a.nodes + 3) >> 2;
-    const bool col_ok = jt * kTile + l16 * 4 < a.col_limit;  // never read past a table row
+    const int col = jt * (LPS * 4) + l16 * 4;
+    const float *src = static_cast<const float *>(a.P) + (int64_t)k * a.map.s_pair +
+                       (int64_t)(col >> 6) * a.map.s_tile + (col & 63);
+    const int chunks = (a.nodes + NG - 1) / NG;
+    const bool col_ok = col < a.col_limit;  // never read past a table row
     for (int c = wave; c < chunks; c += WAVES) {
-        const int node = c * 4 + g;
+        const int node = c * NG + g;
         if (node < a.nodes && col_ok)
             lds_dma16(src + (int64_t)node * a.map.s_node,
                       __builtin_amdgcn_readfirstlane(base + c * (4 * kRowBytes)));
@@ -185,23 +190,26 @@ __device__ __forceinline__ void issue_slab_load(const SlabArgs &a, float *slab, 
 // issue() requests the wave's chunks (8 bytes per lane: the lane's four outputs of one
 // row), commit() converts and stores them; between the two the wave computes on the other
 // buffer.  For float32 storage issue() is the LDS-direct load above and commit() is empty.
-constexpr int kMaxSlabNodes = 17 * 17;  // slabs fit LDS twice up to G = 16
+constexpr int kMaxSlabBytes = 80 * 1024;  // one of the two slab buffers
 
-template <typename CT, int WAVES>
+template <typename CT, int WAVES, int LPS = 16>
 struct SlabFill {
-    static constexpr int kChunksPerWave = ((kMaxSlabNodes + 3) / 4 + WAVES - 1) / WAVES;
+    static constexpr int NG = 64 / LPS;  // rows per 1 KiB chunk
+    static constexpr int kChunksPerWave = (kMaxSlabBytes / 1024 + WAVES - 1) / WAVES;
     static constexpr int kPerPhase = (kChunksPerWave + 1) / 2;  // two phases keep the staging registers few
     uint2 v[kPerPhase];
 
     template <int PHASE>
     __device__ __forceinline__ void issue(const SlabArgs &a, float *, int k, int jt, int wave, int lane)
     {
-        const int g = lane >> 4, l16 = lane & 15;
-        const CT *src = static_cast<const CT *>(a.P) + (int64_t)k * a.map.s_pair + (int64_t)jt * a.map.s_tile + l16 * 4;
-        const bool col_ok = jt * kTile + l16 * 4 < a.col_limit;
+        const int g = lane / LPS, l16 = lane % LPS;
+        const int col = jt * (LPS * 4) + l16 * 4;
+        const CT *src = static_cast<const CT *>(a.P) + (int64_t)k * a.map.s_pair + (int64_t)(col >> 6) * a.map.s_tile +
+                        (col & 63);
+        const bool col_ok = col < a.col_limit;
 #pragma unroll
         for (int i = 0; i < kPerPhase; ++i) {
-            const int node = (wave + (PHASE * kPerPhase + i) * WAVES) * 4 + g;
+            const int node = (wave + (PHASE * kPerPhase + i) * WAVES) * NG + g;
             v[i] = make_uint2(0u, 0u);
             if (node < a.nodes && col_ok) v[i] = *reinterpret_cast<const uint2 *>(src + (int64_t)node * a.map.s_node);
         }
@@ -209,11 +217,11 @@ struct SlabFill {
     template <int PHASE>
     __device__ __forceinline__ void commit(const SlabArgs &a, float *slab, int wave, int lane)
     {
-        const int g = lane >> 4;
+        const int g = lane / LPS;
 #pragma unroll
         for (int i = 0; i < kPerPhase; ++i) {
             const int c = wave + (PHASE * kPerPhase + i) * WAVES;
-            if (c * 4 + g < a.nodes) {
+            if (c * NG + g < a.nodes) {
                 float4 f;
                 if constexpr (!is_bf16<CT>::value) {
                     typedef _Float16 h2v __attribute__((ext_vector_type(2)));
@@ -229,12 +237,12 @@ struct SlabFill {
     }
 };
 
-template <int WAVES>
-struct SlabFill<float, WAVES> {
+template <int WAVES, int LPS>
+struct SlabFill<float, WAVES, LPS> {
     template <int PHASE>
     __device__ __forceinline__ void issue(const SlabArgs &a, float *slab, int k, int jt, int wave, int lane)
     {
-        if constexpr (PHASE == 0) issue_slab_load<WAVES>(a, slab, k, jt, wave, lane);
+        if constexpr (PHASE == 0) issue_slab_load<WAVES, LPS>(a, slab, k, jt, wave, lane);
     }
     template <int PHASE>
     __device__ __forceinline__ void commit(const SlabArgs &, float *, int, int)
@@ -659,6 +667,193 @@ __global__ __launch_bounds__(WAVES * 64) __attribute__((amdgpu_waves_per_eu(2, 2
     }
 }
 
+// ---------------------------------------------------------------------------
+// Forward for grids whose 64-output slab does not fit LDS twice (17 <= G <= 34): the same
+// streaming with 16-output tiles.  A table row is then 64 bytes, read by four lanes, so a wave
+// takes 16 samples per step and the sample's weights reach its four lanes through the DPP
+// quad broadcast.  A wave owns SETS x 64 samples (512 with SETS = 8: a whole batch of 4096
+// per workgroup, so that for such batches every slab is fetched exactly once); the records of
+// a set are fetched three sets ahead into a ring of four.
+// ---------------------------------------------------------------------------
+template <int T>
+__device__ __forceinline__ int quad_bcast(int v)
+{
+    return __builtin_amdgcn_update_dpp(0, v, T * 0x55, 0xf, 0xf, true);
+}
+
+// acc += (w of lane T of this quad) * c
+template <int T>
+__device__ __forceinline__ void fmac_quad_bcast(float &acc, float w, float c)
+{
+    asm("v_fmac_f32_dpp %0, %1, %2 quad_perm:[%3,%3,%3,%3] row_mask:0xf bank_mask:0xf"
+        : "+v"(acc)
+        : "v"(w), "v"(c), "n"(T));
+}
+
+constexpr int kNarrowTile = 16;               // outputs per workgroup tile
+constexpr int kNarrowRowBytes = kNarrowTile * 4;
+
+template <int T>
+__device__ __forceinline__ void load_corners_quad(Corners &c, const float *slab, int off_bytes, int lane_bytes, int W)
+{
+    const float *rowp =
+        reinterpret_cast<const float *>(reinterpret_cast<const char *>(slab) + quad_bcast<T>(off_bytes) + lane_bytes);
+    c.c00 = *reinterpret_cast<const float4 *>(rowp);
+    c.c01 = *reinterpret_cast<const float4 *>(rowp + kNarrowTile);
+    c.c10 = *reinterpret_cast<const float4 *>(rowp + W * kNarrowTile);
+    c.c11 = *reinterpret_cast<const float4 *>(rowp + W * kNarrowTile + kNarrowTile);
+}
+
+template <int T>
+__device__ __forceinline__ void fma_corners_quad(float *acc, const Corners &c, float w00, float w10, float w01,
+                                                 float w11)
+{
+    fmac_quad_bcast<T>(acc[0], w00, c.c00.x);
+    fmac_quad_bcast<T>(acc[1], w00, c.c00.y);
+    fmac_quad_bcast<T>(acc[2], w00, c.c00.z);
+    fmac_quad_bcast<T>(acc[3], w00, c.c00.w);
+    fmac_quad_bcast<T>(acc[0], w10, c.c10.x);
+    fmac_quad_bcast<T>(acc[1], w10, c.c10.y);
+    fmac_quad_bcast<T>(acc[2], w10, c.c10.z);
+    fmac_quad_bcast<T>(acc[3], w10, c.c10.w);
+    fmac_quad_bcast<T>(acc[0], w01, c.c01.x);
+    fmac_quad_bcast<T>(acc[1], w01, c.c01.y);
+    fmac_quad_bcast<T>(acc[2], w01, c.c01.z);
+    fmac_quad_bcast<T>(acc[3], w01, c.c01.w);
+    fmac_quad_bcast<T>(acc[0], w11, c.c11.x);
+    fmac_quad_bcast<T>(acc[1], w11, c.c11.y);
+    fmac_quad_bcast<T>(acc[2], w11, c.c11.z);
+    fmac_quad_bcast<T>(acc[3], w11, c.c11.w);
+}
+
+template <typename CT, int WAVES, int SETS>
+__global__ __launch_bounds__(WAVES * 64) __attribute__((amdgpu_waves_per_eu(2, 2))) void forward_slab_narrow_kernel(
+    SlabArgs a)
+{
+    static_assert(sizeof(CT) == 2, "the slab is staged through registers (16-bit tables)");
+    extern __shared__ __align__(16) float smem[];
+    constexpr int LPS = 4;             // lanes per sample
+    constexpr int STEPS = SETS * LPS;  // steps per pair, 16 samples each
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int sub = lane & 3, grp = lane >> 2;
+    constexpr int kTileB = WAVES * SETS * 64;
+
+    int id = blockIdx.x;
+    const int total = gridDim.x;
+    if ((total & 7) == 0) id = (id & 7) * (total >> 3) + (id >> 3);
+    const int btile = id % a.n_btiles;
+    const int rest = id / a.n_btiles;
+    const int ks = rest % a.n_split;
+    const int jt = rest / a.n_split;
+
+    const int k_begin = ks * a.pairs_per_split;
+    const int k_end = min(a.K, k_begin + a.pairs_per_split);
+    const int slab_floats = a.nodes * kNarrowTile;
+    float *slab0 = smem;
+    float *slab1 = smem + slab_floats;
+    const int64_t n_wave = (int64_t)btile * kTileB + (int64_t)wave * (SETS * 64);
+
+    float acc[SETS * 16];
+#pragma unroll
+    for (int i = 0; i < SETS * 16; ++i) acc[i] = 0.0f;
+
+    // Record ring, one slot per set: slot s holds (node, u, v) of sample n_wave + s * 64 + lane.
+    // A slot is refilled for the next pair as soon as its set has started, a whole pair before
+    // it is needed again.  Vector loads return in order, so a wait for a record also waits for
+    // every older load: the order of issue below keeps the slab loads (long latency, straight
+    // from HBM) younger than any record that is waited for before they are due.
+    int r_node[SETS];
+    float r_u[SETS], r_v[SETS];
+    auto fetch_record = [&](int slot, int k) {
+        const int64_t n = n_wave + slot * 64 + lane;
+        r_node[slot] = 0;
+        r_u[slot] = 0.f;
+        r_v[slot] = 0.f;
+        if (n < a.B && k < k_end) {
+            const int64_t o = (int64_t)k * a.B + n;
+            r_node[slot] = a.rec_node[o];
+            r_u[slot] = a.rec_u[o];
+            r_v[slot] = a.rec_v[o];
+        }
+    };
+
+    SlabFill<CT, WAVES, LPS> fill;
+    if (k_begin < k_end) {
+#pragma unroll
+        for (int s = 0; s < SETS; ++s) fetch_record(s, k_begin);
+        fill.template issue<0>(a, slab0, k_begin, jt, wave, lane);
+        fill.template commit<0>(a, slab0, wave, lane);
+        fill.template issue<1>(a, slab0, k_begin, jt, wave, lane);
+        fill.template commit<1>(a, slab0, wave, lane);
+    }
+    const int lane_bytes = sub * 16;
+    for (int k = k_begin; k < k_end; ++k) {
+        const float *slab = ((k - k_begin) & 1) ? slab1 : slab0;
+        float *slab_next = ((k - k_begin) & 1) ? slab0 : slab1;
+        __syncthreads();  // the slab of pair k is complete, nobody reads the other buffer any more
+        if (k + 1 < k_end) fill.template issue<0>(a, slab_next, k + 1, jt, wave, lane);
+
+        constexpr int kNear = 1;  // LDS reads run one step ahead (registers are short here)
+        Corners ring[kNear + 1];
+        int off_cur = r_node[0] * kNarrowRowBytes, off_nxt = 0;
+        float w00 = 0.f, w10 = 0.f, w01 = 0.f, w11 = 0.f;
+        load_corners_quad<0>(ring[0], slab, off_cur, lane_bytes, a.W);
+        static_for(std::make_integer_sequence<int, STEPS>{}, [&](auto fc) {
+            constexpr int F = decltype(fc)::value;
+            constexpr int set = F / LPS, t = F % LPS;
+            if constexpr (t == 0) {
+                if constexpr (set == SETS / 2) {
+                    if (k + 1 < k_end) {
+                        fill.template commit<0>(a, slab_next, wave, lane);
+                        fill.template issue<1>(a, slab_next, k + 1, jt, wave, lane);
+                    }
+                }
+                // weights of this set, offsets of the next one; then the slot is free
+                const float u = r_u[set], v = r_v[set];
+                const float a_lo = 1.0f - u, b_lo = 1.0f - v;
+                w00 = a_lo * b_lo;
+                w10 = u * b_lo;
+                w01 = a_lo * v;
+                w11 = u * v;
+                if constexpr (set > 0) off_cur = off_nxt;
+                if constexpr (set + 1 < SETS) off_nxt = r_node[set + 1] * kNarrowRowBytes;
+                // VALU results must not be read through DPP in the next two issue slots
+                asm volatile("s_nop 1" : "+v"(w00), "+v"(w10), "+v"(w01), "+v"(w11), "+v"(off_cur), "+v"(off_nxt));
+                fetch_record(set, k + 1);
+            }
+            if constexpr (F + kNear < STEPS) {
+                constexpr int F2 = F + kNear;
+                load_corners_quad<F2 % LPS>(ring[F2 % (kNear + 1)], slab, (F2 / LPS == set) ? off_cur : off_nxt,
+                                            lane_bytes, a.W);
+            }
+            fma_corners_quad<t>(acc + 4 * F, ring[F % (kNear + 1)], w00, w10, w01, w11);
+        });
+        if (k + 1 < k_end) fill.template commit<1>(a, slab_next, wave, lane);
+    }
+
+    // lane (grp, sub) holds outputs jt*16 + 4*sub .. +3 of samples n_wave + set*64 + 4*grp + t
+    const int col = jt * kNarrowTile + sub * 4;
+    if (col < a.n_out) {
+#pragma unroll
+        for (int F = 0; F < STEPS; ++F) {
+            const int64_t n = n_wave + (F / LPS) * 64 + grp * LPS + (F % LPS);
+            if (n < a.B) {
+                float *dst = a.y + n * a.n_out + col;
+                const float *v = acc + 4 * F;
+                if (a.atomic_out) {
+                    unsafeAtomicAdd(dst + 0, v[0]);
+                    unsafeAtomicAdd(dst + 1, v[1]);
+                    unsafeAtomicAdd(dst + 2, v[2]);
+                    unsafeAtomicAdd(dst + 3, v[3]);
+                } else {
+                    *reinterpret_cast<float4 *>(dst) = make_float4(v[0], v[1], v[2], v[3]);
+                }
+            }
+        }
+    }
+}
+
 }  // namespace
 
 size_t slab_forward_lds_bytes(const LayerShape &s)
@@ -683,7 +878,8 @@ void launch_preamble_records(const LayerShape &s, const GridTab &tab, const floa
     preamble_records_kernel<<<grid, 256, 0, stream>>>(tab, x, rec_node, rec_u, rec_v, s.batch, s.n_in);
 }
 
-bool slab_forward_shape_ok(const LayerShape &s)
+// 64-output tiles: the float32 slab fits LDS twice (G <= 16)
+static bool slab_wide_ok(const LayerShape &s)
 {
     if (s.n_out % 4 != 0) return false;
     if (slab_forward_lds_bytes(s) > 160 * 1024) return false;
@@ -691,15 +887,70 @@ bool slab_forward_shape_ok(const LayerShape &s)
     return true;
 }
 
+// 16-output tiles for larger grids (G <= 34), 16-bit tables only
+static bool slab_narrow_ok(const LayerShape &s)
+{
+    if (s.dtype == LMKAN_F32 || s.n_out % 4 != 0 || s.batch < 256) return false;
+    return !slab_wide_ok(s) && (size_t)2 * s.nodes() * kNarrowRowBytes <= 160 * 1024;
+}
+
+bool slab_forward_shape_ok(const LayerShape &s) { return slab_wide_ok(s) || slab_narrow_ok(s); }
+
 bool slab_forward_applicable(const LayerShape &s, const void *coef, const float *y)
 {
     if (!slab_forward_shape_ok(s)) return false;
     return ((reinterpret_cast<uintptr_t>(coef) | reinterpret_cast<uintptr_t>(y)) & 15) == 0;
 }
 
+static void launch_forward_slab_narrow(const LayerShape &s, const void *coef, float *y, const void *records,
+                                       hipStream_t stream)
+{
+    constexpr int WAVES = 8, SETS = 8;
+    constexpr int kTileB = WAVES * SETS * 64;
+    typedef void (*Kernel)(SlabArgs);
+    const Kernel kernel = s.dtype == LMKAN_F16 ? forward_slab_narrow_kernel<_Float16, WAVES, SETS>
+                                               : forward_slab_narrow_kernel<bf16_t, WAVES, SETS>;
+    static bool attr_set[3] = {false, false, false};
+    if (!attr_set[s.dtype]) {
+        (void)hipFuncSetAttribute(reinterpret_cast<const void *>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize,
+                                  160 * 1024);
+        attr_set[s.dtype] = true;
+    }
+    const size_t n = (size_t)s.pairs() * (size_t)s.batch;
+    SlabArgs a;
+    a.x_unused = nullptr;
+    a.P = coef;
+    a.y = y;
+    a.rec_node = static_cast<const int32_t *>(records);
+    a.rec_u = reinterpret_cast<const float *>(a.rec_node + n);
+    a.rec_v = a.rec_u + n;
+    a.map = coef_map(s);
+    a.B = s.batch;
+    a.n_out = s.n_out;
+    a.K = s.pairs();
+    a.W = s.G + 1;
+    a.nodes = s.nodes();
+    a.col_limit = s.layout == LMKAN_LAYOUT_PACKED ? s.out_tiles() * kTile : s.n_out;
+    a.packed = s.layout == LMKAN_LAYOUT_PACKED;
+    a.n_btiles = (int)((s.batch + kTileB - 1) / kTileB);
+    a.n_jt = (s.n_out + kNarrowTile - 1) / kNarrowTile;
+    const int tiles = a.n_btiles * a.n_jt;
+    int split = 1;
+    while (tiles * split < 256 && a.K / (split * 2) >= 32) split *= 2;
+    a.n_split = split;
+    a.pairs_per_split = (a.K + split - 1) / split;
+    a.atomic_out = split > 1;
+    if (a.atomic_out) launch_fill_zero(y, (size_t)s.batch * s.n_out, stream);
+    kernel<<<tiles * split, WAVES * 64, (size_t)2 * s.nodes() * kNarrowRowBytes, stream>>>(a);
+}
+
 void launch_forward_slab(const LayerShape &s, const void *coef, float *y, const void *records,
                          hipStream_t stream)
 {
+    if (!slab_wide_ok(s)) {
+        launch_forward_slab_narrow(s, coef, y, records, stream);
+        return;
+    }
     constexpr int WAVES = 8, SETS = 2;
     constexpr int kTileB = WAVES * SETS * 64;
     typedef void (*Kernel)(SlabArgs);
@@ -745,9 +996,11 @@ void launch_forward_slab(const LayerShape &s, const void *coef, float *y, const 
 
 namespace lmkan {
 
+bool slab_backward_input_shape_ok(const LayerShape &s) { return slab_wide_ok(s); }
+
 bool slab_backward_input_applicable(const LayerShape &s, const void *coef, const float *gy, const float *gx)
 {
-    if (!slab_forward_shape_ok(s)) return false;
+    if (!slab_backward_input_shape_ok(s)) return false;
     return ((reinterpret_cast<uintptr_t>(coef) | reinterpret_cast<uintptr_t>(gy)) & 15) == 0 &&
            (reinterpret_cast<uintptr_t>(gx) & 3) == 0;
 }

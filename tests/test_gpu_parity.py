@@ -60,6 +60,11 @@ SHAPES = [
     (1100, 140, 132, 16),
     (2053, 64, 64, 12),
     (300, 10, 260, 3),
+    # grids too fine for 64-output slabs: 16-output slabs (16-bit tables), ragged everything,
+    # more samples than one workgroup takes
+    (700, 12, 72, 20),
+    (4200, 6, 40, 32),
+    (300, 8, 20, 34),
 ]
 
 
