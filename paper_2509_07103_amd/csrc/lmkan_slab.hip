@@ -854,6 +854,178 @@ __global__ __launch_bounds__(WAVES * 64) __attribute__((amdgpu_waves_per_eu(2, 2
     }
 }
 
+// ---------------------------------------------------------------------------
+// Input gradient with 16-output slabs (the mirror of forward_slab_narrow_kernel): gy of the
+// wave's SETS x 64 samples stays in registers, a step forms the four partial dot products of
+// 16 samples, applies each sample's weights by the DPP quad broadcast and sums over the four
+// lanes of the sample with two quad permutations.  Lanes 0-1 of a quad end up with d/dx1,
+// lanes 2-3 with d/dx2; over the four steps of a set every lane keeps two results, which
+// leave with two atomic instructions per set into the transposed scratch.
+// ---------------------------------------------------------------------------
+template <int T>
+__device__ __forceinline__ float mul_quad_bcast(float w, float x)
+{
+    float d;
+    asm("v_mul_f32_dpp %0, %1, %2 quad_perm:[%3,%3,%3,%3] row_mask:0xf bank_mask:0xf"
+        : "=v"(d)
+        : "v"(w), "v"(x), "n"(T));
+    return d;
+}
+
+template <int T>
+__device__ __forceinline__ float grad_step_quad(const float4 g, const Corners &c, float b_lo, float b_hi, float a_lo,
+                                                float a_hi, bool upper)
+{
+    const float s00 = fmaf(g.w, c.c00.w, fmaf(g.z, c.c00.z, fmaf(g.y, c.c00.y, g.x * c.c00.x)));
+    const float s10 = fmaf(g.w, c.c10.w, fmaf(g.z, c.c10.z, fmaf(g.y, c.c10.y, g.x * c.c10.x)));
+    const float s01 = fmaf(g.w, c.c01.w, fmaf(g.z, c.c01.z, fmaf(g.y, c.c01.y, g.x * c.c01.x)));
+    const float s11 = fmaf(g.w, c.c11.w, fmaf(g.z, c.c11.z, fmaf(g.y, c.c11.y, g.x * c.c11.x)));
+    float t1 = mul_quad_bcast<T>(b_lo, s10 - s00);
+    fmac_quad_bcast<T>(t1, b_hi, s11 - s01);
+    float t2 = mul_quad_bcast<T>(a_lo, s01 - s00);
+    fmac_quad_bcast<T>(t2, a_hi, s11 - s10);
+    const float keep = upper ? t2 : t1;
+    const float send = upper ? t1 : t2;
+    float v = keep + dpp_move<0x4E>(send);  // quad_perm [2,3,0,1]
+    v += dpp_move<0xB1>(v);                 // quad_perm [1,0,3,2]
+    return v;
+}
+
+template <typename CT, int WAVES, int SETS>
+__global__ __launch_bounds__(WAVES * 64) __attribute__((amdgpu_waves_per_eu(2, 2))) void backward_input_slab_narrow_kernel(
+    GradInArgs a)
+{
+    static_assert(sizeof(CT) == 2, "the slab is staged through registers (16-bit tables)");
+    extern __shared__ __align__(16) float smem[];  // two slab buffers, then 1/h of the grid
+    constexpr int LPS = 4;
+    constexpr int STEPS = SETS * LPS;
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int sub = lane & 3, grp = lane >> 2;
+    constexpr int kTileB = WAVES * SETS * 64;
+    int id = blockIdx.x;
+    const int total = gridDim.x;
+    if ((total & 7) == 0) id = (id & 7) * (total >> 3) + (id >> 3);
+    const int btile = id % a.n_btiles;
+    const int rest = id / a.n_btiles;
+    const int ks = rest % a.n_split;
+    const int jt = rest / a.n_split;
+
+    const int k_begin = ks * a.pairs_per_split;
+    const int k_end = min(a.K, k_begin + a.pairs_per_split);
+    const int slab_floats = a.nodes * kNarrowTile;
+    float *slab0 = smem;
+    float *slab1 = smem + slab_floats;
+    float *s_invh = smem + 2 * slab_floats;
+    for (int i = threadIdx.x; i < a.tab.G; i += blockDim.x) s_invh[i] = a.tab.inv_h[i];
+    SlabArgs sa;  // only the fields the slab fill reads
+    sa.P = a.P;
+    sa.map = a.map;
+    sa.nodes = a.nodes;
+    sa.col_limit = a.col_limit;
+    sa.packed = a.packed;
+
+    const int64_t n_wave = (int64_t)btile * kTileB + (int64_t)wave * (SETS * 64);
+    const int col = jt * kNarrowTile + sub * 4;
+    const bool upper = (sub & 2) != 0;
+    const float inv_w = 1.0f / (float)a.W;
+
+    // gy of (sample n_wave + set*64 + 4 grp + t, outputs col .. col+3), resident for the walk
+    float4 gyr[STEPS];
+#pragma unroll
+    for (int F = 0; F < STEPS; ++F) {
+        const int64_t n = n_wave + (F / LPS) * 64 + grp * LPS + (F % LPS);
+        gyr[F] = make_float4(0.f, 0.f, 0.f, 0.f);
+        if (n < a.B && col < a.n_out) gyr[F] = *reinterpret_cast<const float4 *>(a.gy + n * a.n_out + col);
+    }
+
+    int r_node[SETS];
+    float r_u[SETS], r_v[SETS];
+    auto fetch_record = [&](int slot, int k) {
+        const int64_t n = n_wave + slot * 64 + lane;
+        r_node[slot] = 0;
+        r_u[slot] = 0.f;
+        r_v[slot] = 0.f;
+        if (n < a.B && k < k_end) {
+            const int64_t o = (int64_t)k * a.B + n;
+            r_node[slot] = a.rec_node[o];
+            r_u[slot] = a.rec_u[o];
+            r_v[slot] = a.rec_v[o];
+        }
+    };
+
+    // columns past the end of a ragged output tile are never loaded: the staged fill writes
+    // zeros there; s_invh must be in place before the first set
+    SlabFill<CT, WAVES, LPS> fill;
+    if (k_begin < k_end) {
+#pragma unroll
+        for (int s = 0; s < SETS; ++s) fetch_record(s, k_begin);
+        fill.template issue<0>(sa, slab0, k_begin, jt, wave, lane);
+        fill.template commit<0>(sa, slab0, wave, lane);
+        fill.template issue<1>(sa, slab0, k_begin, jt, wave, lane);
+        fill.template commit<1>(sa, slab0, wave, lane);
+    }
+    const int lane_bytes = sub * 16;
+    // where this lane's two results of a set go: samples 4 grp + (sub & 1) and + 2 more, input
+    // 2k (lanes 0-1 of the quad) or 2k + 1 (lanes 2-3)
+    const int64_t n_lane = n_wave + grp * LPS + (sub & 1);
+    float *gx_lane = a.gx + (int64_t)(sub >> 1) * a.B + n_lane;
+
+    for (int k = k_begin; k < k_end; ++k) {
+        const float *slab = ((k - k_begin) & 1) ? slab1 : slab0;
+        float *slab_next = ((k - k_begin) & 1) ? slab0 : slab1;
+        __syncthreads();
+        if (k + 1 < k_end) fill.template issue<0>(sa, slab_next, k + 1, jt, wave, lane);
+
+        constexpr int kNear = 1;
+        Corners ring[kNear + 1];
+        int off_cur = r_node[0] * kNarrowRowBytes, off_nxt = 0;
+        float b_lo = 0.f, b_hi = 0.f, a_lo = 0.f, a_hi = 0.f;
+        float stash_a = 0.f, stash_b = 0.f;
+        load_corners_quad<0>(ring[0], slab, off_cur, lane_bytes, a.W);
+        static_for(std::make_integer_sequence<int, STEPS>{}, [&](auto fc) {
+            constexpr int F = decltype(fc)::value;
+            constexpr int set = F / LPS, t = F % LPS;
+            if constexpr (t == 0) {
+                if constexpr (set == SETS / 2) {
+                    if (k + 1 < k_end) {
+                        fill.template commit<0>(sa, slab_next, wave, lane);
+                        fill.template issue<1>(sa, slab_next, k + 1, jt, wave, lane);
+                    }
+                }
+                const int node = r_node[set];
+                const int i1 = (int)(((float)node + 0.5f) * inv_w);  // node / W, exact for these sizes
+                const float rh1 = s_invh[i1], rh2 = s_invh[node - i1 * a.W];
+                const float u = r_u[set], v = r_v[set];
+                b_lo = (1.0f - v) * rh1;
+                b_hi = v * rh1;
+                a_lo = (1.0f - u) * rh2;
+                a_hi = u * rh2;
+                if constexpr (set > 0) off_cur = off_nxt;
+                if constexpr (set + 1 < SETS) off_nxt = r_node[set + 1] * kNarrowRowBytes;
+                asm volatile("s_nop 1" : "+v"(b_lo), "+v"(b_hi), "+v"(a_lo), "+v"(a_hi), "+v"(off_cur), "+v"(off_nxt));
+                fetch_record(set, k + 1);
+            }
+            if constexpr (F + kNear < STEPS) {
+                constexpr int F2 = F + kNear;
+                load_corners_quad<F2 % LPS>(ring[F2 % (kNear + 1)], slab, (F2 / LPS == set) ? off_cur : off_nxt,
+                                            lane_bytes, a.W);
+            }
+            const float v = grad_step_quad<t>(gyr[F], ring[F % (kNear + 1)], b_lo, b_hi, a_lo, a_hi, upper);
+            if ((sub & 1) == (t & 1)) {
+                if constexpr (t < 2) stash_a = v; else stash_b = v;
+            }
+            if constexpr (t == LPS - 1) {
+                const int64_t n = n_lane + set * 64;
+                float *dst = gx_lane + (int64_t)(2 * k) * a.B + set * 64;
+                if (n < a.B) unsafeAtomicAdd(dst, stash_a);
+                if (n + 2 < a.B) unsafeAtomicAdd(dst + 2, stash_b);
+            }
+        });
+        if (k + 1 < k_end) fill.template commit<1>(sa, slab_next, wave, lane);
+    }
+}
+
 }  // namespace
 
 size_t slab_forward_lds_bytes(const LayerShape &s)
@@ -996,7 +1168,7 @@ void launch_forward_slab(const LayerShape &s, const void *coef, float *y, const 
 
 namespace lmkan {
 
-bool slab_backward_input_shape_ok(const LayerShape &s) { return slab_wide_ok(s); }
+bool slab_backward_input_shape_ok(const LayerShape &s) { return slab_wide_ok(s) || slab_narrow_ok(s); }
 
 bool slab_backward_input_applicable(const LayerShape &s, const void *coef, const float *gy, const float *gx)
 {
@@ -1016,15 +1188,21 @@ void launch_backward_input_slab(const LayerShape &s, const GridTab &tab, const v
     constexpr int WAVES = 8, SETS = 2;
     constexpr int kTileB = WAVES * SETS * 64;
     typedef void (*Kernel)(GradInArgs);
-    const Kernel kernels[3] = {backward_input_slab_kernel<float, WAVES, SETS>,
+    const bool narrow = !slab_wide_ok(s);
+    constexpr int kNarrowSets = 8;
+    const Kernel kernels[6] = {backward_input_slab_kernel<float, WAVES, SETS>,
                                backward_input_slab_kernel<_Float16, WAVES, SETS>,
-                               backward_input_slab_kernel<bf16_t, WAVES, SETS>};
-    const Kernel kernel = kernels[s.dtype];
-    static bool attr_set[3] = {false, false, false};
-    if (!attr_set[s.dtype]) {
+                               backward_input_slab_kernel<bf16_t, WAVES, SETS>,
+                               nullptr,
+                               backward_input_slab_narrow_kernel<_Float16, WAVES, kNarrowSets>,
+                               backward_input_slab_narrow_kernel<bf16_t, WAVES, kNarrowSets>};
+    const int which = s.dtype + (narrow ? 3 : 0);
+    const Kernel kernel = kernels[which];
+    static bool attr_set[6] = {false, false, false, false, false, false};
+    if (!attr_set[which]) {
         (void)hipFuncSetAttribute(reinterpret_cast<const void *>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize,
                                   160 * 1024);
-        attr_set[s.dtype] = true;
+        attr_set[which] = true;
     }
     const size_t n = (size_t)s.pairs() * (size_t)s.batch;
     GradInArgs a;
@@ -1044,15 +1222,17 @@ void launch_backward_input_slab(const LayerShape &s, const GridTab &tab, const v
     a.nodes = s.nodes();
     a.col_limit = s.layout == LMKAN_LAYOUT_PACKED ? s.out_tiles() * kTile : s.n_out;
     a.packed = s.layout == LMKAN_LAYOUT_PACKED;
-    a.n_btiles = (int)((s.batch + kTileB - 1) / kTileB);
-    a.n_jt = s.out_tiles();
+    const int tile_b = narrow ? WAVES * kNarrowSets * 64 : kTileB;
+    a.n_btiles = (int)((s.batch + tile_b - 1) / tile_b);
+    a.n_jt = narrow ? (s.n_out + kNarrowTile - 1) / kNarrowTile : s.out_tiles();
     const int tiles = a.n_btiles * a.n_jt;
     int split = 1;
     while (tiles * split < 256 && a.K / (split * 2) >= 32) split *= 2;
     a.n_split = split;
     a.pairs_per_split = (a.K + split - 1) / split;
     launch_fill_zero(a.gx, (size_t)s.batch * s.n_in, stream);
-    kernel<<<tiles * split, WAVES * 64, slab_forward_lds_bytes(s) + LMKAN_MAX_GRID * sizeof(float), stream>>>(a);
+    const size_t slabs = narrow ? (size_t)2 * s.nodes() * kNarrowRowBytes : slab_forward_lds_bytes(s);
+    kernel<<<tiles * split, WAVES * 64, slabs + LMKAN_MAX_GRID * sizeof(float), stream>>>(a);
     const dim3 tgrid((unsigned)((s.batch + 63) / 64), (unsigned)((s.n_in + 63) / 64));
     transpose_kernel<<<tgrid, 256, 0, stream>>>(a.gx, gx, s.batch, s.n_in);
 }
