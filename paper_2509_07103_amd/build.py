@@ -14,10 +14,14 @@ LIB = os.path.join(HERE, "liblmkan.so")
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 
 # Packed float32 VALU instructions are switched off: some of their forms have given
-# silently wrong results on the target machines.
+# silently wrong results on the target machines.  MFMA accumulators are kept in ordinary
+# vector registers (gfx950 allows it): the coefficient-gradient kernel reads them with
+# vector instructions at the end of every cell, and copies out of the accumulation
+# registers would cost as much as the combine itself.
 FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+    "-mllvm", "-amdgpu-mfma-vgpr-form",
     "-munsafe-fp-atomics", "-Wall", "-Wno-unused-command-line-argument",
     "-I", os.path.join(ROOT, "include"), "-I", CSRC,
 ]

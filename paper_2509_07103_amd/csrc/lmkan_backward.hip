@@ -254,13 +254,15 @@ struct CoefGradArgs {
 // the four blocks of a group is taken from the group's block SUB (broadcast size 4 blocks),
 // the B operand is the lane's own gy value, and row q of the result lands in register q of
 // the same lane.
-template <int SUB>
+template <int SUB, bool FRESH>
 __device__ __forceinline__ void chunk_fma(f4v (&acc)[4], float w, const f4v &g)
 {
-    acc[0] = __builtin_amdgcn_mfma_f32_4x4x1f32(w, g.x, acc[0], 2, SUB, 0);
-    acc[1] = __builtin_amdgcn_mfma_f32_4x4x1f32(w, g.y, acc[1], 2, SUB, 0);
-    acc[2] = __builtin_amdgcn_mfma_f32_4x4x1f32(w, g.z, acc[2], 2, SUB, 0);
-    acc[3] = __builtin_amdgcn_mfma_f32_4x4x1f32(w, g.w, acc[3], 2, SUB, 0);
+    // the first chunk of a cell starts from zero instead of clearing the accumulators
+    const f4v zero = {0.f, 0.f, 0.f, 0.f};
+    acc[0] = __builtin_amdgcn_mfma_f32_4x4x1f32(w, g.x, FRESH ? zero : acc[0], 2, SUB, 0);
+    acc[1] = __builtin_amdgcn_mfma_f32_4x4x1f32(w, g.y, FRESH ? zero : acc[1], 2, SUB, 0);
+    acc[2] = __builtin_amdgcn_mfma_f32_4x4x1f32(w, g.z, FRESH ? zero : acc[2], 2, SUB, 0);
+    acc[3] = __builtin_amdgcn_mfma_f32_4x4x1f32(w, g.w, FRESH ? zero : acc[3], 2, SUB, 0);
 }
 
 // The four groups' partial sums acc[output i][corner q] -> f[i] of group r = total of corner r,
@@ -383,8 +385,6 @@ __global__ __launch_bounds__(64) void backward_coef_stream_kernel(CoefGradArgs a
         v.z += f[2];
         v.w += f[3];
         *p = v;
-#pragma unroll
-        for (int i = 0; i < 4; ++i) acc[i] = f4v{0.f, 0.f, 0.f, 0.f};
     };
     // table rows below `upto` can receive nothing more: write them and recycle their buffers;
     // four table entries per store instruction, group g takes b = 4 i + g
@@ -455,8 +455,10 @@ __global__ __launch_bounds__(64) void backward_coef_stream_kernel(CoefGradArgs a
                     if (cur_cell >= 0) flush();
                     retire_rows(cell_cur >> 8);
                     cur_cell = cell_cur;
+                    chunk_fma<P % kPerW, true>(acc, wq[P / kPerW], gq[P % kDepth]);
+                } else {
+                    chunk_fma<P % kPerW, false>(acc, wq[P / kPerW], gq[P % kDepth]);
                 }
-                chunk_fma<P % kPerW>(acc, wq[P / kPerW], gq[P % kDepth]);
                 gq[P % kDepth] = load_gy(std::integral_constant<int, (P + kDepth) % kUnroll>{},
                                          P + kDepth < kUnroll ? n_now : n_nxt);
                 if constexpr (P % kPerW == kPerW - 1) wq[P / kPerW] = load_w(c + kUnroll + (P / kPerW) * kPerW);
