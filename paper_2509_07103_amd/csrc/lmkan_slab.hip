@@ -289,30 +289,35 @@ __device__ __forceinline__ void fma_corners(float *acc, const Corners &c, float 
     fmac_row_bcast<S>(acc[3], w11, c.c11.w);
 }
 
-// Software pipeline over the SETS * 16 steps of one pair: the rows of step T + kAhead are
+// Software pipeline over the SETS * 16 steps of one pair: the rows of step T + AHEAD are
 // requested from LDS before the multiply-adds of step T are issued.
-constexpr int kAhead = 2;
 
-template <int T, int END, int TOTAL>
-__device__ __forceinline__ void slab_pipeline(float *acc, Corners (&ring)[kAhead + 1], const float *slab,
+template <int T, int END, int TOTAL, int AHEAD>
+__device__ __forceinline__ void slab_pipeline(float *acc, Corners (&ring)[AHEAD + 1], const float *slab,
                                               const int *off, const float *w00, const float *w10,
                                               const float *w01, const float *w11, int lane_bytes, int W)
 {
     if constexpr (T < END) {
-        if constexpr (T + kAhead < TOTAL)
-            load_corners<(T + kAhead) % 16>(ring[(T + kAhead) % (kAhead + 1)], slab, off[(T + kAhead) / 16],
-                                            lane_bytes, W);
-        fma_corners<T % 16>(acc + 4 * T, ring[T % (kAhead + 1)], w00[T / 16], w10[T / 16], w01[T / 16],
+        if constexpr (T + AHEAD < TOTAL)
+            load_corners<(T + AHEAD) % 16>(ring[(T + AHEAD) % (AHEAD + 1)], slab, off[(T + AHEAD) / 16],
+                                           lane_bytes, W);
+        fma_corners<T % 16>(acc + 4 * T, ring[T % (AHEAD + 1)], w00[T / 16], w10[T / 16], w01[T / 16],
                             w11[T / 16]);
-        slab_pipeline<T + 1, END, TOTAL>(acc, ring, slab, off, w00, w10, w01, w11, lane_bytes, W);
+        slab_pipeline<T + 1, END, TOTAL, AHEAD>(acc, ring, slab, off, w00, w10, w01, w11, lane_bytes, W);
     }
 }
 
 // WAVES waves per workgroup, SETS x 64 samples per wave.
 // Two waves per SIMD by construction (one workgroup per CU); telling the compiler lets
 // it spend registers on keeping several LDS reads in flight.
-template <typename CT, int WAVES, int SETS>
-__global__ __launch_bounds__(WAVES * 64) __attribute__((amdgpu_waves_per_eu(2, 2))) void forward_slab_kernel(SlabArgs a)
+// WAVES / 4 waves per SIMD by construction (one workgroup per CU); telling the compiler lets
+// it spend exactly that share of the registers.  The multiply-add rate of a SIMD grows with
+// the number of waves it can pick from (measured: DPP multiply-adds 49 per clock and CU with
+// two waves per SIMD, 60 with four), hence 16 waves of 64 samples rather than 8 of 128 when
+// the registers allow.
+template <typename CT, int WAVES, int SETS, int AHEAD>
+__global__ __launch_bounds__(WAVES * 64) __attribute__((amdgpu_waves_per_eu(WAVES / 4, WAVES / 4))) void forward_slab_kernel(
+    SlabArgs a)
 {
     extern __shared__ __align__(16) float smem[];
     const int lane = threadIdx.x & 63;
@@ -400,20 +405,17 @@ __global__ __launch_bounds__(WAVES * 64) __attribute__((amdgpu_waves_per_eu(2, 2
             // VALU results must not be read through DPP in the next two issue slots
             asm volatile("s_nop 1" : "+v"(w00[s]), "+v"(w10[s]), "+v"(w01[s]), "+v"(w11[s]));
         }
-        Corners ring[kAhead + 1];
-#pragma unroll
-        for (int t = 0; t < kAhead; ++t) {
-            if (t == 0) load_corners<0>(ring[0], slab, off[0], lane_bytes, a.W);
-            if (t == 1) load_corners<1>(ring[1], slab, off[0], lane_bytes, a.W);
-        }
+        Corners ring[AHEAD + 1];
+        load_corners<0>(ring[0], slab, off[0], lane_bytes, a.W);
+        if constexpr (AHEAD > 1) load_corners<1>(ring[1], slab, off[0], lane_bytes, a.W);
         // the steps of the pair in two halves; a 16-bit table is staged half a slab at a time
         constexpr int kHalf = SETS * 8;
-        slab_pipeline<0, kHalf, SETS * 16>(acc, ring, slab, off, w00, w10, w01, w11, lane_bytes, a.W);
+        slab_pipeline<0, kHalf, SETS * 16, AHEAD>(acc, ring, slab, off, w00, w10, w01, w11, lane_bytes, a.W);
         if (k + 1 < k_end) {
             fill.template commit<0>(a, slab_next, wave, lane);
             fill.template issue<1>(a, slab_next, k + 1, jt, wave, lane);
         }
-        slab_pipeline<kHalf, SETS * 16, SETS * 16>(acc, ring, slab, off, w00, w10, w01, w11, lane_bytes, a.W);
+        slab_pipeline<kHalf, SETS * 16, SETS * 16, AHEAD>(acc, ring, slab, off, w00, w10, w01, w11, lane_bytes, a.W);
         if (k + 1 < k_end) fill.template commit<1>(a, slab_next, wave, lane);
     }
 
@@ -535,8 +537,8 @@ __device__ __forceinline__ float grad_step(const float4 g, const Corners &c, con
     return v;
 }
 
-template <typename CT, int WAVES, int SETS>
-__global__ __launch_bounds__(WAVES * 64) __attribute__((amdgpu_waves_per_eu(2, 2))) void backward_input_slab_kernel(
+template <typename CT, int WAVES, int SETS, int AHEAD>
+__global__ __launch_bounds__(WAVES * 64) __attribute__((amdgpu_waves_per_eu(WAVES / 4, WAVES / 4))) void backward_input_slab_kernel(
     GradInArgs a)
 {
     extern __shared__ __align__(16) float smem[];  // two slab buffers, then 1/h of the grid
@@ -641,22 +643,22 @@ __global__ __launch_bounds__(WAVES * 64) __attribute__((amdgpu_waves_per_eu(2, 2
         for (int s = 0; s < SETS; ++s)
             asm volatile("s_nop 1" : "+v"(rec[s].b_lo), "+v"(rec[s].b_hi), "+v"(rec[s].a_lo), "+v"(rec[s].a_hi));
 
-        Corners ring[kAhead + 1];
+        Corners ring[AHEAD + 1];
         load_corners<0>(ring[0], slab, rec[0].off, lane_bytes, a.W);
-        load_corners<1>(ring[1], slab, rec[0].off, lane_bytes, a.W);
+        if constexpr (AHEAD > 1) load_corners<1>(ring[1], slab, rec[0].off, lane_bytes, a.W);
         float stash = 0.0f;
         static_for(std::make_integer_sequence<int, TOTAL>{}, [&](auto tc) {
             constexpr int T = decltype(tc)::value;
-            if constexpr (T + kAhead < TOTAL)
-                load_corners<(T + kAhead) % 16>(ring[(T + kAhead) % (kAhead + 1)], slab,
-                                                rec[(T + kAhead) / 16].off, lane_bytes, a.W);
+            if constexpr (T + AHEAD < TOTAL)
+                load_corners<(T + AHEAD) % 16>(ring[(T + AHEAD) % (AHEAD + 1)], slab,
+                                               rec[(T + AHEAD) / 16].off, lane_bytes, a.W);
             if constexpr (T == TOTAL / 2) {
                 if (k + 1 < k_end) {
                     fill.template commit<0>(sa, slab_next, wave, lane);
                     fill.template issue<1>(sa, slab_next, k + 1, jt, wave, lane);
                 }
             }
-            const float v = grad_step<T % 16>(gyr[T], ring[T % (kAhead + 1)], rec[T / 16], upper);
+            const float v = grad_step<T % 16>(gyr[T], ring[T % (AHEAD + 1)], rec[T / 16], upper);
             if ((l16 & 7) == (T & 7)) stash = v;
             if constexpr ((T & 7) == 7) {
                 const int64_t n = n_lane + (T / 16) * 64 + ((T % 16) & ~7);
@@ -1123,12 +1125,17 @@ void launch_forward_slab(const LayerShape &s, const void *coef, float *y, const 
         launch_forward_slab_narrow(s, coef, y, records, stream);
         return;
     }
-    constexpr int WAVES = 8, SETS = 2;
-    constexpr int kTileB = WAVES * SETS * 64;
+    // 1024 samples per workgroup either way: 16 waves x 64 samples for float32 tables, 8 x 128 for
+    // 16-bit tables (their staging registers do not fit the smaller register share)
+    constexpr int kTileB = 1024;
     typedef void (*Kernel)(SlabArgs);
-    const Kernel kernels[3] = {forward_slab_kernel<float, WAVES, SETS>, forward_slab_kernel<_Float16, WAVES, SETS>,
-                               forward_slab_kernel<bf16_t, WAVES, SETS>};
+#ifndef LMKAN_FWD_AHEAD
+#define LMKAN_FWD_AHEAD 1
+#endif
+    const Kernel kernels[3] = {forward_slab_kernel<float, 16, 1, LMKAN_FWD_AHEAD>, forward_slab_kernel<_Float16, 8, 2, 2>,
+                               forward_slab_kernel<bf16_t, 8, 2, 2>};
     const Kernel kernel = kernels[s.dtype];
+    const int waves = s.dtype == LMKAN_F32 ? 16 : 8;
     static bool attr_set[3] = {false, false, false};
     if (!attr_set[s.dtype]) {
         (void)hipFuncSetAttribute(reinterpret_cast<const void *>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize,
@@ -1161,7 +1168,7 @@ void launch_forward_slab(const LayerShape &s, const void *coef, float *y, const 
     a.pairs_per_split = (a.K + split - 1) / split;
     a.atomic_out = split > 1;
     if (a.atomic_out) launch_fill_zero(y, (size_t)s.batch * s.n_out, stream);
-    kernel<<<tiles * split, WAVES * 64, slab_forward_lds_bytes(s), stream>>>(a);
+    kernel<<<tiles * split, waves * 64, slab_forward_lds_bytes(s), stream>>>(a);
 }
 
 }  // namespace lmkan
@@ -1190,9 +1197,13 @@ void launch_backward_input_slab(const LayerShape &s, const GridTab &tab, const v
     typedef void (*Kernel)(GradInArgs);
     const bool narrow = !slab_wide_ok(s);
     constexpr int kNarrowSets = 8;
-    const Kernel kernels[6] = {backward_input_slab_kernel<float, WAVES, SETS>,
-                               backward_input_slab_kernel<_Float16, WAVES, SETS>,
-                               backward_input_slab_kernel<bf16_t, WAVES, SETS>,
+#ifndef LMKAN_GX_WAVES
+#define LMKAN_GX_WAVES 16
+#define LMKAN_GX_AHEAD 1
+#endif
+    const Kernel kernels[6] = {backward_input_slab_kernel<float, LMKAN_GX_WAVES, 16 / LMKAN_GX_WAVES, LMKAN_GX_AHEAD>,
+                               backward_input_slab_kernel<_Float16, WAVES, SETS, 2>,
+                               backward_input_slab_kernel<bf16_t, WAVES, SETS, 2>,
                                nullptr,
                                backward_input_slab_narrow_kernel<_Float16, WAVES, kNarrowSets>,
                                backward_input_slab_narrow_kernel<bf16_t, WAVES, kNarrowSets>};
@@ -1232,7 +1243,8 @@ void launch_backward_input_slab(const LayerShape &s, const GridTab &tab, const v
     a.pairs_per_split = (a.K + split - 1) / split;
     launch_fill_zero(a.gx, (size_t)s.batch * s.n_in, stream);
     const size_t slabs = narrow ? (size_t)2 * s.nodes() * kNarrowRowBytes : slab_forward_lds_bytes(s);
-    kernel<<<tiles * split, WAVES * 64, slabs + LMKAN_MAX_GRID * sizeof(float), stream>>>(a);
+    const int waves = which == 0 ? LMKAN_GX_WAVES : WAVES;
+    kernel<<<tiles * split, waves * 64, slabs + LMKAN_MAX_GRID * sizeof(float), stream>>>(a);
     const dim3 tgrid((unsigned)((s.batch + 63) / 64), (unsigned)((s.n_in + 63) / 64));
     transpose_kernel<<<tgrid, 256, 0, stream>>>(a.gx, gx, s.batch, s.n_in);
 }
