@@ -255,16 +255,27 @@ struct Corners {
     float4 c00, c01, c10, c11;
 };
 
-template <int S>
-__device__ __forceinline__ void load_corners(Corners &c, const float *slab, int off_bytes, int lane_bytes,
-                                             int W)
+// lane_base = LDS address of the slab + this lane's column bytes; the broadcast of the
+// sample's row offset folds into the one integer add that forms the address.  W_CT is G + 1
+// when it is known at compile time (the second row pair then sits at an immediate offset),
+// 0 otherwise.
+typedef float f4raw __attribute__((ext_vector_type(4)));
+
+__device__ __forceinline__ float4 lds_load4(unsigned addr)
 {
-    const float *rowp =
-        reinterpret_cast<const float *>(reinterpret_cast<const char *>(slab) + row_bcast<S>(off_bytes) + lane_bytes);
-    c.c00 = *reinterpret_cast<const float4 *>(rowp);
-    c.c01 = *reinterpret_cast<const float4 *>(rowp + kTile);
-    c.c10 = *reinterpret_cast<const float4 *>(rowp + W * kTile);
-    c.c11 = *reinterpret_cast<const float4 *>(rowp + W * kTile + kTile);
+    const f4raw v = *reinterpret_cast<__attribute__((address_space(3))) const f4raw *>(addr);
+    return make_float4(v.x, v.y, v.z, v.w);
+}
+
+template <int S, int W_CT>
+__device__ __forceinline__ void load_corners(Corners &c, int lane_base, int off_bytes, int W)
+{
+    const unsigned addr = (unsigned)(row_bcast<S>(off_bytes) + lane_base);
+    const int w = W_CT > 0 ? W_CT : W;
+    c.c00 = lds_load4(addr);
+    c.c01 = lds_load4(addr + kRowBytes);
+    c.c10 = lds_load4(addr + w * kRowBytes);
+    c.c11 = lds_load4(addr + w * kRowBytes + kRowBytes);
 }
 
 template <int S>
@@ -292,18 +303,17 @@ __device__ __forceinline__ void fma_corners(float *acc, const Corners &c, float 
 // Software pipeline over the SETS * 16 steps of one pair: the rows of step T + AHEAD are
 // requested from LDS before the multiply-adds of step T are issued.
 
-template <int T, int END, int TOTAL, int AHEAD>
-__device__ __forceinline__ void slab_pipeline(float *acc, Corners (&ring)[AHEAD + 1], const float *slab,
+template <int T, int END, int TOTAL, int AHEAD, int W_CT>
+__device__ __forceinline__ void slab_pipeline(float *acc, Corners (&ring)[AHEAD + 1], int lane_base,
                                               const int *off, const float *w00, const float *w10,
-                                              const float *w01, const float *w11, int lane_bytes, int W)
+                                              const float *w01, const float *w11, int W)
 {
     if constexpr (T < END) {
         if constexpr (T + AHEAD < TOTAL)
-            load_corners<(T + AHEAD) % 16>(ring[(T + AHEAD) % (AHEAD + 1)], slab, off[(T + AHEAD) / 16],
-                                           lane_bytes, W);
+            load_corners<(T + AHEAD) % 16, W_CT>(ring[(T + AHEAD) % (AHEAD + 1)], lane_base, off[(T + AHEAD) / 16], W);
         fma_corners<T % 16>(acc + 4 * T, ring[T % (AHEAD + 1)], w00[T / 16], w10[T / 16], w01[T / 16],
                             w11[T / 16]);
-        slab_pipeline<T + 1, END, TOTAL, AHEAD>(acc, ring, slab, off, w00, w10, w01, w11, lane_bytes, W);
+        slab_pipeline<T + 1, END, TOTAL, AHEAD, W_CT>(acc, ring, lane_base, off, w00, w10, w01, w11, W);
     }
 }
 
@@ -315,7 +325,7 @@ __device__ __forceinline__ void slab_pipeline(float *acc, Corners (&ring)[AHEAD 
 // the number of waves it can pick from (measured: DPP multiply-adds 49 per clock and CU with
 // two waves per SIMD, 60 with four), hence 16 waves of 64 samples rather than 8 of 128 when
 // the registers allow.
-template <typename CT, int WAVES, int SETS, int AHEAD>
+template <typename CT, int WAVES, int SETS, int AHEAD, int W_CT>
 __global__ __launch_bounds__(WAVES * 64) __attribute__((amdgpu_waves_per_eu(WAVES / 4, WAVES / 4))) void forward_slab_kernel(
     SlabArgs a)
 {
@@ -406,16 +416,17 @@ __global__ __launch_bounds__(WAVES * 64) __attribute__((amdgpu_waves_per_eu(WAVE
             asm volatile("s_nop 1" : "+v"(w00[s]), "+v"(w10[s]), "+v"(w01[s]), "+v"(w11[s]));
         }
         Corners ring[AHEAD + 1];
-        load_corners<0>(ring[0], slab, off[0], lane_bytes, a.W);
-        if constexpr (AHEAD > 1) load_corners<1>(ring[1], slab, off[0], lane_bytes, a.W);
+        const int lane_base = (int)lds_address(slab) + lane_bytes;
+        load_corners<0, W_CT>(ring[0], lane_base, off[0], a.W);
+        if constexpr (AHEAD > 1) load_corners<1, W_CT>(ring[1], lane_base, off[0], a.W);
         // the steps of the pair in two halves; a 16-bit table is staged half a slab at a time
         constexpr int kHalf = SETS * 8;
-        slab_pipeline<0, kHalf, SETS * 16, AHEAD>(acc, ring, slab, off, w00, w10, w01, w11, lane_bytes, a.W);
+        slab_pipeline<0, kHalf, SETS * 16, AHEAD, W_CT>(acc, ring, lane_base, off, w00, w10, w01, w11, a.W);
         if (k + 1 < k_end) {
             fill.template commit<0>(a, slab_next, wave, lane);
             fill.template issue<1>(a, slab_next, k + 1, jt, wave, lane);
         }
-        slab_pipeline<kHalf, SETS * 16, SETS * 16, AHEAD>(acc, ring, slab, off, w00, w10, w01, w11, lane_bytes, a.W);
+        slab_pipeline<kHalf, SETS * 16, SETS * 16, AHEAD, W_CT>(acc, ring, lane_base, off, w00, w10, w01, w11, a.W);
         if (k + 1 < k_end) fill.template commit<1>(a, slab_next, wave, lane);
     }
 
@@ -537,7 +548,7 @@ __device__ __forceinline__ float grad_step(const float4 g, const Corners &c, con
     return v;
 }
 
-template <typename CT, int WAVES, int SETS, int AHEAD>
+template <typename CT, int WAVES, int SETS, int AHEAD, int W_CT>
 __global__ __launch_bounds__(WAVES * 64) __attribute__((amdgpu_waves_per_eu(WAVES / 4, WAVES / 4))) void backward_input_slab_kernel(
     GradInArgs a)
 {
@@ -644,14 +655,15 @@ __global__ __launch_bounds__(WAVES * 64) __attribute__((amdgpu_waves_per_eu(WAVE
             asm volatile("s_nop 1" : "+v"(rec[s].b_lo), "+v"(rec[s].b_hi), "+v"(rec[s].a_lo), "+v"(rec[s].a_hi));
 
         Corners ring[AHEAD + 1];
-        load_corners<0>(ring[0], slab, rec[0].off, lane_bytes, a.W);
-        if constexpr (AHEAD > 1) load_corners<1>(ring[1], slab, rec[0].off, lane_bytes, a.W);
+        const int lane_base = (int)lds_address(slab) + lane_bytes;
+        load_corners<0, W_CT>(ring[0], lane_base, rec[0].off, a.W);
+        if constexpr (AHEAD > 1) load_corners<1, W_CT>(ring[1], lane_base, rec[0].off, a.W);
         float stash = 0.0f;
         static_for(std::make_integer_sequence<int, TOTAL>{}, [&](auto tc) {
             constexpr int T = decltype(tc)::value;
             if constexpr (T + AHEAD < TOTAL)
-                load_corners<(T + AHEAD) % 16>(ring[(T + AHEAD) % (AHEAD + 1)], slab,
-                                               rec[(T + AHEAD) / 16].off, lane_bytes, a.W);
+                load_corners<(T + AHEAD) % 16, W_CT>(ring[(T + AHEAD) % (AHEAD + 1)], lane_base,
+                                                     rec[(T + AHEAD) / 16].off, a.W);
             if constexpr (T == TOTAL / 2) {
                 if (k + 1 < k_end) {
                     fill.template commit<0>(sa, slab_next, wave, lane);
@@ -1132,15 +1144,19 @@ void launch_forward_slab(const LayerShape &s, const void *coef, float *y, const 
 #ifndef LMKAN_FWD_AHEAD
 #define LMKAN_FWD_AHEAD 1
 #endif
-    const Kernel kernels[3] = {forward_slab_kernel<float, 16, 1, LMKAN_FWD_AHEAD>, forward_slab_kernel<_Float16, 8, 2, 2>,
-                               forward_slab_kernel<bf16_t, 8, 2, 2>};
-    const Kernel kernel = kernels[s.dtype];
+    // G = 16 (the usual grid) gets a kernel with the row stride folded into the LDS offsets
+    const Kernel kernels[3] = {forward_slab_kernel<float, 16, 1, LMKAN_FWD_AHEAD, 0>,
+                               forward_slab_kernel<_Float16, 8, 2, 2, 0>, forward_slab_kernel<bf16_t, 8, 2, 2, 0>};
+    const Kernel kernels17[3] = {forward_slab_kernel<float, 16, 1, LMKAN_FWD_AHEAD, 17>,
+                                 forward_slab_kernel<_Float16, 8, 2, 2, 17>, forward_slab_kernel<bf16_t, 8, 2, 2, 17>};
+    const Kernel kernel = s.G == 16 ? kernels17[s.dtype] : kernels[s.dtype];
     const int waves = s.dtype == LMKAN_F32 ? 16 : 8;
-    static bool attr_set[3] = {false, false, false};
-    if (!attr_set[s.dtype]) {
+    static bool attr_set[6] = {false, false, false, false, false, false};
+    const int slot = s.dtype + (s.G == 16 ? 3 : 0);
+    if (!attr_set[slot]) {
         (void)hipFuncSetAttribute(reinterpret_cast<const void *>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize,
                                   160 * 1024);
-        attr_set[s.dtype] = true;
+        attr_set[slot] = true;
     }
     const size_t n = (size_t)s.pairs() * (size_t)s.batch;
     SlabArgs a;
@@ -1201,15 +1217,18 @@ void launch_backward_input_slab(const LayerShape &s, const GridTab &tab, const v
 #define LMKAN_GX_WAVES 16
 #define LMKAN_GX_AHEAD 1
 #endif
-    const Kernel kernels[6] = {backward_input_slab_kernel<float, LMKAN_GX_WAVES, 16 / LMKAN_GX_WAVES, LMKAN_GX_AHEAD>,
-                               backward_input_slab_kernel<_Float16, WAVES, SETS, 2>,
-                               backward_input_slab_kernel<bf16_t, WAVES, SETS, 2>,
+    const Kernel kernels[9] = {backward_input_slab_kernel<float, LMKAN_GX_WAVES, 16 / LMKAN_GX_WAVES, LMKAN_GX_AHEAD, 0>,
+                               backward_input_slab_kernel<_Float16, WAVES, SETS, 2, 0>,
+                               backward_input_slab_kernel<bf16_t, WAVES, SETS, 2, 0>,
                                nullptr,
                                backward_input_slab_narrow_kernel<_Float16, WAVES, kNarrowSets>,
-                               backward_input_slab_narrow_kernel<bf16_t, WAVES, kNarrowSets>};
-    const int which = s.dtype + (narrow ? 3 : 0);
+                               backward_input_slab_narrow_kernel<bf16_t, WAVES, kNarrowSets>,
+                               backward_input_slab_kernel<float, LMKAN_GX_WAVES, 16 / LMKAN_GX_WAVES, LMKAN_GX_AHEAD, 17>,
+                               backward_input_slab_kernel<_Float16, WAVES, SETS, 2, 17>,
+                               backward_input_slab_kernel<bf16_t, WAVES, SETS, 2, 17>};
+    const int which = s.dtype + (narrow ? 3 : (s.G == 16 ? 6 : 0));
     const Kernel kernel = kernels[which];
-    static bool attr_set[6] = {false, false, false, false, false, false};
+    static bool attr_set[9] = {false, false, false, false, false, false, false, false, false};
     if (!attr_set[which]) {
         (void)hipFuncSetAttribute(reinterpret_cast<const void *>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize,
                                   160 * 1024);
@@ -1243,7 +1262,7 @@ void launch_backward_input_slab(const LayerShape &s, const GridTab &tab, const v
     a.pairs_per_split = (a.K + split - 1) / split;
     launch_fill_zero(a.gx, (size_t)s.batch * s.n_in, stream);
     const size_t slabs = narrow ? (size_t)2 * s.nodes() * kNarrowRowBytes : slab_forward_lds_bytes(s);
-    const int waves = which == 0 ? LMKAN_GX_WAVES : WAVES;
+    const int waves = s.dtype == LMKAN_F32 ? LMKAN_GX_WAVES : WAVES;
     kernel<<<tiles * split, waves * 64, slabs + LMKAN_MAX_GRID * sizeof(float), stream>>>(a);
     const dim3 tgrid((unsigned)((s.batch + 63) / 64), (unsigned)((s.n_in + 63) / 64));
     transpose_kernel<<<tgrid, 256, 0, stream>>>(a.gx, gx, s.batch, s.n_in);
