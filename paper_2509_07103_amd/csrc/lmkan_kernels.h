@@ -52,6 +52,13 @@ size_t slab_backward_input_scratch_bytes(const LayerShape &s);
 void launch_backward_input_slab(const LayerShape &s, const GridTab &tab, const void *coef, const float *gy,
                                 float *gx, const void *records, void *scratch, hipStream_t stream);
 
+// float16 tables kept as float16 in LDS (lmkan_slab_f16.hip); reached through the two slab
+// launchers above when slab_f16_native_ok().  gx_scratch is the zero-filled transposed scratch.
+bool slab_f16_native_ok(const LayerShape &s);
+void launch_forward_slab_f16(const LayerShape &s, const void *coef, float *y, const void *records, hipStream_t stream);
+void launch_backward_input_slab_f16(const LayerShape &s, const GridTab &tab, const void *coef, const float *gy,
+                                    float *gx_scratch, const void *records, hipStream_t stream);
+
 // Coefficient gradient by cell-sorted samples (lmkan_backward.hip).  `records` is the output
 // of launch_preamble_records; `sorted` is scratch of sorted_records_bytes().  Needs n_out to be a
 // multiple of 4 and 16-byte aligned gy and gcoef (coef_sorted_applicable); other shapes take the

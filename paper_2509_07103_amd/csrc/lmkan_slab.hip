@@ -18,6 +18,7 @@
 #include <utility>
 
 #include "lmkan_kernels.h"
+#include "lmkan_slab_common.h"
 
 namespace lmkan {
 
@@ -95,55 +96,6 @@ __global__ __launch_bounds__(256) void preamble_records_kernel(GridTab tab, cons
             }
         }
     }
-}
-
-struct SlabArgs {
-    const float *x_unused;
-    const void *P;     // float32, or 16-bit storage converted while the slab is filled
-    float *y;
-    const int32_t *rec_node;
-    const float *rec_u;
-    const float *rec_v;
-    CoefMap map;
-    int64_t B;
-    int n_out;
-    int K;
-    int W;             // G + 1
-    int nodes;         // W * W
-    int col_limit;     // columns >= col_limit do not exist in the coefficient tensor
-    int packed;        // 1: packed layout, the slab of (pair, tile) is contiguous
-    int pairs_per_split;
-    int n_btiles;
-    int n_jt;
-    int n_split;
-    int atomic_out;    // 1: add into y with atomics (split over pairs), 0: plain store
-};
-
-// 16 bytes per lane from global memory straight into LDS at lds_base + lane * 16
-// (lds_base wave-uniform).  Written as inline assembly on purpose: the compiler does not
-// track it, so it cannot make every later LDS read wait for loads that fill the *other*
-// buffer; completion is awaited explicitly with s_waitcnt vmcnt(0) before the barrier.
-__device__ __forceinline__ void lds_dma16(const void *gptr, unsigned lds_base)
-{
-    asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off"
-                 :
-                 : "v"(gptr), "s"(lds_base)
-                 : "memory");
-}
-
-__device__ __forceinline__ unsigned lds_address(const void *p)
-{
-    return (unsigned)(size_t)(__attribute__((address_space(3))) const void *)p;
-}
-
-// Same, with the global address given as a wave-uniform base (scalar registers) plus a 32-bit
-// per-lane byte offset: stepping through a contiguous slab then costs scalar instructions only.
-__device__ __forceinline__ void lds_dma16_uniform(const void *gbase, unsigned lane_off, unsigned lds_base)
-{
-    asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1"
-                 :
-                 : "v"(lane_off), "s"(gbase), "s"(lds_base)
-                 : "memory");
 }
 
 // Stream the slab of (pair k, output tile jt) into LDS.  A wave instruction moves
@@ -467,29 +419,6 @@ __global__ __launch_bounds__(WAVES * 64) __attribute__((amdgpu_waves_per_eu(WAVE
 // collected across the lanes and added into grad_x with one atomic instruction (the
 // output tiles of a sample are spread over several workgroups).
 // ---------------------------------------------------------------------------
-struct GradInArgs {
-    const void *P;     // float32, or 16-bit storage converted while the slab is filled
-    const float *gy;
-    float *gx;  // transposed scratch [n_in][B], zero on entry
-    const int32_t *rec_node;
-    const float *rec_u;
-    const float *rec_v;
-    CoefMap map;
-    GridTab tab;
-    int64_t B;
-    int n_in;
-    int n_out;
-    int K;
-    int W;
-    int nodes;
-    int pairs_per_split;
-    int n_btiles;
-    int n_jt;
-    int n_split;
-    int col_limit;
-    int packed;
-};
-
 // out[B][n_in] = in[n_in][B]
 __global__ __launch_bounds__(256) void transpose_kernel(const float *__restrict__ in, float *__restrict__ out,
                                                        int64_t B, int n_in)
@@ -505,11 +434,6 @@ __global__ __launch_bounds__(256) void transpose_kernel(const float *__restrict_
         if (n0 + r < B && c0 + tx < n_in) out[(n0 + r) * n_in + c0 + tx] = tile[tx][r];
 }
 
-template <int CTRL>
-__device__ __forceinline__ float dpp_move(float v)
-{
-    return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), CTRL, 0xf, 0xf, false));
-}
 
 // d = (w of lane S of this row) * x
 template <int S>
@@ -1137,6 +1061,10 @@ void launch_forward_slab(const LayerShape &s, const void *coef, float *y, const 
         launch_forward_slab_narrow(s, coef, y, records, stream);
         return;
     }
+    if (slab_f16_native_ok(s)) {
+        launch_forward_slab_f16(s, coef, y, records, stream);
+        return;
+    }
     // 1024 samples per workgroup either way: 16 waves x 64 samples for float32 tables, 8 x 128 for
     // 16-bit tables (their staging registers do not fit the smaller register share)
     constexpr int kTileB = 1024;
@@ -1208,6 +1136,13 @@ size_t slab_backward_input_scratch_bytes(const LayerShape &s)
 void launch_backward_input_slab(const LayerShape &s, const GridTab &tab, const void *coef, const float *gy,
                                 float *gx, const void *records, void *scratch, hipStream_t stream)
 {
+    if (slab_wide_ok(s) && slab_f16_native_ok(s)) {
+        launch_fill_zero(static_cast<float *>(scratch), (size_t)s.batch * s.n_in, stream);
+        launch_backward_input_slab_f16(s, tab, coef, gy, static_cast<float *>(scratch), records, stream);
+        const dim3 tg((unsigned)((s.batch + 63) / 64), (unsigned)((s.n_in + 63) / 64));
+        transpose_kernel<<<tg, 256, 0, stream>>>(static_cast<float *>(scratch), gx, s.batch, s.n_in);
+        return;
+    }
     constexpr int WAVES = 8, SETS = 2;
     constexpr int kTileB = WAVES * SETS * 64;
     typedef void (*Kernel)(GradInArgs);
