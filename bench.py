@@ -151,14 +151,17 @@ def main():
     # each call = its main kernel plus the small preamble-record / zero-fill / sort / transpose
     # launches; which kernel serves a call follows the library's own dispatch rules
     ok = n_out % 4 == 0 and B >= 256
-    if ok and w.grid <= 16:
+    if n_out <= 8:
+        fwd_name, gx_name = "forward_small_kernel", "backward_input_small_kernel"
+    elif ok and w.grid <= 16:
         fwd_name, gx_name = "forward_slab_kernel", "backward_input_slab_kernel"
     elif ok and w.grid <= 34 and args.storage != "f32":
         fwd_name, gx_name = "forward_slab_narrow_kernel", "backward_input_slab_narrow_kernel"
     else:
         fwd_name, gx_name = "forward_generic_kernel", "backward_generic_kernel(grad_x)"
     calls = {fwd_name: fwd_ms, gx_name: gx_ms,
-             ("backward_coef_stream_kernel" if n_out % 4 == 0 else "backward_generic_kernel(grad_coef)"): gp_ms}
+             ("backward_coef_small_kernel" if n_out <= 8 else "backward_coef_stream_kernel" if n_out % 4 == 0
+              else "backward_generic_kernel(grad_coef)"): gp_ms}
     dom_name = max(calls, key=calls.get)
     dom_ms = calls[dom_name]
     # algorithmic work of one such launch: 4 B K n_out multiply-adds; compulsory HBM bytes: the

@@ -112,11 +112,11 @@ size_t lmkan_workspace_bytes(const lmkan_desc *desc, int64_t batch, int32_t pass
 {
     if (check_desc(desc) != LMKAN_OK || batch <= 0) return 0;
     const LayerShape s = shape_of(desc, batch);
-    if (pass == 0) return slab_forward_shape_ok(s) ? records_bytes(s) : 0;
+    if (pass == 0) return (slab_forward_shape_ok(s) || small_out_shape_ok(s)) ? records_bytes(s) : 0;
     // backward: preamble records, the cell-sorted copy used by the coefficient gradient, and the
     // transposed scratch of the input gradient
     return align256(records_bytes(s)) + sorted_records_bytes(s) +
-           (slab_backward_input_shape_ok(s) ? slab_backward_input_scratch_bytes(s) : 0);
+           ((slab_backward_input_shape_ok(s) || small_out_shape_ok(s)) ? slab_backward_input_scratch_bytes(s) : 0);
 }
 
 lmkan_status lmkan_pack(const lmkan_desc *desc, const void *coef_paper_dev, void *coef_packed_dev,
@@ -164,7 +164,10 @@ lmkan_status lmkan_forward(const lmkan_desc *desc, int64_t batch, const float *x
     build_grid(desc->grid, &tab);
     const LayerShape s = shape_of(desc, batch);
     hipStream_t hs = static_cast<hipStream_t>(stream);
-    if (slab_forward_applicable(s, coef_dev, y_dev)) {
+    if (small_out_shape_ok(s)) {
+        launch_preamble_records(s, tab, x_dev, workspace_dev, hs);
+        launch_forward_small(s, coef_dev, y_dev, workspace_dev, hs);
+    } else if (slab_forward_applicable(s, coef_dev, y_dev)) {
         launch_preamble_records(s, tab, x_dev, workspace_dev, hs);
         launch_forward_slab(s, coef_dev, y_dev, workspace_dev, hs);
     } else {
@@ -200,28 +203,38 @@ lmkan_status lmkan_backward(const lmkan_desc *desc, int64_t batch, const float *
         (grad_coef_dev && !aligned(grad_coef_dev, 4)) ||
         (coef_dev && !aligned(coef_dev, dtype_size(desc->coef_dtype))))
         return LMKAN_ERR_ALIGN;
-    const bool gx_slab = grad_x_dev && slab_backward_input_applicable(s, coef_dev, grad_y_dev, grad_x_dev);
-    const bool gp_sorted = grad_coef_dev && coef_sorted_applicable(s, grad_y_dev, grad_coef_dev);
-    const size_t need = (gp_sorted || gx_slab) ? lmkan_workspace_bytes(desc, batch, 1) : 0;
+    const bool small = small_out_shape_ok(s);
+    const bool gx_small = grad_x_dev && small;
+    const bool gp_small = grad_coef_dev && small && small_coef_ok(s);
+    const bool gx_slab = grad_x_dev && !small && slab_backward_input_applicable(s, coef_dev, grad_y_dev, grad_x_dev);
+    const bool gp_sorted = grad_coef_dev && !gp_small && coef_sorted_applicable(s, grad_y_dev, grad_coef_dev);
+    const bool need_records = gp_sorted || gx_slab || gx_small || gp_small;
+    const size_t need = need_records ? lmkan_workspace_bytes(desc, batch, 1) : 0;
     if (need > 0 && (!workspace_dev || workspace_bytes < need)) return LMKAN_ERR_WORKSPACE;
     if (need > 0 && !aligned(workspace_dev, 256)) return LMKAN_ERR_ALIGN;
     GridTab tab;
     build_grid(desc->grid, &tab);
     char *ws = static_cast<char *>(workspace_dev);
-    if (gp_sorted || gx_slab) launch_preamble_records(s, tab, x_dev, ws, hs);
-    if (gp_sorted) {
-        launch_backward_coef_sorted(s, ws, ws + align256(records_bytes(s)), grad_y_dev, grad_coef_dev,
-                                    !overwrite, hs);
+    char *ws_sorted = ws + align256(records_bytes(s));
+    float *ws_scratch = reinterpret_cast<float *>(ws_sorted + sorted_records_bytes(s));
+    if (need_records) launch_preamble_records(s, tab, x_dev, ws, hs);
+    if (gp_small) {
+        launch_backward_coef_small(s, ws, grad_y_dev, grad_coef_dev, !overwrite, hs);
+    } else if (gp_sorted) {
+        launch_backward_coef_sorted(s, ws, ws_sorted, grad_y_dev, grad_coef_dev, !overwrite, hs);
     } else if (grad_coef_dev) {
         // odd output counts or unaligned buffers: atomics on a gradient that starts at zero
         if (overwrite) launch_fill_zero(grad_coef_dev, (size_t)s.nodes() * s.pairs() * s.n_out, hs);
         launch_backward_generic(s, tab, x_dev, coef_dev, grad_y_dev, nullptr, grad_coef_dev, hs);
     }
-    if (gx_slab)
-        launch_backward_input_slab(s, tab, coef_dev, grad_y_dev, grad_x_dev, ws,
-                                   ws + align256(records_bytes(s)) + sorted_records_bytes(s), hs);
-    else if (grad_x_dev)
+    if (gx_small) {
+        launch_backward_input_small(s, tab, coef_dev, grad_y_dev, ws_scratch, ws, hs);
+        launch_transpose(ws_scratch, grad_x_dev, s.batch, s.n_in, hs);
+    } else if (gx_slab) {
+        launch_backward_input_slab(s, tab, coef_dev, grad_y_dev, grad_x_dev, ws, ws_scratch, hs);
+    } else if (grad_x_dev) {
         launch_backward_generic(s, tab, x_dev, coef_dev, grad_y_dev, grad_x_dev, nullptr, hs);
+    }
     return launch_status();
 }
 

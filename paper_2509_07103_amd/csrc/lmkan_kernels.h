@@ -59,6 +59,19 @@ void launch_forward_slab_f16(const LayerShape &s, const void *coef, float *y, co
 void launch_backward_input_slab_f16(const LayerShape &s, const GridTab &tab, const void *coef, const float *gy,
                                     float *gx_scratch, const void *records, hipStream_t stream);
 
+// Layers with at most kSmallMaxOut outputs (lmkan_small.hip): a lane is a sample.  All three use
+// the preamble records; the input gradient goes to the transposed scratch [n_in][B] (every
+// element written, no zero fill needed) and launch_transpose finishes it.
+constexpr int kSmallMaxOut = 8;
+bool small_out_shape_ok(const LayerShape &s);
+bool small_coef_ok(const LayerShape &s);
+void launch_forward_small(const LayerShape &s, const void *coef, float *y, const void *records, hipStream_t stream);
+void launch_backward_input_small(const LayerShape &s, const GridTab &tab, const void *coef, const float *gy,
+                                 float *gx_scratch, const void *records, hipStream_t stream);
+void launch_backward_coef_small(const LayerShape &s, const void *records, const float *gy, float *gcoef,
+                                bool accumulate, hipStream_t stream);
+void launch_transpose(const float *in_t, float *out, int64_t batch, int n_in, hipStream_t stream);
+
 // Coefficient gradient by cell-sorted samples (lmkan_backward.hip).  `records` is the output
 // of launch_preamble_records; `sorted` is scratch of sorted_records_bytes().  Needs n_out to be a
 // multiple of 4 and 16-byte aligned gy and gcoef (coef_sorted_applicable); other shapes take the

@@ -1128,6 +1128,12 @@ bool slab_backward_input_applicable(const LayerShape &s, const void *coef, const
            (reinterpret_cast<uintptr_t>(gx) & 3) == 0;
 }
 
+void launch_transpose(const float *in_t, float *out, int64_t batch, int n_in, hipStream_t stream)
+{
+    const dim3 tgrid((unsigned)((batch + 63) / 64), (unsigned)((n_in + 63) / 64));
+    transpose_kernel<<<tgrid, 256, 0, stream>>>(in_t, out, batch, n_in);
+}
+
 size_t slab_backward_input_scratch_bytes(const LayerShape &s)
 {
     return ((size_t)s.batch * s.n_in * sizeof(float) + 255) & ~(size_t)255;

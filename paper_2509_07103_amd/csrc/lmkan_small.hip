@@ -1,0 +1,255 @@
+// Layers with very few outputs (n_out <= 8: regression and classification heads).
+//
+// With so few outputs the lanes cannot be outputs: here a lane is a sample and walks over the
+// pairs, the preamble records (cell, local coordinates) arriving coalesced along the sample
+// axis.  The table of such a layer is small ((G+1)^2 K n_out values) and is gathered from L2.
+//   forward:        y[n][j] accumulated in registers over the pairs
+//   input gradient: both derivatives of a (sample, pair) come from one lane, written once
+//                   into the transposed scratch [n_in][B] (no atomics, no zero fill)
+//   coefficient gradient: a workgroup owns a range of pairs whose table slice fits LDS, adds
+//                   its samples into that slice with LDS atomics and then adds the slice into
+//                   the zero-filled gradient (float32 atomics)
+#include "lmkan_kernels.h"
+
+namespace lmkan {
+
+namespace {
+
+constexpr int kSmallMax = kSmallMaxOut;
+constexpr int kThreads = 256;
+
+struct SmallArgs {
+    const void *P;
+    CoefMap map;
+    const int32_t *rec_node;
+    const float *rec_u;
+    const float *rec_v;
+    const float *gy;
+    float *y;
+    float *gx_t;   // transposed scratch [n_in][B]
+    float *gP;     // layout of Alg. 1, float32
+    GridTab tab;
+    int64_t B;
+    int n_out;
+    int K;
+    int W;
+    int pairs_per_block;
+    int atomic_out;
+};
+
+template <typename CT>
+__global__ __launch_bounds__(kThreads) void forward_small_kernel(SmallArgs a)
+{
+    const int64_t n = (int64_t)blockIdx.x * kThreads + threadIdx.x;
+    const int k0 = blockIdx.y * a.pairs_per_block;
+    const int k1 = min(a.K, k0 + a.pairs_per_block);
+    if (n >= a.B) return;
+    const CT *P = static_cast<const CT *>(a.P);
+    const int64_t d_i1 = (int64_t)a.W * a.map.s_node, d_i2 = a.map.s_node;
+    float acc[kSmallMax];
+#pragma unroll
+    for (int j = 0; j < kSmallMax; ++j) acc[j] = 0.f;
+    for (int k = k0; k < k1; ++k) {
+        const int64_t o = (int64_t)k * a.B + n;
+        const int node = a.rec_node[o];
+        const float u = a.rec_u[o], v = a.rec_v[o];
+        const float a_lo = 1.0f - u, b_lo = 1.0f - v;
+        const float w00 = a_lo * b_lo, w10 = u * b_lo, w01 = a_lo * v, w11 = u * v;
+        const CT *row = P + (int64_t)node * a.map.s_node + (int64_t)k * a.map.s_pair;
+#pragma unroll
+        for (int j = 0; j < kSmallMax; ++j) {
+            if (j < a.n_out) {
+                acc[j] = fmaf(w00, widen(row[j]), acc[j]);
+                acc[j] = fmaf(w10, widen(row[d_i1 + j]), acc[j]);
+                acc[j] = fmaf(w01, widen(row[d_i2 + j]), acc[j]);
+                acc[j] = fmaf(w11, widen(row[d_i1 + d_i2 + j]), acc[j]);
+            }
+        }
+    }
+    float *dst = a.y + n * a.n_out;
+#pragma unroll
+    for (int j = 0; j < kSmallMax; ++j) {
+        if (j < a.n_out) {
+            if (a.atomic_out)
+                unsafeAtomicAdd(dst + j, acc[j]);
+            else
+                dst[j] = acc[j];
+        }
+    }
+}
+
+template <typename CT>
+__global__ __launch_bounds__(kThreads) void backward_input_small_kernel(SmallArgs a)
+{
+    __shared__ float s_invh[LMKAN_MAX_GRID];
+    for (int i = threadIdx.x; i < a.tab.G; i += blockDim.x) s_invh[i] = a.tab.inv_h[i];
+    __syncthreads();
+    const int64_t n = (int64_t)blockIdx.x * kThreads + threadIdx.x;
+    const int k0 = blockIdx.y * a.pairs_per_block;
+    const int k1 = min(a.K, k0 + a.pairs_per_block);
+    if (n >= a.B) return;
+    const CT *P = static_cast<const CT *>(a.P);
+    const int64_t d_i1 = (int64_t)a.W * a.map.s_node, d_i2 = a.map.s_node;
+    float g[kSmallMax];
+#pragma unroll
+    for (int j = 0; j < kSmallMax; ++j) g[j] = j < a.n_out ? a.gy[n * a.n_out + j] : 0.f;
+    for (int k = k0; k < k1; ++k) {
+        const int64_t o = (int64_t)k * a.B + n;
+        const int node = a.rec_node[o];
+        const float u = a.rec_u[o], v = a.rec_v[o];
+        const CT *row = P + (int64_t)node * a.map.s_node + (int64_t)k * a.map.s_pair;
+        float s00 = 0.f, s10 = 0.f, s01 = 0.f, s11 = 0.f;
+#pragma unroll
+        for (int j = 0; j < kSmallMax; ++j) {
+            if (j < a.n_out) {
+                s00 = fmaf(g[j], widen(row[j]), s00);
+                s10 = fmaf(g[j], widen(row[d_i1 + j]), s10);
+                s01 = fmaf(g[j], widen(row[d_i2 + j]), s01);
+                s11 = fmaf(g[j], widen(row[d_i1 + d_i2 + j]), s11);
+            }
+        }
+        const int i1 = node / a.W, i2 = node - i1 * a.W;
+        const float d1 = s_invh[i1] * ((s10 - s00) * (1.0f - v) + (s11 - s01) * v);
+        const float d2 = s_invh[i2] * ((s01 - s00) * (1.0f - u) + (s11 - s10) * u);
+        a.gx_t[(int64_t)(2 * k) * a.B + n] = d1;
+        a.gx_t[(int64_t)(2 * k + 1) * a.B + n] = d2;
+    }
+}
+
+// blockIdx.y: range of pairs [k0, k1) whose slice [(G+1)^2][k1-k0][n_out] sits in LDS;
+// blockIdx.x: the samples n = blockIdx.x * 256 + tid, stepping by gridDim.x * 256
+__global__ __launch_bounds__(kThreads) void backward_coef_small_kernel(SmallArgs a)
+{
+    extern __shared__ float s_tab[];
+    const int k0 = blockIdx.y * a.pairs_per_block;
+    const int k1 = min(a.K, k0 + a.pairs_per_block);
+    const int kc = k1 - k0;
+    const int nodes = a.W * a.W;
+    const int slice = nodes * kc * a.n_out;
+    for (int i = threadIdx.x; i < slice; i += blockDim.x) s_tab[i] = 0.f;
+    __syncthreads();
+    const int row_stride = kc * a.n_out;  // one node of the slice
+    for (int64_t n = (int64_t)blockIdx.x * kThreads + threadIdx.x; n < a.B; n += (int64_t)gridDim.x * kThreads) {
+        float g[kSmallMax];
+#pragma unroll
+        for (int j = 0; j < kSmallMax; ++j) g[j] = j < a.n_out ? a.gy[n * a.n_out + j] : 0.f;
+        for (int k = k0; k < k1; ++k) {
+            const int64_t o = (int64_t)k * a.B + n;
+            const int node = a.rec_node[o];
+            const float u = a.rec_u[o], v = a.rec_v[o];
+            const float a_lo = 1.0f - u, b_lo = 1.0f - v;
+            const float w00 = a_lo * b_lo, w10 = u * b_lo, w01 = a_lo * v, w11 = u * v;
+            float *p = s_tab + node * row_stride + (k - k0) * a.n_out;
+#pragma unroll
+            for (int j = 0; j < kSmallMax; ++j) {
+                if (j < a.n_out) {
+                    atomicAdd(p + j, w00 * g[j]);
+                    atomicAdd(p + a.W * row_stride + j, w10 * g[j]);
+                    atomicAdd(p + row_stride + j, w01 * g[j]);
+                    atomicAdd(p + (a.W + 1) * row_stride + j, w11 * g[j]);
+                }
+            }
+        }
+    }
+    __syncthreads();
+    for (int i = threadIdx.x; i < slice; i += blockDim.x) {
+        const float v = s_tab[i];
+        if (v != 0.f) {
+            const int node = i / row_stride, r = i - node * row_stride;
+            const int k = k0 + r / a.n_out, j = r - (r / a.n_out) * a.n_out;
+            unsafeAtomicAdd(a.gP + (int64_t)node * a.map.s_node + (int64_t)k * a.map.s_pair + j, v);
+        }
+    }
+}
+
+SmallArgs small_args(const LayerShape &s, const void *coef, const void *records)
+{
+    const size_t n = (size_t)s.pairs() * (size_t)s.batch;
+    SmallArgs a = {};
+    a.P = coef;
+    a.map = coef_map(s);
+    a.rec_node = static_cast<const int32_t *>(records);
+    a.rec_u = reinterpret_cast<const float *>(a.rec_node + n);
+    a.rec_v = a.rec_u + n;
+    a.B = s.batch;
+    a.n_out = s.n_out;
+    a.K = s.pairs();
+    a.W = s.G + 1;
+    return a;
+}
+
+// enough blocks for 256 CUs: split the pairs when the batch alone gives too few
+int pair_split(const LayerShape &s)
+{
+    const int64_t bblocks = (s.batch + kThreads - 1) / kThreads;
+    int split = 1;
+    while (bblocks * split < 512 && s.pairs() / (split * 2) >= 8) split *= 2;
+    return split;
+}
+
+}  // namespace
+
+bool small_out_shape_ok(const LayerShape &s) { return s.n_out <= kSmallMax; }
+
+void launch_forward_small(const LayerShape &s, const void *coef, float *y, const void *records, hipStream_t stream)
+{
+    SmallArgs a = small_args(s, coef, records);
+    a.y = y;
+    const int split = pair_split(s);
+    a.pairs_per_block = (a.K + split - 1) / split;
+    a.atomic_out = split > 1;
+    if (a.atomic_out) launch_fill_zero(y, (size_t)s.batch * s.n_out, stream);
+    const dim3 grid((unsigned)((s.batch + kThreads - 1) / kThreads), (unsigned)split);
+    switch (s.dtype) {
+    case LMKAN_F32: forward_small_kernel<float><<<grid, kThreads, 0, stream>>>(a); break;
+    case LMKAN_F16: forward_small_kernel<_Float16><<<grid, kThreads, 0, stream>>>(a); break;
+    default: forward_small_kernel<bf16_t><<<grid, kThreads, 0, stream>>>(a); break;
+    }
+}
+
+void launch_backward_input_small(const LayerShape &s, const GridTab &tab, const void *coef, const float *gy,
+                                 float *gx_scratch, const void *records, hipStream_t stream)
+{
+    SmallArgs a = small_args(s, coef, records);
+    a.gy = gy;
+    a.gx_t = gx_scratch;
+    a.tab = tab;
+    const int split = pair_split(s);
+    a.pairs_per_block = (a.K + split - 1) / split;
+    const dim3 grid((unsigned)((s.batch + kThreads - 1) / kThreads), (unsigned)split);
+    switch (s.dtype) {
+    case LMKAN_F32: backward_input_small_kernel<float><<<grid, kThreads, 0, stream>>>(a); break;
+    case LMKAN_F16: backward_input_small_kernel<_Float16><<<grid, kThreads, 0, stream>>>(a); break;
+    default: backward_input_small_kernel<bf16_t><<<grid, kThreads, 0, stream>>>(a); break;
+    }
+}
+
+void launch_backward_coef_small(const LayerShape &s, const void *records, const float *gy, float *gcoef,
+                                bool accumulate, hipStream_t stream)
+{
+    SmallArgs a = small_args(s, nullptr, records);
+    a.gy = gy;
+    a.gP = gcoef;
+    LayerShape g = s;
+    g.layout = LMKAN_LAYOUT_PAPER;
+    a.map = coef_map(g);
+    // pairs per block: the slice must fit 64 KiB of LDS
+    const int per_pair = s.nodes() * s.n_out * (int)sizeof(float);
+    int kc = (64 * 1024) / per_pair;
+    if (kc > a.K) kc = a.K;
+    a.pairs_per_block = kc;  // >= 1: (G+1)^2 n_out 4 <= 65^2 * 8 * 4 bytes would not fit, see small_coef_ok
+    const int groups = (a.K + kc - 1) / kc;
+    int64_t bblocks = (s.batch + kThreads - 1) / kThreads;
+    int64_t want = (1024 + groups - 1) / groups;  // about 1024 workgroups in all
+    if (bblocks > want) bblocks = want;
+    if (!accumulate) launch_fill_zero(gcoef, (size_t)s.nodes() * (size_t)s.pairs() * (size_t)s.n_out, stream);
+    const dim3 grid((unsigned)bblocks, (unsigned)groups);
+    backward_coef_small_kernel<<<grid, kThreads, (size_t)kc * per_pair, stream>>>(a);
+}
+
+bool small_coef_ok(const LayerShape &s)
+{
+    return small_out_shape_ok(s) && (size_t)s.nodes() * s.n_out * sizeof(float) <= 64 * 1024;
+}
+
+}  // namespace lmkan
