@@ -36,30 +36,46 @@ constexpr int kUnroll = 16;  // chunks per trip of the main loop: one load of sa
 constexpr int kPerW = 4;     // chunks whose products one load instruction brings in
 static_assert(kUnroll % kDepth == 0, "the gy ring must divide the unrolled trip");
 
-// Samples per pair in the sorted stream: every non-empty cell is padded to whole chunks, and
-// the end is padded so that the pipeline below can run (and prefetch) over whole trips of
-// kUnroll chunks without bounds checks.
+// Locality blocks.  A wave reads gy rows in the order of the sorted stream, i.e. all over the
+// batch; as long as the 64-column slice of gy (256 bytes per sample) fits the L2 of an XCD
+// next to the streams, the waves of that XCD share it.  Longer batches are cut into blocks of
+// kBlockSamples samples, the stream of a pair is sorted by (block, cell), and all waves of an
+// XCD work on one block at a time.
+constexpr int kSortSeg = 4096;       // samples per workgroup in the count and scatter passes
+constexpr int kBlockSamples = 8192;  // 2 MiB of gy per block and 64-column tile
+constexpr int kSegPerBlock = kBlockSamples / kSortSeg;
+
+__host__ __device__ inline int stream_blocks(int64_t B)
+{
+    return B > kBlockSamples + kBlockSamples / 2 ? (int)((B + kBlockSamples - 1) / kBlockSamples) : 1;
+}
+
+// Samples per pair in the sorted stream: every non-empty (block, cell) is padded to whole
+// chunks, every block to whole trips of kUnroll chunks, and the end is padded so that the
+// pipeline below can prefetch a trip beyond the last one without bounds checks.
 __host__ __device__ inline int64_t stream_stride(int64_t B, int G)
 {
-    const int64_t body = (B + (int64_t)(kChunk - 1) * G * G + kChunk - 1) / kChunk * kChunk;
-    return body + (int64_t)kChunk * (2 * kUnroll);
+    const int64_t blocks = stream_blocks(B);
+    const int64_t body = B + blocks * ((int64_t)(kChunk - 1) * G * G + (int64_t)kChunk * kUnroll);
+    return (body + kChunk - 1) / kChunk * kChunk + (int64_t)kChunk * (2 * kUnroll);
 }
 
 // Counting sort of the samples of every pair by cell, in three launches so that long batches
 // are spread over many workgroups.  records_in: [3][K][B] (node, u, v) from the preamble
-// pass.  Per pair k, with S = stream_stride:
+// pass.  Per pair k, with S = stream_stride, the samples ordered by (block, cell):
 //   sorted_w [K][S]      the four products (w00, w10, w01, w11) of a sample, 16 bytes
 //   sorted_n [K][S]      its index.  Padding entries have zero products and repeat the index
 //                        of a sample of the same cell, so that what they multiply is a value
 //                        the cell sees anyway.
 //   chunk_cell [K][S/4]  i1 << 8 | i2 of the cell each chunk belongs to, non-decreasing
-//   n_chunks [K]         chunks to process, a multiple of kUnroll
+//                        inside a block
+//   block_start [K][blocks+1]  first chunk of every block (multiples of kUnroll) and the
+//                        number of chunks to process
 // and as scratch between the launches, with nblk = ceil(B / kSortSeg) batch segments:
 //   seg_count [K][nblk][G*G]  population of a cell inside a segment, then the offset of the
 //                             segment's first sample of that cell within the cell
-//   cell_start [K][G*G]       first stream position of the cell
+//   cell_start [K][blocks][G*G]  first stream position of the (block, cell)
 //   cell_rep [K][G*G]         index of some sample of the cell (any one)
-constexpr int kSortSeg = 4096;     // samples per workgroup in the count and scatter passes
 constexpr int kSortSegThreads = 256;
 constexpr int kMaxCells = LMKAN_MAX_GRID * LMKAN_MAX_GRID;
 
@@ -93,107 +109,122 @@ __global__ __launch_bounds__(kSortSegThreads) void sort_count_kernel(const int32
     }
 }
 
-// 2: per pair, positions of the cells (each padded to whole chunks), the cell of every chunk,
-// padding entries and the tail
+// 2: per pair, block after block: positions of the cells (each padded to whole chunks), the
+// cell of every chunk, padding entries, dummy chunks that round the block up to whole trips
+// (they belong to the block's last cell), and after the last block the tail
 __global__ __launch_bounds__(kSortThreads) void sort_layout_kernel(int32_t *__restrict__ seg_count,
                                                                   int32_t *__restrict__ cell_start,
                                                                   const int32_t *__restrict__ cell_rep,
                                                                   f4v *__restrict__ sorted_w,
                                                                   int32_t *__restrict__ sorted_n,
                                                                   int32_t *__restrict__ chunk_cell,
-                                                                  int32_t *__restrict__ n_chunks, int64_t B,
-                                                                  int G, int nblk)
+                                                                  int32_t *__restrict__ block_start, int64_t B,
+                                                                  int G, int nseg)
 {
-    __shared__ int s_count[kMaxCells];      // population of the cell
-    __shared__ int s_start[kMaxCells + 1];  // first stream position of the cell; [cells] = total
+    __shared__ int s_count[kMaxCells];      // population of the cell in this block
+    __shared__ int s_start[kMaxCells + 1];  // first stream position of the cell; [cells] = end
     __shared__ int s_wave_total[kSortThreads / 64];
     __shared__ int s_last_cell;
     const int k = blockIdx.x;
     const int cells = G * G;
+    const int blocks = stream_blocks(B);
+    const int seg_per_block = blocks > 1 ? kSegPerBlock : nseg;
     const int64_t S = stream_stride(B, G);
     f4v *out_w = sorted_w + (int64_t)k * S;
     int32_t *out_n = sorted_n + (int64_t)k * S;
     int32_t *out_cell = chunk_cell + (int64_t)k * (S / kChunk);
-    int32_t *cnt_k = seg_count + (int64_t)k * nblk * cells;
+    int32_t *cnt_k = seg_count + (int64_t)k * nseg * cells;
     const int32_t *rep_k = cell_rep + (int64_t)k * cells;
+    int32_t *bs_k = block_start + (int64_t)k * (blocks + 1);
     const f4v zero = {0.f, 0.f, 0.f, 0.f};
 
-    if (threadIdx.x == 0) s_last_cell = 0;
-    // populations; the per-segment counts become offsets inside the cell
-    for (int c = threadIdx.x; c < cells; c += blockDim.x) {
-        int run = 0;
-        for (int b = 0; b < nblk; ++b) {
-            const int v = cnt_k[(int64_t)b * cells + c];
-            cnt_k[(int64_t)b * cells + c] = run;
-            run += v;
-        }
-        s_count[c] = run;
-    }
-    __syncthreads();
-    // exclusive scan of the padded populations, in pieces of blockDim.x cells
-    int carry = 0;
-    for (int base = 0; base < cells; base += blockDim.x) {
-        const int c = base + threadIdx.x;
-        const int cnt = c < cells ? s_count[c] : 0;
-        const int v = (cnt + kChunk - 1) / kChunk * kChunk;
-        if (cnt > 0) atomicMax(&s_last_cell, c);
-        int incl = v;
-#pragma unroll
-        for (int d = 1; d < 64; d <<= 1) {
-            const int t = __shfl_up(incl, d, 64);
-            if ((threadIdx.x & 63) >= d) incl += t;
-        }
-        if ((threadIdx.x & 63) == 63) s_wave_total[threadIdx.x >> 6] = incl;
+    int base_pos = 0;  // stream position where the current block starts (a multiple of kChunk * kUnroll)
+    for (int blk = 0; blk < blocks; ++blk) {
+        const int b0 = blk * seg_per_block, b1 = min(nseg, b0 + seg_per_block);
+        if (threadIdx.x == 0) s_last_cell = 0;
         __syncthreads();
-        int wave_off = 0;
-        for (int w = 0; w < (int)(threadIdx.x >> 6); ++w) wave_off += s_wave_total[w];
-        int piece_total = 0;
-        for (int w = 0; w < (int)(blockDim.x >> 6); ++w) piece_total += s_wave_total[w];
-        if (c < cells) s_start[c] = carry + wave_off + incl - v;
-        carry += piece_total;
-        __syncthreads();
-    }
-    const int total = carry;  // padded samples of all cells, a multiple of kChunk
-    if (threadIdx.x == 0) s_start[cells] = total;
-    __syncthreads();
-    for (int c = threadIdx.x; c < cells; c += blockDim.x) cell_start[(int64_t)k * cells + c] = s_start[c];
-    const int real_chunks = total / kChunk;
-    const int run_chunks = (real_chunks + kUnroll - 1) / kUnroll * kUnroll;
-    const int tail_end = run_chunks + kUnroll;  // chunks the pipelines may touch
-    const int last = s_last_cell;
-    // the cell of every chunk: the highest cell whose start is <= the chunk's first position
-    // (an empty cell shares its start with the next one, so the highest such cell is never empty)
-    for (int q = threadIdx.x; q < tail_end; q += blockDim.x) {
-        int c = last;
-        if (q < real_chunks) {
-            const int pos = q * kChunk;
-            int lo = 0, hi = cells - 1;
-            while (lo < hi) {
-                const int mid = (lo + hi + 1) >> 1;
-                if (s_start[mid] <= pos) lo = mid; else hi = mid - 1;
+        // populations; the per-segment counts become offsets inside the (block, cell)
+        for (int c = threadIdx.x; c < cells; c += blockDim.x) {
+            int run = 0;
+            for (int b = b0; b < b1; ++b) {
+                const int v = cnt_k[(int64_t)b * cells + c];
+                cnt_k[(int64_t)b * cells + c] = run;
+                run += v;
             }
-            c = lo;
+            s_count[c] = run;
+            if (run > 0) atomicMax(&s_last_cell, c);
         }
-        out_cell[q] = ((c / G) << 8) | (c % G);
-    }
-    // padding entries of every cell, then the tail: zero products, a sample of that cell
-    for (int c = threadIdx.x; c < cells; c += blockDim.x) {
-        const int cnt = s_count[c];
-        if (cnt == 0) continue;
-        const int first = s_start[c], padded = (cnt + kChunk - 1) / kChunk * kChunk;
-        const int32_t n0 = rep_k[c];
-        for (int i = cnt; i < padded; ++i) {
-            out_w[first + i] = zero;
-            out_n[first + i] = n0;
+        __syncthreads();
+        // exclusive scan of the padded populations, in pieces of blockDim.x cells
+        int carry = base_pos;
+        for (int base = 0; base < cells; base += blockDim.x) {
+            const int c = base + threadIdx.x;
+            const int cnt = c < cells ? s_count[c] : 0;
+            const int v = (cnt + kChunk - 1) / kChunk * kChunk;
+            int incl = v;
+#pragma unroll
+            for (int d = 1; d < 64; d <<= 1) {
+                const int t = __shfl_up(incl, d, 64);
+                if ((threadIdx.x & 63) >= d) incl += t;
+            }
+            if ((threadIdx.x & 63) == 63) s_wave_total[threadIdx.x >> 6] = incl;
+            __syncthreads();
+            int wave_off = 0;
+            for (int w = 0; w < (int)(threadIdx.x >> 6); ++w) wave_off += s_wave_total[w];
+            int piece_total = 0;
+            for (int w = 0; w < (int)(blockDim.x >> 6); ++w) piece_total += s_wave_total[w];
+            if (c < cells) s_start[c] = carry + wave_off + incl - v;
+            carry += piece_total;
+            __syncthreads();
         }
-    }
-    {
-        const int32_t n0 = rep_k[last];
-        for (int i = total + threadIdx.x; i < tail_end * kChunk; i += blockDim.x) {
-            out_w[i] = zero;
-            out_n[i] = n0;
+        const int real_end = carry;  // end of the padded samples of this block
+        const int block_chunks = ((real_end - base_pos) / kChunk + kUnroll - 1) / kUnroll * kUnroll;
+        const int block_end = base_pos + block_chunks * kChunk;
+        // the last block is followed by the chunks the pipelines may touch beyond the end
+        const int fill_end = blk + 1 < blocks ? block_end : block_end + kUnroll * kChunk;
+        for (int c = threadIdx.x; c < cells; c += blockDim.x)
+            cell_start[((int64_t)k * blocks + blk) * cells + c] = s_start[c];
+        const int last = s_last_cell;
+        // the cell of every chunk: the highest cell whose start is <= the chunk's first position
+        // (an empty cell shares its start with the next one, so the highest such cell is never
+        // empty); chunks past the real ones belong to the block's last cell
+        for (int q = base_pos / kChunk + threadIdx.x; q < fill_end / kChunk; q += blockDim.x) {
+            int c = last;
+            const int pos = q * kChunk;
+            if (pos < real_end) {
+                int lo = 0, hi = cells - 1;
+                while (lo < hi) {
+                    const int mid = (lo + hi + 1) >> 1;
+                    if (s_start[mid] <= pos) lo = mid; else hi = mid - 1;
+                }
+                c = lo;
+            }
+            out_cell[q] = ((c / G) << 8) | (c % G);
         }
-        if (threadIdx.x == 0) n_chunks[k] = run_chunks;
+        // padding entries of every cell, then the dummy chunks: zero products, a sample of that cell
+        for (int c = threadIdx.x; c < cells; c += blockDim.x) {
+            const int cnt = s_count[c];
+            if (cnt == 0) continue;
+            const int first = s_start[c], padded = (cnt + kChunk - 1) / kChunk * kChunk;
+            const int32_t n0 = rep_k[c];
+            for (int i = cnt; i < padded; ++i) {
+                out_w[first + i] = zero;
+                out_n[first + i] = n0;
+            }
+        }
+        {
+            const int32_t n0 = rep_k[last];
+            for (int i = real_end + threadIdx.x; i < fill_end; i += blockDim.x) {
+                out_w[i] = zero;
+                out_n[i] = n0;
+            }
+        }
+        if (threadIdx.x == 0) {
+            bs_k[blk] = base_pos / kChunk;
+            if (blk + 1 == blocks) bs_k[blocks] = block_end / kChunk;
+        }
+        base_pos = block_end;
+        __syncthreads();  // s_count / s_start are rebuilt for the next block
     }
 }
 
@@ -208,14 +239,16 @@ __global__ __launch_bounds__(kSortSegThreads) void sort_scatter_kernel(const int
                                                                       int G)
 {
     __shared__ int s_cursor[kMaxCells];
-    const int blk = blockIdx.x, nblk = gridDim.x, k = blockIdx.y;
+    const int seg = blockIdx.x, nseg = gridDim.x, k = blockIdx.y;
     const int cells = G * G;
+    const int blocks = stream_blocks(B);
+    const int blk = blocks > 1 ? seg / kSegPerBlock : 0;
     const int64_t S = stream_stride(B, G);
-    const int32_t *off = seg_count + ((int64_t)k * nblk + blk) * cells;
+    const int32_t *off = seg_count + ((int64_t)k * nseg + seg) * cells;
     for (int c = threadIdx.x; c < cells; c += blockDim.x)
-        s_cursor[c] = cell_start[(int64_t)k * cells + c] + off[c];
+        s_cursor[c] = cell_start[((int64_t)k * blocks + blk) * cells + c] + off[c];
     __syncthreads();
-    const int64_t n0 = (int64_t)blk * kSortSeg;
+    const int64_t n0 = (int64_t)seg * kSortSeg;
     const int64_t n1 = n0 + kSortSeg < B ? n0 + kSortSeg : B;
     const int32_t *node_k = rec_node + (int64_t)k * B;
     const float *u_k = rec_u + (int64_t)k * B;
@@ -235,7 +268,7 @@ struct CoefGradArgs {
     const f4v *sorted_w;
     const int32_t *sorted_n;
     const int32_t *chunk_cell;
-    const int32_t *n_chunks;
+    const int32_t *block_start;  // [K][n_blocks + 1], in chunks
     const float *gy;
     float *gP;
     CoefMap gmap;  // layout of Alg. 1
@@ -245,7 +278,8 @@ struct CoefGradArgs {
     int K;
     int G;
     int accumulate;
-    int n_seg;  // waves per (pair, output tile)
+    int n_blocks;  // locality blocks of the batch
+    int n_sub;     // waves per (pair, output tile, block)
 };
 
 // acc[i][q] += (product q of this group's sample) * gy[i] for the chunk whose products sit in
@@ -311,32 +345,37 @@ __global__ __launch_bounds__(64) void backward_coef_stream_kernel(CoefGradArgs a
     const int g = lane >> 4, l16 = lane & 15;
     const int G = a.G, W = G + 1;
 
-    // Waves that run together on one XCD (ids congruent mod 8) take the same output tile, so
-    // the 64-column slice of gy they all stream stays in that XCD's L2.
+    // Waves that run together on one XCD (ids congruent mod 8) take the same output tile and the
+    // same block of the batch, so the piece of gy they all gather from stays in that XCD's L2.
     int id = blockIdx.x;
     const int total = gridDim.x;
     if ((total & 7) == 0) id = (id & 7) * (total >> 3) + (id >> 3);
-    const int seg = id % a.n_seg;
-    id /= a.n_seg;
-    const int jt = id / a.K;
+    const int sub = id % a.n_sub;
+    id /= a.n_sub;
     const int k = id % a.K;
+    id /= a.K;
+    const int blk = id % a.n_blocks;
+    const int jt = id / a.n_blocks;
 
     const int col = jt * kTile + l16 * 4;
     const bool col_ok = col < a.n_out;
     typedef __attribute__((address_space(4))) const int32_t *ScalarIntPtr;
-    // When (pairs x output tiles) alone cannot fill the chip, the stream of a pair is cut into
-    // n_seg runs of whole trips, one wave each.  A run may begin and end anywhere, even inside
-    // a cell: every wave then adds what it has into a gradient that starts at zero (atomics).
-    const bool split = a.n_seg > 1;
-    int c_begin = 0;
-    int nch = ((ScalarIntPtr)a.n_chunks)[k];
-    if (split) {
+    // With one block and one wave per (pair, tile) the wave owns its columns of the gradient and
+    // writes every row once.  Otherwise (long batches; too few pairs x tiles to fill the chip)
+    // a wave takes a run of whole trips of one block; a run may begin and end anywhere, even
+    // inside a cell: every wave then adds what it has into a gradient that starts at zero.
+    const bool split = a.n_blocks > 1 || a.n_sub > 1;
+    ScalarIntPtr bs = (ScalarIntPtr)(a.block_start + (int64_t)k * (a.n_blocks + 1));
+    int c_begin = bs[blk];
+    int nch = bs[blk + 1] - c_begin;
+    if (a.n_sub > 1) {
         const int trips = nch / kUnroll;
-        const int per = (trips + a.n_seg - 1) / a.n_seg * kUnroll;
-        c_begin = min(seg * per, nch);
-        nch = min(per, nch - c_begin);
-        if (nch == 0) return;
+        const int per = (trips + a.n_sub - 1) / a.n_sub * kUnroll;
+        const int skip = min(sub * per, nch);
+        c_begin += skip;
+        nch = min(per, nch - skip);
     }
+    if (split && nch == 0) return;
     ScalarIntPtr cc = (ScalarIntPtr)(a.chunk_cell + (int64_t)k * (a.S / kChunk) + c_begin);
     float *out = a.gP + (int64_t)k * a.gmap.s_pair + col;
 
@@ -386,26 +425,32 @@ __global__ __launch_bounds__(64) void backward_coef_stream_kernel(CoefGradArgs a
         v.w += f[3];
         *p = v;
     };
-    // table rows below `upto` can receive nothing more: write them and recycle their buffers;
-    // four table entries per store instruction, group g takes b = 4 i + g
+    // table rows below `upto` can receive nothing more: write them and recycle their buffers.
+    // Owned columns: four table entries per store instruction, group g takes b = 4 i + g.
+    // Shared gradient: one atomic instruction per entry, lanes on consecutive floats (256
+    // contiguous bytes), entries this wave never touched left alone.
+    const int out_col = jt * kTile + lane;
+    float *out_lane = a.gP + (int64_t)k * a.gmap.s_pair + out_col;
     auto retire_rows = [&](int upto) {
         for (; rows_done < upto; ++rows_done) {
-            f4v *row = reinterpret_cast<f4v *>(win + (rows_done & 1) * W * kTile) + l16;
-            for (int b = g; b < W; b += 4) {
-                if (col_ok) {
-                    f4v *dst = reinterpret_cast<f4v *>(out + (int64_t)(rows_done * W + b) * a.gmap.s_node);
-                    const f4v v = row[b * (kTile / 4)];
-                    if (split) {
-                        float *d = reinterpret_cast<float *>(dst);
-                        unsafeAtomicAdd(d + 0, v.x);
-                        unsafeAtomicAdd(d + 1, v.y);
-                        unsafeAtomicAdd(d + 2, v.z);
-                        unsafeAtomicAdd(d + 3, v.w);
-                    } else {
+            if (split) {
+                float *row = win + (rows_done & 1) * W * kTile + lane;
+                for (int b = 0; b < W; ++b) {
+                    const float v = row[b * kTile];
+                    row[b * kTile] = 0.f;
+                    if (v != 0.f && out_col < a.n_out)
+                        unsafeAtomicAdd(out_lane + (int64_t)(rows_done * W + b) * a.gmap.s_node, v);
+                }
+            } else {
+                f4v *row = reinterpret_cast<f4v *>(win + (rows_done & 1) * W * kTile) + l16;
+                for (int b = g; b < W; b += 4) {
+                    if (col_ok) {
+                        f4v *dst = reinterpret_cast<f4v *>(out + (int64_t)(rows_done * W + b) * a.gmap.s_node);
+                        const f4v v = row[b * (kTile / 4)];
                         *dst = a.accumulate ? *dst + v : v;
                     }
+                    row[b * (kTile / 4)] = f4v{0.f, 0.f, 0.f, 0.f};
                 }
-                row[b * (kTile / 4)] = f4v{0.f, 0.f, 0.f, 0.f};
             }
         }
     };
@@ -477,10 +522,11 @@ __global__ __launch_bounds__(64) void backward_coef_stream_kernel(CoefGradArgs a
 size_t sorted_records_bytes(const LayerShape &s)
 {
     const size_t S = (size_t)stream_stride(s.batch, s.G);
-    const size_t nblk = ((size_t)s.batch + kSortSeg - 1) / kSortSeg;
+    const size_t nseg = ((size_t)s.batch + kSortSeg - 1) / kSortSeg;
+    const size_t blocks = (size_t)stream_blocks(s.batch);
     const size_t cells = (size_t)s.G * s.G;
-    const size_t per_pair = S * (sizeof(f4v) + sizeof(int32_t)) + (S / kChunk) * sizeof(int32_t) + sizeof(int32_t) +
-                            (nblk + 2) * cells * sizeof(int32_t);
+    const size_t per_pair = S * (sizeof(f4v) + sizeof(int32_t)) + (S / kChunk) * sizeof(int32_t) +
+                            (blocks + 1) * sizeof(int32_t) + (nseg + blocks + 1) * cells * sizeof(int32_t);
     return ((size_t)s.pairs() * per_pair + 255) & ~(size_t)255;
 }
 
@@ -502,23 +548,24 @@ void launch_backward_coef_sorted(const LayerShape &s, const void *records, void 
     f4v *sorted_w = static_cast<f4v *>(sorted);  // 16-byte items first, then the 4-byte ones
     int32_t *sorted_n = reinterpret_cast<int32_t *>(sorted_w + K * S);
     int32_t *chunk_cell = sorted_n + K * S;
-    int32_t *n_chunks = chunk_cell + K * (S / kChunk);
-    const size_t nblk = ((size_t)s.batch + kSortSeg - 1) / kSortSeg;
+    const size_t nseg = ((size_t)s.batch + kSortSeg - 1) / kSortSeg;
+    const size_t blocks = (size_t)stream_blocks(s.batch);
     const size_t cells = (size_t)s.G * s.G;
-    int32_t *seg_count = n_chunks + K;
-    int32_t *cell_start = seg_count + K * nblk * cells;
-    int32_t *cell_rep = cell_start + K * cells;
-    const dim3 seg_grid((unsigned)nblk, (unsigned)K);
+    int32_t *block_start = chunk_cell + K * (S / kChunk);
+    int32_t *seg_count = block_start + K * (blocks + 1);
+    int32_t *cell_start = seg_count + K * nseg * cells;
+    int32_t *cell_rep = cell_start + K * blocks * cells;
+    const dim3 seg_grid((unsigned)nseg, (unsigned)K);
     sort_count_kernel<<<seg_grid, kSortSegThreads, 0, stream>>>(rec_node, seg_count, cell_rep, s.batch, s.G);
     sort_layout_kernel<<<(unsigned)K, kSortThreads, 0, stream>>>(seg_count, cell_start, cell_rep, sorted_w, sorted_n,
-                                                               chunk_cell, n_chunks, s.batch, s.G, (int)nblk);
+                                                               chunk_cell, block_start, s.batch, s.G, (int)nseg);
     sort_scatter_kernel<<<seg_grid, kSortSegThreads, 0, stream>>>(rec_node, rec_u, rec_v, seg_count, cell_start,
                                                                  sorted_w, sorted_n, s.batch, s.G);
     CoefGradArgs a;
     a.sorted_w = sorted_w;
     a.sorted_n = sorted_n;
     a.chunk_cell = chunk_cell;
-    a.n_chunks = n_chunks;
+    a.block_start = block_start;
     a.gy = gy;
     a.gP = gcoef;
     LayerShape g = s;
@@ -531,16 +578,25 @@ void launch_backward_coef_sorted(const LayerShape &s, const void *records, void 
     a.G = s.G;
     a.accumulate = accumulate ? 1 : 0;
     const unsigned lds = (unsigned)(2 * (s.G + 1) * kTile * sizeof(float));
-    // cut the streams when there are too few of them to fill 256 CUs x 16 waves, keeping at
-    // least four trips per wave
+    // Runs per (pair, tile, block).  One block: cut the stream when pairs x tiles cannot fill
+    // 256 CUs x 16 waves.  Several blocks: as many runs as it takes for the pairs of one (tile,
+    // block) to occupy an XCD (512 waves), so that the XCD works on one block at a time.  A run
+    // keeps at least four trips.
     const int64_t streams = (int64_t)s.pairs() * s.out_tiles();
-    const int64_t trips = (int64_t)S / (kChunk * kUnroll);
-    int n_seg = 1;
-    while (streams * n_seg < 4096 && trips / (n_seg * 2) >= 4 && n_seg < 64) n_seg *= 2;
-    a.n_seg = n_seg;
-    if (n_seg > 1 && !accumulate)
+    const int n_blocks = (int)blocks;
+    int n_sub = 1;
+    if (n_blocks == 1) {
+        const int64_t trips = (int64_t)S / (kChunk * kUnroll);
+        while (streams * n_sub < 4096 && trips / (n_sub * 2) >= 4 && n_sub < 64) n_sub *= 2;
+    } else {
+        const int64_t trips = kBlockSamples / (kChunk * kUnroll);
+        while ((int64_t)s.pairs() * n_sub < 512 && trips / (n_sub * 2) >= 4 && n_sub < 32) n_sub *= 2;
+    }
+    a.n_blocks = n_blocks;
+    a.n_sub = n_sub;
+    if ((n_blocks > 1 || n_sub > 1) && !accumulate)
         launch_fill_zero(gcoef, (size_t)s.nodes() * (size_t)s.pairs() * (size_t)s.n_out, stream);
-    const unsigned grid = (unsigned)(streams * n_seg);
+    const unsigned grid = (unsigned)(streams * n_blocks * n_sub);
     // 24-bit multiply and 32-bit byte offsets into gy when the tensor is small enough
     const bool offset32 = s.batch < (1 << 24) && (int64_t)s.n_out * 4 < (1 << 24) &&
                           (int64_t)s.batch * s.n_out * 4 < ((int64_t)1 << 32);

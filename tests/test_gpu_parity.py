@@ -65,6 +65,8 @@ SHAPES = [
     (700, 12, 72, 20),
     (4200, 6, 40, 32),
     (300, 8, 20, 34),
+    # a batch long enough for the coefficient gradient to sort it block by block
+    (13000, 6, 68, 5),
 ]
 
 
@@ -135,8 +137,13 @@ def test_backward_matches_oracle(dev, oracle, shape, storage, layout):
         assert diff <= TOL_HALF * np.linalg.norm(master)
 
 
-def test_backward_pieces_and_accumulate_flag(dev, oracle):
-    B, n_in, n_out, G = 90, 12, 70, 8
+# one shape per way the coefficient gradient can be formed: float32 atomics in the generic
+# kernel (n_out not a multiple of 4), the cell-sorted stream written row by row, the same
+# stream cut into runs that meet through atomics (long batch, few pairs), the LDS-privatised
+# kernel of narrow layers
+@pytest.mark.parametrize("shape", [(90, 12, 70, 8), (90, 12, 72, 8), (2100, 12, 72, 8), (90, 12, 3, 8)])
+def test_backward_pieces_and_accumulate_flag(dev, oracle, shape):
+    B, n_in, n_out, G = shape
     x, P, gy = _inputs(B, n_in, n_out, G, 41, dev)
     desc = _desc(n_in, n_out, G)
     gx_only, none = pkg.lmkan_backward(desc, x, P, gy, need_grad_coef=False)
@@ -145,7 +152,8 @@ def test_backward_pieces_and_accumulate_flag(dev, oracle):
     assert none is None
     gx, gP = pkg.lmkan_backward(desc, x, P, gy)
     torch.cuda.synchronize()
-    assert torch.equal(gx, gx_only)
+    # same kernel, same inputs; only the order of a few float atomics may differ
+    assert rowwise_rel_err(gx.cpu().numpy(), gx_only.cpu().numpy().astype(np.float64)) <= 1e-6
     want = oracle.backward_coef(x.cpu().numpy(), gy.cpu().numpy(), G)
     for got in (gP, gP_only):
         assert np.abs(got.cpu().numpy() - want).max() <= TOL_F32 * np.abs(want).max()
