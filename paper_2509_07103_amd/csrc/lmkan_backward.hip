@@ -109,7 +109,36 @@ __global__ __launch_bounds__(kSortSegThreads) void sort_count_kernel(const int32
     }
 }
 
-// 2: per pair, block after block: positions of the cells (each padded to whole chunks), the
+// 1b: chunks of every (pair, block): cells padded to whole chunks, the block to whole trips
+__global__ __launch_bounds__(kSortSegThreads) void sort_block_size_kernel(const int32_t *__restrict__ seg_count,
+                                                                         int32_t *__restrict__ block_size, int64_t B,
+                                                                         int G, int nseg)
+{
+    __shared__ int s_sum[kSortSegThreads / 64];
+    const int k = blockIdx.x, blk = blockIdx.y;
+    const int cells = G * G;
+    const int blocks = stream_blocks(B);
+    const int seg_per_block = blocks > 1 ? kSegPerBlock : nseg;
+    const int b0 = blk * seg_per_block, b1 = min(nseg, b0 + seg_per_block);
+    const int32_t *cnt_k = seg_count + (int64_t)k * nseg * cells;
+    int mine = 0;
+    for (int c = threadIdx.x; c < cells; c += blockDim.x) {
+        int run = 0;
+        for (int b = b0; b < b1; ++b) run += cnt_k[(int64_t)b * cells + c];
+        mine += (run + kChunk - 1) / kChunk;
+    }
+#pragma unroll
+    for (int d = 32; d > 0; d >>= 1) mine += __shfl_down(mine, d, 64);
+    if ((threadIdx.x & 63) == 0) s_sum[threadIdx.x >> 6] = mine;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        int total = 0;
+        for (int w = 0; w < (int)(blockDim.x >> 6); ++w) total += s_sum[w];
+        block_size[(int64_t)k * blocks + blk] = (total + kUnroll - 1) / kUnroll * kUnroll;
+    }
+}
+
+// 2: per (pair, block): positions of the cells (each padded to whole chunks), the
 // cell of every chunk, padding entries, dummy chunks that round the block up to whole trips
 // (they belong to the block's last cell), and after the last block the tail
 __global__ __launch_bounds__(kSortThreads) void sort_layout_kernel(int32_t *__restrict__ seg_count,
@@ -118,7 +147,8 @@ __global__ __launch_bounds__(kSortThreads) void sort_layout_kernel(int32_t *__re
                                                                   f4v *__restrict__ sorted_w,
                                                                   int32_t *__restrict__ sorted_n,
                                                                   int32_t *__restrict__ chunk_cell,
-                                                                  int32_t *__restrict__ block_start, int64_t B,
+                                                                  int32_t *__restrict__ block_start,
+                                                                  const int32_t *__restrict__ block_size, int64_t B,
                                                                   int G, int nseg)
 {
     __shared__ int s_count[kMaxCells];      // population of the cell in this block
@@ -138,8 +168,11 @@ __global__ __launch_bounds__(kSortThreads) void sort_layout_kernel(int32_t *__re
     int32_t *bs_k = block_start + (int64_t)k * (blocks + 1);
     const f4v zero = {0.f, 0.f, 0.f, 0.f};
 
-    int base_pos = 0;  // stream position where the current block starts (a multiple of kChunk * kUnroll)
-    for (int blk = 0; blk < blocks; ++blk) {
+    const int blk = blockIdx.y;
+    // stream position where this block starts (a multiple of kChunk * kUnroll)
+    int base_pos = 0;
+    for (int b = 0; b < blk; ++b) base_pos += block_size[(int64_t)k * blocks + b] * kChunk;
+    {
         const int b0 = blk * seg_per_block, b1 = min(nseg, b0 + seg_per_block);
         if (threadIdx.x == 0) s_last_cell = 0;
         __syncthreads();
@@ -223,8 +256,6 @@ __global__ __launch_bounds__(kSortThreads) void sort_layout_kernel(int32_t *__re
             bs_k[blk] = base_pos / kChunk;
             if (blk + 1 == blocks) bs_k[blocks] = block_end / kChunk;
         }
-        base_pos = block_end;
-        __syncthreads();  // s_count / s_start are rebuilt for the next block
     }
 }
 
@@ -526,7 +557,7 @@ size_t sorted_records_bytes(const LayerShape &s)
     const size_t blocks = (size_t)stream_blocks(s.batch);
     const size_t cells = (size_t)s.G * s.G;
     const size_t per_pair = S * (sizeof(f4v) + sizeof(int32_t)) + (S / kChunk) * sizeof(int32_t) +
-                            (blocks + 1) * sizeof(int32_t) + (nseg + blocks + 1) * cells * sizeof(int32_t);
+                            (2 * blocks + 1) * sizeof(int32_t) + (nseg + blocks + 1) * cells * sizeof(int32_t);
     return ((size_t)s.pairs() * per_pair + 255) & ~(size_t)255;
 }
 
@@ -552,13 +583,17 @@ void launch_backward_coef_sorted(const LayerShape &s, const void *records, void 
     const size_t blocks = (size_t)stream_blocks(s.batch);
     const size_t cells = (size_t)s.G * s.G;
     int32_t *block_start = chunk_cell + K * (S / kChunk);
-    int32_t *seg_count = block_start + K * (blocks + 1);
+    int32_t *block_size = block_start + K * (blocks + 1);
+    int32_t *seg_count = block_size + K * blocks;
     int32_t *cell_start = seg_count + K * nseg * cells;
     int32_t *cell_rep = cell_start + K * blocks * cells;
     const dim3 seg_grid((unsigned)nseg, (unsigned)K);
     sort_count_kernel<<<seg_grid, kSortSegThreads, 0, stream>>>(rec_node, seg_count, cell_rep, s.batch, s.G);
-    sort_layout_kernel<<<(unsigned)K, kSortThreads, 0, stream>>>(seg_count, cell_start, cell_rep, sorted_w, sorted_n,
-                                                               chunk_cell, block_start, s.batch, s.G, (int)nseg);
+    const dim3 block_grid((unsigned)K, (unsigned)blocks);
+    sort_block_size_kernel<<<block_grid, kSortSegThreads, 0, stream>>>(seg_count, block_size, s.batch, s.G, (int)nseg);
+    sort_layout_kernel<<<block_grid, kSortThreads, 0, stream>>>(seg_count, cell_start, cell_rep, sorted_w, sorted_n,
+                                                              chunk_cell, block_start, block_size, s.batch, s.G,
+                                                              (int)nseg);
     sort_scatter_kernel<<<seg_grid, kSortSegThreads, 0, stream>>>(rec_node, rec_u, rec_v, seg_count, cell_start,
                                                                  sorted_w, sorted_n, s.batch, s.G);
     CoefGradArgs a;
