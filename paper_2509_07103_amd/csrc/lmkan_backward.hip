@@ -259,7 +259,14 @@ __global__ __launch_bounds__(kSortThreads) void sort_layout_kernel(int32_t *__re
     }
 }
 
-// 3: scatter of one batch segment
+// 3: scatter of one batch segment.  The segment is first ordered by cell inside LDS, so that
+// consecutive threads then write consecutive stream positions (the samples of one cell that
+// lie in this segment form one contiguous run of the stream).
+__host__ __device__ inline size_t scatter_lds_bytes(int G)
+{
+    return (size_t)G * G * 3 * sizeof(int) + (size_t)kSortSeg * (2 * sizeof(float) + 3 * sizeof(unsigned short));
+}
+
 __global__ __launch_bounds__(kSortSegThreads) void sort_scatter_kernel(const int32_t *__restrict__ rec_node,
                                                                       const float *__restrict__ rec_u,
                                                                       const float *__restrict__ rec_v,
@@ -269,29 +276,74 @@ __global__ __launch_bounds__(kSortSegThreads) void sort_scatter_kernel(const int
                                                                       int32_t *__restrict__ sorted_n, int64_t B,
                                                                       int G)
 {
-    __shared__ int s_cursor[kMaxCells];
+    extern __shared__ int s_dyn[];
+    __shared__ int s_wave[kSortSegThreads / 64];
     const int seg = blockIdx.x, nseg = gridDim.x, k = blockIdx.y;
     const int cells = G * G;
+    int *s_cnt = s_dyn;              // population of the cell inside this segment
+    int *s_lstart = s_cnt + cells;   // its first position in the segment's own cell order
+    int *s_gbase = s_lstart + cells; // its first position in the stream
+    float *s_u = reinterpret_cast<float *>(s_gbase + cells);
+    float *s_v = s_u + kSortSeg;
+    unsigned short *s_cell = reinterpret_cast<unsigned short *>(s_v + kSortSeg);
+    unsigned short *s_rank = s_cell + kSortSeg;
+    unsigned short *s_order = s_rank + kSortSeg;
     const int blocks = stream_blocks(B);
     const int blk = blocks > 1 ? seg / kSegPerBlock : 0;
     const int64_t S = stream_stride(B, G);
     const int32_t *off = seg_count + ((int64_t)k * nseg + seg) * cells;
-    for (int c = threadIdx.x; c < cells; c += blockDim.x)
-        s_cursor[c] = cell_start[((int64_t)k * blocks + blk) * cells + c] + off[c];
+    for (int c = threadIdx.x; c < cells; c += blockDim.x) {
+        s_cnt[c] = 0;
+        s_gbase[c] = cell_start[((int64_t)k * blocks + blk) * cells + c] + off[c];
+    }
     __syncthreads();
     const int64_t n0 = (int64_t)seg * kSortSeg;
-    const int64_t n1 = n0 + kSortSeg < B ? n0 + kSortSeg : B;
-    const int32_t *node_k = rec_node + (int64_t)k * B;
-    const float *u_k = rec_u + (int64_t)k * B;
-    const float *v_k = rec_v + (int64_t)k * B;
+    const int count = (int)((n0 + kSortSeg < B ? n0 + kSortSeg : B) - n0);
+    const int32_t *node_k = rec_node + (int64_t)k * B + n0;
+    const float *u_k = rec_u + (int64_t)k * B + n0;
+    const float *v_k = rec_v + (int64_t)k * B + n0;
+    for (int i = threadIdx.x; i < count; i += blockDim.x) {
+        const int c = cell_of_node(node_k[i], G);
+        s_cell[i] = (unsigned short)c;
+        s_rank[i] = (unsigned short)atomicAdd(&s_cnt[c], 1);
+        s_u[i] = u_k[i];
+        s_v[i] = v_k[i];
+    }
+    __syncthreads();
+    // exclusive scan of the populations: a run of consecutive cells per thread
+    {
+        const int per = (cells + kSortSegThreads - 1) / kSortSegThreads;
+        const int c0 = threadIdx.x * per, c1 = min(cells, c0 + per);
+        int mine = 0;
+        for (int c = c0; c < c1; ++c) mine += s_cnt[c];
+        int incl = mine;
+#pragma unroll
+        for (int d = 1; d < 64; d <<= 1) {
+            const int t = __shfl_up(incl, d, 64);
+            if ((threadIdx.x & 63) >= d) incl += t;
+        }
+        if ((threadIdx.x & 63) == 63) s_wave[threadIdx.x >> 6] = incl;
+        __syncthreads();
+        int run = incl - mine;
+        for (int w = 0; w < (int)(threadIdx.x >> 6); ++w) run += s_wave[w];
+        for (int c = c0; c < c1; ++c) {
+            s_lstart[c] = run;
+            run += s_cnt[c];
+        }
+    }
+    __syncthreads();
+    for (int i = threadIdx.x; i < count; i += blockDim.x) s_order[s_lstart[s_cell[i]] + s_rank[i]] = (unsigned short)i;
+    __syncthreads();
     f4v *out_w = sorted_w + (int64_t)k * S;
     int32_t *out_n = sorted_n + (int64_t)k * S;
-    for (int64_t n = n0 + threadIdx.x; n < n1; n += blockDim.x) {
-        const float u = u_k[n], v = v_k[n];
-        const int pos = atomicAdd(&s_cursor[cell_of_node(node_k[n], G)], 1);
+    for (int lp = threadIdx.x; lp < count; lp += blockDim.x) {
+        const int i = s_order[lp];
+        const int c = s_cell[i];
+        const int pos = s_gbase[c] + lp - s_lstart[c];
+        const float u = s_u[i], v = s_v[i];
         const float a_lo = 1.0f - u, b_lo = 1.0f - v;
         out_w[pos] = f4v{a_lo * b_lo, u * b_lo, a_lo * v, u * v};
-        out_n[pos] = (int32_t)n;
+        out_n[pos] = (int32_t)(n0 + i);
     }
 }
 
@@ -594,8 +646,18 @@ void launch_backward_coef_sorted(const LayerShape &s, const void *records, void 
     sort_layout_kernel<<<block_grid, kSortThreads, 0, stream>>>(seg_count, cell_start, cell_rep, sorted_w, sorted_n,
                                                               chunk_cell, block_start, block_size, s.batch, s.G,
                                                               (int)nseg);
-    sort_scatter_kernel<<<seg_grid, kSortSegThreads, 0, stream>>>(rec_node, rec_u, rec_v, seg_count, cell_start,
-                                                                 sorted_w, sorted_n, s.batch, s.G);
+    const size_t scatter_lds = scatter_lds_bytes(s.G);
+    if (scatter_lds > 64 * 1024) {
+        static bool attr_set = false;
+        if (!attr_set) {
+            (void)hipFuncSetAttribute(reinterpret_cast<const void *>(sort_scatter_kernel),
+                                      hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024 - 64);
+            attr_set = true;
+        }
+    }
+    sort_scatter_kernel<<<seg_grid, kSortSegThreads, scatter_lds, stream>>>(rec_node, rec_u, rec_v, seg_count,
+                                                                           cell_start, sorted_w, sorted_n, s.batch,
+                                                                           s.G);
     CoefGradArgs a;
     a.sorted_w = sorted_w;
     a.sorted_n = sorted_n;
