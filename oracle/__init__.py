@@ -88,6 +88,9 @@ class Oracle:
                                             C.c_int, _fp, _dp, C.c_int]
         L.oracle_backward_coef_pair.argtypes = [C.c_int64, C.c_int, C.c_int, C.c_int, C.c_int,
                                                 _fp, _fp, _dp]
+        L.oracle_hessian_reg_2d.restype = C.c_double
+        L.oracle_hessian_reg_2d.argtypes = [C.c_int, _dp, _dp, _dp]
+        L.oracle_hessian_reg.argtypes = [C.c_int, C.c_int, C.c_int, C.c_void_p, C.c_int, _dp, _dp]
 
     # ---- scalars and small pieces -------------------------------------
     def sigma(self, x: float) -> float:
@@ -203,6 +206,27 @@ class Oracle:
                                               _ptr(gPk, _dp)):
             raise ValueError("oracle_backward_coef_pair rejected its arguments")
         return gPk
+
+    def hessian_reg_2d(self, G: int, E: np.ndarray, p2: np.ndarray, want_grad: bool = False):
+        """Regulariser of one 2-D table p2[G+1][G+1] on the grid E (any increasing points)."""
+        E, p2 = _f64(E), _f64(p2)
+        assert E.shape == (G + 1,) and p2.shape == (G + 1, G + 1)
+        if not want_grad:
+            return self.lib.oracle_hessian_reg_2d(G, _ptr(E, _dp), _ptr(p2, _dp), None)
+        g = np.zeros((G + 1, G + 1), dtype=np.float64)
+        v = self.lib.oracle_hessian_reg_2d(G, _ptr(E, _dp), _ptr(p2, _dp), _ptr(g, _dp))
+        return v, g
+
+    def hessian_reg(self, P, G: int, dtype: int = F32, want_grad: bool = True):
+        """Regulariser of a layer (sum over pairs and outputs) and its gradient w.r.t. P."""
+        K, N_out = P.shape[2], P.shape[3]
+        P = self._coef(P, dtype, G, K, N_out)
+        value = np.zeros(1, dtype=np.float64)
+        grad = np.empty((G + 1, G + 1, K, N_out), dtype=np.float64) if want_grad else None
+        if self.lib.oracle_hessian_reg(2 * K, N_out, G, P.ctypes.data, dtype, _ptr(value, _dp),
+                                       _ptr(grad, _dp) if want_grad else None):
+            raise ValueError("oracle_hessian_reg rejected its arguments")
+        return float(value[0]), grad
 
     def backward_coef(self, x, gy, G: int) -> np.ndarray:
         """All pairs, assembled into the layout of Alg. 1: [G+1][G+1][K][N_out]."""

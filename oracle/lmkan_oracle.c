@@ -509,3 +509,91 @@ int oracle_backward_coef_pair(int64_t B, int N_in, int N_out, int G, int k, cons
     free(E32);
     return 0;
 }
+
+/* ------------------------------------------------------------------------
+ * Off-diagonal Hessian regulariser (Sec. 3.5, App. C).
+ *
+ * For one 2-D function with table p[a][b] on the grid E[0..G], at every node
+ * that has all its neighbours (a, b in [1, G-1]; the values at the ghost
+ * nodes enter as neighbours) the three finite-difference second derivatives
+ * of App. C are formed with the non-uniform spacings
+ *   hl = E[a] - E[a-1], hr = E[a+1] - E[a]   (and hb, hu along the second axis)
+ *   D11 = 2 (hl p[a+1][b] - (hl + hr) p[a][b] + hr p[a-1][b]) / (hl hr (hl + hr))
+ *   D22 = the same along b
+ *   D12 = (p[a+1][b+1] - p[a+1][b-1] - p[a-1][b+1] + p[a-1][b-1]) / ((hl + hr)(hb + hu))
+ *   H   = D11^2 + 2 D12^2 + D22^2
+ * and the function's term is the mean of H over those (G-1)^2 nodes.  The
+ * paper is silent on which nodes "all the grid points" are; this reading takes
+ * every node where the stencil exists.
+ *
+ * Returns the mean; if grad != NULL adds d(mean)/dp[a][b] into grad[a*(G+1)+b]
+ * (scatter form: each centre adds 2 D dD/dp to the nodes of its stencil).
+ * --------------------------------------------------------------------- */
+double oracle_hessian_reg_2d(int G, const double *E, const double *p, double *grad)
+{
+    const int W = G + 1;
+    const double inv_n = 1.0 / ((double)(G - 1) * (double)(G - 1));
+    double sum = 0.0;
+    for (int a = 1; a <= G - 1; ++a) {
+        const double hl = E[a] - E[a - 1], hr = E[a + 1] - E[a];
+        for (int b = 1; b <= G - 1; ++b) {
+            const double hb = E[b] - E[b - 1], hu = E[b + 1] - E[b];
+            const double d11 = 2.0 * (hl * p[(a + 1) * W + b] - (hl + hr) * p[a * W + b] + hr * p[(a - 1) * W + b]) /
+                               (hl * hr * (hl + hr));
+            const double d22 = 2.0 * (hb * p[a * W + b + 1] - (hb + hu) * p[a * W + b] + hu * p[a * W + b - 1]) /
+                               (hb * hu * (hb + hu));
+            const double d12 = (p[(a + 1) * W + b + 1] - p[(a + 1) * W + b - 1] - p[(a - 1) * W + b + 1] +
+                                p[(a - 1) * W + b - 1]) /
+                               ((hl + hr) * (hb + hu));
+            sum += d11 * d11 + 2.0 * d12 * d12 + d22 * d22;
+            if (grad != NULL) {
+                const double c11 = 2.0 * d11 * 2.0 / (hl * hr * (hl + hr)) * inv_n;
+                grad[(a + 1) * W + b] += c11 * hl;
+                grad[a * W + b] -= c11 * (hl + hr);
+                grad[(a - 1) * W + b] += c11 * hr;
+                const double c22 = 2.0 * d22 * 2.0 / (hb * hu * (hb + hu)) * inv_n;
+                grad[a * W + b + 1] += c22 * hb;
+                grad[a * W + b] -= c22 * (hb + hu);
+                grad[a * W + b - 1] += c22 * hu;
+                const double c12 = 4.0 * d12 / ((hl + hr) * (hb + hu)) * inv_n;
+                grad[(a + 1) * W + b + 1] += c12;
+                grad[(a + 1) * W + b - 1] -= c12;
+                grad[(a - 1) * W + b + 1] -= c12;
+                grad[(a - 1) * W + b - 1] += c12;
+            }
+        }
+    }
+    return sum * inv_n;
+}
+
+/* The regulariser of a whole layer: the sum of the 2-D terms over all pairs and outputs
+ * (App. C, last paragraph), on the float32-rounded sigma grid promoted to double (the grid
+ * every other function here uses).  P in the layout of Alg. 1, stored as `dtype`;
+ * grad, if not NULL, is [G+1][G+1][K][N_out] in double and is overwritten. */
+int oracle_hessian_reg(int N_in, int N_out, int G, const void *P, int dtype, double *value, double *grad)
+{
+    if (N_in < 2 || (N_in & 1) || N_out < 1 || G < 3) return 1;
+    const int K = N_in / 2, W = G + 1;
+    float *E32 = (float *)malloc((size_t)W * sizeof(float));
+    double *E = (double *)malloc((size_t)W * sizeof(double));
+    double *p = (double *)malloc((size_t)W * W * sizeof(double));
+    double *g = (double *)malloc((size_t)W * W * sizeof(double));
+    if (!E32 || !E || !p || !g || oracle_grid_f32(G, E32) != 0) {
+        free(E32); free(E); free(p); free(g);
+        return 1;
+    }
+    for (int a = 0; a < W; ++a) E[a] = (double)E32[a];
+    double total = 0.0;
+    for (int k = 0; k < K; ++k) {
+        for (int j = 0; j < N_out; ++j) {
+            for (int n = 0; n < W * W; ++n) p[n] = coef_at(P, dtype, ((size_t)n * K + k) * N_out + j);
+            if (grad != NULL) memset(g, 0, (size_t)W * W * sizeof(double));
+            total += oracle_hessian_reg_2d(G, E, p, grad != NULL ? g : NULL);
+            if (grad != NULL)
+                for (int n = 0; n < W * W; ++n) grad[((size_t)n * K + k) * N_out + j] = g[n];
+        }
+    }
+    *value = total;
+    free(E32); free(E); free(p); free(g);
+    return 0;
+}
