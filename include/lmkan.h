@@ -169,6 +169,25 @@ lmkan_status lmkan_backward(const lmkan_desc *desc, int64_t batch, const float *
                             float *grad_coef_dev, void *workspace_dev, size_t workspace_bytes,
                             void *stream);
 
+/*
+ * Off-diagonal Hessian regulariser of the layer (Sec. 3.5, App. C).  For every 2-D
+ * function (pair, output) and every table node with a full stencil (both indices
+ * in [1, G-1]; ghost-node coefficients enter as neighbours) App. C's finite
+ * differences on the non-uniform grid give D11, D22, D12 and
+ * H = D11^2 + 2 D12^2 + D22^2; a function contributes the mean of H over those
+ * (G-1)^2 nodes, the layer the sum over its functions.
+ *   coef_dev      coefficients in desc->coef_dtype / desc->coef_layout
+ *   value_dev     one double on the device, overwritten with the layer's value
+ *                 (unscaled); NULL skips it
+ *   grad_coef_dev float32 in the layout of Alg. 1: receives scale * d value / d coef,
+ *                 overwritten, or added to when LMKAN_FLAG_ACCUMULATE_GRAD_COEF is
+ *                 set (so it can share the buffer lmkan_backward wrote); NULL skips it
+ * The value is a sum of per-wave partial sums through a double atomic: its last
+ * bits can differ from run to run.  No workspace.
+ */
+lmkan_status lmkan_hessian_reg(const lmkan_desc *desc, const void *coef_dev, float scale, double *value_dev,
+                               float *grad_coef_dev, void *stream);
+
 #ifdef __cplusplus
 }
 #endif

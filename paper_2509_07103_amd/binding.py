@@ -93,6 +93,8 @@ def lib() -> C.CDLL:
     L.lmkan_forward.restype = C.c_int
     L.lmkan_forward.argtypes = [dp, C.c_int64, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p,
                                 C.c_size_t, C.c_void_p]
+    L.lmkan_hessian_reg.restype = C.c_int
+    L.lmkan_hessian_reg.argtypes = [dp, C.c_void_p, C.c_float, C.c_void_p, C.c_void_p, C.c_void_p]
     L.lmkan_backward.restype = C.c_int
     L.lmkan_backward.argtypes = [dp, C.c_int64, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p,
                                  C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]
@@ -220,3 +222,19 @@ def lmkan_backward(desc: LayerDesc, x: torch.Tensor, coef: torch.Tensor | None, 
                                 ws.data_ptr() if ws is not None else None, wsz, _stream(stream)),
            "lmkan_backward")
     return (grad_x if need_grad_x else None), (grad_coef if need_grad_coef else None)
+
+
+def lmkan_hessian_reg(desc: LayerDesc, coef: torch.Tensor, scale: float = 1.0, need_value: bool = True,
+                      need_grad: bool = True, grad_coef: torch.Tensor | None = None, stream=None):
+    """Returns (value tensor of one float64 or None, scale * gradient float32 in the layout of Alg. 1 or None)."""
+    cp = _coef_ptr(desc, coef)
+    value = torch.empty(1, dtype=torch.float64, device=coef.device) if need_value else None
+    if need_grad and grad_coef is None:
+        if desc.flags & LMKAN_FLAG_ACCUMULATE_GRAD_COEF:
+            raise ValueError("accumulating into grad_coef needs an existing grad_coef tensor")
+        grad_coef = torch.empty(desc.coef_shape(), dtype=torch.float32, device=coef.device)
+    gcp = _dev(grad_coef, torch.float32, desc.coef_shape(), "grad_coef") if need_grad else None
+    _check(lib().lmkan_hessian_reg(C.byref(desc.c()), cp, float(scale),
+                                   value.data_ptr() if need_value else None, gcp, _stream(stream)),
+           "lmkan_hessian_reg")
+    return value, (grad_coef if need_grad else None)

@@ -238,4 +238,21 @@ lmkan_status lmkan_backward(const lmkan_desc *desc, int64_t batch, const float *
     return launch_status();
 }
 
+lmkan_status lmkan_hessian_reg(const lmkan_desc *desc, const void *coef_dev, float scale, double *value_dev,
+                               float *grad_coef_dev, void *stream)
+{
+    const lmkan_status st = check_desc(desc);
+    if (st != LMKAN_OK) return st;
+    if (!coef_dev) return LMKAN_ERR_NULL;
+    if (!value_dev && !grad_coef_dev) return LMKAN_OK;
+    if (!aligned(coef_dev, dtype_size(desc->coef_dtype)) || (value_dev && !aligned(value_dev, 8)) ||
+        (grad_coef_dev && !aligned(grad_coef_dev, 4)))
+        return LMKAN_ERR_ALIGN;
+    GridTab tab;
+    build_grid(desc->grid, &tab);
+    launch_hessian_reg(shape_of(desc, 0), tab, coef_dev, scale, value_dev, grad_coef_dev,
+                       (desc->flags & LMKAN_FLAG_ACCUMULATE_GRAD_COEF) != 0, static_cast<hipStream_t>(stream));
+    return launch_status();
+}
+
 }  // extern "C"

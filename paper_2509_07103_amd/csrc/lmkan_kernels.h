@@ -81,4 +81,9 @@ bool coef_sorted_applicable(const LayerShape &s, const float *gy, const float *g
 void launch_backward_coef_sorted(const LayerShape &s, const void *records, void *sorted, const float *gy,
                                  float *gcoef, bool accumulate, hipStream_t stream);
 
+// Hessian regulariser (lmkan_hessian.hip): value (double, overwritten; may be null) and
+// scale * gradient (float32, layout of Alg. 1; overwritten or added to; may be null).
+void launch_hessian_reg(const LayerShape &s, const GridTab &tab, const void *coef, float scale, double *value,
+                        float *grad, bool accumulate, hipStream_t stream);
+
 }  // namespace lmkan

@@ -229,3 +229,44 @@ def test_results_do_not_depend_on_the_stream(dev, oracle):
     s.synchronize()
     torch.cuda.synchronize()
     assert torch.equal(y0, y1)
+
+
+# ---- Hessian regulariser (Sec. 3.5, App. C) ---------------------------------------------------
+@pytest.mark.parametrize("layout", [pkg.LMKAN_LAYOUT_PAPER, pkg.LMKAN_LAYOUT_PACKED])
+@pytest.mark.parametrize("storage", ["f32", "f16", "bf16"])
+@pytest.mark.parametrize("shape", [(4, 3, 3), (6, 70, 4), (18, 132, 16), (8, 200, 33), (6, 5, 64)])
+def test_hessian_reg_matches_oracle(dev, oracle, shape, storage, layout):
+    n_in, n_out, G = shape
+    g = torch.Generator(device="cpu").manual_seed(71)
+    P = (torch.randn((G + 1, G + 1, n_in // 2, n_out), generator=g) * 0.1).to(dev)
+    desc = _desc(n_in, n_out, G, storage, layout)
+    Ps, Pdev = _stored(P, storage, desc, layout)
+    value, grad = pkg.lmkan_hessian_reg(desc, Pdev, scale=0.5)
+    torch.cuda.synchronize()
+    want_v, want_g = oracle.hessian_reg(bits(Ps), G, dtype=ORACLE_DTYPE[storage])
+    assert float(value.cpu()[0]) == pytest.approx(want_v, rel=1e-5)
+    got = grad.cpu().numpy()
+    for k in range(n_in // 2):
+        assert pair_slice_rel_err(got[:, :, k, :], 0.5 * want_g[:, :, k, :]) <= TOL_F32
+    # accumulate on top of an existing gradient; value alone; gradient alone
+    acc = torch.full_like(grad, 0.25)
+    dacc = _desc(n_in, n_out, G, storage, layout, flags=pkg.LMKAN_FLAG_ACCUMULATE_GRAD_COEF)
+    v2, _ = pkg.lmkan_hessian_reg(dacc, Pdev, scale=0.5, grad_coef=acc)
+    only_v, none = pkg.lmkan_hessian_reg(desc, Pdev, need_grad=False)
+    torch.cuda.synchronize()
+    assert none is None
+    assert np.abs(acc.cpu().numpy() - (0.5 * want_g + 0.25)).max() <= 2e-5 * max(1.0, np.abs(want_g).max())
+    assert float(v2.cpu()[0]) == pytest.approx(want_v, rel=1e-5)
+    assert float(only_v.cpu()[0]) == pytest.approx(want_v, rel=1e-5)
+
+
+def test_hessian_reg_is_zero_on_linear_tables(dev, oracle):
+    n_in, n_out, G = 6, 40, 12
+    E = torch.from_numpy(oracle.grid_f32(G).astype(np.float32))
+    lin = 0.3 + 1.5 * E[:, None] - 0.7 * E[None, :]
+    P = lin[:, :, None, None].expand(G + 1, G + 1, n_in // 2, n_out).contiguous().to(dev)
+    value, grad = pkg.lmkan_hessian_reg(_desc(n_in, n_out, G), P)
+    torch.cuda.synchronize()
+    # float32 second differences of O(1) values over spacings down to 0.1: rounding only
+    assert float(value.cpu()[0]) < 1e-6 * n_in * n_out
+    assert float(grad.abs().max()) < 1e-2
