@@ -204,6 +204,19 @@ def main():
         "roofline": roofline,
     }
 
+    # ---- Hessian regulariser of the same table (Sec. 3.5): value + gradient, HBM-bound ----------
+    hval = torch.empty(1, dtype=torch.float64, device=dev)
+
+    def hessian():
+        st = L.lmkan_hessian_reg(C.byref(d), P_packed.data_ptr(), 1.0, hval.data_ptr(), gP.data_ptr(), stream)
+        assert st == 0, pkg.lmkan_status_string(st)
+
+    hess_ms = event_ms(hessian, reps)
+    hess_bytes = (w.grid + 1) ** 2 * K * n_out * (s_bytes + 4)      # table read once, gradient written once
+    out["hessian_reg"] = {"ms": round(hess_ms, 4), "GBps": round(hess_bytes / (hess_ms * 1e-3) / 1e9, 1),
+                          "vs_hbm_peak": round(hess_bytes / (hess_ms * 1e-3) / 1e9 / PEAK_HBM_GBS, 3),
+                          "note": "value + gradient of the off-diagonal Hessian regulariser; not part of the step"}
+
     if args.calibrate_copy:
         src = torch.empty(1 << 28, dtype=torch.float32, device=dev).normal_()
         dst = torch.empty_like(src)

@@ -116,6 +116,21 @@ def test_cfg3_headline(dev, oracle, storage):
     _check_layer(wl.CFG3, storage, dev, oracle, n_rows=256 if storage == "f32" else 128, n_pairs=8)
 
 
+def test_cfg3_hessian_regulariser(dev, oracle):
+    """The regulariser over the whole 606 MB table; the oracle walks all 524288 functions."""
+    w = wl.CFG3
+    P = wl.make_coef(w, dev)
+    paper, packed = _descs(w, "f32")
+    Pp = pkg.lmkan_pack(paper, P)
+    value, grad = pkg.lmkan_hessian_reg(packed, Pp, scale=1.0)
+    torch.cuda.synchronize()
+    want_v, want_g = oracle.hessian_reg(P.cpu().numpy(), w.grid)
+    assert float(value.cpu()[0]) == pytest.approx(want_v, rel=1e-5)
+    got = grad.cpu().numpy()
+    for k in np.random.default_rng(300).choice(w.n_in // 2, size=16, replace=False):
+        assert pair_slice_rel_err(got[:, :, int(k), :], want_g[:, :, int(k), :]) <= TOL_F32
+
+
 def test_cfg4_rows(dev, oracle):
     _check_layer(wl.CFG4, "f32", dev, oracle, n_rows=1024, n_pairs=4)
 
