@@ -88,6 +88,7 @@ class Oracle:
                                             C.c_int, _fp, _dp, C.c_int]
         L.oracle_backward_coef_pair.argtypes = [C.c_int64, C.c_int, C.c_int, C.c_int, C.c_int,
                                                 _fp, _fp, _dp]
+        L.oracle_fold.argtypes = [C.c_int, C.c_int, C.c_int, _fp, C.c_double, _dp, _dp, _dp, _dp, _dp]
         L.oracle_hessian_reg_2d.restype = C.c_double
         L.oracle_hessian_reg_2d.argtypes = [C.c_int, _dp, _dp, _dp]
         L.oracle_hessian_reg.argtypes = [C.c_int, C.c_int, C.c_int, C.c_void_p, C.c_int, _dp, _dp]
@@ -206,6 +207,19 @@ class Oracle:
                                               _ptr(gPk, _dp)):
             raise ValueError("oracle_backward_coef_pair rejected its arguments")
         return gPk
+
+    def fold(self, P, G: int, gamma: float = 1.0, lin_w=None, lin_b=None, scale=None, shift=None) -> np.ndarray:
+        """Table of the single layer equal to  scale * (gamma lmKAN + Linear(ReLU(x))) + shift  (float64)."""
+        P = _f32(P)
+        K, N_out = P.shape[2], P.shape[3]
+        opt = lambda v: (None, None) if v is None else (lambda arr: (arr, _ptr(arr, _dp)))(_f64(v))
+        (w, wp), (b, bp), (s, sp), (t, tp) = opt(lin_w), opt(lin_b), opt(scale), opt(shift)
+        if w is not None:
+            assert w.shape == (N_out, 2 * K)
+        out = np.empty(P.shape, dtype=np.float64)
+        if self.lib.oracle_fold(2 * K, N_out, G, _ptr(P, _fp), float(gamma), wp, bp, sp, tp, _ptr(out, _dp)):
+            raise ValueError("oracle_fold rejected its arguments")
+        return out
 
     def hessian_reg_2d(self, G: int, E: np.ndarray, p2: np.ndarray, want_grad: bool = False):
         """Regulariser of one 2-D table p2[G+1][G+1] on the grid E (any increasing points)."""

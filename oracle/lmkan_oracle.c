@@ -597,3 +597,49 @@ int oracle_hessian_reg(int N_in, int N_out, int G, const void *P, int dtype, dou
     free(E32); free(E); free(p); free(g);
     return 0;
 }
+
+/* ------------------------------------------------------------------------
+ * Inference-time folds (App. E "Preconditioning", Eq. 4b; App. F.1).
+ *
+ * A ReLU-first preconditioned layer  y = gamma lmKAN(x) + Linear(ReLU(x))  followed by an
+ * evaluation-mode batch normalisation  y' = s_j y_j + t_j  is again one lmKAN layer:
+ *   f_kj <- gamma f_kj + Wl[j][2k] ReLU(x1) + Wl[j][2k+1] ReLU(x2)
+ * is exact when 0 is a grid point (G even), because a piecewise-linear table with a node at
+ * the kink reproduces ReLU, and a per-output constant c_j can be added to the table of any
+ * one pair (here pair 0) because the four weights of a cell sum to one.  In coefficients:
+ *   P'[a][b][k][j] = s_j (gamma P[a][b][k][j] + Wl[j][2k] max(E[a],0) + Wl[j][2k+1] max(E[b],0))
+ *                    + [k == 0] (s_j bias_j + t_j)
+ * on the float32-rounded grid E (the grid the layer is evaluated on).  lin_w is
+ * [N_out][N_in] row-major, any of lin_w / lin_b / scale / shift may be NULL (absent
+ * term; scale defaults to 1).  P and P_out are float32 / double in the layout of Alg. 1.
+ * --------------------------------------------------------------------- */
+int oracle_fold(int N_in, int N_out, int G, const float *P, double gamma, const double *lin_w,
+                const double *lin_b, const double *scale, const double *shift, double *P_out)
+{
+    if (N_in < 2 || (N_in & 1) || N_out < 1 || G < 3) return 1;
+    const int K = N_in / 2, W = G + 1;
+    float *E32 = (float *)malloc((size_t)W * sizeof(float));
+    if (E32 == NULL || oracle_grid_f32(G, E32) != 0) {
+        free(E32);
+        return 1;
+    }
+    for (int a = 0; a < W; ++a) {
+        const double ra = E32[a] > 0.0f ? (double)E32[a] : 0.0;
+        for (int b = 0; b < W; ++b) {
+            const double rb = E32[b] > 0.0f ? (double)E32[b] : 0.0;
+            for (int k = 0; k < K; ++k) {
+                for (int j = 0; j < N_out; ++j) {
+                    const size_t idx = p_index(G, K, N_out, a, b, k, j);
+                    double v = gamma * (double)P[idx];
+                    if (lin_w != NULL) v += lin_w[(size_t)j * N_in + 2 * k] * ra + lin_w[(size_t)j * N_in + 2 * k + 1] * rb;
+                    const double s = scale != NULL ? scale[j] : 1.0;
+                    v *= s;
+                    if (k == 0) v += s * (lin_b != NULL ? lin_b[j] : 0.0) + (shift != NULL ? shift[j] : 0.0);
+                    P_out[idx] = v;
+                }
+            }
+        }
+    }
+    free(E32);
+    return 0;
+}
