@@ -188,6 +188,28 @@ lmkan_status lmkan_backward(const lmkan_desc *desc, int64_t batch, const float *
 lmkan_status lmkan_hessian_reg(const lmkan_desc *desc, const void *coef_dev, float scale, double *value_dev,
                                float *grad_coef_dev, void *stream);
 
+/*
+ * Inference-time folds, in place on a float32 table (App. E Eq. 4b, App. F.1).
+ * The ReLU-first preconditioned layer followed by an evaluation-mode batch
+ * normalisation,
+ *     y'_j = s_j (gamma lmKAN(x) + Linear(ReLU(x)))_j + t_j,
+ * becomes a plain lmKAN layer with
+ *     P'[a][b][k][j] = s_j (gamma P[a][b][k][j] + Wl[j][2k] max(E[a],0) + Wl[j][2k+1] max(E[b],0))
+ *                      + [k == 0] (s_j bias_j + t_j).
+ * The ReLU part is exact only when 0 is a grid point (grid even); the library does
+ * not check this, and the other terms are exact for any grid.
+ *   coef_dev       float32 table in desc->coef_layout, overwritten
+ *                  (LMKAN_ERR_UNSUPPORTED for 16-bit tables: fold first, round after)
+ *   gamma          weight of the lmKAN term (1 leaves it as it is)
+ *   lin_w_dev      [n_out][n_in] float32 row-major, weight of Linear; NULL = no such term
+ *   lin_b_dev      [n_out] bias of Linear; NULL = none
+ *   out_scale_dev  [n_out] s_j; NULL = 1
+ *   out_shift_dev  [n_out] t_j; NULL = 0
+ */
+lmkan_status lmkan_fold(const lmkan_desc *desc, void *coef_dev, float gamma, const float *lin_w_dev,
+                        const float *lin_b_dev, const float *out_scale_dev, const float *out_shift_dev,
+                        void *stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -2,7 +2,7 @@
 from .binding import (LMKAN_BF16, LMKAN_F16, LMKAN_F32, LMKAN_FLAG_ACCUMULATE_GRAD_COEF,
                       LMKAN_LAYOUT_PACKED, LMKAN_LAYOUT_PAPER, LMKAN_MAX_GRID, LMKAN_PACK_TILE,
                       LayerDesc, LmkanError, lib, lmkan_backward, lmkan_forward, lmkan_grid,
-                      lmkan_hessian_reg,
+                      lmkan_fold, lmkan_hessian_reg,
                       lmkan_locate, lmkan_pack, lmkan_packed_bytes, lmkan_status_string,
                       lmkan_version, lmkan_workspace_bytes)
 

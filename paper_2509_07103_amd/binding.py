@@ -93,6 +93,8 @@ def lib() -> C.CDLL:
     L.lmkan_forward.restype = C.c_int
     L.lmkan_forward.argtypes = [dp, C.c_int64, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p,
                                 C.c_size_t, C.c_void_p]
+    L.lmkan_fold.restype = C.c_int
+    L.lmkan_fold.argtypes = [dp, C.c_void_p, C.c_float, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]
     L.lmkan_hessian_reg.restype = C.c_int
     L.lmkan_hessian_reg.argtypes = [dp, C.c_void_p, C.c_float, C.c_void_p, C.c_void_p, C.c_void_p]
     L.lmkan_backward.restype = C.c_int
@@ -238,3 +240,16 @@ def lmkan_hessian_reg(desc: LayerDesc, coef: torch.Tensor, scale: float = 1.0, n
                                    value.data_ptr() if need_value else None, gcp, _stream(stream)),
            "lmkan_hessian_reg")
     return value, (grad_coef if need_grad else None)
+
+
+def lmkan_fold(desc: LayerDesc, coef: torch.Tensor, gamma: float = 1.0, lin_w: torch.Tensor | None = None,
+               lin_b: torch.Tensor | None = None, out_scale: torch.Tensor | None = None,
+               out_shift: torch.Tensor | None = None, stream=None) -> torch.Tensor:
+    """Folds, in place, the ReLU-first preconditioning and an output affine into a float32 table."""
+    cp = _coef_ptr(desc, coef)
+    wp = _dev(lin_w, torch.float32, (desc.n_out, desc.n_in), "lin_w") if lin_w is not None else None
+    bp = _dev(lin_b, torch.float32, (desc.n_out,), "lin_b") if lin_b is not None else None
+    sp = _dev(out_scale, torch.float32, (desc.n_out,), "out_scale") if out_scale is not None else None
+    tp = _dev(out_shift, torch.float32, (desc.n_out,), "out_shift") if out_shift is not None else None
+    _check(lib().lmkan_fold(C.byref(desc.c()), cp, float(gamma), wp, bp, sp, tp, _stream(stream)), "lmkan_fold")
+    return coef

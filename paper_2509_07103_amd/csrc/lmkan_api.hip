@@ -255,4 +255,22 @@ lmkan_status lmkan_hessian_reg(const lmkan_desc *desc, const void *coef_dev, flo
     return launch_status();
 }
 
+lmkan_status lmkan_fold(const lmkan_desc *desc, void *coef_dev, float gamma, const float *lin_w_dev,
+                        const float *lin_b_dev, const float *out_scale_dev, const float *out_shift_dev,
+                        void *stream)
+{
+    const lmkan_status st = check_desc(desc);
+    if (st != LMKAN_OK) return st;
+    if (desc->coef_dtype != LMKAN_F32) return LMKAN_ERR_UNSUPPORTED;  // fold first, round to 16 bits after
+    if (!coef_dev) return LMKAN_ERR_NULL;
+    if (!aligned(coef_dev, 4) || !aligned(lin_w_dev, 4) || !aligned(lin_b_dev, 4) || !aligned(out_scale_dev, 4) ||
+        !aligned(out_shift_dev, 4))
+        return LMKAN_ERR_ALIGN;
+    GridTab tab;
+    build_grid(desc->grid, &tab);
+    launch_fold(shape_of(desc, 0), tab, static_cast<float *>(coef_dev), gamma, lin_w_dev, lin_b_dev, out_scale_dev,
+                out_shift_dev, static_cast<hipStream_t>(stream));
+    return launch_status();
+}
+
 }  // extern "C"

@@ -81,6 +81,10 @@ bool coef_sorted_applicable(const LayerShape &s, const float *gy, const float *g
 void launch_backward_coef_sorted(const LayerShape &s, const void *records, void *sorted, const float *gy,
                                  float *gcoef, bool accumulate, hipStream_t stream);
 
+// In-place inference folds of a float32 table (lmkan_fold.hip); absent terms are null pointers.
+void launch_fold(const LayerShape &s, const GridTab &tab, float *coef, float gamma, const float *lin_w,
+                 const float *lin_b, const float *scale, const float *shift, hipStream_t stream);
+
 // Hessian regulariser (lmkan_hessian.hip): value (double, overwritten; may be null) and
 // scale * gradient (float32, layout of Alg. 1; overwritten or added to; may be null).
 void launch_hessian_reg(const LayerShape &s, const GridTab &tab, const void *coef, float scale, double *value,

@@ -28,7 +28,7 @@ def test_library_exports_every_declared_symbol():
     declared = _declared_functions()
     assert {"lmkan_forward", "lmkan_backward", "lmkan_locate", "lmkan_pack", "lmkan_grid",
             "lmkan_version", "lmkan_status_string", "lmkan_packed_bytes",
-            "lmkan_workspace_bytes", "lmkan_hessian_reg"} <= declared
+            "lmkan_workspace_bytes", "lmkan_hessian_reg", "lmkan_fold"} <= declared
     for name in declared:
         assert hasattr(L, name), name
         assert hasattr(pkg, name), f"python binding lacks {name}"

@@ -270,3 +270,35 @@ def test_hessian_reg_is_zero_on_linear_tables(dev, oracle):
     # float32 second differences of O(1) values over spacings down to 0.1: rounding only
     assert float(value.cpu()[0]) < 1e-6 * n_in * n_out
     assert float(grad.abs().max()) < 1e-2
+
+
+# ---- inference-time folds (App. E Eq. 4b, App. F.1) -------------------------------------------
+@pytest.mark.parametrize("layout", [pkg.LMKAN_LAYOUT_PAPER, pkg.LMKAN_LAYOUT_PACKED])
+@pytest.mark.parametrize("shape", [(4, 3, 4), (10, 70, 8), (34, 132, 16)])
+def test_fold_matches_oracle_and_the_unfolded_layer(dev, oracle, shape, layout):
+    n_in, n_out, G = shape
+    g = torch.Generator(device="cpu").manual_seed(81)
+    P = torch.randn((G + 1, G + 1, n_in // 2, n_out), generator=g) * 0.1
+    lin_w = torch.randn((n_out, n_in), generator=g) * 0.3
+    lin_b = torch.randn((n_out,), generator=g)
+    scale = torch.rand((n_out,), generator=g) + 0.5
+    shift = torch.randn((n_out,), generator=g)
+    x = (torch.randn((200, n_in), generator=g) * 2.0).to(dev)
+    desc = _desc(n_in, n_out, G, "f32", layout)
+    _, table = _stored(P.to(dev), "f32", desc, layout)
+    table = table.clone()
+    y_plain = pkg.lmkan_forward(desc, x, table)
+    pkg.lmkan_fold(desc, table, 0.3, lin_w.to(dev), lin_b.to(dev), scale.to(dev), shift.to(dev))
+    y_folded = pkg.lmkan_forward(desc, x, table)
+    torch.cuda.synchronize()
+    # the folded table itself against the oracle's (paper layout only: it can be read back as is)
+    want_table = oracle.fold(P.numpy(), G, 0.3, lin_w.numpy(), lin_b.numpy(), scale.numpy(), shift.numpy())
+    if layout == pkg.LMKAN_LAYOUT_PAPER:
+        got = table.cpu().numpy().astype(np.float64)
+        assert np.abs(got - want_table).max() <= 1e-6 * np.abs(want_table).max()
+    # and the identity it stands for: one folded layer == scale (gamma layer + Linear(ReLU x)) + shift
+    want_y = scale.to(dev) * (0.3 * y_plain + torch.relu(x) @ lin_w.to(dev).T + lin_b.to(dev)) + shift.to(dev)
+    assert rowwise_rel_err(y_folded.cpu().numpy(), want_y.double().cpu().numpy()) <= 2e-5
+    # the oracle's forward on the oracle's folded table agrees too
+    want = oracle.forward(x.cpu().numpy(), want_table.astype(np.float32), G)
+    assert rowwise_rel_err(y_folded.cpu().numpy(), want) <= TOL_F32
