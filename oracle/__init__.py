@@ -92,6 +92,8 @@ class Oracle:
         L.oracle_hessian_reg_2d.restype = C.c_double
         L.oracle_hessian_reg_2d.argtypes = [C.c_int, _dp, _dp, _dp]
         L.oracle_hessian_reg.argtypes = [C.c_int, C.c_int, C.c_int, C.c_void_p, C.c_int, _dp, _dp]
+        L.oracle_conv2d_patches.argtypes = [C.c_int] * 7 + [_fp, _fp]
+        L.oracle_conv2d_patches_adjoint.argtypes = [C.c_int] * 7 + [_dp, _dp]
 
     # ---- scalars and small pieces -------------------------------------
     def sigma(self, x: float) -> float:
@@ -241,6 +243,52 @@ class Oracle:
                                        _ptr(grad, _dp) if want_grad else None):
             raise ValueError("oracle_hessian_reg rejected its arguments")
         return float(value[0]), grad
+
+    # ---- convolution = fully connected layer on patches (Sec. 5) -------
+
+    @staticmethod
+    def conv2d_out_hw(H: int, W: int, kh: int, kw: int, stride: int):
+        return (H - kh) // stride + 1, (W - kw) // stride + 1
+
+    def conv2d_patches(self, x, kh: int, kw: int, stride: int) -> np.ndarray:
+        """x[N][H][W][C] -> patches[N*OH*OW][kh*kw*C] (float32 copy of the inputs, no arithmetic)."""
+        x = _f32(x)
+        N, H, W, Cc = x.shape
+        OH, OW = self.conv2d_out_hw(H, W, kh, kw, stride)
+        out = np.empty((N * OH * OW, kh * kw * Cc), dtype=np.float32)
+        if self.lib.oracle_conv2d_patches(N, H, W, Cc, kh, kw, stride, _ptr(x, _fp), _ptr(out, _fp)):
+            raise ValueError("oracle_conv2d_patches rejected its arguments")
+        return out
+
+    def conv2d_patches_adjoint(self, g_patches, shape, kh: int, kw: int, stride: int) -> np.ndarray:
+        """Gradient w.r.t. the image from the gradient w.r.t. its patches (float64)."""
+        N, H, W, Cc = shape
+        g = _f64(g_patches)
+        OH, OW = self.conv2d_out_hw(H, W, kh, kw, stride)
+        assert g.shape == (N * OH * OW, kh * kw * Cc)
+        out = np.empty((N, H, W, Cc), dtype=np.float64)
+        if self.lib.oracle_conv2d_patches_adjoint(N, H, W, Cc, kh, kw, stride, _ptr(g, _dp), _ptr(out, _dp)):
+            raise ValueError("oracle_conv2d_patches_adjoint rejected its arguments")
+        return out
+
+    def conv2d_forward(self, x, P, G: int, kh: int, kw: int, stride: int, dtype: int = F32,
+                       threads: int = 1) -> np.ndarray:
+        """y[N][OH][OW][C_out]: the layer applied to every window."""
+        N, H, W, _ = np.shape(x)
+        OH, OW = self.conv2d_out_hw(H, W, kh, kw, stride)
+        y = self.forward(self.conv2d_patches(x, kh, kw, stride), P, G, dtype=dtype, threads=threads)
+        return y.reshape(N, OH, OW, -1)
+
+    def conv2d_backward_input(self, x, P, gy, G: int, kh: int, kw: int, stride: int, dtype: int = F32,
+                              threads: int = 1) -> np.ndarray:
+        shape = np.shape(x)
+        gy2 = _f32(gy).reshape(-1, np.shape(gy)[-1])
+        gp = self.backward_input(self.conv2d_patches(x, kh, kw, stride), P, gy2, G, dtype=dtype, threads=threads)
+        return self.conv2d_patches_adjoint(gp, shape, kh, kw, stride)
+
+    def conv2d_backward_coef(self, x, gy, G: int, kh: int, kw: int, stride: int) -> np.ndarray:
+        gy2 = _f32(gy).reshape(-1, np.shape(gy)[-1])
+        return self.backward_coef(self.conv2d_patches(x, kh, kw, stride), gy2, G)
 
     def backward_coef(self, x, gy, G: int) -> np.ndarray:
         """All pairs, assembled into the layout of Alg. 1: [G+1][G+1][K][N_out]."""

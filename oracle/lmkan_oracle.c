@@ -643,3 +643,61 @@ int oracle_fold(int N_in, int N_out, int G, const float *P, double gamma, const 
     free(E32);
     return 0;
 }
+
+/* ---------------------------------------------------------------------------------------------
+ * Convolution as a fully connected layer on patches (Sec. 5, "lmKAN-based Convolutional Neural
+ * Networks": a kh x kw convolution is the map R^{kh kw C_in} -> R^{C_out} applied to every window;
+ * the paper casts it to a fully connected layer by memory reshaping).  The oracle does exactly
+ * that reshaping, written out, and then calls the fully connected functions above.
+ *
+ * Reading: channels-last image x[N][H][W][C]; no padding; window (oy, ox) covers rows
+ * oy*stride .. oy*stride + kh - 1 and columns ox*stride .. ox*stride + kw - 1; OH = (H - kh) / stride + 1
+ * (floor), likewise OW; patch row r = (img*OH + oy)*OW + ox; patch column e = (ky*kw + kx)*C + c.
+ * With C even, consecutive columns 2k, 2k+1 (one lmKAN pair) are two channels of one pixel.
+ * ------------------------------------------------------------------------------------------- */
+
+/* patches[r][e] = x[img][oy*stride + ky][ox*stride + kx][c] */
+int oracle_conv2d_patches(int N, int H, int W, int C, int kh, int kw, int stride, const float *x,
+                          float *patches)
+{
+    if (N < 0 || H < kh || W < kw || C < 1 || kh < 1 || kw < 1 || stride < 1) return 1;
+    const int OH = (H - kh) / stride + 1, OW = (W - kw) / stride + 1;
+    const size_t E = (size_t)kh * kw * C;
+    for (int img = 0; img < N; ++img)
+        for (int oy = 0; oy < OH; ++oy)
+            for (int ox = 0; ox < OW; ++ox) {
+                const size_t r = ((size_t)img * OH + oy) * OW + ox;
+                for (int ky = 0; ky < kh; ++ky)
+                    for (int kx = 0; kx < kw; ++kx)
+                        for (int c = 0; c < C; ++c) {
+                            const size_t e = ((size_t)ky * kw + kx) * C + c;
+                            const size_t src = (((size_t)img * H + (oy * stride + ky)) * W + (ox * stride + kx)) * C + c;
+                            patches[r * E + e] = x[src];
+                        }
+            }
+    return 0;
+}
+
+/* The chain rule through the reshaping above: every image element receives the sum of the patch
+ * gradients of all windows that contain it; elements outside every window receive zero. */
+int oracle_conv2d_patches_adjoint(int N, int H, int W, int C, int kh, int kw, int stride,
+                                  const double *g_patches, double *gx)
+{
+    if (N < 0 || H < kh || W < kw || C < 1 || kh < 1 || kw < 1 || stride < 1) return 1;
+    const int OH = (H - kh) / stride + 1, OW = (W - kw) / stride + 1;
+    const size_t E = (size_t)kh * kw * C;
+    for (size_t i = 0; i < (size_t)N * H * W * C; ++i) gx[i] = 0.0;
+    for (int img = 0; img < N; ++img)
+        for (int oy = 0; oy < OH; ++oy)
+            for (int ox = 0; ox < OW; ++ox) {
+                const size_t r = ((size_t)img * OH + oy) * OW + ox;
+                for (int ky = 0; ky < kh; ++ky)
+                    for (int kx = 0; kx < kw; ++kx)
+                        for (int c = 0; c < C; ++c) {
+                            const size_t e = ((size_t)ky * kw + kx) * C + c;
+                            const size_t dst = (((size_t)img * H + (oy * stride + ky)) * W + (ox * stride + kx)) * C + c;
+                            gx[dst] += g_patches[r * E + e];
+                        }
+            }
+    return 0;
+}
