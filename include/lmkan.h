@@ -210,6 +210,47 @@ lmkan_status lmkan_fold(const lmkan_desc *desc, void *coef_dev, float gamma, con
                         const float *lin_b_dev, const float *out_scale_dev, const float *out_shift_dev,
                         void *stream);
 
+/*
+ * Convolution (Sec. 5, "lmKAN-based Convolutional Neural Networks"): a kh x kw
+ * convolution is the layer R^{kh kw c_in} -> R^{n_out} applied to every window of a
+ * channels-last image.  The paper reshapes the windows into rows first; here the rows
+ * are never written out: the kernels read the image through the window map.
+ *   image   x[n][h][w][c_in] float32, no padding
+ *   window  (oy, ox) covers rows oy*stride .. oy*stride + kh - 1 and columns
+ *           ox*stride .. ox*stride + kw - 1;  out_h = (h - kh) / stride + 1 (floor),
+ *           out_w likewise (0 when the image is smaller than the window)
+ *   input   e = (ky*kw + kx)*c_in + c of the layer is x[img][oy*stride+ky][ox*stride+kx][c];
+ *           desc->n_in must equal kh*kw*c_in (even); with an odd c_in the two inputs of
+ *           a pair can come from neighbouring pixels
+ *   output  y[n][out_h][out_w][n_out]
+ */
+typedef struct lmkan_conv2d {
+    int32_t n, h, w, c_in;
+    int32_t kh, kw, stride;
+} lmkan_conv2d;
+
+/* Rows of the equivalent fully connected layer, n*out_h*out_w (the `batch` to pass to
+ * lmkan_workspace_bytes); writes out_h / out_w when not NULL.  -1 for an invalid struct. */
+int64_t lmkan_conv2d_rows(const lmkan_conv2d *conv, int32_t *out_h, int32_t *out_w);
+
+/*
+ * Forward and backward of the convolution.  Arguments as for lmkan_forward /
+ * lmkan_backward with batch = lmkan_conv2d_rows(conv): grad_y_dev is
+ * [n][out_h][out_w][n_out]; grad_x_dev has the shape of the image and is
+ * overwritten (every element gets the sum over the windows that contain it, zero
+ * where no window does); grad_coef_dev as in lmkan_backward.  x_dev, grad_x_dev
+ * need 4-byte alignment only.  workspace: lmkan_workspace_bytes(desc, rows, pass).
+ * LMKAN_ERR_SHAPE when desc->n_in != kh*kw*c_in or a size is not positive.
+ * For shapes the tuned kernels do not take, grad_x is summed with float32 atomics
+ * (sum order, and so the last bits, can differ between runs).
+ */
+lmkan_status lmkan_conv2d_forward(const lmkan_desc *desc, const lmkan_conv2d *conv, const float *x_dev,
+                                  const void *coef_dev, float *y_dev, void *workspace_dev, size_t workspace_bytes,
+                                  void *stream);
+lmkan_status lmkan_conv2d_backward(const lmkan_desc *desc, const lmkan_conv2d *conv, const float *x_dev,
+                                   const void *coef_dev, const float *grad_y_dev, float *grad_x_dev,
+                                   float *grad_coef_dev, void *workspace_dev, size_t workspace_bytes, void *stream);
+
 #ifdef __cplusplus
 }
 #endif

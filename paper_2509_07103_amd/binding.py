@@ -40,6 +40,29 @@ class _Desc(C.Structure):
                 ("coef_layout", C.c_int32), ("flags", C.c_int32)]
 
 
+class _Conv2d(C.Structure):
+    _fields_ = [("n", C.c_int32), ("h", C.c_int32), ("w", C.c_int32), ("c_in", C.c_int32),
+                ("kh", C.c_int32), ("kw", C.c_int32), ("stride", C.c_int32)]
+
+
+@dataclass
+class Conv2d:
+    """Mirror of ``lmkan_conv2d``: channels-last image [n][h][w][c_in], kh x kw windows, no padding."""
+    n: int
+    h: int
+    w: int
+    c_in: int
+    kh: int
+    kw: int
+    stride: int
+
+    def c(self) -> _Conv2d:
+        return _Conv2d(self.n, self.h, self.w, self.c_in, self.kh, self.kw, self.stride)
+
+    def image_shape(self):
+        return (self.n, self.h, self.w, self.c_in)
+
+
 @dataclass
 class LayerDesc:
     """Mirror of ``lmkan_desc``."""
@@ -100,6 +123,15 @@ def lib() -> C.CDLL:
     L.lmkan_backward.restype = C.c_int
     L.lmkan_backward.argtypes = [dp, C.c_int64, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p,
                                  C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]
+    cp = C.POINTER(_Conv2d)
+    L.lmkan_conv2d_rows.restype = C.c_int64
+    L.lmkan_conv2d_rows.argtypes = [cp, C.POINTER(C.c_int32), C.POINTER(C.c_int32)]
+    L.lmkan_conv2d_forward.restype = C.c_int
+    L.lmkan_conv2d_forward.argtypes = [dp, cp, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_size_t,
+                                       C.c_void_p]
+    L.lmkan_conv2d_backward.restype = C.c_int
+    L.lmkan_conv2d_backward.argtypes = [dp, cp, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p,
+                                        C.c_void_p, C.c_size_t, C.c_void_p]
     _lib = L
     return L
 
@@ -223,6 +255,54 @@ def lmkan_backward(desc: LayerDesc, x: torch.Tensor, coef: torch.Tensor | None, 
     _check(lib().lmkan_backward(C.byref(desc.c()), batch, xp, cp, gyp, gxp, gcp,
                                 ws.data_ptr() if ws is not None else None, wsz, _stream(stream)),
            "lmkan_backward")
+    return (grad_x if need_grad_x else None), (grad_coef if need_grad_coef else None)
+
+
+def lmkan_conv2d_rows(conv: Conv2d):
+    """(rows, out_h, out_w) of the equivalent fully connected layer."""
+    oh, ow = C.c_int32(0), C.c_int32(0)
+    rows = lib().lmkan_conv2d_rows(C.byref(conv.c()), C.byref(oh), C.byref(ow))
+    if rows < 0:
+        raise ValueError(f"invalid convolution geometry {conv}")
+    return rows, oh.value, ow.value
+
+
+def lmkan_conv2d_forward(desc: LayerDesc, conv: Conv2d, x: torch.Tensor, coef: torch.Tensor,
+                         y: torch.Tensor | None = None, stream=None) -> torch.Tensor:
+    """x[n][h][w][c_in] -> y[n][out_h][out_w][n_out]."""
+    rows, oh, ow = lmkan_conv2d_rows(conv)
+    xp = _dev(x, torch.float32, conv.image_shape(), "x")
+    cp = _coef_ptr(desc, coef)
+    if y is None:
+        y = torch.empty((conv.n, oh, ow, desc.n_out), dtype=torch.float32, device=x.device)
+    yp = _dev(y, torch.float32, (conv.n, oh, ow, desc.n_out), "y")
+    ws, wsz = _workspace(desc, rows, False, x.device)
+    _check(lib().lmkan_conv2d_forward(C.byref(desc.c()), C.byref(conv.c()), xp, cp, yp,
+                                      ws.data_ptr() if ws is not None else None, wsz, _stream(stream)),
+           "lmkan_conv2d_forward")
+    return y
+
+
+def lmkan_conv2d_backward(desc: LayerDesc, conv: Conv2d, x: torch.Tensor, coef: torch.Tensor | None,
+                          grad_y: torch.Tensor, need_grad_x: bool = True, need_grad_coef: bool = True,
+                          grad_x: torch.Tensor | None = None, grad_coef: torch.Tensor | None = None, stream=None):
+    """Returns (grad_x in the shape of the image or None, grad_coef in the layout of Alg. 1 or None)."""
+    rows, oh, ow = lmkan_conv2d_rows(conv)
+    xp = _dev(x, torch.float32, conv.image_shape(), "x")
+    cp = _coef_ptr(desc, coef)
+    gyp = _dev(grad_y, torch.float32, (conv.n, oh, ow, desc.n_out), "grad_y")
+    if need_grad_x and grad_x is None:
+        grad_x = torch.empty(conv.image_shape(), dtype=torch.float32, device=x.device)
+    if need_grad_coef and grad_coef is None:
+        if desc.flags & LMKAN_FLAG_ACCUMULATE_GRAD_COEF:
+            raise ValueError("accumulating into grad_coef needs an existing grad_coef tensor")
+        grad_coef = torch.empty(desc.coef_shape(), dtype=torch.float32, device=x.device)
+    gxp = _dev(grad_x, torch.float32, conv.image_shape(), "grad_x") if need_grad_x else None
+    gcp = _dev(grad_coef, torch.float32, desc.coef_shape(), "grad_coef") if need_grad_coef else None
+    ws, wsz = _workspace(desc, rows, True, x.device)
+    _check(lib().lmkan_conv2d_backward(C.byref(desc.c()), C.byref(conv.c()), xp, cp, gyp, gxp, gcp,
+                                       ws.data_ptr() if ws is not None else None, wsz, _stream(stream)),
+           "lmkan_conv2d_backward")
     return (grad_x if need_grad_x else None), (grad_coef if need_grad_coef else None)
 
 

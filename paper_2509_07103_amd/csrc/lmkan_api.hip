@@ -146,16 +146,21 @@ lmkan_status lmkan_locate(const lmkan_desc *desc, int64_t batch, const float *x_
     return launch_status();
 }
 
-lmkan_status lmkan_forward(const lmkan_desc *desc, int64_t batch, const float *x_dev,
-                           const void *coef_dev, float *y_dev, void *workspace_dev,
-                           size_t workspace_bytes, void *stream)
+}  // extern "C"
+
+namespace {
+
+// conv == nullptr: rows x[batch][n_in]; otherwise the rows are the windows of an image
+lmkan_status forward_impl(const lmkan_desc *desc, int64_t batch, const float *x_dev, const void *coef_dev,
+                          float *y_dev, void *workspace_dev, size_t workspace_bytes, void *stream,
+                          const ConvGeom *conv)
 {
     const lmkan_status st = check_desc(desc);
     if (st != LMKAN_OK) return st;
     if (batch < 0) return LMKAN_ERR_SHAPE;
     if (batch == 0) return LMKAN_OK;
     if (!x_dev || !coef_dev || !y_dev) return LMKAN_ERR_NULL;
-    if (!aligned(x_dev, 8) || !aligned(y_dev, 4) || !aligned(coef_dev, dtype_size(desc->coef_dtype)))
+    if (!aligned(x_dev, conv ? 4 : 8) || !aligned(y_dev, 4) || !aligned(coef_dev, dtype_size(desc->coef_dtype)))
         return LMKAN_ERR_ALIGN;
     const size_t need = lmkan_workspace_bytes(desc, batch, 0);
     if (need > 0 && (!workspace_dev || workspace_bytes < need)) return LMKAN_ERR_WORKSPACE;
@@ -165,21 +170,20 @@ lmkan_status lmkan_forward(const lmkan_desc *desc, int64_t batch, const float *x
     const LayerShape s = shape_of(desc, batch);
     hipStream_t hs = static_cast<hipStream_t>(stream);
     if (small_out_shape_ok(s)) {
-        launch_preamble_records(s, tab, x_dev, workspace_dev, hs);
+        launch_preamble_records(s, tab, x_dev, workspace_dev, hs, conv);
         launch_forward_small(s, coef_dev, y_dev, workspace_dev, hs);
     } else if (slab_forward_applicable(s, coef_dev, y_dev)) {
-        launch_preamble_records(s, tab, x_dev, workspace_dev, hs);
+        launch_preamble_records(s, tab, x_dev, workspace_dev, hs, conv);
         launch_forward_slab(s, coef_dev, y_dev, workspace_dev, hs);
     } else {
-        launch_forward_generic(s, tab, x_dev, coef_dev, y_dev, hs);
+        launch_forward_generic(s, tab, x_dev, coef_dev, y_dev, hs, conv);
     }
     return launch_status();
 }
 
-lmkan_status lmkan_backward(const lmkan_desc *desc, int64_t batch, const float *x_dev,
-                            const void *coef_dev, const float *grad_y_dev, float *grad_x_dev,
-                            float *grad_coef_dev, void *workspace_dev, size_t workspace_bytes,
-                            void *stream)
+lmkan_status backward_impl(const lmkan_desc *desc, int64_t batch, const float *x_dev, const void *coef_dev,
+                           const float *grad_y_dev, float *grad_x_dev, float *grad_coef_dev, void *workspace_dev,
+                           size_t workspace_bytes, void *stream, const ConvGeom *conv)
 {
     const lmkan_status st = check_desc(desc);
     if (st != LMKAN_OK) return st;
@@ -188,18 +192,20 @@ lmkan_status lmkan_backward(const lmkan_desc *desc, int64_t batch, const float *
     const LayerShape s = shape_of(desc, batch);
     hipStream_t hs = static_cast<hipStream_t>(stream);
     const bool overwrite = !(desc->flags & LMKAN_FLAG_ACCUMULATE_GRAD_COEF);
+    const size_t image_elems = conv ? (size_t)conv->N * conv->H * conv->W * conv->C : 0;
     if (batch == 0) {
-        // an empty batch still defines the coefficient gradient: all zeros
-        if (grad_coef_dev && overwrite) {
-            if (!aligned(grad_coef_dev, 4)) return LMKAN_ERR_ALIGN;
+        // an empty batch still defines the coefficient gradient: all zeros; an image too small for
+        // one window still defines its gradient: all zeros
+        if ((grad_coef_dev && !aligned(grad_coef_dev, 4)) || (grad_x_dev && !aligned(grad_x_dev, 4)))
+            return LMKAN_ERR_ALIGN;
+        if (grad_coef_dev && overwrite)
             launch_fill_zero(grad_coef_dev, (size_t)s.nodes() * s.pairs() * s.n_out, hs);
-            return launch_status();
-        }
-        return LMKAN_OK;
+        if (grad_x_dev && image_elems) launch_fill_zero(grad_x_dev, image_elems, hs);
+        return launch_status();
     }
     if (!x_dev || !grad_y_dev) return LMKAN_ERR_NULL;
     if (grad_x_dev && !coef_dev) return LMKAN_ERR_NULL;
-    if (!aligned(x_dev, 8) || !aligned(grad_y_dev, 4) || (grad_x_dev && !aligned(grad_x_dev, 8)) ||
+    if (!aligned(x_dev, conv ? 4 : 8) || !aligned(grad_y_dev, 4) || (grad_x_dev && !aligned(grad_x_dev, conv ? 4 : 8)) ||
         (grad_coef_dev && !aligned(grad_coef_dev, 4)) ||
         (coef_dev && !aligned(coef_dev, dtype_size(desc->coef_dtype))))
         return LMKAN_ERR_ALIGN;
@@ -217,7 +223,7 @@ lmkan_status lmkan_backward(const lmkan_desc *desc, int64_t batch, const float *
     char *ws = static_cast<char *>(workspace_dev);
     char *ws_sorted = ws + align256(records_bytes(s));
     float *ws_scratch = reinterpret_cast<float *>(ws_sorted + sorted_records_bytes(s));
-    if (need_records) launch_preamble_records(s, tab, x_dev, ws, hs);
+    if (need_records) launch_preamble_records(s, tab, x_dev, ws, hs, conv);
     if (gp_small) {
         launch_backward_coef_small(s, ws, grad_y_dev, grad_coef_dev, !overwrite, hs);
     } else if (gp_sorted) {
@@ -225,17 +231,88 @@ lmkan_status lmkan_backward(const lmkan_desc *desc, int64_t batch, const float *
     } else if (grad_coef_dev) {
         // odd output counts or unaligned buffers: atomics on a gradient that starts at zero
         if (overwrite) launch_fill_zero(grad_coef_dev, (size_t)s.nodes() * s.pairs() * s.n_out, hs);
-        launch_backward_generic(s, tab, x_dev, coef_dev, grad_y_dev, nullptr, grad_coef_dev, hs);
+        launch_backward_generic(s, tab, x_dev, coef_dev, grad_y_dev, nullptr, grad_coef_dev, hs, conv);
     }
     if (gx_small) {
         launch_backward_input_small(s, tab, coef_dev, grad_y_dev, ws_scratch, ws, hs);
-        launch_transpose(ws_scratch, grad_x_dev, s.batch, s.n_in, hs);
+        launch_input_gradient_out(ws_scratch, grad_x_dev, s, conv, hs);
     } else if (gx_slab) {
-        launch_backward_input_slab(s, tab, coef_dev, grad_y_dev, grad_x_dev, ws, ws_scratch, hs);
+        launch_backward_input_slab(s, tab, coef_dev, grad_y_dev, grad_x_dev, ws, ws_scratch, hs, conv);
     } else if (grad_x_dev) {
-        launch_backward_generic(s, tab, x_dev, coef_dev, grad_y_dev, grad_x_dev, nullptr, hs);
+        if (conv) launch_fill_zero(grad_x_dev, image_elems, hs);  // the kernel sums into the image
+        launch_backward_generic(s, tab, x_dev, coef_dev, grad_y_dev, grad_x_dev, nullptr, hs, conv);
     }
     return launch_status();
+}
+
+// window geometry from the public struct; false when it does not describe a convolution this layer fits
+bool conv_geom(const lmkan_desc *desc, const lmkan_conv2d *c, ConvGeom *g)
+{
+    if (!desc || !c) return false;
+    if (c->n < 0 || c->h < 1 || c->w < 1 || c->c_in < 1 || c->kh < 1 || c->kw < 1 || c->stride < 1) return false;
+    if ((int64_t)c->kh * c->kw * c->c_in != desc->n_in) return false;
+    if ((int64_t)c->n * c->h * c->w * c->c_in > (int64_t)1 << 40) return false;
+    g->N = c->n, g->H = c->h, g->W = c->w, g->C = c->c_in, g->kh = c->kh, g->kw = c->kw, g->stride = c->stride;
+    g->OH = c->h >= c->kh ? (c->h - c->kh) / c->stride + 1 : 0;
+    g->OW = c->w >= c->kw ? (c->w - c->kw) / c->stride + 1 : 0;
+    return true;
+}
+
+}  // namespace
+
+extern "C" {
+
+lmkan_status lmkan_forward(const lmkan_desc *desc, int64_t batch, const float *x_dev,
+                           const void *coef_dev, float *y_dev, void *workspace_dev,
+                           size_t workspace_bytes, void *stream)
+{
+    return forward_impl(desc, batch, x_dev, coef_dev, y_dev, workspace_dev, workspace_bytes, stream, nullptr);
+}
+
+lmkan_status lmkan_backward(const lmkan_desc *desc, int64_t batch, const float *x_dev,
+                            const void *coef_dev, const float *grad_y_dev, float *grad_x_dev,
+                            float *grad_coef_dev, void *workspace_dev, size_t workspace_bytes,
+                            void *stream)
+{
+    return backward_impl(desc, batch, x_dev, coef_dev, grad_y_dev, grad_x_dev, grad_coef_dev, workspace_dev,
+                         workspace_bytes, stream, nullptr);
+}
+
+int64_t lmkan_conv2d_rows(const lmkan_conv2d *conv, int32_t *out_h, int32_t *out_w)
+{
+    if (!conv || conv->n < 0 || conv->h < 1 || conv->w < 1 || conv->kh < 1 || conv->kw < 1 || conv->stride < 1)
+        return -1;
+    const int32_t oh = conv->h >= conv->kh ? (conv->h - conv->kh) / conv->stride + 1 : 0;
+    const int32_t ow = conv->w >= conv->kw ? (conv->w - conv->kw) / conv->stride + 1 : 0;
+    if (out_h) *out_h = oh;
+    if (out_w) *out_w = ow;
+    return (int64_t)conv->n * oh * ow;
+}
+
+lmkan_status lmkan_conv2d_forward(const lmkan_desc *desc, const lmkan_conv2d *conv, const float *x_dev,
+                                  const void *coef_dev, float *y_dev, void *workspace_dev, size_t workspace_bytes,
+                                  void *stream)
+{
+    const lmkan_status st = check_desc(desc);
+    if (st != LMKAN_OK) return st;
+    if (!conv) return LMKAN_ERR_NULL;
+    ConvGeom g;
+    if (!conv_geom(desc, conv, &g)) return LMKAN_ERR_SHAPE;
+    return forward_impl(desc, (int64_t)g.N * g.OH * g.OW, x_dev, coef_dev, y_dev, workspace_dev, workspace_bytes,
+                        stream, &g);
+}
+
+lmkan_status lmkan_conv2d_backward(const lmkan_desc *desc, const lmkan_conv2d *conv, const float *x_dev,
+                                   const void *coef_dev, const float *grad_y_dev, float *grad_x_dev,
+                                   float *grad_coef_dev, void *workspace_dev, size_t workspace_bytes, void *stream)
+{
+    const lmkan_status st = check_desc(desc);
+    if (st != LMKAN_OK) return st;
+    if (!conv) return LMKAN_ERR_NULL;
+    ConvGeom g;
+    if (!conv_geom(desc, conv, &g)) return LMKAN_ERR_SHAPE;
+    return backward_impl(desc, (int64_t)g.N * g.OH * g.OW, x_dev, coef_dev, grad_y_dev, grad_x_dev, grad_coef_dev,
+                         workspace_dev, workspace_bytes, stream, &g);
 }
 
 lmkan_status lmkan_hessian_reg(const lmkan_desc *desc, const void *coef_dev, float scale, double *value_dev,

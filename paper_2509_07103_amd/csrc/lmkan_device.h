@@ -20,6 +20,37 @@ struct GridTab {
     int G;
 };
 
+// Convolution as a fully connected layer on windows (Sec. 5, "lmKAN-based Convolutional Neural
+// Networks"): channels-last image x[N][H][W][C], kh x kw window, no padding; row r of the layer =
+// output pixel (img, oy, ox), r = (img OH + oy) OW + ox; input e = (ky kw + kx) C + c of that row is
+// x[img][oy stride + ky][ox stride + kx][c].  The patches are never written out: every kernel that
+// reads x goes through this map.  C == 0 stands for a plain layer on rows x[n][n_in].
+struct ConvGeom {
+    int N, H, W, C, kh, kw, stride, OH, OW;
+};
+
+// offset, in elements, of input e of row n
+__host__ __device__ inline int64_t conv_input_offset(const ConvGeom &cg, int64_t n, int e)
+{
+    const int c = e % cg.C, kx = (e / cg.C) % cg.kw, ky = e / (cg.C * cg.kw);
+    const int ox = (int)(n % cg.OW), oy = (int)((n / cg.OW) % cg.OH);
+    const int64_t img = n / ((int64_t)cg.OW * cg.OH);
+    return ((img * cg.H + (oy * cg.stride + ky)) * cg.W + (ox * cg.stride + kx)) * cg.C + c;
+}
+
+// the two inputs of pair k of row n (with an odd channel count they can sit in two pixels)
+template <bool CONV>
+__device__ inline float2 load_input_pair(const float *__restrict__ x, int64_t n, int n_in, int k, const ConvGeom &cg)
+{
+    if constexpr (!CONV) {
+        return *reinterpret_cast<const float2 *>(x + n * n_in + 2 * k);
+    } else {
+        const int64_t o0 = conv_input_offset(cg, n, 2 * k);
+        const int64_t o1 = (cg.C & 1) ? conv_input_offset(cg, n, 2 * k + 1) : o0 + 1;
+        return make_float2(x[o0], x[o1]);
+    }
+}
+
 // Where coefficient (node, pair k, output tile jt, column jl) lives, in elements:
 //   node * s_node + k * s_pair + jt * s_tile + jl,
 // and moving one node along the second axis adds s_node, along the first (G+1) * s_node.

@@ -40,12 +40,12 @@ constexpr int kFwdSamplesPerWave = 8;
 constexpr int kFwdTileB = kWaves * kFwdSamplesPerWave;
 constexpr int kFwdPairChunk = 16;
 
-template <typename CT>
+template <typename CT, bool CONV>
 __global__ __launch_bounds__(kThreads) void forward_generic_kernel(GridTab tab, CoefMap map,
                                                                   const float *__restrict__ x,
                                                                   const CT *__restrict__ P,
                                                                   float *__restrict__ y, int64_t B,
-                                                                  int n_in, int n_out)
+                                                                  int n_in, int n_out, ConvGeom cg)
 {
     __shared__ float s_node[LMKAN_MAX_GRID + 1];
     __shared__ float s_invh[LMKAN_MAX_GRID];
@@ -74,7 +74,7 @@ __global__ __launch_bounds__(kThreads) void forward_generic_kernel(GridTab tab, 
             int node = 0;
             float4 w = make_float4(0.f, 0.f, 0.f, 0.f);
             if (n < B && k0 + kk < K) {
-                const float2 xv = *reinterpret_cast<const float2 *>(x + n * n_in + 2 * (k0 + kk));
+                const float2 xv = load_input_pair<CONV>(x, n, n_in, k0 + kk, cg);
                 const Preamble p = preamble(s_node, s_invh, G, xv.x, xv.y);
                 node = p.node;
                 w = make_float4(p.a_lo * p.b_lo, p.a_hi * p.b_lo, p.a_lo * p.b_hi, p.a_hi * p.b_hi);
@@ -121,11 +121,11 @@ __global__ __launch_bounds__(kThreads) void forward_generic_kernel(GridTab tab, 
 //            d/dx1 = (1/h1) ((s10-s00) b_lo + (s11-s01) b_hi), d/dx2 alike.
 //   grad_P : gP[corner ab][j] += w_ab gy[j]  with float32 atomics.
 // ---------------------------------------------------------------------------
-template <typename CT, bool DO_GX, bool DO_GP>
+template <typename CT, bool DO_GX, bool DO_GP, bool CONV>
 __global__ __launch_bounds__(kThreads) void backward_generic_kernel(
     GridTab tab, CoefMap map, CoefMap gmap, const float *__restrict__ x, const CT *__restrict__ P,
     const float *__restrict__ gy, float *__restrict__ gx, float *__restrict__ gP, int64_t B, int n_in,
-    int n_out)
+    int n_out, ConvGeom cg)
 {
     __shared__ float s_node[LMKAN_MAX_GRID + 1];
     __shared__ float s_invh[LMKAN_MAX_GRID];
@@ -145,7 +145,7 @@ __global__ __launch_bounds__(kThreads) void backward_generic_kernel(
         mine.node = 0;
         mine.a_lo = mine.a_hi = mine.b_lo = mine.b_hi = mine.rh1 = mine.rh2 = 0.0f;
         if (k0 + lane < K) {
-            const float2 xv = *reinterpret_cast<const float2 *>(x + n * n_in + 2 * (k0 + lane));
+            const float2 xv = load_input_pair<CONV>(x, n, n_in, k0 + lane, cg);
             mine = preamble(s_node, s_invh, G, xv.x, xv.y);
         }
         float my_d1 = 0.0f, my_d2 = 0.0f;
@@ -188,8 +188,15 @@ __global__ __launch_bounds__(kThreads) void backward_generic_kernel(
                 }
             }
         }
-        if (DO_GX && k0 + lane < K)
-            *reinterpret_cast<float2 *>(gx + n * n_in + 2 * (k0 + lane)) = make_float2(my_d1, my_d2);
+        if (DO_GX && k0 + lane < K) {
+            if constexpr (CONV) {
+                // windows may overlap: an image element collects from every window that holds it
+                atomicAdd(gx + conv_input_offset(cg, n, 2 * (k0 + lane)), my_d1);
+                atomicAdd(gx + conv_input_offset(cg, n, 2 * (k0 + lane) + 1), my_d2);
+            } else {
+                *reinterpret_cast<float2 *>(gx + n * n_in + 2 * (k0 + lane)) = make_float2(my_d1, my_d2);
+            }
+        }
     }
 }
 
@@ -259,31 +266,34 @@ CoefMap coef_map(const LayerShape &s)
     return m;
 }
 
-void launch_forward_generic(const LayerShape &s, const GridTab &tab, const float *x, const void *coef,
-                            float *y, hipStream_t stream)
+template <typename CT>
+static void forward_generic_dispatch(const LayerShape &s, const GridTab &tab, const float *x, const CT *coef,
+                                     float *y, hipStream_t stream, const ConvGeom *conv)
 {
     const dim3 grid((unsigned)((s.batch + kFwdTileB - 1) / kFwdTileB), (unsigned)s.out_tiles());
     const CoefMap map = coef_map(s);
+    if (conv)
+        forward_generic_kernel<CT, true><<<grid, kThreads, 0, stream>>>(tab, map, x, coef, y, s.batch, s.n_in,
+                                                                        s.n_out, *conv);
+    else
+        forward_generic_kernel<CT, false><<<grid, kThreads, 0, stream>>>(tab, map, x, coef, y, s.batch, s.n_in,
+                                                                         s.n_out, ConvGeom{});
+}
+
+void launch_forward_generic(const LayerShape &s, const GridTab &tab, const float *x, const void *coef,
+                            float *y, hipStream_t stream, const ConvGeom *conv)
+{
     switch (s.dtype) {
-    case LMKAN_F32:
-        forward_generic_kernel<float><<<grid, kThreads, 0, stream>>>(
-            tab, map, x, static_cast<const float *>(coef), y, s.batch, s.n_in, s.n_out);
-        break;
-    case LMKAN_F16:
-        forward_generic_kernel<_Float16><<<grid, kThreads, 0, stream>>>(
-            tab, map, x, static_cast<const _Float16 *>(coef), y, s.batch, s.n_in, s.n_out);
-        break;
-    default:
-        forward_generic_kernel<bf16_t><<<grid, kThreads, 0, stream>>>(
-            tab, map, x, static_cast<const bf16_t *>(coef), y, s.batch, s.n_in, s.n_out);
-        break;
+    case LMKAN_F32: forward_generic_dispatch(s, tab, x, static_cast<const float *>(coef), y, stream, conv); break;
+    case LMKAN_F16: forward_generic_dispatch(s, tab, x, static_cast<const _Float16 *>(coef), y, stream, conv); break;
+    default: forward_generic_dispatch(s, tab, x, static_cast<const bf16_t *>(coef), y, stream, conv); break;
     }
 }
 
-template <typename CT>
+template <typename CT, bool CONV>
 static void backward_generic_dispatch(const LayerShape &s, const GridTab &tab, const float *x,
                                       const CT *coef, const float *gy, float *gx, float *gcoef,
-                                      hipStream_t stream)
+                                      hipStream_t stream, const ConvGeom &cg)
 {
     const dim3 grid((unsigned)((s.batch + kWaves - 1) / kWaves));
     const CoefMap map = coef_map(s);
@@ -291,29 +301,40 @@ static void backward_generic_dispatch(const LayerShape &s, const GridTab &tab, c
     g.layout = LMKAN_LAYOUT_PAPER;  // the gradient is always in the layout of Alg. 1
     const CoefMap gmap = coef_map(g);
     if (gx && gcoef)
-        backward_generic_kernel<CT, true, true><<<grid, kThreads, 0, stream>>>(
-            tab, map, gmap, x, coef, gy, gx, gcoef, s.batch, s.n_in, s.n_out);
+        backward_generic_kernel<CT, true, true, CONV><<<grid, kThreads, 0, stream>>>(
+            tab, map, gmap, x, coef, gy, gx, gcoef, s.batch, s.n_in, s.n_out, cg);
     else if (gx)
-        backward_generic_kernel<CT, true, false><<<grid, kThreads, 0, stream>>>(
-            tab, map, gmap, x, coef, gy, gx, gcoef, s.batch, s.n_in, s.n_out);
+        backward_generic_kernel<CT, true, false, CONV><<<grid, kThreads, 0, stream>>>(
+            tab, map, gmap, x, coef, gy, gx, gcoef, s.batch, s.n_in, s.n_out, cg);
     else if (gcoef)
-        backward_generic_kernel<CT, false, true><<<grid, kThreads, 0, stream>>>(
-            tab, map, gmap, x, coef, gy, gx, gcoef, s.batch, s.n_in, s.n_out);
+        backward_generic_kernel<CT, false, true, CONV><<<grid, kThreads, 0, stream>>>(
+            tab, map, gmap, x, coef, gy, gx, gcoef, s.batch, s.n_in, s.n_out, cg);
+}
+
+template <typename CT>
+static void backward_generic_conv_or_rows(const LayerShape &s, const GridTab &tab, const float *x, const CT *coef,
+                                          const float *gy, float *gx, float *gcoef, hipStream_t stream,
+                                          const ConvGeom *conv)
+{
+    if (conv)
+        backward_generic_dispatch<CT, true>(s, tab, x, coef, gy, gx, gcoef, stream, *conv);
+    else
+        backward_generic_dispatch<CT, false>(s, tab, x, coef, gy, gx, gcoef, stream, ConvGeom{});
 }
 
 void launch_backward_generic(const LayerShape &s, const GridTab &tab, const float *x,
                              const void *coef, const float *gy, float *gx, float *gcoef,
-                             hipStream_t stream)
+                             hipStream_t stream, const ConvGeom *conv)
 {
     switch (s.dtype) {
     case LMKAN_F32:
-        backward_generic_dispatch(s, tab, x, static_cast<const float *>(coef), gy, gx, gcoef, stream);
+        backward_generic_conv_or_rows(s, tab, x, static_cast<const float *>(coef), gy, gx, gcoef, stream, conv);
         break;
     case LMKAN_F16:
-        backward_generic_dispatch(s, tab, x, static_cast<const _Float16 *>(coef), gy, gx, gcoef, stream);
+        backward_generic_conv_or_rows(s, tab, x, static_cast<const _Float16 *>(coef), gy, gx, gcoef, stream, conv);
         break;
     default:
-        backward_generic_dispatch(s, tab, x, static_cast<const bf16_t *>(coef), gy, gx, gcoef, stream);
+        backward_generic_conv_or_rows(s, tab, x, static_cast<const bf16_t *>(coef), gy, gx, gcoef, stream, conv);
         break;
     }
 }

@@ -23,13 +23,15 @@ struct LayerShape {
 
 CoefMap coef_map(const LayerShape &s);
 
+
 // Generic kernels: any shape, any dtype, both layouts; coefficient rows are read
 // straight from global memory.
 void launch_forward_generic(const LayerShape &s, const GridTab &tab, const float *x, const void *coef,
-                            float *y, hipStream_t stream);
+                            float *y, hipStream_t stream, const ConvGeom *conv = nullptr);
+// with conv, grad_x is summed into gx with atomics: the caller clears it first
 void launch_backward_generic(const LayerShape &s, const GridTab &tab, const float *x,
                              const void *coef, const float *gy, float *gx, float *gcoef,
-                             hipStream_t stream);
+                             hipStream_t stream, const ConvGeom *conv = nullptr);
 void launch_locate(const LayerShape &s, const GridTab &tab, const float *x, int32_t *cell,
                    hipStream_t stream);
 void launch_pack(const LayerShape &s, const void *src, void *dst, hipStream_t stream);
@@ -42,7 +44,7 @@ size_t slab_forward_lds_bytes(const LayerShape &s);
 bool slab_forward_shape_ok(const LayerShape &s);
 bool slab_forward_applicable(const LayerShape &s, const void *coef, const float *y);
 void launch_preamble_records(const LayerShape &s, const GridTab &tab, const float *x, void *records,
-                             hipStream_t stream);
+                             hipStream_t stream, const ConvGeom *conv = nullptr);
 void launch_forward_slab(const LayerShape &s, const void *coef, float *y, const void *records,
                          hipStream_t stream);
 
@@ -50,7 +52,8 @@ bool slab_backward_input_shape_ok(const LayerShape &s);
 bool slab_backward_input_applicable(const LayerShape &s, const void *coef, const float *gy, const float *gx);
 size_t slab_backward_input_scratch_bytes(const LayerShape &s);
 void launch_backward_input_slab(const LayerShape &s, const GridTab &tab, const void *coef, const float *gy,
-                                float *gx, const void *records, void *scratch, hipStream_t stream);
+                                float *gx, const void *records, void *scratch, hipStream_t stream,
+                                const ConvGeom *conv = nullptr);
 
 // float16 tables kept as float16 in LDS (lmkan_slab_f16.hip); reached through the two slab
 // launchers above when slab_f16_native_ok().  gx_scratch is the zero-filled transposed scratch.
@@ -71,6 +74,10 @@ void launch_backward_input_small(const LayerShape &s, const GridTab &tab, const 
 void launch_backward_coef_small(const LayerShape &s, const void *records, const float *gy, float *gcoef,
                                 bool accumulate, hipStream_t stream);
 void launch_transpose(const float *in_t, float *out, int64_t batch, int n_in, hipStream_t stream);
+// the transposed scratch [n_in][rows] -> grad_x: a transpose for a plain layer, for a convolution
+// the sum over the patches that contain each input element
+void launch_input_gradient_out(const float *in_t, float *gx, const LayerShape &s, const ConvGeom *conv,
+                               hipStream_t stream);
 
 // Coefficient gradient by cell-sorted samples (lmkan_backward.hip).  `records` is the output
 // of launch_preamble_records; `sorted` is scratch of sorted_records_bytes().  Needs n_out to be a

@@ -46,11 +46,12 @@ struct is_bf16<bf16_t> {
 // ---------------------------------------------------------------------------
 constexpr int kRecTile = 64;
 
+template <bool CONV>
 __global__ __launch_bounds__(256) void preamble_records_kernel(GridTab tab, const float *__restrict__ x,
                                                               int32_t *__restrict__ rec_node,
                                                               float *__restrict__ rec_u,
                                                               float *__restrict__ rec_v, int64_t B,
-                                                              int n_in)
+                                                              int n_in, ConvGeom cg)
 {
     __shared__ float s_node[LMKAN_MAX_GRID + 1];
     __shared__ float s_invh[LMKAN_MAX_GRID];
@@ -72,7 +73,7 @@ __global__ __launch_bounds__(256) void preamble_records_kernel(GridTab tab, cons
         int node = 0;
         float u = 0.f, v = 0.f;
         if (n < B && k0 + p < K) {
-            const float2 xv = *reinterpret_cast<const float2 *>(x + n * n_in + 2 * (k0 + p));
+            const float2 xv = load_input_pair<CONV>(x, n, n_in, k0 + p, cg);
             const Preamble pr = preamble(s_node, s_invh, tab.G, xv.x, xv.y);
             node = pr.node;
             u = pr.a_hi;
@@ -977,7 +978,7 @@ size_t records_bytes(const LayerShape &s)
 }
 
 void launch_preamble_records(const LayerShape &s, const GridTab &tab, const float *x, void *records,
-                             hipStream_t stream)
+                             hipStream_t stream, const ConvGeom *conv)
 {
     const size_t n = (size_t)s.pairs() * (size_t)s.batch;
     int32_t *rec_node = static_cast<int32_t *>(records);
@@ -985,7 +986,11 @@ void launch_preamble_records(const LayerShape &s, const GridTab &tab, const floa
     float *rec_v = rec_u + n;
     const dim3 grid((unsigned)((s.batch + kRecTile - 1) / kRecTile),
                     (unsigned)((s.pairs() + kRecTile - 1) / kRecTile));
-    preamble_records_kernel<<<grid, 256, 0, stream>>>(tab, x, rec_node, rec_u, rec_v, s.batch, s.n_in);
+    if (conv)
+        preamble_records_kernel<true><<<grid, 256, 0, stream>>>(tab, x, rec_node, rec_u, rec_v, s.batch, s.n_in, *conv);
+    else
+        preamble_records_kernel<false><<<grid, 256, 0, stream>>>(tab, x, rec_node, rec_u, rec_v, s.batch, s.n_in,
+                                                                ConvGeom{});
 }
 
 // 64-output tiles: the float32 slab fits LDS twice (G <= 16)
@@ -1128,6 +1133,51 @@ bool slab_backward_input_applicable(const LayerShape &s, const void *coef, const
            (reinterpret_cast<uintptr_t>(gx) & 3) == 0;
 }
 
+namespace {
+
+// gx[img][y][x][c] = sum over the windows that contain (y, x) of the patch gradient
+// in_t[(ky kw + kx) C + c][row of that window]; elements no window covers get zero
+__global__ __launch_bounds__(256) void conv_input_gradient_kernel(const float *__restrict__ in_t,
+                                                                 float *__restrict__ gx, ConvGeom cg, int64_t rows)
+{
+    const int64_t total = (int64_t)cg.N * cg.H * cg.W * cg.C;
+    const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (i >= total) return;
+    const int c = (int)(i % cg.C);
+    const int xw = (int)((i / cg.C) % cg.W);
+    const int yh = (int)((i / ((int64_t)cg.C * cg.W)) % cg.H);
+    const int64_t img = i / ((int64_t)cg.C * cg.W * cg.H);
+    float sum = 0.f;
+    for (int ky = 0; ky < cg.kh; ++ky) {
+        const int ty = yh - ky;
+        if (ty < 0 || ty % cg.stride != 0) continue;
+        const int oy = ty / cg.stride;
+        if (oy >= cg.OH) continue;
+        for (int kx = 0; kx < cg.kw; ++kx) {
+            const int tx = xw - kx;
+            if (tx < 0 || tx % cg.stride != 0) continue;
+            const int ox = tx / cg.stride;
+            if (ox >= cg.OW) continue;
+            const int64_t row = (img * cg.OH + oy) * cg.OW + ox;
+            sum += in_t[(int64_t)((ky * cg.kw + kx) * cg.C + c) * rows + row];
+        }
+    }
+    gx[i] = sum;
+}
+
+}  // namespace
+
+void launch_input_gradient_out(const float *in_t, float *gx, const LayerShape &s, const ConvGeom *conv,
+                               hipStream_t stream)
+{
+    if (!conv) {
+        launch_transpose(in_t, gx, s.batch, s.n_in, stream);
+        return;
+    }
+    const int64_t total = (int64_t)conv->N * conv->H * conv->W * conv->C;
+    conv_input_gradient_kernel<<<(unsigned)((total + 255) / 256), 256, 0, stream>>>(in_t, gx, *conv, s.batch);
+}
+
 void launch_transpose(const float *in_t, float *out, int64_t batch, int n_in, hipStream_t stream)
 {
     const dim3 tgrid((unsigned)((batch + 63) / 64), (unsigned)((n_in + 63) / 64));
@@ -1140,13 +1190,13 @@ size_t slab_backward_input_scratch_bytes(const LayerShape &s)
 }
 
 void launch_backward_input_slab(const LayerShape &s, const GridTab &tab, const void *coef, const float *gy,
-                                float *gx, const void *records, void *scratch, hipStream_t stream)
+                                float *gx, const void *records, void *scratch, hipStream_t stream,
+                                const ConvGeom *conv)
 {
     if (slab_wide_ok(s) && slab_f16_native_ok(s)) {
         launch_fill_zero(static_cast<float *>(scratch), (size_t)s.batch * s.n_in, stream);
         launch_backward_input_slab_f16(s, tab, coef, gy, static_cast<float *>(scratch), records, stream);
-        const dim3 tg((unsigned)((s.batch + 63) / 64), (unsigned)((s.n_in + 63) / 64));
-        transpose_kernel<<<tg, 256, 0, stream>>>(static_cast<float *>(scratch), gx, s.batch, s.n_in);
+        launch_input_gradient_out(static_cast<float *>(scratch), gx, s, conv, stream);
         return;
     }
     constexpr int WAVES = 8, SETS = 2;
@@ -1205,8 +1255,7 @@ void launch_backward_input_slab(const LayerShape &s, const GridTab &tab, const v
     const size_t slabs = narrow ? (size_t)2 * s.nodes() * kNarrowRowBytes : slab_forward_lds_bytes(s);
     const int waves = s.dtype == LMKAN_F32 ? LMKAN_GX_WAVES : WAVES;
     kernel<<<tiles * split, waves * 64, slabs + LMKAN_MAX_GRID * sizeof(float), stream>>>(a);
-    const dim3 tgrid((unsigned)((s.batch + 63) / 64), (unsigned)((s.n_in + 63) / 64));
-    transpose_kernel<<<tgrid, 256, 0, stream>>>(a.gx, gx, s.batch, s.n_in);
+    launch_input_gradient_out(a.gx, gx, s, conv, stream);
 }
 
 }  // namespace lmkan

@@ -28,7 +28,8 @@ def test_library_exports_every_declared_symbol():
     declared = _declared_functions()
     assert {"lmkan_forward", "lmkan_backward", "lmkan_locate", "lmkan_pack", "lmkan_grid",
             "lmkan_version", "lmkan_status_string", "lmkan_packed_bytes",
-            "lmkan_workspace_bytes", "lmkan_hessian_reg", "lmkan_fold"} <= declared
+            "lmkan_workspace_bytes", "lmkan_hessian_reg", "lmkan_fold", "lmkan_conv2d_rows",
+            "lmkan_conv2d_forward", "lmkan_conv2d_backward"} <= declared
     for name in declared:
         assert hasattr(L, name), name
         assert hasattr(pkg, name), f"python binding lacks {name}"
@@ -120,3 +121,27 @@ def test_binding_refuses_host_tensors():
     P = torch.zeros(d.coef_shape())
     with pytest.raises(ValueError):
         pkg.lmkan_forward(d, x, P)
+
+
+def test_conv2d_rows_and_geometry_checks():
+    """Output size by the floor rule; geometry that does not fit the layer is a shape error
+    before any launch (the pointers are never dereferenced)."""
+    assert pkg.lmkan_conv2d_rows(pkg.Conv2d(4, 32, 32, 6, 2, 2, 2)) == (4 * 16 * 16, 16, 16)
+    assert pkg.lmkan_conv2d_rows(pkg.Conv2d(2, 9, 8, 3, 3, 2, 2)) == (2 * 4 * 4, 4, 4)
+    assert pkg.lmkan_conv2d_rows(pkg.Conv2d(2, 7, 5, 2, 3, 3, 1)) == (2 * 5 * 3, 5, 3)
+    assert pkg.lmkan_conv2d_rows(pkg.Conv2d(2, 2, 5, 2, 3, 3, 1)) == (0, 0, 3)   # image smaller than the window
+    with pytest.raises(ValueError):
+        pkg.lmkan_conv2d_rows(pkg.Conv2d(2, 8, 8, 2, 2, 2, 0))
+    L = pkg.lib()
+    fake = C.c_void_p(0x1000)
+    d = _desc(n_in=8).c()
+    good = pkg.Conv2d(1, 4, 4, 2, 2, 2, 2).c()
+    for bad in (pkg.Conv2d(1, 4, 4, 3, 2, 2, 2), pkg.Conv2d(1, 4, 4, 2, 2, 2, 0), pkg.Conv2d(1, 0, 4, 2, 2, 2, 2),
+                pkg.Conv2d(-1, 4, 4, 2, 2, 2, 2)):
+        b = bad.c()
+        assert L.lmkan_conv2d_forward(C.byref(d), C.byref(b), fake, fake, fake, None, 0, None) == 2
+        assert L.lmkan_conv2d_backward(C.byref(d), C.byref(b), fake, fake, fake, fake, fake, None, 0, None) == 2
+    assert L.lmkan_conv2d_forward(C.byref(d), None, fake, fake, fake, None, 0, None) == 1
+    assert L.lmkan_conv2d_forward(C.byref(d), C.byref(good), None, fake, fake, None, 0, None) == 1
+    odd = _desc(n_in=7).c()
+    assert L.lmkan_conv2d_forward(C.byref(odd), C.byref(good), fake, fake, fake, None, 0, None) == 2
