@@ -65,12 +65,13 @@ def main():
         sys.exit(2)
     dev = torch.device("cuda:0")
     L = pkg.lib()
-    w = wl.BY_NAME[args.workload]
+    conv = args.workload in wl.CONV_BY_NAME     # a convolution stage: rows = windows of the images
+    w = wl.CONV_BY_NAME[args.workload] if conv else wl.BY_NAME[args.workload]
     dt_code = {"f32": pkg.LMKAN_F32, "f16": pkg.LMKAN_F16, "bf16": pkg.LMKAN_BF16}[args.storage]
     B, K, n_out = w.batch, w.n_in // 2, w.n_out
 
     # ---- inputs, resident in HBM before anything is timed -------------------------------
-    x = wl.make_x(w, dev)
+    x = wl.make_image(w, dev) if conv else wl.make_x(w, dev)
     gy = wl.make_grad_y(w, dev)
     if w.name.startswith("cfg5") and args.storage == "bf16":
         P_stored = wl.make_coef_bf16_chunked(w, dev)      # no room for a float32 master beside it
@@ -90,22 +91,37 @@ def main():
                              flags=pkg.LMKAN_FLAG_ACCUMULATE_GRAD_COEF)
 
     y = torch.empty((B, n_out), dtype=torch.float32, device=dev)
-    gx = torch.empty((B, w.n_in), dtype=torch.float32, device=dev)
+    gx = torch.empty_like(x)
     gP = torch.empty(paper.coef_shape(), dtype=torch.float32, device=dev)
     need = max(pkg.lmkan_workspace_bytes(desc, B, False), pkg.lmkan_workspace_bytes(desc, B, True), 256)
     ws = torch.empty(need, dtype=torch.uint8, device=dev)
     stream = torch.cuda.current_stream().cuda_stream
     d, d_acc = desc.c(), desc_acc.c()
 
+    if conv:
+        geom = pkg.Conv2d(w.n, w.h, w.w, w.c_in, w.kh, w.kw, w.stride).c()
+        assert pkg.lmkan_conv2d_rows(pkg.Conv2d(w.n, w.h, w.w, w.c_in, w.kh, w.kw, w.stride))[0] == B
+
     def forward():
-        st = L.lmkan_forward(C.byref(d), B, x.data_ptr(), P_packed.data_ptr(), y.data_ptr(),
-                             ws.data_ptr(), need, stream)
+        if conv:
+            st = L.lmkan_conv2d_forward(C.byref(d), C.byref(geom), x.data_ptr(), P_packed.data_ptr(), y.data_ptr(),
+                                        ws.data_ptr(), need, stream)
+        else:
+            st = L.lmkan_forward(C.byref(d), B, x.data_ptr(), P_packed.data_ptr(), y.data_ptr(),
+                                 ws.data_ptr(), need, stream)
         assert st == 0, pkg.lmkan_status_string(st)
 
-    def backward(dd=d):
-        st = L.lmkan_backward(C.byref(dd), B, x.data_ptr(), P_packed.data_ptr(), gy.data_ptr(),
-                              gx.data_ptr(), gP.data_ptr(), ws.data_ptr(), need, stream)
+    def backward_only(gx_ptr, gp_ptr):
+        if conv:
+            st = L.lmkan_conv2d_backward(C.byref(d), C.byref(geom), x.data_ptr(), P_packed.data_ptr(),
+                                         gy.data_ptr(), gx_ptr, gp_ptr, ws.data_ptr(), need, stream)
+        else:
+            st = L.lmkan_backward(C.byref(d), B, x.data_ptr(), P_packed.data_ptr(), gy.data_ptr(),
+                                  gx_ptr, gp_ptr, ws.data_ptr(), need, stream)
         assert st == 0, pkg.lmkan_status_string(st)
+
+    def backward():
+        backward_only(gx.data_ptr(), gP.data_ptr())
 
     def step():
         forward()
@@ -133,11 +149,6 @@ def main():
 
     reps = max(3, min(args.steps, 20))
     null = C.c_void_p(0)
-
-    def backward_only(gx_ptr, gp_ptr):
-        st = L.lmkan_backward(C.byref(d), B, x.data_ptr(), P_packed.data_ptr(), gy.data_ptr(),
-                              gx_ptr, gp_ptr, ws.data_ptr(), need, stream)
-        assert st == 0, pkg.lmkan_status_string(st)
 
     fwd_ms = event_ms(forward, reps)
     bwd_ms = event_ms(backward, reps)
@@ -167,7 +178,7 @@ def main():
     # algorithmic work of one such launch: 4 B K n_out multiply-adds; compulsory HBM bytes: the
     # table (read, or written in float32 by the coefficient gradient) + x + one y-sized tensor
     table_bytes = (w.grid + 1) ** 2 * K * n_out * (4 if "coef" in dom_name else s_bytes)
-    algo_bytes = table_bytes + B * w.n_in * 4 + B * n_out * 4
+    algo_bytes = table_bytes + x.numel() * 4 + B * n_out * 4
     t_alu = 2.0 * fma / (PEAK_FP32_VECTOR_TFLOPS * 1e12)
     t_hbm = algo_bytes / (PEAK_HBM_GBS * 1e9)
     if t_hbm > t_alu:
@@ -191,7 +202,9 @@ def main():
         "ms_per_step": round(ms_per_step, 4),
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "f32", "data": "synthetic",
-        "config": {"workload": f"{w.name}: n_in={w.n_in} n_out={n_out} G={w.grid} batch={B} "
+        "config": {"workload": (f"convolution {w.kh}x{w.kw} stride {w.stride} on [{w.n}][{w.h}][{w.w}][{w.c_in}] images, "
+                                f"a sample = one window; " if conv else "") +
+                               f"{w.name}: n_in={w.n_in} n_out={n_out} G={w.grid} batch={B} "
                                f"coef_storage={args.storage} x~{w.x_kind} coef~N(0,{w.coef_std})",
                    "pass": "forward+backward(grad_x,grad_coef)", "coef_layout": "packed",
                    "pack_ms_once": round(pack_ms, 3)},
@@ -230,7 +243,11 @@ def main():
         import oracle
         o = oracle.get()
         rows = min(args.cpu_rows, B)
-        xh = x[:rows].cpu().numpy()
+        if conv:    # the oracle's own gathering of the windows into rows, timed with the rest
+            n_img = -(-rows // (B // w.n))
+            xh = o.conv2d_patches(x[:n_img].cpu().numpy(), w.kh, w.kw, w.stride)[:rows]
+        else:
+            xh = x[:rows].cpu().numpy()
         gyh = gy[:rows].cpu().numpy()
         Pc = P_stored.cpu().contiguous()
         Ph = Pc.numpy() if args.storage == "f32" else Pc.view(torch.int16).numpy().view(np.uint16)

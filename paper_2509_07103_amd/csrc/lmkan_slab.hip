@@ -60,20 +60,35 @@ __global__ __launch_bounds__(256) void preamble_records_kernel(GridTab tab, cons
     __shared__ float s_v[kRecTile][kRecTile + 1];
     for (int i = threadIdx.x; i <= tab.G; i += blockDim.x) s_node[i] = tab.node[i];
     for (int i = threadIdx.x; i < tab.G; i += blockDim.x) s_invh[i] = tab.inv_h[i];
-    __syncthreads();
 
     const int K = n_in / 2;
     const int64_t n0 = (int64_t)blockIdx.x * kRecTile;
     const int k0 = blockIdx.y * kRecTile;
     const int p = threadIdx.x & 63;  // pair within tile (fast axis of the read)
     const int r0 = threadIdx.x >> 6;
+    // convolution: offset of a row's window once per tile, offsets of this thread's two inputs
+    // inside a window once per thread
+    __shared__ int64_t s_base[CONV ? kRecTile : 1];
+    int64_t e_off0 = 0, e_off1 = 0;
+    if constexpr (CONV) {
+        if (threadIdx.x < kRecTile && n0 + threadIdx.x < B) s_base[threadIdx.x] = conv_input_offset(cg, n0 + threadIdx.x, 0);
+        if (k0 + p < K) {
+            e_off0 = conv_input_offset(cg, 0, 2 * (k0 + p));
+            e_off1 = conv_input_offset(cg, 0, 2 * (k0 + p) + 1);
+        }
+    }
+    __syncthreads();
 #pragma unroll 4
     for (int r = r0; r < kRecTile; r += 4) {
         const int64_t n = n0 + r;
         int node = 0;
         float u = 0.f, v = 0.f;
         if (n < B && k0 + p < K) {
-            const float2 xv = load_input_pair<CONV>(x, n, n_in, k0 + p, cg);
+            float2 xv;
+            if constexpr (CONV)
+                xv = make_float2(x[s_base[r] + e_off0], x[s_base[r] + e_off1]);
+            else
+                xv = load_input_pair<false>(x, n, n_in, k0 + p, cg);
             const Preamble pr = preamble(s_node, s_invh, tab.G, xv.x, xv.y);
             node = pr.node;
             u = pr.a_hi;
@@ -1165,6 +1180,30 @@ __global__ __launch_bounds__(256) void conv_input_gradient_kernel(const float *_
     gx[i] = sum;
 }
 
+// Windows that do not overlap (stride >= window): every image element belongs to at most one
+// window, so the transposed scratch is scattered straight into the image, 64 rows x 64 inputs per
+// block through an LDS tile: reads run along the rows, writes along the channels of a pixel.
+__global__ __launch_bounds__(256) void conv_input_gradient_scatter_kernel(const float *__restrict__ in_t,
+                                                                         float *__restrict__ gx, ConvGeom cg,
+                                                                         int64_t rows, int n_in)
+{
+    __shared__ float tile[64][65];
+    __shared__ int64_t s_base[64];
+    const int64_t n0 = (int64_t)blockIdx.x * 64;
+    const int e0 = blockIdx.y * 64;
+    const int tx = threadIdx.x & 63, ty = threadIdx.x >> 6;
+    if (threadIdx.x < 64 && n0 + tx < rows) s_base[tx] = conv_input_offset(cg, n0 + tx, 0);
+    for (int r = ty; r < 64; r += 4)
+        if (e0 + r < n_in && n0 + tx < rows) tile[r][tx] = in_t[(int64_t)(e0 + r) * rows + n0 + tx];
+    __syncthreads();
+    const int e = e0 + tx;
+    if (e >= n_in) return;
+    const int c = e % cg.C, kx = (e / cg.C) % cg.kw, ky = e / (cg.C * cg.kw);
+    const int64_t e_off = ((int64_t)ky * cg.W + kx) * cg.C + c;
+    for (int r = ty; r < 64; r += 4)
+        if (n0 + r < rows) gx[s_base[r] + e_off] = tile[tx][r];
+}
+
 }  // namespace
 
 void launch_input_gradient_out(const float *in_t, float *gx, const LayerShape &s, const ConvGeom *conv,
@@ -1174,8 +1213,16 @@ void launch_input_gradient_out(const float *in_t, float *gx, const LayerShape &s
         launch_transpose(in_t, gx, s.batch, s.n_in, stream);
         return;
     }
-    const int64_t total = (int64_t)conv->N * conv->H * conv->W * conv->C;
-    conv_input_gradient_kernel<<<(unsigned)((total + 255) / 256), 256, 0, stream>>>(in_t, gx, *conv, s.batch);
+    const ConvGeom &cg = *conv;
+    const int64_t total = (int64_t)cg.N * cg.H * cg.W * cg.C;
+    if (cg.stride >= cg.kh && cg.stride >= cg.kw) {
+        const bool covered = cg.stride == cg.kh && cg.stride == cg.kw && cg.OH * cg.kh == cg.H && cg.OW * cg.kw == cg.W;
+        if (!covered) launch_fill_zero(gx, (size_t)total, stream);  // gaps between or beyond the windows
+        const dim3 grid((unsigned)((s.batch + 63) / 64), (unsigned)((s.n_in + 63) / 64));
+        conv_input_gradient_scatter_kernel<<<grid, 256, 0, stream>>>(in_t, gx, cg, s.batch, s.n_in);
+        return;
+    }
+    conv_input_gradient_kernel<<<(unsigned)((total + 255) / 256), 256, 0, stream>>>(in_t, gx, cg, s.batch);
 }
 
 void launch_transpose(const float *in_t, float *out, int64_t batch, int n_in, hipStream_t stream)

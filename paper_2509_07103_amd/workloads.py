@@ -42,10 +42,59 @@ CFG5 = Workload("cfg5_4096x4096_G32", 4096, 4096, 32, 4096, 0.05, 5, x_kind="nor
 BY_NAME = {w.name: w for w in (CFG1, *CFG2_LAYERS, CFG3, CFG4, CFG5)}
 
 
+@dataclass(frozen=True)
+class ConvWorkload:
+    """A convolution stage: channels-last images [n][h][w][c_in], kh x kw windows."""
+    name: str
+    n: int
+    h: int
+    w: int
+    c_in: int
+    kh: int
+    kw: int
+    stride: int
+    n_out: int
+    grid: int
+    coef_std: float
+    seed: int
+    x_kind: str = "normal"
+    storage: tuple = ("f32",)
+
+    @property
+    def n_in(self) -> int:
+        return self.kh * self.kw * self.c_in
+
+    @property
+    def out_hw(self):
+        return (self.h - self.kh) // self.stride + 1, (self.w - self.kw) // self.stride + 1
+
+    @property
+    def batch(self) -> int:      # rows of the equivalent fully connected layer
+        oh, ow = self.out_hw
+        return self.n * oh * ow
+
+
+# Stages shaped like the convolutional backbones of Sec. 5 at width 128: the second 2x2 stride-2
+# stage of the 32x32 backbone (16x16 feature maps), the second 3x3 stride-3 stage of the 81x81
+# one (27x27 feature maps), and an overlapping 3x3 stride-1 stage for the gradient gathering.
+# Feature maps are standardised (batch normalisation without affine parameters precedes every
+# lmKAN layer), hence N(0,1) inputs.
+CONV_2X2 = ConvWorkload("conv_2x2s2_16x16x128_to_128_G12", 1024, 16, 16, 128, 2, 2, 2, 128, 12, 0.1, 40)
+CONV_3X3 = ConvWorkload("conv_3x3s3_27x27x32_to_96_G12", 512, 27, 27, 32, 3, 3, 3, 96, 12, 0.1, 41)
+CONV_3X3_S1 = ConvWorkload("conv_3x3s1_16x16x32_to_64_G12", 256, 16, 16, 32, 3, 3, 1, 64, 12, 0.1, 42)
+CONV_BY_NAME = {w.name: w for w in (CONV_2X2, CONV_3X3, CONV_3X3_S1)}
+
+
 def _gen(device, seed: int) -> torch.Generator:
     g = torch.Generator(device=device)
     g.manual_seed(seed)
     return g
+
+
+def make_image(w: ConvWorkload, device) -> torch.Tensor:
+    """Feature maps [n][h][w][c_in] float32 ~ N(0,1)."""
+    g = _gen(device, 1000 + w.seed)
+    return torch.randn((w.n, w.h, w.w, w.c_in), generator=g, device=device, dtype=torch.float32)
 
 
 def make_x(w: Workload, device, batch: int | None = None) -> torch.Tensor:
