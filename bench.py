@@ -39,6 +39,8 @@ def parse():
     ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--storage", default="f32", choices=["f32", "f16", "bf16"])
     ap.add_argument("--workload", default="cfg3_1024x1024_G16")
+    ap.add_argument("--grid", type=int, default=0,
+                    help="override the workload's number of grid intervals G (for sweeps over G)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-rows", type=int, default=8192)
     ap.add_argument("--calibrate-copy", action="store_true",
@@ -67,6 +69,9 @@ def main():
     L = pkg.lib()
     conv = args.workload in wl.CONV_BY_NAME     # a convolution stage: rows = windows of the images
     w = wl.CONV_BY_NAME[args.workload] if conv else wl.BY_NAME[args.workload]
+    if args.grid:
+        import dataclasses
+        w = dataclasses.replace(w, grid=args.grid, name=f"{w.name}@G={args.grid}")
     dt_code = {"f32": pkg.LMKAN_F32, "f16": pkg.LMKAN_F16, "bf16": pkg.LMKAN_BF16}[args.storage]
     B, K, n_out = w.batch, w.n_in // 2, w.n_out
 
@@ -166,7 +171,7 @@ def main():
         fwd_name, gx_name = "forward_small_kernel", "backward_input_small_kernel"
     elif ok and w.grid <= 16:
         fwd_name, gx_name = "forward_slab_kernel", "backward_input_slab_kernel"
-    elif ok and w.grid <= 34 and args.storage != "f32":
+    elif ok and w.grid <= 34:
         fwd_name, gx_name = "forward_slab_narrow_kernel", "backward_input_slab_narrow_kernel"
     else:
         fwd_name, gx_name = "forward_generic_kernel", "backward_generic_kernel(grad_x)"

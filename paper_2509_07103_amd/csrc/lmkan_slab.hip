@@ -684,7 +684,6 @@ template <typename CT, int WAVES, int SETS>
 __global__ __launch_bounds__(WAVES * 64) __attribute__((amdgpu_waves_per_eu(2, 2))) void forward_slab_narrow_kernel(
     SlabArgs a)
 {
-    static_assert(sizeof(CT) == 2, "the slab is staged through registers (16-bit tables)");
     extern __shared__ __align__(16) float smem[];
     constexpr int LPS = 4;             // lanes per sample
     constexpr int STEPS = SETS * LPS;  // steps per pair, 16 samples each
@@ -745,6 +744,8 @@ __global__ __launch_bounds__(WAVES * 64) __attribute__((amdgpu_waves_per_eu(2, 2
     for (int k = k_begin; k < k_end; ++k) {
         const float *slab = ((k - k_begin) & 1) ? slab1 : slab0;
         float *slab_next = ((k - k_begin) & 1) ? slab0 : slab1;
+        // a float32 table arrives by LDS-direct loads, which nothing but this wait tracks
+        if constexpr (sizeof(CT) == 4) asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
         __syncthreads();  // the slab of pair k is complete, nobody reads the other buffer any more
         if (k + 1 < k_end) fill.template issue<0>(a, slab_next, k + 1, jt, wave, lane);
 
@@ -849,7 +850,6 @@ template <typename CT, int WAVES, int SETS>
 __global__ __launch_bounds__(WAVES * 64) __attribute__((amdgpu_waves_per_eu(2, 2))) void backward_input_slab_narrow_kernel(
     GradInArgs a)
 {
-    static_assert(sizeof(CT) == 2, "the slab is staged through registers (16-bit tables)");
     extern __shared__ __align__(16) float smem[];  // two slab buffers, then 1/h of the grid
     constexpr int LPS = 4;
     constexpr int STEPS = SETS * LPS;
@@ -909,7 +909,12 @@ __global__ __launch_bounds__(WAVES * 64) __attribute__((amdgpu_waves_per_eu(2, 2
     };
 
     // columns past the end of a ragged output tile are never loaded: the staged fill writes
-    // zeros there; s_invh must be in place before the first set
+    // zeros there, the LDS-direct loads of a float32 table leave them as they are, so they are
+    // cleared first; s_invh must be in place before the first set
+    if constexpr (sizeof(CT) == 4) {
+        for (int i = threadIdx.x; i < 2 * slab_floats; i += blockDim.x) smem[i] = 0.0f;
+        __syncthreads();
+    }
     SlabFill<CT, WAVES, LPS> fill;
     if (k_begin < k_end) {
 #pragma unroll
@@ -928,6 +933,7 @@ __global__ __launch_bounds__(WAVES * 64) __attribute__((amdgpu_waves_per_eu(2, 2
     for (int k = k_begin; k < k_end; ++k) {
         const float *slab = ((k - k_begin) & 1) ? slab1 : slab0;
         float *slab_next = ((k - k_begin) & 1) ? slab0 : slab1;
+        if constexpr (sizeof(CT) == 4) asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
         __syncthreads();
         if (k + 1 < k_end) fill.template issue<0>(sa, slab_next, k + 1, jt, wave, lane);
 
@@ -1017,10 +1023,10 @@ static bool slab_wide_ok(const LayerShape &s)
     return true;
 }
 
-// 16-output tiles for larger grids (G <= 34), 16-bit tables only
+// 16-output tiles for larger grids (G <= 34)
 static bool slab_narrow_ok(const LayerShape &s)
 {
-    if (s.dtype == LMKAN_F32 || s.n_out % 4 != 0 || s.batch < 256) return false;
+    if (s.n_out % 4 != 0 || s.batch < 256) return false;
     return !slab_wide_ok(s) && (size_t)2 * s.nodes() * kNarrowRowBytes <= 160 * 1024;
 }
 
@@ -1038,8 +1044,10 @@ static void launch_forward_slab_narrow(const LayerShape &s, const void *coef, fl
     constexpr int WAVES = 8, SETS = 8;
     constexpr int kTileB = WAVES * SETS * 64;
     typedef void (*Kernel)(SlabArgs);
-    const Kernel kernel = s.dtype == LMKAN_F16 ? forward_slab_narrow_kernel<_Float16, WAVES, SETS>
-                                               : forward_slab_narrow_kernel<bf16_t, WAVES, SETS>;
+    const Kernel kernels[3] = {forward_slab_narrow_kernel<float, WAVES, SETS>,
+                               forward_slab_narrow_kernel<_Float16, WAVES, SETS>,
+                               forward_slab_narrow_kernel<bf16_t, WAVES, SETS>};
+    const Kernel kernel = kernels[s.dtype];
     static bool attr_set[3] = {false, false, false};
     if (!attr_set[s.dtype]) {
         (void)hipFuncSetAttribute(reinterpret_cast<const void *>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize,
@@ -1258,7 +1266,7 @@ void launch_backward_input_slab(const LayerShape &s, const GridTab &tab, const v
     const Kernel kernels[9] = {backward_input_slab_kernel<float, LMKAN_GX_WAVES, 16 / LMKAN_GX_WAVES, LMKAN_GX_AHEAD, 0>,
                                backward_input_slab_kernel<_Float16, WAVES, SETS, 2, 0>,
                                backward_input_slab_kernel<bf16_t, WAVES, SETS, 2, 0>,
-                               nullptr,
+                               backward_input_slab_narrow_kernel<float, WAVES, kNarrowSets>,
                                backward_input_slab_narrow_kernel<_Float16, WAVES, kNarrowSets>,
                                backward_input_slab_narrow_kernel<bf16_t, WAVES, kNarrowSets>,
                                backward_input_slab_kernel<float, LMKAN_GX_WAVES, 16 / LMKAN_GX_WAVES, LMKAN_GX_AHEAD, 17>,
@@ -1300,7 +1308,7 @@ void launch_backward_input_slab(const LayerShape &s, const GridTab &tab, const v
     a.pairs_per_split = (a.K + split - 1) / split;
     launch_fill_zero(a.gx, (size_t)s.batch * s.n_in, stream);
     const size_t slabs = narrow ? (size_t)2 * s.nodes() * kNarrowRowBytes : slab_forward_lds_bytes(s);
-    const int waves = s.dtype == LMKAN_F32 ? LMKAN_GX_WAVES : WAVES;
+    const int waves = (s.dtype == LMKAN_F32 && !narrow) ? LMKAN_GX_WAVES : WAVES;
     kernel<<<tiles * split, waves * 64, slabs + LMKAN_MAX_GRID * sizeof(float), stream>>>(a);
     launch_input_gradient_out(a.gx, gx, s, conv, stream);
 }
