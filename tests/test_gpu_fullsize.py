@@ -175,3 +175,41 @@ def test_cfg5_large_table_bf16(dev, oracle):
         want_k = oracle.backward_coef_pair(xh, gyh, G, int(k))
         assert pair_slice_rel_err(got_k, want_k) <= TOL_F32
         assert np.all(got_k[want_k == 0.0] == 0.0)
+
+
+def test_cfg2_inference_stack_with_folded_normalisation(dev, oracle):
+    """The four layers chained for inference (App. F.1): the evaluation-mode batch normalisation
+    after each hidden layer, a per-output scale and shift, is folded into that layer's table, so
+    the device runs lmKAN -> lmKAN -> lmKAN -> lmKAN with nothing in between; the oracle applies
+    the normalisation explicitly in double precision on sampled rows.  The statistics are
+    seeded stand-ins for running statistics (scale ~ 1 / expected output deviation)."""
+    layers = wl.CFG2_LAYERS
+    g = torch.Generator(device="cpu").manual_seed(77)
+    x = wl.make_x(layers[0], dev)
+    rows = _rows(layers[0], 384, 177)
+    a_dev = x
+    a_ref = x.cpu().numpy()[rows]
+    worst = 0.0
+    for i, w in enumerate(layers):
+        P = wl.make_coef(w, dev)
+        paper, packed = _descs(w, "f32")
+        last = i == len(layers) - 1
+        if not last:
+            scale = (torch.rand((w.n_out,), generator=g) * 0.4 + 0.8) / (w.coef_std * (w.n_in / 2) ** 0.5)
+            shift = torch.randn((w.n_out,), generator=g) * 0.2
+            folded = P.clone()
+            pkg.lmkan_fold(paper, folded, 1.0, None, None, scale.to(dev), shift.to(dev))
+        else:
+            folded = P
+        a_dev = pkg.lmkan_forward(packed, a_dev, pkg.lmkan_pack(paper, folded))
+        torch.cuda.synchronize()
+        y = oracle.forward(a_ref, P.cpu().numpy(), w.grid, threads=THREADS)
+        if not last:
+            y = y * scale.numpy().astype(np.float64) + shift.numpy().astype(np.float64)
+        err = _rel_err(a_dev.cpu().numpy()[rows], y)
+        worst = max(worst, err)
+        # float32 rounding of one layer is ~1e-6 of the row scale; later layers see it magnified by
+        # the slope of the next layer's functions summed over its pairs, hence the wider bound
+        assert err <= (TOL_F32 if i == 0 else 2e-4), (i, err)
+        a_ref = y.astype(np.float32)     # the oracle's own activations feed its next layer
+    assert np.isfinite(worst)
