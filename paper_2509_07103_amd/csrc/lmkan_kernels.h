@@ -77,7 +77,7 @@ void launch_transpose(const float *in_t, float *out, int64_t batch, int n_in, hi
 // the transposed scratch [n_in][rows] -> grad_x: a transpose for a plain layer, for a convolution
 // the sum over the patches that contain each input element
 void launch_input_gradient_out(const float *in_t, float *gx, const LayerShape &s, const ConvGeom *conv,
-                               hipStream_t stream);
+                               hipStream_t stream, int scratch_layout = 0);
 
 // Coefficient gradient by cell-sorted samples (lmkan_backward.hip).  `records` is the output
 // of launch_preamble_records; `sorted` is scratch of sorted_records_bytes().  Needs n_out to be a

@@ -437,14 +437,15 @@ __global__ __launch_bounds__(WAVES * 64) __attribute__((amdgpu_waves_per_eu(WAVE
 // ---------------------------------------------------------------------------
 // out[B][n_in] = in[n_in][B]
 __global__ __launch_bounds__(256) void transpose_kernel(const float *__restrict__ in, float *__restrict__ out,
-                                                       int64_t B, int n_in)
+                                                       int64_t B, int n_in, int64_t ld, int layout)
 {
     __shared__ float tile[64][65];
     const int64_t n0 = (int64_t)blockIdx.x * 64;
     const int c0 = blockIdx.y * 64;
     const int tx = threadIdx.x & 63, ty = threadIdx.x >> 6;
+    const int64_t src = scratch_position(n0 + tx, layout);
     for (int r = ty; r < 64; r += 4)
-        if (c0 + r < n_in && n0 + tx < B) tile[r][tx] = in[(int64_t)(c0 + r) * B + n0 + tx];
+        if (c0 + r < n_in && n0 + tx < B) tile[r][tx] = in[(int64_t)(c0 + r) * ld + src];
     __syncthreads();
     for (int r = ty; r < 64; r += 4)
         if (n0 + r < B && c0 + tx < n_in) out[(n0 + r) * n_in + c0 + tx] = tile[tx][r];
@@ -565,9 +566,10 @@ __global__ __launch_bounds__(WAVES * 64) __attribute__((amdgpu_waves_per_eu(WAVE
     const int lane_bytes = l16 * 16;
     // where this lane's collected results go: sample 16 g + (l16 & 7) of each block of 8 steps,
     // input 2k (lanes 0-7) or 2k+1 (lanes 8-15).  The scratch gradient is stored transposed,
-    // [n_in][B], so that the eight lanes of a block hit 32 contiguous bytes.
+    // [n_in][ld], in the kScratchOct layout: the first block of 8 steps lands at 8 g + (l16 & 7),
+    // the second 32 further, so an atomic instruction covers 128 contiguous bytes of each row.
     const int64_t n_lane = n_wave + g * 16 + (l16 & 7);
-    float *gx_lane = a.gx + (int64_t)(l16 >> 3) * a.B + n_lane;
+    float *gx_lane = a.gx + (int64_t)(l16 >> 3) * a.ld + n_wave + g * 8 + (l16 & 7);
 
     for (int k = k_begin; k < k_end; ++k) {
         const float *slab = ((k - k_begin) & 1) ? slab1 : slab0;
@@ -614,7 +616,7 @@ __global__ __launch_bounds__(WAVES * 64) __attribute__((amdgpu_waves_per_eu(WAVE
             if ((l16 & 7) == (T & 7)) stash = v;
             if constexpr ((T & 7) == 7) {
                 const int64_t n = n_lane + (T / 16) * 64 + ((T % 16) & ~7);
-                if (n < a.B) unsafeAtomicAdd(gx_lane + (int64_t)(2 * k) * a.B + ((T / 16) * 64 + ((T % 16) & ~7)), stash);
+                if (n < a.B) unsafeAtomicAdd(gx_lane + (int64_t)(2 * k) * a.ld + ((T / 16) * 64 + ((T % 16) >> 3) * 32), stash);
             }
         });
         if (k + 1 < k_end) fill.template commit<1>(sa, slab_next, wave, lane);
@@ -681,7 +683,7 @@ __device__ __forceinline__ void fma_corners_quad(float *acc, const Corners &c, f
 }
 
 template <typename CT, int WAVES, int SETS>
-__global__ __launch_bounds__(WAVES * 64) __attribute__((amdgpu_waves_per_eu(2, 2))) void forward_slab_narrow_kernel(
+__global__ __launch_bounds__(WAVES * 64) __attribute__((amdgpu_waves_per_eu(WAVES / 4, WAVES / 4))) void forward_slab_narrow_kernel(
     SlabArgs a)
 {
     extern __shared__ __align__(16) float smem[];
@@ -847,7 +849,7 @@ __device__ __forceinline__ float grad_step_quad(const float4 g, const Corners &c
 }
 
 template <typename CT, int WAVES, int SETS>
-__global__ __launch_bounds__(WAVES * 64) __attribute__((amdgpu_waves_per_eu(2, 2))) void backward_input_slab_narrow_kernel(
+__global__ __launch_bounds__(WAVES * 64) __attribute__((amdgpu_waves_per_eu(WAVES / 4, WAVES / 4))) void backward_input_slab_narrow_kernel(
     GradInArgs a)
 {
     extern __shared__ __align__(16) float smem[];  // two slab buffers, then 1/h of the grid
@@ -900,7 +902,7 @@ __global__ __launch_bounds__(WAVES * 64) __attribute__((amdgpu_waves_per_eu(2, 2
         r_node[slot] = 0;
         r_u[slot] = 0.f;
         r_v[slot] = 0.f;
-        if (n < a.B && k < k_end) {
+        if (n < a.B && k >= 0) {
             const int64_t o = (int64_t)k * a.B + n;
             r_node[slot] = a.rec_node[o];
             r_u[slot] = a.rec_u[o];
@@ -915,27 +917,39 @@ __global__ __launch_bounds__(WAVES * 64) __attribute__((amdgpu_waves_per_eu(2, 2
         for (int i = threadIdx.x; i < 2 * slab_floats; i += blockDim.x) smem[i] = 0.0f;
         __syncthreads();
     }
+    // Workgroups that differ only in their output tile add into the same entries of the
+    // gradient.  Each starts its walk over the pairs at a different one, so that at any moment
+    // they are on different pairs and their atomics go to different cache lines.
+    const int n_k = k_end - k_begin;
+    const int rot = n_k > 0 ? (int)(((int64_t)jt * n_k) / a.n_jt) : 0;
+    auto pair_at = [&](int i) {  // pair of step i of the walk; -1 past its end
+        const int r = i + rot;
+        return i < n_k ? k_begin + (r >= n_k ? r - n_k : r) : -1;
+    };
     SlabFill<CT, WAVES, LPS> fill;
-    if (k_begin < k_end) {
+    if (n_k > 0) {
+        const int k0 = pair_at(0);
 #pragma unroll
-        for (int s = 0; s < SETS; ++s) fetch_record(s, k_begin);
-        fill.template issue<0>(sa, slab0, k_begin, jt, wave, lane);
+        for (int s = 0; s < SETS; ++s) fetch_record(s, k0);
+        fill.template issue<0>(sa, slab0, k0, jt, wave, lane);
         fill.template commit<0>(sa, slab0, wave, lane);
-        fill.template issue<1>(sa, slab0, k_begin, jt, wave, lane);
+        fill.template issue<1>(sa, slab0, k0, jt, wave, lane);
         fill.template commit<1>(sa, slab0, wave, lane);
     }
     const int lane_bytes = sub * 16;
     // where this lane's two results of a set go: samples 4 grp + (sub & 1) and + 2 more, input
     // 2k (lanes 0-1 of the quad) or 2k + 1 (lanes 2-3)
+    // (kScratchQuad layout of the scratch rows: the first two land at 2 grp + (sub & 1), the others 32 further)
     const int64_t n_lane = n_wave + grp * LPS + (sub & 1);
-    float *gx_lane = a.gx + (int64_t)(sub >> 1) * a.B + n_lane;
+    float *gx_lane = a.gx + (int64_t)(sub >> 1) * a.ld + n_wave + grp * 2 + (sub & 1);
 
-    for (int k = k_begin; k < k_end; ++k) {
-        const float *slab = ((k - k_begin) & 1) ? slab1 : slab0;
-        float *slab_next = ((k - k_begin) & 1) ? slab0 : slab1;
+    for (int step = 0; step < n_k; ++step) {
+        const int k = pair_at(step), k_next = pair_at(step + 1);
+        const float *slab = (step & 1) ? slab1 : slab0;
+        float *slab_next = (step & 1) ? slab0 : slab1;
         if constexpr (sizeof(CT) == 4) asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
         __syncthreads();
-        if (k + 1 < k_end) fill.template issue<0>(sa, slab_next, k + 1, jt, wave, lane);
+        if (k_next >= 0) fill.template issue<0>(sa, slab_next, k_next, jt, wave, lane);
 
         constexpr int kNear = 1;
         Corners ring[kNear + 1];
@@ -948,9 +962,9 @@ __global__ __launch_bounds__(WAVES * 64) __attribute__((amdgpu_waves_per_eu(2, 2
             constexpr int set = F / LPS, t = F % LPS;
             if constexpr (t == 0) {
                 if constexpr (set == SETS / 2) {
-                    if (k + 1 < k_end) {
+                    if (k_next >= 0) {
                         fill.template commit<0>(sa, slab_next, wave, lane);
-                        fill.template issue<1>(sa, slab_next, k + 1, jt, wave, lane);
+                        fill.template issue<1>(sa, slab_next, k_next, jt, wave, lane);
                     }
                 }
                 const int node = r_node[set];
@@ -964,7 +978,7 @@ __global__ __launch_bounds__(WAVES * 64) __attribute__((amdgpu_waves_per_eu(2, 2
                 if constexpr (set > 0) off_cur = off_nxt;
                 if constexpr (set + 1 < SETS) off_nxt = r_node[set + 1] * kNarrowRowBytes;
                 asm volatile("s_nop 1" : "+v"(b_lo), "+v"(b_hi), "+v"(a_lo), "+v"(a_hi), "+v"(off_cur), "+v"(off_nxt));
-                fetch_record(set, k + 1);
+                fetch_record(set, k_next);
             }
             if constexpr (F + kNear < STEPS) {
                 constexpr int F2 = F + kNear;
@@ -977,12 +991,12 @@ __global__ __launch_bounds__(WAVES * 64) __attribute__((amdgpu_waves_per_eu(2, 2
             }
             if constexpr (t == LPS - 1) {
                 const int64_t n = n_lane + set * 64;
-                float *dst = gx_lane + (int64_t)(2 * k) * a.B + set * 64;
+                float *dst = gx_lane + (int64_t)(2 * k) * a.ld + set * 64;
                 if (n < a.B) unsafeAtomicAdd(dst, stash_a);
-                if (n + 2 < a.B) unsafeAtomicAdd(dst + 2, stash_b);
+                if (n + 2 < a.B) unsafeAtomicAdd(dst + 32, stash_b);
             }
         });
-        if (k + 1 < k_end) fill.template commit<1>(sa, slab_next, wave, lane);
+        if (k_next >= 0) fill.template commit<1>(sa, slab_next, wave, lane);
     }
 }
 
@@ -1044,10 +1058,12 @@ static void launch_forward_slab_narrow(const LayerShape &s, const void *coef, fl
     constexpr int WAVES = 8, SETS = 8;
     constexpr int kTileB = WAVES * SETS * 64;
     typedef void (*Kernel)(SlabArgs);
-    const Kernel kernels[3] = {forward_slab_narrow_kernel<float, WAVES, SETS>,
+    // a float32 table needs no staging registers: 16 waves of 256 samples instead of 8 of 512
+    const Kernel kernels[3] = {forward_slab_narrow_kernel<float, 2 * WAVES, SETS / 2>,
                                forward_slab_narrow_kernel<_Float16, WAVES, SETS>,
                                forward_slab_narrow_kernel<bf16_t, WAVES, SETS>};
     const Kernel kernel = kernels[s.dtype];
+    const int waves = s.dtype == LMKAN_F32 ? 2 * WAVES : WAVES;
     static bool attr_set[3] = {false, false, false};
     if (!attr_set[s.dtype]) {
         (void)hipFuncSetAttribute(reinterpret_cast<const void *>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize,
@@ -1079,7 +1095,7 @@ static void launch_forward_slab_narrow(const LayerShape &s, const void *coef, fl
     a.pairs_per_split = (a.K + split - 1) / split;
     a.atomic_out = split > 1;
     if (a.atomic_out) launch_fill_zero(y, (size_t)s.batch * s.n_out, stream);
-    kernel<<<tiles * split, WAVES * 64, (size_t)2 * s.nodes() * kNarrowRowBytes, stream>>>(a);
+    kernel<<<tiles * split, waves * 64, (size_t)2 * s.nodes() * kNarrowRowBytes, stream>>>(a);
 }
 
 void launch_forward_slab(const LayerShape &s, const void *coef, float *y, const void *records,
@@ -1161,7 +1177,8 @@ namespace {
 // gx[img][y][x][c] = sum over the windows that contain (y, x) of the patch gradient
 // in_t[(ky kw + kx) C + c][row of that window]; elements no window covers get zero
 __global__ __launch_bounds__(256) void conv_input_gradient_kernel(const float *__restrict__ in_t,
-                                                                 float *__restrict__ gx, ConvGeom cg, int64_t rows)
+                                                                 float *__restrict__ gx, ConvGeom cg, int64_t ld,
+                                                                 int layout)
 {
     const int64_t total = (int64_t)cg.N * cg.H * cg.W * cg.C;
     const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
@@ -1182,7 +1199,7 @@ __global__ __launch_bounds__(256) void conv_input_gradient_kernel(const float *_
             const int ox = tx / cg.stride;
             if (ox >= cg.OW) continue;
             const int64_t row = (img * cg.OH + oy) * cg.OW + ox;
-            sum += in_t[(int64_t)((ky * cg.kw + kx) * cg.C + c) * rows + row];
+            sum += in_t[(int64_t)((ky * cg.kw + kx) * cg.C + c) * ld + scratch_position(row, layout)];
         }
     }
     gx[i] = sum;
@@ -1193,7 +1210,7 @@ __global__ __launch_bounds__(256) void conv_input_gradient_kernel(const float *_
 // block through an LDS tile: reads run along the rows, writes along the channels of a pixel.
 __global__ __launch_bounds__(256) void conv_input_gradient_scatter_kernel(const float *__restrict__ in_t,
                                                                          float *__restrict__ gx, ConvGeom cg,
-                                                                         int64_t rows, int n_in)
+                                                                         int64_t rows, int n_in, int64_t ld, int layout)
 {
     __shared__ float tile[64][65];
     __shared__ int64_t s_base[64];
@@ -1201,8 +1218,9 @@ __global__ __launch_bounds__(256) void conv_input_gradient_scatter_kernel(const 
     const int e0 = blockIdx.y * 64;
     const int tx = threadIdx.x & 63, ty = threadIdx.x >> 6;
     if (threadIdx.x < 64 && n0 + tx < rows) s_base[tx] = conv_input_offset(cg, n0 + tx, 0);
+    const int64_t src = scratch_position(n0 + tx, layout);
     for (int r = ty; r < 64; r += 4)
-        if (e0 + r < n_in && n0 + tx < rows) tile[r][tx] = in_t[(int64_t)(e0 + r) * rows + n0 + tx];
+        if (e0 + r < n_in && n0 + tx < rows) tile[r][tx] = in_t[(int64_t)(e0 + r) * ld + src];
     __syncthreads();
     const int e = e0 + tx;
     if (e >= n_in) return;
@@ -1215,10 +1233,12 @@ __global__ __launch_bounds__(256) void conv_input_gradient_scatter_kernel(const 
 }  // namespace
 
 void launch_input_gradient_out(const float *in_t, float *gx, const LayerShape &s, const ConvGeom *conv,
-                               hipStream_t stream)
+                               hipStream_t stream, int scratch_layout)
 {
+    const int64_t ld = scratch_row_stride(s.batch, scratch_layout);
     if (!conv) {
-        launch_transpose(in_t, gx, s.batch, s.n_in, stream);
+        const dim3 grid((unsigned)((s.batch + 63) / 64), (unsigned)((s.n_in + 63) / 64));
+        transpose_kernel<<<grid, 256, 0, stream>>>(in_t, gx, s.batch, s.n_in, ld, scratch_layout);
         return;
     }
     const ConvGeom &cg = *conv;
@@ -1227,21 +1247,22 @@ void launch_input_gradient_out(const float *in_t, float *gx, const LayerShape &s
         const bool covered = cg.stride == cg.kh && cg.stride == cg.kw && cg.OH * cg.kh == cg.H && cg.OW * cg.kw == cg.W;
         if (!covered) launch_fill_zero(gx, (size_t)total, stream);  // gaps between or beyond the windows
         const dim3 grid((unsigned)((s.batch + 63) / 64), (unsigned)((s.n_in + 63) / 64));
-        conv_input_gradient_scatter_kernel<<<grid, 256, 0, stream>>>(in_t, gx, cg, s.batch, s.n_in);
+        conv_input_gradient_scatter_kernel<<<grid, 256, 0, stream>>>(in_t, gx, cg, s.batch, s.n_in, ld, scratch_layout);
         return;
     }
-    conv_input_gradient_kernel<<<(unsigned)((total + 255) / 256), 256, 0, stream>>>(in_t, gx, cg, s.batch);
+    conv_input_gradient_kernel<<<(unsigned)((total + 255) / 256), 256, 0, stream>>>(in_t, gx, cg, ld, scratch_layout);
 }
 
 void launch_transpose(const float *in_t, float *out, int64_t batch, int n_in, hipStream_t stream)
 {
-    const dim3 tgrid((unsigned)((batch + 63) / 64), (unsigned)((n_in + 63) / 64));
-    transpose_kernel<<<tgrid, 256, 0, stream>>>(in_t, out, batch, n_in);
+    const dim3 grid((unsigned)((batch + 63) / 64), (unsigned)((n_in + 63) / 64));
+    transpose_kernel<<<grid, 256, 0, stream>>>(in_t, out, batch, n_in, batch, kScratchPlain);
 }
 
 size_t slab_backward_input_scratch_bytes(const LayerShape &s)
 {
-    return ((size_t)s.batch * s.n_in * sizeof(float) + 255) & ~(size_t)255;
+    // rows padded to whole blocks of 64 samples (the quad layout permutes inside such blocks)
+    return ((((size_t)s.batch + 63) & ~(size_t)63) * s.n_in * sizeof(float) + 255) & ~(size_t)255;
 }
 
 void launch_backward_input_slab(const LayerShape &s, const GridTab &tab, const void *coef, const float *gy,
@@ -1266,7 +1287,7 @@ void launch_backward_input_slab(const LayerShape &s, const GridTab &tab, const v
     const Kernel kernels[9] = {backward_input_slab_kernel<float, LMKAN_GX_WAVES, 16 / LMKAN_GX_WAVES, LMKAN_GX_AHEAD, 0>,
                                backward_input_slab_kernel<_Float16, WAVES, SETS, 2, 0>,
                                backward_input_slab_kernel<bf16_t, WAVES, SETS, 2, 0>,
-                               backward_input_slab_narrow_kernel<float, WAVES, kNarrowSets>,
+                               backward_input_slab_narrow_kernel<float, 2 * WAVES, kNarrowSets / 2>,
                                backward_input_slab_narrow_kernel<_Float16, WAVES, kNarrowSets>,
                                backward_input_slab_narrow_kernel<bf16_t, WAVES, kNarrowSets>,
                                backward_input_slab_kernel<float, LMKAN_GX_WAVES, 16 / LMKAN_GX_WAVES, LMKAN_GX_AHEAD, 17>,
@@ -1306,11 +1327,13 @@ void launch_backward_input_slab(const LayerShape &s, const GridTab &tab, const v
     while (tiles * split < 256 && a.K / (split * 2) >= 32) split *= 2;
     a.n_split = split;
     a.pairs_per_split = (a.K + split - 1) / split;
-    launch_fill_zero(a.gx, (size_t)s.batch * s.n_in, stream);
+    const int layout = narrow ? kScratchQuad : kScratchOct;
+    a.ld = scratch_row_stride(s.batch, layout);
+    launch_fill_zero(a.gx, (size_t)a.ld * s.n_in, stream);
     const size_t slabs = narrow ? (size_t)2 * s.nodes() * kNarrowRowBytes : slab_forward_lds_bytes(s);
-    const int waves = (s.dtype == LMKAN_F32 && !narrow) ? LMKAN_GX_WAVES : WAVES;
+    const int waves = s.dtype == LMKAN_F32 ? (narrow ? 2 * WAVES : LMKAN_GX_WAVES) : WAVES;
     kernel<<<tiles * split, waves * 64, slabs + LMKAN_MAX_GRID * sizeof(float), stream>>>(a);
-    launch_input_gradient_out(a.gx, gx, s, conv, stream);
+    launch_input_gradient_out(a.gx, gx, s, conv, stream, layout);
 }
 
 }  // namespace lmkan

@@ -60,7 +60,8 @@ __device__ __forceinline__ void lds_dma16_uniform(const void *gbase, unsigned la
 struct GradInArgs {
     const void *P;     // float32, or 16-bit storage converted while the slab is filled
     const float *gy;
-    float *gx;  // transposed scratch [n_in][B], zero on entry
+    float *gx;  // transposed scratch [n_in][ld], zero on entry
+    int64_t ld; // row stride of the scratch: B, or B rounded up to 64 with a permuted layout
     const int32_t *rec_node;
     const float *rec_u;
     const float *rec_v;
@@ -79,6 +80,30 @@ struct GradInArgs {
     int col_limit;
     int packed;
 };
+
+// Layouts of a row of the transposed scratch gradient.  The slab kernels leave a set of 64
+// samples spread over the lanes so that one atomic instruction holds every other run of 8
+// (64-output tiles) or 2 (16-output tiles) samples; stored plainly, the instruction would touch
+// 32- or 8-byte pieces with gaps.  Inside each aligned block of 64 samples the row is therefore
+// permuted so that each instruction covers 128 contiguous bytes:
+//   kScratchOct  (64-output tiles): sample s = 16 g + 8 h + i  sits at 32 h + 8 g + i
+//   kScratchQuad (16-output tiles): sample s = 4 g + 2 h + i   sits at 32 h + 2 g + i
+// Rows are padded to whole blocks.  The kernels that read the scratch undo the permutation.
+enum ScratchLayout { kScratchPlain = 0, kScratchOct = 1, kScratchQuad = 2 };
+
+__host__ __device__ inline int64_t scratch_position(int64_t n, int layout)
+{
+    if (layout == kScratchPlain) return n;
+    const int s = (int)(n & 63);
+    const int p = layout == kScratchOct ? ((s & 8) << 2) + ((s >> 4) << 3) + (s & 7)
+                                        : ((s & 2) << 4) + ((s >> 2) << 1) + (s & 1);
+    return (n & ~(int64_t)63) + p;
+}
+
+__host__ __device__ inline int64_t scratch_row_stride(int64_t batch, int layout)
+{
+    return layout == kScratchPlain ? batch : (batch + 63) & ~(int64_t)63;
+}
 
 template <int CTRL>
 __device__ __forceinline__ float dpp_move(float v)

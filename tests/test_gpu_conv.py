@@ -35,6 +35,9 @@ CASES = [
     (3, 9, 10, 2, 2, 2, 1, 10, 5),      # 216   generic (10 outputs), overlapping: atomics into the image
     (2, 16, 16, 8, 1, 1, 1, 32, 16),    # 512   1x1: the layer on pixel rows
     (1, 4, 4, 2, 4, 4, 4, 6, 4),        # 1     one window
+    (5, 18, 18, 4, 3, 3, 1, 20, 20),    # 1280  16-output slabs (G > 16), overlapping windows
+    (3, 20, 20, 2, 2, 2, 2, 24, 24),    # 300   16-output slabs, rows not a multiple of 64
+    (3, 21, 20, 2, 2, 2, 2, 64, 8),     # 300   64-output slabs, rows not a multiple of 64, a row of pixels left over
 ]
 
 
