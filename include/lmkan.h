@@ -118,7 +118,11 @@ lmkan_status lmkan_pack(const lmkan_desc *desc, const void *coef_paper_dev, void
 /*
  * Device scratch memory lmkan_forward (pass = 0) or lmkan_backward (pass = 1)
  * needs for this batch size; may be 0.  Forward: the preamble records of Alg. 1
- * (cell and local coordinates per (sample, pair), 12 bytes each).  Backward:
+ * (cell and local coordinates per (sample, pair), 12 bytes each) and, when few
+ * samples and outputs leave compute units idle and the pairs are therefore split
+ * over several workgroups, one [batch][n_out] float32 partial output per extra
+ * split (summed in a fixed order: the forward result does not vary between runs,
+ * except for n_out <= 8, where the splits add atomically).  Backward:
  * the same records, their copy sorted by cell for the coefficient gradient
  * (about 21 bytes per (sample, pair) plus per-pair tables), and a transposed
  * float32 copy of grad_x.  The contents are scratch: nothing is kept between

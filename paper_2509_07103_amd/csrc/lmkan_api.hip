@@ -112,7 +112,11 @@ size_t lmkan_workspace_bytes(const lmkan_desc *desc, int64_t batch, int32_t pass
 {
     if (check_desc(desc) != LMKAN_OK || batch <= 0) return 0;
     const LayerShape s = shape_of(desc, batch);
-    if (pass == 0) return (slab_forward_shape_ok(s) || small_out_shape_ok(s)) ? records_bytes(s) : 0;
+    // forward: preamble records, then the partial outputs of a forward split over the pairs
+    if (pass == 0) {
+        if (small_out_shape_ok(s)) return records_bytes(s);
+        return slab_forward_shape_ok(s) ? align256(records_bytes(s)) + slab_forward_partial_bytes(s) : 0;
+    }
     // backward: preamble records, the cell-sorted copy used by the coefficient gradient, and the
     // transposed scratch of the input gradient
     return align256(records_bytes(s)) + sorted_records_bytes(s) +
@@ -174,7 +178,10 @@ lmkan_status forward_impl(const lmkan_desc *desc, int64_t batch, const float *x_
         launch_forward_small(s, coef_dev, y_dev, workspace_dev, hs);
     } else if (slab_forward_applicable(s, coef_dev, y_dev)) {
         launch_preamble_records(s, tab, x_dev, workspace_dev, hs, conv);
-        launch_forward_slab(s, coef_dev, y_dev, workspace_dev, hs);
+        float *partials = slab_forward_partial_bytes(s) > 0
+                              ? reinterpret_cast<float *>(static_cast<char *>(workspace_dev) + align256(records_bytes(s)))
+                              : nullptr;
+        launch_forward_slab(s, coef_dev, y_dev, workspace_dev, partials, hs);
     } else {
         launch_forward_generic(s, tab, x_dev, coef_dev, y_dev, hs, conv);
     }

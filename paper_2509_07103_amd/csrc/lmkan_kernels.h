@@ -45,7 +45,13 @@ bool slab_forward_shape_ok(const LayerShape &s);
 bool slab_forward_applicable(const LayerShape &s, const void *coef, const float *y);
 void launch_preamble_records(const LayerShape &s, const GridTab &tab, const float *x, void *records,
                              hipStream_t stream, const ConvGeom *conv = nullptr);
-void launch_forward_slab(const LayerShape &s, const void *coef, float *y, const void *records,
+// Pair splits of the slab forward (1: none) and the bytes of the split - 1 partial outputs
+// [batch][n_out] it then needs; `partials` = NULL makes the splits add into y atomically.
+int slab_forward_split(const LayerShape &s);
+size_t slab_forward_partial_bytes(const LayerShape &s);
+// y[i] += sum over p of part[p][i], i < elems (a multiple of 4)
+void launch_sum_partials(float *y, const float *part, int n_part, int64_t elems, hipStream_t stream);
+void launch_forward_slab(const LayerShape &s, const void *coef, float *y, const void *records, float *partials,
                          hipStream_t stream);
 
 bool slab_backward_input_shape_ok(const LayerShape &s);
@@ -58,7 +64,8 @@ void launch_backward_input_slab(const LayerShape &s, const GridTab &tab, const v
 // float16 tables kept as float16 in LDS (lmkan_slab_f16.hip); reached through the two slab
 // launchers above when slab_f16_native_ok().  gx_scratch is the zero-filled transposed scratch.
 bool slab_f16_native_ok(const LayerShape &s);
-void launch_forward_slab_f16(const LayerShape &s, const void *coef, float *y, const void *records, hipStream_t stream);
+void launch_forward_slab_f16(const LayerShape &s, const void *coef, float *y, const void *records, float *partials,
+                             hipStream_t stream);
 void launch_backward_input_slab_f16(const LayerShape &s, const GridTab &tab, const void *coef, const float *gy,
                                     float *gx_scratch, const void *records, hipStream_t stream);
 

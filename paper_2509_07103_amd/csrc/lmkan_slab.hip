@@ -400,6 +400,8 @@ __global__ __launch_bounds__(WAVES * 64) __attribute__((amdgpu_waves_per_eu(WAVE
 
     // lane (g, l16) holds outputs jt*64 + 4*l16 .. +3 of samples n_wave + set*64 + 16*g + step
     const int col = jt * kTile + l16 * 4;
+    bool atomic;
+    float *ybase = forward_out_base(a, ks, atomic);
     if (col < a.n_out) {
 #pragma unroll
         for (int s = 0; s < SETS; ++s) {
@@ -407,9 +409,9 @@ __global__ __launch_bounds__(WAVES * 64) __attribute__((amdgpu_waves_per_eu(WAVE
             for (int st = 0; st < 16; ++st) {
                 const int64_t n = n_wave + s * 64 + g * 16 + st;
                 if (n < a.B) {
-                    float *dst = a.y + n * a.n_out + col;
+                    float *dst = ybase + n * a.n_out + col;
                     const float *v = acc + s * 64 + st * 4;
-                    if (a.atomic_out) {
+                    if (atomic) {
                         unsafeAtomicAdd(dst + 0, v[0]);
                         unsafeAtomicAdd(dst + 1, v[1]);
                         unsafeAtomicAdd(dst + 2, v[2]);
@@ -791,14 +793,16 @@ __global__ __launch_bounds__(WAVES * 64) __attribute__((amdgpu_waves_per_eu(WAVE
 
     // lane (grp, sub) holds outputs jt*16 + 4*sub .. +3 of samples n_wave + set*64 + 4*grp + t
     const int col = jt * kNarrowTile + sub * 4;
+    bool atomic;
+    float *ybase = forward_out_base(a, ks, atomic);
     if (col < a.n_out) {
 #pragma unroll
         for (int F = 0; F < STEPS; ++F) {
             const int64_t n = n_wave + (F / LPS) * 64 + grp * LPS + (F % LPS);
             if (n < a.B) {
-                float *dst = a.y + n * a.n_out + col;
+                float *dst = ybase + n * a.n_out + col;
                 const float *v = acc + 4 * F;
-                if (a.atomic_out) {
+                if (atomic) {
                     unsafeAtomicAdd(dst + 0, v[0]);
                     unsafeAtomicAdd(dst + 1, v[1]);
                     unsafeAtomicAdd(dst + 2, v[2]);
@@ -1046,6 +1050,49 @@ static bool slab_narrow_ok(const LayerShape &s)
 
 bool slab_forward_shape_ok(const LayerShape &s) { return slab_wide_ok(s) || slab_narrow_ok(s); }
 
+// Samples per forward workgroup: 1024 with 64-output tiles, 4096 with 16-output tiles.
+int slab_forward_split(const LayerShape &s)
+{
+    if (!slab_forward_shape_ok(s)) return 1;
+    const bool wide = slab_wide_ok(s);
+    const int64_t tile_b = wide ? 1024 : 4096;
+    const int64_t n_jt = wide ? s.out_tiles() : (s.n_out + 15) / 16;
+    return pair_split_count((int)(((s.batch + tile_b - 1) / tile_b) * n_jt), s.pairs());
+}
+
+size_t slab_forward_partial_bytes(const LayerShape &s)
+{
+    const size_t parts = (size_t)slab_forward_split(s) - 1;
+    return (parts * (size_t)s.batch * s.n_out * sizeof(float) + 255) & ~(size_t)255;
+}
+
+namespace {
+__global__ __launch_bounds__(256) void sum_partials_kernel(float4 *__restrict__ y, const float4 *__restrict__ part,
+                                                          int n_part, int64_t quads)
+{
+    const int64_t stride = (int64_t)gridDim.x * 256;
+    for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < quads; i += stride) {
+        float4 v = y[i];
+        for (int p = 0; p < n_part; ++p) {
+            const float4 w = part[(int64_t)p * quads + i];
+            v.x += w.x;
+            v.y += w.y;
+            v.z += w.z;
+            v.w += w.w;
+        }
+        y[i] = v;
+    }
+}
+}  // namespace
+
+void launch_sum_partials(float *y, const float *part, int n_part, int64_t elems, hipStream_t stream)
+{
+    const int64_t quads = elems / 4;
+    const int64_t blocks = (quads + 255) / 256;
+    sum_partials_kernel<<<(unsigned)(blocks < 8192 ? blocks : 8192), 256, 0, stream>>>(
+        reinterpret_cast<float4 *>(y), reinterpret_cast<const float4 *>(part), n_part, quads);
+}
+
 bool slab_forward_applicable(const LayerShape &s, const void *coef, const float *y)
 {
     if (!slab_forward_shape_ok(s)) return false;
@@ -1053,7 +1100,7 @@ bool slab_forward_applicable(const LayerShape &s, const void *coef, const float 
 }
 
 static void launch_forward_slab_narrow(const LayerShape &s, const void *coef, float *y, const void *records,
-                                       hipStream_t stream)
+                                       float *partials, hipStream_t stream)
 {
     constexpr int WAVES = 8, SETS = 8;
     constexpr int kTileB = WAVES * SETS * 64;
@@ -1089,24 +1136,23 @@ static void launch_forward_slab_narrow(const LayerShape &s, const void *coef, fl
     a.n_btiles = (int)((s.batch + kTileB - 1) / kTileB);
     a.n_jt = (s.n_out + kNarrowTile - 1) / kNarrowTile;
     const int tiles = a.n_btiles * a.n_jt;
-    int split = 1;
-    while (tiles * split < 256 && a.K / (split * 2) >= 32) split *= 2;
+    const int split = pair_split_count(tiles, a.K);
     a.n_split = split;
     a.pairs_per_split = (a.K + split - 1) / split;
-    a.atomic_out = split > 1;
-    if (a.atomic_out) launch_fill_zero(y, (size_t)s.batch * s.n_out, stream);
+    finish_split_setup(a, s, y, partials, stream);
     kernel<<<tiles * split, waves * 64, (size_t)2 * s.nodes() * kNarrowRowBytes, stream>>>(a);
+    if (a.y_part) launch_sum_partials(y, a.y_part, split - 1, a.part_elems, stream);
 }
 
-void launch_forward_slab(const LayerShape &s, const void *coef, float *y, const void *records,
+void launch_forward_slab(const LayerShape &s, const void *coef, float *y, const void *records, float *partials,
                          hipStream_t stream)
 {
     if (!slab_wide_ok(s)) {
-        launch_forward_slab_narrow(s, coef, y, records, stream);
+        launch_forward_slab_narrow(s, coef, y, records, partials, stream);
         return;
     }
     if (slab_f16_native_ok(s)) {
-        launch_forward_slab_f16(s, coef, y, records, stream);
+        launch_forward_slab_f16(s, coef, y, records, partials, stream);
         return;
     }
     // 1024 samples per workgroup either way: 16 waves x 64 samples for float32 tables, 8 x 128 for
@@ -1150,13 +1196,12 @@ void launch_forward_slab(const LayerShape &s, const void *coef, float *y, const 
     a.n_jt = s.out_tiles();
     // split the pairs over several workgroups when the tiles alone cannot fill 256 CUs
     const int tiles = a.n_btiles * a.n_jt;
-    int split = 1;
-    while (tiles * split < 256 && a.K / (split * 2) >= 32) split *= 2;
+    const int split = pair_split_count(tiles, a.K);
     a.n_split = split;
     a.pairs_per_split = (a.K + split - 1) / split;
-    a.atomic_out = split > 1;
-    if (a.atomic_out) launch_fill_zero(y, (size_t)s.batch * s.n_out, stream);
+    finish_split_setup(a, s, y, partials, stream);
     kernel<<<tiles * split, waves * 64, slab_forward_lds_bytes(s), stream>>>(a);
+    if (a.y_part) launch_sum_partials(y, a.y_part, split - 1, a.part_elems, stream);
 }
 
 }  // namespace lmkan

@@ -28,7 +28,37 @@ struct SlabArgs {
     int n_jt;
     int n_split;
     int atomic_out;    // 1: add into y with atomics (split over pairs), 0: plain store
+    // Split over pairs without atomics: the workgroups of split 0 store into y, those of split
+    // ks > 0 into y_part + (ks - 1) * part_elems, and a later pass adds the parts to y.
+    float *y_part;     // NULL: use atomic_out
+    int64_t part_elems;
 };
+
+// Pair splits for a launch of `tiles` workgroups over K pairs: double until 256 CUs have work,
+// keeping at least 32 pairs per split.
+inline int pair_split_count(int tiles, int K)
+{
+    int split = 1;
+    while (tiles * split < 256 && K / (split * 2) >= 32) split *= 2;
+    return split;
+}
+
+// How the splits of a forward launch combine: separate parts when the caller brought room for
+// them, atomics on a cleared y otherwise.
+inline void finish_split_setup(SlabArgs &a, const LayerShape &s, float *y, float *partials, hipStream_t stream)
+{
+    a.y_part = a.n_split > 1 ? partials : nullptr;
+    a.part_elems = (int64_t)s.batch * s.n_out;
+    a.atomic_out = a.n_split > 1 && !a.y_part;
+    if (a.atomic_out) launch_fill_zero(y, (size_t)s.batch * s.n_out, stream);
+}
+
+// where a forward workgroup of pair split ks stores, and whether it has to add atomically
+__device__ __forceinline__ float *forward_out_base(const SlabArgs &a, int ks, bool &atomic)
+{
+    atomic = a.atomic_out && !a.y_part;
+    return (a.y_part && ks > 0) ? a.y_part + (int64_t)(ks - 1) * a.part_elems : a.y;
+}
 
 // 16 bytes per lane from global memory straight into LDS at lds_base + lane * 16
 // (lds_base wave-uniform).  Written as inline assembly on purpose: the compiler does not

@@ -170,14 +170,16 @@ __global__ __launch_bounds__(kWaves * 64) __attribute__((amdgpu_waves_per_eu(4, 
 
     // lane (g, l16) holds outputs jt*64 + 4*l16 .. +3 of samples n_wave + 16*g + step
     const int col = jt * kTile + l16 * 4;
+    bool atomic;
+    float *ybase = forward_out_base(a, ks, atomic);
     if (col < a.n_out) {
 #pragma unroll
         for (int st = 0; st < 16; ++st) {
             const int64_t n = n_wave + g * 16 + st;
             if (n < a.B) {
-                float *dst = a.y + n * a.n_out + col;
+                float *dst = ybase + n * a.n_out + col;
                 const float *v = acc + st * 4;
-                if (a.atomic_out) {
+                if (atomic) {
                     unsafeAtomicAdd(dst + 0, v[0]);
                     unsafeAtomicAdd(dst + 1, v[1]);
                     unsafeAtomicAdd(dst + 2, v[2]);
@@ -343,7 +345,8 @@ bool slab_f16_native_ok(const LayerShape &s)
     return true;
 }
 
-void launch_forward_slab_f16(const LayerShape &s, const void *coef, float *y, const void *records, hipStream_t stream)
+void launch_forward_slab_f16(const LayerShape &s, const void *coef, float *y, const void *records, float *partials,
+                             hipStream_t stream)
 {
     constexpr int kTileB = kWaves * 64;
     static bool attr_set = false;
@@ -371,13 +374,12 @@ void launch_forward_slab_f16(const LayerShape &s, const void *coef, float *y, co
     a.n_btiles = (int)((s.batch + kTileB - 1) / kTileB);
     a.n_jt = s.out_tiles();
     const int tiles = a.n_btiles * a.n_jt;
-    int split = 1;
-    while (tiles * split < 256 && a.K / (split * 2) >= 32) split *= 2;
+    const int split = pair_split_count(tiles, a.K);
     a.n_split = split;
     a.pairs_per_split = (a.K + split - 1) / split;
-    a.atomic_out = split > 1;
-    if (a.atomic_out) launch_fill_zero(y, (size_t)s.batch * s.n_out, stream);
+    finish_split_setup(a, s, y, partials, stream);
     forward_slab_f16_kernel<<<tiles * split, kWaves * 64, (size_t)2 * s.nodes() * kRowBytesH, stream>>>(a);
+    if (a.y_part) launch_sum_partials(y, a.y_part, split - 1, a.part_elems, stream);
 }
 
 void launch_backward_input_slab_f16(const LayerShape &s, const GridTab &tab, const void *coef, const float *gy,
