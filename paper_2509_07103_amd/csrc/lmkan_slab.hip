@@ -1315,9 +1315,10 @@ void launch_backward_input_slab(const LayerShape &s, const GridTab &tab, const v
                                 const ConvGeom *conv)
 {
     if (slab_wide_ok(s) && slab_f16_native_ok(s)) {
-        launch_fill_zero(static_cast<float *>(scratch), (size_t)s.batch * s.n_in, stream);
+        launch_fill_zero(static_cast<float *>(scratch), (size_t)scratch_row_stride(s.batch, kScratchOct) * s.n_in,
+                         stream);
         launch_backward_input_slab_f16(s, tab, coef, gy, static_cast<float *>(scratch), records, stream);
-        launch_input_gradient_out(static_cast<float *>(scratch), gx, s, conv, stream);
+        launch_input_gradient_out(static_cast<float *>(scratch), gx, s, conv, stream, kScratchOct);
         return;
     }
     constexpr int WAVES = 8, SETS = 2;

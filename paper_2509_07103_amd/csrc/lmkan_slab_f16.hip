@@ -297,7 +297,9 @@ __global__ __launch_bounds__(kWaves * 64) __attribute__((amdgpu_waves_per_eu(4, 
     }
     const int lane_bytes = l16 * 8;
     const int64_t n_lane = n_wave + g * 16 + (l16 & 7);
-    float *gx_lane = a.gx + (int64_t)(l16 >> 3) * a.B + n_lane;
+    // kScratchOct layout of the scratch rows: the first eight steps land at 8 g + (l16 & 7), the
+    // other eight 32 further
+    float *gx_lane = a.gx + (int64_t)(l16 >> 3) * a.ld + n_wave + g * 8 + (l16 & 7);
 
     for (int k = k_begin; k < k_end; ++k) {
         const unsigned cur = ((k - k_begin) & 1) ? base1 : base0;
@@ -328,7 +330,7 @@ __global__ __launch_bounds__(kWaves * 64) __attribute__((amdgpu_waves_per_eu(4, 
             if ((l16 & 7) == (T & 7)) stash = v;
             if constexpr ((T & 7) == 7) {
                 const int64_t n = n_lane + (T & ~7);
-                if (n < a.B) unsafeAtomicAdd(gx_lane + (int64_t)(2 * k) * a.B + (T & ~7), stash);
+                if (n < a.B) unsafeAtomicAdd(gx_lane + (int64_t)(2 * k) * a.ld + (T >> 3) * 32, stash);
             }
         });
     }
@@ -403,6 +405,7 @@ void launch_backward_input_slab_f16(const LayerShape &s, const GridTab &tab, con
     a.map = coef_map(s);
     a.tab = tab;
     a.B = s.batch;
+    a.ld = scratch_row_stride(s.batch, kScratchOct);
     a.n_in = s.n_in;
     a.n_out = s.n_out;
     a.K = s.pairs();
