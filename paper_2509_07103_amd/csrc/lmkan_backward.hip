@@ -95,10 +95,21 @@ __global__ __launch_bounds__(kSortSegThreads) void sort_count_kernel(const int32
     const int64_t n0 = (int64_t)blk * kSortSeg;
     const int64_t n1 = n0 + kSortSeg < B ? n0 + kSortSeg : B;
     const int32_t *node_k = rec_node + (int64_t)k * B;
-    for (int64_t n = n0 + threadIdx.x; n < n1; n += blockDim.x) {
-        const int c = cell_of_node(node_k[n], G);
-        atomicAdd(&s_count[c], 1);
-        s_rep[c] = (int)n;  // any writer wins
+    // all loads of the thread first: these passes are bound by the bytes in flight
+    constexpr int kPer = kSortSeg / kSortSegThreads;
+    int nd[kPer];
+#pragma unroll
+    for (int j = 0; j < kPer; ++j) {
+        const int64_t n = n0 + threadIdx.x + j * kSortSegThreads;
+        nd[j] = n < n1 ? node_k[n] : -1;
+    }
+#pragma unroll
+    for (int j = 0; j < kPer; ++j) {
+        if (nd[j] >= 0) {
+            const int c = cell_of_node(nd[j], G);
+            atomicAdd(&s_count[c], 1);
+            s_rep[c] = (int)(n0 + threadIdx.x + j * kSortSegThreads);  // any writer wins
+        }
     }
     __syncthreads();
     int32_t *out = seg_count + ((int64_t)k * nblk + blk) * cells;
@@ -302,12 +313,32 @@ __global__ __launch_bounds__(kSortSegThreads) void sort_scatter_kernel(const int
     const int32_t *node_k = rec_node + (int64_t)k * B + n0;
     const float *u_k = rec_u + (int64_t)k * B + n0;
     const float *v_k = rec_v + (int64_t)k * B + n0;
-    for (int i = threadIdx.x; i < count; i += blockDim.x) {
-        const int c = cell_of_node(node_k[i], G);
-        s_cell[i] = (unsigned short)c;
-        s_rank[i] = (unsigned short)atomicAdd(&s_cnt[c], 1);
-        s_u[i] = u_k[i];
-        s_v[i] = v_k[i];
+    {
+        constexpr int kPer = kSortSeg / kSortSegThreads;
+        int nd[kPer];
+        float uu[kPer], vv[kPer];
+#pragma unroll
+        for (int j = 0; j < kPer; ++j) {
+            const int i = threadIdx.x + j * kSortSegThreads;
+            nd[j] = -1;
+            uu[j] = vv[j] = 0.f;
+            if (i < count) {
+                nd[j] = node_k[i];
+                uu[j] = u_k[i];
+                vv[j] = v_k[i];
+            }
+        }
+#pragma unroll
+        for (int j = 0; j < kPer; ++j) {
+            const int i = threadIdx.x + j * kSortSegThreads;
+            if (nd[j] >= 0) {
+                const int c = cell_of_node(nd[j], G);
+                s_cell[i] = (unsigned short)c;
+                s_rank[i] = (unsigned short)atomicAdd(&s_cnt[c], 1);
+                s_u[i] = uu[j];
+                s_v[i] = vv[j];
+            }
+        }
     }
     __syncthreads();
     // exclusive scan of the populations: a run of consecutive cells per thread

@@ -78,18 +78,28 @@ __global__ __launch_bounds__(256) void preamble_records_kernel(GridTab tab, cons
         }
     }
     __syncthreads();
-#pragma unroll 4
-    for (int r = r0; r < kRecTile; r += 4) {
+    // all sixteen loads of the thread first: the pass is bound by how many bytes are in flight
+    const bool pair_ok = k0 + p < K;
+    float2 xv[kRecTile / 4];
+#pragma unroll
+    for (int i = 0; i < kRecTile / 4; ++i) {
+        const int r = r0 + 4 * i;
         const int64_t n = n0 + r;
+        xv[i] = make_float2(0.f, 0.f);
+        if (n < B && pair_ok) {
+            if constexpr (CONV)
+                xv[i] = make_float2(x[s_base[r] + e_off0], x[s_base[r] + e_off1]);
+            else
+                xv[i] = load_input_pair<false>(x, n, n_in, k0 + p, cg);
+        }
+    }
+#pragma unroll
+    for (int i = 0; i < kRecTile / 4; ++i) {
+        const int r = r0 + 4 * i;
         int node = 0;
         float u = 0.f, v = 0.f;
-        if (n < B && k0 + p < K) {
-            float2 xv;
-            if constexpr (CONV)
-                xv = make_float2(x[s_base[r] + e_off0], x[s_base[r] + e_off1]);
-            else
-                xv = load_input_pair<false>(x, n, n_in, k0 + p, cg);
-            const Preamble pr = preamble(s_node, s_invh, tab.G, xv.x, xv.y);
+        if (n0 + r < B && pair_ok) {
+            const Preamble pr = preamble(s_node, s_invh, tab.G, xv[i].x, xv[i].y);
             node = pr.node;
             u = pr.a_hi;
             v = pr.b_hi;
