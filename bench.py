@@ -235,6 +235,19 @@ def main():
                           "vs_hbm_peak": round(hess_bytes / (hess_ms * 1e-3) / 1e9 / PEAK_HBM_GBS, 3),
                           "note": "value + gradient of the off-diagonal Hessian regulariser; not part of the step"}
 
+    # ---- yardstick of App. G: a dense float32 linear layer of the same shape (library GEMM) ------------
+    # The paper normalises its kernel by this ratio (about 8 on its H100 for large batches).  Context only.
+    if not conv and w.n_in * n_out * 4 <= 1 << 28:
+        xw = torch.randn((w.n_in, n_out), dtype=torch.float32, device=dev)
+        yl = torch.empty((B, n_out), dtype=torch.float32, device=dev)
+        for _ in range(3):      # library set-up and kernel selection happen on the first calls
+            torch.matmul(x, xw, out=yl)
+        torch.cuda.synchronize()
+        lin_ms = event_ms(lambda: torch.matmul(x, xw, out=yl), reps)
+        out["dense_linear"] = {"ms": round(lin_ms, 4), "forward_ratio": round(fwd_ms / lin_ms, 2),
+                               "note": "torch.matmul float32 [B,n_in]x[n_in,n_out]; lmKAN forward time / this"}
+        del xw, yl
+
     if args.calibrate_copy:
         src = torch.empty(1 << 28, dtype=torch.float32, device=dev).normal_()
         dst = torch.empty_like(src)
