@@ -27,8 +27,8 @@ PEAK_HBM_GBS = 8000.0
 # here per (workload, storage, kernel); anything not measured reports null.
 MEASURED_TRAFFIC_BYTES = {
     ("cfg3_1024x1024_G16", "f32", "backward_input_slab_kernel"): 1.581e9,
-    ("cfg3_1024x1024_G16", "f32", "forward_slab_kernel"): 1.278e9,
-    ("cfg3_1024x1024_G16", "f32", "backward_coef_stream_kernel"): 2.707e9,
+    ("cfg3_1024x1024_G16", "f32", "forward_slab_kernel"): 1.076e9,
+    ("cfg3_1024x1024_G16", "f32", "backward_coef_stream_kernel"): 2.823e9,
 }
 
 
