@@ -91,9 +91,6 @@ def main():
     torch.cuda.synchronize()
     pack_ms = (time.perf_counter() - t0) * 1e3
     desc = pkg.LayerDesc(w.n_in, n_out, w.grid, coef_dtype=dt_code, coef_layout=pkg.LMKAN_LAYOUT_PACKED)
-    desc_acc = pkg.LayerDesc(w.n_in, n_out, w.grid, coef_dtype=dt_code,
-                             coef_layout=pkg.LMKAN_LAYOUT_PACKED,
-                             flags=pkg.LMKAN_FLAG_ACCUMULATE_GRAD_COEF)
 
     y = torch.empty((B, n_out), dtype=torch.float32, device=dev)
     gx = torch.empty_like(x)
@@ -101,7 +98,7 @@ def main():
     need = max(pkg.lmkan_workspace_bytes(desc, B, False), pkg.lmkan_workspace_bytes(desc, B, True), 256)
     ws = torch.empty(need, dtype=torch.uint8, device=dev)
     stream = torch.cuda.current_stream().cuda_stream
-    d, d_acc = desc.c(), desc_acc.c()
+    d = desc.c()
 
     if conv:
         geom = pkg.Conv2d(w.n, w.h, w.w, w.c_in, w.kh, w.kw, w.stride).c()

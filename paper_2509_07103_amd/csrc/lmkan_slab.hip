@@ -1129,7 +1129,6 @@ static void launch_forward_slab_narrow(const LayerShape &s, const void *coef, fl
     }
     const size_t n = (size_t)s.pairs() * (size_t)s.batch;
     SlabArgs a;
-    a.x_unused = nullptr;
     a.P = coef;
     a.y = y;
     a.rec_node = static_cast<const int32_t *>(records);
@@ -1188,7 +1187,6 @@ void launch_forward_slab(const LayerShape &s, const void *coef, float *y, const 
     }
     const size_t n = (size_t)s.pairs() * (size_t)s.batch;
     SlabArgs a;
-    a.x_unused = nullptr;
     a.P = coef;
     a.y = y;
     a.rec_node = static_cast<const int32_t *>(records);

@@ -9,7 +9,6 @@ namespace lmkan {
 constexpr int kSlabTile = LMKAN_PACK_TILE;  // 64 outputs per workgroup tile
 
 struct SlabArgs {
-    const float *x_unused;
     const void *P;     // float32, or 16-bit storage converted while the slab is filled
     float *y;
     const int32_t *rec_node;

@@ -359,7 +359,6 @@ void launch_forward_slab_f16(const LayerShape &s, const void *coef, float *y, co
     }
     const size_t n = (size_t)s.pairs() * (size_t)s.batch;
     SlabArgs a;
-    a.x_unused = nullptr;
     a.P = coef;
     a.y = y;
     a.rec_node = static_cast<const int32_t *>(records);
