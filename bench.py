@@ -41,6 +41,8 @@ def parse():
     ap.add_argument("--workload", default="cfg3_1024x1024_G16")
     ap.add_argument("--grid", type=int, default=0,
                     help="override the workload's number of grid intervals G (for sweeps over G)")
+    ap.add_argument("--graph", action="store_true",
+                    help="time the step as a replayed HIP graph (one launch per step instead of a dozen)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-rows", type=int, default=8192)
     ap.add_argument("--calibrate-copy", action="store_true",
@@ -97,7 +99,6 @@ def main():
     gP = torch.empty(paper.coef_shape(), dtype=torch.float32, device=dev)
     need = max(pkg.lmkan_workspace_bytes(desc, B, False), pkg.lmkan_workspace_bytes(desc, B, True), 256)
     ws = torch.empty(need, dtype=torch.uint8, device=dev)
-    stream = torch.cuda.current_stream().cuda_stream
     d = desc.c()
 
     if conv:
@@ -107,19 +108,19 @@ def main():
     def forward():
         if conv:
             st = L.lmkan_conv2d_forward(C.byref(d), C.byref(geom), x.data_ptr(), P_packed.data_ptr(), y.data_ptr(),
-                                        ws.data_ptr(), need, stream)
+                                        ws.data_ptr(), need, torch.cuda.current_stream().cuda_stream)
         else:
             st = L.lmkan_forward(C.byref(d), B, x.data_ptr(), P_packed.data_ptr(), y.data_ptr(),
-                                 ws.data_ptr(), need, stream)
+                                 ws.data_ptr(), need, torch.cuda.current_stream().cuda_stream)
         assert st == 0, pkg.lmkan_status_string(st)
 
     def backward_only(gx_ptr, gp_ptr):
         if conv:
             st = L.lmkan_conv2d_backward(C.byref(d), C.byref(geom), x.data_ptr(), P_packed.data_ptr(),
-                                         gy.data_ptr(), gx_ptr, gp_ptr, ws.data_ptr(), need, stream)
+                                         gy.data_ptr(), gx_ptr, gp_ptr, ws.data_ptr(), need, torch.cuda.current_stream().cuda_stream)
         else:
             st = L.lmkan_backward(C.byref(d), B, x.data_ptr(), P_packed.data_ptr(), gy.data_ptr(),
-                                  gx_ptr, gp_ptr, ws.data_ptr(), need, stream)
+                                  gx_ptr, gp_ptr, ws.data_ptr(), need, torch.cuda.current_stream().cuda_stream)
         assert st == 0, pkg.lmkan_status_string(st)
 
     def backward():
@@ -132,9 +133,17 @@ def main():
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
+    run_step = step
+    if args.graph:      # the same step recorded once as a HIP graph and replayed (launch-bound layers)
+        hip_graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(hip_graph):
+            step()
+        run_step = hip_graph.replay
+        run_step()
+        torch.cuda.synchronize()
     t0 = time.perf_counter()
     for _ in range(args.steps):
-        step()
+        run_step()
     torch.cuda.synchronize()
     ms_per_step = (time.perf_counter() - t0) * 1e3 / args.steps
 
@@ -209,6 +218,7 @@ def main():
                                f"{w.name}: n_in={w.n_in} n_out={n_out} G={w.grid} batch={B} "
                                f"coef_storage={args.storage} x~{w.x_kind} coef~N(0,{w.coef_std})",
                    "pass": "forward+backward(grad_x,grad_coef)", "coef_layout": "packed",
+                   "launch": "hip graph replay" if args.graph else "stream launches",
                    "pack_ms_once": round(pack_ms, 3)},
         "forward": {"ms": round(fwd_ms, 4), "samples_per_s": round(B / (fwd_ms * 1e-3), 1),
                     "gather_GBps": round(fma_fwd * s_bytes / (fwd_ms * 1e-3) / 1e9, 1),
@@ -223,7 +233,8 @@ def main():
     hval = torch.empty(1, dtype=torch.float64, device=dev)
 
     def hessian():
-        st = L.lmkan_hessian_reg(C.byref(d), P_packed.data_ptr(), 1.0, hval.data_ptr(), gP.data_ptr(), stream)
+        st = L.lmkan_hessian_reg(C.byref(d), P_packed.data_ptr(), 1.0, hval.data_ptr(), gP.data_ptr(),
+                                 torch.cuda.current_stream().cuda_stream)
         assert st == 0, pkg.lmkan_status_string(st)
 
     hess_ms = event_ms(hessian, reps)

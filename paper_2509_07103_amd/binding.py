@@ -181,7 +181,13 @@ def lmkan_workspace_bytes(desc: LayerDesc, batch: int, backward: bool) -> int:
     return lib().lmkan_workspace_bytes(C.byref(desc.c()), batch, 1 if backward else 0)
 
 
-def _workspace(desc: LayerDesc, batch: int, backward: bool, device):
+def _workspace(desc: LayerDesc, batch: int, backward: bool, device, workspace: torch.Tensor | None = None):
+    """(tensor or None, bytes): the caller's workspace when given (any dtype, contiguous, on the device;
+    its size goes to the library, which checks it), else a fresh allocation of the size the library asks for."""
+    if workspace is not None:
+        if not workspace.is_cuda or not workspace.is_contiguous():
+            raise ValueError("workspace: expected a contiguous device tensor")
+        return workspace, workspace.numel() * workspace.element_size()
     need = lmkan_workspace_bytes(desc, batch, backward)
     if need == 0:
         return None, 0
@@ -220,14 +226,14 @@ def lmkan_locate(desc: LayerDesc, x: torch.Tensor, stream=None) -> torch.Tensor:
 
 
 def lmkan_forward(desc: LayerDesc, x: torch.Tensor, coef: torch.Tensor, y: torch.Tensor | None = None,
-                  stream=None) -> torch.Tensor:
+                  stream=None, workspace: torch.Tensor | None = None) -> torch.Tensor:
     batch = x.shape[0]
     xp = _dev(x, torch.float32, (batch, desc.n_in), "x")
     cp = _coef_ptr(desc, coef)
     if y is None:
         y = torch.empty((batch, desc.n_out), dtype=torch.float32, device=x.device)
     yp = _dev(y, torch.float32, (batch, desc.n_out), "y")
-    ws, wsz = _workspace(desc, batch, False, x.device)
+    ws, wsz = _workspace(desc, batch, False, x.device, workspace)
     _check(lib().lmkan_forward(C.byref(desc.c()), batch, xp, cp, yp,
                                ws.data_ptr() if ws is not None else None, wsz, _stream(stream)),
            "lmkan_forward")
@@ -237,7 +243,7 @@ def lmkan_forward(desc: LayerDesc, x: torch.Tensor, coef: torch.Tensor, y: torch
 def lmkan_backward(desc: LayerDesc, x: torch.Tensor, coef: torch.Tensor | None, grad_y: torch.Tensor,
                    need_grad_x: bool = True, need_grad_coef: bool = True,
                    grad_x: torch.Tensor | None = None, grad_coef: torch.Tensor | None = None,
-                   stream=None):
+                   stream=None, workspace: torch.Tensor | None = None):
     """Returns (grad_x or None, grad_coef or None); grad_coef is float32 in the layout of Alg. 1."""
     batch = x.shape[0]
     xp = _dev(x, torch.float32, (batch, desc.n_in), "x")
@@ -251,7 +257,7 @@ def lmkan_backward(desc: LayerDesc, x: torch.Tensor, coef: torch.Tensor | None, 
         grad_coef = torch.empty(desc.coef_shape(), dtype=torch.float32, device=x.device)
     gxp = _dev(grad_x, torch.float32, (batch, desc.n_in), "grad_x") if need_grad_x else None
     gcp = _dev(grad_coef, torch.float32, desc.coef_shape(), "grad_coef") if need_grad_coef else None
-    ws, wsz = _workspace(desc, batch, True, x.device)
+    ws, wsz = _workspace(desc, batch, True, x.device, workspace)
     _check(lib().lmkan_backward(C.byref(desc.c()), batch, xp, cp, gyp, gxp, gcp,
                                 ws.data_ptr() if ws is not None else None, wsz, _stream(stream)),
            "lmkan_backward")
@@ -268,7 +274,8 @@ def lmkan_conv2d_rows(conv: Conv2d):
 
 
 def lmkan_conv2d_forward(desc: LayerDesc, conv: Conv2d, x: torch.Tensor, coef: torch.Tensor,
-                         y: torch.Tensor | None = None, stream=None) -> torch.Tensor:
+                         y: torch.Tensor | None = None, stream=None,
+                         workspace: torch.Tensor | None = None) -> torch.Tensor:
     """x[n][h][w][c_in] -> y[n][out_h][out_w][n_out]."""
     rows, oh, ow = lmkan_conv2d_rows(conv)
     xp = _dev(x, torch.float32, conv.image_shape(), "x")
@@ -276,7 +283,7 @@ def lmkan_conv2d_forward(desc: LayerDesc, conv: Conv2d, x: torch.Tensor, coef: t
     if y is None:
         y = torch.empty((conv.n, oh, ow, desc.n_out), dtype=torch.float32, device=x.device)
     yp = _dev(y, torch.float32, (conv.n, oh, ow, desc.n_out), "y")
-    ws, wsz = _workspace(desc, rows, False, x.device)
+    ws, wsz = _workspace(desc, rows, False, x.device, workspace)
     _check(lib().lmkan_conv2d_forward(C.byref(desc.c()), C.byref(conv.c()), xp, cp, yp,
                                       ws.data_ptr() if ws is not None else None, wsz, _stream(stream)),
            "lmkan_conv2d_forward")
@@ -285,7 +292,8 @@ def lmkan_conv2d_forward(desc: LayerDesc, conv: Conv2d, x: torch.Tensor, coef: t
 
 def lmkan_conv2d_backward(desc: LayerDesc, conv: Conv2d, x: torch.Tensor, coef: torch.Tensor | None,
                           grad_y: torch.Tensor, need_grad_x: bool = True, need_grad_coef: bool = True,
-                          grad_x: torch.Tensor | None = None, grad_coef: torch.Tensor | None = None, stream=None):
+                          grad_x: torch.Tensor | None = None, grad_coef: torch.Tensor | None = None, stream=None,
+                          workspace: torch.Tensor | None = None):
     """Returns (grad_x in the shape of the image or None, grad_coef in the layout of Alg. 1 or None)."""
     rows, oh, ow = lmkan_conv2d_rows(conv)
     xp = _dev(x, torch.float32, conv.image_shape(), "x")
@@ -299,7 +307,7 @@ def lmkan_conv2d_backward(desc: LayerDesc, conv: Conv2d, x: torch.Tensor, coef: 
         grad_coef = torch.empty(desc.coef_shape(), dtype=torch.float32, device=x.device)
     gxp = _dev(grad_x, torch.float32, conv.image_shape(), "grad_x") if need_grad_x else None
     gcp = _dev(grad_coef, torch.float32, desc.coef_shape(), "grad_coef") if need_grad_coef else None
-    ws, wsz = _workspace(desc, rows, True, x.device)
+    ws, wsz = _workspace(desc, rows, True, x.device, workspace)
     _check(lib().lmkan_conv2d_backward(C.byref(desc.c()), C.byref(conv.c()), xp, cp, gyp, gxp, gcp,
                                        ws.data_ptr() if ws is not None else None, wsz, _stream(stream)),
            "lmkan_conv2d_backward")
