@@ -302,3 +302,44 @@ def test_fold_matches_oracle_and_the_unfolded_layer(dev, oracle, shape, layout):
     # the oracle's forward on the oracle's folded table agrees too
     want = oracle.forward(x.cpu().numpy(), want_table.astype(np.float32), G)
     assert rowwise_rel_err(y_folded.cpu().numpy(), want) <= TOL_F32
+
+
+def _shifted(t, elems=1):
+    """A contiguous copy of t whose storage starts `elems` elements past an aligned allocation."""
+    buf = torch.empty(t.numel() + elems, dtype=t.dtype, device=t.device)
+    out = buf[elems:].view(t.shape)
+    out.copy_(t)
+    return out
+
+
+@pytest.mark.parametrize("storage", ["f32", "bf16"])
+def test_buffers_off_the_16_byte_grid_take_the_general_kernels(dev, oracle, storage):
+    """The tuned kernels move 16 bytes per lane; buffers that are only element-aligned must still
+    give the same results (the dispatch falls back), and an x that is not 8-byte aligned is an
+    error, not a fault."""
+    B, n_in, n_out, G = 600, 12, 72, 8
+    x, P, gy = _inputs(B, n_in, n_out, G, 31, dev)
+    desc = _desc(n_in, n_out, G, storage)
+    Ps = wl.store(P, storage).contiguous()
+    Pu, gyu = _shifted(Ps), _shifted(gy)
+    y = _shifted(torch.empty((B, n_out), device=dev))
+    gx = torch.empty((B, n_in), device=dev)
+    gP = _shifted(torch.empty(desc.coef_shape(), device=dev))
+    assert Pu.data_ptr() % 16 != 0 and gyu.data_ptr() % 16 != 0 and y.data_ptr() % 16 != 0
+    pkg.lmkan_forward(desc, x, Pu, y=y)
+    pkg.lmkan_backward(desc, x, Pu, gyu, grad_x=gx, grad_coef=gP)
+    torch.cuda.synchronize()
+    xh, gyh = x.cpu().numpy(), gy.cpu().numpy()
+    code = ORACLE_DTYPE[storage]
+    assert rowwise_rel_err(y.cpu().numpy(), oracle.forward(xh, bits(Ps), G, dtype=code)) <= TOL_F32
+    assert rowwise_rel_err(gx.cpu().numpy(), oracle.backward_input(xh, bits(Ps), gyh, G, dtype=code)) <= TOL_F32
+    want = oracle.backward_coef(xh, gyh, G)
+    got = gP.cpu().numpy()
+    for k in range(n_in // 2):
+        assert pair_slice_rel_err(got[:, :, k, :], want[:, :, k, :]) <= TOL_F32
+    # x on a 4-byte boundary only: rejected on the host
+    xu = _shifted(x)
+    assert xu.data_ptr() % 8 == 4
+    with pytest.raises(pkg.LmkanError) as e:
+        pkg.lmkan_forward(desc, xu, Ps)
+    assert e.value.status == 5
