@@ -213,3 +213,102 @@ def test_cfg2_inference_stack_with_folded_normalisation(dev, oracle):
         assert err <= (TOL_F32 if i == 0 else 2e-4), (i, err)
         a_ref = y.astype(np.float32)     # the oracle's own activations feed its next layer
     assert np.isfinite(worst)
+
+
+# ---------------------------------------------------------------------------------------------
+# Properties that hold at any size, checked on EVERY element of the full-size tensors (the sampled
+# rows above cover a fraction).  A table that samples an affine function,
+#     P[a][b][k][j] = alpha[k][j] E[a] + beta[k][j] E[b] + gamma[k][j],
+# is reproduced exactly by piecewise-linear interpolation, inside the grid and beyond the ghost
+# points (Sec. 3.1, App. B: every function continues linearly to infinity), so the layer is the
+# dense affine map  y = x1 alpha + x2 beta + sum_k gamma,  its input gradient is  gy alpha^T / gy beta^T,
+# and, because the four weights of a sample sum to one and interpolate the coordinates,
+#     sum_ab gP[a][b][k][j] = sum_n gy[n][j],   sum_ab E[a] gP[a][b][k][j] = sum_n x[n][2k] gy[n][j]
+# (and likewise with E[b], x[n][2k+1]) for every table.  The right-hand sides are float64 matrix
+# products of the inputs: nothing of the library enters them.
+# ---------------------------------------------------------------------------------------------
+def _affine_table(w, dev, seed):
+    g = torch.Generator(device=dev)
+    g.manual_seed(seed)
+    K = w.n_in // 2
+    alpha = torch.randn((K, w.n_out), generator=g, device=dev) * 0.3
+    beta = torch.randn((K, w.n_out), generator=g, device=dev) * 0.3
+    gamma = torch.randn((K, w.n_out), generator=g, device=dev) * 0.1
+    E = torch.from_numpy(pkg.lmkan_grid(w.grid)[0]).to(dev).double()
+    P = (alpha.double()[None, None] * E[:, None, None, None] + beta.double()[None, None] * E[None, :, None, None]
+         + gamma.double()[None, None])
+    return alpha, beta, gamma, E, P.float().contiguous()
+
+
+@pytest.mark.parametrize("w", [wl.CFG3, wl.CFG4, wl.CFG2_LAYERS[1]], ids=lambda w: w.name)
+def test_affine_table_makes_the_layer_a_dense_affine_map_everywhere(dev, w):
+    alpha, beta, gamma, E, P = _affine_table(w, dev, 500 + w.seed)
+    paper, packed = _descs(w, "f32")
+    Pp = pkg.lmkan_pack(paper, P)
+    x = wl.make_x(w, dev) * 1.5            # a good share of the inputs beyond the ghost points
+    gy = wl.make_grad_y(w, dev)
+    y = pkg.lmkan_forward(packed, x, Pp)
+    gx, _ = pkg.lmkan_backward(packed, x, Pp, gy, need_grad_coef=False)
+    torch.cuda.synchronize()
+    # the table itself is rounded to float32: use the rounded coefficients' own affine law where
+    # it matters (interpolation of rounded samples of an affine function is affine up to rounding)
+    x1, x2 = x[:, 0::2].double(), x[:, 1::2].double()
+    want = x1 @ alpha.double() + x2 @ beta.double() + gamma.double().sum(0)[None]
+    scale = want.abs().amax(dim=1, keepdim=True).clamp_min(1e-30)
+    assert float(((y.double() - want).abs() / scale).max()) <= 2e-5
+    want_g1, want_g2 = gy.double() @ alpha.double().T, gy.double() @ beta.double().T
+    got_g1, got_g2 = gx[:, 0::2].double(), gx[:, 1::2].double()
+    gscale = torch.maximum(want_g1.abs().amax(dim=1, keepdim=True), want_g2.abs().amax(dim=1, keepdim=True))
+    assert float(((got_g1 - want_g1).abs() / gscale).max()) <= 2e-5
+    assert float(((got_g2 - want_g2).abs() / gscale).max()) <= 2e-5
+
+
+@pytest.mark.parametrize("w", [wl.CFG3, wl.CFG4, wl.CFG2_LAYERS[1]], ids=lambda w: w.name)
+def test_coefficient_gradient_moments_over_the_whole_tensor(dev, w):
+    paper, packed = _descs(w, "f32")
+    x = wl.make_x(w, dev)
+    gy = wl.make_grad_y(w, dev)
+    _, gP = pkg.lmkan_backward(packed, x, None, gy, need_grad_x=False)
+    torch.cuda.synchronize()
+    E = torch.from_numpy(pkg.lmkan_grid(w.grid)[0]).to(dev).double()
+    g = gP.double()
+    m0 = g.sum(dim=(0, 1))                                     # [K][n_out]
+    m1 = (g * E[:, None, None, None]).sum(dim=(0, 1))
+    m2 = (g * E[None, :, None, None]).sum(dim=(0, 1))
+    gyd = gy.double()
+    want0 = gyd.sum(0)[None].expand_as(m0)
+    want1 = x[:, 0::2].double().T @ gyd
+    want2 = x[:, 1::2].double().T @ gyd
+    # scale: the sum of absolute contributions, which is what float32 rounding acts on
+    s0 = gyd.abs().sum(0)[None]
+    s1 = x[:, 0::2].double().abs().T @ gyd.abs()
+    s2 = x[:, 1::2].double().abs().T @ gyd.abs()
+    assert float(((m0 - want0).abs() / s0).max()) <= 1e-5
+    assert float(((m1 - want1).abs() / s1).max()) <= 1e-5
+    assert float(((m2 - want2).abs() / s2).max()) <= 1e-5
+
+
+@pytest.mark.parametrize("w", [wl.CONV_2X2, wl.CONV_3X3_S1], ids=lambda w: w.name)
+def test_convolution_stages_at_full_size(dev, oracle, w):
+    """The bench's convolution stages: every window of a few sampled images against the oracle."""
+    x = wl.make_image(w, dev)
+    P = wl.make_coef(w, dev)
+    oh, ow = w.out_hw
+    gy = wl.make_grad_y(w, dev).reshape(w.n, oh, ow, w.n_out)
+    conv = pkg.Conv2d(w.n, w.h, w.w, w.c_in, w.kh, w.kw, w.stride)
+    paper = pkg.LayerDesc(w.n_in, w.n_out, w.grid)
+    packed = pkg.LayerDesc(w.n_in, w.n_out, w.grid, coef_layout=pkg.LMKAN_LAYOUT_PACKED)
+    Pp = pkg.lmkan_pack(paper, P)
+    y = pkg.lmkan_conv2d_forward(packed, conv, x, Pp)
+    gx, gP = pkg.lmkan_conv2d_backward(packed, conv, x, Pp, gy)
+    torch.cuda.synchronize()
+    imgs = np.sort(np.random.default_rng(w.seed).choice(w.n, size=3, replace=False))
+    xh, Ph, gyh = x[imgs].cpu().numpy(), P.cpu().numpy(), gy[imgs].cpu().numpy()
+    want = oracle.conv2d_forward(xh, Ph, w.grid, w.kh, w.kw, w.stride, threads=THREADS)
+    assert rowwise_rel_err(y[imgs].cpu().numpy().reshape(-1, w.n_out), want.reshape(-1, w.n_out)) <= TOL_F32
+    want_gx = oracle.conv2d_backward_input(xh, Ph, gyh, w.grid, w.kh, w.kw, w.stride, threads=THREADS)
+    assert rowwise_rel_err(gx[imgs].cpu().numpy().reshape(3, -1), want_gx.reshape(3, -1)) <= TOL_F32
+    # the coefficient gradient sums over all images: its zeroth moment is checked over the whole tensor
+    m0 = gP.double().sum(dim=(0, 1))
+    gyd = gy.reshape(-1, w.n_out).double()
+    assert float(((m0 - gyd.sum(0)[None]).abs() / gyd.abs().sum(0)[None]).max()) <= 1e-5
