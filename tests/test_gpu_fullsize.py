@@ -175,6 +175,19 @@ def test_cfg5_large_table_bf16(dev, oracle):
         want_k = oracle.backward_coef_pair(xh, gyh, G, int(k))
         assert pair_slice_rel_err(got_k, want_k) <= TOL_F32
         assert np.all(got_k[want_k == 0.0] == 0.0)
+    # every element of the 36 GB gradient enters its moments over the nodes (see the property tests
+    # below), taken 128 pairs at a time
+    E = torch.from_numpy(pkg.lmkan_grid(G)[0]).to(dev).double()
+    gyd = gy.double()
+    s0 = gyd.abs().sum(0)[None]
+    for k0 in range(0, K, 128):
+        g = gP[:, :, k0:k0 + 128, :].double()
+        m0 = g.sum(dim=(0, 1))
+        m1 = (g * E[:, None, None, None]).sum(dim=(0, 1))
+        x1 = x[:, 2 * k0:2 * (k0 + 128):2].double()
+        assert float(((m0 - gyd.sum(0)[None]).abs() / s0).max()) <= 1e-5
+        assert float(((m1 - x1.T @ gyd).abs() / (x1.abs().T @ gyd.abs())).max()) <= 1e-5
+        del g, m0, m1
 
 
 def test_cfg2_inference_stack_with_folded_normalisation(dev, oracle):
