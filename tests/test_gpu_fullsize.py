@@ -129,6 +129,9 @@ def test_cfg3_hessian_regulariser(dev, oracle):
     got = grad.cpu().numpy()
     for k in np.random.default_rng(300).choice(w.n_in // 2, size=16, replace=False):
         assert pair_slice_rel_err(got[:, :, int(k), :], want_g[:, :, int(k), :]) <= TOL_F32
+    # over the whole tensor: the regulariser is a quadratic form of the table, so <grad, P> = 2 value
+    euler = float((grad.double() * P.double()).sum())
+    assert euler == pytest.approx(2.0 * want_v, rel=1e-5)
 
 
 def test_cfg4_rows(dev, oracle):
