@@ -67,6 +67,16 @@ SHAPES = [
     (300, 8, 20, 34),
     # a batch long enough for the coefficient gradient to sort it block by block
     (13000, 6, 68, 5),
+    # either side of the thresholds at which the dispatch changes kernels: 256 rows, 8 and 9
+    # outputs, G = 16 / 17 and 34 / 35, 12288 rows
+    (255, 6, 12, 8),
+    (256, 6, 12, 8),
+    (1024, 66, 4, 16),
+    (2049, 130, 8, 12),
+    (300, 4, 9, 16),
+    (300, 6, 12, 17),
+    (300, 6, 12, 35),
+    (12289, 4, 12, 6),
 ]
 
 
