@@ -39,3 +39,26 @@ def test_inputs_are_seeded(name):
     a, b = make(w, torch.device("cpu")), make(w, torch.device("cpu"))
     assert torch.equal(a, b)
     assert torch.equal(wl.make_coef(w, "cpu"), wl.make_coef(w, "cpu"))
+
+
+def test_the_product_never_touches_the_oracle():
+    """The oracle is test infrastructure: nothing under the package may import or load it, and the
+    package has no CPU path to fall back on (a missing library is an ImportError)."""
+    import re
+    pkg_dir = os.path.join(ROOT, "paper_2509_07103_amd")
+    for dirpath, _, files in os.walk(pkg_dir):
+        for fn in files:
+            if fn.endswith((".py", ".hip", ".h")):
+                text = open(os.path.join(dirpath, fn)).read()
+                assert not re.search(r"^\s*(import|from)\s+oracle\b|oracle\.(get|build)|liblmkan_oracle", text, re.M), \
+                    f"{fn} uses the oracle"
+    bench = open(os.path.join(ROOT, "bench.py")).read()
+    assert bench.count("import oracle") == 1 and bench.index("import oracle") > bench.index("if not args.no_cpu_baseline")
+
+
+def test_missing_library_is_a_loud_error(tmp_path, monkeypatch):
+    from paper_2509_07103_amd import binding
+    monkeypatch.setattr(binding, "_lib", None)
+    monkeypatch.setattr(binding, "LIB_PATH", str(tmp_path / "liblmkan.so"))
+    with pytest.raises(ImportError):
+        binding.lib()
