@@ -161,6 +161,21 @@ def main():
     reps = max(3, min(args.steps, 20))
     null = C.c_void_p(0)
 
+    def kernel_ms(fn, reps):
+        """Duration of the call's main kernel alone: the library records the two events around it
+        on the launch stream (lmkan_time_next_kernel), leaving out the passes before and after."""
+        pairs = []
+        for _ in range(reps):
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            e1.record()         # the events exist from here on; the library records them again
+            pkg.lmkan_time_next_kernel(e0, e1)
+            fn()
+            pairs.append((e0, e1))
+        pkg.lmkan_time_next_kernel(None, None)
+        torch.cuda.synchronize()
+        return float(np.mean([a.elapsed_time(b) for a, b in pairs]))
+
     fwd_ms = event_ms(forward, reps)
     bwd_ms = event_ms(backward, reps)
     gx_ms = event_ms(lambda: backward_only(gx.data_ptr(), null), reps)
@@ -181,11 +196,14 @@ def main():
         fwd_name, gx_name = "forward_slab_narrow_kernel", "backward_input_slab_narrow_kernel"
     else:
         fwd_name, gx_name = "forward_generic_kernel", "backward_generic_kernel(grad_x)"
-    calls = {fwd_name: fwd_ms, gx_name: gx_ms,
-             ("backward_coef_small_kernel" if n_out <= 8 else "backward_coef_stream_kernel" if n_out % 4 == 0
-              else "backward_generic_kernel(grad_coef)"): gp_ms}
-    dom_name = max(calls, key=calls.get)
-    dom_ms = calls[dom_name]
+    gp_name = ("backward_coef_small_kernel" if n_out <= 8 else "backward_coef_stream_kernel" if n_out % 4 == 0
+               else "backward_generic_kernel(grad_coef)")
+    calls = {fwd_name: fwd_ms, gx_name: gx_ms, gp_name: gp_ms}
+    kernels = {fwd_name: kernel_ms(forward, reps),
+               gx_name: kernel_ms(lambda: backward_only(gx.data_ptr(), null), reps),
+               gp_name: kernel_ms(lambda: backward_only(null, gP.data_ptr()), reps)}
+    dom_name = max(kernels, key=kernels.get)
+    dom_ms = kernels[dom_name]
     # algorithmic work of one such launch: 4 B K n_out multiply-adds; compulsory HBM bytes: the
     # table (read, or written in float32 by the coefficient gradient) + x + one y-sized tensor
     table_bytes = (w.grid + 1) ** 2 * K * n_out * (4 if "coef" in dom_name else s_bytes)
@@ -203,7 +221,10 @@ def main():
     roofline.update({"traffic": MEASURED_TRAFFIC_BYTES.get((w.name, args.storage, dom_name)),
                      "traffic_unit": "bytes per launch (HBM read + write)", "kernel": dom_name,
                      "kernel_ms": round(dom_ms, 4),
-                     "all_ms": {k: round(v, 4) for k, v in calls.items()}})
+                     "kernels_ms": {k: round(v, 4) for k, v in kernels.items()},
+                     "all_ms": {k: round(v, 4) for k, v in calls.items()},
+                     "note": "kernel_ms / kernels_ms: the kernel alone, events recorded by the library around "
+                             "its launch; all_ms: whole calls (kernel + preamble, sort, fill, transpose passes)"})
 
     out = {
         "metric": f"lmKAN layer samples/sec (forward + backward, {w.n_in}->{n_out}, 1 GPU)",

@@ -215,6 +215,19 @@ lmkan_status lmkan_fold(const lmkan_desc *desc, void *coef_dev, float gamma, con
                         void *stream);
 
 /*
+ * For callers that measure (benchmarks; not part of the paper's method): the next
+ * lmkan_forward / lmkan_backward / lmkan_conv2d_* call made by this host thread records
+ * start_event on its stream right before its main kernel and stop_event right after it,
+ * leaving out the passes around it (preamble records, sorting, zero fills, transposes,
+ * partial sums).  The main kernel is the forward kernel; for a backward call the
+ * input-gradient kernel when grad_x is requested, else the coefficient-gradient kernel.
+ * Both are hipEvent_t created by the caller with timing enabled; the pair is used once.
+ * Two NULLs disarm; one NULL is LMKAN_ERR_NULL.  A call that launches no such kernel
+ * (empty batch, argument error) leaves the events armed for the next call.
+ */
+lmkan_status lmkan_time_next_kernel(void *start_event, void *stop_event);
+
+/*
  * Convolution (Sec. 5, "lmKAN-based Convolutional Neural Networks"): a kh x kw
  * convolution is the layer R^{kh kw c_in} -> R^{n_out} applied to every window of a
  * channels-last image.  The paper reshapes the windows into rows first; here the rows

@@ -123,6 +123,8 @@ def lib() -> C.CDLL:
     L.lmkan_backward.restype = C.c_int
     L.lmkan_backward.argtypes = [dp, C.c_int64, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p,
                                  C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]
+    L.lmkan_time_next_kernel.restype = C.c_int
+    L.lmkan_time_next_kernel.argtypes = [C.c_void_p, C.c_void_p]
     cp = C.POINTER(_Conv2d)
     L.lmkan_conv2d_rows.restype = C.c_int64
     L.lmkan_conv2d_rows.argtypes = [cp, C.POINTER(C.c_int32), C.POINTER(C.c_int32)]
@@ -262,6 +264,16 @@ def lmkan_backward(desc: LayerDesc, x: torch.Tensor, coef: torch.Tensor | None, 
                                 ws.data_ptr() if ws is not None else None, wsz, _stream(stream)),
            "lmkan_backward")
     return (grad_x if need_grad_x else None), (grad_coef if need_grad_coef else None)
+
+
+def lmkan_time_next_kernel(start: torch.cuda.Event | None, stop: torch.cuda.Event | None) -> None:
+    """Arms two timing events (already created: record them once beforehand) for the main kernel of
+    the next compute call of this thread; (None, None) disarms."""
+    hs = None if start is None else start.cuda_event
+    he = None if stop is None else stop.cuda_event
+    if (start is not None and not hs) or (stop is not None and not he):
+        raise ValueError("the events must exist already: record each once before arming them")
+    _check(lib().lmkan_time_next_kernel(hs, he), "lmkan_time_next_kernel")
 
 
 def lmkan_conv2d_rows(conv: Conv2d):

@@ -70,7 +70,36 @@ lmkan_status launch_status()
     return hipGetLastError() == hipSuccess ? LMKAN_OK : LMKAN_ERR_HIP;
 }
 
+// lmkan_time_next_kernel: events of the calling host thread, and the kind of kernel the call
+// in progress wants bracketed
+struct TimingState {
+    hipEvent_t start = nullptr, stop = nullptr;
+    bool armed = false;
+    int target = -1;
+};
+thread_local TimingState g_timing;
+
+// scope of one compute call: chooses the kernel kind, disarms once the events were used
+struct TimedCall {
+    explicit TimedCall(int kind) { g_timing.target = g_timing.armed ? kind : -1; }
+    ~TimedCall() { g_timing.target = -1; }
+};
+
 }  // namespace
+
+KernelTiming::KernelTiming(hipStream_t s, TimedKernel kind) : stream(s), on(g_timing.armed && g_timing.target == (int)kind)
+{
+    if (on) (void)hipEventRecord(g_timing.start, stream);
+}
+
+KernelTiming::~KernelTiming()
+{
+    if (on) {
+        (void)hipEventRecord(g_timing.stop, stream);
+        g_timing.armed = false;
+        g_timing.target = -1;
+    }
+}
 
 extern "C" {
 
@@ -173,6 +202,7 @@ lmkan_status forward_impl(const lmkan_desc *desc, int64_t batch, const float *x_
     build_grid(desc->grid, &tab);
     const LayerShape s = shape_of(desc, batch);
     hipStream_t hs = static_cast<hipStream_t>(stream);
+    TimedCall timed(kTimeForward);
     if (small_out_shape_ok(s)) {
         launch_preamble_records(s, tab, x_dev, workspace_dev, hs, conv);
         launch_forward_small(s, coef_dev, y_dev, workspace_dev, hs);
@@ -230,6 +260,7 @@ lmkan_status backward_impl(const lmkan_desc *desc, int64_t batch, const float *x
     char *ws = static_cast<char *>(workspace_dev);
     char *ws_sorted = ws + align256(records_bytes(s));
     float *ws_scratch = reinterpret_cast<float *>(ws_sorted + sorted_records_bytes(s));
+    TimedCall timed(grad_x_dev ? kTimeGradInput : kTimeGradCoef);
     if (need_records) launch_preamble_records(s, tab, x_dev, ws, hs, conv);
     if (gp_small) {
         launch_backward_coef_small(s, ws, grad_y_dev, grad_coef_dev, !overwrite, hs);
@@ -283,6 +314,16 @@ lmkan_status lmkan_backward(const lmkan_desc *desc, int64_t batch, const float *
 {
     return backward_impl(desc, batch, x_dev, coef_dev, grad_y_dev, grad_x_dev, grad_coef_dev, workspace_dev,
                          workspace_bytes, stream, nullptr);
+}
+
+lmkan_status lmkan_time_next_kernel(void *start_event, void *stop_event)
+{
+    if ((start_event == nullptr) != (stop_event == nullptr)) return LMKAN_ERR_NULL;
+    g_timing.start = static_cast<hipEvent_t>(start_event);
+    g_timing.stop = static_cast<hipEvent_t>(stop_event);
+    g_timing.armed = start_event != nullptr;
+    g_timing.target = -1;
+    return LMKAN_OK;
 }
 
 int64_t lmkan_conv2d_rows(const lmkan_conv2d *conv, int32_t *out_h, int32_t *out_w)

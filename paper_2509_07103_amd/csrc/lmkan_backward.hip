@@ -728,6 +728,7 @@ void launch_backward_coef_sorted(const LayerShape &s, const void *records, void 
     // 24-bit multiply and 32-bit byte offsets into gy when the tensor is small enough
     const bool offset32 = s.batch < (1 << 24) && (int64_t)s.n_out * 4 < (1 << 24) &&
                           (int64_t)s.batch * s.n_out * 4 < ((int64_t)1 << 32);
+    KernelTiming timing(stream, kTimeGradCoef);
     if (offset32)
         backward_coef_stream_kernel<true><<<grid, 64, lds, stream>>>(a);
     else

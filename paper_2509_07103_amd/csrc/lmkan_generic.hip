@@ -272,6 +272,7 @@ static void forward_generic_dispatch(const LayerShape &s, const GridTab &tab, co
 {
     const dim3 grid((unsigned)((s.batch + kFwdTileB - 1) / kFwdTileB), (unsigned)s.out_tiles());
     const CoefMap map = coef_map(s);
+    KernelTiming timing(stream, kTimeForward);
     if (conv)
         forward_generic_kernel<CT, true><<<grid, kThreads, 0, stream>>>(tab, map, x, coef, y, s.batch, s.n_in,
                                                                         s.n_out, *conv);
@@ -300,6 +301,7 @@ static void backward_generic_dispatch(const LayerShape &s, const GridTab &tab, c
     LayerShape g = s;
     g.layout = LMKAN_LAYOUT_PAPER;  // the gradient is always in the layout of Alg. 1
     const CoefMap gmap = coef_map(g);
+    KernelTiming timing(stream, gx ? kTimeGradInput : kTimeGradCoef);
     if (gx && gcoef)
         backward_generic_kernel<CT, true, true, CONV><<<grid, kThreads, 0, stream>>>(
             tab, map, gmap, x, coef, gy, gx, gcoef, s.batch, s.n_in, s.n_out, cg);

@@ -45,6 +45,16 @@ bool slab_forward_shape_ok(const LayerShape &s);
 bool slab_forward_applicable(const LayerShape &s, const void *coef, const float *y);
 void launch_preamble_records(const LayerShape &s, const GridTab &tab, const float *x, void *records,
                              hipStream_t stream, const ConvGeom *conv = nullptr);
+// Measurement aid (lmkan_time_next_kernel): while armed, the main kernel of the chosen kind is
+// bracketed by the caller's two events on its stream.  Put one in the scope of the launch.
+enum TimedKernel { kTimeForward = 0, kTimeGradInput = 1, kTimeGradCoef = 2 };
+struct KernelTiming {
+    KernelTiming(hipStream_t stream, TimedKernel kind);
+    ~KernelTiming();
+    hipStream_t stream;
+    bool on;
+};
+
 // Pair splits of the slab forward (1: none) and the bytes of the split - 1 partial outputs
 // [batch][n_out] it then needs; `partials` = NULL makes the splits add into y atomically.
 int slab_forward_split(const LayerShape &s);

@@ -1149,7 +1149,10 @@ static void launch_forward_slab_narrow(const LayerShape &s, const void *coef, fl
     a.n_split = split;
     a.pairs_per_split = (a.K + split - 1) / split;
     finish_split_setup(a, s, y, partials, stream);
-    kernel<<<tiles * split, waves * 64, (size_t)2 * s.nodes() * kNarrowRowBytes, stream>>>(a);
+    {
+        KernelTiming timing(stream, kTimeForward);
+        kernel<<<tiles * split, waves * 64, (size_t)2 * s.nodes() * kNarrowRowBytes, stream>>>(a);
+    }
     if (a.y_part) launch_sum_partials(y, a.y_part, split - 1, a.part_elems, stream);
 }
 
@@ -1208,7 +1211,10 @@ void launch_forward_slab(const LayerShape &s, const void *coef, float *y, const 
     a.n_split = split;
     a.pairs_per_split = (a.K + split - 1) / split;
     finish_split_setup(a, s, y, partials, stream);
-    kernel<<<tiles * split, waves * 64, slab_forward_lds_bytes(s), stream>>>(a);
+    {
+        KernelTiming timing(stream, kTimeForward);
+        kernel<<<tiles * split, waves * 64, slab_forward_lds_bytes(s), stream>>>(a);
+    }
     if (a.y_part) launch_sum_partials(y, a.y_part, split - 1, a.part_elems, stream);
 }
 
@@ -1386,7 +1392,10 @@ void launch_backward_input_slab(const LayerShape &s, const GridTab &tab, const v
     launch_fill_zero(a.gx, (size_t)a.ld * s.n_in, stream);
     const size_t slabs = narrow ? (size_t)2 * s.nodes() * kNarrowRowBytes : slab_forward_lds_bytes(s);
     const int waves = s.dtype == LMKAN_F32 ? (narrow ? 2 * WAVES : LMKAN_GX_WAVES) : WAVES;
-    kernel<<<tiles * split, waves * 64, slabs + LMKAN_MAX_GRID * sizeof(float), stream>>>(a);
+    {
+        KernelTiming timing(stream, kTimeGradInput);
+        kernel<<<tiles * split, waves * 64, slabs + LMKAN_MAX_GRID * sizeof(float), stream>>>(a);
+    }
     launch_input_gradient_out(a.gx, gx, s, conv, stream, layout);
 }
 

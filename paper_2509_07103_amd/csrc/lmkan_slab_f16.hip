@@ -379,7 +379,10 @@ void launch_forward_slab_f16(const LayerShape &s, const void *coef, float *y, co
     a.n_split = split;
     a.pairs_per_split = (a.K + split - 1) / split;
     finish_split_setup(a, s, y, partials, stream);
-    forward_slab_f16_kernel<<<tiles * split, kWaves * 64, (size_t)2 * s.nodes() * kRowBytesH, stream>>>(a);
+    {
+        KernelTiming timing(stream, kTimeForward);
+        forward_slab_f16_kernel<<<tiles * split, kWaves * 64, (size_t)2 * s.nodes() * kRowBytesH, stream>>>(a);
+    }
     if (a.y_part) launch_sum_partials(y, a.y_part, split - 1, a.part_elems, stream);
 }
 
@@ -420,6 +423,7 @@ void launch_backward_input_slab_f16(const LayerShape &s, const GridTab &tab, con
     a.n_split = split;
     a.pairs_per_split = (a.K + split - 1) / split;
     const size_t lds = (((size_t)2 * s.nodes() * kRowBytesH + 15) & ~(size_t)15) + LMKAN_MAX_GRID * sizeof(float);
+    KernelTiming timing(stream, kTimeGradInput);
     backward_input_slab_f16_kernel<<<tiles * split, kWaves * 64, lds, stream>>>(a);
 }
 

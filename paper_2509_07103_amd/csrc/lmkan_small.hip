@@ -200,6 +200,7 @@ void launch_forward_small(const LayerShape &s, const void *coef, float *y, const
     a.atomic_out = split > 1;
     if (a.atomic_out) launch_fill_zero(y, (size_t)s.batch * s.n_out, stream);
     const dim3 grid((unsigned)((s.batch + kThreads - 1) / kThreads), (unsigned)split);
+    KernelTiming timing(stream, kTimeForward);
     switch (s.dtype) {
     case LMKAN_F32: forward_small_kernel<float><<<grid, kThreads, 0, stream>>>(a); break;
     case LMKAN_F16: forward_small_kernel<_Float16><<<grid, kThreads, 0, stream>>>(a); break;
@@ -217,6 +218,7 @@ void launch_backward_input_small(const LayerShape &s, const GridTab &tab, const 
     const int split = pair_split(s);
     a.pairs_per_block = (a.K + split - 1) / split;
     const dim3 grid((unsigned)((s.batch + kThreads - 1) / kThreads), (unsigned)split);
+    KernelTiming timing(stream, kTimeGradInput);
     switch (s.dtype) {
     case LMKAN_F32: backward_input_small_kernel<float><<<grid, kThreads, 0, stream>>>(a); break;
     case LMKAN_F16: backward_input_small_kernel<_Float16><<<grid, kThreads, 0, stream>>>(a); break;
@@ -244,6 +246,7 @@ void launch_backward_coef_small(const LayerShape &s, const void *records, const 
     if (bblocks > want) bblocks = want;
     if (!accumulate) launch_fill_zero(gcoef, (size_t)s.nodes() * (size_t)s.pairs() * (size_t)s.n_out, stream);
     const dim3 grid((unsigned)bblocks, (unsigned)groups);
+    KernelTiming timing(stream, kTimeGradCoef);
     backward_coef_small_kernel<<<grid, kThreads, (size_t)kc * per_pair, stream>>>(a);
 }
 

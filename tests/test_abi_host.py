@@ -29,7 +29,7 @@ def test_library_exports_every_declared_symbol():
     assert {"lmkan_forward", "lmkan_backward", "lmkan_locate", "lmkan_pack", "lmkan_grid",
             "lmkan_version", "lmkan_status_string", "lmkan_packed_bytes",
             "lmkan_workspace_bytes", "lmkan_hessian_reg", "lmkan_fold", "lmkan_conv2d_rows",
-            "lmkan_conv2d_forward", "lmkan_conv2d_backward"} <= declared
+            "lmkan_conv2d_forward", "lmkan_conv2d_backward", "lmkan_time_next_kernel"} <= declared
     for name in declared:
         assert hasattr(L, name), name
         assert hasattr(pkg, name), f"python binding lacks {name}"

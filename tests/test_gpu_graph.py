@@ -107,3 +107,49 @@ def test_convolution_and_regulariser_replay(dev):
         assert torch.equal(y, y_e)
         torch.testing.assert_close(gx, gx_e, rtol=0, atol=1e-5 * float(gx_e.abs().max()))
         torch.testing.assert_close(gP, gP_e, rtol=0, atol=1e-5 * float(gP_e.abs().max()))
+
+
+def test_time_next_kernel_brackets_only_the_main_kernel(dev):
+    """The measurement aid: armed events are recorded around the main kernel of the next call and
+    used once; the kernel's time is positive and no longer than the whole call's."""
+    B, n_in, n_out, G = 4096, 64, 64, 16
+    desc = pkg.LayerDesc(n_in, n_out, G)
+    P = _rand(desc.coef_shape(), 3, dev, 0.1)
+    x, gy = _rand((B, n_in), 4, dev), _rand((B, n_out), 5, dev)
+    pkg.lmkan_forward(desc, x, P)           # warm-up
+    pkg.lmkan_backward(desc, x, P, gy)
+    torch.cuda.synchronize()
+
+    def armed(call):
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        c0, c1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        e1.record()
+        pkg.lmkan_time_next_kernel(e0, e1)
+        c0.record()
+        call()
+        c1.record()
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1), c0.elapsed_time(c1)
+
+    for call in (lambda: pkg.lmkan_forward(desc, x, P),
+                 lambda: pkg.lmkan_backward(desc, x, P, gy, need_grad_coef=False),
+                 lambda: pkg.lmkan_backward(desc, x, P, gy, need_grad_x=False),
+                 lambda: pkg.lmkan_backward(desc, x, P, gy)):
+        kernel, whole = armed(call)
+        assert 0.0 < kernel <= whole
+    # used once: a second call leaves fresh events untouched (stop is not after start by a kernel's time)
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    e1.record()
+    pkg.lmkan_time_next_kernel(e0, e1)
+    pkg.lmkan_forward(desc, x, P)
+    torch.cuda.synchronize()
+    first = e0.elapsed_time(e1)
+    pkg.lmkan_forward(desc, x, P)           # not armed any more
+    torch.cuda.synchronize()
+    assert e0.elapsed_time(e1) == first
+    with pytest.raises(pkg.LmkanError):
+        pkg.lib().lmkan_time_next_kernel  # attribute exists
+        pkg.binding._check(pkg.lib().lmkan_time_next_kernel(e0.cuda_event, None), "lmkan_time_next_kernel")
+    pkg.lmkan_time_next_kernel(None, None)
