@@ -41,10 +41,11 @@ struct is_bf16<bf16_t> {
 //   field 0: node = i1 (G+1) + i2 (int32), field 1: u, field 2: v  with
 //   u = (x1 - node[i1]) / h1, v likewise; the four B-spline products are
 //   (1-u)(1-v), u(1-v), (1-u)v, uv.
-// A 64 x 64 (sample x pair) tile is read along the rows of x, transposed
+// A 64 x 32 (sample x pair) tile is read along the rows of x, transposed
 // through LDS and written along the sample axis.
 // ---------------------------------------------------------------------------
-constexpr int kRecTile = 64;
+constexpr int kRecTile = 64;   // samples per tile
+constexpr int kRecPairs = 32;  // pairs per tile: 25 KB of LDS, six workgroups per CU
 
 template <bool CONV>
 __global__ __launch_bounds__(256) void preamble_records_kernel(GridTab tab, const float *__restrict__ x,
@@ -55,17 +56,18 @@ __global__ __launch_bounds__(256) void preamble_records_kernel(GridTab tab, cons
 {
     __shared__ float s_node[LMKAN_MAX_GRID + 1];
     __shared__ float s_invh[LMKAN_MAX_GRID];
-    __shared__ int s_n[kRecTile][kRecTile + 1];
-    __shared__ float s_u[kRecTile][kRecTile + 1];
-    __shared__ float s_v[kRecTile][kRecTile + 1];
+    __shared__ int s_n[kRecPairs][kRecTile + 1];
+    __shared__ float s_u[kRecPairs][kRecTile + 1];
+    __shared__ float s_v[kRecPairs][kRecTile + 1];
     for (int i = threadIdx.x; i <= tab.G; i += blockDim.x) s_node[i] = tab.node[i];
     for (int i = threadIdx.x; i < tab.G; i += blockDim.x) s_invh[i] = tab.inv_h[i];
 
     const int K = n_in / 2;
     const int64_t n0 = (int64_t)blockIdx.x * kRecTile;
-    const int k0 = blockIdx.y * kRecTile;
-    const int p = threadIdx.x & 63;  // pair within tile (fast axis of the read)
-    const int r0 = threadIdx.x >> 6;
+    const int k0 = blockIdx.y * kRecPairs;
+    const int p = threadIdx.x % kRecPairs;  // pair within tile (fast axis of the read)
+    const int r0 = threadIdx.x / kRecPairs;
+    constexpr int kRowStep = 256 / kRecPairs, kPerThread = kRecTile / kRowStep;
     // convolution: offset of a row's window once per tile, offsets of this thread's two inputs
     // inside a window once per thread
     __shared__ int64_t s_base[CONV ? kRecTile : 1];
@@ -78,12 +80,12 @@ __global__ __launch_bounds__(256) void preamble_records_kernel(GridTab tab, cons
         }
     }
     __syncthreads();
-    // all sixteen loads of the thread first: the pass is bound by how many bytes are in flight
+    // all loads of the thread first: the pass is bound by how many bytes are in flight
     const bool pair_ok = k0 + p < K;
-    float2 xv[kRecTile / 4];
+    float2 xv[kPerThread];
 #pragma unroll
-    for (int i = 0; i < kRecTile / 4; ++i) {
-        const int r = r0 + 4 * i;
+    for (int i = 0; i < kPerThread; ++i) {
+        const int r = r0 + kRowStep * i;
         const int64_t n = n0 + r;
         xv[i] = make_float2(0.f, 0.f);
         if (n < B && pair_ok) {
@@ -94,8 +96,8 @@ __global__ __launch_bounds__(256) void preamble_records_kernel(GridTab tab, cons
         }
     }
 #pragma unroll
-    for (int i = 0; i < kRecTile / 4; ++i) {
-        const int r = r0 + 4 * i;
+    for (int i = 0; i < kPerThread; ++i) {
+        const int r = r0 + kRowStep * i;
         int node = 0;
         float u = 0.f, v = 0.f;
         if (n0 + r < B && pair_ok) {
@@ -113,7 +115,7 @@ __global__ __launch_bounds__(256) void preamble_records_kernel(GridTab tab, cons
     const int q0 = threadIdx.x >> 6;
     const int64_t n = n0 + r;
     if (n < B) {
-        for (int q = q0; q < kRecTile; q += 4) {
+        for (int q = q0; q < kRecPairs; q += 4) {
             if (k0 + q < K) {
                 const int64_t o = (int64_t)(k0 + q) * B + n;
                 rec_node[o] = s_n[q][r];
@@ -1034,7 +1036,7 @@ void launch_preamble_records(const LayerShape &s, const GridTab &tab, const floa
     float *rec_u = reinterpret_cast<float *>(rec_node + n);
     float *rec_v = rec_u + n;
     const dim3 grid((unsigned)((s.batch + kRecTile - 1) / kRecTile),
-                    (unsigned)((s.pairs() + kRecTile - 1) / kRecTile));
+                    (unsigned)((s.pairs() + kRecPairs - 1) / kRecPairs));
     if (conv)
         preamble_records_kernel<true><<<grid, 256, 0, stream>>>(tab, x, rec_node, rec_u, rec_v, s.batch, s.n_in, *conv);
     else
