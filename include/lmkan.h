@@ -42,13 +42,20 @@ extern "C" {
  * kernels by value; the paper's own experiments use G <= 40 (Sec. 3.4). */
 #define LMKAN_MAX_GRID 64
 
+/* Largest layer and batch: launch grids index pairs and output tiles with 16-bit
+ * block coordinates and rows with 32-bit ones. */
+#define LMKAN_MAX_N_IN 131070
+#define LMKAN_MAX_N_OUT 4194240
+#define LMKAN_MAX_BATCH 2147483647LL
+
 /* Outputs per tile of the packed coefficient layout (see lmkan_pack). */
 #define LMKAN_PACK_TILE 64
 
 typedef enum {
     LMKAN_OK = 0,
     LMKAN_ERR_NULL = 1,        /* a required pointer is NULL                       */
-    LMKAN_ERR_SHAPE = 2,       /* n_in odd or < 2, n_out < 1, G out of range, batch < 0 */
+    LMKAN_ERR_SHAPE = 2,       /* n_in odd or < 2, n_out < 1, G out of range, batch < 0,
+                                  or a size above LMKAN_MAX_N_IN / _N_OUT / _BATCH     */
     LMKAN_ERR_UNSUPPORTED = 3, /* spline order, dtype, layout or flag not implemented  */
     LMKAN_ERR_WORKSPACE = 4,   /* workspace smaller than lmkan_workspace_bytes()   */
     LMKAN_ERR_ALIGN = 5,       /* a pointer is not aligned to its element size     */
@@ -69,8 +76,8 @@ typedef enum {
 
 /* Description of one layer (Alg. 1 "Require"). */
 typedef struct {
-    int32_t n_in;         /* input width, even, >= 2 (Eq. 2 with d = 2)                  */
-    int32_t n_out;        /* output width, >= 1                                          */
+    int32_t n_in;         /* input width, even, 2 .. LMKAN_MAX_N_IN (Eq. 2 with d = 2)   */
+    int32_t n_out;        /* output width, 1 .. LMKAN_MAX_N_OUT                          */
     int32_t grid;         /* G: grid intervals per axis, 3 <= G <= LMKAN_MAX_GRID.
                              G-1 real grid points plus two ghost points (App. B)        */
     int32_t spline_order; /* must be 2: the paper's second-order (piecewise linear)

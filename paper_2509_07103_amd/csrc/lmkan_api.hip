@@ -43,6 +43,7 @@ lmkan_status check_desc(const lmkan_desc *d)
 {
     if (d == nullptr) return LMKAN_ERR_NULL;
     if (d->n_in < 2 || (d->n_in & 1) || d->n_out < 1) return LMKAN_ERR_SHAPE;
+    if (d->n_in > LMKAN_MAX_N_IN || d->n_out > LMKAN_MAX_N_OUT) return LMKAN_ERR_SHAPE;
     if (d->grid < 3 || d->grid > LMKAN_MAX_GRID) return LMKAN_ERR_SHAPE;
     if (d->spline_order != 2) return LMKAN_ERR_UNSUPPORTED;
     if (d->coef_dtype != LMKAN_F32 && d->coef_dtype != LMKAN_F16 && d->coef_dtype != LMKAN_BF16)
@@ -169,7 +170,7 @@ lmkan_status lmkan_locate(const lmkan_desc *desc, int64_t batch, const float *x_
 {
     const lmkan_status st = check_desc(desc);
     if (st != LMKAN_OK) return st;
-    if (batch < 0) return LMKAN_ERR_SHAPE;
+    if (batch < 0 || batch > LMKAN_MAX_BATCH) return LMKAN_ERR_SHAPE;
     if (batch == 0) return LMKAN_OK;
     if (!x_dev || !cell_dev) return LMKAN_ERR_NULL;
     if (!aligned(x_dev, 8) || !aligned(cell_dev, 4)) return LMKAN_ERR_ALIGN;
@@ -190,7 +191,7 @@ lmkan_status forward_impl(const lmkan_desc *desc, int64_t batch, const float *x_
 {
     const lmkan_status st = check_desc(desc);
     if (st != LMKAN_OK) return st;
-    if (batch < 0) return LMKAN_ERR_SHAPE;
+    if (batch < 0 || batch > LMKAN_MAX_BATCH) return LMKAN_ERR_SHAPE;
     if (batch == 0) return LMKAN_OK;
     if (!x_dev || !coef_dev || !y_dev) return LMKAN_ERR_NULL;
     if (!aligned(x_dev, conv ? 4 : 8) || !aligned(y_dev, 4) || !aligned(coef_dev, dtype_size(desc->coef_dtype)))
@@ -224,7 +225,7 @@ lmkan_status backward_impl(const lmkan_desc *desc, int64_t batch, const float *x
 {
     const lmkan_status st = check_desc(desc);
     if (st != LMKAN_OK) return st;
-    if (batch < 0) return LMKAN_ERR_SHAPE;
+    if (batch < 0 || batch > LMKAN_MAX_BATCH) return LMKAN_ERR_SHAPE;
     if (!grad_x_dev && !grad_coef_dev) return LMKAN_OK;
     const LayerShape s = shape_of(desc, batch);
     hipStream_t hs = static_cast<hipStream_t>(stream);
