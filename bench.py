@@ -51,6 +51,55 @@ def parse():
     return ap.parse_args()
 
 
+def stack_inference(args, pkg, wl, torch, np, dev):
+    """cfg2 as it runs at inference (App. F.1): the four layers chained, the evaluation-mode batch
+    normalisation after each hidden layer folded into that layer's table, forward only.  A step is
+    one batch through the whole stack; workspace and activations are allocated once."""
+    layers = wl.CFG2_LAYERS
+    B = layers[0].batch
+    g = torch.Generator(device="cpu").manual_seed(77)
+    x = wl.make_x(layers[0], dev)
+    descs, tables, outs = [], [], []
+    need = 256
+    for i, w in enumerate(layers):
+        paper = pkg.LayerDesc(w.n_in, w.n_out, w.grid)
+        P = wl.make_coef(w, dev)
+        if i + 1 < len(layers):     # seeded stand-ins for the running statistics, as in the full-size test
+            scale = (torch.rand((w.n_out,), generator=g) * 0.4 + 0.8) / (w.coef_std * (w.n_in / 2) ** 0.5)
+            shift = torch.randn((w.n_out,), generator=g) * 0.2
+            pkg.lmkan_fold(paper, P, 1.0, None, None, scale.to(dev), shift.to(dev))
+        tables.append(pkg.lmkan_pack(paper, P))
+        d = pkg.LayerDesc(w.n_in, w.n_out, w.grid, coef_layout=pkg.LMKAN_LAYOUT_PACKED)
+        descs.append(d)
+        outs.append(torch.empty((B, w.n_out), dtype=torch.float32, device=dev))
+        need = max(need, pkg.lmkan_workspace_bytes(d, B, False))
+    ws = torch.empty(need, dtype=torch.uint8, device=dev)
+
+    def step():
+        a = x
+        for d, t, y in zip(descs, tables, outs):
+            pkg.lmkan_forward(d, a, t, y=y, workspace=ws)
+            a = y
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    ms = (time.perf_counter() - t0) * 1e3 / args.steps
+    fma = sum(4.0 * B * (w.n_in // 2) * w.n_out for w in layers)
+    print(json.dumps({
+        "metric": "lmKAN stack inference samples/sec (cfg2: 64->256->256->256->1, forward only, 1 GPU)",
+        "value": round(B / (ms * 1e-3), 1), "unit": "samples/s", "n_gpus": 1, "steps": args.steps,
+        "warmup": args.warmup, "ms_per_step": round(ms, 4), "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+        "config": {"workload": f"cfg2_stack_inference: batch={B} G=16, normalisation folded into the tables, "
+                               "activations pass through device memory between the layers"},
+        "tflops": round(2 * fma / (ms * 1e-3) / 1e12, 3)}))
+
+
 def main():
     args = parse()
     if args.gpus != 1:
@@ -69,6 +118,8 @@ def main():
         sys.exit(2)
     dev = torch.device("cuda:0")
     L = pkg.lib()
+    if args.workload == "cfg2_stack_inference":
+        return stack_inference(args, pkg, wl, torch, np, dev)
     conv = args.workload in wl.CONV_BY_NAME     # a convolution stage: rows = windows of the images
     w = wl.CONV_BY_NAME[args.workload] if conv else wl.BY_NAME[args.workload]
     if args.grid:
