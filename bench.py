@@ -278,7 +278,9 @@ def main():
                              "its launch; all_ms: whole calls (kernel + preamble, sort, fill, transpose passes)"})
 
     out = {
-        "metric": f"lmKAN layer samples/sec (forward + backward, {w.n_in}->{n_out}, 1 GPU)",
+        # the benchmark's metric; `value` is the samples/sec of a forward + backward step, the gather rate
+        # and its ratio to the HBM peak are in "forward"
+        "metric": f"lmKAN layer samples/sec + achieved gather GB/s vs HBM peak ({w.n_in}->{n_out}, 1 GPU)",
         "value": round(B / (ms_per_step * 1e-3), 1),
         "unit": "samples/s",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
