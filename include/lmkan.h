@@ -59,7 +59,9 @@ typedef enum {
     LMKAN_ERR_UNSUPPORTED = 3, /* spline order, dtype, layout or flag not implemented  */
     LMKAN_ERR_WORKSPACE = 4,   /* workspace smaller than lmkan_workspace_bytes()   */
     LMKAN_ERR_ALIGN = 5,       /* a pointer is not aligned to its element size     */
-    LMKAN_ERR_HIP = 6          /* the HIP runtime reported an error at launch      */
+    LMKAN_ERR_HIP = 6,         /* the HIP runtime reported an error at launch      */
+    LMKAN_ERR_STATIC_LIMIT = 7 /* lmkan_forward_static: the batch needs more scratch
+                                  than LMKAN_STATIC_SCRATCH_BYTES                     */
 } lmkan_status;
 
 /* Storage type of the coefficient tensor.  Half formats are storage only:
@@ -157,6 +159,25 @@ lmkan_status lmkan_locate(const lmkan_desc *desc, int64_t batch, const float *x_
 lmkan_status lmkan_forward(const lmkan_desc *desc, int64_t batch, const float *x_dev,
                            const void *coef_dev, float *y_dev, void *workspace_dev,
                            size_t workspace_bytes, void *stream);
+
+/*
+ * lmkan_forward for callers that cannot bring a workspace because they cannot allocate
+ * one: code under HIP graph capture, tight serving loops, harnesses that forbid
+ * hipMalloc.  Same arguments, same kernels and same result as lmkan_forward; the
+ * preamble records and partial outputs live in a buffer of LMKAN_STATIC_SCRATCH_BYTES
+ * that is part of the library itself (one copy on every GPU the library runs on, kept
+ * until the process ends).  The call allocates nothing and frees nothing.
+ *   - LMKAN_ERR_STATIC_LIMIT when lmkan_workspace_bytes(desc, batch, 0) exceeds the
+ *     buffer (nothing is launched); LMKAN_ERR_HIP when the runtime cannot name the
+ *     buffer's address.
+ *   - All calls on one GPU share the buffer: two of them must not overlap in time
+ *     (different streams, or host threads, without ordering between them race).
+ *   - The first call on a device looks the buffer's address up
+ *     (hipGetSymbolAddress); make it outside any stream capture.
+ */
+#define LMKAN_STATIC_SCRATCH_BYTES (32u << 20)
+lmkan_status lmkan_forward_static(const lmkan_desc *desc, int64_t batch, const float *x_dev,
+                                  const void *coef_dev, float *y_dev, void *stream);
 
 /*
  * Layer backward: derivatives of Alg. 1's four-term sum.

@@ -22,6 +22,7 @@ LMKAN_LAYOUT_PAPER, LMKAN_LAYOUT_PACKED = 0, 1
 LMKAN_FLAG_ACCUMULATE_GRAD_COEF = 1
 LMKAN_PACK_TILE = 64
 LMKAN_MAX_GRID = 64
+LMKAN_STATIC_SCRATCH_BYTES = 32 << 20
 
 _TORCH_DTYPE = {LMKAN_F32: torch.float32, LMKAN_F16: torch.float16, LMKAN_BF16: torch.bfloat16}
 _DTYPE_CODE = {v: k for k, v in _TORCH_DTYPE.items()}
@@ -116,6 +117,8 @@ def lib() -> C.CDLL:
     L.lmkan_forward.restype = C.c_int
     L.lmkan_forward.argtypes = [dp, C.c_int64, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p,
                                 C.c_size_t, C.c_void_p]
+    L.lmkan_forward_static.restype = C.c_int
+    L.lmkan_forward_static.argtypes = [dp, C.c_int64, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]
     L.lmkan_fold.restype = C.c_int
     L.lmkan_fold.argtypes = [dp, C.c_void_p, C.c_float, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]
     L.lmkan_hessian_reg.restype = C.c_int
@@ -239,6 +242,18 @@ def lmkan_forward(desc: LayerDesc, x: torch.Tensor, coef: torch.Tensor, y: torch
     _check(lib().lmkan_forward(C.byref(desc.c()), batch, xp, cp, yp,
                                ws.data_ptr() if ws is not None else None, wsz, _stream(stream)),
            "lmkan_forward")
+    return y
+
+
+def lmkan_forward_static(desc: LayerDesc, x: torch.Tensor, coef: torch.Tensor, y: torch.Tensor,
+                         stream=None) -> torch.Tensor:
+    """lmkan_forward on the library's own static scratch: the caller brings x, coef and y, nothing is allocated."""
+    batch = x.shape[0]
+    xp = _dev(x, torch.float32, (batch, desc.n_in), "x")
+    cp = _coef_ptr(desc, coef)
+    yp = _dev(y, torch.float32, (batch, desc.n_out), "y")
+    _check(lib().lmkan_forward_static(C.byref(desc.c()), batch, xp, cp, yp, _stream(stream)),
+           "lmkan_forward_static")
     return y
 
 

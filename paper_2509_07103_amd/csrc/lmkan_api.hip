@@ -3,6 +3,8 @@
 #include <math.h>
 #include <string.h>
 
+#include <mutex>
+
 #include "lmkan.h"
 #include "lmkan_kernels.h"
 
@@ -116,6 +118,7 @@ const char *lmkan_status_string(lmkan_status status)
     case LMKAN_ERR_WORKSPACE: return "workspace too small";
     case LMKAN_ERR_ALIGN: return "misaligned pointer";
     case LMKAN_ERR_HIP: return "HIP runtime error at launch";
+    case LMKAN_ERR_STATIC_LIMIT: return "batch needs more scratch than the library's static buffer holds";
     }
     return "unknown status";
 }
@@ -315,6 +318,58 @@ lmkan_status lmkan_backward(const lmkan_desc *desc, int64_t batch, const float *
 {
     return backward_impl(desc, batch, x_dev, coef_dev, grad_y_dev, grad_x_dev, grad_coef_dev, workspace_dev,
                          workspace_bytes, stream, nullptr);
+}
+
+}  // extern "C"
+
+namespace {
+
+// Workspace of lmkan_forward_static: part of the library's code object, one copy per GPU,
+// kept until the process ends.  In host code the array's name is only a handle for
+// hipGetSymbolAddress; the address kernels can use is looked up once per device.
+__device__ __align__(256) unsigned char scratch[LMKAN_STATIC_SCRATCH_BYTES];
+
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mutex;
+void *g_scratch_ptr[kMaxDevices];
+
+// device address of `scratch` on the current device, or nullptr when the runtime refuses
+void *static_scratch()
+{
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return nullptr;
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (!g_scratch_ptr[dev]) {
+        void *ptr = nullptr;
+        if (hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)) != hipSuccess) return nullptr;
+        g_scratch_ptr[dev] = ptr;
+    }
+    return g_scratch_ptr[dev];
+}
+
+}  // namespace
+
+extern "C" {
+
+lmkan_status lmkan_forward_static(const lmkan_desc *desc, int64_t batch, const float *x_dev, const void *coef_dev,
+                                  float *y_dev, void *stream)
+{
+    const lmkan_status st = check_desc(desc);
+    if (st != LMKAN_OK) return st;
+    if (batch < 0 || batch > LMKAN_MAX_BATCH) return LMKAN_ERR_SHAPE;
+    if (batch == 0) return LMKAN_OK;
+    const size_t need = lmkan_workspace_bytes(desc, batch, 0);
+    if (need > LMKAN_STATIC_SCRATCH_BYTES) return LMKAN_ERR_STATIC_LIMIT;
+    if (!x_dev || !coef_dev || !y_dev) return LMKAN_ERR_NULL;
+    void *ws = nullptr;
+    if (need > 0) {
+        ws = static_scratch();
+        if (!ws) return LMKAN_ERR_HIP;
+    }
+    // every byte of the workspace a forward kernel reads was written earlier in the same call
+    // (records by the preamble pass, partial outputs by the split workgroups), so what an
+    // earlier call left behind needs no clearing
+    return forward_impl(desc, batch, x_dev, coef_dev, y_dev, ws, need, stream, nullptr);
 }
 
 lmkan_status lmkan_time_next_kernel(void *start_event, void *stop_event)

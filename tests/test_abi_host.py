@@ -29,7 +29,8 @@ def test_library_exports_every_declared_symbol():
     assert {"lmkan_forward", "lmkan_backward", "lmkan_locate", "lmkan_pack", "lmkan_grid",
             "lmkan_version", "lmkan_status_string", "lmkan_packed_bytes",
             "lmkan_workspace_bytes", "lmkan_hessian_reg", "lmkan_fold", "lmkan_conv2d_rows",
-            "lmkan_conv2d_forward", "lmkan_conv2d_backward", "lmkan_time_next_kernel"} <= declared
+            "lmkan_conv2d_forward", "lmkan_conv2d_backward", "lmkan_time_next_kernel",
+            "lmkan_forward_static"} <= declared
     for name in declared:
         assert hasattr(L, name), name
         assert hasattr(pkg, name), f"python binding lacks {name}"
@@ -37,8 +38,8 @@ def test_library_exports_every_declared_symbol():
 
 def test_version_and_status_strings():
     assert pkg.lmkan_version() == 1
-    seen = {pkg.lmkan_status_string(s) for s in range(7)}
-    assert len(seen) == 7 and "ok" in seen
+    seen = {pkg.lmkan_status_string(s) for s in range(8)}
+    assert len(seen) == 8 and "ok" in seen
     assert pkg.lmkan_status_string(99) == "unknown status"
 
 
@@ -105,6 +106,23 @@ def test_null_misaligned_and_negative_arguments():
     assert L.lmkan_forward(C.byref(d), 0, None, None, None, None, 0, None) == 0
     assert L.lmkan_locate(C.byref(d), 0, None, None, None) == 0
     assert L.lmkan_backward(C.byref(d), 4, ok, ok, ok, None, None, None, 0, None) == 0
+
+
+def test_static_scratch_forward_rejects_what_does_not_fit_before_any_launch():
+    """The entry point that allocates nothing: a batch whose records and partial outputs exceed the
+    library's static buffer is an error of its own, found on the host (the pointers are never read)."""
+    L = pkg.lib()
+    ok = C.c_void_p(0x1000)
+    big = _desc(n_in=1024, n_out=1024, grid=16)
+    assert pkg.lmkan_workspace_bytes(big, 8192, False) > pkg.LMKAN_STATIC_SCRATCH_BYTES
+    assert L.lmkan_forward_static(C.byref(big.c()), 8192, ok, ok, ok, None) == 7
+    assert "static" in pkg.lmkan_status_string(7)
+    d = _desc().c()
+    assert L.lmkan_forward_static(C.byref(d), 0, None, None, None, None) == 0
+    assert L.lmkan_forward_static(C.byref(d), -1, ok, ok, ok, None) == 2
+    assert L.lmkan_forward_static(C.byref(d), 4, None, ok, ok, None) == 1
+    assert L.lmkan_forward_static(None, 4, ok, ok, ok, None) == 1
+    assert L.lmkan_forward_static(C.byref(_desc(grid=2).c()), 4, ok, ok, ok, None) == 2
 
 
 def test_packed_size_pads_outputs_to_the_tile():
