@@ -125,17 +125,22 @@ lmkan_status lmkan_pack(const lmkan_desc *desc, const void *coef_paper_dev, void
                         void *stream);
 
 /*
- * Device scratch memory lmkan_forward (pass = 0) or lmkan_backward (pass = 1)
- * needs for this batch size; may be 0.  Forward: the preamble records of Alg. 1
- * (cell and local coordinates per (sample, pair), 12 bytes each) and, when few
- * samples and outputs leave compute units idle and the pairs are therefore split
- * over several workgroups, one [batch][n_out] float32 partial output per extra
- * split (summed in a fixed order: the forward result does not vary between runs,
- * except for n_out <= 8, where the splits add atomically).  Backward:
- * the same records, their copy sorted by cell for the coefficient gradient
- * (about 21 bytes per (sample, pair) plus per-pair tables), and a transposed
- * float32 copy of grad_x.  The contents are scratch: nothing is kept between
- * calls, and two calls that share a workspace must not overlap in time.
+ * Device scratch memory a call needs for this batch size; may be 0.
+ *   pass = 0  lmkan_forward: the preamble records of Alg. 1 (cell and local coordinates
+ *             per (sample, pair), 12 bytes each) and, when few samples and outputs
+ *             leave compute units idle and the pairs are therefore split over several
+ *             workgroups, one [batch][n_out] float32 partial output per extra split
+ *             (summed in a fixed order: the forward result does not vary between
+ *             runs, except for n_out <= 8, where the splits add atomically).
+ *   pass = 1  lmkan_backward with both gradients; 2: grad_x only; 3: grad_coef only.
+ *             The same records; their copy sorted by cell (16 bytes per (sample,
+ *             pair) plus per-pair tables) when a kernel that walks it can serve the
+ *             shape; for grad_x a transposed float32 copy of it and, for grids too
+ *             fine for the slab kernels, its per-output-tile partial sums (8 bytes
+ *             per (sample, pair) and 64 outputs).  The size for pass = 1 covers the
+ *             other two.
+ * The contents are scratch: nothing is kept between calls, and two calls that share a
+ * workspace must not overlap in time.  Any other pass gives 0.
  */
 size_t lmkan_workspace_bytes(const lmkan_desc *desc, int64_t batch, int32_t pass);
 
@@ -191,10 +196,15 @@ lmkan_status lmkan_forward_static(const lmkan_desc *desc, int64_t batch, const f
  *   coef_dev      may be NULL when grad_x_dev is NULL.
  *   workspace_dev / workspace_bytes: at least lmkan_workspace_bytes(desc, batch, 1),
  *                 256-byte aligned.
- * Sums are float32 and their order is not fixed (samples of one cell are taken
- * in the order a parallel counting sort leaves them; partial sums of grad_x and,
- * for some shapes, of grad_coef meet through float32 atomics), so the last bits
- * of both gradients can differ from run to run.
+ * Sums are float32.  Run-to-run variation: the counting sort by cell is stable
+ * (samples of a cell stay in index order), so a grad_coef written by the
+ * cell-sorted kernels repeats bit for bit when every (pair, 64-output tile) is
+ * walked by one wave (batch <= 12288 rows and at least 4096 (pair, tile) streams,
+ * e.g. 1024 -> 1024); shorter layers and longer batches cut the streams into
+ * runs that meet through float32 atomics, and the generic kernels use atomics
+ * throughout: there the last bits can differ.  grad_x repeats bit for bit on the
+ * sorted walk (grids finer than 34 intervals) and for n_out <= 8; the slab
+ * kernels (grids up to 34) add their output tiles with float32 atomics.
  */
 lmkan_status lmkan_backward(const lmkan_desc *desc, int64_t batch, const float *x_dev,
                             const void *coef_dev, const float *grad_y_dev, float *grad_x_dev,

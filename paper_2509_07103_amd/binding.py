@@ -182,18 +182,25 @@ def lmkan_packed_bytes(desc: LayerDesc) -> int:
     return lib().lmkan_packed_bytes(C.byref(desc.c()))
 
 
-def lmkan_workspace_bytes(desc: LayerDesc, batch: int, backward: bool) -> int:
-    return lib().lmkan_workspace_bytes(C.byref(desc.c()), batch, 1 if backward else 0)
+def lmkan_workspace_bytes(desc: LayerDesc, batch: int, backward: bool, need_grad_x: bool = True,
+                          need_grad_coef: bool = True) -> int:
+    """Workspace of a forward call, or of a backward call for the gradients it is asked for."""
+    if not backward:
+        code = 0
+    else:
+        code = 1 if (need_grad_x and need_grad_coef) else (2 if need_grad_x else 3)
+    return lib().lmkan_workspace_bytes(C.byref(desc.c()), batch, code)
 
 
-def _workspace(desc: LayerDesc, batch: int, backward: bool, device, workspace: torch.Tensor | None = None):
+def _workspace(desc: LayerDesc, batch: int, backward: bool, device, workspace: torch.Tensor | None = None,
+               need_grad_x: bool = True, need_grad_coef: bool = True):
     """(tensor or None, bytes): the caller's workspace when given (any dtype, contiguous, on the device;
     its size goes to the library, which checks it), else a fresh allocation of the size the library asks for."""
     if workspace is not None:
         if not workspace.is_cuda or not workspace.is_contiguous():
             raise ValueError("workspace: expected a contiguous device tensor")
         return workspace, workspace.numel() * workspace.element_size()
-    need = lmkan_workspace_bytes(desc, batch, backward)
+    need = lmkan_workspace_bytes(desc, batch, backward, need_grad_x, need_grad_coef)
     if need == 0:
         return None, 0
     ws = torch.empty(need, dtype=torch.uint8, device=device)
@@ -274,7 +281,7 @@ def lmkan_backward(desc: LayerDesc, x: torch.Tensor, coef: torch.Tensor | None, 
         grad_coef = torch.empty(desc.coef_shape(), dtype=torch.float32, device=x.device)
     gxp = _dev(grad_x, torch.float32, (batch, desc.n_in), "grad_x") if need_grad_x else None
     gcp = _dev(grad_coef, torch.float32, desc.coef_shape(), "grad_coef") if need_grad_coef else None
-    ws, wsz = _workspace(desc, batch, True, x.device, workspace)
+    ws, wsz = _workspace(desc, batch, True, x.device, workspace, need_grad_x, need_grad_coef)
     _check(lib().lmkan_backward(C.byref(desc.c()), batch, xp, cp, gyp, gxp, gcp,
                                 ws.data_ptr() if ws is not None else None, wsz, _stream(stream)),
            "lmkan_backward")
@@ -334,7 +341,7 @@ def lmkan_conv2d_backward(desc: LayerDesc, conv: Conv2d, x: torch.Tensor, coef: 
         grad_coef = torch.empty(desc.coef_shape(), dtype=torch.float32, device=x.device)
     gxp = _dev(grad_x, torch.float32, conv.image_shape(), "grad_x") if need_grad_x else None
     gcp = _dev(grad_coef, torch.float32, desc.coef_shape(), "grad_coef") if need_grad_coef else None
-    ws, wsz = _workspace(desc, rows, True, x.device, workspace)
+    ws, wsz = _workspace(desc, rows, True, x.device, workspace, need_grad_x, need_grad_coef)
     _check(lib().lmkan_conv2d_backward(C.byref(desc.c()), C.byref(conv.c()), xp, cp, gyp, gxp, gcp,
                                        ws.data_ptr() if ws is not None else None, wsz, _stream(stream)),
            "lmkan_conv2d_backward")

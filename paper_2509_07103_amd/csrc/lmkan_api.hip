@@ -7,6 +7,7 @@
 
 #include "lmkan.h"
 #include "lmkan_kernels.h"
+#include "lmkan_sorted.h"
 
 using namespace lmkan;
 
@@ -17,6 +18,26 @@ size_t dtype_size(int dtype) { return dtype == LMKAN_F32 ? 4 : 2; }
 size_t align256(size_t n) { return (n + 255) & ~(size_t)255; }
 
 bool aligned(const void *p, size_t a) { return (reinterpret_cast<uintptr_t>(p) % a) == 0; }
+
+// How a backward workspace is carved up; sizes depend on the shape and on which gradients are
+// wanted only (pointer alignment, which also steers the choice of kernels, is not known when the
+// caller asks for the size, so every path the shape admits is provided for).
+struct BackwardWorkspace {
+    size_t records, sorted, scratch, partial;  // offsets
+    size_t total;
+};
+BackwardWorkspace backward_workspace(const LayerShape &s, bool want_gx, bool want_gp)
+{
+    BackwardWorkspace w;
+    const bool small = small_out_shape_ok(s);
+    const bool sorted = sorted_shape_ok(s) && (want_gx ? !small : !(small && small_coef_ok(s)));
+    w.records = 0;
+    w.sorted = align256(records_bytes(s));
+    w.scratch = w.sorted + (sorted ? sorted_records_bytes(s) : 0);
+    w.partial = w.scratch + (want_gx ? slab_backward_input_scratch_bytes(s) : 0);
+    w.total = w.partial + (want_gx && sorted ? fused_partial_bytes(s) : 0);
+    return w;
+}
 
 // Sec. 3.1 "Sigma grid" + App. B: real points where sigma crosses the levels k/G, with
 // sigma from Eq. 5 (0.5 e^x on the left half, mirrored on the right), then the two ghost
@@ -150,10 +171,12 @@ size_t lmkan_workspace_bytes(const lmkan_desc *desc, int64_t batch, int32_t pass
         if (small_out_shape_ok(s)) return records_bytes(s);
         return slab_forward_shape_ok(s) ? align256(records_bytes(s)) + slab_forward_partial_bytes(s) : 0;
     }
-    // backward: preamble records, the cell-sorted copy used by the coefficient gradient, and the
-    // transposed scratch of the input gradient
-    return align256(records_bytes(s)) + sorted_records_bytes(s) +
-           ((slab_backward_input_shape_ok(s) || small_out_shape_ok(s)) ? slab_backward_input_scratch_bytes(s) : 0);
+    // backward (1: both gradients, 2: grad_x only, 3: grad_coef only): preamble records, their
+    // cell-sorted copy, the per-tile partial sums of grad_x, and a transposed copy of grad_x for the
+    // paths that finish with a transpose (small outputs, unaligned tables, convolutions)
+    if (pass < 1 || pass > 3) return 0;
+    const BackwardWorkspace w = backward_workspace(s, pass != 3, pass != 2);
+    return w.total;
 }
 
 lmkan_status lmkan_pack(const lmkan_desc *desc, const void *coef_paper_dev, void *coef_packed_dev,
@@ -253,29 +276,49 @@ lmkan_status backward_impl(const lmkan_desc *desc, int64_t batch, const float *x
     const bool small = small_out_shape_ok(s);
     const bool gx_small = grad_x_dev && small;
     const bool gp_small = grad_coef_dev && small && small_coef_ok(s);
-    const bool gx_slab = grad_x_dev && !small && slab_backward_input_applicable(s, coef_dev, grad_y_dev, grad_x_dev);
+    // Input gradient.  Where a slab kernel applies (G <= 34) it is the faster one for the input
+    // gradient alone.  The walk over the cell-sorted samples yields both gradients from one pass
+    // over gy: it takes the grids too fine for any slab, and the 16-output slab range when both
+    // gradients are wanted and cells hold enough samples for its chunks of four to fill (16 per
+    // cell on average).  Whatever neither takes goes to the generic kernel.
+    const bool slab_ok = grad_x_dev && !small && slab_backward_input_applicable(s, coef_dev, grad_y_dev, grad_x_dev);
+    const bool dense_cells = s.batch >= (int64_t)16 * s.G * s.G;
+    const bool fused_pays = !slab_ok || (!slab_tile_is_wide(s) && grad_coef_dev && dense_cells);
+    const bool gx_fused = grad_x_dev && !small && s.batch >= 256 && fused_pays &&
+                          fused_backward_applicable(s, coef_dev, grad_y_dev, grad_coef_dev);
+    const bool gx_slab = slab_ok && !gx_fused;
     const bool gp_sorted = grad_coef_dev && !gp_small && coef_sorted_applicable(s, grad_y_dev, grad_coef_dev);
-    const bool need_records = gp_sorted || gx_slab || gx_small || gp_small;
-    const size_t need = need_records ? lmkan_workspace_bytes(desc, batch, 1) : 0;
+    const bool need_records = gp_sorted || gx_fused || gx_slab || gx_small || gp_small;
+    const BackwardWorkspace w = backward_workspace(s, grad_x_dev != nullptr, grad_coef_dev != nullptr);
+    const size_t need = need_records ? w.total : 0;
     if (need > 0 && (!workspace_dev || workspace_bytes < need)) return LMKAN_ERR_WORKSPACE;
     if (need > 0 && !aligned(workspace_dev, 256)) return LMKAN_ERR_ALIGN;
     GridTab tab;
     build_grid(desc->grid, &tab);
     char *ws = static_cast<char *>(workspace_dev);
-    char *ws_sorted = ws + align256(records_bytes(s));
-    float *ws_scratch = reinterpret_cast<float *>(ws_sorted + sorted_records_bytes(s));
+    char *ws_sorted = ws + w.sorted;
+    float *ws_scratch = reinterpret_cast<float *>(ws + w.scratch);
+    char *ws_partial = ws + w.partial;
     TimedCall timed(grad_x_dev ? kTimeGradInput : kTimeGradCoef);
     if (need_records) launch_preamble_records(s, tab, x_dev, ws, hs, conv);
+    SortedStream stream_k{};
+    if (gp_sorted || gx_fused) stream_k = launch_sort(s, ws, ws_sorted, hs);
     if (gp_small) {
         launch_backward_coef_small(s, ws, grad_y_dev, grad_coef_dev, !overwrite, hs);
-    } else if (gp_sorted) {
-        launch_backward_coef_sorted(s, ws, ws_sorted, grad_y_dev, grad_coef_dev, !overwrite, hs);
-    } else if (grad_coef_dev) {
+    } else if (gp_sorted && !gx_fused) {
+        launch_backward_coef_sorted(s, stream_k, grad_y_dev, grad_coef_dev, !overwrite, hs);
+    } else if (grad_coef_dev && !gx_fused) {
         // odd output counts or unaligned buffers: atomics on a gradient that starts at zero
         if (overwrite) launch_fill_zero(grad_coef_dev, (size_t)s.nodes() * s.pairs() * s.n_out, hs);
         launch_backward_generic(s, tab, x_dev, coef_dev, grad_y_dev, nullptr, grad_coef_dev, hs, conv);
     }
-    if (gx_small) {
+    if (gx_fused) {
+        // one walk over the cell-sorted samples yields both gradients (the coefficient gradient
+        // qualifies whenever the input gradient does)
+        launch_backward_fused(s, tab, stream_k, ws, coef_dev, grad_y_dev, grad_x_dev, grad_coef_dev, !overwrite, ws_partial,
+                              conv ? ws_scratch : nullptr, hs);
+        if (conv) launch_input_gradient_out(ws_scratch, grad_x_dev, s, conv, hs);
+    } else if (gx_small) {
         launch_backward_input_small(s, tab, coef_dev, grad_y_dev, ws_scratch, ws, hs);
         launch_input_gradient_out(ws_scratch, grad_x_dev, s, conv, hs);
     } else if (gx_slab) {

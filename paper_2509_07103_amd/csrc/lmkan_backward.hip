@@ -18,7 +18,10 @@
 // two-row window of the table kept in LDS; a table row is written to global memory exactly
 // once, when the walk has passed it.  Rows no sample touches are written as exact zeros, so
 // no separate zero fill is needed.
+#include <mutex>
+
 #include "lmkan_kernels.h"
+#include "lmkan_sorted.h"
 
 namespace lmkan {
 
@@ -27,46 +30,16 @@ namespace {
 constexpr int kTile = LMKAN_PACK_TILE;
 constexpr int kSortThreads = 1024;
 
-typedef float f4v __attribute__((ext_vector_type(4)));
-typedef unsigned u2v __attribute__((ext_vector_type(2)));
-
-constexpr int kChunk = 4;    // samples per chunk; a chunk never straddles two cells
 constexpr int kDepth = 8;    // chunks of gy values in flight
-constexpr int kUnroll = 16;  // chunks per trip of the main loop: one load of sample indices
-constexpr int kPerW = 4;     // chunks whose products one load instruction brings in
+constexpr int kPerW = 4;     // chunks whose entries one load instruction brings in
 static_assert(kUnroll % kDepth == 0, "the gy ring must divide the unrolled trip");
-
-// Locality blocks.  A wave reads gy rows in the order of the sorted stream, i.e. all over the
-// batch; as long as the 64-column slice of gy (256 bytes per sample) fits the L2 of an XCD
-// next to the streams, the waves of that XCD share it.  Longer batches are cut into blocks of
-// kBlockSamples samples, the stream of a pair is sorted by (block, cell), and all waves of an
-// XCD work on one block at a time.
-constexpr int kSortSeg = 4096;       // samples per workgroup in the count and scatter passes
-constexpr int kBlockSamples = 8192;  // 2 MiB of gy per block and 64-column tile
-constexpr int kSegPerBlock = kBlockSamples / kSortSeg;
-
-__host__ __device__ inline int stream_blocks(int64_t B)
-{
-    return B > kBlockSamples + kBlockSamples / 2 ? (int)((B + kBlockSamples - 1) / kBlockSamples) : 1;
-}
-
-// Samples per pair in the sorted stream: every non-empty (block, cell) is padded to whole
-// chunks, every block to whole trips of kUnroll chunks, and the end is padded so that the
-// pipeline below can prefetch a trip beyond the last one without bounds checks.
-__host__ __device__ inline int64_t stream_stride(int64_t B, int G)
-{
-    const int64_t blocks = stream_blocks(B);
-    const int64_t body = B + blocks * ((int64_t)(kChunk - 1) * G * G + (int64_t)kChunk * kUnroll);
-    return (body + kChunk - 1) / kChunk * kChunk + (int64_t)kChunk * (2 * kUnroll);
-}
 
 // Counting sort of the samples of every pair by cell, in three launches so that long batches
 // are spread over many workgroups.  records_in: [3][K][B] (node, u, v) from the preamble
 // pass.  Per pair k, with S = stream_stride, the samples ordered by (block, cell):
-//   sorted_w [K][S]      the four products (w00, w10, w01, w11) of a sample, 16 bytes
-//   sorted_n [K][S]      its index.  Padding entries have zero products and repeat the index
-//                        of a sample of the same cell, so that what they multiply is a value
-//                        the cell sees anyway.
+//   rec [K][S]           (u, v, 1, index) of a sample, 16 bytes; padding entries are
+//                        (0, 0, 0, index of a sample of the same cell)
+//   rec_pos [K][B]       where sample n went
 //   chunk_cell [K][S/4]  i1 << 8 | i2 of the cell each chunk belongs to, non-decreasing
 //                        inside a block
 //   block_start [K][blocks+1]  first chunk of every block (multiples of kUnroll) and the
@@ -155,8 +128,7 @@ __global__ __launch_bounds__(kSortSegThreads) void sort_block_size_kernel(const 
 __global__ __launch_bounds__(kSortThreads) void sort_layout_kernel(int32_t *__restrict__ seg_count,
                                                                   int32_t *__restrict__ cell_start,
                                                                   const int32_t *__restrict__ cell_rep,
-                                                                  f4v *__restrict__ sorted_w,
-                                                                  int32_t *__restrict__ sorted_n,
+                                                                  f4v *__restrict__ rec,
                                                                   int32_t *__restrict__ chunk_cell,
                                                                   int32_t *__restrict__ block_start,
                                                                   const int32_t *__restrict__ block_size, int64_t B,
@@ -171,13 +143,12 @@ __global__ __launch_bounds__(kSortThreads) void sort_layout_kernel(int32_t *__re
     const int blocks = stream_blocks(B);
     const int seg_per_block = blocks > 1 ? kSegPerBlock : nseg;
     const int64_t S = stream_stride(B, G);
-    f4v *out_w = sorted_w + (int64_t)k * S;
-    int32_t *out_n = sorted_n + (int64_t)k * S;
+    f4v *out = rec + (int64_t)k * S;
     int32_t *out_cell = chunk_cell + (int64_t)k * (S / kChunk);
     int32_t *cnt_k = seg_count + (int64_t)k * nseg * cells;
     const int32_t *rep_k = cell_rep + (int64_t)k * cells;
     int32_t *bs_k = block_start + (int64_t)k * (blocks + 1);
-    const f4v zero = {0.f, 0.f, 0.f, 0.f};
+    auto filler = [](int32_t n) { return f4v{0.f, 0.f, 0.f, __int_as_float(n)}; };
 
     const int blk = blockIdx.y;
     // stream position where this block starts (a multiple of kChunk * kUnroll)
@@ -250,18 +221,12 @@ __global__ __launch_bounds__(kSortThreads) void sort_layout_kernel(int32_t *__re
             const int cnt = s_count[c];
             if (cnt == 0) continue;
             const int first = s_start[c], padded = (cnt + kChunk - 1) / kChunk * kChunk;
-            const int32_t n0 = rep_k[c];
-            for (int i = cnt; i < padded; ++i) {
-                out_w[first + i] = zero;
-                out_n[first + i] = n0;
-            }
+            const f4v fill = filler(rep_k[c]);
+            for (int i = cnt; i < padded; ++i) out[first + i] = fill;
         }
         {
-            const int32_t n0 = rep_k[last];
-            for (int i = real_end + threadIdx.x; i < fill_end; i += blockDim.x) {
-                out_w[i] = zero;
-                out_n[i] = n0;
-            }
+            const f4v fill = filler(rep_k[last]);
+            for (int i = real_end + threadIdx.x; i < fill_end; i += blockDim.x) out[i] = fill;
         }
         if (threadIdx.x == 0) {
             bs_k[blk] = base_pos / kChunk;
@@ -283,9 +248,8 @@ __global__ __launch_bounds__(kSortSegThreads) void sort_scatter_kernel(const int
                                                                       const float *__restrict__ rec_v,
                                                                       const int32_t *__restrict__ seg_count,
                                                                       const int32_t *__restrict__ cell_start,
-                                                                      f4v *__restrict__ sorted_w,
-                                                                      int32_t *__restrict__ sorted_n, int64_t B,
-                                                                      int G)
+                                                                      f4v *__restrict__ rec,
+                                                                      int32_t *__restrict__ rec_pos, int64_t B, int G)
 {
     extern __shared__ int s_dyn[];
     __shared__ int s_wave[kSortSegThreads / 64];
@@ -365,22 +329,34 @@ __global__ __launch_bounds__(kSortSegThreads) void sort_scatter_kernel(const int
     __syncthreads();
     for (int i = threadIdx.x; i < count; i += blockDim.x) s_order[s_lstart[s_cell[i]] + s_rank[i]] = (unsigned short)i;
     __syncthreads();
-    f4v *out_w = sorted_w + (int64_t)k * S;
-    int32_t *out_n = sorted_n + (int64_t)k * S;
+    // The ranks so far are in the order the atomics happened to be served.  Replace them by the
+    // order of the sample indices (rank = number of samples of the same cell, in this segment,
+    // with a smaller index), so that the stream, and with it the order of every float32 sum
+    // over the samples of a cell, is the same in every run.
+    for (int i = threadIdx.x; i < count; i += blockDim.x) {
+        const int c = s_cell[i];
+        const unsigned short *run = s_order + s_lstart[c];
+        const int len = s_cnt[c];
+        int r = 0;
+        for (int t = 0; t < len; ++t) r += run[t] < i;
+        s_rank[i] = (unsigned short)r;
+    }
+    __syncthreads();
+    for (int i = threadIdx.x; i < count; i += blockDim.x) s_order[s_lstart[s_cell[i]] + s_rank[i]] = (unsigned short)i;
+    __syncthreads();
+    f4v *out = rec + (int64_t)k * S;
+    int32_t *out_pos = rec_pos + (int64_t)k * B + n0;
     for (int lp = threadIdx.x; lp < count; lp += blockDim.x) {
         const int i = s_order[lp];
         const int c = s_cell[i];
         const int pos = s_gbase[c] + lp - s_lstart[c];
-        const float u = s_u[i], v = s_v[i];
-        const float a_lo = 1.0f - u, b_lo = 1.0f - v;
-        out_w[pos] = f4v{a_lo * b_lo, u * b_lo, a_lo * v, u * v};
-        out_n[pos] = (int32_t)(n0 + i);
+        out[pos] = f4v{s_u[i], s_v[i], 1.0f, __int_as_float((int32_t)(n0 + i))};
+        out_pos[i] = pos;
     }
 }
 
 struct CoefGradArgs {
-    const f4v *sorted_w;
-    const int32_t *sorted_n;
+    const f4v *rec;
     const int32_t *chunk_cell;
     const int32_t *block_start;  // [K][n_blocks + 1], in chunks
     const float *gy;
@@ -395,61 +371,6 @@ struct CoefGradArgs {
     int n_blocks;  // locality blocks of the batch
     int n_sub;     // waves per (pair, output tile, block)
 };
-
-// acc[i][q] += (product q of this group's sample) * gy[i] for the chunk whose products sit in
-// quad SUB of every group of `w` (lane 16 g + 4 SUB + q holds product q of group g's sample).
-// One MFMA is 16 independent 4x4 outer products, block b = lanes 4b .. 4b+3: the A operand of
-// the four blocks of a group is taken from the group's block SUB (broadcast size 4 blocks),
-// the B operand is the lane's own gy value, and row q of the result lands in register q of
-// the same lane.
-template <int SUB, bool FRESH>
-__device__ __forceinline__ void chunk_fma(f4v (&acc)[4], float w, const f4v &g)
-{
-    // the first chunk of a cell starts from zero instead of clearing the accumulators
-    const f4v zero = {0.f, 0.f, 0.f, 0.f};
-    acc[0] = __builtin_amdgcn_mfma_f32_4x4x1f32(w, g.x, FRESH ? zero : acc[0], 2, SUB, 0);
-    acc[1] = __builtin_amdgcn_mfma_f32_4x4x1f32(w, g.y, FRESH ? zero : acc[1], 2, SUB, 0);
-    acc[2] = __builtin_amdgcn_mfma_f32_4x4x1f32(w, g.z, FRESH ? zero : acc[2], 2, SUB, 0);
-    acc[3] = __builtin_amdgcn_mfma_f32_4x4x1f32(w, g.w, FRESH ? zero : acc[3], 2, SUB, 0);
-}
-
-// The four groups' partial sums acc[output i][corner q] -> f[i] of group r = total of corner r,
-// output i.  Two rounds of "swap halves of two registers, add": the first pairs corner q
-// with corner q + 2 across the 32-lane halves, the second pairs the results across odd and
-// even 16-lane rows.
-__device__ __forceinline__ void combine_groups(const f4v (&acc)[4], float (&f)[4])
-{
-#if defined(LMKAN_COMBINE_BPERMUTE)
-    const int g = (threadIdx.x >> 4) & 3;
-#pragma unroll
-    for (int i = 0; i < 4; ++i) {
-        float keep = 0.f;
-#pragma unroll
-        for (int q = 0; q < 4; ++q) {
-            float t = acc[i][q];
-            t += __shfl_xor(t, 16, 64);
-            t += __shfl_xor(t, 32, 64);
-            keep = (g == q) ? t : keep;
-        }
-        f[i] = keep;
-    }
-#else
-#pragma unroll
-    for (int i = 0; i < 4; ++i) {
-        float z[2];
-#pragma unroll
-        for (int q = 0; q < 2; ++q) {
-            // upper half of acc[q] <-> lower half of acc[q + 2]
-            const u2v s = __builtin_amdgcn_permlane32_swap(__float_as_uint(acc[i][q]),
-                                                           __float_as_uint(acc[i][q + 2]), false, false);
-            z[q] = __uint_as_float(s.x) + __uint_as_float(s.y);  // rows 0,1: corner q; rows 2,3: corner q + 2
-        }
-        // odd rows of z[0] <-> even rows of z[1]
-        const u2v s = __builtin_amdgcn_permlane16_swap(__float_as_uint(z[0]), __float_as_uint(z[1]), false, false);
-        f[i] = __uint_as_float(s.x) + __uint_as_float(s.y);
-    }
-#endif
-}
 
 template <bool kOffset32>
 __global__ __launch_bounds__(64) void backward_coef_stream_kernel(CoefGradArgs a)
@@ -493,14 +414,15 @@ __global__ __launch_bounds__(64) void backward_coef_stream_kernel(CoefGradArgs a
     ScalarIntPtr cc = (ScalarIntPtr)(a.chunk_cell + (int64_t)k * (a.S / kChunk) + c_begin);
     float *out = a.gP + (int64_t)k * a.gmap.s_pair + col;
 
-    // products: lane (g, 4 j + q) fetches product q of group g's sample of chunk c + j, so one
-    // load brings in four chunks (256 contiguous bytes); sample indices: lane (g, j) fetches the
-    // index of group g's sample of chunk c + j, sixteen chunks per load
-    const float *w_ptr = reinterpret_cast<const float *>(a.sorted_w + (int64_t)k * a.S + (int64_t)c_begin * kChunk) +
-                         ((l16 >> 2) * kChunk + g) * 4 + (l16 & 3);
-    const int32_t *n_ptr = a.sorted_n + (int64_t)k * a.S + (int64_t)c_begin * kChunk + l16 * kChunk + g;
-    auto load_w = [&](int chunk) { return w_ptr[(int64_t)chunk * (kChunk * 4)]; };
-    auto load_n = [&](int chunk) { return n_ptr[(int64_t)chunk * kChunk]; };
+    // entries: lane (g, 4 j + q) fetches the entry of group g's sample of chunk c + j and will
+    // form its product q, so one load brings in four chunks (256 contiguous bytes); sample
+    // indices: lane (g, j) fetches the index of group g's sample of chunk c + j, sixteen chunks
+    // per load
+    const f4v *rec_k = a.rec + (int64_t)k * a.S + (int64_t)c_begin * kChunk;
+    const f4v *e_ptr = rec_k + (l16 >> 2) * kChunk + g;
+    const int32_t *n_ptr = reinterpret_cast<const int32_t *>(rec_k + l16 * kChunk + g) + 3;
+    auto load_e = [&](int chunk) { return e_ptr[(int64_t)chunk * kChunk]; };
+    auto load_n = [&](int chunk) { return n_ptr[(int64_t)chunk * (kChunk * 4)]; };
 
     const unsigned col_bytes = (unsigned)(col_ok ? col : 0) * 4u;
     const unsigned row_bytes = (unsigned)a.n_out * 4u;
@@ -574,7 +496,8 @@ __global__ __launch_bounds__(64) void backward_coef_stream_kernel(CoefGradArgs a
         // c + P is consumed and the gy values of chunk c + P + kDepth are requested (their sample
         // indices were loaded a trip earlier); a register of products is refilled for the next
         // trip as soon as its fourth chunk has been consumed.
-        float wq[kUnroll / kPerW];
+        f4v eq[kUnroll / kPerW];   // entries as loaded
+        float wq[kUnroll / kPerW];  // their products, formed when the first of the four chunks is consumed
         f4v gq[kDepth];
         int n_now, n_nxt;
         // The fill is issued in the order the steady state leaves the loads in at the top of a
@@ -583,7 +506,7 @@ __global__ __launch_bounds__(64) void backward_coef_stream_kernel(CoefGradArgs a
         static_for(std::make_integer_sequence<int, kUnroll / kPerW>{}, [&](auto rc) {
             constexpr int r = decltype(rc)::value;
             if constexpr (r * kPerW < kUnroll - kDepth) {
-                wq[r] = load_w(r * kPerW);
+                eq[r] = load_e(r * kPerW);
                 __builtin_amdgcn_sched_barrier(0);
             }
         });
@@ -593,7 +516,7 @@ __global__ __launch_bounds__(64) void backward_coef_stream_kernel(CoefGradArgs a
             gq[d] = load_gy(std::integral_constant<int, d>{}, n_now);
             __builtin_amdgcn_sched_barrier(0);
             if constexpr (P % kPerW == kPerW - 1) {
-                wq[P / kPerW] = load_w((P / kPerW) * kPerW);
+                eq[P / kPerW] = load_e((P / kPerW) * kPerW);
                 __builtin_amdgcn_sched_barrier(0);
             }
         });
@@ -610,6 +533,7 @@ __global__ __launch_bounds__(64) void backward_coef_stream_kernel(CoefGradArgs a
             static_for(std::make_integer_sequence<int, kUnroll>{}, [&](auto pc) {
                 constexpr int P = decltype(pc)::value;
                 const int cell_cur = cells_now[P];
+                if constexpr (P % kPerW == 0) wq[P / kPerW] = entry_product(eq[P / kPerW], l16 & 3);
                 if (cell_cur != cur_cell) {
                     if (cur_cell >= 0) flush();
                     retire_rows(cell_cur >> 8);
@@ -620,7 +544,7 @@ __global__ __launch_bounds__(64) void backward_coef_stream_kernel(CoefGradArgs a
                 }
                 gq[P % kDepth] = load_gy(std::integral_constant<int, (P + kDepth) % kUnroll>{},
                                          P + kDepth < kUnroll ? n_now : n_nxt);
-                if constexpr (P % kPerW == kPerW - 1) wq[P / kPerW] = load_w(c + kUnroll + (P / kPerW) * kPerW);
+                if constexpr (P % kPerW == kPerW - 1) eq[P / kPerW] = load_e(c + kUnroll + (P / kPerW) * kPerW);
             });
             n_now = n_nxt;
 #pragma unroll
@@ -639,100 +563,141 @@ size_t sorted_records_bytes(const LayerShape &s)
     const size_t nseg = ((size_t)s.batch + kSortSeg - 1) / kSortSeg;
     const size_t blocks = (size_t)stream_blocks(s.batch);
     const size_t cells = (size_t)s.G * s.G;
-    const size_t per_pair = S * (sizeof(f4v) + sizeof(int32_t)) + (S / kChunk) * sizeof(int32_t) +
-                            (2 * blocks + 1) * sizeof(int32_t) + (nseg + blocks + 1) * cells * sizeof(int32_t);
+    const size_t per_pair = S * sizeof(f4v) + (S / kChunk) * sizeof(int32_t) + (2 * blocks + 1) * sizeof(int32_t) +
+                            (nseg + blocks + 1) * cells * sizeof(int32_t) + (size_t)s.batch * sizeof(int32_t);
     return ((size_t)s.pairs() * per_pair + 255) & ~(size_t)255;
 }
 
+// The cell-sorted paths index stream positions, and the launch grids batch segments, with 32-bit
+// integers: the longest batch they take.  Longer ones go to the generic kernels.
+bool sorted_batch_ok(const LayerShape &s)
+{
+    const int64_t nseg = (s.batch + kSortSeg - 1) / kSortSeg;
+    return nseg <= 65535 && stream_blocks(s.batch) <= 65535 && stream_stride(s.batch, s.G) < ((int64_t)1 << 31);
+}
+
+bool sorted_shape_ok(const LayerShape &s) { return s.n_out % 4 == 0 && sorted_batch_ok(s); }
+
 bool coef_sorted_applicable(const LayerShape &s, const float *gy, const float *gcoef)
 {
-    return s.n_out % 4 == 0 &&
+    return sorted_shape_ok(s) &&
            ((reinterpret_cast<uintptr_t>(gy) | reinterpret_cast<uintptr_t>(gcoef)) & 15) == 0;
 }
 
-void launch_backward_coef_sorted(const LayerShape &s, const void *records, void *sorted, const float *gy,
-                                 float *gcoef, bool accumulate, hipStream_t stream)
+SortBuffers sort_buffers(const LayerShape &s, void *sorted)
+{
+    const size_t S = (size_t)stream_stride(s.batch, s.G);
+    const size_t K = (size_t)s.pairs();
+    const size_t nseg = ((size_t)s.batch + kSortSeg - 1) / kSortSeg;
+    const size_t blocks = (size_t)stream_blocks(s.batch);
+    const size_t cells = (size_t)s.G * s.G;
+    SortBuffers b;
+    b.rec = static_cast<f4v *>(sorted);  // 16-byte items first, then the 4-byte ones
+    b.chunk_cell = reinterpret_cast<int32_t *>(b.rec + K * S);
+    b.block_start = b.chunk_cell + K * (S / kChunk);
+    b.block_size = b.block_start + K * (blocks + 1);
+    b.seg_count = b.block_size + K * blocks;
+    b.cell_start = b.seg_count + K * nseg * cells;
+    b.cell_rep = b.cell_start + K * blocks * cells;
+    b.rec_pos = b.cell_rep + K * cells;
+    return b;
+}
+
+SortedStream launch_sort(const LayerShape &s, const void *records, void *sorted, hipStream_t stream)
 {
     const size_t n = (size_t)s.pairs() * (size_t)s.batch;
-    const size_t S = (size_t)stream_stride(s.batch, s.G);
     const size_t K = (size_t)s.pairs();
     const int32_t *rec_node = static_cast<const int32_t *>(records);
     const float *rec_u = reinterpret_cast<const float *>(rec_node + n);
     const float *rec_v = rec_u + n;
-    f4v *sorted_w = static_cast<f4v *>(sorted);  // 16-byte items first, then the 4-byte ones
-    int32_t *sorted_n = reinterpret_cast<int32_t *>(sorted_w + K * S);
-    int32_t *chunk_cell = sorted_n + K * S;
+    const SortBuffers b = sort_buffers(s, sorted);
     const size_t nseg = ((size_t)s.batch + kSortSeg - 1) / kSortSeg;
     const size_t blocks = (size_t)stream_blocks(s.batch);
-    const size_t cells = (size_t)s.G * s.G;
-    int32_t *block_start = chunk_cell + K * (S / kChunk);
-    int32_t *block_size = block_start + K * (blocks + 1);
-    int32_t *seg_count = block_size + K * blocks;
-    int32_t *cell_start = seg_count + K * nseg * cells;
-    int32_t *cell_rep = cell_start + K * blocks * cells;
     const dim3 seg_grid((unsigned)nseg, (unsigned)K);
-    sort_count_kernel<<<seg_grid, kSortSegThreads, 0, stream>>>(rec_node, seg_count, cell_rep, s.batch, s.G);
+    sort_count_kernel<<<seg_grid, kSortSegThreads, 0, stream>>>(rec_node, b.seg_count, b.cell_rep, s.batch, s.G);
     const dim3 block_grid((unsigned)K, (unsigned)blocks);
-    sort_block_size_kernel<<<block_grid, kSortSegThreads, 0, stream>>>(seg_count, block_size, s.batch, s.G, (int)nseg);
-    sort_layout_kernel<<<block_grid, kSortThreads, 0, stream>>>(seg_count, cell_start, cell_rep, sorted_w, sorted_n,
-                                                              chunk_cell, block_start, block_size, s.batch, s.G,
+    sort_block_size_kernel<<<block_grid, kSortSegThreads, 0, stream>>>(b.seg_count, b.block_size, s.batch, s.G,
+                                                                       (int)nseg);
+    sort_layout_kernel<<<block_grid, kSortThreads, 0, stream>>>(b.seg_count, b.cell_start, b.cell_rep, b.rec,
+                                                              b.chunk_cell, b.block_start, b.block_size, s.batch, s.G,
                                                               (int)nseg);
     const size_t scatter_lds = scatter_lds_bytes(s.G);
     if (scatter_lds > 64 * 1024) {
-        static bool attr_set = false;
-        if (!attr_set) {
+        static std::once_flag once;
+        std::call_once(once, [] {
             (void)hipFuncSetAttribute(reinterpret_cast<const void *>(sort_scatter_kernel),
                                       hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024 - 64);
-            attr_set = true;
-        }
+        });
     }
-    sort_scatter_kernel<<<seg_grid, kSortSegThreads, scatter_lds, stream>>>(rec_node, rec_u, rec_v, seg_count,
-                                                                           cell_start, sorted_w, sorted_n, s.batch,
+    sort_scatter_kernel<<<seg_grid, kSortSegThreads, scatter_lds, stream>>>(rec_node, rec_u, rec_v, b.seg_count,
+                                                                           b.cell_start, b.rec, b.rec_pos, s.batch,
                                                                            s.G);
+    SortedStream st;
+    st.rec = b.rec;
+    st.chunk_cell = b.chunk_cell;
+    st.block_start = b.block_start;
+    st.rec_pos = b.rec_pos;
+    st.S = (int64_t)stream_stride(s.batch, s.G);
+    st.n_blocks = (int)blocks;
+    return st;
+}
+
+void launch_backward_coef_sorted(const LayerShape &s, const SortedStream &st, const float *gy, float *gcoef,
+                                 bool accumulate, hipStream_t stream)
+{
     CoefGradArgs a;
-    a.sorted_w = sorted_w;
-    a.sorted_n = sorted_n;
-    a.chunk_cell = chunk_cell;
-    a.block_start = block_start;
+    a.rec = st.rec;
+    a.chunk_cell = st.chunk_cell;
+    a.block_start = st.block_start;
     a.gy = gy;
     a.gP = gcoef;
     LayerShape g = s;
     g.layout = LMKAN_LAYOUT_PAPER;
     a.gmap = coef_map(g);
     a.B = s.batch;
-    a.S = (int64_t)S;
+    a.S = st.S;
     a.n_out = s.n_out;
     a.K = s.pairs();
     a.G = s.G;
     a.accumulate = accumulate ? 1 : 0;
     const unsigned lds = (unsigned)(2 * (s.G + 1) * kTile * sizeof(float));
-    // Runs per (pair, tile, block).  One block: cut the stream when pairs x tiles cannot fill
-    // 256 CUs x 16 waves.  Several blocks: as many runs as it takes for the pairs of one (tile,
-    // block) to occupy an XCD (512 waves), so that the XCD works on one block at a time.  A run
-    // keeps at least four trips.
+    int n_sub;
+    stream_run_split(s, st, &n_sub);
+    a.n_blocks = st.n_blocks;
+    a.n_sub = n_sub;
+    if ((st.n_blocks > 1 || n_sub > 1) && !accumulate)
+        launch_fill_zero(gcoef, (size_t)s.nodes() * (size_t)s.pairs() * (size_t)s.n_out, stream);
+    const unsigned grid = (unsigned)((int64_t)s.pairs() * s.out_tiles() * st.n_blocks * n_sub);
+    KernelTiming timing(stream, kTimeGradCoef);
+    if (gy_offsets_fit_32_bits(s))
+        backward_coef_stream_kernel<true><<<grid, 64, lds, stream>>>(a);
+    else
+        backward_coef_stream_kernel<false><<<grid, 64, lds, stream>>>(a);
+}
+
+// Runs per (pair, tile, block).  One block: cut the stream when pairs x tiles cannot fill
+// 256 CUs x 16 waves.  Several blocks: as many runs as it takes for the pairs of one (tile,
+// block) to occupy an XCD (512 waves), so that the XCD works on one block at a time.  A run
+// keeps at least four trips.
+void stream_run_split(const LayerShape &s, const SortedStream &st, int *n_sub_out)
+{
     const int64_t streams = (int64_t)s.pairs() * s.out_tiles();
-    const int n_blocks = (int)blocks;
     int n_sub = 1;
-    if (n_blocks == 1) {
-        const int64_t trips = (int64_t)S / (kChunk * kUnroll);
+    if (st.n_blocks == 1) {
+        const int64_t trips = st.S / (kChunk * kUnroll);
         while (streams * n_sub < 4096 && trips / (n_sub * 2) >= 4 && n_sub < 64) n_sub *= 2;
     } else {
         const int64_t trips = kBlockSamples / (kChunk * kUnroll);
         while ((int64_t)s.pairs() * n_sub < 512 && trips / (n_sub * 2) >= 4 && n_sub < 32) n_sub *= 2;
     }
-    a.n_blocks = n_blocks;
-    a.n_sub = n_sub;
-    if ((n_blocks > 1 || n_sub > 1) && !accumulate)
-        launch_fill_zero(gcoef, (size_t)s.nodes() * (size_t)s.pairs() * (size_t)s.n_out, stream);
-    const unsigned grid = (unsigned)(streams * n_blocks * n_sub);
-    // 24-bit multiply and 32-bit byte offsets into gy when the tensor is small enough
-    const bool offset32 = s.batch < (1 << 24) && (int64_t)s.n_out * 4 < (1 << 24) &&
-                          (int64_t)s.batch * s.n_out * 4 < ((int64_t)1 << 32);
-    KernelTiming timing(stream, kTimeGradCoef);
-    if (offset32)
-        backward_coef_stream_kernel<true><<<grid, 64, lds, stream>>>(a);
-    else
-        backward_coef_stream_kernel<false><<<grid, 64, lds, stream>>>(a);
+    *n_sub_out = n_sub;
+}
+
+// 24-bit multiply and 32-bit byte offsets into gy when the tensor is small enough
+bool gy_offsets_fit_32_bits(const LayerShape &s)
+{
+    return s.batch < (1 << 24) && (int64_t)s.n_out * 4 < (1 << 24) &&
+           (int64_t)s.batch * s.n_out * 4 < ((int64_t)1 << 32);
 }
 
 }  // namespace lmkan

@@ -42,6 +42,7 @@ void launch_fill_zero(float *p, size_t n, hipStream_t stream);
 size_t records_bytes(const LayerShape &s);
 size_t slab_forward_lds_bytes(const LayerShape &s);
 bool slab_forward_shape_ok(const LayerShape &s);
+bool slab_tile_is_wide(const LayerShape &s);  // 64-output tiles (G <= 16) rather than 16-output ones
 bool slab_forward_applicable(const LayerShape &s, const void *coef, const float *y);
 void launch_preamble_records(const LayerShape &s, const GridTab &tab, const float *x, void *records,
                              hipStream_t stream, const ConvGeom *conv = nullptr);
@@ -101,9 +102,10 @@ void launch_input_gradient_out(const float *in_t, float *gx, const LayerShape &s
 // multiple of 4 and 16-byte aligned gy and gcoef (coef_sorted_applicable); other shapes take the
 // generic kernel with atomics on a zeroed gradient.
 size_t sorted_records_bytes(const LayerShape &s);
+bool sorted_shape_ok(const LayerShape &s);
 bool coef_sorted_applicable(const LayerShape &s, const float *gy, const float *gcoef);
-void launch_backward_coef_sorted(const LayerShape &s, const void *records, void *sorted, const float *gy,
-                                 float *gcoef, bool accumulate, hipStream_t stream);
+// per-tile partial sums of the input gradient from the sorted stream (lmkan_backward_fused.hip)
+size_t fused_partial_bytes(const LayerShape &s);
 
 // In-place inference folds of a float32 table (lmkan_fold.hip); absent terms are null pointers.
 void launch_fold(const LayerShape &s, const GridTab &tab, float *coef, float gamma, const float *lin_w,

@@ -1061,6 +1061,7 @@ static bool slab_narrow_ok(const LayerShape &s)
 }
 
 bool slab_forward_shape_ok(const LayerShape &s) { return slab_wide_ok(s) || slab_narrow_ok(s); }
+bool slab_tile_is_wide(const LayerShape &s) { return slab_wide_ok(s); }
 
 // Samples per forward workgroup: 1024 with 64-output tiles, 4096 with 16-output tiles.
 int slab_forward_split(const LayerShape &s)

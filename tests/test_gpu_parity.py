@@ -77,6 +77,13 @@ SHAPES = [
     (300, 6, 12, 17),
     (300, 6, 12, 35),
     (12289, 4, 12, 6),
+    # both gradients from one walk over the cell-sorted samples: grids too fine for any slab
+    # (ragged output tile, more than one trip per cell, a batch long enough to be sorted block by
+    # block), and the 16-output slab range with enough samples per cell
+    (2100, 10, 132, 40),
+    (600, 4, 64, 64),
+    (13000, 6, 68, 36),
+    (7000, 12, 72, 20),
 ]
 
 
@@ -151,7 +158,9 @@ def test_backward_matches_oracle(dev, oracle, shape, storage, layout):
 # kernel (n_out not a multiple of 4), the cell-sorted stream written row by row, the same
 # stream cut into runs that meet through atomics (long batch, few pairs), the LDS-privatised
 # kernel of narrow layers
-@pytest.mark.parametrize("shape", [(90, 12, 70, 8), (90, 12, 72, 8), (2100, 12, 72, 8), (90, 12, 3, 8)])
+# and the walk that forms both gradients at once (a grid too fine for the slab kernels)
+@pytest.mark.parametrize("shape", [(90, 12, 70, 8), (90, 12, 72, 8), (2100, 12, 72, 8), (90, 12, 3, 8),
+                                   (2100, 10, 132, 40)])
 def test_backward_pieces_and_accumulate_flag(dev, oracle, shape):
     B, n_in, n_out, G = shape
     x, P, gy = _inputs(B, n_in, n_out, G, 41, dev)
@@ -173,11 +182,39 @@ def test_backward_pieces_and_accumulate_flag(dev, oracle, shape):
     pkg.lmkan_backward(dacc, x, P, gy, need_grad_x=False, grad_coef=acc)
     torch.cuda.synchronize()
     assert np.abs(acc.cpu().numpy() - (want + 0.5)).max() <= 2e-5 * max(1.0, np.abs(want).max())
+    # the same with both gradients in one call
+    acc = torch.full_like(gP, 0.5)
+    gx_acc, _ = pkg.lmkan_backward(dacc, x, P, gy, grad_coef=acc)
+    torch.cuda.synchronize()
+    assert np.abs(acc.cpu().numpy() - (want + 0.5)).max() <= 2e-5 * max(1.0, np.abs(want).max())
+    assert rowwise_rel_err(gx_acc.cpu().numpy(), gx.cpu().numpy().astype(np.float64)) <= 1e-6
     # overwrite really overwrites stale contents
     stale = torch.full_like(gP, 123.0)
     pkg.lmkan_backward(desc, x, P, gy, need_grad_x=False, grad_coef=stale)
     torch.cuda.synchronize()
     assert np.abs(stale.cpu().numpy() - want).max() <= TOL_F32 * np.abs(want).max()
+
+
+def test_sorted_paths_repeat_bit_for_bit(dev):
+    """What the header promises about run-to-run variation: the counting sort leaves the samples of
+    a cell in the order of their indices, so a coefficient gradient that one wave writes row by
+    row (stream not cut into runs) is the same float32 sum in every run, and so is the input
+    gradient of the walk over the sorted samples (its tiles are added in a fixed order).  Paths
+    that meet through float32 atomics are only held to the tolerance (other tests)."""
+    # a short stream: one run per (pair, tile)
+    B, n_in, n_out, G = 30, 12, 72, 4
+    x, P, gy = _inputs(B, n_in, n_out, G, 51, dev)
+    desc = _desc(n_in, n_out, G)
+    runs = [pkg.lmkan_backward(desc, x, None, gy, need_grad_x=False)[1] for _ in range(3)]
+    torch.cuda.synchronize()
+    assert torch.equal(runs[0], runs[1]) and torch.equal(runs[0], runs[2])
+    # both gradients from the sorted walk: grad_x repeats exactly
+    B, n_in, n_out, G = 2100, 10, 132, 40
+    x, P, gy = _inputs(B, n_in, n_out, G, 52, dev)
+    desc = _desc(n_in, n_out, G)
+    gxs = [pkg.lmkan_backward(desc, x, P, gy)[0] for _ in range(3)]
+    torch.cuda.synchronize()
+    assert torch.equal(gxs[0], gxs[1]) and torch.equal(gxs[0], gxs[2])
 
 
 def test_empty_batch(dev):
