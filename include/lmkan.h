@@ -20,9 +20,9 @@
  *     written when a status other than LMKAN_OK or LMKAN_ERR_HIP comes back.
  *   - batch == 0 is legal: nothing is read, and only lmkan_backward writes
  *     (an overwritten grad_coef becomes all zeros).
- *   - Alignment: x_dev and grad_x_dev 8 bytes (a pair of float32 is read at
- *     once), every other tensor its element size.  Faster kernels are chosen
- *     at run time when pointers and widths allow 16-byte accesses.
+ *   - Alignment: every tensor its element size.  Faster kernels are chosen at
+ *     run time when pointers and widths allow wider accesses (8 bytes for x_dev
+ *     and grad_x_dev, 16 bytes for the other tensors).
  *   - Non-finite inputs are memory-safe: cell indices are always clamped to
  *     [0, G-1]; the affected outputs are whatever IEEE arithmetic gives.
  */

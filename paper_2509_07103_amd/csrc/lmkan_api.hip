@@ -4,6 +4,8 @@
 #include <string.h>
 
 #include <mutex>
+#include <set>
+#include <utility>
 
 #include "lmkan.h"
 #include "lmkan_kernels.h"
@@ -89,6 +91,10 @@ LayerShape shape_of(const lmkan_desc *d, int64_t batch)
     return s;
 }
 
+// Errors other code left behind on this host thread are not this call's: entry points that
+// launch drop them first and report what their own launches produced.
+void drop_stale_error() { (void)hipGetLastError(); }
+
 lmkan_status launch_status()
 {
     return hipGetLastError() == hipSuccess ? LMKAN_OK : LMKAN_ERR_HIP;
@@ -110,6 +116,19 @@ struct TimedCall {
 };
 
 }  // namespace
+
+namespace lmkan {
+void allow_large_lds(const void *kernel, int bytes)
+{
+    static std::mutex mutex;
+    static std::set<std::pair<int, const void *>> done;
+    int dev = 0;
+    (void)hipGetDevice(&dev);
+    std::lock_guard<std::mutex> lock(mutex);
+    if (done.insert(std::make_pair(dev, kernel)).second)
+        (void)hipFuncSetAttribute(kernel, hipFuncAttributeMaxDynamicSharedMemorySize, bytes);
+}
+}  // namespace lmkan
 
 KernelTiming::KernelTiming(hipStream_t s, TimedKernel kind) : stream(s), on(g_timing.armed && g_timing.target == (int)kind)
 {
@@ -187,6 +206,7 @@ lmkan_status lmkan_pack(const lmkan_desc *desc, const void *coef_paper_dev, void
     if (!coef_paper_dev || !coef_packed_dev) return LMKAN_ERR_NULL;
     const size_t es = dtype_size(desc->coef_dtype);
     if (!aligned(coef_paper_dev, es) || !aligned(coef_packed_dev, es)) return LMKAN_ERR_ALIGN;
+    drop_stale_error();
     launch_pack(shape_of(desc, 0), coef_paper_dev, coef_packed_dev, static_cast<hipStream_t>(stream));
     return launch_status();
 }
@@ -199,7 +219,8 @@ lmkan_status lmkan_locate(const lmkan_desc *desc, int64_t batch, const float *x_
     if (batch < 0 || batch > LMKAN_MAX_BATCH) return LMKAN_ERR_SHAPE;
     if (batch == 0) return LMKAN_OK;
     if (!x_dev || !cell_dev) return LMKAN_ERR_NULL;
-    if (!aligned(x_dev, 8) || !aligned(cell_dev, 4)) return LMKAN_ERR_ALIGN;
+    if (!aligned(x_dev, 4) || !aligned(cell_dev, 4)) return LMKAN_ERR_ALIGN;
+    drop_stale_error();
     GridTab tab;
     build_grid(desc->grid, &tab);
     launch_locate(shape_of(desc, batch), tab, x_dev, cell_dev, static_cast<hipStream_t>(stream));
@@ -209,6 +230,16 @@ lmkan_status lmkan_locate(const lmkan_desc *desc, int64_t batch, const float *x_
 }  // extern "C"
 
 namespace {
+
+// A plain layer on rows seen as a 1 x 1 convolution on a batch x 1 x 1 image: the window map of
+// the kernels then reads and writes x element by element, which is what buffers that are only
+// 4-byte aligned need (the row kernels move a pair of inputs, 8 bytes, at once).
+ConvGeom rows_as_windows(const LayerShape &s)
+{
+    ConvGeom g;
+    g.N = (int)s.batch, g.H = 1, g.W = 1, g.C = s.n_in, g.kh = 1, g.kw = 1, g.stride = 1, g.OH = 1, g.OW = 1;
+    return g;
+}
 
 // conv == nullptr: rows x[batch][n_in]; otherwise the rows are the windows of an image
 lmkan_status forward_impl(const lmkan_desc *desc, int64_t batch, const float *x_dev, const void *coef_dev,
@@ -220,8 +251,13 @@ lmkan_status forward_impl(const lmkan_desc *desc, int64_t batch, const float *x_
     if (batch < 0 || batch > LMKAN_MAX_BATCH) return LMKAN_ERR_SHAPE;
     if (batch == 0) return LMKAN_OK;
     if (!x_dev || !coef_dev || !y_dev) return LMKAN_ERR_NULL;
-    if (!aligned(x_dev, conv ? 4 : 8) || !aligned(y_dev, 4) || !aligned(coef_dev, dtype_size(desc->coef_dtype)))
+    if (!aligned(x_dev, 4) || !aligned(y_dev, 4) || !aligned(coef_dev, dtype_size(desc->coef_dtype)))
         return LMKAN_ERR_ALIGN;
+    ConvGeom plain;
+    if (!conv && !aligned(x_dev, 8)) {
+        plain = rows_as_windows(shape_of(desc, batch));
+        conv = &plain;
+    }
     const size_t need = lmkan_workspace_bytes(desc, batch, 0);
     if (need > 0 && (!workspace_dev || workspace_bytes < need)) return LMKAN_ERR_WORKSPACE;
     if (need > 0 && !aligned(workspace_dev, 256)) return LMKAN_ERR_ALIGN;
@@ -229,6 +265,7 @@ lmkan_status forward_impl(const lmkan_desc *desc, int64_t batch, const float *x_
     build_grid(desc->grid, &tab);
     const LayerShape s = shape_of(desc, batch);
     hipStream_t hs = static_cast<hipStream_t>(stream);
+    drop_stale_error();
     TimedCall timed(kTimeForward);
     if (small_out_shape_ok(s)) {
         launch_preamble_records(s, tab, x_dev, workspace_dev, hs, conv);
@@ -256,7 +293,13 @@ lmkan_status backward_impl(const lmkan_desc *desc, int64_t batch, const float *x
     const LayerShape s = shape_of(desc, batch);
     hipStream_t hs = static_cast<hipStream_t>(stream);
     const bool overwrite = !(desc->flags & LMKAN_FLAG_ACCUMULATE_GRAD_COEF);
+    ConvGeom plain;
+    if (!conv && batch > 0 && (!aligned(x_dev, 8) || (grad_x_dev && !aligned(grad_x_dev, 8)))) {
+        plain = rows_as_windows(s);
+        conv = &plain;
+    }
     const size_t image_elems = conv ? (size_t)conv->N * conv->H * conv->W * conv->C : 0;
+    drop_stale_error();
     if (batch == 0) {
         // an empty batch still defines the coefficient gradient: all zeros; an image too small for
         // one window still defines its gradient: all zeros
@@ -269,7 +312,7 @@ lmkan_status backward_impl(const lmkan_desc *desc, int64_t batch, const float *x
     }
     if (!x_dev || !grad_y_dev) return LMKAN_ERR_NULL;
     if (grad_x_dev && !coef_dev) return LMKAN_ERR_NULL;
-    if (!aligned(x_dev, conv ? 4 : 8) || !aligned(grad_y_dev, 4) || (grad_x_dev && !aligned(grad_x_dev, conv ? 4 : 8)) ||
+    if (!aligned(x_dev, 4) || !aligned(grad_y_dev, 4) || (grad_x_dev && !aligned(grad_x_dev, 4)) ||
         (grad_coef_dev && !aligned(grad_coef_dev, 4)) ||
         (coef_dev && !aligned(coef_dev, dtype_size(desc->coef_dtype))))
         return LMKAN_ERR_ALIGN;
@@ -472,6 +515,7 @@ lmkan_status lmkan_hessian_reg(const lmkan_desc *desc, const void *coef_dev, flo
     if (!aligned(coef_dev, dtype_size(desc->coef_dtype)) || (value_dev && !aligned(value_dev, 8)) ||
         (grad_coef_dev && !aligned(grad_coef_dev, 4)))
         return LMKAN_ERR_ALIGN;
+    drop_stale_error();
     GridTab tab;
     build_grid(desc->grid, &tab);
     launch_hessian_reg(shape_of(desc, 0), tab, coef_dev, scale, value_dev, grad_coef_dev,
@@ -490,6 +534,7 @@ lmkan_status lmkan_fold(const lmkan_desc *desc, void *coef_dev, float gamma, con
     if (!aligned(coef_dev, 4) || !aligned(lin_w_dev, 4) || !aligned(lin_b_dev, 4) || !aligned(out_scale_dev, 4) ||
         !aligned(out_shift_dev, 4))
         return LMKAN_ERR_ALIGN;
+    drop_stale_error();
     GridTab tab;
     build_grid(desc->grid, &tab);
     launch_fold(shape_of(desc, 0), tab, static_cast<float *>(coef_dev), gamma, lin_w_dev, lin_b_dev, out_scale_dev,

@@ -18,8 +18,6 @@
 // two-row window of the table kept in LDS; a table row is written to global memory exactly
 // once, when the walk has passed it.  Rows no sample touches are written as exact zeros, so
 // no separate zero fill is needed.
-#include <mutex>
-
 #include "lmkan_kernels.h"
 #include "lmkan_sorted.h"
 
@@ -39,7 +37,6 @@ static_assert(kUnroll % kDepth == 0, "the gy ring must divide the unrolled trip"
 // pass.  Per pair k, with S = stream_stride, the samples ordered by (block, cell):
 //   rec [K][S]           (u, v, 1, index) of a sample, 16 bytes; padding entries are
 //                        (0, 0, 0, index of a sample of the same cell)
-//   rec_pos [K][B]       where sample n went
 //   chunk_cell [K][S/4]  i1 << 8 | i2 of the cell each chunk belongs to, non-decreasing
 //                        inside a block
 //   block_start [K][blocks+1]  first chunk of every block (multiples of kUnroll) and the
@@ -240,7 +237,7 @@ __global__ __launch_bounds__(kSortThreads) void sort_layout_kernel(int32_t *__re
 // lie in this segment form one contiguous run of the stream).
 __host__ __device__ inline size_t scatter_lds_bytes(int G)
 {
-    return (size_t)G * G * 3 * sizeof(int) + (size_t)kSortSeg * (2 * sizeof(float) + 3 * sizeof(unsigned short));
+    return (size_t)((G * G * 3 + 3) & ~3) * sizeof(int) + (size_t)kSortSeg * (2 * sizeof(float) + 3 * sizeof(unsigned short));
 }
 
 __global__ __launch_bounds__(kSortSegThreads) void sort_scatter_kernel(const int32_t *__restrict__ rec_node,
@@ -248,17 +245,17 @@ __global__ __launch_bounds__(kSortSegThreads) void sort_scatter_kernel(const int
                                                                       const float *__restrict__ rec_v,
                                                                       const int32_t *__restrict__ seg_count,
                                                                       const int32_t *__restrict__ cell_start,
-                                                                      f4v *__restrict__ rec,
-                                                                      int32_t *__restrict__ rec_pos, int64_t B, int G)
+                                                                      f4v *__restrict__ rec, int64_t B, int G,
+                                                                      int stable)
 {
-    extern __shared__ int s_dyn[];
+    extern __shared__ __align__(16) int s_dyn[];
     __shared__ int s_wave[kSortSegThreads / 64];
     const int seg = blockIdx.x, nseg = gridDim.x, k = blockIdx.y;
     const int cells = G * G;
     int *s_cnt = s_dyn;              // population of the cell inside this segment
     int *s_lstart = s_cnt + cells;   // its first position in the segment's own cell order
     int *s_gbase = s_lstart + cells; // its first position in the stream
-    float *s_u = reinterpret_cast<float *>(s_gbase + cells);
+    float *s_u = reinterpret_cast<float *>(s_dyn + ((3 * cells + 3) & ~3));  // 16-byte aligned: s_order is read 16 bytes at a time
     float *s_v = s_u + kSortSeg;
     unsigned short *s_cell = reinterpret_cast<unsigned short *>(s_v + kSortSeg);
     unsigned short *s_rank = s_cell + kSortSeg;
@@ -329,29 +326,38 @@ __global__ __launch_bounds__(kSortSegThreads) void sort_scatter_kernel(const int
     __syncthreads();
     for (int i = threadIdx.x; i < count; i += blockDim.x) s_order[s_lstart[s_cell[i]] + s_rank[i]] = (unsigned short)i;
     __syncthreads();
-    // The ranks so far are in the order the atomics happened to be served.  Replace them by the
-    // order of the sample indices (rank = number of samples of the same cell, in this segment,
-    // with a smaller index), so that the stream, and with it the order of every float32 sum
-    // over the samples of a cell, is the same in every run.
-    for (int i = threadIdx.x; i < count; i += blockDim.x) {
+    // The ranks so far are in the order the atomics happened to be served.  Where the order of
+    // the samples inside a cell reaches the result (a coefficient gradient summed cell by cell by
+    // one wave), replace them by the order of the sample indices (rank = number of samples of the
+    // same cell, in this segment, with a smaller index), so that the stream, and with it the
+    // order of every float32 sum over the samples of a cell, is the same in every run.
+    for (int i = threadIdx.x; stable && i < count; i += blockDim.x) {
         const int c = s_cell[i];
-        const unsigned short *run = s_order + s_lstart[c];
-        const int len = s_cnt[c];
+        // the run is read eight entries (16 bytes) at a time from an aligned position; entries
+        // outside the run are masked
+        const int first = s_lstart[c], end = first + s_cnt[c];
         int r = 0;
-        for (int t = 0; t < len; ++t) r += run[t] < i;
+        for (int a = first & ~7; a < end; a += 8) {
+            const uint4 w = *reinterpret_cast<const uint4 *>(s_order + a);
+            const unsigned word[4] = {w.x, w.y, w.z, w.w};
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+                const int v = (int)((word[e >> 1] >> (16 * (e & 1))) & 0xffffu);
+                r += (a + e >= first) & (a + e < end) & (v < i);
+            }
+        }
         s_rank[i] = (unsigned short)r;
     }
     __syncthreads();
-    for (int i = threadIdx.x; i < count; i += blockDim.x) s_order[s_lstart[s_cell[i]] + s_rank[i]] = (unsigned short)i;
+    for (int i = threadIdx.x; stable && i < count; i += blockDim.x)
+        s_order[s_lstart[s_cell[i]] + s_rank[i]] = (unsigned short)i;
     __syncthreads();
     f4v *out = rec + (int64_t)k * S;
-    int32_t *out_pos = rec_pos + (int64_t)k * B + n0;
     for (int lp = threadIdx.x; lp < count; lp += blockDim.x) {
         const int i = s_order[lp];
         const int c = s_cell[i];
         const int pos = s_gbase[c] + lp - s_lstart[c];
         out[pos] = f4v{s_u[i], s_v[i], 1.0f, __int_as_float((int32_t)(n0 + i))};
-        out_pos[i] = pos;
     }
 }
 
@@ -564,7 +570,7 @@ size_t sorted_records_bytes(const LayerShape &s)
     const size_t blocks = (size_t)stream_blocks(s.batch);
     const size_t cells = (size_t)s.G * s.G;
     const size_t per_pair = S * sizeof(f4v) + (S / kChunk) * sizeof(int32_t) + (2 * blocks + 1) * sizeof(int32_t) +
-                            (nseg + blocks + 1) * cells * sizeof(int32_t) + (size_t)s.batch * sizeof(int32_t);
+                            (nseg + blocks + 1) * cells * sizeof(int32_t);
     return ((size_t)s.pairs() * per_pair + 255) & ~(size_t)255;
 }
 
@@ -599,12 +605,13 @@ SortBuffers sort_buffers(const LayerShape &s, void *sorted)
     b.seg_count = b.block_size + K * blocks;
     b.cell_start = b.seg_count + K * nseg * cells;
     b.cell_rep = b.cell_start + K * blocks * cells;
-    b.rec_pos = b.cell_rep + K * cells;
     return b;
 }
 
 SortedStream launch_sort(const LayerShape &s, const void *records, void *sorted, hipStream_t stream)
 {
+    // a fixed order inside the cells matters only where one wave sums a cell from start to end
+    const bool stable = stream_blocks(s.batch) == 1 && stream_run_split(s) == 1;
     const size_t n = (size_t)s.pairs() * (size_t)s.batch;
     const size_t K = (size_t)s.pairs();
     const int32_t *rec_node = static_cast<const int32_t *>(records);
@@ -622,21 +629,14 @@ SortedStream launch_sort(const LayerShape &s, const void *records, void *sorted,
                                                               b.chunk_cell, b.block_start, b.block_size, s.batch, s.G,
                                                               (int)nseg);
     const size_t scatter_lds = scatter_lds_bytes(s.G);
-    if (scatter_lds > 64 * 1024) {
-        static std::once_flag once;
-        std::call_once(once, [] {
-            (void)hipFuncSetAttribute(reinterpret_cast<const void *>(sort_scatter_kernel),
-                                      hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024 - 64);
-        });
-    }
+    if (scatter_lds > 64 * 1024) allow_large_lds(reinterpret_cast<const void *>(sort_scatter_kernel), 160 * 1024 - 64);
     sort_scatter_kernel<<<seg_grid, kSortSegThreads, scatter_lds, stream>>>(rec_node, rec_u, rec_v, b.seg_count,
-                                                                           b.cell_start, b.rec, b.rec_pos, s.batch,
-                                                                           s.G);
+                                                                           b.cell_start, b.rec, s.batch,
+                                                                           s.G, stable ? 1 : 0);
     SortedStream st;
     st.rec = b.rec;
     st.chunk_cell = b.chunk_cell;
     st.block_start = b.block_start;
-    st.rec_pos = b.rec_pos;
     st.S = (int64_t)stream_stride(s.batch, s.G);
     st.n_blocks = (int)blocks;
     return st;
@@ -661,8 +661,7 @@ void launch_backward_coef_sorted(const LayerShape &s, const SortedStream &st, co
     a.G = s.G;
     a.accumulate = accumulate ? 1 : 0;
     const unsigned lds = (unsigned)(2 * (s.G + 1) * kTile * sizeof(float));
-    int n_sub;
-    stream_run_split(s, st, &n_sub);
+    const int n_sub = stream_run_split(s);
     a.n_blocks = st.n_blocks;
     a.n_sub = n_sub;
     if ((st.n_blocks > 1 || n_sub > 1) && !accumulate)
@@ -679,18 +678,18 @@ void launch_backward_coef_sorted(const LayerShape &s, const SortedStream &st, co
 // 256 CUs x 16 waves.  Several blocks: as many runs as it takes for the pairs of one (tile,
 // block) to occupy an XCD (512 waves), so that the XCD works on one block at a time.  A run
 // keeps at least four trips.
-void stream_run_split(const LayerShape &s, const SortedStream &st, int *n_sub_out)
+int stream_run_split(const LayerShape &s)
 {
     const int64_t streams = (int64_t)s.pairs() * s.out_tiles();
     int n_sub = 1;
-    if (st.n_blocks == 1) {
-        const int64_t trips = st.S / (kChunk * kUnroll);
+    if (stream_blocks(s.batch) == 1) {
+        const int64_t trips = stream_stride(s.batch, s.G) / (kChunk * kUnroll);
         while (streams * n_sub < 4096 && trips / (n_sub * 2) >= 4 && n_sub < 64) n_sub *= 2;
     } else {
         const int64_t trips = kBlockSamples / (kChunk * kUnroll);
         while ((int64_t)s.pairs() * n_sub < 512 && trips / (n_sub * 2) >= 4 && n_sub < 32) n_sub *= 2;
     }
-    *n_sub_out = n_sub;
+    return n_sub;
 }
 
 // 24-bit multiply and 32-bit byte offsets into gy when the tensor is small enough

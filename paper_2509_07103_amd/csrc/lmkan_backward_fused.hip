@@ -509,8 +509,7 @@ void launch_backward_fused(const LayerShape &s, const GridTab &tab, const Sorted
     a.G = s.G;
     a.accumulate = accumulate ? 1 : 0;
     a.col_limit = s.layout == LMKAN_LAYOUT_PACKED ? s.out_tiles() * kTile : s.n_out;
-    int n_sub;
-    stream_run_split(s, st, &n_sub);
+    const int n_sub = stream_run_split(s);
     a.n_blocks = st.n_blocks;
     a.n_sub = n_sub;
     if (gcoef && (st.n_blocks > 1 || n_sub > 1) && !accumulate)

@@ -203,6 +203,7 @@ __global__ __launch_bounds__(kThreads) void backward_generic_kernel(
 // ---------------------------------------------------------------------------
 // Cell lookup alone, packing, zero fill
 // ---------------------------------------------------------------------------
+template <bool PAIRED>  // PAIRED: x is 8-byte aligned, the two inputs of a pair are read at once
 __global__ __launch_bounds__(kThreads) void locate_kernel(GridTab tab, const float *__restrict__ x,
                                                          int32_t *__restrict__ cell, int64_t total,
                                                          int K)
@@ -212,7 +213,11 @@ __global__ __launch_bounds__(kThreads) void locate_kernel(GridTab tab, const flo
     stage_grid(tab, s_node, s_invh);
     const int64_t stride = (int64_t)gridDim.x * blockDim.x;
     for (int64_t r = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; r < total; r += stride) {
-        const float2 xv = reinterpret_cast<const float2 *>(x)[r];  // x[n][2k], x[n][2k+1]
+        float2 xv;  // x[n][2k], x[n][2k+1]
+        if constexpr (PAIRED)
+            xv = reinterpret_cast<const float2 *>(x)[r];
+        else
+            xv = make_float2(x[2 * r], x[2 * r + 1]);
         cell[r] = locate(s_node, tab.G, xv.x) * tab.G + locate(s_node, tab.G, xv.y);
     }
     (void)K;
@@ -345,8 +350,10 @@ void launch_locate(const LayerShape &s, const GridTab &tab, const float *x, int3
                    hipStream_t stream)
 {
     const int64_t total = s.batch * s.pairs();
-    locate_kernel<<<blocks_for(total, kThreads, 65536), kThreads, 0, stream>>>(tab, x, cell, total,
-                                                                              s.pairs());
+    if ((reinterpret_cast<uintptr_t>(x) & 7) == 0)
+        locate_kernel<true><<<blocks_for(total, kThreads, 65536), kThreads, 0, stream>>>(tab, x, cell, total, s.pairs());
+    else
+        locate_kernel<false><<<blocks_for(total, kThreads, 65536), kThreads, 0, stream>>>(tab, x, cell, total, s.pairs());
 }
 
 void launch_pack(const LayerShape &s, const void *src, void *dst, hipStream_t stream)

@@ -226,14 +226,7 @@ void launch_hessian_reg(const LayerShape &s, const GridTab &tab, const void *coe
     const int which = s.G == 8 ? 1 : s.G == 12 ? 2 : s.G == 16 ? 3 : s.G == 32 ? 4 : 0;
     const Kernel kernel = table[which][s.dtype];
     const size_t lds = (size_t)((which ? 3 : 4) + kGradRows) * (s.G + 1) * kThreads * sizeof(float);
-    if (lds > 48 * 1024) {
-        static bool attr_set[5][3] = {};
-        if (!attr_set[which][s.dtype]) {
-            (void)hipFuncSetAttribute(reinterpret_cast<const void *>(kernel),
-                                      hipFuncAttributeMaxDynamicSharedMemorySize, 150 * 1024);
-            attr_set[which][s.dtype] = true;
-        }
-    }
+    if (lds > 48 * 1024) allow_large_lds(reinterpret_cast<const void *>(kernel), 150 * 1024);
     kernel<<<grid, kThreads, lds, stream>>>(a);
 }
 

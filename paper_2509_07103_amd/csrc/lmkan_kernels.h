@@ -23,6 +23,11 @@ struct LayerShape {
 
 CoefMap coef_map(const LayerShape &s);
 
+// Raises the dynamic LDS limit of a kernel on the current device, once per (device, kernel);
+// safe to call from several host threads.  The first call for a kernel on a device talks to
+// the runtime (hipFuncSetAttribute), so it must not happen inside a stream capture.
+void allow_large_lds(const void *kernel, int bytes);
+
 
 // Generic kernels: any shape, any dtype, both layouts; coefficient rows are read
 // straight from global memory.

@@ -1124,12 +1124,7 @@ static void launch_forward_slab_narrow(const LayerShape &s, const void *coef, fl
                                forward_slab_narrow_kernel<bf16_t, WAVES, SETS>};
     const Kernel kernel = kernels[s.dtype];
     const int waves = s.dtype == LMKAN_F32 ? 2 * WAVES : WAVES;
-    static bool attr_set[3] = {false, false, false};
-    if (!attr_set[s.dtype]) {
-        (void)hipFuncSetAttribute(reinterpret_cast<const void *>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize,
-                                  160 * 1024);
-        attr_set[s.dtype] = true;
-    }
+    allow_large_lds(reinterpret_cast<const void *>(kernel), 160 * 1024);
     const size_t n = (size_t)s.pairs() * (size_t)s.batch;
     SlabArgs a;
     a.P = coef;
@@ -1174,23 +1169,14 @@ void launch_forward_slab(const LayerShape &s, const void *coef, float *y, const 
     // 16-bit tables (their staging registers do not fit the smaller register share)
     constexpr int kTileB = 1024;
     typedef void (*Kernel)(SlabArgs);
-#ifndef LMKAN_FWD_AHEAD
-#define LMKAN_FWD_AHEAD 1
-#endif
     // G = 16 (the usual grid) gets a kernel with the row stride folded into the LDS offsets
-    const Kernel kernels[3] = {forward_slab_kernel<float, 16, 1, LMKAN_FWD_AHEAD, 0>,
+    const Kernel kernels[3] = {forward_slab_kernel<float, 16, 1, 1, 0>,
                                forward_slab_kernel<_Float16, 8, 2, 2, 0>, forward_slab_kernel<bf16_t, 8, 2, 2, 0>};
-    const Kernel kernels17[3] = {forward_slab_kernel<float, 16, 1, LMKAN_FWD_AHEAD, 17>,
+    const Kernel kernels17[3] = {forward_slab_kernel<float, 16, 1, 1, 17>,
                                  forward_slab_kernel<_Float16, 8, 2, 2, 17>, forward_slab_kernel<bf16_t, 8, 2, 2, 17>};
     const Kernel kernel = s.G == 16 ? kernels17[s.dtype] : kernels[s.dtype];
     const int waves = s.dtype == LMKAN_F32 ? 16 : 8;
-    static bool attr_set[6] = {false, false, false, false, false, false};
-    const int slot = s.dtype + (s.G == 16 ? 3 : 0);
-    if (!attr_set[slot]) {
-        (void)hipFuncSetAttribute(reinterpret_cast<const void *>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize,
-                                  160 * 1024);
-        attr_set[slot] = true;
-    }
+    allow_large_lds(reinterpret_cast<const void *>(kernel), 160 * 1024);
     const size_t n = (size_t)s.pairs() * (size_t)s.batch;
     SlabArgs a;
     a.P = coef;
@@ -1343,27 +1329,19 @@ void launch_backward_input_slab(const LayerShape &s, const GridTab &tab, const v
     typedef void (*Kernel)(GradInArgs);
     const bool narrow = !slab_wide_ok(s);
     constexpr int kNarrowSets = 8;
-#ifndef LMKAN_GX_WAVES
-#define LMKAN_GX_WAVES 16
-#define LMKAN_GX_AHEAD 1
-#endif
-    const Kernel kernels[9] = {backward_input_slab_kernel<float, LMKAN_GX_WAVES, 16 / LMKAN_GX_WAVES, LMKAN_GX_AHEAD, 0>,
+    constexpr int kWavesF32 = 16;  // float32 tables need no staging registers: 16 waves of 64 samples
+    const Kernel kernels[9] = {backward_input_slab_kernel<float, kWavesF32, 16 / kWavesF32, 1, 0>,
                                backward_input_slab_kernel<_Float16, WAVES, SETS, 2, 0>,
                                backward_input_slab_kernel<bf16_t, WAVES, SETS, 2, 0>,
                                backward_input_slab_narrow_kernel<float, 2 * WAVES, kNarrowSets / 2>,
                                backward_input_slab_narrow_kernel<_Float16, WAVES, kNarrowSets>,
                                backward_input_slab_narrow_kernel<bf16_t, WAVES, kNarrowSets>,
-                               backward_input_slab_kernel<float, LMKAN_GX_WAVES, 16 / LMKAN_GX_WAVES, LMKAN_GX_AHEAD, 17>,
+                               backward_input_slab_kernel<float, kWavesF32, 16 / kWavesF32, 1, 17>,
                                backward_input_slab_kernel<_Float16, WAVES, SETS, 2, 17>,
                                backward_input_slab_kernel<bf16_t, WAVES, SETS, 2, 17>};
     const int which = s.dtype + (narrow ? 3 : (s.G == 16 ? 6 : 0));
     const Kernel kernel = kernels[which];
-    static bool attr_set[9] = {false, false, false, false, false, false, false, false, false};
-    if (!attr_set[which]) {
-        (void)hipFuncSetAttribute(reinterpret_cast<const void *>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize,
-                                  160 * 1024);
-        attr_set[which] = true;
-    }
+    allow_large_lds(reinterpret_cast<const void *>(kernel), 160 * 1024);
     const size_t n = (size_t)s.pairs() * (size_t)s.batch;
     GradInArgs a;
     a.P = coef;
@@ -1394,7 +1372,7 @@ void launch_backward_input_slab(const LayerShape &s, const GridTab &tab, const v
     a.ld = scratch_row_stride(s.batch, layout);
     launch_fill_zero(a.gx, (size_t)a.ld * s.n_in, stream);
     const size_t slabs = narrow ? (size_t)2 * s.nodes() * kNarrowRowBytes : slab_forward_lds_bytes(s);
-    const int waves = s.dtype == LMKAN_F32 ? (narrow ? 2 * WAVES : LMKAN_GX_WAVES) : WAVES;
+    const int waves = s.dtype == LMKAN_F32 ? (narrow ? 2 * WAVES : kWavesF32) : WAVES;
     {
         KernelTiming timing(stream, kTimeGradInput);
         kernel<<<tiles * split, waves * 64, slabs + LMKAN_MAX_GRID * sizeof(float), stream>>>(a);

@@ -63,6 +63,9 @@ __device__ __forceinline__ float *forward_out_base(const SlabArgs &a, int ks, bo
 // (lds_base wave-uniform).  Written as inline assembly on purpose: the compiler does not
 // track it, so it cannot make every later LDS read wait for loads that fill the *other*
 // buffer; completion is awaited explicitly with s_waitcnt vmcnt(0) before the barrier.
+// m0 is overwritten without being listed as clobbered: it is a reserved register to this
+// compiler, which rejects it in a clobber list and never keeps a value in it across
+// statements (it sets m0 itself right before any instruction of its own that reads it).
 __device__ __forceinline__ void lds_dma16(const void *gptr, unsigned lds_base)
 {
     asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off"

@@ -351,12 +351,7 @@ void launch_forward_slab_f16(const LayerShape &s, const void *coef, float *y, co
                              hipStream_t stream)
 {
     constexpr int kTileB = kWaves * 64;
-    static bool attr_set = false;
-    if (!attr_set) {
-        (void)hipFuncSetAttribute(reinterpret_cast<const void *>(forward_slab_f16_kernel),
-                                  hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
-        attr_set = true;
-    }
+    allow_large_lds(reinterpret_cast<const void *>(forward_slab_f16_kernel), 160 * 1024);
     const size_t n = (size_t)s.pairs() * (size_t)s.batch;
     SlabArgs a;
     a.P = coef;
@@ -390,12 +385,7 @@ void launch_backward_input_slab_f16(const LayerShape &s, const GridTab &tab, con
                                     float *gx_scratch, const void *records, hipStream_t stream)
 {
     constexpr int kTileB = kWaves * 64;
-    static bool attr_set = false;
-    if (!attr_set) {
-        (void)hipFuncSetAttribute(reinterpret_cast<const void *>(backward_input_slab_f16_kernel),
-                                  hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
-        attr_set = true;
-    }
+    allow_large_lds(reinterpret_cast<const void *>(backward_input_slab_f16_kernel), 160 * 1024);
     const size_t n = (size_t)s.pairs() * (size_t)s.batch;
     GradInArgs a;
     a.P = coef;

@@ -53,7 +53,6 @@ struct SortedStream {
                                  //           non-decreasing inside a block
     const int32_t *block_start;  // [K][blocks + 1]  first chunk of every block (multiples of
                                  //           kUnroll) and the number of chunks to process
-    const int32_t *rec_pos;      // [K][B]    position of sample n in the stream of pair k
     int64_t S;                   // stream_stride
     int n_blocks;
 };
@@ -68,7 +67,6 @@ struct SortBuffers {
     int32_t *seg_count;
     int32_t *cell_start;
     int32_t *cell_rep;
-    int32_t *rec_pos;
 };
 SortBuffers sort_buffers(const LayerShape &s, void *sorted);
 // records = output of launch_preamble_records; fills the stream in `sorted`
@@ -77,7 +75,7 @@ SortedStream launch_sort(const LayerShape &s, const void *records, void *sorted,
 // whether the batch is short enough for the 32-bit stream positions and 16-bit grid coordinates
 bool sorted_batch_ok(const LayerShape &s);
 // waves per (pair, output tile, block) of the walking kernels
-void stream_run_split(const LayerShape &s, const SortedStream &st, int *n_sub);
+int stream_run_split(const LayerShape &s);
 bool gy_offsets_fit_32_bits(const LayerShape &s);
 // coefficient gradient alone (lmkan_backward.hip)
 void launch_backward_coef_sorted(const LayerShape &s, const SortedStream &st, const float *gy, float *gcoef,

@@ -362,8 +362,8 @@ def _shifted(t, elems=1):
 @pytest.mark.parametrize("storage", ["f32", "bf16"])
 def test_buffers_off_the_16_byte_grid_take_the_general_kernels(dev, oracle, storage):
     """The tuned kernels move 16 bytes per lane; buffers that are only element-aligned must still
-    give the same results (the dispatch falls back), and an x that is not 8-byte aligned is an
-    error, not a fault."""
+    give the same results (the dispatch falls back); that includes x and grad_x on a 4-byte
+    boundary, which are read and written element by element."""
     B, n_in, n_out, G = 600, 12, 72, 8
     x, P, gy = _inputs(B, n_in, n_out, G, 31, dev)
     desc = _desc(n_in, n_out, G, storage)
@@ -384,9 +384,27 @@ def test_buffers_off_the_16_byte_grid_take_the_general_kernels(dev, oracle, stor
     got = gP.cpu().numpy()
     for k in range(n_in // 2):
         assert pair_slice_rel_err(got[:, :, k, :], want[:, :, k, :]) <= TOL_F32
-    # x on a 4-byte boundary only: rejected on the host
-    xu = _shifted(x)
-    assert xu.data_ptr() % 8 == 4
-    with pytest.raises(pkg.LmkanError) as e:
-        pkg.lmkan_forward(desc, xu, Ps)
-    assert e.value.status == 5
+    # x and grad_x on a 4-byte boundary only, everything else aligned; then everything shifted
+    xu, gxu = _shifted(x), _shifted(torch.empty((B, n_in), device=dev))
+    assert xu.data_ptr() % 8 == 4 and gxu.data_ptr() % 8 == 4
+    want_y = oracle.forward(xh, bits(Ps), G, dtype=code)
+    want_gx = oracle.backward_input(xh, bits(Ps), gyh, G, dtype=code)
+    for Pq, gyq, yq, gPq in ((Ps, gy, torch.empty((B, n_out), device=dev), torch.empty(desc.coef_shape(), device=dev)),
+                             (Pu, gyu, y, gP)):
+        yq.fill_(float("nan"))
+        gxu.fill_(float("nan"))
+        pkg.lmkan_forward(desc, xu, Pq, y=yq)
+        pkg.lmkan_backward(desc, xu, Pq, gyq, grad_x=gxu, grad_coef=gPq)
+        torch.cuda.synchronize()
+        assert rowwise_rel_err(yq.cpu().numpy(), want_y) <= TOL_F32
+        assert rowwise_rel_err(gxu.cpu().numpy(), want_gx) <= TOL_F32
+        got = gPq.cpu().numpy()
+        for k in range(n_in // 2):
+            assert pair_slice_rel_err(got[:, :, k, :], want[:, :, k, :]) <= TOL_F32
+    assert np.array_equal(pkg.lmkan_locate(desc, xu).cpu().numpy(), oracle.locate_batch(xh, G))
+    # a pointer off its element size is an error, not a fault
+    L = pkg.lib()
+    import ctypes as C
+    d = desc.c()
+    assert L.lmkan_forward(C.byref(d), B, C.c_void_p(x.data_ptr() + 2), C.c_void_p(Ps.data_ptr()),
+                           C.c_void_p(y.data_ptr()), None, 0, None) == 5
