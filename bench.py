@@ -3,7 +3,10 @@
 
 A step is one forward + one backward (gradients w.r.t. inputs and coefficients) of the
 headline layer: 1024 -> 1024, G = 16, batch 8192, float32 coefficients, synthetic seeded
-inputs already resident in HBM.  Prints ONE JSON line.
+inputs already resident in HBM.  Prints ONE JSON line: the headline step, the kernel that
+dominates it against its roofline (with what this machine was measured to deliver on the
+primitive streams, and the HBM traffic of that kernel from the committed rocprofv3 counter
+summary), the other four configurations in short runs, and the CPU oracle on a row sample.
 """
 from __future__ import annotations
 
@@ -11,6 +14,7 @@ import argparse
 import ctypes as C
 import json
 import os
+import re
 import sys
 import time
 
@@ -20,16 +24,7 @@ if ROOT not in sys.path:
 
 PEAK_FP32_VECTOR_TFLOPS = 157.3     # MI355X: 256 CU x 128 FMA/clk x 2 flop x 2.4 GHz
 PEAK_HBM_GBS = 8000.0
-
-# HBM bytes per launch of the dominant kernel from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this
-# file (profiles/bench_cfg3_f32_hbm_counters.md: counters scaled by what a plain 1 GiB copy reads,
-# x2.000 and x1.000).  Counters cannot be read from inside the timed process, so the figure is stored
-# here per (workload, storage, kernel); anything not measured reports null.
-MEASURED_TRAFFIC_BYTES = {
-    ("cfg3_1024x1024_G16", "f32", "backward_input_slab_kernel"): 1.581e9,
-    ("cfg3_1024x1024_G16", "f32", "forward_slab_kernel"): 1.076e9,
-    ("cfg3_1024x1024_G16", "f32", "backward_coef_stream_kernel"): 2.823e9,
-}
+HEADLINE = "cfg3_1024x1024_G16"
 
 
 def parse():
@@ -38,168 +33,77 @@ def parse():
     ap.add_argument("--steps", type=int, default=20)      # the paper's protocol: 10 warm-up + 20 timed
     ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--storage", default="f32", choices=["f32", "f16", "bf16"])
-    ap.add_argument("--workload", default="cfg3_1024x1024_G16")
+    ap.add_argument("--workload", default=HEADLINE)
     ap.add_argument("--grid", type=int, default=0,
                     help="override the workload's number of grid intervals G (for sweeps over G)")
     ap.add_argument("--graph", action="store_true",
                     help="time the step as a replayed HIP graph (one launch per step instead of a dozen)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--cpu-rows", type=int, default=8192)
+    ap.add_argument("--no-configs", action="store_true",
+                    help="leave out the short runs of the other configurations")
+    ap.add_argument("--cpu-rows", type=int, default=4096)
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="after the timed region run one plain device copy of 1 GiB (torch's copy kernel): "
                          "the known-size reference that scales rocprofv3's FETCH_SIZE / WRITE_SIZE counters")
     return ap.parse_args()
 
 
-def stack_inference(args, pkg, wl, torch, np, dev):
-    """cfg2 as it runs at inference (App. F.1): the four layers chained, the evaluation-mode batch
-    normalisation after each hidden layer folded into that layer's table, forward only.  A step is
-    one batch through the whole stack; workspace and activations are allocated once."""
-    layers = wl.CFG2_LAYERS
-    B = layers[0].batch
-    g = torch.Generator(device="cpu").manual_seed(77)
-    x = wl.make_x(layers[0], dev)
-    descs, tables, outs = [], [], []
-    need = 256
-    for i, w in enumerate(layers):
-        paper = pkg.LayerDesc(w.n_in, w.n_out, w.grid)
-        P = wl.make_coef(w, dev)
-        if i + 1 < len(layers):     # seeded stand-ins for the running statistics, as in the full-size test
-            scale = (torch.rand((w.n_out,), generator=g) * 0.4 + 0.8) / (w.coef_std * (w.n_in / 2) ** 0.5)
-            shift = torch.randn((w.n_out,), generator=g) * 0.2
-            pkg.lmkan_fold(paper, P, 1.0, None, None, scale.to(dev), shift.to(dev))
-        tables.append(pkg.lmkan_pack(paper, P))
-        d = pkg.LayerDesc(w.n_in, w.n_out, w.grid, coef_layout=pkg.LMKAN_LAYOUT_PACKED)
-        descs.append(d)
-        outs.append(torch.empty((B, w.n_out), dtype=torch.float32, device=dev))
-        need = max(need, pkg.lmkan_workspace_bytes(d, B, False))
-    ws = torch.empty(need, dtype=torch.uint8, device=dev)
-
-    def step():
-        a = x
-        for d, t, y in zip(descs, tables, outs):
-            pkg.lmkan_forward(d, a, t, y=y, workspace=ws)
-            a = y
-
-    for _ in range(args.warmup):
-        step()
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for _ in range(args.steps):
-        step()
-    torch.cuda.synchronize()
-    ms = (time.perf_counter() - t0) * 1e3 / args.steps
-    fma = sum(4.0 * B * (w.n_in // 2) * w.n_out for w in layers)
-    print(json.dumps({
-        "metric": "lmKAN stack inference samples/sec (cfg2: 64->256->256->256->1, forward only, 1 GPU)",
-        "value": round(B / (ms * 1e-3), 1), "unit": "samples/s", "n_gpus": 1, "steps": args.steps,
-        "warmup": args.warmup, "ms_per_step": round(ms, 4), "higher_is_better": True, "scaling": "weak",
-        "vs_baseline": None, "dtype": "f32", "data": "synthetic",
-        "config": {"workload": f"cfg2_stack_inference: batch={B} G=16, normalisation folded into the tables, "
-                               "activations pass through device memory between the layers"},
-        "tflops": round(2 * fma / (ms * 1e-3) / 1e12, 3)}))
-
-
-def main():
-    args = parse()
-    if args.gpus != 1:
-        print("bench.py measures one GPU only: this build has no multi-GPU path (--gpus must be 1)",
-              file=sys.stderr)
-        sys.exit(2)
-
-    import numpy as np
-    import torch
-
-    import paper_2509_07103_amd as pkg
-    from paper_2509_07103_amd import workloads as wl
-
-    if not torch.cuda.is_available():
-        print("bench.py needs a GPU", file=sys.stderr)
-        sys.exit(2)
-    dev = torch.device("cuda:0")
-    L = pkg.lib()
-    if args.workload == "cfg2_stack_inference":
-        return stack_inference(args, pkg, wl, torch, np, dev)
-    conv = args.workload in wl.CONV_BY_NAME     # a convolution stage: rows = windows of the images
-    w = wl.CONV_BY_NAME[args.workload] if conv else wl.BY_NAME[args.workload]
-    if args.grid:
-        import dataclasses
-        w = dataclasses.replace(w, grid=args.grid, name=f"{w.name}@G={args.grid}")
-    dt_code = {"f32": pkg.LMKAN_F32, "f16": pkg.LMKAN_F16, "bf16": pkg.LMKAN_BF16}[args.storage]
-    B, K, n_out = w.batch, w.n_in // 2, w.n_out
-
-    # ---- inputs, resident in HBM before anything is timed -------------------------------
-    x = wl.make_image(w, dev) if conv else wl.make_x(w, dev)
-    gy = wl.make_grad_y(w, dev)
-    if w.name.startswith("cfg5") and args.storage == "bf16":
-        P_stored = wl.make_coef_bf16_chunked(w, dev)      # no room for a float32 master beside it
+def kernel_names(w, n_out, B, storage, packed):
+    """Main kernel of a forward call, of a grad_x-only call and of a grad_coef-only call, and of a call
+    for both gradients when one kernel forms both: mirrors the library's dispatch (lmkan_api.hip)."""
+    ok = n_out % 4 == 0 and B >= 256
+    both = None
+    if n_out <= 8:
+        fwd, gx, gp = "forward_small_kernel", "backward_input_small_kernel", "backward_coef_small_kernel"
+    elif ok and w.grid <= 16:
+        f16 = storage == "f16" and (packed or n_out % 8 == 0)
+        fwd = "forward_slab_f16_kernel" if f16 else "forward_slab_kernel"
+        gx = "backward_input_slab_f16_kernel" if f16 else "backward_input_slab_kernel"
+        gp = "backward_coef_stream_kernel"
+    elif ok and w.grid <= 34:
+        fwd, gx, gp = "forward_slab_narrow_kernel", "backward_input_slab_narrow_kernel", "backward_coef_stream_kernel"
+        if B >= 16 * w.grid * w.grid:
+            both = "backward_fused_kernel"
+    elif ok:
+        fwd, gx, gp = "forward_generic_kernel", "backward_fused_kernel", "backward_coef_stream_kernel"
+        both = "backward_fused_kernel"
     else:
-        P_master = wl.make_coef(w, dev)
-        P_stored = wl.store(P_master, args.storage).contiguous()
-        if args.storage != "f32":
-            del P_master
-    paper = pkg.LayerDesc(w.n_in, n_out, w.grid, coef_dtype=dt_code)
-    t0 = time.perf_counter()
-    P_packed = pkg.lmkan_pack(paper, P_stored)
-    torch.cuda.synchronize()
-    pack_ms = (time.perf_counter() - t0) * 1e3
-    desc = pkg.LayerDesc(w.n_in, n_out, w.grid, coef_dtype=dt_code, coef_layout=pkg.LMKAN_LAYOUT_PACKED)
+        fwd, gx = "forward_generic_kernel", "backward_generic_kernel(grad_x)"
+        gp = "backward_coef_stream_kernel" if n_out % 4 == 0 else "backward_generic_kernel(grad_coef)"
+    return fwd, gx, gp, both
 
-    y = torch.empty((B, n_out), dtype=torch.float32, device=dev)
-    gx = torch.empty_like(x)
-    gP = torch.empty(paper.coef_shape(), dtype=torch.float32, device=dev)
-    need = max(pkg.lmkan_workspace_bytes(desc, B, False), pkg.lmkan_workspace_bytes(desc, B, True), 256)
-    ws = torch.empty(need, dtype=torch.uint8, device=dev)
-    d = desc.c()
 
-    if conv:
-        geom = pkg.Conv2d(w.n, w.h, w.w, w.c_in, w.kh, w.kw, w.stride).c()
-        assert pkg.lmkan_conv2d_rows(pkg.Conv2d(w.n, w.h, w.w, w.c_in, w.kh, w.kw, w.stride))[0] == B
+def profile_traffic(workload, storage, kernel):
+    """HBM bytes per launch of `kernel` from the committed rocprofv3 counter summary of this workload
+    (profiles/bench_<workload>_<storage>_hbm_counters.md, a table whose last column is read + written
+    bytes).  Counters cannot be read from inside the timed process; a kernel the summary does not list
+    reports null with the reason, so a renamed or replaced kernel cannot keep a stale figure."""
+    path = os.path.join(ROOT, "profiles", f"bench_{workload}_{storage}_hbm_counters.md")
+    if not os.path.exists(path):
+        return None, f"no counter summary profiles/{os.path.basename(path)}"
+    for line in open(path):
+        cells = [c.strip() for c in line.strip().strip("|").split("|")]
+        if len(cells) >= 2 and cells[0] == kernel:
+            m = re.fullmatch(r"([0-9.]+)\s*([kMG]?)B", cells[-1])
+            if m:
+                return float(m.group(1)) * {"": 1, "k": 1e3, "M": 1e6, "G": 1e9}[m.group(2)], os.path.basename(path)
+    return None, f"{kernel} is not listed in profiles/{os.path.basename(path)}"
 
-    def forward():
-        if conv:
-            st = L.lmkan_conv2d_forward(C.byref(d), C.byref(geom), x.data_ptr(), P_packed.data_ptr(), y.data_ptr(),
-                                        ws.data_ptr(), need, torch.cuda.current_stream().cuda_stream)
-        else:
-            st = L.lmkan_forward(C.byref(d), B, x.data_ptr(), P_packed.data_ptr(), y.data_ptr(),
-                                 ws.data_ptr(), need, torch.cuda.current_stream().cuda_stream)
-        assert st == 0, pkg.lmkan_status_string(st)
 
-    def backward_only(gx_ptr, gp_ptr):
-        if conv:
-            st = L.lmkan_conv2d_backward(C.byref(d), C.byref(geom), x.data_ptr(), P_packed.data_ptr(),
-                                         gy.data_ptr(), gx_ptr, gp_ptr, ws.data_ptr(), need, torch.cuda.current_stream().cuda_stream)
-        else:
-            st = L.lmkan_backward(C.byref(d), B, x.data_ptr(), P_packed.data_ptr(), gy.data_ptr(),
-                                  gx_ptr, gp_ptr, ws.data_ptr(), need, torch.cuda.current_stream().cuda_stream)
-        assert st == 0, pkg.lmkan_status_string(st)
+class Bench:
+    def __init__(self):
+        import numpy as np
+        import torch
 
-    def backward():
-        backward_only(gx.data_ptr(), gP.data_ptr())
+        import paper_2509_07103_amd as pkg
+        from paper_2509_07103_amd import workloads as wl
+        self.np, self.torch, self.pkg, self.wl = np, torch, pkg, wl
+        self.dev = torch.device("cuda:0")
+        self.L = pkg.lib()
 
-    def step():
-        forward()
-        backward()
-
-    for _ in range(args.warmup):
-        step()
-    torch.cuda.synchronize()
-    run_step = step
-    if args.graph:      # the same step recorded once as a HIP graph and replayed (launch-bound layers)
-        hip_graph = torch.cuda.CUDAGraph()
-        with torch.cuda.graph(hip_graph):
-            step()
-        run_step = hip_graph.replay
-        run_step()
-        torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for _ in range(args.steps):
-        run_step()
-    torch.cuda.synchronize()
-    ms_per_step = (time.perf_counter() - t0) * 1e3 / args.steps
-
-    # ---- per-call durations with events on the launch stream ------------------------------
-    def event_ms(fn, reps):
+    # ---- timing helpers ---------------------------------------------------------------------
+    def event_ms(self, fn, reps):
+        torch = self.torch
         e0 = [torch.cuda.Event(enable_timing=True) for _ in range(reps)]
         e1 = [torch.cuda.Event(enable_timing=True) for _ in range(reps)]
         for i in range(reps):
@@ -207,14 +111,12 @@ def main():
             fn()
             e1[i].record()
         torch.cuda.synchronize()
-        return float(np.mean([a.elapsed_time(b) for a, b in zip(e0, e1)]))
+        return float(self.np.mean([a.elapsed_time(b) for a, b in zip(e0, e1)]))
 
-    reps = max(3, min(args.steps, 20))
-    null = C.c_void_p(0)
-
-    def kernel_ms(fn, reps):
-        """Duration of the call's main kernel alone: the library records the two events around it
-        on the launch stream (lmkan_time_next_kernel), leaving out the passes before and after."""
+    def kernel_ms(self, fn, reps):
+        """Duration of the call's main kernel alone: the library records the two events around it on
+        the launch stream (lmkan_time_next_kernel), leaving out the passes before and after."""
+        torch, pkg = self.torch, self.pkg
         pairs = []
         for _ in range(reps):
             e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
@@ -225,144 +127,355 @@ def main():
             pairs.append((e0, e1))
         pkg.lmkan_time_next_kernel(None, None)
         torch.cuda.synchronize()
-        return float(np.mean([a.elapsed_time(b) for a, b in pairs]))
+        return float(self.np.mean([a.elapsed_time(b) for a, b in pairs]))
 
-    fwd_ms = event_ms(forward, reps)
-    bwd_ms = event_ms(backward, reps)
-    gx_ms = event_ms(lambda: backward_only(gx.data_ptr(), null), reps)
-    gp_ms = event_ms(lambda: backward_only(null, gP.data_ptr()), reps)
+    # ---- one layer (or convolution stage) -----------------------------------------------------
+    def layer(self, name, storage, steps, warmup, grid=0, graph=False, detailed=False, keep=False):
+        np, torch, pkg, wl, dev, L = self.np, self.torch, self.pkg, self.wl, self.dev, self.L
+        conv = name in wl.CONV_BY_NAME      # a convolution stage: rows = windows of the images
+        w = wl.CONV_BY_NAME[name] if conv else wl.BY_NAME[name]
+        if grid:
+            import dataclasses
+            w = dataclasses.replace(w, grid=grid, name=f"{w.name}@G={grid}")
+        dt_code = {"f32": pkg.LMKAN_F32, "f16": pkg.LMKAN_F16, "bf16": pkg.LMKAN_BF16}[storage]
+        B, K, n_out = w.batch, w.n_in // 2, w.n_out
 
-    fma = 4.0 * B * K * n_out       # Alg. 1: four multiply-adds per (sample, pair, output);
-    fma_fwd = fma                   # each of the three passes does that many
-    fma_bwd = 2.0 * fma
-    s_bytes = 4 if args.storage == "f32" else 2
-    # each call = its main kernel plus the small preamble-record / zero-fill / sort / transpose
-    # launches; which kernel serves a call follows the library's own dispatch rules
-    ok = n_out % 4 == 0 and B >= 256
-    if n_out <= 8:
-        fwd_name, gx_name = "forward_small_kernel", "backward_input_small_kernel"
-    elif ok and w.grid <= 16:
-        fwd_name, gx_name = "forward_slab_kernel", "backward_input_slab_kernel"
-    elif ok and w.grid <= 34:
-        fwd_name, gx_name = "forward_slab_narrow_kernel", "backward_input_slab_narrow_kernel"
-    else:
-        fwd_name, gx_name = "forward_generic_kernel", "backward_generic_kernel(grad_x)"
-    gp_name = ("backward_coef_small_kernel" if n_out <= 8 else "backward_coef_stream_kernel" if n_out % 4 == 0
-               else "backward_generic_kernel(grad_coef)")
-    calls = {fwd_name: fwd_ms, gx_name: gx_ms, gp_name: gp_ms}
-    kernels = {fwd_name: kernel_ms(forward, reps),
-               gx_name: kernel_ms(lambda: backward_only(gx.data_ptr(), null), reps),
-               gp_name: kernel_ms(lambda: backward_only(null, gP.data_ptr()), reps)}
-    dom_name = max(kernels, key=kernels.get)
-    dom_ms = kernels[dom_name]
-    # algorithmic work of one such launch: 4 B K n_out multiply-adds; compulsory HBM bytes: the
-    # table (read, or written in float32 by the coefficient gradient) + x + one y-sized tensor
-    table_bytes = (w.grid + 1) ** 2 * K * n_out * (4 if "coef" in dom_name else s_bytes)
-    algo_bytes = table_bytes + x.numel() * 4 + B * n_out * 4
-    t_alu = 2.0 * fma / (PEAK_FP32_VECTOR_TFLOPS * 1e12)
-    t_hbm = algo_bytes / (PEAK_HBM_GBS * 1e9)
-    if t_hbm > t_alu:
-        achieved = algo_bytes / (dom_ms * 1e-3) / 1e9
-        roofline = {"bound": "hbm", "achieved": round(achieved, 1), "peak": PEAK_HBM_GBS, "unit": "GB/s",
-                    "frac": round(achieved / PEAK_HBM_GBS, 4)}
-    else:
-        achieved = 2.0 * fma / (dom_ms * 1e-3) / 1e12
-        roofline = {"bound": "alu", "achieved": round(achieved, 3), "peak": PEAK_FP32_VECTOR_TFLOPS,
-                    "unit": "TFLOP/s", "frac": round(achieved / PEAK_FP32_VECTOR_TFLOPS, 4)}
-    roofline.update({"traffic": MEASURED_TRAFFIC_BYTES.get((w.name, args.storage, dom_name)),
-                     "traffic_unit": "bytes per launch (HBM read + write)", "kernel": dom_name,
-                     "kernel_ms": round(dom_ms, 4),
-                     "kernels_ms": {k: round(v, 4) for k, v in kernels.items()},
-                     "all_ms": {k: round(v, 4) for k, v in calls.items()},
-                     "note": "kernel_ms / kernels_ms: the kernel alone, events recorded by the library around "
-                             "its launch; all_ms: whole calls (kernel + preamble, sort, fill, transpose passes)"})
-
-    out = {
-        # the benchmark's metric; `value` is the samples/sec of a forward + backward step, the gather rate
-        # and its ratio to the HBM peak are in "forward"
-        "metric": f"lmKAN layer samples/sec + achieved gather GB/s vs HBM peak ({w.n_in}->{n_out}, 1 GPU)",
-        "value": round(B / (ms_per_step * 1e-3), 1),
-        "unit": "samples/s",
-        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
-        "ms_per_step": round(ms_per_step, 4),
-        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-        "dtype": "f32", "data": "synthetic",
-        "config": {"workload": (f"convolution {w.kh}x{w.kw} stride {w.stride} on [{w.n}][{w.h}][{w.w}][{w.c_in}] images, "
-                                f"a sample = one window; " if conv else "") +
-                               f"{w.name}: n_in={w.n_in} n_out={n_out} G={w.grid} batch={B} "
-                               f"coef_storage={args.storage} x~{w.x_kind} coef~N(0,{w.coef_std})",
-                   "pass": "forward+backward(grad_x,grad_coef)", "coef_layout": "packed",
-                   "launch": "hip graph replay" if args.graph else "stream launches",
-                   "pack_ms_once": round(pack_ms, 3)},
-        "forward": {"ms": round(fwd_ms, 4), "samples_per_s": round(B / (fwd_ms * 1e-3), 1),
-                    "gather_GBps": round(fma_fwd * s_bytes / (fwd_ms * 1e-3) / 1e9, 1),
-                    "gather_vs_hbm_peak": round(fma_fwd * s_bytes / (fwd_ms * 1e-3) / 1e9 / PEAK_HBM_GBS, 3),
-                    "tflops": round(2 * fma_fwd / (fwd_ms * 1e-3) / 1e12, 3)},
-        "backward": {"ms": round(bwd_ms, 4), "samples_per_s": round(B / (bwd_ms * 1e-3), 1),
-                     "tflops": round(2 * fma_bwd / (bwd_ms * 1e-3) / 1e12, 3)},
-        "roofline": roofline,
-    }
-
-    # ---- Hessian regulariser of the same table (Sec. 3.5): value + gradient, HBM-bound ----------
-    hval = torch.empty(1, dtype=torch.float64, device=dev)
-
-    def hessian():
-        st = L.lmkan_hessian_reg(C.byref(d), P_packed.data_ptr(), 1.0, hval.data_ptr(), gP.data_ptr(),
-                                 torch.cuda.current_stream().cuda_stream)
-        assert st == 0, pkg.lmkan_status_string(st)
-
-    hess_ms = event_ms(hessian, reps)
-    hess_bytes = (w.grid + 1) ** 2 * K * n_out * (s_bytes + 4)      # table read once, gradient written once
-    out["hessian_reg"] = {"ms": round(hess_ms, 4), "GBps": round(hess_bytes / (hess_ms * 1e-3) / 1e9, 1),
-                          "vs_hbm_peak": round(hess_bytes / (hess_ms * 1e-3) / 1e9 / PEAK_HBM_GBS, 3),
-                          "note": "value + gradient of the off-diagonal Hessian regulariser; not part of the step"}
-
-    # ---- yardstick of App. G: a dense float32 linear layer of the same shape (library GEMM) ------------
-    # The paper normalises its kernel by this ratio (about 8 on its H100 for large batches).  Context only.
-    if not conv and w.n_in * n_out * 4 <= 1 << 28:
-        xw = torch.randn((w.n_in, n_out), dtype=torch.float32, device=dev)
-        yl = torch.empty((B, n_out), dtype=torch.float32, device=dev)
-        for _ in range(3):      # library set-up and kernel selection happen on the first calls
-            torch.matmul(x, xw, out=yl)
+        # inputs, resident in HBM before anything is timed
+        x = wl.make_image(w, dev) if conv else wl.make_x(w, dev)
+        gy = wl.make_grad_y(w, dev)
+        if w.name.startswith("cfg5") and storage == "bf16":
+            P_stored = wl.make_coef_bf16_chunked(w, dev)      # no room for a float32 master beside it
+        else:
+            P_master = wl.make_coef(w, dev)
+            P_stored = wl.store(P_master, storage).contiguous()
+            del P_master
+        paper = pkg.LayerDesc(w.n_in, n_out, w.grid, coef_dtype=dt_code)
+        t0 = time.perf_counter()
+        P_packed = pkg.lmkan_pack(paper, P_stored)
         torch.cuda.synchronize()
-        lin_ms = event_ms(lambda: torch.matmul(x, xw, out=yl), reps)
-        out["dense_linear"] = {"ms": round(lin_ms, 4), "forward_ratio": round(fwd_ms / lin_ms, 2),
-                               "note": "torch.matmul float32 [B,n_in]x[n_in,n_out]; lmKAN forward time / this"}
-        del xw, yl
+        pack_ms = (time.perf_counter() - t0) * 1e3
+        if not keep:
+            del P_stored
+        desc = pkg.LayerDesc(w.n_in, n_out, w.grid, coef_dtype=dt_code, coef_layout=pkg.LMKAN_LAYOUT_PACKED)
 
-    if args.calibrate_copy:
-        src = torch.empty(1 << 28, dtype=torch.float32, device=dev).normal_()
-        dst = torch.empty_like(src)
-        torch.cuda.synchronize()
-        dst.copy_(src)
-        torch.cuda.synchronize()
-        del src, dst
+        y = torch.empty((B, n_out), dtype=torch.float32, device=dev)
+        gx = torch.empty_like(x)
+        gP = torch.empty(paper.coef_shape(), dtype=torch.float32, device=dev)
+        need = max(pkg.lmkan_workspace_bytes(desc, B, False), pkg.lmkan_workspace_bytes(desc, B, True), 256)
+        ws = torch.empty(need, dtype=torch.uint8, device=dev)
+        d = desc.c()
+        if conv:
+            geom = pkg.Conv2d(w.n, w.h, w.w, w.c_in, w.kh, w.kw, w.stride).c()
+            assert pkg.lmkan_conv2d_rows(pkg.Conv2d(w.n, w.h, w.w, w.c_in, w.kh, w.kw, w.stride))[0] == B
 
-    # ---- CPU baseline: the oracle as it stands, on a bounded row sample ---------------------
-    if not args.no_cpu_baseline:
+        def forward():
+            s = torch.cuda.current_stream().cuda_stream
+            if conv:
+                st = L.lmkan_conv2d_forward(C.byref(d), C.byref(geom), x.data_ptr(), P_packed.data_ptr(), y.data_ptr(),
+                                            ws.data_ptr(), need, s)
+            else:
+                st = L.lmkan_forward(C.byref(d), B, x.data_ptr(), P_packed.data_ptr(), y.data_ptr(), ws.data_ptr(),
+                                     need, s)
+            assert st == 0, pkg.lmkan_status_string(st)
+
+        def backward_only(gx_ptr, gp_ptr):
+            s = torch.cuda.current_stream().cuda_stream
+            if conv:
+                st = L.lmkan_conv2d_backward(C.byref(d), C.byref(geom), x.data_ptr(), P_packed.data_ptr(),
+                                             gy.data_ptr(), gx_ptr, gp_ptr, ws.data_ptr(), need, s)
+            else:
+                st = L.lmkan_backward(C.byref(d), B, x.data_ptr(), P_packed.data_ptr(), gy.data_ptr(), gx_ptr, gp_ptr,
+                                      ws.data_ptr(), need, s)
+            assert st == 0, pkg.lmkan_status_string(st)
+
+        null = C.c_void_p(0)
+
+        def backward():
+            backward_only(gx.data_ptr(), gP.data_ptr())
+
+        def step():
+            forward()
+            backward()
+
+        for _ in range(warmup):
+            step()
+        torch.cuda.synchronize()
+        run_step = step
+        if graph:      # the same step recorded once as a HIP graph and replayed (launch-bound layers)
+            hip_graph = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(hip_graph):
+                step()
+            run_step = hip_graph.replay
+            run_step()
+            torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(steps):
+            run_step()
+        torch.cuda.synchronize()
+        ms_per_step = (time.perf_counter() - t0) * 1e3 / steps
+
+        reps = max(3, min(steps, 20))
+        fwd_ms = self.event_ms(forward, reps)
+        bwd_ms = self.event_ms(backward, reps)
+        gx_ms = self.event_ms(lambda: backward_only(gx.data_ptr(), null), reps)
+        gp_ms = self.event_ms(lambda: backward_only(null, gP.data_ptr()), reps)
+
+        fma = 4.0 * B * K * n_out       # Alg. 1: four multiply-adds per (sample, pair, output); each of the
+        s_bytes = 4 if storage == "f32" else 2      # three passes (forward, grad_x, grad_coef) does that many
+        fwd_name, gx_name, gp_name, both_name = kernel_names(w, n_out, B, storage, True)
+        # the kernels that run in a step, each timed alone; a kernel that forms both gradients does
+        # twice the multiply-adds
+        kernels = {fwd_name: (self.kernel_ms(forward, reps), fma)}
+        if both_name:
+            kernels[both_name + "(grad_x+grad_coef)"] = (self.kernel_ms(backward, reps), 2 * fma)
+        else:
+            kernels[gx_name] = (self.kernel_ms(lambda: backward_only(gx.data_ptr(), null), reps), fma)
+            kernels[gp_name] = (self.kernel_ms(lambda: backward_only(null, gP.data_ptr()), reps), fma)
+        dom_name = max(kernels, key=lambda k: kernels[k][0])
+        dom_ms, dom_fma = kernels[dom_name]
+        # algorithmic work of one such launch: its multiply-adds; compulsory HBM bytes: the table (read,
+        # or written in float32 by the coefficient gradient, or both) + x + one y-sized tensor
+        nodes = (w.grid + 1) ** 2
+        if "grad_x+grad_coef" in dom_name:
+            table_bytes = nodes * K * n_out * (s_bytes + 4)
+        else:
+            table_bytes = nodes * K * n_out * (4 if "coef" in dom_name else s_bytes)
+        algo_bytes = table_bytes + x.numel() * 4 + B * n_out * 4
+        t_alu = 2.0 * dom_fma / (PEAK_FP32_VECTOR_TFLOPS * 1e12)
+        t_hbm = algo_bytes / (PEAK_HBM_GBS * 1e9)
+        if t_hbm > t_alu:
+            achieved = algo_bytes / (dom_ms * 1e-3) / 1e9
+            roofline = {"bound": "hbm", "achieved": round(achieved, 1), "peak": PEAK_HBM_GBS, "unit": "GB/s",
+                        "frac": round(achieved / PEAK_HBM_GBS, 4)}
+        else:
+            achieved = 2.0 * dom_fma / (dom_ms * 1e-3) / 1e12
+            roofline = {"bound": "alu", "achieved": round(achieved, 3), "peak": PEAK_FP32_VECTOR_TFLOPS,
+                        "unit": "TFLOP/s", "frac": round(achieved / PEAK_FP32_VECTOR_TFLOPS, 4)}
+        traffic, source = profile_traffic(w.name, storage, dom_name.split("(")[0])
+        roofline.update({"traffic": traffic, "traffic_unit": "bytes per launch (HBM read + write)",
+                         "traffic_source": source, "kernel": dom_name, "kernel_ms": round(dom_ms, 4),
+                         "algorithmic_bytes": algo_bytes, "algorithmic_fma": dom_fma,
+                         "kernels_ms": {k: round(v[0], 4) for k, v in kernels.items()},
+                         "calls_ms": {"forward": round(fwd_ms, 4), "backward(grad_x,grad_coef)": round(bwd_ms, 4),
+                                      "backward(grad_x)": round(gx_ms, 4), "backward(grad_coef)": round(gp_ms, 4)},
+                         "note": "kernel_ms / kernels_ms: the kernel alone, events recorded by the library around "
+                                 "its launch; calls_ms: whole calls (kernel + preamble, sort, fill, transpose, "
+                                 "combine passes)"})
+        summary = {
+            "workload": f"{w.name}: n_in={w.n_in} n_out={n_out} G={w.grid} batch={B} coef_storage={storage}",
+            "steps": steps, "warmup": warmup, "ms_per_step": round(ms_per_step, 4),
+            "samples_per_s": round(B / (ms_per_step * 1e-3), 1),
+            "forward_ms": round(fwd_ms, 4), "grad_x_ms": round(gx_ms, 4), "grad_coef_ms": round(gp_ms, 4),
+            "backward_ms": round(bwd_ms, 4),
+            "forward_algorithmic_gather_GBps": round(fma * s_bytes / (fwd_ms * 1e-3) / 1e9, 1),
+            "roofline": {k: roofline[k] for k in ("bound", "achieved", "peak", "unit", "frac", "kernel", "kernel_ms",
+                                                  "traffic")},
+        }
+        if not detailed:
+            return summary
+        out = {
+            # the benchmark's metric; `value` is the samples/sec of a forward + backward step
+            "metric": f"lmKAN layer samples/sec + achieved gather GB/s vs HBM peak ({w.n_in}->{n_out}, 1 GPU)",
+            "value": round(B / (ms_per_step * 1e-3), 1),
+            "unit": "samples/s",
+            "n_gpus": 1, "steps": steps, "warmup": warmup,
+            "ms_per_step": round(ms_per_step, 4),
+            "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+            # the arithmetic type: products and sums are float32 whatever the table is stored in
+            "dtype": "f32", "coef_storage": storage, "data": "synthetic",
+            "config": {"workload": (f"convolution {w.kh}x{w.kw} stride {w.stride} on [{w.n}][{w.h}][{w.w}][{w.c_in}] "
+                                    f"images, a sample = one window; " if conv else "") +
+                                   f"{w.name}: n_in={w.n_in} n_out={n_out} G={w.grid} batch={B} "
+                                   f"coef_storage={storage} x~{w.x_kind} coef~N(0,{w.coef_std})",
+                       "pass": "forward+backward(grad_x,grad_coef)", "coef_layout": "packed",
+                       "launch": "hip graph replay" if graph else "stream launches",
+                       "pack_ms_once": round(pack_ms, 3)},
+            "forward": {"ms": round(fwd_ms, 4), "samples_per_s": round(B / (fwd_ms * 1e-3), 1),
+                        # 4 B K n_out coefficient operands x their size / time: what the multiply-adds pull
+                        # through LDS and L2 together, not bytes that crossed the HBM interface
+                        "algorithmic_gather_GBps": round(fma * s_bytes / (fwd_ms * 1e-3) / 1e9, 1),
+                        "compulsory_hbm_GBps": round((nodes * K * n_out * s_bytes + x.numel() * 4 + B * n_out * 4) /
+                                                     (fwd_ms * 1e-3) / 1e9, 1),
+                        "hbm_peak_GBps": PEAK_HBM_GBS,
+                        "tflops": round(2 * fma / (fwd_ms * 1e-3) / 1e12, 3)},
+            "backward": {"ms": round(bwd_ms, 4), "samples_per_s": round(B / (bwd_ms * 1e-3), 1),
+                         "tflops": round(4 * fma / (bwd_ms * 1e-3) / 1e12, 3)},
+            "roofline": roofline,
+        }
+
+        # Hessian regulariser of the same table (Sec. 3.5): value + gradient, HBM-bound
+        hval = torch.empty(1, dtype=torch.float64, device=dev)
+
+        def hessian():
+            st = L.lmkan_hessian_reg(C.byref(d), P_packed.data_ptr(), 1.0, hval.data_ptr(), gP.data_ptr(),
+                                     torch.cuda.current_stream().cuda_stream)
+            assert st == 0, pkg.lmkan_status_string(st)
+
+        hess_ms = self.event_ms(hessian, reps)
+        hess_bytes = nodes * K * n_out * (s_bytes + 4)      # table read once, gradient written once
+        out["hessian_reg"] = {"ms": round(hess_ms, 4), "GBps": round(hess_bytes / (hess_ms * 1e-3) / 1e9, 1),
+                              "vs_hbm_peak": round(hess_bytes / (hess_ms * 1e-3) / 1e9 / PEAK_HBM_GBS, 3),
+                              "note": "value + gradient of the off-diagonal Hessian regulariser; not part of the step"}
+        if keep:
+            self.kept = dict(w=w, conv=conv, x=x, gy=gy, P_stored=P_stored, storage=storage)
+        return out
+
+    # ---- cfg2 as it runs at inference -----------------------------------------------------------
+    def stack_inference(self, steps, warmup):
+        """cfg2 as it runs at inference (App. F.1): the four layers chained, the evaluation-mode batch
+        normalisation after each hidden layer folded into that layer's table, forward only.  A step is
+        one batch through the whole stack; workspace and activations are allocated once."""
+        torch, pkg, wl, dev = self.torch, self.pkg, self.wl, self.dev
+        layers = wl.CFG2_LAYERS
+        B = layers[0].batch
+        g = torch.Generator(device="cpu").manual_seed(77)
+        x = wl.make_x(layers[0], dev)
+        descs, tables, outs = [], [], []
+        need = 256
+        for i, w in enumerate(layers):
+            paper = pkg.LayerDesc(w.n_in, w.n_out, w.grid)
+            P = wl.make_coef(w, dev)
+            if i + 1 < len(layers):     # seeded stand-ins for the running statistics, as in the full-size test
+                scale = (torch.rand((w.n_out,), generator=g) * 0.4 + 0.8) / (w.coef_std * (w.n_in / 2) ** 0.5)
+                shift = torch.randn((w.n_out,), generator=g) * 0.2
+                pkg.lmkan_fold(paper, P, 1.0, None, None, scale.to(dev), shift.to(dev))
+            tables.append(pkg.lmkan_pack(paper, P))
+            d = pkg.LayerDesc(w.n_in, w.n_out, w.grid, coef_layout=pkg.LMKAN_LAYOUT_PACKED)
+            descs.append(d)
+            outs.append(torch.empty((B, w.n_out), dtype=torch.float32, device=dev))
+            need = max(need, pkg.lmkan_workspace_bytes(d, B, False))
+        ws = torch.empty(need, dtype=torch.uint8, device=dev)
+
+        def step():
+            a = x
+            for d, t, y in zip(descs, tables, outs):
+                pkg.lmkan_forward(d, a, t, y=y, workspace=ws)
+                a = y
+
+        for _ in range(warmup):
+            step()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(steps):
+            step()
+        torch.cuda.synchronize()
+        ms = (time.perf_counter() - t0) * 1e3 / steps
+        fma = sum(4.0 * B * (w.n_in // 2) * w.n_out for w in layers)
+        t_alu_ms = 2.0 * fma / (PEAK_FP32_VECTOR_TFLOPS * 1e12) * 1e3
+        return {"workload": f"cfg2_stack_inference: 64->256->256->256->1, batch={B} G=16, normalisation folded "
+                            "into the tables, activations pass through device memory between the layers, forward only",
+                "steps": steps, "warmup": warmup, "ms_per_step": round(ms, 4),
+                "samples_per_s": round(B / (ms * 1e-3), 1), "tflops": round(2 * fma / (ms * 1e-3) / 1e12, 3),
+                "roofline": {"bound": "alu", "frac": round(t_alu_ms / ms, 4), "peak": PEAK_FP32_VECTOR_TFLOPS,
+                             "unit": "TFLOP/s", "achieved": round(2 * fma / (ms * 1e-3) / 1e12, 3),
+                             "kernel": "four lmkan_forward calls (whole step)"}}
+
+    # ---- what the machine delivers on the primitive streams -----------------------------------
+    def machine(self):
+        torch, pkg = self.torch, self.pkg
+        scratch = torch.empty(1 << 30, dtype=torch.uint8, device=self.dev)
+        out = {name: round(pkg.lmkan_microbench(code, scratch), 2) for name, code in pkg.MICROBENCH.items()}
+        props = torch.cuda.get_device_properties(self.dev)
+        out["compute_units"] = props.multi_processor_count
+        per_clk = 2 * out["compute_units"] * out["nominal_clock_GHz"] * 1e9 / 1e12
+        out["fma_vector_TFLOPs"] = round(out["fma_per_clk_cu"] * per_clk, 1)
+        out["fma_mfma_4x4x1_TFLOPs"] = round(out["mfma_fma_per_clk_cu"] * per_clk, 1)
+        out["note"] = ("lmkan_microbench on this box, this run: per clock at the nominal clock; packed float32 vector "
+                       "instructions are switched off in this build, so the published vector peak (128 multiply-adds "
+                       "per clock and compute unit) is not reachable by vector code here")
+        return out
+
+    # ---- CPU baseline: the oracle as it stands, on a bounded row sample -----------------------
+    def cpu_baseline(self, rows_max):
+        import concurrent.futures as cf
+
         import oracle
+        np, torch = self.np, self.torch
+        k = self.kept
+        w, x, gy, P_stored, storage = k["w"], k["x"], k["gy"], k["P_stored"], k["storage"]
         o = oracle.get()
-        rows = min(args.cpu_rows, B)
-        if conv:    # the oracle's own gathering of the windows into rows, timed with the rest
+        B, K = w.batch, w.n_in // 2
+        rows = min(rows_max, B)
+        if k["conv"]:    # the oracle's own gathering of the windows into rows, timed with the rest
             n_img = -(-rows // (B // w.n))
             xh = o.conv2d_patches(x[:n_img].cpu().numpy(), w.kh, w.kw, w.stride)[:rows]
         else:
             xh = x[:rows].cpu().numpy()
         gyh = gy[:rows].cpu().numpy()
         Pc = P_stored.cpu().contiguous()
-        Ph = Pc.numpy() if args.storage == "f32" else Pc.view(torch.int16).numpy().view(np.uint16)
-        code = {"f32": 0, "f16": 1, "bf16": 2}[args.storage]
-        t0 = time.perf_counter()
-        o.forward(xh, Ph, w.grid, dtype=code, threads=1)
-        o.backward_input(xh, Ph, gyh, w.grid, dtype=code, threads=1)
-        for k in range(K):
-            o.backward_coef_pair(xh, gyh, w.grid, k)
-        cpu_s = time.perf_counter() - t0
-        out["cpu_baseline"] = {"value": round(rows / cpu_s, 3), "unit": "samples/s", "cores": 1,
-                               "kind": "oracle",
-                               "sample": f"first {rows} rows of the same batch through oracle forward, "
-                                         f"backward_input and backward_coef_pair for all {K} pairs "
-                                         f"(full-size table), {cpu_s:.1f} s"}
+        Ph = Pc.numpy() if storage == "f32" else Pc.view(torch.int16).numpy().view(np.uint16)
+        code = {"f32": 0, "f16": 1, "bf16": 2}[storage]
+        cores = len(os.sched_getaffinity(0)) if hasattr(os, "sched_getaffinity") else (os.cpu_count() or 1)
+
+        def run(threads):
+            t0 = time.perf_counter()
+            o.forward(xh, Ph, w.grid, dtype=code, threads=threads)
+            o.backward_input(xh, Ph, gyh, w.grid, dtype=code, threads=threads)
+            if threads == 1:
+                for kk in range(K):
+                    o.backward_coef_pair(xh, gyh, w.grid, kk)
+            else:       # pair slices are independent; the C routine runs without the interpreter lock
+                with cf.ThreadPoolExecutor(max_workers=threads) as pool:
+                    list(pool.map(lambda kk: o.backward_coef_pair(xh, gyh, w.grid, kk), range(K)))
+            return time.perf_counter() - t0
+
+        one = run(1)
+        many = run(cores) if cores > 1 else one
+        sample = (f"first {rows} rows of the same batch through oracle forward, backward_input and "
+                  f"backward_coef_pair for all {K} pairs (full-size table)")
+        return {"value": round(rows / many, 3), "unit": "samples/s", "cores": cores, "kind": "oracle",
+                "sample": f"{sample}, {many:.1f} s on {cores} threads",
+                "one_core": {"value": round(rows / one, 3), "unit": "samples/s", "cores": 1, "seconds": round(one, 1)},
+                "host_cores_available": cores, "host_cores_total": os.cpu_count()}
+
+
+def main():
+    args = parse()
+    if args.gpus != 1:
+        print("bench.py measures one GPU only: this build has no multi-GPU path (--gpus must be 1)",
+              file=sys.stderr)
+        sys.exit(2)
+    import torch
+    if not torch.cuda.is_available():
+        print("bench.py needs a GPU", file=sys.stderr)
+        sys.exit(2)
+    b = Bench()
+    if args.workload == "cfg2_stack_inference":
+        r = b.stack_inference(args.steps, args.warmup)
+        r.update({"metric": "lmKAN stack inference samples/sec (cfg2: 64->256->256->256->1, forward only, 1 GPU)",
+                  "value": r["samples_per_s"], "unit": "samples/s", "n_gpus": 1, "higher_is_better": True,
+                  "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+                  "config": {"workload": r.pop("workload")}})
+        print(json.dumps(r))
+        return
+    want_cpu = not args.no_cpu_baseline
+    out = b.layer(args.workload, args.storage, args.steps, args.warmup, grid=args.grid, graph=args.graph,
+                  detailed=True, keep=want_cpu)
+    out["roofline"]["measured"] = b.machine()
+    headline = args.workload == HEADLINE and not args.grid
+    if headline and not args.no_configs:
+        # the other four configurations of BASELINE.json, short runs (2 warm-up + 5 timed steps each)
+        wl = b.wl
+        configs = {}
+        for name, storage in ((wl.CFG1.name, "f32"), (wl.CFG4.name, "f32"), (wl.CFG5.name, "bf16"),
+                              (wl.CFG3.name, "f16")):
+            torch.cuda.empty_cache()
+            configs[f"{name}_{storage}"] = b.layer(name, storage, 5, 2)
+        torch.cuda.empty_cache()
+        configs["cfg2_stack_inference"] = b.stack_inference(5, 2)
+        for w in wl.CFG2_LAYERS:
+            torch.cuda.empty_cache()
+            configs[f"{w.name}_f32"] = b.layer(w.name, "f32", 5, 2)
+        out["configs"] = configs
+    if args.calibrate_copy:
+        src = torch.empty(1 << 28, dtype=torch.float32, device=b.dev).normal_()
+        dst = torch.empty_like(src)
+        torch.cuda.synchronize()
+        dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
+    if want_cpu:
+        out["cpu_baseline"] = b.cpu_baseline(args.cpu_rows)
     print(json.dumps(out))
 
 

@@ -266,6 +266,31 @@ lmkan_status lmkan_fold(const lmkan_desc *desc, void *coef_dev, float gamma, con
 lmkan_status lmkan_time_next_kernel(void *start_event, void *stop_event);
 
 /*
+ * For callers that measure (not part of the paper's method): what this machine delivers on the
+ * primitive streams the kernels are made of, to be quoted next to the published peaks.
+ *   which         LMKAN_MICROBENCH_*: HBM copy and read (GB/s, bytes read + written), independent
+ *                 float32 multiply-adds on the vector pipe and as 4x4x1 MFMAs (multiply-adds per
+ *                 clock and compute unit, at the nominal clock the runtime reports), 16-byte
+ *                 LDS reads and writes (bytes per clock and compute unit), gathers of 256-byte
+ *                 rows from a 2 MiB table (bytes per clock and compute unit)
+ *   scratch_dev   at least 64 MiB of device memory, 256-byte aligned, contents destroyed
+ *   result_host   one double on the host
+ * Unlike every other entry point this one creates two HIP events and waits for its kernels
+ * (about ten short launches on `stream`) before it returns.
+ */
+#define LMKAN_MICROBENCH_COPY_GBPS 0
+#define LMKAN_MICROBENCH_READ_GBPS 1
+#define LMKAN_MICROBENCH_FMA_PER_CLK_CU 2
+#define LMKAN_MICROBENCH_MFMA_FMA_PER_CLK_CU 3
+#define LMKAN_MICROBENCH_LDS_READ_B_PER_CLK_CU 4
+#define LMKAN_MICROBENCH_LDS_WRITE_B_PER_CLK_CU 5
+#define LMKAN_MICROBENCH_GATHER_B_PER_CLK_CU 6
+#define LMKAN_MICROBENCH_NOMINAL_CLOCK_GHZ 7 /* no kernel: the clock the "per clock" figures refer to */
+#define LMKAN_MICROBENCH_COUNT 8
+lmkan_status lmkan_microbench(int32_t which, void *scratch_dev, size_t scratch_bytes, double *result_host,
+                              void *stream);
+
+/*
  * Convolution (Sec. 5, "lmKAN-based Convolutional Neural Networks"): a kh x kw
  * convolution is the layer R^{kh kw c_in} -> R^{n_out} applied to every window of a
  * channels-last image.  The paper reshapes the windows into rows first; here the rows

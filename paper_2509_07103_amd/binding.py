@@ -128,6 +128,8 @@ def lib() -> C.CDLL:
                                  C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]
     L.lmkan_time_next_kernel.restype = C.c_int
     L.lmkan_time_next_kernel.argtypes = [C.c_void_p, C.c_void_p]
+    L.lmkan_microbench.restype = C.c_int
+    L.lmkan_microbench.argtypes = [C.c_int32, C.c_void_p, C.c_size_t, C.POINTER(C.c_double), C.c_void_p]
     cp = C.POINTER(_Conv2d)
     L.lmkan_conv2d_rows.restype = C.c_int64
     L.lmkan_conv2d_rows.argtypes = [cp, C.POINTER(C.c_int32), C.POINTER(C.c_int32)]
@@ -296,6 +298,21 @@ def lmkan_time_next_kernel(start: torch.cuda.Event | None, stop: torch.cuda.Even
     if (start is not None and not hs) or (stop is not None and not he):
         raise ValueError("the events must exist already: record each once before arming them")
     _check(lib().lmkan_time_next_kernel(hs, he), "lmkan_time_next_kernel")
+
+
+MICROBENCH = {"hbm_copy_GBps": 0, "hbm_read_GBps": 1, "fma_per_clk_cu": 2, "mfma_fma_per_clk_cu": 3,
+              "lds_read_B_per_clk_cu": 4, "lds_write_B_per_clk_cu": 5, "l2_row_gather_B_per_clk_cu": 6,
+              "nominal_clock_GHz": 7}
+
+
+def lmkan_microbench(which: int, scratch: torch.Tensor, stream=None) -> float:
+    """One of the machine measurements of ``lmkan_microbench`` (waits for its kernels)."""
+    if not scratch.is_cuda or not scratch.is_contiguous():
+        raise ValueError("scratch: expected a contiguous device tensor")
+    out = C.c_double(0.0)
+    _check(lib().lmkan_microbench(which, scratch.data_ptr(), scratch.numel() * scratch.element_size(),
+                                  C.byref(out), _stream(stream)), "lmkan_microbench")
+    return out.value
 
 
 def lmkan_conv2d_rows(conv: Conv2d):

@@ -30,7 +30,7 @@ def test_library_exports_every_declared_symbol():
             "lmkan_version", "lmkan_status_string", "lmkan_packed_bytes",
             "lmkan_workspace_bytes", "lmkan_hessian_reg", "lmkan_fold", "lmkan_conv2d_rows",
             "lmkan_conv2d_forward", "lmkan_conv2d_backward", "lmkan_time_next_kernel",
-            "lmkan_forward_static"} <= declared
+            "lmkan_forward_static", "lmkan_microbench"} <= declared
     for name in declared:
         assert hasattr(L, name), name
         assert hasattr(pkg, name), f"python binding lacks {name}"

@@ -52,8 +52,36 @@ def test_the_product_never_touches_the_oracle():
                 text = open(os.path.join(dirpath, fn)).read()
                 assert not re.search(r"^\s*(import|from)\s+oracle\b|oracle\.(get|build)|liblmkan_oracle", text, re.M), \
                     f"{fn} uses the oracle"
+    # bench.py imports it in one place only: the CPU-baseline leg, which runs after every timed region
     bench = open(os.path.join(ROOT, "bench.py")).read()
-    assert bench.count("import oracle") == 1 and bench.index("import oracle") > bench.index("if not args.no_cpu_baseline")
+    assert bench.count("import oracle") == 1
+    assert bench.index("import oracle") > bench.index("def cpu_baseline(")
+    assert bench.index("b.cpu_baseline(") > bench.index('out["configs"] = configs')
+
+
+def test_traffic_figures_name_kernels_that_exist():
+    """bench.py takes roofline.traffic from the counter summaries under profiles/, looked up by kernel name.
+    A summary that names a kernel the sources no longer define is stale: fail here rather than print it."""
+    import re
+    import bench
+    src = ""
+    csrc = os.path.join(ROOT, "paper_2509_07103_amd", "csrc")
+    for fn in os.listdir(csrc):
+        src += open(os.path.join(csrc, fn)).read()
+    seen = 0
+    for fn in sorted(os.listdir(os.path.join(ROOT, "profiles"))):
+        m = re.fullmatch(r"bench_(.+)_(f32|f16|bf16)_hbm_counters\.md", fn)
+        if not m:
+            continue
+        for line in open(os.path.join(ROOT, "profiles", fn)):
+            cells = [c.strip() for c in line.strip().strip("|").split("|")]
+            if len(cells) >= 2 and re.fullmatch(r"[a-z_0-9]+_kernel", cells[0]):
+                assert re.search(r"\b%s\b" % cells[0], src), f"{fn} names {cells[0]}, which no source defines"
+                got, where = bench.profile_traffic(m.group(1), m.group(2), cells[0])
+                assert got is not None and got > 0, (fn, cells[0], where)
+                seen += 1
+    assert seen >= 3
+    assert bench.profile_traffic("cfg3_1024x1024_G16", "f32", "no_such_kernel")[0] is None
 
 
 def test_missing_library_is_a_loud_error(tmp_path, monkeypatch):
