@@ -25,7 +25,7 @@ bool aligned(const void *p, size_t a) { return (reinterpret_cast<uintptr_t>(p) %
 // wanted only (pointer alignment, which also steers the choice of kernels, is not known when the
 // caller asks for the size, so every path the shape admits is provided for).
 struct BackwardWorkspace {
-    size_t records, sorted, scratch, partial;  // offsets
+    size_t records, sorted, scratch, partial, gy_tiles;  // offsets
     size_t total;
 };
 BackwardWorkspace backward_workspace(const LayerShape &s, bool want_gx, bool want_gp)
@@ -37,7 +37,8 @@ BackwardWorkspace backward_workspace(const LayerShape &s, bool want_gx, bool wan
     w.sorted = align256(records_bytes(s));
     w.scratch = w.sorted + (sorted ? sorted_records_bytes(s) : 0);
     w.partial = w.scratch + (want_gx ? slab_backward_input_scratch_bytes(s) : 0);
-    w.total = w.partial + (want_gx && sorted ? fused_partial_bytes(s) : 0);
+    w.gy_tiles = w.partial + (want_gx && sorted ? fused_partial_bytes(s) : 0);
+    w.total = w.gy_tiles + (sorted ? gy_tiles_bytes(s) : 0);
     return w;
 }
 
@@ -345,11 +346,15 @@ lmkan_status backward_impl(const lmkan_desc *desc, int64_t batch, const float *x
     TimedCall timed(grad_x_dev ? kTimeGradInput : kTimeGradCoef);
     if (need_records) launch_preamble_records(s, tab, x_dev, ws, hs, conv);
     SortedStream stream_k{};
-    if (gp_sorted || gx_fused) stream_k = launch_sort(s, ws, ws_sorted, hs);
+    GyView gy_k{};
+    if (gp_sorted || gx_fused) {
+        stream_k = launch_sort(s, ws, ws_sorted, hs);
+        gy_k = launch_gy_tiles(s, grad_y_dev, ws + w.gy_tiles, hs);
+    }
     if (gp_small) {
         launch_backward_coef_small(s, ws, grad_y_dev, grad_coef_dev, !overwrite, hs);
     } else if (gp_sorted && !gx_fused) {
-        launch_backward_coef_sorted(s, stream_k, grad_y_dev, grad_coef_dev, !overwrite, hs);
+        launch_backward_coef_sorted(s, stream_k, gy_k, grad_coef_dev, !overwrite, hs);
     } else if (grad_coef_dev && !gx_fused) {
         // odd output counts or unaligned buffers: atomics on a gradient that starts at zero
         if (overwrite) launch_fill_zero(grad_coef_dev, (size_t)s.nodes() * s.pairs() * s.n_out, hs);
@@ -358,7 +363,7 @@ lmkan_status backward_impl(const lmkan_desc *desc, int64_t batch, const float *x
     if (gx_fused) {
         // one walk over the cell-sorted samples yields both gradients (the coefficient gradient
         // qualifies whenever the input gradient does)
-        launch_backward_fused(s, tab, stream_k, ws, coef_dev, grad_y_dev, grad_x_dev, grad_coef_dev, !overwrite, ws_partial,
+        launch_backward_fused(s, tab, stream_k, ws, coef_dev, gy_k, grad_x_dev, grad_coef_dev, !overwrite, ws_partial,
                               conv ? ws_scratch : nullptr, hs);
         if (conv) launch_input_gradient_out(ws_scratch, grad_x_dev, s, conv, hs);
     } else if (gx_small) {

@@ -50,7 +50,7 @@ struct FusedArgs {
     const f4v *rec;
     const int32_t *chunk_cell;
     const int32_t *block_start;
-    const float *gy;
+    GyView gy;
     const void *P;
     float *gP;        // NULL: input gradient only
     float2 *partial;  // [tiles][K][S]
@@ -134,8 +134,9 @@ __global__ __launch_bounds__(64) void backward_fused_kernel(FusedArgs a)
     const f4v *e_ptr = rec_k + (l16 >> 2) * kChunk + g;
     auto load_e = [&](int chunk) { return e_ptr[(int64_t)chunk * kChunk]; };
 
-    const unsigned col_bytes = (unsigned)(col_ok ? col : 0) * 4u;
-    const unsigned row_bytes = (unsigned)a.n_out * 4u;
+    const unsigned col_bytes = col_ok ? (unsigned)l16 * 16u : 0u;
+    const unsigned row_bytes = a.gy.row_stride;
+    const char *gy_tile = reinterpret_cast<const char *>(a.gy.base) + (int64_t)jt * a.gy.tile_stride;
     // gy row piece of sample g of the chunk whose row offset sits in lane (g, 4 SUB) of off16
     // (the byte offset of the sample's row when it fits 32 bits, else the sample index)
     auto row_offset = [&](int n) { return kOffset32 ? (int)__umul24((unsigned)n, row_bytes) : n; };
@@ -144,11 +145,10 @@ __global__ __launch_bounds__(64) void backward_fused_kernel(FusedArgs a)
         if constexpr (kOffset32) {
             // one instruction: (offset of lane 4 SUB of this row) + this lane's column bytes
             const unsigned off = (unsigned)__builtin_amdgcn_update_dpp(0, off16, 0x150 + 4 * SUB, 0xf, 0xf, true) + col_bytes;
-            return *reinterpret_cast<const f4v *>(reinterpret_cast<const char *>(a.gy) + off);
+            return *reinterpret_cast<const f4v *>(gy_tile + off);
         } else {
             const int n = row_bcast<4 * SUB>(off16);
-            return *reinterpret_cast<const f4v *>(reinterpret_cast<const char *>(a.gy) +
-                                                  ((int64_t)n * row_bytes + col_bytes));
+            return *reinterpret_cast<const f4v *>(gy_tile + ((int64_t)n * row_bytes + col_bytes));
         }
     };
     // Rows of a cell as the input gradient wants them: the derivative along the first axis pairs
@@ -487,7 +487,7 @@ size_t fused_partial_bytes(const LayerShape &s)
 }
 
 void launch_backward_fused(const LayerShape &s, const GridTab &tab, const SortedStream &st, const void *records,
-                           const void *coef, const float *gy, float *gx, float *gcoef, bool accumulate,
+                           const void *coef, const GyView &gy, float *gx, float *gcoef, bool accumulate,
                            void *partial, float *gx_transposed, hipStream_t stream)
 {
     FusedArgs a;
@@ -530,7 +530,7 @@ void launch_backward_fused(const LayerShape &s, const GridTab &tab, const Sorted
 #undef LMKAN_FUSED_ROW
     // the last tile is ragged when the table has fewer columns than whole tiles
     const bool ragged = a.col_limit % kTile != 0;
-    const Kernel kernel = kernels[s.dtype][gcoef ? 1 : 0][gy_offsets_fit_32_bits(s) ? 1 : 0][ragged ? 1 : 0];
+    const Kernel kernel = kernels[s.dtype][gcoef ? 1 : 0][gy_offsets_fit_32_bits(s, gy) ? 1 : 0][ragged ? 1 : 0];
     {
         KernelTiming timing(stream, kTimeGradInput);
         kernel<<<grid, 64, lds, stream>>>(a);

@@ -76,9 +76,24 @@ SortedStream launch_sort(const LayerShape &s, const void *records, void *sorted,
 bool sorted_batch_ok(const LayerShape &s);
 // waves per (pair, output tile, block) of the walking kernels
 int stream_run_split(const LayerShape &s);
-bool gy_offsets_fit_32_bits(const LayerShape &s);
+
+// gy as the walking kernels gather it: the 64 columns of output tile t of row n start at
+// base + t * tile_stride + n * row_stride (bytes).  The gradient as the caller holds it,
+// [batch][n_out], is such a view with strides 256 and 4 n_out; but the rows of one tile then sit
+// 4 n_out bytes apart, a power-of-two stride for the usual widths, and pile up on a few sets of
+// the L2 (a 1 MB tile slice of a 4096-wide layer misses four times in ten).  For wide layers
+// launch_gy_tiles copies gy once into [tiles][batch][64] (columns past n_out zero), where a tile
+// slice is contiguous; for narrower ones it returns the view of gy itself.
+struct GyView {
+    const float *base;
+    int64_t tile_stride;
+    unsigned row_stride;
+};
+size_t gy_tiles_bytes(const LayerShape &s);
+GyView launch_gy_tiles(const LayerShape &s, const float *gy, void *tiles, hipStream_t stream);
+bool gy_offsets_fit_32_bits(const LayerShape &s, const GyView &gy);
 // coefficient gradient alone (lmkan_backward.hip)
-void launch_backward_coef_sorted(const LayerShape &s, const SortedStream &st, const float *gy, float *gcoef,
+void launch_backward_coef_sorted(const LayerShape &s, const SortedStream &st, const GyView &gy, float *gcoef,
                                  bool accumulate, hipStream_t stream);
 
 // input gradient, with the coefficient gradient when gcoef is not NULL (lmkan_backward_fused.hip).
@@ -86,7 +101,7 @@ void launch_backward_coef_sorted(const LayerShape &s, const SortedStream &st, co
 // gx_transposed is not NULL, to that scratch as [n_in][batch] (for the convolution).
 bool fused_backward_applicable(const LayerShape &s, const void *coef, const float *gy, const float *gcoef);
 void launch_backward_fused(const LayerShape &s, const GridTab &tab, const SortedStream &st, const void *records,
-                           const void *coef, const float *gy, float *gx, float *gcoef, bool accumulate,
+                           const void *coef, const GyView &gy, float *gx, float *gcoef, bool accumulate,
                            void *partial, float *gx_transposed, hipStream_t stream);
 
 // acc[i][q] += (product q of this group's sample) * gy[i] for the chunk whose products sit in

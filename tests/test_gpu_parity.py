@@ -67,6 +67,8 @@ SHAPES = [
     (300, 8, 20, 34),
     # a batch long enough for the coefficient gradient to sort it block by block
     (13000, 6, 68, 5),
+    # rows wide enough for the sorted kernels to gather gy from a tile-by-tile copy (ragged last tile)
+    (600, 4, 2116, 9),
     # either side of the thresholds at which the dispatch changes kernels: 256 rows, 8 and 9
     # outputs, G = 16 / 17 and 34 / 35, 12288 rows
     (255, 6, 12, 8),
