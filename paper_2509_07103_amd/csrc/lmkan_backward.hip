@@ -424,23 +424,48 @@ __global__ __launch_bounds__(64) void backward_coef_stream_kernel(CoefGradArgs a
     // form its product q, so one load brings in four chunks (256 contiguous bytes); sample
     // indices: lane (g, j) fetches the index of group g's sample of chunk c + j, sixteen chunks
     // per load
-    const f4v *rec_k = a.rec + (int64_t)k * a.S + (int64_t)c_begin * kChunk;
-    const f4v *e_ptr = rec_k + (l16 >> 2) * kChunk + g;
-    const int32_t *n_ptr = reinterpret_cast<const int32_t *>(rec_k + l16 * kChunk + g) + 3;
-    auto load_e = [&](int chunk) { return e_ptr[(int64_t)chunk * kChunk]; };
-    auto load_n = [&](int chunk) { return n_ptr[(int64_t)chunk * (kChunk * 4)]; };
+    const f4v *rec_k = a.rec + (int64_t)k * a.S + (int64_t)c_begin * kChunk;  // wave-uniform
+    // The loads of the main loop are written as inline assembly, and so are the waits for them:
+    // vector loads return in the order they were issued, and with the cell changes branching
+    // inside the loop the compiler sizes its own waits for the worst path it can imagine, which
+    // drains the ring of gy values at every step (it emitted vmcnt(0) ... vmcnt(6) where 9 loads
+    // may stay in flight).  Every load below is issued at a fixed place of a trip, so the number
+    // of younger loads at the point of use is known; loads the compiler adds on the rare paths
+    // (row stores, atomics) only add to that number, which keeps the waits safe.
+    const unsigned e_off = (unsigned)(((l16 >> 2) * kChunk + g) * sizeof(f4v));
+    const unsigned n_off = (unsigned)((l16 * kChunk + g) * sizeof(f4v) + 12);
+    // (operands are copied into locals first: a name used only as an asm operand is not captured)
+    auto load_e = [&](f4v &dst, int chunk) {
+        const f4v *base = rec_k + (int64_t)chunk * kChunk;
+        const unsigned off = e_off;
+        asm volatile("global_load_dwordx4 %0, %1, %2" : "=v"(dst) : "v"(off), "s"(base) : "memory");
+    };
+    auto load_n = [&](int &dst, int chunk) {
+        const f4v *base = rec_k + (int64_t)chunk * kChunk;
+        const unsigned off = n_off;
+        asm volatile("global_load_dword %0, %1, %2" : "=v"(dst) : "v"(off), "s"(base) : "memory");
+    };
+    // blocks until at most N loads younger than the one that fills v are outstanding, i.e. until v has landed
+    auto landed = [](auto &v, auto nc) {
+        asm volatile("s_waitcnt vmcnt(%1)" : "+v"(v) : "n"(decltype(nc)::value) : "memory");
+    };
 
     const unsigned col_bytes = col_ok ? (unsigned)l16 * 16u : 0u;
     const unsigned row_bytes = a.gy.row_stride;
     const char *gy_tile = reinterpret_cast<const char *>(a.gy.base) + (int64_t)jt * a.gy.tile_stride;
-    auto load_gy = [&](auto subc, int n16) {
+    // what a lane keeps of the sixteen samples of a trip: the byte offset of the sample's row when
+    // every offset fits 32 bits (one multiply per trip; the broadcast to the group then folds into
+    // the add of the lane's column, a single DPP instruction per chunk), else the sample index
+    auto row_offset = [&](int n) { return kOffset32 ? (int)__umul24((unsigned)n, row_bytes) : n; };
+    auto load_gy = [&](f4v &dst, auto subc, int off16) {
         constexpr int SUB = decltype(subc)::value;
-        const int n = row_bcast<SUB>(n16);
         if constexpr (kOffset32) {
-            const unsigned off = __umul24((unsigned)n, row_bytes) + col_bytes;
-            return *reinterpret_cast<const f4v *>(gy_tile + off);
+            const unsigned off = (unsigned)row_bcast<SUB>(off16) + col_bytes;
+            const char *base = gy_tile;
+            asm volatile("global_load_dwordx4 %0, %1, %2" : "=v"(dst) : "v"(off), "s"(base) : "memory");
         } else {
-            return *reinterpret_cast<const f4v *>(gy_tile + ((int64_t)n * row_bytes + col_bytes));
+            const char *ptr = gy_tile + ((int64_t)row_bcast<SUB>(off16) * row_bytes + col_bytes);
+            asm volatile("global_load_dwordx4 %0, %1, off" : "=v"(dst) : "v"(ptr) : "memory");
         }
     };
 
@@ -501,30 +526,27 @@ __global__ __launch_bounds__(64) void backward_coef_stream_kernel(CoefGradArgs a
         // Software pipeline, all through in-order vector loads: at step P of a trip the chunk
         // c + P is consumed and the gy values of chunk c + P + kDepth are requested (their sample
         // indices were loaded a trip earlier); a register of products is refilled for the next
-        // trip as soon as its fourth chunk has been consumed.
+        // trip as soon as its fourth chunk has been consumed.  Order of issue in a trip: the
+        // indices of the next trip, then per step one gy load, after every fourth step one load
+        // of entries: 21 loads.
         f4v eq[kUnroll / kPerW];   // entries as loaded
         float wq[kUnroll / kPerW];  // their products, formed when the first of the four chunks is consumed
         f4v gq[kDepth];
         int n_now, n_nxt;
         // The fill is issued in the order the steady state leaves the loads in at the top of a
         // trip, so that the wait counts of the first steps are those of every other trip.
-        n_now = load_n(0);
+        load_n(n_now, 0);
         static_for(std::make_integer_sequence<int, kUnroll / kPerW>{}, [&](auto rc) {
             constexpr int r = decltype(rc)::value;
-            if constexpr (r * kPerW < kUnroll - kDepth) {
-                eq[r] = load_e(r * kPerW);
-                __builtin_amdgcn_sched_barrier(0);
-            }
+            if constexpr (r * kPerW < kUnroll - kDepth) load_e(eq[r], r * kPerW);
         });
+        landed(n_now, std::integral_constant<int, (kUnroll - kDepth) / kPerW>{});
+        n_now = row_offset(n_now);
         static_for(std::make_integer_sequence<int, kDepth>{}, [&](auto dc) {
             constexpr int d = decltype(dc)::value;
             constexpr int P = kUnroll - kDepth + d;  // the step that requests this chunk in later trips
-            gq[d] = load_gy(std::integral_constant<int, d>{}, n_now);
-            __builtin_amdgcn_sched_barrier(0);
-            if constexpr (P % kPerW == kPerW - 1) {
-                eq[P / kPerW] = load_e((P / kPerW) * kPerW);
-                __builtin_amdgcn_sched_barrier(0);
-            }
+            load_gy(gq[d], std::integral_constant<int, d>{}, n_now);
+            if constexpr (P % kPerW == kPerW - 1) load_e(eq[P / kPerW], (P / kPerW) * kPerW);
         });
         // cells of a whole trip are fetched one trip ahead (scalar loads return out of order, so
         // every use waits for all of them: keep them few and early)
@@ -535,11 +557,23 @@ __global__ __launch_bounds__(64) void backward_coef_stream_kernel(CoefGradArgs a
         for (int c = 0; c < nch; c += kUnroll) {
 #pragma unroll
             for (int p = 0; p < kUnroll; ++p) cells_nxt[p] = cc[c + kUnroll + p];
-            n_nxt = load_n(c + kUnroll);
+            load_n(n_nxt, c + kUnroll);
             static_for(std::make_integer_sequence<int, kUnroll>{}, [&](auto pc) {
                 constexpr int P = decltype(pc)::value;
                 const int cell_cur = cells_now[P];
-                if constexpr (P % kPerW == 0) wq[P / kPerW] = entry_product(eq[P / kPerW], l16 & 3);
+                // Younger loads at this point.  A gy value: the 7 gy loads after it and two loads
+                // of entries (three in the first trip, four when the top of a trip lies between).
+                // Entries: 16 (12 for the first register in the first trip).  Indices: 8 gy loads
+                // and 2 loads of entries.
+                if constexpr (P == kUnroll - kDepth) {
+                    landed(n_nxt, std::integral_constant<int, kDepth + kDepth / kPerW>{});
+                    n_nxt = row_offset(n_nxt);  // first needed below
+                }
+                if constexpr (P % kPerW == 0) {
+                    landed(eq[P / kPerW], std::integral_constant<int, P == 0 ? 12 : 15>{});
+                    wq[P / kPerW] = entry_product(eq[P / kPerW], l16 & 3);
+                }
+                landed(gq[P % kDepth], std::integral_constant<int, kDepth - 1 + kDepth / kPerW>{});
                 if (cell_cur != cur_cell) {
                     if (cur_cell >= 0) flush();
                     retire_rows(cell_cur >> 8);
@@ -548,14 +582,16 @@ __global__ __launch_bounds__(64) void backward_coef_stream_kernel(CoefGradArgs a
                 } else {
                     chunk_fma<P % kPerW, false>(acc, wq[P / kPerW], gq[P % kDepth]);
                 }
-                gq[P % kDepth] = load_gy(std::integral_constant<int, (P + kDepth) % kUnroll>{},
-                                         P + kDepth < kUnroll ? n_now : n_nxt);
-                if constexpr (P % kPerW == kPerW - 1) eq[P / kPerW] = load_e(c + kUnroll + (P / kPerW) * kPerW);
+                load_gy(gq[P % kDepth], std::integral_constant<int, (P + kDepth) % kUnroll>{},
+                        P + kDepth < kUnroll ? n_now : n_nxt);
+                if constexpr (P % kPerW == kPerW - 1) load_e(eq[P / kPerW], c + kUnroll + (P / kPerW) * kPerW);
             });
             n_now = n_nxt;
 #pragma unroll
             for (int p = 0; p < kUnroll; ++p) cells_now[p] = cells_nxt[p];
         }
+        // nothing may still be on its way to a register once the compiler is free to reuse it
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     }
     if (cur_cell >= 0) flush();
     retire_rows(split ? min(W, (cur_cell >> 8) + 2) : W);
