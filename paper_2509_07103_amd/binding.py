@@ -154,6 +154,21 @@ def _stream(stream) -> int:
     return stream.cuda_stream if hasattr(stream, "cuda_stream") else int(stream)
 
 
+def _used_on(stream, *tensors) -> None:
+    """Tells torch's caching allocator that `tensors` (what a call allocated itself: the workspace it
+    frees on return, the outputs it hands back) are in use on `stream` when that is not the current
+    stream: their memory is then not given out again before the work queued there has finished."""
+    if stream is None:
+        return
+    handle = _stream(stream)
+    if handle == torch.cuda.current_stream().cuda_stream:
+        return
+    s = stream if isinstance(stream, torch.cuda.Stream) else torch.cuda.ExternalStream(handle)
+    for t in tensors:
+        if t is not None:
+            t.record_stream(s)
+
+
 def _dev(t: torch.Tensor | None, dtype, shape, name: str) -> int | None:
     if t is None:
         return None
@@ -216,6 +231,7 @@ def lmkan_pack(desc: LayerDesc, coef: torch.Tensor, stream=None) -> torch.Tensor
     nbytes = lmkan_packed_bytes(desc)
     out = torch.empty(nbytes // coef.element_size(), dtype=dt, device=coef.device)
     _check(lib().lmkan_pack(C.byref(desc.c()), src, out.data_ptr(), _stream(stream)), "lmkan_pack")
+    _used_on(stream, out)
     return out
 
 
@@ -236,6 +252,7 @@ def lmkan_locate(desc: LayerDesc, x: torch.Tensor, stream=None) -> torch.Tensor:
     cell = torch.empty((batch, desc.pairs), dtype=torch.int32, device=x.device)
     _check(lib().lmkan_locate(C.byref(desc.c()), batch, xp, cell.data_ptr(), _stream(stream)),
            "lmkan_locate")
+    _used_on(stream, cell)
     return cell
 
 
@@ -251,6 +268,7 @@ def lmkan_forward(desc: LayerDesc, x: torch.Tensor, coef: torch.Tensor, y: torch
     _check(lib().lmkan_forward(C.byref(desc.c()), batch, xp, cp, yp,
                                ws.data_ptr() if ws is not None else None, wsz, _stream(stream)),
            "lmkan_forward")
+    _used_on(stream, ws, y)
     return y
 
 
@@ -287,6 +305,7 @@ def lmkan_backward(desc: LayerDesc, x: torch.Tensor, coef: torch.Tensor | None, 
     _check(lib().lmkan_backward(C.byref(desc.c()), batch, xp, cp, gyp, gxp, gcp,
                                 ws.data_ptr() if ws is not None else None, wsz, _stream(stream)),
            "lmkan_backward")
+    _used_on(stream, ws, grad_x, grad_coef)
     return (grad_x if need_grad_x else None), (grad_coef if need_grad_coef else None)
 
 
@@ -338,6 +357,7 @@ def lmkan_conv2d_forward(desc: LayerDesc, conv: Conv2d, x: torch.Tensor, coef: t
     _check(lib().lmkan_conv2d_forward(C.byref(desc.c()), C.byref(conv.c()), xp, cp, yp,
                                       ws.data_ptr() if ws is not None else None, wsz, _stream(stream)),
            "lmkan_conv2d_forward")
+    _used_on(stream, ws, y)
     return y
 
 
@@ -362,6 +382,7 @@ def lmkan_conv2d_backward(desc: LayerDesc, conv: Conv2d, x: torch.Tensor, coef: 
     _check(lib().lmkan_conv2d_backward(C.byref(desc.c()), C.byref(conv.c()), xp, cp, gyp, gxp, gcp,
                                        ws.data_ptr() if ws is not None else None, wsz, _stream(stream)),
            "lmkan_conv2d_backward")
+    _used_on(stream, ws, grad_x, grad_coef)
     return (grad_x if need_grad_x else None), (grad_coef if need_grad_coef else None)
 
 
@@ -378,6 +399,7 @@ def lmkan_hessian_reg(desc: LayerDesc, coef: torch.Tensor, scale: float = 1.0, n
     _check(lib().lmkan_hessian_reg(C.byref(desc.c()), cp, float(scale),
                                    value.data_ptr() if need_value else None, gcp, _stream(stream)),
            "lmkan_hessian_reg")
+    _used_on(stream, value, grad_coef)
     return value, (grad_coef if need_grad else None)
 
 

@@ -124,6 +124,26 @@ def test_static_scratch_forward_rejects_what_does_not_fit_before_any_launch():
     assert L.lmkan_forward_static(C.byref(_desc(grid=2).c()), 4, ok, ok, ok, None) == 2
 
 
+def test_workspace_sizes_follow_the_limits_of_the_sorted_path():
+    """The cell-sorted kernels index stream positions with 32 bits and launch one workgroup per 4096
+    samples in the second grid dimension (at most 65535): batches beyond that go to the generic
+    kernels, and the workspace no longer holds a sorted stream.  Sizes are size_t: no overflow up
+    to the largest batch the header admits."""
+    d = _desc(n_in=4, n_out=64, grid=4)
+    limit = 65535 * 4096                       # the longest batch the sort takes
+    records = 3 * 2 * 4                        # bytes per row: (node, u, v) for each of the 2 pairs
+    with_sort = pkg.lmkan_workspace_bytes(d, limit, True, need_grad_x=False)
+    without = pkg.lmkan_workspace_bytes(d, limit + 1, True, need_grad_x=False)
+    assert with_sort >= limit * (records + 2 * 16)          # records + one 16-byte entry per pair and sample
+    assert (limit + 1) * records <= without < (limit + 1) * records + 4096
+    assert pkg.lmkan_workspace_bytes(d, limit, True) > with_sort    # grad_x adds its scratch
+    max_batch = 2147483647                     # LMKAN_MAX_BATCH
+    top = pkg.lmkan_workspace_bytes(d, max_batch, True)
+    assert top >= max_batch * records
+    # forward only: the records alone, whatever the batch
+    assert pkg.lmkan_workspace_bytes(d, limit + 1, False) >= (limit + 1) * records
+
+
 def test_packed_size_pads_outputs_to_the_tile():
     for n_out, tiles in ((1, 1), (64, 1), (65, 2), (1024, 16)):
         for dt, sz in ((binding.LMKAN_F32, 4), (binding.LMKAN_F16, 2), (binding.LMKAN_BF16, 2)):

@@ -217,11 +217,17 @@ def test_cfg2_inference_stack_with_folded_normalisation(dev, oracle):
             pkg.lmkan_fold(paper, folded, 1.0, None, None, scale.to(dev), shift.to(dev))
         else:
             folded = P
+        a_in = a_dev.cpu().numpy()[rows]    # what this layer was given on the device
         a_dev = pkg.lmkan_forward(packed, a_dev, pkg.lmkan_pack(paper, folded))
         torch.cuda.synchronize()
         y = oracle.forward(a_ref, P.cpu().numpy(), w.grid, threads=THREADS)
+        # every layer on its own, to the single-layer bar: the oracle is fed the device's own
+        # activations, so nothing of the earlier layers' rounding enters the comparison
+        y_own = oracle.forward(a_in, P.cpu().numpy(), w.grid, threads=THREADS)
         if not last:
             y = y * scale.numpy().astype(np.float64) + shift.numpy().astype(np.float64)
+            y_own = y_own * scale.numpy().astype(np.float64) + shift.numpy().astype(np.float64)
+        assert _rel_err(a_dev.cpu().numpy()[rows], y_own) <= TOL_F32, i
         err = _rel_err(a_dev.cpu().numpy()[rows], y)
         worst = max(worst, err)
         # float32 rounding of one layer is ~1e-6 of the row scale; later layers see it magnified by

@@ -217,6 +217,14 @@ def test_sorted_paths_repeat_bit_for_bit(dev):
     gxs = [pkg.lmkan_backward(desc, x, P, gy)[0] for _ in range(3)]
     torch.cuda.synchronize()
     assert torch.equal(gxs[0], gxs[1]) and torch.equal(gxs[0], gxs[2])
+    # enough (pair, tile) streams to fill the chip, so that none is cut into runs (256 pairs x 16
+    # tiles), many trips per wave, several waves per CU
+    B, n_in, n_out, G = 2000, 512, 1024, 8
+    x, P, gy = _inputs(B, n_in, n_out, G, 53, dev)
+    desc = _desc(n_in, n_out, G)
+    runs = [pkg.lmkan_backward(desc, x, None, gy, need_grad_x=False)[1] for _ in range(2)]
+    torch.cuda.synchronize()
+    assert torch.equal(runs[0], runs[1])
 
 
 def test_empty_batch(dev):
@@ -278,6 +286,25 @@ def test_results_do_not_depend_on_the_stream(dev, oracle):
     s.synchronize()
     torch.cuda.synchronize()
     assert torch.equal(y0, y1)
+    # a stream passed by argument while another one is current: the binding's own allocations
+    # (the workspace it frees on return, the outputs) must survive allocations made meanwhile on
+    # the current stream
+    B, n_in, n_out, G = 4000, 64, 128, 12      # large enough for a workspace
+    x, P, gy = _inputs(B, n_in, n_out, G, 62, dev)
+    desc = _desc(n_in, n_out, G)
+    want_y = pkg.lmkan_forward(desc, x, P)
+    want_gx, want_gp = pkg.lmkan_backward(desc, x, P, gy)
+    torch.cuda.synchronize()
+    s.wait_stream(torch.cuda.current_stream())
+    y2 = pkg.lmkan_forward(desc, x, P, stream=s)
+    gx2, gp2 = pkg.lmkan_backward(desc, x, P, gy, stream=s)
+    junk = [torch.full((1 << 20,), float(i), device=dev) for i in range(16)]   # current stream
+    s.synchronize()
+    torch.cuda.synchronize()
+    assert torch.equal(want_y, y2)
+    assert rowwise_rel_err(gx2.cpu().numpy(), want_gx.cpu().numpy().astype(np.float64)) <= TOL_F32
+    assert torch.allclose(gp2, want_gp, rtol=1e-4, atol=1e-5)
+    del junk
 
 
 # ---- Hessian regulariser (Sec. 3.5, App. C) ---------------------------------------------------
@@ -316,9 +343,20 @@ def test_hessian_reg_is_zero_on_linear_tables(dev, oracle):
     P = lin[:, :, None, None].expand(G + 1, G + 1, n_in // 2, n_out).contiguous().to(dev)
     value, grad = pkg.lmkan_hessian_reg(_desc(n_in, n_out, G), P)
     torch.cuda.synchronize()
-    # float32 second differences of O(1) values over spacings down to 0.1: rounding only
-    assert float(value.cpu()[0]) < 1e-6 * n_in * n_out
-    assert float(grad.abs().max()) < 1e-2
+    # Exactly zero for an exactly linear table; what is left is rounding.  The table itself is
+    # linear only up to float32 rounding of its entries (a relative 2^-24 of values up to
+    # |P|max), and a second difference divides such an error by a product of two spacings:
+    # derivative errors up to 4 * 2^-24 |P|max / hmin^2 on either side, squared and averaged in the
+    # value, times the same 1 / h^2 factors (over the (G-1)^2 interior nodes) in the gradient.
+    Pmax = float(P.abs().max())
+    h = np.diff(E.numpy().astype(np.float64))
+    d_err = 4.0 * 2.0 ** -24 * Pmax / h.min() ** 2
+    assert float(value.cpu()[0]) <= 4.0 * d_err ** 2 * (n_in // 2) * n_out
+    assert float(grad.abs().max()) <= 16.0 * d_err / h.min() ** 2 / (G - 1) ** 2
+    # and the double-precision oracle, on the same float32 table, agrees to the same bound
+    want_v, want_g = oracle.hessian_reg(P.cpu().numpy(), G)
+    assert np.abs(grad.cpu().numpy() - want_g).max() <= 16.0 * d_err / h.min() ** 2 / (G - 1) ** 2
+    assert want_v <= 4.0 * d_err ** 2 * (n_in // 2) * n_out
 
 
 # ---- inference-time folds (App. E Eq. 4b, App. F.1) -------------------------------------------
