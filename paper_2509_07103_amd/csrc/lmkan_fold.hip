@@ -27,22 +27,30 @@ struct FoldArgs {
     int K;
 };
 
-// grid: x over (k, j) columns in units of 256 threads, y over table nodes
+// grid: x over (k, j) columns in units of 256 threads, y over the first node index; a thread
+// walks the second one, so that its two linear weights and its per-output terms (strided,
+// uncoalesced reads) are fetched once per table row rather than once per node
 __global__ __launch_bounds__(256) void fold_kernel(FoldArgs a)
 {
     const int64_t col = (int64_t)blockIdx.x * 256 + threadIdx.x;
     if (col >= (int64_t)a.K * a.n_out) return;
     const int k = (int)(col / a.n_out), j = (int)(col - (int64_t)k * a.n_out);
     const int W = a.tab.G + 1;
-    const int node = blockIdx.y, ia = node / W, ib = node - ia * W;
-    const float ra = fmaxf(a.tab.node[ia], 0.0f), rb = fmaxf(a.tab.node[ib], 0.0f);
-    float *p = a.P + (int64_t)node * a.map.s_node + (int64_t)k * a.map.s_pair + (int64_t)(j >> 6) * a.map.s_tile + (j & 63);
-    float v = a.gamma * *p;
-    if (a.lin_w) v += a.lin_w[(int64_t)j * a.n_in + 2 * k] * ra + a.lin_w[(int64_t)j * a.n_in + 2 * k + 1] * rb;
+    const int ia = blockIdx.y;
+    const float ra = fmaxf(a.tab.node[ia], 0.0f);
+    const float wa = a.lin_w ? a.lin_w[(int64_t)j * a.n_in + 2 * k] : 0.0f;
+    const float wb = a.lin_w ? a.lin_w[(int64_t)j * a.n_in + 2 * k + 1] : 0.0f;
     const float s = a.scale ? a.scale[j] : 1.0f;
-    v *= s;
-    if (k == 0) v += s * (a.lin_b ? a.lin_b[j] : 0.0f) + (a.shift ? a.shift[j] : 0.0f);
-    *p = v;
+    const float c = k == 0 ? s * (a.lin_b ? a.lin_b[j] : 0.0f) + (a.shift ? a.shift[j] : 0.0f) : 0.0f;
+    float *p = a.P + (int64_t)ia * W * a.map.s_node + (int64_t)k * a.map.s_pair + (int64_t)(j >> 6) * a.map.s_tile + (j & 63);
+    for (int ib = 0; ib < W; ++ib, p += a.map.s_node) {
+        const float rb = fmaxf(a.tab.node[ib], 0.0f);
+        float v = a.gamma * *p;
+        if (a.lin_w) v += wa * ra + wb * rb;
+        v *= s;
+        if (k == 0) v += c;
+        *p = v;
+    }
 }
 
 }  // namespace
@@ -63,7 +71,7 @@ void launch_fold(const LayerShape &s, const GridTab &tab, float *coef, float gam
     a.n_out = s.n_out;
     a.K = s.pairs();
     const int64_t cols = (int64_t)s.pairs() * s.n_out;
-    const dim3 grid((unsigned)((cols + 255) / 256), (unsigned)s.nodes());
+    const dim3 grid((unsigned)((cols + 255) / 256), (unsigned)(s.G + 1));
     fold_kernel<<<grid, 256, 0, stream>>>(a);
 }
 

@@ -154,6 +154,19 @@ def test_backward_matches_oracle(dev, oracle, shape, storage, layout):
         master = oracle.backward_input(xh, P.cpu().numpy(), gyh, G)
         diff = np.linalg.norm(gx.cpu().numpy().astype(np.float64) - master)
         assert diff <= TOL_HALF * np.linalg.norm(master)
+        # element by element, to the bound the arithmetic gives: an input gradient is 1/h times a
+        # weighted sum over j of gy[n][j] times differences of two stored coefficients, each of
+        # which is off by at most one unit roundoff u of the storage format times |P|max
+        # (the two differences enter with weights 1 - t and t of the pair's *other* coordinate,
+        # |1 - t| + |t| = 1 inside the grid and 1 + 2 (distance past the outermost point) / h beyond it,
+        # where every function continues linearly)
+        u = 2.0 ** -11 if storage == "f16" else 2.0 ** -8
+        E = oracle.grid_f32(G).astype(np.float64)
+        inv_h = 1.0 / np.diff(E).min()
+        beyond = np.maximum(np.abs(xh.astype(np.float64)) - E[G], 0.0) / (E[G] - E[G - 1])
+        other = (1.0 + 2.0 * beyond).reshape(B, n_in // 2, 2)[:, :, ::-1].reshape(B, n_in)
+        bound = 2.0 * u * float(P.abs().max()) * inv_h * other * np.abs(gyh.astype(np.float64)).sum(axis=1, keepdims=True)
+        assert np.all(np.abs(gx.cpu().numpy().astype(np.float64) - master) <= bound + 1e-30)
 
 
 # one shape per way the coefficient gradient can be formed: float32 atomics in the generic
