@@ -487,8 +487,7 @@ struct GradRecord {
 // the row) ends up with the derivative b3 (d/dx1 or d/dx2) of step 4 b0 + 2 b1 + b2 of the
 // eight.  15 instructions per eight steps and derivative pair instead of 32.
 //
-// stage 1 (this function), lanes 8 apart: lanes 0-7 of a row keep d/dx1, lanes 8-15 d/dx2.
-// A DPP add with a bank mask writes only the enabled quarter rows, so no select is needed.
+// The stages are grad_fold_halves / _steps / _pairs in lmkan_slab_common.h.
 template <int S>
 __device__ __forceinline__ float grad_step(const float4 g, const Corners &c, const GradRecord &r)
 {
@@ -500,30 +499,7 @@ __device__ __forceinline__ float grad_step(const float4 g, const Corners &c, con
     fmac_row_bcast<S>(t1, r.b_hi, s11 - s01);
     float t2 = mul_row_bcast<S>(r.a_lo, s01 - s00);
     fmac_row_bcast<S>(t2, r.a_hi, s11 - s10);
-    float v;
-    asm("v_add_f32_dpp %0, %1, %1 row_ror:8 row_mask:0xf bank_mask:0x3" : "=v"(v) : "v"(t1));
-    asm("v_add_f32_dpp %0, %1, %1 row_ror:8 row_mask:0xf bank_mask:0xc" : "+v"(v) : "v"(t2));
-    return v;
-}
-
-// stage 2, lanes 4 apart: quarter rows 0 and 2 keep the even step (and add what the quarter row
-// above holds of it), quarter rows 1 and 3 the odd one
-__device__ __forceinline__ float grad_fold_steps(float even, float odd)
-{
-    float w;
-    asm("v_add_f32_dpp %0, %1, %1 row_ror:12 row_mask:0xf bank_mask:0x5" : "=v"(w) : "v"(even));
-    asm("v_add_f32_dpp %0, %1, %1 row_ror:4 row_mask:0xf bank_mask:0xa" : "+v"(w) : "v"(odd));
-    return w;
-}
-
-// stages 3 and 4, lanes 2 and 1 apart: lanes with bit 1 clear keep the first pair of steps
-__device__ __forceinline__ float grad_fold_pairs(float first, float second, bool second_half)
-{
-    const float keep = second_half ? second : first;
-    const float send = second_half ? first : second;
-    float z = keep + dpp_move<0x4E>(send);  // quad_perm [2,3,0,1]
-    z += dpp_move<0xB1>(z);                 // quad_perm [1,0,3,2]
-    return z;
+    return grad_fold_halves(t1, t2);
 }
 
 template <typename CT, int WAVES, int SETS, int AHEAD, int W_CT>

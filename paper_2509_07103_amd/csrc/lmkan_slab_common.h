@@ -143,4 +143,35 @@ __device__ __forceinline__ float dpp_move(float v)
     return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), CTRL, 0xf, 0xf, false));
 }
 
+// Cross-lane sums of the 64-output input-gradient kernels, in three pieces (see grad_step in
+// lmkan_slab.hip).  stage 1, lanes 8 apart: lanes 0-7 of a row keep d/dx1 (t1), lanes 8-15 d/dx2
+// (t2).  A DPP add with a bank mask writes only the enabled quarter rows, so no select is needed.
+__device__ __forceinline__ float grad_fold_halves(float t1, float t2)
+{
+    float v;
+    asm("v_add_f32_dpp %0, %1, %1 row_ror:8 row_mask:0xf bank_mask:0x3" : "=v"(v) : "v"(t1));
+    asm("v_add_f32_dpp %0, %1, %1 row_ror:8 row_mask:0xf bank_mask:0xc" : "+v"(v) : "v"(t2));
+    return v;
+}
+
+// stage 2, lanes 4 apart: quarter rows 0 and 2 keep the even step (and add what the quarter row
+// above holds of it), quarter rows 1 and 3 the odd one
+__device__ __forceinline__ float grad_fold_steps(float even, float odd)
+{
+    float w;
+    asm("v_add_f32_dpp %0, %1, %1 row_ror:12 row_mask:0xf bank_mask:0x5" : "=v"(w) : "v"(even));
+    asm("v_add_f32_dpp %0, %1, %1 row_ror:4 row_mask:0xf bank_mask:0xa" : "+v"(w) : "v"(odd));
+    return w;
+}
+
+// stages 3 and 4, lanes 2 and 1 apart: lanes with bit 1 clear keep the first pair of steps
+__device__ __forceinline__ float grad_fold_pairs(float first, float second, bool second_half)
+{
+    const float keep = second_half ? second : first;
+    const float send = second_half ? first : second;
+    float z = keep + dpp_move<0x4E>(send);  // quad_perm [2,3,0,1]
+    z += dpp_move<0xB1>(z);                 // quad_perm [1,0,3,2]
+    return z;
+}
+
 }  // namespace lmkan

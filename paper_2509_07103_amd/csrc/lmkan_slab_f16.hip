@@ -206,23 +206,18 @@ __device__ __forceinline__ float dot4_h(const float4 g, const h4v c)
     return fmaf(g.w, (float)c[3], fmaf(g.z, (float)c[2], fmaf(g.y, (float)c[1], g.x * (float)c[0])));
 }
 
-// returns, in lanes 0-7 of each row, the row's d/dx1 and, in lanes 8-15, its d/dx2
+// first stage of the sum over the row (lanes 0-7: d/dx1, lanes 8-15: d/dx2); the other stages
+// fold the results of eight steps together, as in backward_input_slab_kernel
 template <int S>
 __device__ __forceinline__ float grad_step_h(const float4 g, const CornersH &c, float b_lo, float b_hi, float a_lo,
-                                             float a_hi, bool upper)
+                                             float a_hi)
 {
     const float s00 = dot4_h(g, c.c00), s10 = dot4_h(g, c.c10), s01 = dot4_h(g, c.c01), s11 = dot4_h(g, c.c11);
     float t1 = mul_row_bcast_h<S>(b_lo, s10 - s00);
     fmac_row_bcast<S>(t1, b_hi, s11 - s01);
     float t2 = mul_row_bcast_h<S>(a_lo, s01 - s00);
     fmac_row_bcast<S>(t2, a_hi, s11 - s10);
-    const float keep = upper ? t2 : t1;
-    const float send = upper ? t1 : t2;
-    float v = keep + dpp_move<0x128>(send);  // row_ror:8
-    v += dpp_move<0xB1>(v);                  // quad_perm [1,0,3,2]
-    v += dpp_move<0x4E>(v);                  // quad_perm [2,3,0,1]
-    v += dpp_move<0x141>(v);                 // row_half_mirror
-    return v;
+    return grad_fold_halves(t1, t2);
 }
 
 // Input gradient, the mirror of the forward kernel (see backward_input_slab_kernel in
@@ -261,7 +256,8 @@ __global__ __launch_bounds__(kWaves * 64) __attribute__((amdgpu_waves_per_eu(4, 
 
     const int64_t n_wave = (int64_t)btile * kTileB + (int64_t)wave * 64;
     const int col = jt * kTile + l16 * 4;
-    const bool upper = (l16 & 8) != 0;
+    // the step of a block of eight whose result this lane ends up with
+    const int my_step = ((l16 & 1) << 2) | (l16 & 2) | ((l16 >> 2) & 1);
 
     // gy of (sample n_wave + 16 g + step, outputs col .. col+3), resident for the walk
     float4 gyr[16];
@@ -296,10 +292,10 @@ __global__ __launch_bounds__(kWaves * 64) __attribute__((amdgpu_waves_per_eu(4, 
         fetch_record(k_begin);
     }
     const int lane_bytes = l16 * 8;
-    const int64_t n_lane = n_wave + g * 16 + (l16 & 7);
-    // kScratchOct layout of the scratch rows: the first eight steps land at 8 g + (l16 & 7), the
+    const int64_t n_lane = n_wave + g * 16 + my_step;
+    // kScratchOct layout of the scratch rows: the first eight steps land at 8 g + step, the
     // other eight 32 further
-    float *gx_lane = a.gx + (int64_t)(l16 >> 3) * a.ld + n_wave + g * 8 + (l16 & 7);
+    float *gx_lane = a.gx + (int64_t)(l16 >> 3) * a.ld + n_wave + g * 8 + my_step;
 
     for (int k = k_begin; k < k_end; ++k) {
         const unsigned cur = ((k - k_begin) & 1) ? base1 : base0;
@@ -321,16 +317,28 @@ __global__ __launch_bounds__(kWaves * 64) __attribute__((amdgpu_waves_per_eu(4, 
         const int lane_base = (int)cur + lane_bytes;
         load_corners_h<0>(ring[0], lane_base, off, a.W);
         load_corners_h<1>(ring[1], lane_base, off, a.W);
-        float stash = 0.0f;
+        float v_even = 0.0f, w_first = 0.0f, z_first = 0.0f;  // results waiting for their partners
         static_for(std::make_integer_sequence<int, 16>{}, [&](auto tc) {
             constexpr int T = decltype(tc)::value;
             if constexpr (T + kAheadH < 16)
                 load_corners_h<T + kAheadH>(ring[(T + kAheadH) % (kAheadH + 1)], lane_base, off, a.W);
-            const float v = grad_step_h<T>(gyr[T], ring[T % (kAheadH + 1)], b_lo, b_hi, a_lo, a_hi, upper);
-            if ((l16 & 7) == (T & 7)) stash = v;
-            if constexpr ((T & 7) == 7) {
-                const int64_t n = n_lane + (T & ~7);
-                if (n < a.B) unsafeAtomicAdd(gx_lane + (int64_t)(2 * k) * a.ld + (T >> 3) * 32, stash);
+            const float v = grad_step_h<T>(gyr[T], ring[T % (kAheadH + 1)], b_lo, b_hi, a_lo, a_hi);
+            if constexpr ((T & 1) == 0) {
+                v_even = v;
+            } else {
+                const float w = grad_fold_steps(v_even, v);
+                if constexpr ((T & 3) == 1) {
+                    w_first = w;
+                } else {
+                    const float z = grad_fold_pairs(w_first, w, (l16 & 2) != 0);
+                    if constexpr ((T & 7) == 3) {
+                        z_first = z;
+                    } else {
+                        const float mine = (l16 & 1) ? z : z_first;
+                        const int64_t n = n_lane + (T & ~7);
+                        if (n < a.B) unsafeAtomicAdd(gx_lane + (int64_t)(2 * k) * a.ld + (T >> 3) * 32, mine);
+                    }
+                }
             }
         });
     }
