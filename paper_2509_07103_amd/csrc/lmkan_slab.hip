@@ -172,11 +172,12 @@ __device__ __forceinline__ void issue_slab_load(const SlabArgs &a, float *slab, 
 // buffer.  For float32 storage issue() is the LDS-direct load above and commit() is empty.
 constexpr int kMaxSlabBytes = 80 * 1024;  // one of the two slab buffers
 
-template <typename CT, int WAVES, int LPS = 16>
+// A slab that has LDS to itself (up to 160 KiB) is filled in four phases of the same size.
+template <typename CT, int WAVES, int LPS = 16, int PHASES = 2>
 struct SlabFill {
     static constexpr int NG = 64 / LPS;  // rows per 1 KiB chunk
-    static constexpr int kChunksPerWave = (kMaxSlabBytes / 1024 + WAVES - 1) / WAVES;
-    static constexpr int kPerPhase = (kChunksPerWave + 1) / 2;  // two phases keep the staging registers few
+    static constexpr int kChunksPerWave = (PHASES / 2 * kMaxSlabBytes / 1024 + WAVES - 1) / WAVES;
+    static constexpr int kPerPhase = (kChunksPerWave + PHASES - 1) / PHASES;  // phases keep the staging registers few
     uint2 v[kPerPhase];
 
     template <int PHASE>
@@ -217,8 +218,8 @@ struct SlabFill {
     }
 };
 
-template <int WAVES, int LPS>
-struct SlabFill<float, WAVES, LPS> {
+template <int WAVES, int LPS, int PHASES>
+struct SlabFill<float, WAVES, LPS, PHASES> {
     template <int PHASE>
     __device__ __forceinline__ void issue(const SlabArgs &a, float *slab, int k, int jt, int wave, int lane)
     {
@@ -709,7 +710,9 @@ __device__ __forceinline__ void fma_corners_quad(float *acc, const Corners &c, f
     fmac_quad_bcast<T>(acc[3], w11, c.c11.w);
 }
 
-template <typename CT, int WAVES, int SETS>
+// SINGLE: the slab fits LDS only once (35 <= G <= 48): no slab is fetched while another is
+// walked; the wave waits for its part of the fill and for the others' at the top of every pair.
+template <typename CT, int WAVES, int SETS, bool SINGLE = false>
 __global__ __launch_bounds__(WAVES * 64) __attribute__((amdgpu_waves_per_eu(WAVES / 4, WAVES / 4))) void forward_slab_narrow_kernel(
     SlabArgs a)
 {
@@ -733,7 +736,7 @@ __global__ __launch_bounds__(WAVES * 64) __attribute__((amdgpu_waves_per_eu(WAVE
     const int k_end = min(a.K, k_begin + a.pairs_per_split);
     const int slab_floats = a.nodes * kNarrowTile;
     float *slab0 = smem;
-    float *slab1 = smem + slab_floats;
+    float *slab1 = SINGLE ? smem : smem + slab_floats;
     const int64_t n_wave = (int64_t)btile * kTileB + (int64_t)wave * (SETS * 64);
 
     float acc[SETS * 16];
@@ -760,23 +763,33 @@ __global__ __launch_bounds__(WAVES * 64) __attribute__((amdgpu_waves_per_eu(WAVE
         }
     };
 
-    SlabFill<CT, WAVES, LPS> fill;
+    SlabFill<CT, WAVES, LPS, SINGLE ? 4 : 2> fill;
+    auto fill_whole = [&](int k) {  // every phase, one after the other
+        static_for(std::make_integer_sequence<int, SINGLE ? 4 : 2>{}, [&](auto pc) {
+            fill.template issue<decltype(pc)::value>(a, slab0, k, jt, wave, lane);
+            fill.template commit<decltype(pc)::value>(a, slab0, wave, lane);
+        });
+    };
     if (k_begin < k_end) {
 #pragma unroll
         for (int s = 0; s < SETS; ++s) fetch_record(s, k_begin);
-        fill.template issue<0>(a, slab0, k_begin, jt, wave, lane);
-        fill.template commit<0>(a, slab0, wave, lane);
-        fill.template issue<1>(a, slab0, k_begin, jt, wave, lane);
-        fill.template commit<1>(a, slab0, wave, lane);
+        fill_whole(k_begin);
     }
     const int lane_bytes = sub * 16;
     for (int k = k_begin; k < k_end; ++k) {
         const float *slab = ((k - k_begin) & 1) ? slab1 : slab0;
         float *slab_next = ((k - k_begin) & 1) ? slab0 : slab1;
+        if constexpr (SINGLE) {
+            if (k > k_begin) {
+                __syncthreads();  // nobody reads the slab of pair k - 1 any more
+                fill_whole(k);
+            }
+        }
         // a float32 table arrives by LDS-direct loads, which nothing but this wait tracks
         if constexpr (sizeof(CT) == 4) asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
         __syncthreads();  // the slab of pair k is complete, nobody reads the other buffer any more
-        if (k + 1 < k_end) fill.template issue<0>(a, slab_next, k + 1, jt, wave, lane);
+        if constexpr (!SINGLE)
+            if (k + 1 < k_end) fill.template issue<0>(a, slab_next, k + 1, jt, wave, lane);
 
         constexpr int kNear = 1;  // LDS reads run one step ahead (registers are short here)
         Corners ring[kNear + 1];
@@ -787,7 +800,7 @@ __global__ __launch_bounds__(WAVES * 64) __attribute__((amdgpu_waves_per_eu(WAVE
             constexpr int F = decltype(fc)::value;
             constexpr int set = F / LPS, t = F % LPS;
             if constexpr (t == 0) {
-                if constexpr (set == SETS / 2) {
+                if constexpr (set == SETS / 2 && !SINGLE) {
                     if (k + 1 < k_end) {
                         fill.template commit<0>(a, slab_next, wave, lane);
                         fill.template issue<1>(a, slab_next, k + 1, jt, wave, lane);
@@ -813,7 +826,8 @@ __global__ __launch_bounds__(WAVES * 64) __attribute__((amdgpu_waves_per_eu(WAVE
             }
             fma_corners_quad<t>(acc + 4 * F, ring[F % (kNear + 1)], w00, w10, w01, w11);
         });
-        if (k + 1 < k_end) fill.template commit<1>(a, slab_next, wave, lane);
+        if constexpr (!SINGLE)
+            if (k + 1 < k_end) fill.template commit<1>(a, slab_next, wave, lane);
     }
 
     // lane (grp, sub) holds outputs jt*16 + 4*sub .. +3 of samples n_wave + set*64 + 4*grp + t
@@ -1073,7 +1087,17 @@ static bool slab_narrow_ok(const LayerShape &s)
     return !slab_wide_ok(s) && (size_t)2 * s.nodes() * kNarrowRowBytes <= 160 * 1024;
 }
 
-bool slab_forward_shape_ok(const LayerShape &s) { return slab_wide_ok(s) || slab_narrow_ok(s); }
+// forward only: one 16-output slab at a time (35 <= G <= 48)
+static bool slab_narrow_single_ok(const LayerShape &s)
+{
+    if (s.n_out % 4 != 0 || s.batch < 256) return false;
+    return !slab_wide_ok(s) && !slab_narrow_ok(s) && (size_t)s.nodes() * kNarrowRowBytes <= 160 * 1024 - 512;
+}
+
+bool slab_forward_shape_ok(const LayerShape &s)
+{
+    return slab_wide_ok(s) || slab_narrow_ok(s) || slab_narrow_single_ok(s);
+}
 bool slab_tile_is_wide(const LayerShape &s) { return slab_wide_ok(s); }
 
 // Samples per forward workgroup: 1024 with 64-output tiles, 4096 with 16-output tiles.
@@ -1132,10 +1156,14 @@ static void launch_forward_slab_narrow(const LayerShape &s, const void *coef, fl
     constexpr int kTileB = WAVES * SETS * 64;
     typedef void (*Kernel)(SlabArgs);
     // a float32 table needs no staging registers: 16 waves of 256 samples instead of 8 of 512
-    const Kernel kernels[3] = {forward_slab_narrow_kernel<float, 2 * WAVES, SETS / 2>,
+    const bool single = slab_narrow_single_ok(s);
+    const Kernel kernels[6] = {forward_slab_narrow_kernel<float, 2 * WAVES, SETS / 2>,
                                forward_slab_narrow_kernel<_Float16, WAVES, SETS>,
-                               forward_slab_narrow_kernel<bf16_t, WAVES, SETS>};
-    const Kernel kernel = kernels[s.dtype];
+                               forward_slab_narrow_kernel<bf16_t, WAVES, SETS>,
+                               forward_slab_narrow_kernel<float, 2 * WAVES, SETS / 2, true>,
+                               forward_slab_narrow_kernel<_Float16, WAVES, SETS, true>,
+                               forward_slab_narrow_kernel<bf16_t, WAVES, SETS, true>};
+    const Kernel kernel = kernels[s.dtype + (single ? 3 : 0)];
     const int waves = s.dtype == LMKAN_F32 ? 2 * WAVES : WAVES;
     allow_large_lds(reinterpret_cast<const void *>(kernel), 160 * 1024);
     const size_t n = (size_t)s.pairs() * (size_t)s.batch;
@@ -1162,7 +1190,7 @@ static void launch_forward_slab_narrow(const LayerShape &s, const void *coef, fl
     finish_split_setup(a, s, y, partials, stream);
     {
         KernelTiming timing(stream, kTimeForward);
-        kernel<<<tiles * split, waves * 64, (size_t)2 * s.nodes() * kNarrowRowBytes, stream>>>(a);
+        kernel<<<tiles * split, waves * 64, (size_t)(single ? 1 : 2) * s.nodes() * kNarrowRowBytes, stream>>>(a);
     }
     if (a.y_part) launch_sum_partials(y, a.y_part, split - 1, a.part_elems, stream);
 }

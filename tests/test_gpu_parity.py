@@ -69,6 +69,10 @@ SHAPES = [
     (13000, 6, 68, 5),
     # rows wide enough for the sorted kernels to gather gy from a tile-by-tile copy (ragged last tile)
     (600, 4, 2116, 9),
+    # the finest grids whose 16-output slab fits LDS once (forward walks one slab at a time), and
+    # the first one beyond
+    (4300, 6, 40, 48),
+    (300, 4, 24, 49),
     # either side of the thresholds at which the dispatch changes kernels: 256 rows, 8 and 9
     # outputs, G = 16 / 17 and 34 / 35, 12288 rows
     (255, 6, 12, 8),
