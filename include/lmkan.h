@@ -75,6 +75,17 @@ typedef enum {
 } lmkan_layout;
 
 #define LMKAN_FLAG_ACCUMULATE_GRAD_COEF 1 /* backward adds into grad_coef instead of overwriting */
+/* The caller's promise that the workspace still holds the preamble records (cell and local
+ * coordinates of every (sample, pair), Alg. 1 "Preamble") that an earlier lmkan_forward,
+ * lmkan_backward or lmkan_conv2d_* call wrote for the same desc, batch (or geometry) and the same
+ * contents of x: the call then skips the pass that computes them (a training step runs forward
+ * and backward on the same x).  It holds only if that earlier call was given a workspace of at
+ * least lmkan_workspace_bytes() for its pass, that size was not zero, the call returned LMKAN_OK,
+ * and nothing has written to the first lmkan_workspace_bytes(desc, batch, 0) bytes since
+ * (the forward pass's partial outputs lie behind the records and do not matter).  The library
+ * cannot check the promise: with stale or foreign contents the records are garbage used as
+ * table indices, which is as undefined as a wrong pointer. */
+#define LMKAN_FLAG_WORKSPACE_HAS_RECORDS 2
 
 /* Description of one layer (Alg. 1 "Require"). */
 typedef struct {

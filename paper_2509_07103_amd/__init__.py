@@ -1,5 +1,5 @@
 """MI355X-native lmKAN layer: Python names mirror the C ABI of include/lmkan.h."""
-from .binding import (LMKAN_BF16, LMKAN_F16, LMKAN_F32, LMKAN_FLAG_ACCUMULATE_GRAD_COEF,
+from .binding import (LMKAN_BF16, LMKAN_F16, LMKAN_F32, LMKAN_FLAG_ACCUMULATE_GRAD_COEF, LMKAN_FLAG_WORKSPACE_HAS_RECORDS,
                       LMKAN_LAYOUT_PACKED, LMKAN_LAYOUT_PAPER, LMKAN_MAX_GRID, LMKAN_PACK_TILE, LMKAN_STATIC_SCRATCH_BYTES,
                       Conv2d, LayerDesc, LmkanError, lib, lmkan_backward, lmkan_conv2d_backward,
                       lmkan_conv2d_forward, lmkan_conv2d_rows, lmkan_forward, lmkan_forward_static, lmkan_grid,

@@ -20,6 +20,7 @@ LIB_PATH = os.path.join(_HERE, "liblmkan.so")
 LMKAN_F32, LMKAN_F16, LMKAN_BF16 = 0, 1, 2
 LMKAN_LAYOUT_PAPER, LMKAN_LAYOUT_PACKED = 0, 1
 LMKAN_FLAG_ACCUMULATE_GRAD_COEF = 1
+LMKAN_FLAG_WORKSPACE_HAS_RECORDS = 2
 LMKAN_PACK_TILE = 64
 LMKAN_MAX_GRID = 64
 LMKAN_STATIC_SCRATCH_BYTES = 32 << 20

@@ -76,7 +76,7 @@ lmkan_status check_desc(const lmkan_desc *d)
         return LMKAN_ERR_UNSUPPORTED;
     if (d->coef_layout != LMKAN_LAYOUT_PAPER && d->coef_layout != LMKAN_LAYOUT_PACKED)
         return LMKAN_ERR_UNSUPPORTED;
-    if (d->flags & ~LMKAN_FLAG_ACCUMULATE_GRAD_COEF) return LMKAN_ERR_UNSUPPORTED;
+    if (d->flags & ~(LMKAN_FLAG_ACCUMULATE_GRAD_COEF | LMKAN_FLAG_WORKSPACE_HAS_RECORDS)) return LMKAN_ERR_UNSUPPORTED;
     return LMKAN_OK;
 }
 
@@ -268,11 +268,13 @@ lmkan_status forward_impl(const lmkan_desc *desc, int64_t batch, const float *x_
     hipStream_t hs = static_cast<hipStream_t>(stream);
     drop_stale_error();
     TimedCall timed(kTimeForward);
-    if (small_out_shape_ok(s)) {
+    // the records are written whenever the shape has a kernel that reads them, also when the
+    // alignment of this call's pointers sends it to the generic kernel: a later call may rely on them
+    if (need > 0 && !(desc->flags & LMKAN_FLAG_WORKSPACE_HAS_RECORDS))
         launch_preamble_records(s, tab, x_dev, workspace_dev, hs, conv);
+    if (small_out_shape_ok(s)) {
         launch_forward_small(s, coef_dev, y_dev, workspace_dev, hs);
     } else if (slab_forward_applicable(s, coef_dev, y_dev)) {
-        launch_preamble_records(s, tab, x_dev, workspace_dev, hs, conv);
         float *partials = slab_forward_partial_bytes(s) > 0
                               ? reinterpret_cast<float *>(static_cast<char *>(workspace_dev) + align256(records_bytes(s)))
                               : nullptr;
@@ -344,7 +346,7 @@ lmkan_status backward_impl(const lmkan_desc *desc, int64_t batch, const float *x
     float *ws_scratch = reinterpret_cast<float *>(ws + w.scratch);
     char *ws_partial = ws + w.partial;
     TimedCall timed(grad_x_dev ? kTimeGradInput : kTimeGradCoef);
-    if (need_records) launch_preamble_records(s, tab, x_dev, ws, hs, conv);
+    if (need_records && !(desc->flags & LMKAN_FLAG_WORKSPACE_HAS_RECORDS)) launch_preamble_records(s, tab, x_dev, ws, hs, conv);
     SortedStream stream_k{};
     GyView gy_k{};
     if (gp_sorted || gx_fused) {

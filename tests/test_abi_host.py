@@ -67,7 +67,7 @@ def _desc(**kw):
 
 BAD_DESCS = [
     (dict(n_in=7), 2), (dict(n_in=0), 2), (dict(n_in=131072), 2), (dict(n_out=4194241), 2), (dict(n_out=0), 2), (dict(grid=2), 2), (dict(grid=65), 2),
-    (dict(spline_order=3), 3), (dict(coef_dtype=7), 3), (dict(coef_layout=2), 3), (dict(flags=2), 3),
+    (dict(spline_order=3), 3), (dict(coef_dtype=7), 3), (dict(coef_layout=2), 3), (dict(flags=4), 3),
 ]
 
 

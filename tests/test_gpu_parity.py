@@ -214,6 +214,34 @@ def test_backward_pieces_and_accumulate_flag(dev, oracle, shape):
     assert np.abs(stale.cpu().numpy() - want).max() <= TOL_F32 * np.abs(want).max()
 
 
+@pytest.mark.parametrize("shape", [(1100, 140, 132, 16), (1024, 66, 4, 16), (4200, 6, 40, 32), (2100, 10, 132, 40)])
+def test_calls_can_reuse_the_records_in_the_workspace(dev, oracle, shape):
+    """LMKAN_FLAG_WORKSPACE_HAS_RECORDS: a backward (or forward) call on the workspace an earlier call
+    on the same x left behind skips the preamble pass and gives what the full call gives."""
+    B, n_in, n_out, G = shape
+    x, P, gy = _inputs(B, n_in, n_out, G, 55, dev)
+    desc = _desc(n_in, n_out, G)
+    reuse = _desc(n_in, n_out, G, flags=pkg.LMKAN_FLAG_WORKSPACE_HAS_RECORDS)
+    need = max(pkg.lmkan_workspace_bytes(desc, B, False), pkg.lmkan_workspace_bytes(desc, B, True))
+    assert pkg.lmkan_workspace_bytes(desc, B, False) > 0
+    ws = torch.empty(need, dtype=torch.uint8, device=dev)
+    want_y = pkg.lmkan_forward(desc, x, P)
+    want_gx, want_gp = pkg.lmkan_backward(desc, x, P, gy)
+    ws.fill_(0xFF)                                   # nothing usable in the workspace yet
+    y = pkg.lmkan_forward(desc, x, P, workspace=ws)  # writes the records
+    gx, gp = pkg.lmkan_backward(reuse, x, P, gy, workspace=ws)
+    y2 = pkg.lmkan_forward(reuse, x, P, workspace=ws)
+    gx2, gp2 = pkg.lmkan_backward(reuse, x, P, gy, workspace=ws)
+    torch.cuda.synchronize()
+    for got in (y, y2):     # (the kernel for narrow outputs adds its pair splits with atomics: not bit-equal)
+        assert rowwise_rel_err(got.cpu().numpy(), want_y.cpu().numpy().astype(np.float64)) <= 1e-6
+    for a, b in ((gx, gp), (gx2, gp2)):
+        assert rowwise_rel_err(a.cpu().numpy(), want_gx.cpu().numpy().astype(np.float64)) <= 1e-6
+        assert torch.allclose(b, want_gp, rtol=1e-5, atol=1e-6 * float(want_gp.abs().max()))
+    want = oracle.backward_input(x.cpu().numpy(), P.cpu().numpy(), gy.cpu().numpy(), G)
+    assert rowwise_rel_err(gx.cpu().numpy(), want) <= TOL_F32
+
+
 def test_sorted_paths_repeat_bit_for_bit(dev):
     """What the header promises about run-to-run variation: the counting sort leaves the samples of
     a cell in the order of their indices, so a coefficient gradient that one wave writes row by
