@@ -201,38 +201,27 @@ typedef struct {
     double B11;         /* B_{i1+1, i2+1}(x1, x2)                           */
 } preamble_t;
 
-#ifdef ORACLE_CLIP_EDGE
-/* Other reading of the edge cells: the hat of the outermost real point is cut
- * at the ghost, so beyond a ghost only the linear edge function survives.   */
-static void clip_axis(int G, const float *E32, int i, double x, double *lo, double *hi)
-{
-    if (i == 0 && x < (double)E32[0])
-        *hi = 0.0;
-    if (i == G - 1 && x > (double)E32[G])
-        *lo = 0.0;
-}
-#endif
-
-/* Alg. 1 "Preamble": two cell indices and the four non-zero 2-D B-splines. */
+/* The four non-zero terms of Eq. 3 at (x1, x2).  Sec. 3.1: on each axis exactly two of the
+ * one-dimensional functions are non-zero at a point, the ones attached to the two ends of the
+ * interval the point falls in, and a two-dimensional function is the product of one function of
+ * x1 and one of x2.  So: find the interval on each axis, evaluate those two functions with the
+ * definition above (oracle_basis, which also carries the reading of the edge cells), and
+ * multiply.  The grid is the float32-rounded one, promoted to double. */
 static preamble_t preamble(int G, const float *E32, float x1f, float x2f)
 {
     preamble_t r;
-    double x1 = (double)x1f, x2 = (double)x2f;
+    double E[G + 1]; /* (a few hundred bytes: G is at most a few dozen) */
+    for (int a = 0; a <= G; ++a)
+        E[a] = (double)E32[a];
+    const double x1 = (double)x1f, x2 = (double)x2f;
     r.i1 = oracle_locate(G, E32, x1f);
     r.i2 = oracle_locate(G, E32, x2f);
-    double g1lo = (double)E32[r.i1], g1hi = (double)E32[r.i1 + 1];
-    double g2lo = (double)E32[r.i2], g2hi = (double)E32[r.i2 + 1];
-    double Ainv = 1.0 / ((g1hi - g1lo) * (g2hi - g2lo));
-    double a_lo = g1hi - x1, a_hi = x1 - g1lo; /* factors of B_{i1}, B_{i1+1} */
-    double b_lo = g2hi - x2, b_hi = x2 - g2lo; /* factors of B_{i2}, B_{i2+1} */
-#ifdef ORACLE_CLIP_EDGE
-    clip_axis(G, E32, r.i1, x1, &a_lo, &a_hi);
-    clip_axis(G, E32, r.i2, x2, &b_lo, &b_hi);
-#endif
-    r.B00 = a_lo * b_lo * Ainv;
-    r.B10 = a_hi * b_lo * Ainv;
-    r.B01 = a_lo * b_hi * Ainv;
-    r.B11 = a_hi * b_hi * Ainv;
+    const double first_lo = oracle_basis(G, E, r.i1, x1), first_hi = oracle_basis(G, E, r.i1 + 1, x1);
+    const double second_lo = oracle_basis(G, E, r.i2, x2), second_hi = oracle_basis(G, E, r.i2 + 1, x2);
+    r.B00 = first_lo * second_lo;
+    r.B10 = first_hi * second_lo;
+    r.B01 = first_lo * second_hi;
+    r.B11 = first_hi * second_hi;
     return r;
 }
 
