@@ -25,6 +25,16 @@
  *     and grad_x_dev, 16 bytes for the other tensors).
  *   - Non-finite inputs are memory-safe: cell indices are always clamped to
  *     [0, G-1]; the affected outputs are whatever IEEE arithmetic gives.
+ *   - Stream capture: every compute call may be recorded into a HIP graph (no
+ *     allocation, no synchronisation, memory is cleared by fill kernels, not by
+ *     memset nodes), with one proviso: the first launch, on a device, of a kernel
+ *     that needs more than 64 KiB of LDS raises that kernel's limit with
+ *     hipFuncSetAttribute, which is not a stream operation.  Make one ordinary
+ *     call of the same shape on that device before capturing.
+ *   - Host threads: calls may be made from several threads at once (the only
+ *     shared host state, which kernels have had their LDS limit raised on which
+ *     device and the address of the static scratch, is guarded by mutexes);
+ *     lmkan_time_next_kernel arms the calling thread only.
  */
 #ifndef LMKAN_H
 #define LMKAN_H
