@@ -54,3 +54,6 @@ def up_to_date() -> bool:
 
 if __name__ == "__main__":
     print(build(verbose=True))
+    sys.path.insert(0, ROOT)
+    from paper_2509_07103_amd import check_codegen
+    check_codegen.check(verbose=True)

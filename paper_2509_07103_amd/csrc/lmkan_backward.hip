@@ -445,9 +445,14 @@ __global__ __launch_bounds__(64) void backward_coef_stream_kernel(CoefGradArgs a
         const unsigned off = n_off;
         asm volatile("global_load_dword %0, %1, %2" : "=v"(dst) : "v"(off), "s"(base) : "memory");
     };
-    // blocks until at most N loads younger than the one that fills v are outstanding, i.e. until v has landed
+    // blocks until at most N loads younger than the one that fills v are outstanding, i.e. until v has landed.
+    // The compiler does not know that v is in flight between the load and this wait: were it to copy
+    // or move v in between, it would copy stale data and hand the old register to something else for
+    // the late load to overwrite.  The comment in the instruction names the register, so that the
+    // generated code can be checked (check_codegen.py does, at every build): on every path from a
+    // load, the first instruction that touches its destination must be this wait.
     auto landed = [](auto &v, auto nc) {
-        asm volatile("s_waitcnt vmcnt(%1)" : "+v"(v) : "n"(decltype(nc)::value) : "memory");
+        asm volatile("s_waitcnt vmcnt(%1) ; landed %0" : "+v"(v) : "n"(decltype(nc)::value) : "memory");
     };
 
     const unsigned col_bytes = col_ok ? (unsigned)l16 * 16u : 0u;

@@ -182,3 +182,52 @@ def test_conv2d_rows_and_geometry_checks():
     assert L.lmkan_conv2d_forward(C.byref(d), C.byref(good), None, fake, fake, None, 0, None) == 1
     odd = _desc(n_in=7).c()
     assert L.lmkan_conv2d_forward(C.byref(odd), C.byref(good), fake, fake, fake, None, 0, None) == 2
+
+
+# ---- the check of the generated code of the kernels that issue their own loads and waits ----
+_ASM_OK = """
+kern:                                   ; @kern
+\ts_load_dwordx2 s[0:1], s[4:5], 0x0
+.LBB0_1:
+\t;;#ASMSTART
+\tglobal_load_dwordx4 v[4:7], v1, s[0:1]
+\t;;#ASMEND
+\tv_add_u32_e32 v1, 16, v1
+\ts_cbranch_scc1 .LBB0_3
+\tv_mov_b32_e32 v9, v2
+.LBB0_3:
+\t;;#ASMSTART
+\ts_waitcnt vmcnt(1) ; landed v[4:7]
+\t;;#ASMEND
+\tv_add_f32_e32 v8, v4, v5
+\ts_cbranch_scc0 .LBB0_1
+\ts_endpgm
+"""
+
+
+def test_codegen_check_accepts_a_load_first_touched_by_its_wait():
+    from paper_2509_07103_amd import check_codegen
+    assert check_codegen.check_assembly(_ASM_OK) == {"kern": 1}
+
+
+@pytest.mark.parametrize("planted", [
+    "\tv_mov_b32_e32 v9, v5",            # a copy of a register still in flight
+    "\tv_mov_b32_e32 v6, 0",             # the register handed to something else
+    "\tv_add_f32_e32 v8, v[4:5], v2",    # named inside a register range
+])
+def test_codegen_check_rejects_a_touch_before_the_wait(planted):
+    from paper_2509_07103_amd import check_codegen
+    # on the branch that skips nothing: only the control flow graph reaches it from the load
+    bad = _ASM_OK.replace("\tv_mov_b32_e32 v9, v2", planted)
+    with pytest.raises(RuntimeError, match="touched before their wait"):
+        check_codegen.check_assembly(bad)
+    # and a wait that names other registers than the load's does not end the path
+    other = _ASM_OK.replace("landed v[4:7]", "landed v[10:13]")
+    with pytest.raises(RuntimeError, match="touched before their wait"):
+        check_codegen.check_assembly(other)
+
+
+def test_codegen_check_passes_on_the_library_sources():
+    from paper_2509_07103_amd import check_codegen
+    counts = check_codegen.check()
+    assert len(counts) == 2 and all(n == 34 for n in counts.values()), counts
