@@ -355,7 +355,11 @@ def test_results_do_not_depend_on_the_stream(dev, oracle):
 # ---- Hessian regulariser (Sec. 3.5, App. C) ---------------------------------------------------
 @pytest.mark.parametrize("layout", [pkg.LMKAN_LAYOUT_PAPER, pkg.LMKAN_LAYOUT_PACKED])
 @pytest.mark.parametrize("storage", ["f32", "f16", "bf16"])
-@pytest.mark.parametrize("shape", [(4, 3, 3), (6, 70, 4), (18, 132, 16), (8, 200, 33), (6, 5, 64)])
+# grids on either side of every band count of the kernel (bands of nine columns: G + 1 = 9, 10, 18, 19 ...),
+# output counts that leave the last tile ragged, a single tile, several tiles
+@pytest.mark.parametrize("shape", [(4, 3, 3), (6, 70, 4), (4, 64, 8), (4, 65, 9), (6, 130, 12), (18, 132, 16),
+                                   (4, 64, 17), (4, 20, 18), (4, 96, 20), (4, 70, 32), (8, 200, 33), (4, 64, 40),
+                                   (6, 5, 64)])
 def test_hessian_reg_matches_oracle(dev, oracle, shape, storage, layout):
     n_in, n_out, G = shape
     g = torch.Generator(device="cpu").manual_seed(71)
