@@ -179,21 +179,27 @@ struct SlabFill {
     static constexpr int kChunksPerWave = (PHASES / 2 * kMaxSlabBytes / 1024 + WAVES - 1) / WAVES;
     static constexpr int kPerPhase = (kChunksPerWave + PHASES - 1) / PHASES;  // phases keep the staging registers few
     uint2 v[kPerPhase];
+    bool col_exists = true;  // the lane's four columns are inside the table (set by issue)
 
     template <int PHASE>
     __device__ __forceinline__ void issue(const SlabArgs &a, float *, int k, int jt, int wave, int lane)
     {
         const int g = lane / LPS, l16 = lane % LPS;
         const int col = jt * (LPS * 4) + l16 * 4;
-        const CT *src = static_cast<const CT *>(a.P) + (int64_t)k * a.map.s_pair + (int64_t)(col >> 6) * a.map.s_tile +
-                        (col & 63);
         const bool col_ok = col < a.col_limit;
+        const int col_rd = col_ok ? col : 0;
+        const CT *src = static_cast<const CT *>(a.P) + (int64_t)k * a.map.s_pair + (int64_t)(col_rd >> 6) * a.map.s_tile +
+                        (col_rd & 63);
 #pragma unroll
         for (int i = 0; i < kPerPhase; ++i) {
+            // Never skipped: a row or column outside the table reads an entry inside it; commit()
+            // drops such a row and writes zeros for such a column.  (The compiler sizes a wait for a load by the path with
+            // the fewest younger loads; a load that may be skipped makes every older load's wait
+            // a wait for everything.)
             const int node = (wave + (PHASE * kPerPhase + i) * WAVES) * NG + g;
-            v[i] = make_uint2(0u, 0u);
-            if (node < a.nodes && col_ok) v[i] = *reinterpret_cast<const uint2 *>(src + (int64_t)node * a.map.s_node);
+            v[i] = *reinterpret_cast<const uint2 *>(src + (int64_t)min(node, a.nodes - 1) * a.map.s_node);
         }
+        col_exists = col_ok;
     }
     template <int PHASE>
     __device__ __forceinline__ void commit(const SlabArgs &a, float *slab, int wave, int lane)
@@ -212,6 +218,7 @@ struct SlabFill {
                     f = make_float4(__uint_as_float(v[i].x << 16), __uint_as_float(v[i].x & 0xffff0000u),
                                     __uint_as_float(v[i].y << 16), __uint_as_float(v[i].y & 0xffff0000u));
                 }
+                if (!col_exists) f = make_float4(0.f, 0.f, 0.f, 0.f);
                 *reinterpret_cast<float4 *>(slab + c * (4 * kTile) + lane * 4) = f;
             }
         }
@@ -750,17 +757,16 @@ __global__ __launch_bounds__(WAVES * 64) __attribute__((amdgpu_waves_per_eu(WAVE
     // from HBM) younger than any record that is waited for before they are due.
     int r_node[SETS];
     float r_u[SETS], r_v[SETS];
+    // No load of the main loop is ever skipped (the compiler sizes the wait for a load by the
+    // path with the fewest younger loads, so a load that may be skipped turns the waits for all
+    // older ones into waits for everything): a sample past the batch reads the last sample's
+    // record (its results are not stored), the step past the last pair reads the last pair again.
     auto fetch_record = [&](int slot, int k) {
-        const int64_t n = n_wave + slot * 64 + lane;
-        r_node[slot] = 0;
-        r_u[slot] = 0.f;
-        r_v[slot] = 0.f;
-        if (n < a.B && k < k_end) {
-            const int64_t o = (int64_t)k * a.B + n;
-            r_node[slot] = a.rec_node[o];
-            r_u[slot] = a.rec_u[o];
-            r_v[slot] = a.rec_v[o];
-        }
+        const int64_t n = min(n_wave + slot * 64 + lane, a.B - 1);
+        const int64_t o = (int64_t)min(k, k_end - 1) * a.B + n;
+        r_node[slot] = a.rec_node[o];
+        r_u[slot] = a.rec_u[o];
+        r_v[slot] = a.rec_v[o];
     };
 
     SlabFill<CT, WAVES, LPS, SINGLE ? 4 : 2> fill;
@@ -788,8 +794,8 @@ __global__ __launch_bounds__(WAVES * 64) __attribute__((amdgpu_waves_per_eu(WAVE
         // a float32 table arrives by LDS-direct loads, which nothing but this wait tracks
         if constexpr (sizeof(CT) == 4) asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
         __syncthreads();  // the slab of pair k is complete, nobody reads the other buffer any more
-        if constexpr (!SINGLE)
-            if (k + 1 < k_end) fill.template issue<0>(a, slab_next, k + 1, jt, wave, lane);
+        const int k_next = min(k + 1, k_end - 1);  // the last pair fetches its own slab once more, for nobody
+        if constexpr (!SINGLE) fill.template issue<0>(a, slab_next, k_next, jt, wave, lane);
 
         constexpr int kNear = 1;  // LDS reads run one step ahead (registers are short here)
         Corners ring[kNear + 1];
@@ -801,10 +807,8 @@ __global__ __launch_bounds__(WAVES * 64) __attribute__((amdgpu_waves_per_eu(WAVE
             constexpr int set = F / LPS, t = F % LPS;
             if constexpr (t == 0) {
                 if constexpr (set == SETS / 2 && !SINGLE) {
-                    if (k + 1 < k_end) {
-                        fill.template commit<0>(a, slab_next, wave, lane);
-                        fill.template issue<1>(a, slab_next, k + 1, jt, wave, lane);
-                    }
+                    fill.template commit<0>(a, slab_next, wave, lane);
+                    fill.template issue<1>(a, slab_next, k_next, jt, wave, lane);
                 }
                 // weights of this set, offsets of the next one; then the slot is free
                 const float u = r_u[set], v = r_v[set];
@@ -826,8 +830,7 @@ __global__ __launch_bounds__(WAVES * 64) __attribute__((amdgpu_waves_per_eu(WAVE
             }
             fma_corners_quad<t>(acc + 4 * F, ring[F % (kNear + 1)], w00, w10, w01, w11);
         });
-        if constexpr (!SINGLE)
-            if (k + 1 < k_end) fill.template commit<1>(a, slab_next, wave, lane);
+        if constexpr (!SINGLE) fill.template commit<1>(a, slab_next, wave, lane);
     }
 
     // lane (grp, sub) holds outputs jt*16 + 4*sub .. +3 of samples n_wave + set*64 + 4*grp + t
@@ -940,17 +943,14 @@ __global__ __launch_bounds__(WAVES * 64) __attribute__((amdgpu_waves_per_eu(WAVE
 
     int r_node[SETS];
     float r_u[SETS], r_v[SETS];
+    // (never skipped, like every load of the main loop: see forward_slab_narrow_kernel; a sample
+    // past the batch has gy = 0 and adds nothing)
     auto fetch_record = [&](int slot, int k) {
-        const int64_t n = n_wave + slot * 64 + lane;
-        r_node[slot] = 0;
-        r_u[slot] = 0.f;
-        r_v[slot] = 0.f;
-        if (n < a.B && k >= 0) {
-            const int64_t o = (int64_t)k * a.B + n;
-            r_node[slot] = a.rec_node[o];
-            r_u[slot] = a.rec_u[o];
-            r_v[slot] = a.rec_v[o];
-        }
+        const int64_t n = min(n_wave + slot * 64 + lane, a.B - 1);
+        const int64_t o = (int64_t)k * a.B + n;
+        r_node[slot] = a.rec_node[o];
+        r_u[slot] = a.rec_u[o];
+        r_v[slot] = a.rec_v[o];
     };
 
     // columns past the end of a ragged output tile are never loaded: the staged fill writes
@@ -965,9 +965,9 @@ __global__ __launch_bounds__(WAVES * 64) __attribute__((amdgpu_waves_per_eu(WAVE
     // they are on different pairs and their atomics go to different cache lines.
     const int n_k = k_end - k_begin;
     const int rot = n_k > 0 ? (int)(((int64_t)jt * n_k) / a.n_jt) : 0;
-    auto pair_at = [&](int i) {  // pair of step i of the walk; -1 past its end
-        const int r = i + rot;
-        return i < n_k ? k_begin + (r >= n_k ? r - n_k : r) : -1;
+    auto pair_at = [&](int i) {  // pair of step i of the walk; past its end the last pair once more, for nobody
+        const int r = min(i, n_k - 1) + rot;
+        return k_begin + (r >= n_k ? r - n_k : r);
     };
     SlabFill<CT, WAVES, LPS> fill;
     if (n_k > 0) {
@@ -992,7 +992,7 @@ __global__ __launch_bounds__(WAVES * 64) __attribute__((amdgpu_waves_per_eu(WAVE
         float *slab_next = (step & 1) ? slab0 : slab1;
         if constexpr (sizeof(CT) == 4) asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
         __syncthreads();
-        if (k_next >= 0) fill.template issue<0>(sa, slab_next, k_next, jt, wave, lane);
+        fill.template issue<0>(sa, slab_next, k_next, jt, wave, lane);
 
         constexpr int kNear = 1;
         Corners ring[kNear + 1];
@@ -1005,10 +1005,8 @@ __global__ __launch_bounds__(WAVES * 64) __attribute__((amdgpu_waves_per_eu(WAVE
             constexpr int set = F / LPS, t = F % LPS;
             if constexpr (t == 0) {
                 if constexpr (set == SETS / 2) {
-                    if (k_next >= 0) {
-                        fill.template commit<0>(sa, slab_next, wave, lane);
-                        fill.template issue<1>(sa, slab_next, k_next, jt, wave, lane);
-                    }
+                    fill.template commit<0>(sa, slab_next, wave, lane);
+                    fill.template issue<1>(sa, slab_next, k_next, jt, wave, lane);
                 }
                 const int node = r_node[set];
                 const int i1 = (int)(((float)node + 0.5f) * inv_w);  // node / W, exact for these sizes
@@ -1039,7 +1037,7 @@ __global__ __launch_bounds__(WAVES * 64) __attribute__((amdgpu_waves_per_eu(WAVE
                 if (n + 2 < a.B) unsafeAtomicAdd(dst + 32, stash_b);
             }
         });
-        if (k_next >= 0) fill.template commit<1>(sa, slab_next, wave, lane);
+        fill.template commit<1>(sa, slab_next, wave, lane);
     }
 }
 
