@@ -239,8 +239,10 @@ __global__ __launch_bounds__(64) void backward_fused_kernel(FusedArgs a)
     // in order: one load that has to go to HBM holds back every gy piece requested after it, so
     // everything that streams from HBM is requested in one burst at the top of a trip.
     const int touch_row = (lane >= 16 ? W : 0) + 4 + ((lane & 15) >> 1);
+    // (two touches per row: its first column and its middle one, where the table has that column)
+    const int touch_col = (lane & 1) != 0 && jt * kTile + kTile / 2 < a.col_limit ? kTile / 2 : 0;
     const char *touch_base = reinterpret_cast<const char *>(static_cast<const CT *>(a.P) + (int64_t)k * a.pmap.s_pair +
-                                                            (int64_t)jt * a.pmap.s_tile) + (lane & 1) * 128;
+                                                            (int64_t)jt * a.pmap.s_tile + touch_col);
     const int last_node = W * W - 1;
     auto touch_ahead = [&](int cell) {
         int v = 0;

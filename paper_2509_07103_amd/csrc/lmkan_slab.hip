@@ -794,8 +794,11 @@ __global__ __launch_bounds__(WAVES * 64) __attribute__((amdgpu_waves_per_eu(WAVE
         // a float32 table arrives by LDS-direct loads, which nothing but this wait tracks
         if constexpr (sizeof(CT) == 4) asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
         __syncthreads();  // the slab of pair k is complete, nobody reads the other buffer any more
-        const int k_next = min(k + 1, k_end - 1);  // the last pair fetches its own slab once more, for nobody
-        if constexpr (!SINGLE) fill.template issue<0>(a, slab_next, k_next, jt, wave, lane);
+        // (16-bit tables: the last pair fetches its own slab once more, for nobody; the LDS-direct
+        // loads of a float32 table are not tracked by the compiler's waits and are simply left out)
+        const int k_next = min(k + 1, k_end - 1);
+        if constexpr (!SINGLE)
+            if (sizeof(CT) != 4 || k + 1 < k_end) fill.template issue<0>(a, slab_next, k_next, jt, wave, lane);
 
         constexpr int kNear = 1;  // LDS reads run one step ahead (registers are short here)
         Corners ring[kNear + 1];
@@ -992,7 +995,7 @@ __global__ __launch_bounds__(WAVES * 64) __attribute__((amdgpu_waves_per_eu(WAVE
         float *slab_next = (step & 1) ? slab0 : slab1;
         if constexpr (sizeof(CT) == 4) asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
         __syncthreads();
-        fill.template issue<0>(sa, slab_next, k_next, jt, wave, lane);
+        if (sizeof(CT) != 4 || step + 1 < n_k) fill.template issue<0>(sa, slab_next, k_next, jt, wave, lane);
 
         constexpr int kNear = 1;
         Corners ring[kNear + 1];
