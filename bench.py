@@ -65,7 +65,9 @@ def kernel_names(w, n_out, B, storage, packed):
         if B >= 16 * w.grid * w.grid:
             both = "backward_fused_kernel"
     elif ok:
-        fwd, gx, gp = "forward_generic_kernel", "backward_fused_kernel", "backward_coef_stream_kernel"
+        # one 16-output slab at a time fits LDS up to G = 48
+        fwd = "forward_slab_narrow_kernel" if (w.grid + 1) ** 2 * 64 <= 160 * 1024 - 512 else "forward_generic_kernel"
+        gx, gp = "backward_fused_kernel", "backward_coef_stream_kernel"
         both = "backward_fused_kernel"
     else:
         fwd, gx = "forward_generic_kernel", "backward_generic_kernel(grad_x)"

@@ -67,21 +67,32 @@ struct FusedArgs {
     int col_limit;    // columns >= col_limit do not exist in P
 };
 
+// Four adjacent coefficients of a row as they are stored, and their float32 values.  The two are
+// kept apart on purpose: a row is requested several chunks before its cell begins, and a
+// conversion written next to the load would wait for the load right there.
 template <typename CT>
-__device__ __forceinline__ f4v load_coef4(const CT *p)
+struct CoefRow {
+    typedef typename std::conditional<sizeof(CT) == 4, f4v, uint2>::type raw;
+};
+
+template <typename CT>
+__device__ __forceinline__ typename CoefRow<CT>::raw load_coef4(const CT *p)
+{
+    return *reinterpret_cast<const typename CoefRow<CT>::raw *>(p);
+}
+
+template <typename CT>
+__device__ __forceinline__ f4v widen_coef4(const typename CoefRow<CT>::raw &v)
 {
     if constexpr (sizeof(CT) == 4) {
-        return *reinterpret_cast<const f4v *>(p);
+        return v;
+    } else if constexpr (std::is_same<CT, _Float16>::value) {
+        typedef _Float16 h2v __attribute__((ext_vector_type(2)));
+        const h2v lo = __builtin_bit_cast(h2v, v.x), hi = __builtin_bit_cast(h2v, v.y);
+        return f4v{(float)lo.x, (float)lo.y, (float)hi.x, (float)hi.y};
     } else {
-        const uint2 v = *reinterpret_cast<const uint2 *>(p);
-        if constexpr (std::is_same<CT, _Float16>::value) {
-            typedef _Float16 h2v __attribute__((ext_vector_type(2)));
-            const h2v lo = __builtin_bit_cast(h2v, v.x), hi = __builtin_bit_cast(h2v, v.y);
-            return f4v{(float)lo.x, (float)lo.y, (float)hi.x, (float)hi.y};
-        } else {
-            return f4v{__uint_as_float(v.x << 16), __uint_as_float(v.x & 0xffff0000u), __uint_as_float(v.y << 16),
-                       __uint_as_float(v.y & 0xffff0000u)};
-        }
+        return f4v{__uint_as_float(v.x << 16), __uint_as_float(v.x & 0xffff0000u), __uint_as_float(v.y << 16),
+                   __uint_as_float(v.y & 0xffff0000u)};
     }
 }
 
@@ -264,8 +275,8 @@ __global__ __launch_bounds__(64) void backward_fused_kernel(FusedArgs a)
     float2 res = make_float2(0.f, 0.f);  // results of this lane's sample of the trip
     int touched = 0;
     f4v gq[kDepth];         // gy row pieces
-    f4v pqa[kCellDepth];    // both rows of this lane's coefficient difference, for the chunks that start a cell
-    f4v pqb[kCellDepth];
+    typename CoefRow<CT>::raw pqa[kCellDepth];  // both rows of this lane's coefficient difference, as stored,
+    typename CoefRow<CT>::raw pqb[kCellDepth];  // for the chunks that start a cell
 
     auto unpack = [&](const f4v &e, float &prod, int &n, float2 &uv) {
         prod = DO_GP ? entry_product(e, l16 & 3) : 0.f;
@@ -321,7 +332,7 @@ __global__ __launch_bounds__(64) void backward_fused_kernel(FusedArgs a)
                 }
                 cur_cell = cell_cur;
                 cur_slot = cur_slot + 1 == kCellSlots ? 0 : cur_slot + 1;
-                f4v d = pqa[P % kCellDepth] - pqb[P % kCellDepth];
+                f4v d = widen_coef4<CT>(pqa[P % kCellDepth]) - widen_coef4<CT>(pqb[P % kCellDepth]);
                 if (RAGGED && !pcol_ok) d = f4v{0.f, 0.f, 0.f, 0.f};
                 *reinterpret_cast<f4v *>(lds + kStageBytes + cur_slot * 1024 + wr_off) = d;
                 // this chunk and the rest of its group take the new slot
