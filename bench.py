@@ -51,7 +51,7 @@ def parse():
 def kernel_names(w, n_out, B, storage, packed):
     """Main kernel of a forward call, of a grad_x-only call and of a grad_coef-only call, and of a call
     for both gradients when one kernel forms both: mirrors the library's dispatch (lmkan_api.hip)."""
-    ok = n_out % 4 == 0 and B >= 256
+    ok = (n_out % 4 == 0 or packed) and B >= 256
     both = None
     if n_out <= 8:
         fwd, gx, gp = "forward_small_kernel", "backward_input_small_kernel", "backward_coef_small_kernel"
@@ -71,7 +71,7 @@ def kernel_names(w, n_out, B, storage, packed):
         both = "backward_fused_kernel"
     else:
         fwd, gx = "forward_generic_kernel", "backward_generic_kernel(grad_x)"
-        gp = "backward_coef_stream_kernel" if n_out % 4 == 0 else "backward_generic_kernel(grad_coef)"
+        gp = "backward_coef_stream_kernel"
     return fwd, gx, gp, both
 
 

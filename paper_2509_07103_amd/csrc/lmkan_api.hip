@@ -31,14 +31,18 @@ struct BackwardWorkspace {
 BackwardWorkspace backward_workspace(const LayerShape &s, bool want_gx, bool want_gp)
 {
     BackwardWorkspace w;
+    // (mirrors backward_impl: the few-output kernels take the input gradient of such layers, and
+    // their coefficient gradient too while a pair's slice of it fits LDS; everything else that
+    // can be sorted is, for the coefficient gradient and for the walk that yields both)
     const bool small = small_out_shape_ok(s);
-    const bool sorted = sorted_shape_ok(s) && (want_gx ? !small : !(small && small_coef_ok(s)));
+    const bool gp_small = small && small_coef_ok(s);
+    const bool sorted = sorted_shape_ok(s) && ((want_gp && !gp_small) || (want_gx && !small));
     w.records = 0;
     w.sorted = align256(records_bytes(s));
     w.scratch = w.sorted + (sorted ? sorted_records_bytes(s) : 0);
     w.partial = w.scratch + (want_gx ? slab_backward_input_scratch_bytes(s) : 0);
-    w.gy_tiles = w.partial + (want_gx && sorted ? fused_partial_bytes(s) : 0);
-    w.total = w.gy_tiles + (sorted ? gy_tiles_bytes(s) : 0);
+    w.gy_tiles = w.partial + (want_gx && !small && sorted ? fused_partial_bytes(s) : 0);
+    w.total = w.gy_tiles + gy_tiles_bytes(s);
     return w;
 }
 
@@ -349,10 +353,10 @@ lmkan_status backward_impl(const lmkan_desc *desc, int64_t batch, const float *x
     if (need_records && !(desc->flags & LMKAN_FLAG_WORKSPACE_HAS_RECORDS)) launch_preamble_records(s, tab, x_dev, ws, hs, conv);
     SortedStream stream_k{};
     GyView gy_k{};
-    if (gp_sorted || gx_fused) {
-        stream_k = launch_sort(s, ws, ws_sorted, hs);
-        gy_k = launch_gy_tiles(s, grad_y_dev, ws + w.gy_tiles, hs);
-    }
+    if (gp_sorted || gx_fused) stream_k = launch_sort(s, ws, ws_sorted, hs);
+    // (the slab kernels read gy as it is, except with a ragged output count)
+    if (gp_sorted || gx_fused || (gx_slab && ragged_outputs(s))) gy_k = launch_gy_tiles(s, grad_y_dev, ws + w.gy_tiles, hs);
+    else gy_k = GyView{grad_y_dev, (int64_t)(LMKAN_PACK_TILE * sizeof(float)), (unsigned)(s.n_out * sizeof(float))};
     if (gp_small) {
         launch_backward_coef_small(s, ws, grad_y_dev, grad_coef_dev, !overwrite, hs);
     } else if (gp_sorted && !gx_fused) {
@@ -372,7 +376,8 @@ lmkan_status backward_impl(const lmkan_desc *desc, int64_t batch, const float *x
         launch_backward_input_small(s, tab, coef_dev, grad_y_dev, ws_scratch, ws, hs);
         launch_input_gradient_out(ws_scratch, grad_x_dev, s, conv, hs);
     } else if (gx_slab) {
-        launch_backward_input_slab(s, tab, coef_dev, grad_y_dev, grad_x_dev, ws, ws_scratch, hs, conv);
+        launch_backward_input_slab(s, tab, coef_dev, gy_k.base, gy_k.tile_stride / (int64_t)sizeof(float),
+                                   gy_k.row_stride / sizeof(float), grad_x_dev, ws, ws_scratch, hs, conv);
     } else if (grad_x_dev) {
         if (conv) launch_fill_zero(grad_x_dev, image_elems, hs);  // the kernel sums into the image
         launch_backward_generic(s, tab, x_dev, coef_dev, grad_y_dev, grad_x_dev, nullptr, hs, conv);

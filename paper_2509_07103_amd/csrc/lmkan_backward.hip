@@ -517,9 +517,17 @@ __global__ __launch_bounds__(64) void backward_coef_stream_kernel(CoefGradArgs a
                 f4v *row = reinterpret_cast<f4v *>(win + (rows_done & 1) * W * kTile) + l16;
                 for (int b = g; b < W; b += 4) {
                     if (col_ok) {
-                        f4v *dst = reinterpret_cast<f4v *>(out + (int64_t)(rows_done * W + b) * a.gmap.s_node);
+                        float *dst = out + (int64_t)(rows_done * W + b) * a.gmap.s_node;
                         const f4v v = row[b * (kTile / 4)];
-                        *dst = a.accumulate ? *dst + v : v;
+                        if ((a.n_out & 3) == 0) {
+                            f4v *d4 = reinterpret_cast<f4v *>(dst);
+                            *d4 = a.accumulate ? *d4 + v : v;
+                        } else {
+                            // rows of the gradient do not start on 16 bytes and the last one is short
+#pragma unroll
+                            for (int e = 0; e < 4; ++e)
+                                if (col + e < a.n_out) dst[e] = a.accumulate ? dst[e] + v[e] : v[e];
+                        }
                     }
                     row[b * (kTile / 4)] = f4v{0.f, 0.f, 0.f, 0.f};
                 }
@@ -623,12 +631,16 @@ bool sorted_batch_ok(const LayerShape &s)
     return nseg <= 65535 && stream_blocks(s.batch) <= 65535 && stream_stride(s.batch, s.G) < ((int64_t)1 << 31);
 }
 
-bool sorted_shape_ok(const LayerShape &s) { return s.n_out % 4 == 0 && sorted_batch_ok(s); }
+// gy is gathered four columns at a time and the gradient leaves four columns at a time: with a
+// ragged output count gy comes from its tile-by-tile copy and the last columns of the gradient are
+// stored one by one, which any 4-byte aligned buffers allow
+bool sorted_shape_ok(const LayerShape &s) { return sorted_batch_ok(s); }
 
 bool coef_sorted_applicable(const LayerShape &s, const float *gy, const float *gcoef)
 {
-    return sorted_shape_ok(s) &&
-           ((reinterpret_cast<uintptr_t>(gy) | reinterpret_cast<uintptr_t>(gcoef)) & 15) == 0;
+    if (!sorted_shape_ok(s)) return false;
+    if (ragged_outputs(s)) return true;
+    return ((reinterpret_cast<uintptr_t>(gy) | reinterpret_cast<uintptr_t>(gcoef)) & 15) == 0;
 }
 
 SortBuffers sort_buffers(const LayerShape &s, void *sorted)
@@ -755,7 +767,14 @@ __global__ __launch_bounds__(256) void gy_tiles_kernel(const float *__restrict__
         const int t = r / (kTile / 4), c = (r % (kTile / 4)) * 4;
         const int col = t * kTile + c;
         f4v v = {0.f, 0.f, 0.f, 0.f};
-        if (col < n_out) v = *reinterpret_cast<const f4v *>(gy + n * n_out + col);
+        if ((n_out & 3) == 0) {
+            if (col < n_out) v = *reinterpret_cast<const f4v *>(gy + n * n_out + col);
+        } else {
+            // rows of gy do not start on 16 bytes
+#pragma unroll
+            for (int e = 0; e < 4; ++e)
+                if (col + e < n_out) v[e] = gy[n * n_out + col + e];
+        }
         *reinterpret_cast<f4v *>(out + ((int64_t)t * B + n) * kTile + c) = v;
     }
 }
@@ -764,7 +783,8 @@ __global__ __launch_bounds__(256) void gy_tiles_kernel(const float *__restrict__
 
 // Measured: the copy pays from rows of 8 KiB on (at 4096 outputs the gathers' HBM reads fall from
 // 62 GB to 18 GB and the coefficient gradient gains 9 %; at 1024 outputs it costs 2 %).
-static bool gy_tiles_pay(const LayerShape &s) { return (size_t)s.n_out * sizeof(float) >= 8192; }
+// A ragged output count needs the copy whatever the width: its rows are padded to whole tiles.
+static bool gy_tiles_pay(const LayerShape &s) { return (size_t)s.n_out * sizeof(float) >= 8192 || ragged_outputs(s); }
 
 size_t gy_tiles_bytes(const LayerShape &s)
 {

@@ -231,9 +231,17 @@ __global__ __launch_bounds__(64) void backward_fused_kernel(FusedArgs a)
                 f4v *row = reinterpret_cast<f4v *>(win + (rows_done & 1) * W * kTile) + l16;
                 for (int b = g; b < W; b += 4) {
                     if (col_ok) {
-                        f4v *dst = reinterpret_cast<f4v *>(out + (int64_t)(rows_done * W + b) * a.gmap.s_node);
+                        float *dst = out + (int64_t)(rows_done * W + b) * a.gmap.s_node;
                         const f4v v = row[b * (kTile / 4)];
-                        *dst = a.accumulate ? *dst + v : v;
+                        if ((a.n_out & 3) == 0) {
+                            f4v *d4 = reinterpret_cast<f4v *>(dst);
+                            *d4 = a.accumulate ? *d4 + v : v;
+                        } else {
+                            // rows of the gradient do not start on 16 bytes and the last one is short
+#pragma unroll
+                            for (int e = 0; e < 4; ++e)
+                                if (col + e < a.n_out) dst[e] = a.accumulate ? dst[e] + v[e] : v[e];
+                        }
                     }
                     row[b * (kTile / 4)] = f4v{0.f, 0.f, 0.f, 0.f};
                 }
@@ -486,10 +494,11 @@ __global__ __launch_bounds__(256) void gx_combine_kernel(const float2 *__restric
 
 bool fused_backward_applicable(const LayerShape &s, const void *coef, const float *gy, const float *gcoef)
 {
-    if (s.n_out % 4 != 0 || !sorted_batch_ok(s)) return false;
+    if (!outputs_by_four_ok(s) || !sorted_batch_ok(s)) return false;
     const uintptr_t coef_align = s.dtype == LMKAN_F32 ? 15 : 7;
     // rows of the table must keep that alignment too: every stride is a multiple of n_out (4 | n_out) or of 64
     if ((reinterpret_cast<uintptr_t>(coef) & coef_align) != 0) return false;
+    if (ragged_outputs(s)) return true;  // gy through its tile-by-tile copy, gradient columns one by one
     return ((reinterpret_cast<uintptr_t>(gy) | reinterpret_cast<uintptr_t>(gcoef)) & 15) == 0;
 }
 

@@ -23,6 +23,14 @@ struct LayerShape {
 
 CoefMap coef_map(const LayerShape &s);
 
+// The tuned kernels move four adjacent outputs at a time.  That needs rows of the table that
+// start on a multiple of four outputs: any n_out in the packed layout (rows padded to 64, the
+// padding finite: lmkan_pack writes zeros), a multiple of four in the layout of Alg. 1.  When
+// n_out itself is not a multiple of four (`ragged_outputs`), y and the coefficient gradient are
+// written element by element in the last columns and gy is read through its tile-by-tile copy.
+inline bool ragged_outputs(const LayerShape &s) { return (s.n_out & 3) != 0; }
+inline bool outputs_by_four_ok(const LayerShape &s) { return !ragged_outputs(s) || s.layout == LMKAN_LAYOUT_PACKED; }
+
 // Raises the dynamic LDS limit of a kernel on the current device, once per (device, kernel);
 // safe to call from several host threads.  The first call for a kernel on a device talks to
 // the runtime (hipFuncSetAttribute), so it must not happen inside a stream capture.
@@ -73,9 +81,11 @@ void launch_forward_slab(const LayerShape &s, const void *coef, float *y, const 
 bool slab_backward_input_shape_ok(const LayerShape &s);
 bool slab_backward_input_applicable(const LayerShape &s, const void *coef, const float *gy, const float *gx);
 size_t slab_backward_input_scratch_bytes(const LayerShape &s);
+// gy as [batch][n_out] (gy_tile_stride = 64, gy_row_stride = n_out, in floats), or its tile-by-tile
+// copy [tiles][batch][64] (batch * 64 and 64), which ragged output counts need
 void launch_backward_input_slab(const LayerShape &s, const GridTab &tab, const void *coef, const float *gy,
-                                float *gx, const void *records, void *scratch, hipStream_t stream,
-                                const ConvGeom *conv = nullptr);
+                                int64_t gy_tile_stride, int64_t gy_row_stride, float *gx, const void *records,
+                                void *scratch, hipStream_t stream, const ConvGeom *conv = nullptr);
 
 // float16 tables kept as float16 in LDS (lmkan_slab_f16.hip); reached through the two slab
 // launchers above when slab_f16_native_ok().  gx_scratch is the zero-filled transposed scratch.
@@ -83,7 +93,8 @@ bool slab_f16_native_ok(const LayerShape &s);
 void launch_forward_slab_f16(const LayerShape &s, const void *coef, float *y, const void *records, float *partials,
                              hipStream_t stream);
 void launch_backward_input_slab_f16(const LayerShape &s, const GridTab &tab, const void *coef, const float *gy,
-                                    float *gx_scratch, const void *records, hipStream_t stream);
+                                    int64_t gy_tile_stride, int64_t gy_row_stride, float *gx_scratch,
+                                    const void *records, hipStream_t stream);
 
 // Layers with at most kSmallMaxOut outputs (lmkan_small.hip): a lane is a sample.  All three use
 // the preamble records; the input gradient goes to the transposed scratch [n_in][B] (every

@@ -428,18 +428,7 @@ __global__ __launch_bounds__(WAVES * 64) __attribute__((amdgpu_waves_per_eu(WAVE
 #pragma unroll
             for (int st = 0; st < 16; ++st) {
                 const int64_t n = n_wave + s * 64 + g * 16 + st;
-                if (n < a.B) {
-                    float *dst = ybase + n * a.n_out + col;
-                    const float *v = acc + s * 64 + st * 4;
-                    if (atomic) {
-                        unsafeAtomicAdd(dst + 0, v[0]);
-                        unsafeAtomicAdd(dst + 1, v[1]);
-                        unsafeAtomicAdd(dst + 2, v[2]);
-                        unsafeAtomicAdd(dst + 3, v[3]);
-                    } else {
-                        *reinterpret_cast<float4 *>(dst) = make_float4(v[0], v[1], v[2], v[3]);
-                    }
-                }
+                if (n < a.B) store_outputs(ybase + n * a.n_out + col, acc + s * 64 + st * 4, a.n_out, col, atomic);
             }
         }
     }
@@ -553,7 +542,8 @@ __global__ __launch_bounds__(WAVES * 64) __attribute__((amdgpu_waves_per_eu(WAVE
     for (int t = 0; t < TOTAL; ++t) {
         const int64_t n = n_wave + (t / 16) * 64 + g * 16 + (t % 16);
         gyr[t] = make_float4(0.f, 0.f, 0.f, 0.f);
-        if (n < a.B && col < a.n_out) gyr[t] = *reinterpret_cast<const float4 *>(a.gy + n * a.n_out + col);
+        if (n < a.B && col < a.n_out)
+            gyr[t] = *reinterpret_cast<const float4 *>(a.gy + (col >> 6) * a.gy_tile_stride + n * a.gy_row_stride + (col & 63));
     }
 
     int nx_node[SETS];
@@ -844,18 +834,7 @@ __global__ __launch_bounds__(WAVES * 64) __attribute__((amdgpu_waves_per_eu(WAVE
 #pragma unroll
         for (int F = 0; F < STEPS; ++F) {
             const int64_t n = n_wave + (F / LPS) * 64 + grp * LPS + (F % LPS);
-            if (n < a.B) {
-                float *dst = ybase + n * a.n_out + col;
-                const float *v = acc + 4 * F;
-                if (atomic) {
-                    unsafeAtomicAdd(dst + 0, v[0]);
-                    unsafeAtomicAdd(dst + 1, v[1]);
-                    unsafeAtomicAdd(dst + 2, v[2]);
-                    unsafeAtomicAdd(dst + 3, v[3]);
-                } else {
-                    *reinterpret_cast<float4 *>(dst) = make_float4(v[0], v[1], v[2], v[3]);
-                }
-            }
+            if (n < a.B) store_outputs(ybase + n * a.n_out + col, acc + 4 * F, a.n_out, col, atomic);
         }
     }
 }
@@ -941,7 +920,8 @@ __global__ __launch_bounds__(WAVES * 64) __attribute__((amdgpu_waves_per_eu(WAVE
     for (int F = 0; F < STEPS; ++F) {
         const int64_t n = n_wave + (F / LPS) * 64 + grp * LPS + (F % LPS);
         gyr[F] = make_float4(0.f, 0.f, 0.f, 0.f);
-        if (n < a.B && col < a.n_out) gyr[F] = *reinterpret_cast<const float4 *>(a.gy + n * a.n_out + col);
+        if (n < a.B && col < a.n_out)
+            gyr[F] = *reinterpret_cast<const float4 *>(a.gy + (col >> 6) * a.gy_tile_stride + n * a.gy_row_stride + (col & 63));
     }
 
     int r_node[SETS];
@@ -1075,7 +1055,7 @@ void launch_preamble_records(const LayerShape &s, const GridTab &tab, const floa
 // 64-output tiles: the float32 slab fits LDS twice (G <= 16)
 static bool slab_wide_ok(const LayerShape &s)
 {
-    if (s.n_out % 4 != 0) return false;
+    if (!outputs_by_four_ok(s)) return false;
     if (slab_forward_lds_bytes(s) > 160 * 1024) return false;
     if (s.batch < 256) return false;  // too little work to pay for the slab streaming
     return true;
@@ -1084,14 +1064,14 @@ static bool slab_wide_ok(const LayerShape &s)
 // 16-output tiles for larger grids (G <= 34)
 static bool slab_narrow_ok(const LayerShape &s)
 {
-    if (s.n_out % 4 != 0 || s.batch < 256) return false;
+    if (!outputs_by_four_ok(s) || s.batch < 256) return false;
     return !slab_wide_ok(s) && (size_t)2 * s.nodes() * kNarrowRowBytes <= 160 * 1024;
 }
 
 // forward only: one 16-output slab at a time (35 <= G <= 48)
 static bool slab_narrow_single_ok(const LayerShape &s)
 {
-    if (s.n_out % 4 != 0 || s.batch < 256) return false;
+    if (!outputs_by_four_ok(s) || s.batch < 256) return false;
     return !slab_wide_ok(s) && !slab_narrow_ok(s) && (size_t)s.nodes() * kNarrowRowBytes <= 160 * 1024 - 512;
 }
 
@@ -1114,24 +1094,33 @@ int slab_forward_split(const LayerShape &s)
 size_t slab_forward_partial_bytes(const LayerShape &s)
 {
     const size_t parts = (size_t)slab_forward_split(s) - 1;
-    return (parts * (size_t)s.batch * s.n_out * sizeof(float) + 255) & ~(size_t)255;
+    return (parts * (size_t)partial_stride((int64_t)s.batch * s.n_out) * sizeof(float) + 255) & ~(size_t)255;
 }
 
 namespace {
-__global__ __launch_bounds__(256) void sum_partials_kernel(float4 *__restrict__ y, const float4 *__restrict__ part,
-                                                          int n_part, int64_t quads)
+// y[i] += sum over p of part[p * stride + i]; stride is a multiple of four, y and part 16-byte aligned
+__global__ __launch_bounds__(256) void sum_partials_kernel(float *__restrict__ y, const float *__restrict__ part,
+                                                          int n_part, int64_t elems, int64_t stride)
 {
-    const int64_t stride = (int64_t)gridDim.x * 256;
-    for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < quads; i += stride) {
-        float4 v = y[i];
+    const int64_t quads = elems / 4;
+    const int64_t step = (int64_t)gridDim.x * 256;
+    for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < quads; i += step) {
+        float4 v = reinterpret_cast<float4 *>(y)[i];
         for (int p = 0; p < n_part; ++p) {
-            const float4 w = part[(int64_t)p * quads + i];
+            const float4 w = reinterpret_cast<const float4 *>(part + (int64_t)p * stride)[i];
             v.x += w.x;
             v.y += w.y;
             v.z += w.z;
             v.w += w.w;
         }
-        y[i] = v;
+        reinterpret_cast<float4 *>(y)[i] = v;
+    }
+    // the last one to three elements of a tensor whose size is not a multiple of four
+    const int64_t t = quads * 4 + (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (t < elems) {
+        float v = y[t];
+        for (int p = 0; p < n_part; ++p) v += part[(int64_t)p * stride + t];
+        y[t] = v;
     }
 }
 }  // namespace
@@ -1139,9 +1128,10 @@ __global__ __launch_bounds__(256) void sum_partials_kernel(float4 *__restrict__ 
 void launch_sum_partials(float *y, const float *part, int n_part, int64_t elems, hipStream_t stream)
 {
     const int64_t quads = elems / 4;
-    const int64_t blocks = (quads + 255) / 256;
-    sum_partials_kernel<<<(unsigned)(blocks < 8192 ? blocks : 8192), 256, 0, stream>>>(
-        reinterpret_cast<float4 *>(y), reinterpret_cast<const float4 *>(part), n_part, quads);
+    int64_t blocks = (quads + 255) / 256;
+    if (blocks < 1) blocks = 1;
+    sum_partials_kernel<<<(unsigned)(blocks < 8192 ? blocks : 8192), 256, 0, stream>>>(y, part, n_part, elems,
+                                                                                      partial_stride(elems));
 }
 
 bool slab_forward_applicable(const LayerShape &s, const void *coef, const float *y)
@@ -1193,7 +1183,7 @@ static void launch_forward_slab_narrow(const LayerShape &s, const void *coef, fl
         KernelTiming timing(stream, kTimeForward);
         kernel<<<tiles * split, waves * 64, (size_t)(single ? 1 : 2) * s.nodes() * kNarrowRowBytes, stream>>>(a);
     }
-    if (a.y_part) launch_sum_partials(y, a.y_part, split - 1, a.part_elems, stream);
+    if (a.y_part) launch_sum_partials(y, a.y_part, split - 1, (int64_t)s.batch * s.n_out, stream);
 }
 
 void launch_forward_slab(const LayerShape &s, const void *coef, float *y, const void *records, float *partials,
@@ -1246,7 +1236,7 @@ void launch_forward_slab(const LayerShape &s, const void *coef, float *y, const 
         KernelTiming timing(stream, kTimeForward);
         kernel<<<tiles * split, waves * 64, slab_forward_lds_bytes(s), stream>>>(a);
     }
-    if (a.y_part) launch_sum_partials(y, a.y_part, split - 1, a.part_elems, stream);
+    if (a.y_part) launch_sum_partials(y, a.y_part, split - 1, (int64_t)s.batch * s.n_out, stream);
 }
 
 }  // namespace lmkan
@@ -1258,8 +1248,9 @@ bool slab_backward_input_shape_ok(const LayerShape &s) { return slab_wide_ok(s) 
 bool slab_backward_input_applicable(const LayerShape &s, const void *coef, const float *gy, const float *gx)
 {
     if (!slab_backward_input_shape_ok(s)) return false;
-    return ((reinterpret_cast<uintptr_t>(coef) | reinterpret_cast<uintptr_t>(gy)) & 15) == 0 &&
-           (reinterpret_cast<uintptr_t>(gx) & 3) == 0;
+    // (with a ragged output count gy is read through its tile-by-tile copy, which is aligned)
+    if ((reinterpret_cast<uintptr_t>(coef) & 15) != 0 || (reinterpret_cast<uintptr_t>(gx) & 3) != 0) return false;
+    return ragged_outputs(s) || (reinterpret_cast<uintptr_t>(gy) & 15) == 0;
 }
 
 namespace {
@@ -1356,13 +1347,14 @@ size_t slab_backward_input_scratch_bytes(const LayerShape &s)
 }
 
 void launch_backward_input_slab(const LayerShape &s, const GridTab &tab, const void *coef, const float *gy,
-                                float *gx, const void *records, void *scratch, hipStream_t stream,
-                                const ConvGeom *conv)
+                                int64_t gy_tile_stride, int64_t gy_row_stride, float *gx, const void *records,
+                                void *scratch, hipStream_t stream, const ConvGeom *conv)
 {
     if (slab_wide_ok(s) && slab_f16_native_ok(s)) {
         launch_fill_zero(static_cast<float *>(scratch), (size_t)scratch_row_stride(s.batch, kScratchOct) * s.n_in,
                          stream);
-        launch_backward_input_slab_f16(s, tab, coef, gy, static_cast<float *>(scratch), records, stream);
+        launch_backward_input_slab_f16(s, tab, coef, gy, gy_tile_stride, gy_row_stride, static_cast<float *>(scratch),
+                                       records, stream);
         launch_input_gradient_out(static_cast<float *>(scratch), gx, s, conv, stream, kScratchOct);
         return;
     }
@@ -1388,6 +1380,8 @@ void launch_backward_input_slab(const LayerShape &s, const GridTab &tab, const v
     GradInArgs a;
     a.P = coef;
     a.gy = gy;
+    a.gy_tile_stride = gy_tile_stride;
+    a.gy_row_stride = gy_row_stride;
     a.gx = static_cast<float *>(scratch);
     a.rec_node = static_cast<const int32_t *>(records);
     a.rec_u = reinterpret_cast<const float *>(a.rec_node + n);

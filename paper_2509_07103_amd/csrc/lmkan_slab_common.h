@@ -42,14 +42,34 @@ inline int pair_split_count(int tiles, int K)
     return split;
 }
 
+// floats between the partial outputs of consecutive pair splits: a whole number of 16-byte pieces
+inline int64_t partial_stride(int64_t elems) { return (elems + 3) & ~(int64_t)3; }
+
 // How the splits of a forward launch combine: separate parts when the caller brought room for
 // them, atomics on a cleared y otherwise.
 inline void finish_split_setup(SlabArgs &a, const LayerShape &s, float *y, float *partials, hipStream_t stream)
 {
     a.y_part = a.n_split > 1 ? partials : nullptr;
-    a.part_elems = (int64_t)s.batch * s.n_out;
+    a.part_elems = partial_stride((int64_t)s.batch * s.n_out);
     a.atomic_out = a.n_split > 1 && !a.y_part;
     if (a.atomic_out) launch_fill_zero(y, (size_t)s.batch * s.n_out, stream);
+}
+
+// four adjacent outputs of a sample leave the registers: one 16-byte store when every row of y
+// starts on a multiple of four outputs, else element by element up to the last column
+__device__ __forceinline__ void store_outputs(float *dst, const float *v, int n_out, int col, bool atomic)
+{
+    if (atomic) {
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+            if (col + i < n_out) unsafeAtomicAdd(dst + i, v[i]);
+    } else if ((n_out & 3) == 0) {
+        *reinterpret_cast<float4 *>(dst) = make_float4(v[0], v[1], v[2], v[3]);
+    } else {
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+            if (col + i < n_out) dst[i] = v[i];
+    }
 }
 
 // where a forward workgroup of pair split ks stores, and whether it has to add atomically
@@ -91,7 +111,9 @@ __device__ __forceinline__ void lds_dma16_uniform(const void *gbase, unsigned la
 
 struct GradInArgs {
     const void *P;     // float32, or 16-bit storage converted while the slab is filled
-    const float *gy;
+    const float *gy;   // column c of row n at gy[(c >> 6) * gy_tile_stride + n * gy_row_stride + (c & 63)]
+    int64_t gy_tile_stride;
+    int64_t gy_row_stride;
     float *gx;  // transposed scratch [n_in][ld], zero on entry
     int64_t ld; // row stride of the scratch: B, or B rounded up to 64 with a permuted layout
     const int32_t *rec_node;

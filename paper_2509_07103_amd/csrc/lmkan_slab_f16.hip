@@ -176,18 +176,7 @@ __global__ __launch_bounds__(kWaves * 64) __attribute__((amdgpu_waves_per_eu(4, 
 #pragma unroll
         for (int st = 0; st < 16; ++st) {
             const int64_t n = n_wave + g * 16 + st;
-            if (n < a.B) {
-                float *dst = ybase + n * a.n_out + col;
-                const float *v = acc + st * 4;
-                if (atomic) {
-                    unsafeAtomicAdd(dst + 0, v[0]);
-                    unsafeAtomicAdd(dst + 1, v[1]);
-                    unsafeAtomicAdd(dst + 2, v[2]);
-                    unsafeAtomicAdd(dst + 3, v[3]);
-                } else {
-                    *reinterpret_cast<float4 *>(dst) = make_float4(v[0], v[1], v[2], v[3]);
-                }
-            }
+            if (n < a.B) store_outputs(ybase + n * a.n_out + col, acc + st * 4, a.n_out, col, atomic);
         }
     }
 }
@@ -265,7 +254,8 @@ __global__ __launch_bounds__(kWaves * 64) __attribute__((amdgpu_waves_per_eu(4, 
     for (int t = 0; t < 16; ++t) {
         const int64_t n = n_wave + g * 16 + t;
         gyr[t] = make_float4(0.f, 0.f, 0.f, 0.f);
-        if (n < a.B && col < a.n_out) gyr[t] = *reinterpret_cast<const float4 *>(a.gy + n * a.n_out + col);
+        if (n < a.B && col < a.n_out)
+            gyr[t] = *reinterpret_cast<const float4 *>(a.gy + (col >> 6) * a.gy_tile_stride + n * a.gy_row_stride + (col & 63));
     }
 
     int nx_node = 0;
@@ -386,11 +376,12 @@ void launch_forward_slab_f16(const LayerShape &s, const void *coef, float *y, co
         KernelTiming timing(stream, kTimeForward);
         forward_slab_f16_kernel<<<tiles * split, kWaves * 64, (size_t)2 * s.nodes() * kRowBytesH, stream>>>(a);
     }
-    if (a.y_part) launch_sum_partials(y, a.y_part, split - 1, a.part_elems, stream);
+    if (a.y_part) launch_sum_partials(y, a.y_part, split - 1, (int64_t)s.batch * s.n_out, stream);
 }
 
 void launch_backward_input_slab_f16(const LayerShape &s, const GridTab &tab, const void *coef, const float *gy,
-                                    float *gx_scratch, const void *records, hipStream_t stream)
+                                    int64_t gy_tile_stride, int64_t gy_row_stride, float *gx_scratch,
+                                    const void *records, hipStream_t stream)
 {
     constexpr int kTileB = kWaves * 64;
     allow_large_lds(reinterpret_cast<const void *>(backward_input_slab_f16_kernel), 160 * 1024);
@@ -398,6 +389,8 @@ void launch_backward_input_slab_f16(const LayerShape &s, const GridTab &tab, con
     GradInArgs a;
     a.P = coef;
     a.gy = gy;
+    a.gy_tile_stride = gy_tile_stride;
+    a.gy_row_stride = gy_row_stride;
     a.gx = gx_scratch;
     a.rec_node = static_cast<const int32_t *>(records);
     a.rec_u = reinterpret_cast<const float *>(a.rec_node + n);

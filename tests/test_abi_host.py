@@ -144,6 +144,26 @@ def test_workspace_sizes_follow_the_limits_of_the_sorted_path():
     assert pkg.lmkan_workspace_bytes(d, limit + 1, False) >= (limit + 1) * records
 
 
+def test_workspace_holds_a_sorted_stream_whenever_a_gradient_needs_one():
+    """Layers with few outputs take kernels of their own, but their coefficient gradient needs the
+    cell-sorted stream once a pair's slice of it no longer fits LDS (fine grids): the workspace of
+    a call for both gradients must then hold the stream, as the call for the coefficient gradient
+    alone does."""
+    B = 1000
+    entry = 16                                  # bytes per pair and sample in the sorted stream
+    fine = _desc(n_in=4, n_out=8, grid=64)      # 65^2 nodes x 8 outputs x 4 bytes > 64 KiB
+    coarse = _desc(n_in=4, n_out=8, grid=8)
+    for d, needs_stream in ((fine, True), (coarse, False)):
+        both = pkg.lmkan_workspace_bytes(d, B, True)
+        gx_only = pkg.lmkan_workspace_bytes(d, B, True, need_grad_coef=False)
+        gp_only = pkg.lmkan_workspace_bytes(d, B, True, need_grad_x=False)
+        assert (both - gx_only >= 2 * B * entry) == needs_stream
+        assert (gp_only >= 2 * B * (entry + 12)) == needs_stream
+    # an output count that is not a multiple of four: sorted as well, with room for the copy of gy
+    ragged = _desc(n_in=4, n_out=10, grid=8)
+    assert pkg.lmkan_workspace_bytes(ragged, B, True, need_grad_x=False) >= 2 * B * (entry + 12) + B * 64 * 4
+
+
 def test_packed_size_pads_outputs_to_the_tile():
     for n_out, tiles in ((1, 1), (64, 1), (65, 2), (1024, 16)):
         for dt, sz in ((binding.LMKAN_F32, 4), (binding.LMKAN_F16, 2), (binding.LMKAN_BF16, 2)):

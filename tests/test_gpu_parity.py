@@ -90,6 +90,18 @@ SHAPES = [
     (600, 4, 64, 64),
     (13000, 6, 68, 36),
     (7000, 12, 72, 20),
+    # output counts that are not a multiple of four on the tuned kernels (packed tables): a ten-way
+    # head, a last tile of one output, 16-output slabs, the single-slab forward, the sorted walk
+    # with dense cells, a pair split; and few outputs on a grid too fine for their own
+    # coefficient-gradient kernel
+    (1000, 16, 10, 16),
+    (2200, 40, 193, 8),
+    (700, 6, 21, 24),
+    (600, 4, 18, 40),
+    (7000, 6, 70, 20),
+    (1100, 140, 66, 16),
+    (300, 4, 8, 64),
+    (300, 4, 3, 64),
 ]
 
 
