@@ -53,7 +53,7 @@ def kernel_names(w, n_out, B, storage, packed):
     for both gradients when one kernel forms both: mirrors the library's dispatch (lmkan_api.hip)."""
     ok = (n_out % 4 == 0 or packed) and B >= 256
     both = None
-    if n_out <= 8:
+    if n_out == 1 or (n_out <= 8 and not (ok and w.grid <= 34)):
         fwd, gx, gp = "forward_small_kernel", "backward_input_small_kernel", "backward_coef_small_kernel"
     elif ok and w.grid <= 16:
         f16 = storage == "f16" and (packed or n_out % 8 == 0)

@@ -134,6 +134,10 @@ lmkan_status lmkan_grid(int32_t grid, float *nodes_host, float *inv_h_host);
  * multiple of LMKAN_PACK_TILE and the tensor is stored as
  * [n_out_tiles][n_in/2][(G+1)^2][LMKAN_PACK_TILE] in desc->coef_dtype, so the
  * table rows one workgroup needs for one pair are contiguous.  0 on bad desc.
+ * The tuned kernels move four adjacent outputs at a time: they take any n_out
+ * with a packed table (padding columns must hold finite values; lmkan_pack
+ * writes zeros), and n_out that is a multiple of four with a table in the
+ * layout of Alg. 1; other layers in that layout run on slower general kernels.
  */
 size_t lmkan_packed_bytes(const lmkan_desc *desc);
 
@@ -152,7 +156,9 @@ lmkan_status lmkan_pack(const lmkan_desc *desc, const void *coef_paper_dev, void
  *             leave compute units idle and the pairs are therefore split over several
  *             workgroups, one [batch][n_out] float32 partial output per extra split
  *             (summed in a fixed order: the forward result does not vary between
- *             runs, except for n_out <= 8, where the splits add atomically).
+ *             runs, except where the kernels for very few outputs run (one output,
+ *             or up to eight where no slab kernel applies): their splits add
+ *             atomically).
  *   pass = 1  lmkan_backward with both gradients; 2: grad_x only; 3: grad_coef only.
  *             The same records; their copy sorted by cell (16 bytes per (sample,
  *             pair) plus per-pair tables) when a kernel that walks it can serve the
@@ -224,7 +230,8 @@ lmkan_status lmkan_forward_static(const lmkan_desc *desc, int64_t batch, const f
  * e.g. 1024 -> 1024); shorter layers and longer batches cut the streams into
  * runs that meet through float32 atomics, and the generic kernels use atomics
  * throughout: there the last bits can differ.  grad_x repeats bit for bit on the
- * sorted walk (grids finer than 34 intervals) and for n_out <= 8; the slab
+ * sorted walk (grids finer than 34 intervals) and in the kernels for very few
+ * outputs (one output, or up to eight where no slab kernel applies); the slab
  * kernels (grids up to 34) add their output tiles with float32 atomics.
  */
 lmkan_status lmkan_backward(const lmkan_desc *desc, int64_t batch, const float *x_dev,

@@ -42,7 +42,7 @@ BackwardWorkspace backward_workspace(const LayerShape &s, bool want_gx, bool wan
     w.scratch = w.sorted + (sorted ? sorted_records_bytes(s) : 0);
     w.partial = w.scratch + (want_gx ? slab_backward_input_scratch_bytes(s) : 0);
     w.gy_tiles = w.partial + (want_gx && !small && sorted ? fused_partial_bytes(s) : 0);
-    w.total = w.gy_tiles + gy_tiles_bytes(s);
+    w.total = w.gy_tiles + (sorted || (want_gx && !small) ? gy_tiles_bytes(s) : 0);
     return w;
 }
 

@@ -96,7 +96,8 @@ void launch_backward_input_slab_f16(const LayerShape &s, const GridTab &tab, con
                                     int64_t gy_tile_stride, int64_t gy_row_stride, float *gx_scratch,
                                     const void *records, hipStream_t stream);
 
-// Layers with at most kSmallMaxOut outputs (lmkan_small.hip): a lane is a sample.  All three use
+// Layers with one output, or with at most kSmallMaxOut where no slab kernel applies
+// (small_out_shape_ok; lmkan_small.hip): a lane is a sample.  All three use
 // the preamble records; the input gradient goes to the transposed scratch [n_in][B] (every
 // element written, no zero fill needed) and launch_transpose finishes it.
 constexpr int kSmallMaxOut = 8;

@@ -1,4 +1,8 @@
-// Layers with very few outputs (n_out <= 8: regression and classification heads).
+// Layers with very few outputs: a single output (regression heads), and up to eight outputs where
+// the slab kernels do not apply (batches under 256 rows, grids finer than 34 intervals, tables in
+// the layout of Alg. 1 whose output count is not a multiple of four).  From two outputs on the
+// slab kernels are faster even with most of their 64-output tile empty (256 -> 8, 65536 rows:
+// 0.44 ms for both gradients against 2.0 ms here; 256 -> 1: 0.46 against 0.37).
 //
 // With so few outputs the lanes cannot be outputs: here a lane is a sample and walks over the
 // pairs, the preamble records (cell, local coordinates) arriving coalesced along the sample
@@ -189,7 +193,10 @@ int pair_split(const LayerShape &s)
 
 }  // namespace
 
-bool small_out_shape_ok(const LayerShape &s) { return s.n_out <= kSmallMax; }
+bool small_out_shape_ok(const LayerShape &s)
+{
+    return s.n_out <= kSmallMax && (s.n_out == 1 || !slab_backward_input_shape_ok(s));
+}
 
 void launch_forward_small(const LayerShape &s, const void *coef, float *y, const void *records, hipStream_t stream)
 {
