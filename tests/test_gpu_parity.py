@@ -102,6 +102,13 @@ SHAPES = [
     (1100, 140, 66, 16),
     (300, 4, 8, 64),
     (300, 4, 3, 64),
+    # batches under 256 rows on layers wide enough for the slab kernels anyway (pairs x outputs
+    # >= 8192), down to a single row; 16-output slabs, the single-slab forward, a ragged head
+    (1, 128, 128, 16),
+    (3, 64, 256, 8),
+    (37, 130, 140, 20),
+    (5, 140, 132, 40),
+    (100, 1100, 10, 12),
 ]
 
 
