@@ -334,7 +334,8 @@ lmkan_status backward_impl(const lmkan_desc *desc, int64_t batch, const float *x
     const bool slab_ok = grad_x_dev && !small && slab_backward_input_applicable(s, coef_dev, grad_y_dev, grad_x_dev);
     const bool dense_cells = s.batch >= (int64_t)16 * s.G * s.G;
     const bool fused_pays = !slab_ok || (!slab_tile_is_wide(s) && grad_coef_dev && dense_cells);
-    const bool gx_fused = grad_x_dev && !small && s.batch >= 256 && fused_pays &&
+    const bool enough_work = s.batch >= 256 || (int64_t)s.pairs() * s.n_out >= 8192;  // as for the slab kernels
+    const bool gx_fused = grad_x_dev && !small && enough_work && fused_pays &&
                           fused_backward_applicable(s, coef_dev, grad_y_dev, grad_coef_dev);
     const bool gx_slab = slab_ok && !gx_fused;
     const bool gp_sorted = grad_coef_dev && !gp_small && coef_sorted_applicable(s, grad_y_dev, grad_coef_dev);
