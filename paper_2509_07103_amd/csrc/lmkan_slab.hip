@@ -1409,7 +1409,7 @@ void launch_backward_input_slab(const LayerShape &s, const GridTab &tab, const v
     a.n_jt = narrow ? (s.n_out + kNarrowTile - 1) / kNarrowTile : s.out_tiles();
     const int tiles = a.n_btiles * a.n_jt;
     int split = 1;
-    while (tiles * split < 256 && a.K / (split * 2) >= 32) split *= 2;
+    while (tiles * split < 256 && a.K / (split * 2) >= 4) split *= 2;
     a.n_split = split;
     a.pairs_per_split = (a.K + split - 1) / split;
     const int layout = narrow ? kScratchQuad : kScratchOct;

@@ -410,7 +410,7 @@ void launch_backward_input_slab_f16(const LayerShape &s, const GridTab &tab, con
     a.n_jt = s.out_tiles();
     const int tiles = a.n_btiles * a.n_jt;
     int split = 1;
-    while (tiles * split < 256 && a.K / (split * 2) >= 32) split *= 2;
+    while (tiles * split < 256 && a.K / (split * 2) >= 4) split *= 2;
     a.n_split = split;
     a.pairs_per_split = (a.K + split - 1) / split;
     const size_t lds = (((size_t)2 * s.nodes() * kRowBytesH + 15) & ~(size_t)15) + LMKAN_MAX_GRID * sizeof(float);
