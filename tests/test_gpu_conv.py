@@ -38,6 +38,8 @@ CASES = [
     (5, 18, 18, 4, 3, 3, 1, 20, 20),    # 1280  16-output slabs (G > 16), overlapping windows
     (3, 20, 20, 2, 2, 2, 2, 24, 24),    # 300   16-output slabs, rows not a multiple of 64
     (3, 21, 20, 2, 2, 2, 2, 64, 8),     # 300   64-output slabs, rows not a multiple of 64, a row of pixels left over
+    (4, 32, 32, 6, 2, 2, 2, 10, 8),     # 1024  slab with a ten-way head (packed table), generic in the layout of Alg. 1
+    (2, 24, 24, 4, 3, 3, 1, 18, 20),    # 968   16-output slabs, output count not a multiple of four, overlapping windows
 ]
 
 
