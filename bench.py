@@ -51,6 +51,8 @@ def parse():
 def kernel_names(w, n_out, B, storage, packed):
     """Main kernel of a forward call, of a grad_x-only call and of a grad_coef-only call, and of a call
     for both gradients when one kernel forms both: mirrors the library's dispatch (lmkan_api.hip)."""
+    # (the forward pass alone takes the slab kernels from pairs x outputs >= 1024 on; every workload
+    # of this file has 256 rows or more, where both rules say yes)
     ok = (n_out % 4 == 0 or packed) and (B >= 256 or (w.n_in // 2) * n_out >= 8192)
     both = None
     if n_out == 1 or (n_out <= 8 and not (ok and w.grid <= 34)):

@@ -1054,46 +1054,46 @@ void launch_preamble_records(const LayerShape &s, const GridTab &tab, const floa
 
 // 64-output tiles: the float32 slab fits LDS twice (G <= 16)
 // Streaming every slab of the table through LDS pays from 256 rows on for any layer, and for any
-// batch once a row is some work (pairs x outputs >= 8192, e.g. 128 -> 128): a single row of a
-// 1024 -> 1024 layer takes 0.13 ms forward and 0.16 ms for grad_x here, about what it takes to
-// read the table, against 0.68 and 2.8 ms on the generic kernels; a 16 -> 16 layer is quicker there.
-static bool slab_batch_ok(const LayerShape &s)
+// batch once a row is some work: pairs x outputs >= 8192 (e.g. 128 -> 128) for the input
+// gradient, >= 1024 (64 -> 32) for the forward pass.  A single row of a 1024 -> 1024 layer takes
+// 0.13 ms forward and 0.16 ms for grad_x here, about what it takes to read the table, against
+// 0.68 and 2.8 ms on the generic kernels; 64 rows of 128 -> 32 take 0.029 ms forward against
+// 0.109, but 0.037 ms for grad_x against 0.043; a 16 -> 16 layer is quicker on the generic kernels.
+static bool slab_batch_ok(const LayerShape &s, bool forward)
 {
-    return s.batch >= 256 || (int64_t)s.pairs() * s.n_out >= 8192;
+    return s.batch >= 256 || (int64_t)s.pairs() * s.n_out >= (forward ? 1024 : 8192);
 }
 
-static bool slab_wide_ok(const LayerShape &s)
+// which tile a shape takes when it takes a slab kernel at all
+static bool slab_wide_fits(const LayerShape &s)
 {
-    if (!outputs_by_four_ok(s)) return false;
-    if (slab_forward_lds_bytes(s) > 160 * 1024) return false;
-    return slab_batch_ok(s);
+    return outputs_by_four_ok(s) && slab_forward_lds_bytes(s) <= 160 * 1024;
 }
 
 // 16-output tiles for larger grids (G <= 34)
-static bool slab_narrow_ok(const LayerShape &s)
+static bool slab_narrow_fits(const LayerShape &s)
 {
-    if (!outputs_by_four_ok(s) || !slab_batch_ok(s)) return false;
-    return !slab_wide_ok(s) && (size_t)2 * s.nodes() * kNarrowRowBytes <= 160 * 1024;
+    return outputs_by_four_ok(s) && !slab_wide_fits(s) && (size_t)2 * s.nodes() * kNarrowRowBytes <= 160 * 1024;
 }
 
 // forward only: one 16-output slab at a time (35 <= G <= 48)
-static bool slab_narrow_single_ok(const LayerShape &s)
+static bool slab_narrow_single_fits(const LayerShape &s)
 {
-    if (!outputs_by_four_ok(s) || !slab_batch_ok(s)) return false;
-    return !slab_wide_ok(s) && !slab_narrow_ok(s) && (size_t)s.nodes() * kNarrowRowBytes <= 160 * 1024 - 512;
+    return outputs_by_four_ok(s) && !slab_wide_fits(s) && !slab_narrow_fits(s) &&
+           (size_t)s.nodes() * kNarrowRowBytes <= 160 * 1024 - 512;
 }
 
 bool slab_forward_shape_ok(const LayerShape &s)
 {
-    return slab_wide_ok(s) || slab_narrow_ok(s) || slab_narrow_single_ok(s);
+    return slab_batch_ok(s, true) && (slab_wide_fits(s) || slab_narrow_fits(s) || slab_narrow_single_fits(s));
 }
-bool slab_tile_is_wide(const LayerShape &s) { return slab_wide_ok(s); }
+bool slab_tile_is_wide(const LayerShape &s) { return slab_wide_fits(s); }
 
 // Samples per forward workgroup: 1024 with 64-output tiles, 4096 with 16-output tiles.
 int slab_forward_split(const LayerShape &s)
 {
     if (!slab_forward_shape_ok(s)) return 1;
-    const bool wide = slab_wide_ok(s);
+    const bool wide = slab_wide_fits(s);
     const int64_t tile_b = wide ? 1024 : 4096;
     const int64_t n_jt = wide ? s.out_tiles() : (s.n_out + 15) / 16;
     return pair_split_count((int)(((s.batch + tile_b - 1) / tile_b) * n_jt), s.pairs());
@@ -1155,7 +1155,7 @@ static void launch_forward_slab_narrow(const LayerShape &s, const void *coef, fl
     constexpr int kTileB = WAVES * SETS * 64;
     typedef void (*Kernel)(SlabArgs);
     // a float32 table needs no staging registers: 16 waves of 256 samples instead of 8 of 512
-    const bool single = slab_narrow_single_ok(s);
+    const bool single = slab_narrow_single_fits(s);
     const Kernel kernels[6] = {forward_slab_narrow_kernel<float, 2 * WAVES, SETS / 2>,
                                forward_slab_narrow_kernel<_Float16, WAVES, SETS>,
                                forward_slab_narrow_kernel<bf16_t, WAVES, SETS>,
@@ -1197,7 +1197,7 @@ static void launch_forward_slab_narrow(const LayerShape &s, const void *coef, fl
 void launch_forward_slab(const LayerShape &s, const void *coef, float *y, const void *records, float *partials,
                          hipStream_t stream)
 {
-    if (!slab_wide_ok(s)) {
+    if (!slab_wide_fits(s)) {
         launch_forward_slab_narrow(s, coef, y, records, partials, stream);
         return;
     }
@@ -1251,7 +1251,10 @@ void launch_forward_slab(const LayerShape &s, const void *coef, float *y, const 
 
 namespace lmkan {
 
-bool slab_backward_input_shape_ok(const LayerShape &s) { return slab_wide_ok(s) || slab_narrow_ok(s); }
+bool slab_backward_input_shape_ok(const LayerShape &s)
+{
+    return slab_batch_ok(s, false) && (slab_wide_fits(s) || slab_narrow_fits(s));
+}
 
 bool slab_backward_input_applicable(const LayerShape &s, const void *coef, const float *gy, const float *gx)
 {
@@ -1358,7 +1361,7 @@ void launch_backward_input_slab(const LayerShape &s, const GridTab &tab, const v
                                 int64_t gy_tile_stride, int64_t gy_row_stride, float *gx, const void *records,
                                 void *scratch, hipStream_t stream, const ConvGeom *conv)
 {
-    if (slab_wide_ok(s) && slab_f16_native_ok(s)) {
+    if (slab_wide_fits(s) && slab_f16_native_ok(s)) {
         launch_fill_zero(static_cast<float *>(scratch), (size_t)scratch_row_stride(s.batch, kScratchOct) * s.n_in,
                          stream);
         launch_backward_input_slab_f16(s, tab, coef, gy, gy_tile_stride, gy_row_stride, static_cast<float *>(scratch),
@@ -1369,7 +1372,7 @@ void launch_backward_input_slab(const LayerShape &s, const GridTab &tab, const v
     constexpr int WAVES = 8, SETS = 2;
     constexpr int kTileB = WAVES * SETS * 64;
     typedef void (*Kernel)(GradInArgs);
-    const bool narrow = !slab_wide_ok(s);
+    const bool narrow = !slab_wide_fits(s);
     constexpr int kNarrowSets = 8;
     constexpr int kWavesF32 = 16;  // float32 tables need no staging registers: 16 waves of 64 samples
     const Kernel kernels[9] = {backward_input_slab_kernel<float, kWavesF32, 16 / kWavesF32, 1, 0>,
