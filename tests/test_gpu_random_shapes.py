@@ -3,7 +3,13 @@ storage type, a table layout, which gradients are asked for and whether the coef
 is added to an existing one, so that combinations nobody listed by hand meet the dispatch
 (which kernel, which workspace layout) and the oracle.  Sizes are small enough for the oracle;
 a quarter of the draws are wide enough (pairs x outputs >= 8192) for the slab kernels to take
-short batches."""
+short batches, a quarter are middling layers (16 to 158 inputs, 1 to 260 outputs) on either side
+of the batch and work thresholds.
+
+LMKAN_TEST_DRAWS and LMKAN_TEST_SEED in the environment replace the number of draws and the seed
+(the committed run uses 144 draws of seed 20240917)."""
+import os
+
 import numpy as np
 import pytest
 import torch
@@ -26,6 +32,10 @@ def _draws(n, seed):
             n_in = 2 * int(rng.randint(33, 70))
             n_out = int(rng.randint(8192 // (n_in // 2) + 1, 8192 // (n_in // 2) + 40))
             B = int(rng.choice([1, 2, 17, 64, 200, 300]))
+        elif i % 4 == 2:     # middling layers around the batch and work thresholds of the dispatch
+            n_in = 2 * int(rng.randint(8, 80))
+            n_out = int(rng.choice([1, 2, 5, 8, 16, 24, 64, 72, 128, 136, 256, 260]))
+            B = int(rng.choice([1, 30, 255, 256, 300, 1024, 1025, 2300]))
         else:
             n_in = 2 * int(rng.randint(1, 12))
             n_out = int(rng.choice([1, 2, 3, 4, 7, 8, 9, 10, 12, 16, 17, 60, 64, 65, 100, 130, 193]))
@@ -40,7 +50,7 @@ def _draws(n, seed):
     return out
 
 
-DRAWS = _draws(144, 20240917)
+DRAWS = _draws(int(os.environ.get("LMKAN_TEST_DRAWS", "144")), int(os.environ.get("LMKAN_TEST_SEED", "20240917")))
 
 
 @pytest.fixture(scope="module")
