@@ -3,6 +3,8 @@ every window) against the oracle, which gathers the windows into rows and calls 
 connected functions.  The library never writes the rows out, so these tests are what checks
 its window map: forward, the input gradient (summed over overlapping windows, zero outside
 every window) and the coefficient gradient, on every kernel family the dispatch can pick."""
+import os
+
 import numpy as np
 import pytest
 import torch
@@ -169,3 +171,58 @@ def test_conv2d_accumulates_coefficient_gradient(dev, oracle):
     torch.cuda.synchronize()
     want = base.cpu().numpy().astype(np.float64) + oracle.conv2d_backward_coef(x.cpu().numpy(), gy.cpu().numpy(), G, kh, kw, stride)
     assert np.abs(gP.cpu().numpy() - want).max() <= TOL_F32 * np.abs(want).max()
+
+
+def _random_geometries(n, seed):
+    """Seeded draws of image, window, stride, output count, grid, storage and layout.  A third of
+    the draws have enough windows (256 and more) for the slab kernels."""
+    rng = np.random.RandomState(seed)
+    out = []
+    while len(out) < n:
+        kh, kw = int(rng.randint(1, 5)), int(rng.randint(1, 5))
+        C = int(rng.randint(1, 9))
+        if (kh * kw * C) % 2:
+            continue
+        stride = int(rng.randint(1, 4))
+        H, W = kh + int(rng.randint(0, 22)), kw + int(rng.randint(0, 22))
+        N = int(rng.randint(1, 7)) if len(out) % 3 else int(rng.randint(6, 12))
+        n_out = int(rng.choice([1, 3, 4, 8, 10, 16, 20, 33, 64, 72]))
+        G = int(rng.choice([4, 8, 12, 16, 20, 24, 40]))
+        storage = str(rng.choice(["f32", "f32", "f16", "bf16"]))
+        layout = int(rng.choice([pkg.LMKAN_LAYOUT_PAPER, pkg.LMKAN_LAYOUT_PACKED]))
+        out.append((N, H, W, C, kh, kw, stride, n_out, G, storage, layout))
+    return out
+
+
+GEOMETRIES = _random_geometries(int(os.environ.get("LMKAN_TEST_DRAWS", "48")),
+                                int(os.environ.get("LMKAN_TEST_SEED", "20250907")))
+
+
+@pytest.mark.parametrize("geo", GEOMETRIES, ids=lambda g: "N%d_%dx%dx%d_w%dx%ds%d_to%d_G%d_%s_%s" % (
+    g[:10] + ("packed" if g[10] == pkg.LMKAN_LAYOUT_PACKED else "paper",)))
+def test_conv2d_random_geometry(dev, oracle, geo):
+    N, H, W, C, kh, kw, stride, n_out, G, storage, layout = geo
+    conv, x, P, gy = _inputs(geo[:9], 25, dev)
+    n_in = kh * kw * C
+    desc = pkg.LayerDesc(n_in, n_out, G, coef_dtype=DT_CODE[storage], coef_layout=layout)
+    Ps = wl.store(P, storage).contiguous()
+    Pd = pkg.lmkan_pack(pkg.LayerDesc(n_in, n_out, G, coef_dtype=DT_CODE[storage]), Ps) \
+        if layout == pkg.LMKAN_LAYOUT_PACKED else Ps
+    xh, gyh = x.cpu().numpy(), gy.cpu().numpy()
+    code = ORACLE_DTYPE[storage]
+
+    y = pkg.lmkan_conv2d_forward(desc, conv, x, Pd)
+    gx, gP = pkg.lmkan_conv2d_backward(desc, conv, x, Pd, gy)
+    torch.cuda.synchronize()
+    want = oracle.conv2d_forward(xh, bits(Ps), G, kh, kw, stride, dtype=code)
+    assert tuple(y.shape) == want.shape
+    assert np.abs(y.cpu().numpy() - want).max() <= TOL_F32 * np.abs(want).max()
+    want_gx = oracle.conv2d_backward_input(xh, bits(Ps), gyh, G, kh, kw, stride, dtype=code)
+    assert tuple(gx.shape) == (N, H, W, C)
+    assert np.abs(gx.cpu().numpy() - want_gx).max() <= TOL_F32 * np.abs(want_gx).max()
+    assert np.all(gx.cpu().numpy()[want_gx == 0.0] == 0.0)
+    want_gP = oracle.conv2d_backward_coef(xh, gyh, G, kh, kw, stride)
+    got_gP = gP.cpu().numpy()
+    for k in range(want_gP.shape[2]):
+        assert pair_slice_rel_err(got_gP[:, :, k, :], want_gP[:, :, k, :]) <= TOL_F32
+    assert np.all(got_gP[want_gP == 0.0] == 0.0)
