@@ -371,6 +371,32 @@ def test_results_do_not_depend_on_the_stream(dev, oracle):
     del junk
 
 
+@pytest.mark.parametrize("G", list(range(3, 65)))
+def test_layer_every_grid(dev, oracle, G):
+    """Forward and both gradients at every grid size the library takes, on a batch long enough for
+    the tiled kernels: the tile (64 or 16 outputs, one or two slabs in LDS), the fused and the
+    generic kernels all change over with G.  Storage, layout and output count rotate with G."""
+    storage = ["f32", "f16", "bf16"][G % 3]
+    layout = [pkg.LMKAN_LAYOUT_PACKED, pkg.LMKAN_LAYOUT_PAPER][(G // 3) % 2]
+    B, n_in = 330, 6
+    n_out = [20, 64, 18, 72][G % 4] if layout == pkg.LMKAN_LAYOUT_PACKED else [20, 64, 16, 72][G % 4]
+    x, P, gy = _inputs(B, n_in, n_out, G, 41 + G, dev, heavy=True)
+    desc = _desc(n_in, n_out, G, storage, layout)
+    Ps, Pdev = _stored(P, storage, desc, layout)
+    y = pkg.lmkan_forward(desc, x, Pdev)
+    gx, gP = pkg.lmkan_backward(desc, x, Pdev, gy)
+    torch.cuda.synchronize()
+    xh, gyh = x.cpu().numpy(), gy.cpu().numpy()
+    code = ORACLE_DTYPE[storage]
+    assert rowwise_rel_err(y.cpu().numpy(), oracle.forward(xh, bits(Ps), G, dtype=code)) <= TOL_F32
+    assert rowwise_rel_err(gx.cpu().numpy(), oracle.backward_input(xh, bits(Ps), gyh, G, dtype=code)) <= TOL_F32
+    gPh = gP.cpu().numpy()
+    for k in range(n_in // 2):
+        want = oracle.backward_coef_pair(xh, gyh, G, k)
+        assert pair_slice_rel_err(gPh[:, :, k, :], want) <= TOL_F32
+        assert np.all(gPh[:, :, k, :][want == 0.0] == 0.0)
+
+
 # ---- Hessian regulariser (Sec. 3.5, App. C) ---------------------------------------------------
 @pytest.mark.parametrize("layout", [pkg.LMKAN_LAYOUT_PAPER, pkg.LMKAN_LAYOUT_PACKED])
 @pytest.mark.parametrize("storage", ["f32", "f16", "bf16"])
@@ -402,6 +428,26 @@ def test_hessian_reg_matches_oracle(dev, oracle, shape, storage, layout):
     assert np.abs(acc.cpu().numpy() - (0.5 * want_g + 0.25)).max() <= 2e-5 * max(1.0, np.abs(want_g).max())
     assert float(v2.cpu()[0]) == pytest.approx(want_v, rel=1e-5)
     assert float(only_v.cpu()[0]) == pytest.approx(want_v, rel=1e-5)
+
+
+@pytest.mark.parametrize("G", list(range(3, 65)))
+def test_hessian_reg_every_grid(dev, oracle, G):
+    """Every grid size the library takes: the kernel's bands, its three-row steps and the rows left
+    over after them all change with G.  Storage, layout and output count rotate with G."""
+    storage = ["f32", "f16", "bf16"][G % 3]
+    layout = [pkg.LMKAN_LAYOUT_PAPER, pkg.LMKAN_LAYOUT_PACKED][(G // 3) % 2]
+    n_in, n_out = 4, [5, 64, 66, 1][G % 4]
+    g = torch.Generator(device="cpu").manual_seed(72 + G)
+    P = (torch.randn((G + 1, G + 1, n_in // 2, n_out), generator=g) * 0.1).to(dev)
+    desc = _desc(n_in, n_out, G, storage, layout)
+    Ps, Pdev = _stored(P, storage, desc, layout)
+    value, grad = pkg.lmkan_hessian_reg(desc, Pdev, scale=2.0)
+    torch.cuda.synchronize()
+    want_v, want_g = oracle.hessian_reg(bits(Ps), G, dtype=ORACLE_DTYPE[storage])
+    assert float(value.cpu()[0]) == pytest.approx(want_v, rel=1e-5)
+    got = grad.cpu().numpy()
+    for k in range(n_in // 2):
+        assert np.abs(got[:, :, k, :] - 2.0 * want_g[:, :, k, :]).max() <= TOL_F32 * np.abs(2.0 * want_g[:, :, k, :]).max()
 
 
 def test_hessian_reg_is_zero_on_linear_tables(dev, oracle):
