@@ -57,6 +57,10 @@ def kernel_names(w, n_out, B, storage, packed):
     both = None
     if n_out == 1 or (n_out <= 8 and not (ok and w.grid <= 34)):
         fwd, gx, gp = "forward_small_kernel", "backward_input_small_kernel", "backward_coef_small_kernel"
+        # one output on rows: the tables of 64 pairs (or of all) fit LDS, the kernel locates by itself
+        fit = ((160 * 1024 - 1024) // 4) // ((w.grid + 1) ** 2 | 1)
+        if n_out == 1 and not getattr(w, "kh", 0) and (fit >= w.n_in // 2 or fit >= 64):
+            fwd = "forward_head_kernel"
     elif ok and w.grid <= 16:
         f16 = storage == "f16" and (packed or n_out % 8 == 0)
         fwd = "forward_slab_f16_kernel" if f16 else "forward_slab_kernel"
@@ -154,13 +158,17 @@ class Bench:
             P_stored = wl.store(P_master, storage).contiguous()
             del P_master
         paper = pkg.LayerDesc(w.n_in, n_out, w.grid, coef_dtype=dt_code)
+        # a one-output table stays in the layout of Alg. 1 (contiguous over the pairs there; packing
+        # would pad it to 64 columns)
+        packed = n_out != 1
         t0 = time.perf_counter()
-        P_packed = pkg.lmkan_pack(paper, P_stored)
+        P_packed = pkg.lmkan_pack(paper, P_stored) if packed else P_stored
         torch.cuda.synchronize()
-        pack_ms = (time.perf_counter() - t0) * 1e3
+        pack_ms = (time.perf_counter() - t0) * 1e3 if packed else 0.0
         if not keep:
             del P_stored
-        desc = pkg.LayerDesc(w.n_in, n_out, w.grid, coef_dtype=dt_code, coef_layout=pkg.LMKAN_LAYOUT_PACKED)
+        layout = pkg.LMKAN_LAYOUT_PACKED if packed else pkg.LMKAN_LAYOUT_PAPER
+        desc = pkg.LayerDesc(w.n_in, n_out, w.grid, coef_dtype=dt_code, coef_layout=layout)
 
         y = torch.empty((B, n_out), dtype=torch.float32, device=dev)
         gx = torch.empty_like(x)
@@ -185,7 +193,7 @@ class Bench:
         # the backward call of a step runs on the same x and the same workspace as its forward call:
         # it is told that the records are there (LMKAN_FLAG_WORKSPACE_HAS_RECORDS) and skips the
         # preamble pass; the calls timed on their own below do everything themselves
-        d_reuse = pkg.LayerDesc(w.n_in, n_out, w.grid, coef_dtype=dt_code, coef_layout=pkg.LMKAN_LAYOUT_PACKED,
+        d_reuse = pkg.LayerDesc(w.n_in, n_out, w.grid, coef_dtype=dt_code, coef_layout=layout,
                                 flags=pkg.LMKAN_FLAG_WORKSPACE_HAS_RECORDS).c()
         has_records = pkg.lmkan_workspace_bytes(desc, B, False) > 0
 
@@ -233,7 +241,7 @@ class Bench:
 
         fma = 4.0 * B * K * n_out       # Alg. 1: four multiply-adds per (sample, pair, output); each of the
         s_bytes = 4 if storage == "f32" else 2      # three passes (forward, grad_x, grad_coef) does that many
-        fwd_name, gx_name, gp_name, both_name = kernel_names(w, n_out, B, storage, True)
+        fwd_name, gx_name, gp_name, both_name = kernel_names(w, n_out, B, storage, packed)
         # the kernels that run in a step, each timed alone; a kernel that forms both gradients does
         # twice the multiply-adds
         kernels = {fwd_name: (self.kernel_ms(forward, reps), fma)}
@@ -298,8 +306,10 @@ class Bench:
                                     f"images, a sample = one window; " if conv else "") +
                                    f"{w.name}: n_in={w.n_in} n_out={n_out} G={w.grid} batch={B} "
                                    f"coef_storage={storage} x~{w.x_kind} coef~N(0,{w.coef_std})",
-                       "pass": "forward+backward(grad_x,grad_coef); the backward call reuses the preamble records "
-                               "its forward call left in the workspace", "coef_layout": "packed",
+                       "pass": "forward+backward(grad_x,grad_coef); " +
+                               ("the backward call reuses the preamble records its forward call left in the workspace"
+                                if has_records else "the forward call locates its inputs itself and leaves no records"),
+                       "coef_layout": "packed" if packed else "alg1",
                        "launch": "hip graph replay" if graph else "stream launches",
                        "pack_ms_once": round(pack_ms, 3)},
             "forward": {"ms": round(fwd_ms, 4), "samples_per_s": round(B / (fwd_ms * 1e-3), 1),
@@ -351,8 +361,10 @@ class Bench:
                 scale = (torch.rand((w.n_out,), generator=g) * 0.4 + 0.8) / (w.coef_std * (w.n_in / 2) ** 0.5)
                 shift = torch.randn((w.n_out,), generator=g) * 0.2
                 pkg.lmkan_fold(paper, P, 1.0, None, None, scale.to(dev), shift.to(dev))
-            tables.append(pkg.lmkan_pack(paper, P))
-            d = pkg.LayerDesc(w.n_in, w.n_out, w.grid, coef_layout=pkg.LMKAN_LAYOUT_PACKED)
+            # (the one-output table of the last layer stays in the layout of Alg. 1)
+            tables.append(pkg.lmkan_pack(paper, P) if w.n_out != 1 else P)
+            d = pkg.LayerDesc(w.n_in, w.n_out, w.grid,
+                              coef_layout=pkg.LMKAN_LAYOUT_PACKED if w.n_out != 1 else pkg.LMKAN_LAYOUT_PAPER)
             descs.append(d)
             outs.append(torch.empty((B, w.n_out), dtype=torch.float32, device=dev))
             need = max(need, pkg.lmkan_workspace_bytes(d, B, False))

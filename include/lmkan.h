@@ -90,7 +90,8 @@ typedef enum {
  * lmkan_backward or lmkan_conv2d_* call wrote for the same desc, batch (or geometry) and the same
  * contents of x: the call then skips the pass that computes them (a training step runs forward
  * and backward on the same x).  It holds only if that earlier call was given a workspace of at
- * least lmkan_workspace_bytes() for its pass, that size was not zero, the call returned LMKAN_OK,
+ * least lmkan_workspace_bytes() for its pass, that size was not zero (a call whose size is zero
+ * writes no records), the call returned LMKAN_OK,
  * and nothing has written to the first lmkan_workspace_bytes(desc, batch, 0) bytes since
  * (the forward pass's partial outputs lie behind the records and do not matter).  The library
  * cannot check the promise: with stale or foreign contents the records are garbage used as
@@ -158,7 +159,9 @@ lmkan_status lmkan_pack(const lmkan_desc *desc, const void *coef_paper_dev, void
  *             (summed in a fixed order: the forward result does not vary between
  *             runs, except where the kernels for very few outputs run (one output,
  *             or up to eight where no slab kernel applies): their splits add
- *             atomically).
+ *             atomically).  Zero for a layer with one output whose tables fit on
+ *             chip 64 pairs at a time (G <= 24, or fewer pairs): its forward kernel
+ *             locates the inputs itself and writes no records.
  *   pass = 1  lmkan_backward with both gradients; 2: grad_x only; 3: grad_coef only.
  *             The same records; their copy sorted by cell (16 bytes per (sample,
  *             pair) plus per-pair tables) when a kernel that walks it can serve the

@@ -192,6 +192,7 @@ size_t lmkan_workspace_bytes(const lmkan_desc *desc, int64_t batch, int32_t pass
     const LayerShape s = shape_of(desc, batch);
     // forward: preamble records, then the partial outputs of a forward split over the pairs
     if (pass == 0) {
+        if (head_forward_shape_ok(s)) return 0;  // locates its inputs itself
         if (small_out_shape_ok(s)) return records_bytes(s);
         return slab_forward_shape_ok(s) ? align256(records_bytes(s)) + slab_forward_partial_bytes(s) : 0;
     }
@@ -276,7 +277,13 @@ lmkan_status forward_impl(const lmkan_desc *desc, int64_t batch, const float *x_
     // alignment of this call's pointers sends it to the generic kernel: a later call may rely on them
     if (need > 0 && !(desc->flags & LMKAN_FLAG_WORKSPACE_HAS_RECORDS))
         launch_preamble_records(s, tab, x_dev, workspace_dev, hs, conv);
-    if (small_out_shape_ok(s)) {
+    if (head_forward_shape_ok(s)) {
+        // one output: no records (need == 0); windows and 4-byte aligned rows go the generic way
+        if (!conv)
+            launch_forward_head(s, tab, x_dev, coef_dev, y_dev, hs);
+        else
+            launch_forward_generic(s, tab, x_dev, coef_dev, y_dev, hs, conv);
+    } else if (small_out_shape_ok(s)) {
         launch_forward_small(s, coef_dev, y_dev, workspace_dev, hs);
     } else if (slab_forward_applicable(s, coef_dev, y_dev)) {
         float *partials = slab_forward_partial_bytes(s) > 0

@@ -104,6 +104,12 @@ constexpr int kSmallMaxOut = 8;
 bool small_out_shape_ok(const LayerShape &s);
 bool small_coef_ok(const LayerShape &s);
 void launch_forward_small(const LayerShape &s, const void *coef, float *y, const void *records, hipStream_t stream);
+// Forward pass of a layer with one output on rows x[batch][n_in] (8-byte aligned): the tables sit
+// in LDS and the kernel locates the inputs itself, so the call needs no records and no workspace.
+// Applies when at least 64 pairs' tables (or all of them) fit LDS at once.
+bool head_forward_shape_ok(const LayerShape &s);
+void launch_forward_head(const LayerShape &s, const GridTab &tab, const float *x, const void *coef, float *y,
+                         hipStream_t stream);
 void launch_backward_input_small(const LayerShape &s, const GridTab &tab, const void *coef, const float *gy,
                                  float *gx_scratch, const void *records, hipStream_t stream);
 void launch_backward_coef_small(const LayerShape &s, const void *records, const float *gy, float *gcoef,

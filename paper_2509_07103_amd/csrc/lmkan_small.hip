@@ -166,6 +166,140 @@ __global__ __launch_bounds__(kThreads) void backward_coef_small_kernel(SmallArgs
     }
 }
 
+// ---------------------------------------------------------------------------
+// One output (a regression head), forward: y[n] = sum_k f_k(x[n][2k], x[n][2k+1]) (Eq. 2 with a
+// single q).  The tables of a chunk of pairs sit in LDS as float32, [pair][node] with an odd pitch.
+// A group of `lps` lanes (a power of two, up to the whole wave) takes a sample with a lane per
+// pair, so the two inputs of its pairs are one contiguous read of the sample's row, and locates
+// them itself (Alg. 1 "Preamble"): no records are written or read.  The products of a sample meet
+// in a sum over its lanes.  A wave has kHeadSamples such steps in flight and asks for the inputs
+// of the next ones before it works on those it has.
+// ---------------------------------------------------------------------------
+struct HeadArgs {
+    const void *P;
+    CoefMap map;
+    const float *x;
+    float *y;
+    GridTab tab;
+    int64_t B;
+    int n_in;
+    int K;
+    int W;
+    int nodes;
+    int pitch;             // LDS floats per pair, odd
+    int pairs_per_chunk;   // a multiple of 64 unless one chunk holds every pair
+    int lps;               // lanes per sample
+    int samples_per_block;
+    int atomic_out;        // several chunks: add into the zero-filled y
+};
+
+constexpr int kHeadSamples = 4;  // steps a wave has in flight
+constexpr int kHeadFill = 8;     // table elements a thread has in flight while LDS is filled
+
+template <typename CT>
+__global__ __launch_bounds__(1024) void forward_head_kernel(HeadArgs a)
+{
+    extern __shared__ __align__(16) float head_smem[];
+    const int k0 = blockIdx.y * a.pairs_per_chunk;
+    const int kc = min(a.K, k0 + a.pairs_per_chunk) - k0;
+    float *s_tab = head_smem;
+    float *s_node = head_smem + (int64_t)a.pairs_per_chunk * a.pitch;
+    float *s_invh = s_node + LMKAN_MAX_GRID + 1;
+    for (int i = threadIdx.x; i <= a.tab.G; i += blockDim.x) s_node[i] = a.tab.node[i];
+    for (int i = threadIdx.x; i < a.tab.G; i += blockDim.x) s_invh[i] = a.tab.inv_h[i];
+    // pairs along the threads: contiguous in the layout of Alg. 1 with one output.  Every load is
+    // unconditional (the index clamped), so that kHeadFill of them are in flight per thread.
+    const CT *P = static_cast<const CT *>(a.P);
+    const int total = kc * a.nodes;
+    // element i = node * kc + kl; a thread's elements lie blockDim.x apart: (node, kl) advance by
+    // (step_node, step_kl) with a carry, without a division per element
+    const int step_node = (int)blockDim.x / kc, step_kl = (int)blockDim.x - step_node * kc;
+    int node = (int)threadIdx.x / kc, kl = (int)threadIdx.x - node * kc;
+    for (int base = threadIdx.x; base < total; base += blockDim.x * kHeadFill) {
+        CT raw[kHeadFill];
+        int at[kHeadFill];
+#pragma unroll
+        for (int u = 0; u < kHeadFill; ++u) {
+            const int node_rd = min(node, a.nodes - 1);   // past the end: the same pair of the last node again
+            at[u] = kl * a.pitch + node_rd;
+            raw[u] = P[(int64_t)node_rd * a.map.s_node + (int64_t)(k0 + kl) * a.map.s_pair];
+            node += step_node;
+            kl += step_kl;
+            if (kl >= kc) {
+                kl -= kc;
+                ++node;
+            }
+        }
+#pragma unroll
+        for (int u = 0; u < kHeadFill; ++u) s_tab[at[u]] = widen(raw[u]);  // (a clamped one rewrites an element of the last node)
+    }
+    __syncthreads();
+
+    const int lane = threadIdx.x & 63;
+    const int wave = threadIdx.x >> 6, waves = blockDim.x >> 6;
+    const int per_step = 64 / a.lps;            // samples of a wave step
+    const int sub = lane / a.lps, pl = lane - sub * a.lps;
+    const int per_round = per_step * kHeadSamples;
+    const int64_t n_begin = (int64_t)blockIdx.x * a.samples_per_block;
+    const int64_t n_end = min(a.B, n_begin + a.samples_per_block);
+
+    // inputs of (round starting at n, pairs kk ...): lanes past the chunk and samples past the block
+    // repeat the last one, every load is in bounds and unconditional, what they add is dropped
+    auto request = [&](int64_t n, int kk, float2 (&xv)[kHeadSamples]) {
+        const int kl = min(kk + pl, kc - 1);
+#pragma unroll
+        for (int s = 0; s < kHeadSamples; ++s) {
+            const int64_t nn = min(n + s * per_step + sub, n_end - 1);
+            xv[s] = *reinterpret_cast<const float2 *>(a.x + nn * a.n_in + 2 * (k0 + kl));
+        }
+    };
+
+    int64_t n = n_begin + (int64_t)wave * per_round;
+    if (n >= n_end) return;
+    float2 xv[kHeadSamples], xv_next[kHeadSamples];
+    request(n, 0, xv_next);
+    while (n < n_end) {
+        float acc[kHeadSamples];
+#pragma unroll
+        for (int s = 0; s < kHeadSamples; ++s) acc[s] = 0.0f;
+        for (int kk = 0; kk < kc; kk += a.lps) {
+#pragma unroll
+            for (int s = 0; s < kHeadSamples; ++s) xv[s] = xv_next[s];
+            // the step after this one: more pairs of these samples, else the wave's next round
+            // (past the end it repeats the block's last sample)
+            const bool more = kk + a.lps < kc;
+            request(more ? n : n + (int64_t)waves * per_round, more ? kk + a.lps : 0, xv_next);
+            const bool on = kk + pl < kc;
+            const float *t_pair = s_tab + min(kk + pl, kc - 1) * a.pitch;
+#pragma unroll
+            for (int s = 0; s < kHeadSamples; ++s) {
+                const Preamble pr = preamble(s_node, s_invh, a.tab.G, xv[s].x, xv[s].y);
+                const float u = pr.a_hi, v = pr.b_hi;
+                const float a_lo = 1.0f - u, b_lo = 1.0f - v;
+                const float *t = t_pair + pr.node;
+                float val = (a_lo * b_lo) * t[0];
+                val = fmaf(u * b_lo, t[a.W], val);
+                val = fmaf(a_lo * v, t[1], val);
+                val = fmaf(u * v, t[a.W + 1], val);
+                acc[s] += on ? val : 0.0f;
+            }
+        }
+#pragma unroll
+        for (int s = 0; s < kHeadSamples; ++s) {
+            float total_s = acc[s];
+            for (int m = a.lps >> 1; m >= 1; m >>= 1) total_s += __shfl_xor(total_s, m, 64);
+            const int64_t mine = n + s * per_step + sub;
+            if (pl == 0 && mine < n_end) {
+                if (a.atomic_out)
+                    unsafeAtomicAdd(a.y + mine, total_s);
+                else
+                    a.y[mine] = total_s;
+            }
+        }
+        n += (int64_t)waves * per_round;
+    }
+}
+
 SmallArgs small_args(const LayerShape &s, const void *coef, const void *records)
 {
     const size_t n = (size_t)s.pairs() * (size_t)s.batch;
@@ -196,6 +330,64 @@ int pair_split(const LayerShape &s)
 bool small_out_shape_ok(const LayerShape &s)
 {
     return s.n_out <= kSmallMax && (s.n_out == 1 || !slab_backward_input_shape_ok(s));
+}
+
+// LDS floats per pair of the one-output forward kernel, and the pairs one workgroup can hold
+static int head_pitch(const LayerShape &s) { return s.nodes() | 1; }
+static int head_chunk(const LayerShape &s)
+{
+    const int budget = (160 * 1024 - 1024) / (int)sizeof(float);  // 1 KB for the grid
+    int kc = budget / head_pitch(s);
+    if (kc >= s.pairs()) return s.pairs();
+    return kc & ~63;
+}
+
+// One output, rows (not windows), and at least a wave of pairs fits LDS at a time (G <= 24, or few pairs)
+bool head_forward_shape_ok(const LayerShape &s)
+{
+    return s.n_out == 1 && head_chunk(s) > 0;
+}
+
+void launch_forward_head(const LayerShape &s, const GridTab &tab, const float *x, const void *coef, float *y,
+                         hipStream_t stream)
+{
+    HeadArgs a = {};
+    a.P = coef;
+    a.map = coef_map(s);
+    a.x = x;
+    a.y = y;
+    a.tab = tab;
+    a.B = s.batch;
+    a.n_in = s.n_in;
+    a.K = s.pairs();
+    a.W = s.G + 1;
+    a.nodes = s.nodes();
+    a.pitch = head_pitch(s);
+    a.pairs_per_chunk = head_chunk(s);
+    const int chunks = (a.K + a.pairs_per_chunk - 1) / a.pairs_per_chunk;
+    a.atomic_out = chunks > 1;
+    // a sample takes as many lanes as the chunk has pairs, rounded up to a power of two
+    a.lps = 1;
+    while (a.lps < 64 && a.lps < a.pairs_per_chunk) a.lps *= 2;
+    const size_t lds = ((size_t)a.pairs_per_chunk * a.pitch + 2 * LMKAN_MAX_GRID + 2) * sizeof(float);
+    // every workgroup fills its LDS with the chunk's tables first: a workgroup should have at least
+    // two rounds of its 16 waves to spread that over, and 256 workgroups fill the chip
+    const int threads = 1024;
+    const int64_t round = (int64_t)(threads / 64) * kHeadSamples * (64 / a.lps);
+    int64_t per_block = 2 * round;
+    if ((s.batch + per_block - 1) / per_block * chunks > 256) {
+        const int64_t blocks = 256 / chunks > 0 ? 256 / chunks : 1;
+        per_block = ((s.batch + blocks - 1) / blocks + round - 1) / round * round;
+    }
+    a.samples_per_block = (int)per_block;
+    const dim3 grid((unsigned)((s.batch + per_block - 1) / per_block), (unsigned)chunks);
+    typedef void (*Kernel)(HeadArgs);
+    const Kernel kernels[3] = {forward_head_kernel<float>, forward_head_kernel<_Float16>, forward_head_kernel<bf16_t>};
+    const Kernel kernel = kernels[s.dtype];
+    if (lds > 64 * 1024) allow_large_lds(reinterpret_cast<const void *>(kernel), 160 * 1024);
+    if (a.atomic_out) launch_fill_zero(y, (size_t)s.batch, stream);
+    KernelTiming timing(stream, kTimeForward);
+    kernel<<<grid, threads, lds, stream>>>(a);
 }
 
 void launch_forward_small(const LayerShape &s, const void *coef, float *y, const void *records, hipStream_t stream)

@@ -28,6 +28,18 @@ def rowwise_rel_err(got: np.ndarray, want: np.ndarray) -> float:
     return float((num / den).max()) if got.size else 0.0
 
 
+def output_rel_err(got: np.ndarray, want: np.ndarray) -> float:
+    """Error of a [batch][n_out] result: row by row where a row has enough entries (eight) for its
+    largest one to set a scale; over the whole tensor for layers with fewer outputs, where a row is
+    one or a few sums that may cancel to nothing."""
+    if want.shape[-1] >= 8:
+        return rowwise_rel_err(got, want)
+    err = np.abs(got.astype(np.float64) - want)
+    if not np.isfinite(err).all():
+        return float("inf")
+    return float(err.max() / max(np.abs(want).max(), 1e-30)) if got.size else 0.0
+
+
 def pair_slice_rel_err(got: np.ndarray, want: np.ndarray) -> float:
     """grad_coef slices [G+1][G+1][n_out] of one pair: max-norm relative error."""
     den = max(np.abs(want).max(), 1e-30)

@@ -8,7 +8,7 @@ import torch
 
 import paper_2509_07103_amd as pkg
 from paper_2509_07103_amd import workloads as wl
-from parity_util import (ORACLE_DTYPE, TOL_F32, TOL_HALF, bits, pair_slice_rel_err,
+from parity_util import (ORACLE_DTYPE, TOL_F32, TOL_HALF, bits, output_rel_err, pair_slice_rel_err,
                          rowwise_rel_err)
 
 pytestmark = pytest.mark.gpu
@@ -109,6 +109,18 @@ SHAPES = [
     (37, 130, 140, 20),
     (5, 140, 132, 40),
     (100, 1100, 10, 12),
+    # one output: the forward kernel that keeps the tables in LDS and locates by itself (all pairs
+    # in one chunk; chunks of 128 and of 64 pairs with a ragged last one; the finest grid it takes
+    # and the first one beyond, with more and fewer pairs than fit; one pair on the finest grid; a
+    # batch long enough for workgroups to take more than eight rounds)
+    (5000, 256, 1, 16),
+    (700, 600, 1, 16),
+    (300, 200, 1, 23),
+    (300, 200, 1, 24),
+    (300, 200, 1, 25),
+    (300, 100, 1, 25),
+    (3, 2, 1, 64),
+    (300000, 4, 1, 4),
 ]
 
 
@@ -144,10 +156,10 @@ def test_forward_matches_oracle(dev, oracle, shape, storage, layout):
     torch.cuda.synchronize()
     xh = x.cpu().numpy()
     want = oracle.forward(xh, bits(Ps), G, dtype=ORACLE_DTYPE[storage])
-    assert rowwise_rel_err(y.cpu().numpy(), want) <= TOL_F32
+    assert output_rel_err(y.cpu().numpy(), want) <= TOL_F32
     if storage != "f32":
         master = oracle.forward(xh, P.cpu().numpy(), G)
-        assert rowwise_rel_err(y.cpu().numpy(), master) <= TOL_HALF
+        assert output_rel_err(y.cpu().numpy(), master) <= TOL_HALF
 
 
 @pytest.mark.parametrize("layout", [pkg.LMKAN_LAYOUT_PAPER, pkg.LMKAN_LAYOUT_PACKED])
@@ -511,6 +523,24 @@ def _shifted(t, elems=1):
     out = buf[elems:].view(t.shape)
     out.copy_(t)
     return out
+
+
+def test_one_output_layer_takes_rows_and_tables_on_any_element_boundary(dev, oracle):
+    """The forward kernel of a layer with one output reads its rows eight bytes at a time; rows on a
+    4-byte boundary go through the general kernel instead, a table or y off the 16-byte grid
+    change nothing."""
+    B, n_in, n_out, G = 500, 40, 1, 12
+    x, P, _ = _inputs(B, n_in, n_out, G, 33, dev)
+    desc = _desc(n_in, n_out, G)
+    want = oracle.forward(x.cpu().numpy(), P.cpu().numpy(), G)
+    xu, Pu = _shifted(x), _shifted(P)
+    assert xu.data_ptr() % 8 == 4 and Pu.data_ptr() % 16 != 0
+    for xq, Pq, yq in ((x, Pu, _shifted(torch.empty((B, 1), device=dev))), (xu, P, torch.empty((B, 1), device=dev)),
+                       (xu, Pu, _shifted(torch.empty((B, 1), device=dev)))):
+        yq.fill_(float("nan"))
+        pkg.lmkan_forward(desc, xq, Pq, y=yq)
+        torch.cuda.synchronize()
+        assert np.abs(yq.cpu().numpy() - want).max() <= TOL_F32 * np.abs(want).max()
 
 
 @pytest.mark.parametrize("storage", ["f32", "bf16"])
