@@ -193,8 +193,8 @@ struct HeadArgs {
     int atomic_out;        // several chunks: add into the zero-filled y
 };
 
-constexpr int kHeadSamples = 4;  // steps a wave has in flight
-constexpr int kHeadFill = 8;     // table elements a thread has in flight while LDS is filled
+constexpr int kHeadSamples = 2;  // steps a wave has in flight (more gain nothing: the two locates of a step bound the kernel)
+constexpr int kHeadFill = 12;    // table elements a thread has in flight while LDS is filled
 
 template <typename CT>
 __global__ __launch_bounds__(1024) void forward_head_kernel(HeadArgs a)
