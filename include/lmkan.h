@@ -139,6 +139,8 @@ lmkan_status lmkan_grid(int32_t grid, float *nodes_host, float *inv_h_host);
  * with a packed table (padding columns must hold finite values; lmkan_pack
  * writes zeros), and n_out that is a multiple of four with a table in the
  * layout of Alg. 1; other layers in that layout run on slower general kernels.
+ * A layer with one output is quickest with its table left in the layout of
+ * Alg. 1 (contiguous over the pairs; packing pads it to 64 columns).
  */
 size_t lmkan_packed_bytes(const lmkan_desc *desc);
 
