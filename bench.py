@@ -60,7 +60,7 @@ def kernel_names(w, n_out, B, storage, packed):
         # one output on rows: the tables of 64 pairs (or of all) fit LDS, the kernel locates by itself
         fit = ((160 * 1024 - 1024) // 4) // ((w.grid + 1) ** 2 | 1)
         if n_out == 1 and not getattr(w, "kh", 0) and (fit >= w.n_in // 2 or fit >= 64):
-            fwd = "forward_head_kernel"
+            fwd, gx, gp = "forward_head_kernel", "backward_input_head_kernel", "backward_coef_head_kernel"
     elif ok and w.grid <= 16:
         f16 = storage == "f16" and (packed or n_out % 8 == 0)
         fwd = "forward_slab_f16_kernel" if f16 else "forward_slab_kernel"

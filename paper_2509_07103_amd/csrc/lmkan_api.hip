@@ -331,8 +331,13 @@ lmkan_status backward_impl(const lmkan_desc *desc, int64_t batch, const float *x
         (coef_dev && !aligned(coef_dev, dtype_size(desc->coef_dtype))))
         return LMKAN_ERR_ALIGN;
     const bool small = small_out_shape_ok(s);
-    const bool gx_small = grad_x_dev && small;
-    const bool gp_small = grad_coef_dev && small && small_coef_ok(s);
+    // one output on rows: kernels that keep the tables (or their gradient) in LDS and locate the
+    // inputs themselves: no records, no scratch (windows and 4-byte aligned rows: the kernels below)
+    const bool head = head_forward_shape_ok(s) && !conv;
+    const bool gx_head = grad_x_dev && head;
+    const bool gp_head = grad_coef_dev && head;
+    const bool gx_small = grad_x_dev && small && !gx_head;
+    const bool gp_small = grad_coef_dev && small && small_coef_ok(s) && !gp_head;
     // Input gradient.  Where a slab kernel applies (G <= 34) it is the faster one for the input
     // gradient alone.  The walk over the cell-sorted samples yields both gradients from one pass
     // over gy: it takes the grids too fine for any slab, and the 16-output slab range when both
@@ -345,7 +350,7 @@ lmkan_status backward_impl(const lmkan_desc *desc, int64_t batch, const float *x
     const bool gx_fused = grad_x_dev && !small && enough_work && fused_pays &&
                           fused_backward_applicable(s, coef_dev, grad_y_dev, grad_coef_dev);
     const bool gx_slab = slab_ok && !gx_fused;
-    const bool gp_sorted = grad_coef_dev && !gp_small && coef_sorted_applicable(s, grad_y_dev, grad_coef_dev);
+    const bool gp_sorted = grad_coef_dev && !gp_small && !gp_head && coef_sorted_applicable(s, grad_y_dev, grad_coef_dev);
     const bool need_records = gp_sorted || gx_fused || gx_slab || gx_small || gp_small;
     const BackwardWorkspace w = backward_workspace(s, grad_x_dev != nullptr, grad_coef_dev != nullptr);
     const size_t need = need_records ? w.total : 0;
@@ -365,7 +370,9 @@ lmkan_status backward_impl(const lmkan_desc *desc, int64_t batch, const float *x
     // (the slab kernels read gy as it is, except with a ragged output count)
     if (gp_sorted || gx_fused || (gx_slab && ragged_outputs(s))) gy_k = launch_gy_tiles(s, grad_y_dev, ws + w.gy_tiles, hs);
     else gy_k = GyView{grad_y_dev, (int64_t)(LMKAN_PACK_TILE * sizeof(float)), (unsigned)(s.n_out * sizeof(float))};
-    if (gp_small) {
+    if (gp_head) {
+        launch_backward_coef_head(s, tab, x_dev, grad_y_dev, grad_coef_dev, !overwrite, hs);
+    } else if (gp_small) {
         launch_backward_coef_small(s, ws, grad_y_dev, grad_coef_dev, !overwrite, hs);
     } else if (gp_sorted && !gx_fused) {
         launch_backward_coef_sorted(s, stream_k, gy_k, grad_coef_dev, !overwrite, hs);
@@ -374,7 +381,9 @@ lmkan_status backward_impl(const lmkan_desc *desc, int64_t batch, const float *x
         if (overwrite) launch_fill_zero(grad_coef_dev, (size_t)s.nodes() * s.pairs() * s.n_out, hs);
         launch_backward_generic(s, tab, x_dev, coef_dev, grad_y_dev, nullptr, grad_coef_dev, hs, conv);
     }
-    if (gx_fused) {
+    if (gx_head) {
+        launch_backward_input_head(s, tab, x_dev, coef_dev, grad_y_dev, grad_x_dev, hs);
+    } else if (gx_fused) {
         // one walk over the cell-sorted samples yields both gradients (the coefficient gradient
         // qualifies whenever the input gradient does)
         launch_backward_fused(s, tab, stream_k, ws, coef_dev, gy_k, grad_x_dev, grad_coef_dev, !overwrite, ws_partial,

@@ -110,6 +110,12 @@ void launch_forward_small(const LayerShape &s, const void *coef, float *y, const
 bool head_forward_shape_ok(const LayerShape &s);
 void launch_forward_head(const LayerShape &s, const GridTab &tab, const float *x, const void *coef, float *y,
                          hipStream_t stream);
+// its gradients, the same way: x, gy [batch] and grad_x 8-byte aligned rows; grad_coef float32 in
+// the layout of Alg. 1
+void launch_backward_input_head(const LayerShape &s, const GridTab &tab, const float *x, const void *coef,
+                                const float *gy, float *gx, hipStream_t stream);
+void launch_backward_coef_head(const LayerShape &s, const GridTab &tab, const float *x, const float *gy,
+                               float *gcoef, bool accumulate, hipStream_t stream);
 void launch_backward_input_small(const LayerShape &s, const GridTab &tab, const void *coef, const float *gy,
                                  float *gx_scratch, const void *records, hipStream_t stream);
 void launch_backward_coef_small(const LayerShape &s, const void *records, const float *gy, float *gcoef,

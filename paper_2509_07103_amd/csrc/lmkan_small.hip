@@ -167,19 +167,31 @@ __global__ __launch_bounds__(kThreads) void backward_coef_small_kernel(SmallArgs
 }
 
 // ---------------------------------------------------------------------------
-// One output (a regression head), forward: y[n] = sum_k f_k(x[n][2k], x[n][2k+1]) (Eq. 2 with a
-// single q).  The tables of a chunk of pairs sit in LDS as float32, [pair][node] with an odd pitch.
-// A group of `lps` lanes (a power of two, up to the whole wave) takes a sample with a lane per
-// pair, so the two inputs of its pairs are one contiguous read of the sample's row, and locates
-// them itself (Alg. 1 "Preamble"): no records are written or read.  The products of a sample meet
-// in a sum over its lanes.  A wave has kHeadSamples such steps in flight and asks for the inputs
-// of the next ones before it works on those it has.
+// One output (a regression head): y[n] = sum_k f_k(x[n][2k], x[n][2k+1]) (Eq. 2 with a single q),
+// its input gradient and its coefficient gradient.  With one output the table of a pair is
+// (G+1)^2 floats, so the tables of a chunk of pairs (or, for the coefficient gradient, their
+// gradient) sit in LDS as float32, [pair][node] with an odd pitch.  A group of `lps` lanes (a
+// power of two, up to the whole wave) takes a sample with a lane per pair, so the two inputs of
+// its pairs are one contiguous read of the sample's row (and the two derivatives one contiguous
+// write), and locates them itself (Alg. 1 "Preamble"): no records are written or read.
+//   kHeadForward    the products of a sample meet in a sum over its lanes
+//   kHeadGradInput  d/dx1 = gy (1/h1) ((P10 - P00)(1 - v) + (P11 - P01) v), d/dx2 likewise
+//   kHeadGradCoef   gP[corner] += w_corner gy with LDS atomics (the lanes of a sample are different
+//                   pairs: their addresses never coincide), the LDS copy added to the zero-filled
+//                   (or existing) gradient once at the end
+// A wave has kHeadSamples such steps in flight and asks for the inputs of the next ones before it
+// works on those it has.
 // ---------------------------------------------------------------------------
+enum HeadMode { kHeadForward = 0, kHeadGradInput = 1, kHeadGradCoef = 2 };
+
 struct HeadArgs {
     const void *P;
-    CoefMap map;
+    CoefMap map;           // of P; for kHeadGradCoef of the gradient
     const float *x;
+    const float *gy;       // [B] (one output)
     float *y;
+    float *gx;             // [B][n_in]
+    float *gP;             // float32, layout of Alg. 1
     GridTab tab;
     int64_t B;
     int n_in;
@@ -190,14 +202,15 @@ struct HeadArgs {
     int pairs_per_chunk;   // a multiple of 64 unless one chunk holds every pair
     int lps;               // lanes per sample
     int samples_per_block;
-    int atomic_out;        // several chunks: add into the zero-filled y
+    int atomic_out;        // forward with several chunks: add into the zero-filled y
 };
 
 constexpr int kHeadSamples = 2;  // steps a wave has in flight (more gain nothing: the two locates of a step bound the kernel)
 constexpr int kHeadFill = 12;    // table elements a thread has in flight while LDS is filled
+constexpr int kHeadThreads = 1024;
 
-template <typename CT>
-__global__ __launch_bounds__(1024) void forward_head_kernel(HeadArgs a)
+template <typename CT, int MODE>
+__device__ __forceinline__ void head_body(const HeadArgs &a)
 {
     extern __shared__ __align__(16) float head_smem[];
     const int k0 = blockIdx.y * a.pairs_per_chunk;
@@ -207,31 +220,36 @@ __global__ __launch_bounds__(1024) void forward_head_kernel(HeadArgs a)
     float *s_invh = s_node + LMKAN_MAX_GRID + 1;
     for (int i = threadIdx.x; i <= a.tab.G; i += blockDim.x) s_node[i] = a.tab.node[i];
     for (int i = threadIdx.x; i < a.tab.G; i += blockDim.x) s_invh[i] = a.tab.inv_h[i];
-    // pairs along the threads: contiguous in the layout of Alg. 1 with one output.  Every load is
-    // unconditional (the index clamped), so that kHeadFill of them are in flight per thread.
-    const CT *P = static_cast<const CT *>(a.P);
     const int total = kc * a.nodes;
-    // element i = node * kc + kl; a thread's elements lie blockDim.x apart: (node, kl) advance by
+    // element i = node * kc + kl (pairs along the threads: contiguous in the layout of Alg. 1 with
+    // one output); a thread's elements lie blockDim.x apart: (node, kl) advance by
     // (step_node, step_kl) with a carry, without a division per element
     const int step_node = (int)blockDim.x / kc, step_kl = (int)blockDim.x - step_node * kc;
-    int node = (int)threadIdx.x / kc, kl = (int)threadIdx.x - node * kc;
-    for (int base = threadIdx.x; base < total; base += blockDim.x * kHeadFill) {
-        CT raw[kHeadFill];
-        int at[kHeadFill];
+    if constexpr (MODE == kHeadGradCoef) {
+        for (int i = threadIdx.x; i < a.pairs_per_chunk * a.pitch; i += blockDim.x) s_tab[i] = 0.0f;
+    } else {
+        // Every load is unconditional (the node clamped), so that kHeadFill of them are in flight
+        // per thread.
+        const CT *P = static_cast<const CT *>(a.P);
+        int node = (int)threadIdx.x / kc, kl = (int)threadIdx.x - node * kc;
+        for (int base = threadIdx.x; base < total; base += blockDim.x * kHeadFill) {
+            CT raw[kHeadFill];
+            int at[kHeadFill];
 #pragma unroll
-        for (int u = 0; u < kHeadFill; ++u) {
-            const int node_rd = min(node, a.nodes - 1);   // past the end: the same pair of the last node again
-            at[u] = kl * a.pitch + node_rd;
-            raw[u] = P[(int64_t)node_rd * a.map.s_node + (int64_t)(k0 + kl) * a.map.s_pair];
-            node += step_node;
-            kl += step_kl;
-            if (kl >= kc) {
-                kl -= kc;
-                ++node;
+            for (int u = 0; u < kHeadFill; ++u) {
+                const int node_rd = min(node, a.nodes - 1);   // past the end: the same pair of the last node again
+                at[u] = kl * a.pitch + node_rd;
+                raw[u] = P[(int64_t)node_rd * a.map.s_node + (int64_t)(k0 + kl) * a.map.s_pair];
+                node += step_node;
+                kl += step_kl;
+                if (kl >= kc) {
+                    kl -= kc;
+                    ++node;
+                }
             }
-        }
 #pragma unroll
-        for (int u = 0; u < kHeadFill; ++u) s_tab[at[u]] = widen(raw[u]);  // (a clamped one rewrites an element of the last node)
+            for (int u = 0; u < kHeadFill; ++u) s_tab[at[u]] = widen(raw[u]);  // (a clamped one rewrites an element of the last node)
+        }
     }
     __syncthreads();
 
@@ -244,60 +262,116 @@ __global__ __launch_bounds__(1024) void forward_head_kernel(HeadArgs a)
     const int64_t n_end = min(a.B, n_begin + a.samples_per_block);
 
     // inputs of (round starting at n, pairs kk ...): lanes past the chunk and samples past the block
-    // repeat the last one, every load is in bounds and unconditional, what they add is dropped
-    auto request = [&](int64_t n, int kk, float2 (&xv)[kHeadSamples]) {
+    // repeat the last one, every load is in bounds and unconditional, what they yield is dropped
+    auto request = [&](int64_t n, int kk, float2 (&xv)[kHeadSamples], float (&g)[kHeadSamples]) {
         const int kl = min(kk + pl, kc - 1);
 #pragma unroll
         for (int s = 0; s < kHeadSamples; ++s) {
             const int64_t nn = min(n + s * per_step + sub, n_end - 1);
             xv[s] = *reinterpret_cast<const float2 *>(a.x + nn * a.n_in + 2 * (k0 + kl));
+            if constexpr (MODE != kHeadForward) g[s] = a.gy[nn];
         }
     };
 
     int64_t n = n_begin + (int64_t)wave * per_round;
-    if (n >= n_end) return;
     float2 xv[kHeadSamples], xv_next[kHeadSamples];
-    request(n, 0, xv_next);
+    float g[kHeadSamples] = {}, g_next[kHeadSamples] = {};
+    request(n, 0, xv_next, g_next);   // (a wave with no round of its own reads the block's last sample)
     while (n < n_end) {
         float acc[kHeadSamples];
 #pragma unroll
         for (int s = 0; s < kHeadSamples; ++s) acc[s] = 0.0f;
         for (int kk = 0; kk < kc; kk += a.lps) {
 #pragma unroll
-            for (int s = 0; s < kHeadSamples; ++s) xv[s] = xv_next[s];
+            for (int s = 0; s < kHeadSamples; ++s) {
+                xv[s] = xv_next[s];
+                g[s] = g_next[s];
+            }
             // the step after this one: more pairs of these samples, else the wave's next round
             // (past the end it repeats the block's last sample)
             const bool more = kk + a.lps < kc;
-            request(more ? n : n + (int64_t)waves * per_round, more ? kk + a.lps : 0, xv_next);
+            request(more ? n : n + (int64_t)waves * per_round, more ? kk + a.lps : 0, xv_next, g_next);
             const bool on = kk + pl < kc;
-            const float *t_pair = s_tab + min(kk + pl, kc - 1) * a.pitch;
+            const int kl = min(kk + pl, kc - 1);
+            float *t_pair = s_tab + kl * a.pitch;
 #pragma unroll
             for (int s = 0; s < kHeadSamples; ++s) {
                 const Preamble pr = preamble(s_node, s_invh, a.tab.G, xv[s].x, xv[s].y);
                 const float u = pr.a_hi, v = pr.b_hi;
                 const float a_lo = 1.0f - u, b_lo = 1.0f - v;
-                const float *t = t_pair + pr.node;
-                float val = (a_lo * b_lo) * t[0];
-                val = fmaf(u * b_lo, t[a.W], val);
-                val = fmaf(a_lo * v, t[1], val);
-                val = fmaf(u * v, t[a.W + 1], val);
-                acc[s] += on ? val : 0.0f;
+                float *t = t_pair + pr.node;
+                const int64_t mine = n + s * per_step + sub;
+                if constexpr (MODE == kHeadForward) {
+                    float val = (a_lo * b_lo) * t[0];
+                    val = fmaf(u * b_lo, t[a.W], val);
+                    val = fmaf(a_lo * v, t[1], val);
+                    val = fmaf(u * v, t[a.W + 1], val);
+                    acc[s] += on ? val : 0.0f;
+                } else if constexpr (MODE == kHeadGradInput) {
+                    const float s00 = g[s] * t[0], s10 = g[s] * t[a.W], s01 = g[s] * t[1], s11 = g[s] * t[a.W + 1];
+                    const float d1 = pr.rh1 * ((s10 - s00) * b_lo + (s11 - s01) * v);
+                    const float d2 = pr.rh2 * ((s01 - s00) * a_lo + (s11 - s10) * u);
+                    if (on && mine < n_end)
+                        *reinterpret_cast<float2 *>(a.gx + mine * a.n_in + 2 * (k0 + kl)) = make_float2(d1, d2);
+                } else {
+                    if (on && mine < n_end) {
+                        atomicAdd(t, (a_lo * b_lo) * g[s]);
+                        atomicAdd(t + a.W, (u * b_lo) * g[s]);
+                        atomicAdd(t + 1, (a_lo * v) * g[s]);
+                        atomicAdd(t + a.W + 1, (u * v) * g[s]);
+                    }
+                }
             }
         }
+        if constexpr (MODE == kHeadForward) {
 #pragma unroll
-        for (int s = 0; s < kHeadSamples; ++s) {
-            float total_s = acc[s];
-            for (int m = a.lps >> 1; m >= 1; m >>= 1) total_s += __shfl_xor(total_s, m, 64);
-            const int64_t mine = n + s * per_step + sub;
-            if (pl == 0 && mine < n_end) {
-                if (a.atomic_out)
-                    unsafeAtomicAdd(a.y + mine, total_s);
-                else
-                    a.y[mine] = total_s;
+            for (int s = 0; s < kHeadSamples; ++s) {
+                float total_s = acc[s];
+                for (int m = a.lps >> 1; m >= 1; m >>= 1) total_s += __shfl_xor(total_s, m, 64);
+                const int64_t mine = n + s * per_step + sub;
+                if (pl == 0 && mine < n_end) {
+                    if (a.atomic_out)
+                        unsafeAtomicAdd(a.y + mine, total_s);
+                    else
+                        a.y[mine] = total_s;
+                }
             }
         }
         n += (int64_t)waves * per_round;
     }
+
+    if constexpr (MODE == kHeadGradCoef) {
+        // every wave comes here (none leaves early): the block's sums go to the gradient
+        __syncthreads();
+        int node = (int)threadIdx.x / kc, kl = (int)threadIdx.x - node * kc;
+        for (int i = threadIdx.x; i < total; i += blockDim.x) {
+            const float v = s_tab[kl * a.pitch + node];
+            if (v != 0.0f) unsafeAtomicAdd(a.gP + (int64_t)node * a.map.s_node + (int64_t)(k0 + kl) * a.map.s_pair, v);
+            node += step_node;
+            kl += step_kl;
+            if (kl >= kc) {
+                kl -= kc;
+                ++node;
+            }
+        }
+    }
+}
+
+template <typename CT>
+__global__ __launch_bounds__(kHeadThreads) void forward_head_kernel(HeadArgs a)
+{
+    head_body<CT, kHeadForward>(a);
+}
+
+template <typename CT>
+__global__ __launch_bounds__(kHeadThreads) void backward_input_head_kernel(HeadArgs a)
+{
+    head_body<CT, kHeadGradInput>(a);
+}
+
+__global__ __launch_bounds__(kHeadThreads) void backward_coef_head_kernel(HeadArgs a)
+{
+    head_body<float, kHeadGradCoef>(a);
 }
 
 SmallArgs small_args(const LayerShape &s, const void *coef, const void *records)
@@ -348,14 +422,13 @@ bool head_forward_shape_ok(const LayerShape &s)
     return s.n_out == 1 && head_chunk(s) > 0;
 }
 
-void launch_forward_head(const LayerShape &s, const GridTab &tab, const float *x, const void *coef, float *y,
-                         hipStream_t stream)
+// grid, LDS and per-block share of a launch of head_kernel over at most `max_blocks` workgroups
+// per chunk of pairs
+static HeadArgs head_args(const LayerShape &s, const GridTab &tab, const float *x, int max_blocks, dim3 *grid,
+                          size_t *lds)
 {
     HeadArgs a = {};
-    a.P = coef;
-    a.map = coef_map(s);
     a.x = x;
-    a.y = y;
     a.tab = tab;
     a.B = s.batch;
     a.n_in = s.n_in;
@@ -365,29 +438,77 @@ void launch_forward_head(const LayerShape &s, const GridTab &tab, const float *x
     a.pitch = head_pitch(s);
     a.pairs_per_chunk = head_chunk(s);
     const int chunks = (a.K + a.pairs_per_chunk - 1) / a.pairs_per_chunk;
-    a.atomic_out = chunks > 1;
     // a sample takes as many lanes as the chunk has pairs, rounded up to a power of two
     a.lps = 1;
     while (a.lps < 64 && a.lps < a.pairs_per_chunk) a.lps *= 2;
-    const size_t lds = ((size_t)a.pairs_per_chunk * a.pitch + 2 * LMKAN_MAX_GRID + 2) * sizeof(float);
-    // every workgroup fills its LDS with the chunk's tables first: a workgroup should have at least
-    // two rounds of its 16 waves to spread that over, and 256 workgroups fill the chip
-    const int threads = 1024;
-    const int64_t round = (int64_t)(threads / 64) * kHeadSamples * (64 / a.lps);
+    *lds = ((size_t)a.pairs_per_chunk * a.pitch + 2 * LMKAN_MAX_GRID + 2) * sizeof(float);
+    // every workgroup fills (or clears and later adds out) its LDS copy of the chunk's tables: a
+    // workgroup should have at least two rounds of its 16 waves to spread that over
+    const int64_t round = (int64_t)(kHeadThreads / 64) * kHeadSamples * (64 / a.lps);
     int64_t per_block = 2 * round;
-    if ((s.batch + per_block - 1) / per_block * chunks > 256) {
-        const int64_t blocks = 256 / chunks > 0 ? 256 / chunks : 1;
-        per_block = ((s.batch + blocks - 1) / blocks + round - 1) / round * round;
-    }
+    if ((s.batch + per_block - 1) / per_block > max_blocks)
+        per_block = ((s.batch + max_blocks - 1) / max_blocks + round - 1) / round * round;
     a.samples_per_block = (int)per_block;
-    const dim3 grid((unsigned)((s.batch + per_block - 1) / per_block), (unsigned)chunks);
-    typedef void (*Kernel)(HeadArgs);
-    const Kernel kernels[3] = {forward_head_kernel<float>, forward_head_kernel<_Float16>, forward_head_kernel<bf16_t>};
-    const Kernel kernel = kernels[s.dtype];
+    *grid = dim3((unsigned)((s.batch + per_block - 1) / per_block), (unsigned)chunks);
+    return a;
+}
+
+typedef void (*HeadKernel)(HeadArgs);
+
+static void launch_head(HeadKernel kernel, const HeadArgs &a, dim3 grid, size_t lds, hipStream_t stream,
+                        TimedKernel kind)
+{
     if (lds > 64 * 1024) allow_large_lds(reinterpret_cast<const void *>(kernel), 160 * 1024);
+    KernelTiming timing(stream, kind);
+    kernel<<<grid, kHeadThreads, lds, stream>>>(a);
+}
+
+void launch_forward_head(const LayerShape &s, const GridTab &tab, const float *x, const void *coef, float *y,
+                         hipStream_t stream)
+{
+    dim3 grid;
+    size_t lds;
+    HeadArgs a = head_args(s, tab, x, 256, &grid, &lds);   // 256 workgroups fill the chip
+    a.P = coef;
+    a.map = coef_map(s);
+    a.y = y;
+    a.atomic_out = grid.y > 1;
     if (a.atomic_out) launch_fill_zero(y, (size_t)s.batch, stream);
-    KernelTiming timing(stream, kTimeForward);
-    kernel<<<grid, threads, lds, stream>>>(a);
+    const HeadKernel kernels[3] = {forward_head_kernel<float>, forward_head_kernel<_Float16>,
+                                   forward_head_kernel<bf16_t>};
+    launch_head(kernels[s.dtype], a, grid, lds, stream, kTimeForward);
+}
+
+void launch_backward_input_head(const LayerShape &s, const GridTab &tab, const float *x, const void *coef,
+                                const float *gy, float *gx, hipStream_t stream)
+{
+    dim3 grid;
+    size_t lds;
+    HeadArgs a = head_args(s, tab, x, 256, &grid, &lds);
+    a.P = coef;
+    a.map = coef_map(s);
+    a.gy = gy;
+    a.gx = gx;   // every (sample, pair) is written by exactly one lane: no clearing, no atomics
+    const HeadKernel kernels[3] = {backward_input_head_kernel<float>, backward_input_head_kernel<_Float16>,
+                                   backward_input_head_kernel<bf16_t>};
+    launch_head(kernels[s.dtype], a, grid, lds, stream, kTimeGradInput);
+}
+
+void launch_backward_coef_head(const LayerShape &s, const GridTab &tab, const float *x, const float *gy,
+                               float *gcoef, bool accumulate, hipStream_t stream)
+{
+    dim3 grid;
+    size_t lds;
+    // (bound by the LDS atomics, about 3.5 clocks per lane and CU: every CU has to take part, although
+    // every workgroup ends by adding its whole LDS copy to the gradient)
+    HeadArgs a = head_args(s, tab, x, 256, &grid, &lds);
+    LayerShape g = s;
+    g.layout = LMKAN_LAYOUT_PAPER;
+    a.map = coef_map(g);
+    a.gy = gy;
+    a.gP = gcoef;
+    if (!accumulate) launch_fill_zero(gcoef, (size_t)s.nodes() * (size_t)s.pairs(), stream);
+    launch_head(backward_coef_head_kernel, a, grid, lds, stream, kTimeGradCoef);
 }
 
 void launch_forward_small(const LayerShape &s, const void *coef, float *y, const void *records, hipStream_t stream)
