@@ -233,8 +233,9 @@ lmkan_status lmkan_forward_static(const lmkan_desc *desc, int64_t batch, const f
  * cell-sorted kernels repeats bit for bit when every (pair, 64-output tile) is
  * walked by one wave (batch <= 12288 rows and at least 4096 (pair, tile) streams,
  * e.g. 1024 -> 1024); shorter layers and longer batches cut the streams into
- * runs that meet through float32 atomics, and the generic kernels use atomics
- * throughout: there the last bits can differ.  grad_x repeats bit for bit on the
+ * runs that meet through float32 atomics, and the generic kernels and the
+ * kernels for very few outputs use atomics throughout: there the last bits can
+ * differ.  grad_x repeats bit for bit on the
  * sorted walk (grids finer than 34 intervals) and in the kernels for very few
  * outputs (one output, or up to eight where no slab kernel applies); the slab
  * kernels (grids up to 34) add their output tiles with float32 atomics.
