@@ -64,7 +64,8 @@ def kernel_names(w, n_out, B, storage, packed):
     elif ok and w.grid <= 16:
         f16 = storage == "f16" and (packed or n_out % 8 == 0)
         fwd = "forward_slab_f16_kernel" if f16 else "forward_slab_kernel"
-        gx = "backward_input_slab_f16_kernel" if f16 else "backward_input_slab_kernel"
+        gx = ("backward_input_slab_f16_kernel" if f16 else
+              "backward_input_lane_kernel" if storage == "f32" else "backward_input_slab_kernel")
         gp = "backward_coef_stream_kernel"
     elif ok and w.grid <= 34:
         fwd, gx, gp = "forward_slab_narrow_kernel", "backward_input_slab_narrow_kernel", "backward_coef_stream_kernel"

@@ -649,6 +649,157 @@ __global__ __launch_bounds__(WAVES * 64) __attribute__((amdgpu_waves_per_eu(WAVE
 }
 
 // ---------------------------------------------------------------------------
+// Input gradient with a lane per sample (float32 tables, 64-output tiles).  The lane keeps the 64
+// gy values of its sample and tile in registers and reads the four corner rows of its own cell,
+// 16 bytes at a time; the four dot products stay inside the lane, so nothing is exchanged between
+// lanes and every multiply-add is a plain one.  All lanes reading piece j of their rows at once
+// would meet on the same four banks; lane l reads piece (j + l) mod 16 instead and holds its gy
+// pieces in that rotated order (a dot product does not care about the order of its terms): the 16
+// lanes of every group of 16 are on 16 different bank groups whatever their rows, which is the
+// best a 1 KiB read can do.
+// ---------------------------------------------------------------------------
+template <int W_CT>
+__global__ __launch_bounds__(1024) __attribute__((amdgpu_waves_per_eu(4, 4))) void backward_input_lane_kernel(GradInArgs a)
+{
+    extern __shared__ __align__(16) float smem[];  // two slab buffers, then 1/h of the grid
+    constexpr int WAVES = 16;
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int l15 = lane & 15;
+    int id = blockIdx.x;
+    const int total = gridDim.x;
+    if ((total & 7) == 0) id = (id & 7) * (total >> 3) + (id >> 3);
+    const int btile = id % a.n_btiles;
+    const int rest = id / a.n_btiles;
+    const int ks = rest % a.n_split;
+    const int jt = rest / a.n_split;
+
+    const int k_begin = ks * a.pairs_per_split;
+    const int k_end = min(a.K, k_begin + a.pairs_per_split);
+    const int slab_floats = a.nodes * kTile;
+    float *slab0 = smem;
+    float *slab1 = smem + slab_floats;
+    float *s_invh = smem + 2 * slab_floats;
+    for (int i = threadIdx.x; i < a.tab.G; i += blockDim.x) s_invh[i] = a.tab.inv_h[i];
+    SlabArgs sa;  // only the fields issue_slab_load reads
+    sa.P = a.P;
+    sa.map = a.map;
+    sa.nodes = a.nodes;
+    sa.col_limit = a.col_limit;
+    sa.packed = a.packed;
+
+    const int64_t n = (int64_t)btile * (WAVES * 64) + wave * 64 + lane;
+    const bool valid = n < a.B;
+    const int64_t n_rd = valid ? n : a.B - 1;
+
+    // register j: gy of outputs jt*64 + 4 p .. + 3 with p = (j + l15) mod 16
+    float4 gyr[16];
+#pragma unroll
+    for (int j = 0; j < 16; ++j) {
+        const int col = jt * kTile + ((j + l15) & 15) * 4;
+        gyr[j] = make_float4(0.f, 0.f, 0.f, 0.f);
+        if (valid && col < a.n_out)
+            gyr[j] = *reinterpret_cast<const float4 *>(a.gy + (col >> 6) * a.gy_tile_stride + n * a.gy_row_stride + (col & 63));
+    }
+
+    // columns past the end of a ragged output tile are never loaded: make them read as zero
+    for (int i = threadIdx.x; i < 2 * slab_floats; i += blockDim.x) smem[i] = 0.0f;
+    __syncthreads();  // zeros and s_invh in place before any slab load lands
+    SlabFill<float, WAVES> fill;
+    int nx_node = 0;
+    float nx_u = 0.f, nx_v = 0.f;
+    auto fetch_record = [&](int k) {
+        const int64_t o = (int64_t)k * a.B + n_rd;
+        nx_node = a.rec_node[o];
+        nx_u = a.rec_u[o];
+        nx_v = a.rec_v[o];
+    };
+    if (k_begin < k_end) {
+        fill.template issue<0>(sa, slab0, k_begin, jt, wave, lane);
+        fill.template commit<0>(sa, slab0, wave, lane);
+        fill.template issue<1>(sa, slab0, k_begin, jt, wave, lane);
+        fill.template commit<1>(sa, slab0, wave, lane);
+        fetch_record(k_begin);
+    }
+    const int w = W_CT > 0 ? W_CT : a.W;
+    float *gx_lane = a.gx + n;   // transposed scratch [n_in][ld], plain layout
+    for (int k = k_begin; k < k_end; ++k) {
+        const float *slab = ((k - k_begin) & 1) ? slab1 : slab0;
+        float *slab_next = ((k - k_begin) & 1) ? slab0 : slab1;
+        const int node = nx_node;
+        const float u = nx_u, v = nx_v;
+        const int i1 = node / w;
+        const float rh1 = s_invh[i1], rh2 = s_invh[node - i1 * w];
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        __syncthreads();
+        if (k + 1 < k_end) {
+            fill.template issue<0>(sa, slab_next, k + 1, jt, wave, lane);
+            fetch_record(k + 1);
+        }
+        // piece (j + l15) mod 16 of the row: from `first` for j < 16 - l15, one row back after the wrap
+        unsigned first = lds_address(slab) + (unsigned)node * kRowBytes + (unsigned)l15 * 16;
+        // The derivative is made of differences between neighbouring corners, and on a smooth table
+        // two dot products over all 64 outputs would agree in most of their digits before they are
+        // subtracted.  So the products with P00 and P01 are only summed over the four outputs of a
+        // piece and taken off at once: dif_a = sum gy (P10 - P00), dif_b = sum gy (P11 - P01),
+        // dif_c = sum gy (P01 - P00); the fourth difference is P11 - P10 = (P11 - P01) + (P01 - P00)
+        // - (P10 - P00), which turns d/dx2 into (dif_c + u (dif_b - dif_a)) / h2.
+        float dif_a = 0.f, dif_b = 0.f, dif_c = 0.f;
+        // the rows of piece j + 1 are requested before the multiply-adds of piece j are issued
+        Corners ring[2];
+        auto request = [&](Corners &c, int j) {
+            // (the empty statement ties the addresses to the sums so far, so that the compiler keeps
+            // that order: left to itself it issues all 64 reads of a pair first and spills them, or
+            // walks one corner at a time with a single read in flight)
+            asm volatile("" : "+v"(first), "+v"(dif_a), "+v"(dif_b), "+v"(dif_c));
+            const unsigned addr = (l15 + j >= 16 ? first - kRowBytes : first) + j * 16;
+            c.c00 = lds_load4(addr);
+            c.c01 = lds_load4(addr + kRowBytes);
+            c.c10 = lds_load4(addr + w * kRowBytes);
+            c.c11 = lds_load4(addr + w * kRowBytes + kRowBytes);
+        };
+        request(ring[0], 0);
+        static_for(std::make_integer_sequence<int, 16>{}, [&](auto jc) {
+            constexpr int j = decltype(jc)::value;
+            if constexpr (j + 1 < 16) request(ring[(j + 1) & 1], j + 1);
+            const Corners &c = ring[j & 1];
+            const float4 g = gyr[j];
+            float p00 = g.x * c.c00.x, p01 = g.x * c.c01.x;
+            dif_a = fmaf(g.x, c.c10.x, dif_a);
+            dif_b = fmaf(g.x, c.c11.x, dif_b);
+            p00 = fmaf(g.y, c.c00.y, p00);
+            p01 = fmaf(g.y, c.c01.y, p01);
+            dif_a = fmaf(g.y, c.c10.y, dif_a);
+            dif_b = fmaf(g.y, c.c11.y, dif_b);
+            p00 = fmaf(g.z, c.c00.z, p00);
+            p01 = fmaf(g.z, c.c01.z, p01);
+            dif_a = fmaf(g.z, c.c10.z, dif_a);
+            dif_b = fmaf(g.z, c.c11.z, dif_b);
+            p00 = fmaf(g.w, c.c00.w, p00);
+            p01 = fmaf(g.w, c.c01.w, p01);
+            dif_a = fmaf(g.w, c.c10.w, dif_a);
+            dif_b = fmaf(g.w, c.c11.w, dif_b);
+            dif_a -= p00;
+            dif_b -= p01;
+            dif_c += p01 - p00;
+            if constexpr (j == 7) {
+                if (k + 1 < k_end) {
+                    fill.template commit<0>(sa, slab_next, wave, lane);
+                    fill.template issue<1>(sa, slab_next, k + 1, jt, wave, lane);
+                }
+            }
+        });
+        if (k + 1 < k_end) fill.template commit<1>(sa, slab_next, wave, lane);
+        const float d1 = rh1 * (dif_a * (1.0f - v) + dif_b * v);
+        const float d2 = rh2 * (dif_c + u * (dif_b - dif_a));
+        if (valid) {
+            unsafeAtomicAdd(gx_lane + (int64_t)(2 * k) * a.ld, d1);
+            unsafeAtomicAdd(gx_lane + (int64_t)(2 * k + 1) * a.ld, d2);
+        }
+    }
+}
+
+// ---------------------------------------------------------------------------
 // Forward for grids whose 64-output slab does not fit LDS twice (17 <= G <= 34): the same
 // streaming with 16-output tiles.  A table row is then 64 bytes, read by four lanes, so a wave
 // takes 16 samples per step and the sample's weights reach its four lanes through the DPP
@@ -1375,13 +1526,14 @@ void launch_backward_input_slab(const LayerShape &s, const GridTab &tab, const v
     const bool narrow = !slab_wide_fits(s);
     constexpr int kNarrowSets = 8;
     constexpr int kWavesF32 = 16;  // float32 tables need no staging registers: 16 waves of 64 samples
-    const Kernel kernels[9] = {backward_input_slab_kernel<float, kWavesF32, 16 / kWavesF32, 1, 0>,
+    // (float32 tables on 64-output tiles: the kernel with a lane per sample)
+    const Kernel kernels[9] = {backward_input_lane_kernel<0>,
                                backward_input_slab_kernel<_Float16, WAVES, SETS, 2, 0>,
                                backward_input_slab_kernel<bf16_t, WAVES, SETS, 2, 0>,
                                backward_input_slab_narrow_kernel<float, 2 * WAVES, kNarrowSets / 2>,
                                backward_input_slab_narrow_kernel<_Float16, WAVES, kNarrowSets>,
                                backward_input_slab_narrow_kernel<bf16_t, WAVES, kNarrowSets>,
-                               backward_input_slab_kernel<float, kWavesF32, 16 / kWavesF32, 1, 17>,
+                               backward_input_lane_kernel<17>,
                                backward_input_slab_kernel<_Float16, WAVES, SETS, 2, 17>,
                                backward_input_slab_kernel<bf16_t, WAVES, SETS, 2, 17>};
     const int which = s.dtype + (narrow ? 3 : (s.G == 16 ? 6 : 0));
@@ -1415,7 +1567,8 @@ void launch_backward_input_slab(const LayerShape &s, const GridTab &tab, const v
     while (tiles * split < 256 && a.K / (split * 2) >= 4) split *= 2;
     a.n_split = split;
     a.pairs_per_split = (a.K + split - 1) / split;
-    const int layout = narrow ? kScratchQuad : kScratchOct;
+    const bool lane_kernel = !narrow && s.dtype == LMKAN_F32;   // its lanes are consecutive samples
+    const int layout = lane_kernel ? kScratchPlain : narrow ? kScratchQuad : kScratchOct;
     a.ld = scratch_row_stride(s.batch, layout);
     launch_fill_zero(a.gx, (size_t)a.ld * s.n_in, stream);
     const size_t slabs = narrow ? (size_t)2 * s.nodes() * kNarrowRowBytes : slab_forward_lds_bytes(s);
