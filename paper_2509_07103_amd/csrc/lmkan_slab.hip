@@ -1513,11 +1513,11 @@ void launch_backward_input_slab(const LayerShape &s, const GridTab &tab, const v
                                 void *scratch, hipStream_t stream, const ConvGeom *conv)
 {
     if (slab_wide_fits(s) && slab_f16_native_ok(s)) {
-        launch_fill_zero(static_cast<float *>(scratch), (size_t)scratch_row_stride(s.batch, kScratchOct) * s.n_in,
+        launch_fill_zero(static_cast<float *>(scratch), (size_t)scratch_row_stride(s.batch, kScratchPlain) * s.n_in,
                          stream);
         launch_backward_input_slab_f16(s, tab, coef, gy, gy_tile_stride, gy_row_stride, static_cast<float *>(scratch),
                                        records, stream);
-        launch_input_gradient_out(static_cast<float *>(scratch), gx, s, conv, stream, kScratchOct);
+        launch_input_gradient_out(static_cast<float *>(scratch), gx, s, conv, stream, kScratchPlain);
         return;
     }
     constexpr int WAVES = 8, SETS = 2;

@@ -181,44 +181,28 @@ __global__ __launch_bounds__(kWaves * 64) __attribute__((amdgpu_waves_per_eu(4, 
     }
 }
 
-// d = (w of lane S of this row) * x
-template <int S>
-__device__ __forceinline__ float mul_row_bcast_h(float w, float x)
+// acc += gy . c over the four outputs of a piece (v_fma_mix_f32 widens the float16 operand)
+__device__ __forceinline__ float fma4_h(const float4 g, const h4v c, float acc)
 {
-    float d;
-    asm("v_mul_f32_dpp %0, %1, %2 row_newbcast:%3 row_mask:0xf bank_mask:0xf" : "=v"(d) : "v"(w), "v"(x), "n"(S));
-    return d;
+    return fmaf(g.w, (float)c[3], fmaf(g.z, (float)c[2], fmaf(g.y, (float)c[1], fmaf(g.x, (float)c[0], acc))));
 }
 
-__device__ __forceinline__ float dot4_h(const float4 g, const h4v c)
-{
-    return fmaf(g.w, (float)c[3], fmaf(g.z, (float)c[2], fmaf(g.y, (float)c[1], g.x * (float)c[0])));
-}
-
-// first stage of the sum over the row (lanes 0-7: d/dx1, lanes 8-15: d/dx2); the other stages
-// fold the results of eight steps together, as in backward_input_slab_kernel
-template <int S>
-__device__ __forceinline__ float grad_step_h(const float4 g, const CornersH &c, float b_lo, float b_hi, float a_lo,
-                                             float a_hi)
-{
-    const float s00 = dot4_h(g, c.c00), s10 = dot4_h(g, c.c10), s01 = dot4_h(g, c.c01), s11 = dot4_h(g, c.c11);
-    float t1 = mul_row_bcast_h<S>(b_lo, s10 - s00);
-    fmac_row_bcast<S>(t1, b_hi, s11 - s01);
-    float t2 = mul_row_bcast_h<S>(a_lo, s01 - s00);
-    fmac_row_bcast<S>(t2, a_hi, s11 - s10);
-    return grad_fold_halves(t1, t2);
-}
-
-// Input gradient, the mirror of the forward kernel (see backward_input_slab_kernel in
-// lmkan_slab.hip for the scheme): gy in registers, four partial dot products per step, the
-// sample's weights by DPP broadcast, DPP row reduction, atomics into the transposed scratch.
+// Input gradient with a lane per sample (see backward_input_lane_kernel in lmkan_slab.hip for
+// the scheme): the 64 gy values of the lane's sample and tile in registers, the four corner rows
+// of its cell read eight bytes (four float16 outputs) at a time, lane l taking piece
+// (j + l) mod 16 at step j so that the 16 lanes of a group never meet on a bank; the four dot
+// products stay inside the lane, the differences of neighbouring corners are taken per piece,
+// and the two derivatives go to the transposed scratch (plain layout) with one atomic each.
+// W_CT: G + 1 when known at compile time (the corner offsets are then immediates), else 0
+template <int W_CT>
 __global__ __launch_bounds__(kWaves * 64) __attribute__((amdgpu_waves_per_eu(4, 4))) void backward_input_slab_f16_kernel(
     GradInArgs a)
 {
     extern __shared__ __align__(16) char smem_h[];  // two slab buffers, then 1/h of the grid
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-    const int l16 = lane & 15, g = lane >> 4;
+    const int l15 = lane & 15;
+    const int w = W_CT > 0 ? W_CT : a.W;
     constexpr int kTileB = kWaves * 64;
     int id = blockIdx.x;
     const int total = gridDim.x;
@@ -243,34 +227,27 @@ __global__ __launch_bounds__(kWaves * 64) __attribute__((amdgpu_waves_per_eu(4, 
     sa.col_limit = a.col_limit;
     sa.packed = a.packed;
 
-    const int64_t n_wave = (int64_t)btile * kTileB + (int64_t)wave * 64;
-    const int col = jt * kTile + l16 * 4;
-    // the step of a block of eight whose result this lane ends up with
-    const int my_step = ((l16 & 1) << 2) | (l16 & 2) | ((l16 >> 2) & 1);
+    const int64_t n = (int64_t)btile * kTileB + (int64_t)wave * 64 + lane;
+    const bool valid = n < a.B;
+    const int64_t n_rd = valid ? n : a.B - 1;
 
-    // gy of (sample n_wave + 16 g + step, outputs col .. col+3), resident for the walk
+    // register j: gy of outputs jt*64 + 4 p .. + 3 with p = (j + l15) mod 16
     float4 gyr[16];
 #pragma unroll
-    for (int t = 0; t < 16; ++t) {
-        const int64_t n = n_wave + g * 16 + t;
-        gyr[t] = make_float4(0.f, 0.f, 0.f, 0.f);
-        if (n < a.B && col < a.n_out)
-            gyr[t] = *reinterpret_cast<const float4 *>(a.gy + (col >> 6) * a.gy_tile_stride + n * a.gy_row_stride + (col & 63));
+    for (int j = 0; j < 16; ++j) {
+        const int col = jt * kTile + ((j + l15) & 15) * 4;
+        gyr[j] = make_float4(0.f, 0.f, 0.f, 0.f);
+        if (valid && col < a.n_out)
+            gyr[j] = *reinterpret_cast<const float4 *>(a.gy + (col >> 6) * a.gy_tile_stride + n * a.gy_row_stride + (col & 63));
     }
 
     int nx_node = 0;
     float nx_u = 0.f, nx_v = 0.f;
     auto fetch_record = [&](int k) {
-        const int64_t n = n_wave + lane;
-        nx_node = 0;
-        nx_u = 0.f;
-        nx_v = 0.f;
-        if (n < a.B) {
-            const int64_t o = (int64_t)k * a.B + n;
-            nx_node = a.rec_node[o];
-            nx_u = a.rec_u[o];
-            nx_v = a.rec_v[o];
-        }
+        const int64_t o = (int64_t)k * a.B + n_rd;
+        nx_node = a.rec_node[o];
+        nx_u = a.rec_u[o];
+        nx_v = a.rec_v[o];
     };
 
     // columns past the end of a ragged output tile are never loaded: make them read as zero
@@ -281,56 +258,54 @@ __global__ __launch_bounds__(kWaves * 64) __attribute__((amdgpu_waves_per_eu(4, 
         issue_slab_load_h(sa, base0, k_begin, jt, wave, lane);
         fetch_record(k_begin);
     }
-    const int lane_bytes = l16 * 8;
-    const int64_t n_lane = n_wave + g * 16 + my_step;
-    // kScratchOct layout of the scratch rows: the first eight steps land at 8 g + step, the
-    // other eight 32 further
-    float *gx_lane = a.gx + (int64_t)(l16 >> 3) * a.ld + n_wave + g * 8 + my_step;
+    float *gx_lane = a.gx + n;   // transposed scratch [n_in][ld], plain layout
 
     for (int k = k_begin; k < k_end; ++k) {
         const unsigned cur = ((k - k_begin) & 1) ? base1 : base0;
         const unsigned nxt = ((k - k_begin) & 1) ? base0 : base1;
         const int node = nx_node;
-        const float rh1 = s_invh[node / a.W], rh2 = s_invh[node % a.W];
-        const int off = node * kRowBytesH;
-        float b_lo = (1.0f - nx_v) * rh1, b_hi = nx_v * rh1, a_lo = (1.0f - nx_u) * rh2, a_hi = nx_u * rh2;
+        const float u = nx_u, v = nx_v;
+        const int i1 = node / w;
+        const float rh1 = s_invh[i1], rh2 = s_invh[node - i1 * w];
         asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
         __syncthreads();
         if (k + 1 < k_end) {
             issue_slab_load_h(sa, nxt, k + 1, jt, wave, lane);
             fetch_record(k + 1);
         }
-        // VALU results must not be read through DPP in the next two issue slots
-        asm volatile("s_nop 1" : "+v"(b_lo), "+v"(b_hi), "+v"(a_lo), "+v"(a_hi));
-
+        // piece (j + l15) mod 16 of the row: from `first` for j < 16 - l15, one row back after the wrap
+        unsigned first = cur + (unsigned)node * kRowBytesH + (unsigned)l15 * 8;
+        // dif_a = sum gy (P10 - P00), dif_b = sum gy (P11 - P01), dif_c = sum gy (P01 - P00), the
+        // products with P00 and P01 summed over the four outputs of a piece only and taken off at once
+        float dif_a = 0.f, dif_b = 0.f, dif_c = 0.f;
         CornersH ring[kAheadH + 1];
-        const int lane_base = (int)cur + lane_bytes;
-        load_corners_h<0>(ring[0], lane_base, off, a.W);
-        load_corners_h<1>(ring[1], lane_base, off, a.W);
-        float v_even = 0.0f, w_first = 0.0f, z_first = 0.0f;  // results waiting for their partners
-        static_for(std::make_integer_sequence<int, 16>{}, [&](auto tc) {
-            constexpr int T = decltype(tc)::value;
-            if constexpr (T + kAheadH < 16)
-                load_corners_h<T + kAheadH>(ring[(T + kAheadH) % (kAheadH + 1)], lane_base, off, a.W);
-            const float v = grad_step_h<T>(gyr[T], ring[T % (kAheadH + 1)], b_lo, b_hi, a_lo, a_hi);
-            if constexpr ((T & 1) == 0) {
-                v_even = v;
-            } else {
-                const float w = grad_fold_steps(v_even, v);
-                if constexpr ((T & 3) == 1) {
-                    w_first = w;
-                } else {
-                    const float z = grad_fold_pairs(w_first, w, (l16 & 2) != 0);
-                    if constexpr ((T & 7) == 3) {
-                        z_first = z;
-                    } else {
-                        const float mine = (l16 & 1) ? z : z_first;
-                        const int64_t n = n_lane + (T & ~7);
-                        if (n < a.B) unsafeAtomicAdd(gx_lane + (int64_t)(2 * k) * a.ld + (T >> 3) * 32, mine);
-                    }
-                }
-            }
+        auto request = [&](CornersH &c, int j) {
+            // (the empty statement ties the addresses to the sums so far: it keeps the reads of a
+            // piece between the multiply-adds of the pieces before it)
+            asm volatile("" : "+v"(first), "+v"(dif_a), "+v"(dif_b), "+v"(dif_c));
+            const unsigned addr = (l15 + j >= 16 ? first - kRowBytesH : first) + j * 8;
+            c.c00 = lds_load_h4(addr);
+            c.c01 = lds_load_h4(addr + kRowBytesH);
+            c.c10 = lds_load_h4(addr + w * kRowBytesH);
+            c.c11 = lds_load_h4(addr + w * kRowBytesH + kRowBytesH);
+        };
+        request(ring[0], 0);
+        request(ring[1], 1);
+        static_for(std::make_integer_sequence<int, 16>{}, [&](auto jc) {
+            constexpr int j = decltype(jc)::value;
+            if constexpr (j + kAheadH < 16) request(ring[(j + kAheadH) % (kAheadH + 1)], j + kAheadH);
+            const CornersH &c = ring[j % (kAheadH + 1)];
+            const float p00 = fma4_h(gyr[j], c.c00, 0.0f), p01 = fma4_h(gyr[j], c.c01, 0.0f);
+            dif_a = fma4_h(gyr[j], c.c10, dif_a) - p00;
+            dif_b = fma4_h(gyr[j], c.c11, dif_b) - p01;
+            dif_c += p01 - p00;
         });
+        const float d1 = rh1 * (dif_a * (1.0f - v) + dif_b * v);
+        const float d2 = rh2 * (dif_c + u * (dif_b - dif_a));
+        if (valid) {
+            unsafeAtomicAdd(gx_lane + (int64_t)(2 * k) * a.ld, d1);
+            unsafeAtomicAdd(gx_lane + (int64_t)(2 * k + 1) * a.ld, d2);
+        }
     }
 }
 
@@ -384,7 +359,8 @@ void launch_backward_input_slab_f16(const LayerShape &s, const GridTab &tab, con
                                     const void *records, hipStream_t stream)
 {
     constexpr int kTileB = kWaves * 64;
-    allow_large_lds(reinterpret_cast<const void *>(backward_input_slab_f16_kernel), 160 * 1024);
+    void (*const kernel)(GradInArgs) = s.G == 16 ? backward_input_slab_f16_kernel<17> : backward_input_slab_f16_kernel<0>;
+    allow_large_lds(reinterpret_cast<const void *>(kernel), 160 * 1024);
     const size_t n = (size_t)s.pairs() * (size_t)s.batch;
     GradInArgs a;
     a.P = coef;
@@ -398,7 +374,7 @@ void launch_backward_input_slab_f16(const LayerShape &s, const GridTab &tab, con
     a.map = coef_map(s);
     a.tab = tab;
     a.B = s.batch;
-    a.ld = scratch_row_stride(s.batch, kScratchOct);
+    a.ld = scratch_row_stride(s.batch, kScratchPlain);
     a.n_in = s.n_in;
     a.n_out = s.n_out;
     a.K = s.pairs();
@@ -415,7 +391,7 @@ void launch_backward_input_slab_f16(const LayerShape &s, const GridTab &tab, con
     a.pairs_per_split = (a.K + split - 1) / split;
     const size_t lds = (((size_t)2 * s.nodes() * kRowBytesH + 15) & ~(size_t)15) + LMKAN_MAX_GRID * sizeof(float);
     KernelTiming timing(stream, kTimeGradInput);
-    backward_input_slab_f16_kernel<<<tiles * split, kWaves * 64, lds, stream>>>(a);
+    kernel<<<tiles * split, kWaves * 64, lds, stream>>>(a);
 }
 
 }  // namespace lmkan
