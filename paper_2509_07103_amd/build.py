@@ -3,6 +3,7 @@ from __future__ import annotations
 
 import glob
 import os
+import re
 import subprocess
 import sys
 
@@ -32,15 +33,25 @@ def sources() -> list[str]:
 
 
 def build(verbose: bool = False, extra: list[str] | None = None) -> str:
-    cmd = [HIPCC, *FLAGS, *(extra or []), "-o", LIB, *sources()]
+    """Compiles the library; the compiler's resource report of the same run goes through
+    check_codegen.check_resources, so a build whose hot kernels spill registers raises."""
+    cmd = [HIPCC, *FLAGS, "-Rpass-analysis=kernel-resource-usage", *(extra or []), "-o", LIB, *sources()]
     if verbose:
         print(" ".join(cmd), flush=True)
     res = subprocess.run(cmd, capture_output=True, text=True)
     if res.returncode != 0:
         sys.stderr.write(res.stdout + res.stderr)
         raise RuntimeError("hipcc failed building liblmkan.so")
-    if verbose and res.stderr.strip():
-        sys.stderr.write(res.stderr)
+    # (what is left of stderr without the report and the source lines it quotes: warnings)
+    other = "\n".join(line for line in res.stderr.split("\n")
+                      if "kernel-resource-usage" not in line and not re.match(r"\s*\d*\s*\|", line))
+    if verbose and other.strip():
+        sys.stderr.write(other)
+    from . import check_codegen
+    scratch = check_codegen.check_resources(res.stderr)
+    if verbose:
+        print(f"resource check: {len(scratch)} kernels, {sum(1 for v in scratch.values() if v)} with scratch "
+              f"(at most {max(scratch.values())} bytes per lane)", flush=True)
     return LIB
 
 

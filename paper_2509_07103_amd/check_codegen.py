@@ -9,6 +9,12 @@ graph that starts after an inline-assembly load, the first instruction that name
 load's destination registers must be the wait that the source marks with "; landed <regs>" for
 exactly those registers.  A path also ends at a wait for every outstanding load (vmcnt(0): the
 kernel drains after its loop) or at the end of the program.
+
+A second check reads the compiler's own resource report of the whole build (check_resources):
+the kernels that carry a step hold their working set in registers by design (64 accumulators or
+gy values per lane, a ring of table rows), a few registers below the limit of their occupancy,
+and a change that pushes them over it does not fail, it spills to scratch memory inside the main
+loop: such a build ran the cfg3 input gradient at 3.1 ms instead of 0.9 with every test green.
 """
 from __future__ import annotations
 
@@ -126,3 +132,35 @@ def check(verbose: bool = False) -> dict[str, int]:
 
 if __name__ == "__main__":
     check(verbose=True)
+
+
+# Kernels that must not touch scratch memory at all (substrings of the mangled names), and the
+# most any kernel may use (bytes per lane: a few registers parked around a prologue are tolerated
+# in the others, a spilled main loop is hundreds of bytes).
+NO_SCRATCH = ("forward_slab_kernelIf", "forward_slab_f16_kernel", "backward_input_lane_kernel",
+              "backward_input_slab_f16_kernel", "backward_coef_stream_kernel", "backward_fused_kernel",
+              "hessian_reg_kernel", "head_kernel")
+MAX_SCRATCH_BYTES = 64
+
+
+def check_resources(report: str) -> dict[str, int]:
+    """`report`: what hipcc prints with -Rpass-analysis=kernel-resource-usage.  Returns scratch bytes
+    per lane of every kernel it lists; raises when a kernel breaks the limits above, or when the
+    report lists no kernel at all."""
+    scratch: dict[str, int] = {}
+    name = None
+    for line in report.split("\n"):
+        m = re.search(r"remark: Function Name: (\S+)", line)
+        if m:
+            name = m.group(1)
+            continue
+        m = re.search(r"remark:\s+ScratchSize \[bytes/lane\]: (\d+)", line)
+        if m and name is not None:
+            scratch[name] = int(m.group(1))
+    if not scratch:
+        raise RuntimeError("resource check: the compiler's report names no kernel")
+    bad = [f"{k}: {v} bytes of scratch per lane" for k, v in scratch.items()
+           if v > MAX_SCRATCH_BYTES or (v > 0 and any(t in k for t in NO_SCRATCH))]
+    if bad:
+        raise RuntimeError("resource check: kernels spill registers to scratch memory\n  " + "\n  ".join(bad))
+    return scratch

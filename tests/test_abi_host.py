@@ -251,3 +251,27 @@ def test_codegen_check_passes_on_the_library_sources():
     from paper_2509_07103_amd import check_codegen
     counts = check_codegen.check()
     assert len(counts) == 2 and all(n == 34 for n in counts.values()), counts
+
+
+_REPORT = """\
+a.hip:10:1: remark: Function Name: _ZN5lmkan12_GLOBAL__N_126backward_input_lane_kernelILi17EEEvNS_10GradInArgsE [-Rpass-analysis=kernel-resource-usage]
+a.hip:10:1: remark:     VGPRs: 120 [-Rpass-analysis=kernel-resource-usage]
+a.hip:10:1: remark:     ScratchSize [bytes/lane]: 0 [-Rpass-analysis=kernel-resource-usage]
+a.hip:90:1: remark: Function Name: _ZN5lmkan12_GLOBAL__N_133backward_input_slab_narrow_kernelIfLi16ELi4EEEvNS_10GradInArgsE [-Rpass-analysis=kernel-resource-usage]
+a.hip:90:1: remark:     VGPRs: 128 [-Rpass-analysis=kernel-resource-usage]
+a.hip:90:1: remark:     ScratchSize [bytes/lane]: 56 [-Rpass-analysis=kernel-resource-usage]
+"""
+
+
+def test_resource_check_accepts_a_clean_report_and_catches_spills():
+    """The build reads the compiler's resource report: a hot kernel with any scratch, any kernel
+    with a spilled loop, or a report without kernels must raise (mistakes planted in the text)."""
+    from paper_2509_07103_amd import check_codegen
+    got = check_codegen.check_resources(_REPORT)
+    assert sorted(got.values()) == [0, 56]
+    with pytest.raises(RuntimeError, match="backward_input_lane_kernel"):
+        check_codegen.check_resources(_REPORT.replace("[bytes/lane]: 0", "[bytes/lane]: 8"))
+    with pytest.raises(RuntimeError, match="narrow"):
+        check_codegen.check_resources(_REPORT.replace("[bytes/lane]: 56", "[bytes/lane]: 1132"))
+    with pytest.raises(RuntimeError, match="no kernel"):
+        check_codegen.check_resources("warning: nothing here")
