@@ -3,12 +3,16 @@
 // Same decomposition as the float32 slab kernels (lmkan_slab.hip): a workgroup owns 1024
 // samples x 64 outputs, 16 waves of 64 samples, and streams the (G+1)^2 x 64 slab of each pair
 // through LDS, double buffered.  Here a table row is 128 bytes in LDS and arrives by LDS-direct
-// loads of the stored values as they are; a lane reads its four outputs of a corner row with one
+// loads of the stored values as they are; a lane reads four outputs of a corner row with one
 // ds_read_b64, and the float16 values enter the float32 multiply-adds directly (v_fma_mix_f32
 // widens an operand on the fly), so nothing is converted in a separate instruction.  Per
-// multiply-add the kernel moves half the LDS and L2 bytes of the float32 path.  The mixed
-// multiply-add has no DPP form: the sample's four weights are copied into the lanes of its
-// group with four DPP moves per step.
+// multiply-add the kernels move half the LDS and L2 bytes of the float32 path.  Forward: lanes
+// are outputs; the mixed multiply-add has no DPP form, so the sample's four weights are copied
+// into the lanes of its group with four DPP moves per step.  Input gradient: a lane is a sample
+// and reads the rows of its own cell in a per-lane rotated order.  (The forward pass with a lane
+// per sample was measured too: 0.76 against 0.80 ms on cfg3, but slower on long batches of
+// narrow layers, 0.58 against 0.53 ms for 262144 rows of 128 -> 128, where the rotated 16-byte
+// stores of y weigh more; it is not kept.)
 #include <utility>
 
 #include "lmkan_kernels.h"
