@@ -656,9 +656,11 @@ __global__ __launch_bounds__(WAVES * 64) __attribute__((amdgpu_waves_per_eu(WAVE
 // would meet on the same four banks; lane l reads piece (j + l) mod 16 instead and holds its gy
 // pieces in that rotated order (a dot product does not care about the order of its terms): the 16
 // lanes of every group of 16 are on 16 different bank groups whatever their rows, which is the
-// best a 1 KiB read can do.
+// best a 1 KiB read can do.  Instantiated for float32 tables only: with a 16-bit table the
+// registers that stage its rows on their way to LDS push the kernel 16 registers over what four
+// waves per SIMD leave it (it then spills in the main loop); those tables keep the kernel above.
 // ---------------------------------------------------------------------------
-template <int W_CT>
+template <typename CT, int W_CT>
 __global__ __launch_bounds__(1024) __attribute__((amdgpu_waves_per_eu(4, 4))) void backward_input_lane_kernel(GradInArgs a)
 {
     extern __shared__ __align__(16) float smem[];  // two slab buffers, then 1/h of the grid
@@ -705,7 +707,7 @@ __global__ __launch_bounds__(1024) __attribute__((amdgpu_waves_per_eu(4, 4))) vo
     // columns past the end of a ragged output tile are never loaded: make them read as zero
     for (int i = threadIdx.x; i < 2 * slab_floats; i += blockDim.x) smem[i] = 0.0f;
     __syncthreads();  // zeros and s_invh in place before any slab load lands
-    SlabFill<float, WAVES> fill;
+    SlabFill<CT, WAVES> fill;
     int nx_node = 0;
     float nx_u = 0.f, nx_v = 0.f;
     auto fetch_record = [&](int k) {
@@ -1527,13 +1529,13 @@ void launch_backward_input_slab(const LayerShape &s, const GridTab &tab, const v
     constexpr int kNarrowSets = 8;
     constexpr int kWavesF32 = 16;  // float32 tables need no staging registers: 16 waves of 64 samples
     // (float32 tables on 64-output tiles: the kernel with a lane per sample)
-    const Kernel kernels[9] = {backward_input_lane_kernel<0>,
+    const Kernel kernels[9] = {backward_input_lane_kernel<float, 0>,
                                backward_input_slab_kernel<_Float16, WAVES, SETS, 2, 0>,
                                backward_input_slab_kernel<bf16_t, WAVES, SETS, 2, 0>,
                                backward_input_slab_narrow_kernel<float, 2 * WAVES, kNarrowSets / 2>,
                                backward_input_slab_narrow_kernel<_Float16, WAVES, kNarrowSets>,
                                backward_input_slab_narrow_kernel<bf16_t, WAVES, kNarrowSets>,
-                               backward_input_lane_kernel<17>,
+                               backward_input_lane_kernel<float, 17>,
                                backward_input_slab_kernel<_Float16, WAVES, SETS, 2, 17>,
                                backward_input_slab_kernel<bf16_t, WAVES, SETS, 2, 17>};
     const int which = s.dtype + (narrow ? 3 : (s.G == 16 ? 6 : 0));
