@@ -69,7 +69,9 @@ def kernel_names(w, n_out, B, storage, packed):
         gp = "backward_coef_stream_kernel"
     elif ok and w.grid <= 34:
         fwd, gx, gp = "forward_slab_narrow_kernel", "backward_input_slab_narrow_kernel", "backward_coef_stream_kernel"
-        if B >= 16 * w.grid * w.grid:
+        if storage != "f32" and packed:      # 32-output tiles of the table as it is stored
+            gx = "backward_input_lane32_kernel"
+        elif B >= 16 * w.grid * w.grid:
             both = "backward_fused_kernel"
     elif ok:
         # one 16-output slab at a time fits LDS up to G = 48

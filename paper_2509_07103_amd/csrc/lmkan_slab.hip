@@ -802,6 +802,195 @@ __global__ __launch_bounds__(1024) __attribute__((amdgpu_waves_per_eu(4, 4))) vo
 }
 
 // ---------------------------------------------------------------------------
+// Input gradient for 16-bit packed tables on grids too fine for 64-output slabs (17 <= G <= 34):
+// 32-output tiles whose slab stays in LDS as it is stored (64 bytes per row, LDS-direct fill, two
+// buffers), a lane per sample as in backward_input_lane_kernel, two samples per lane (2048 per
+// workgroup, so that a slab serves twice as many).  A row is four pieces of eight outputs; lane l
+// reads piece (j + l) mod 4 at step j and holds its gy in that order.  The stored values are
+// widened in registers (a shift or a mask for bfloat16), the differences of neighbouring corners
+// are taken per piece.
+// ---------------------------------------------------------------------------
+constexpr int kHalfTile = 32;
+constexpr int kHalfRowBytes = kHalfTile * 2;
+
+template <typename CT>
+__device__ __forceinline__ void widen8(const uint4 raw, float (&f)[8])
+{
+    const unsigned d[4] = {raw.x, raw.y, raw.z, raw.w};
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        if constexpr (is_bf16<CT>::value) {
+            f[2 * i] = __uint_as_float(d[i] << 16);
+            f[2 * i + 1] = __uint_as_float(d[i] & 0xffff0000u);
+        } else {
+            typedef _Float16 h2v __attribute__((ext_vector_type(2)));
+            const h2v h = __builtin_bit_cast(h2v, d[i]);
+            f[2 * i] = (float)h.x;
+            f[2 * i + 1] = (float)h.y;
+        }
+    }
+}
+
+typedef unsigned u4raw __attribute__((ext_vector_type(4)));
+
+__device__ __forceinline__ uint4 lds_load_u4(unsigned addr)
+{
+    const u4raw v = *reinterpret_cast<__attribute__((address_space(3))) const u4raw *>(addr);
+    return make_uint4(v.x, v.y, v.z, v.w);
+}
+
+struct CornersRaw {
+    uint4 c00, c01, c10, c11;
+};
+
+template <typename CT>
+__global__ __launch_bounds__(1024) __attribute__((amdgpu_waves_per_eu(4, 4))) void backward_input_lane32_kernel(GradInArgs a)
+{
+    extern __shared__ __align__(16) char smem32[];  // two slab buffers, then 1/h of the grid
+    constexpr int WAVES = 16, SETS = 2;
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int l3 = lane & 3;
+    int id = blockIdx.x;
+    const int total = gridDim.x;
+    if ((total & 7) == 0) id = (id & 7) * (total >> 3) + (id >> 3);
+    const int btile = id % a.n_btiles;
+    const int rest = id / a.n_btiles;
+    const int ks = rest % a.n_split;
+    const int jt = rest / a.n_split;   // 32-output tile
+
+    const int k_begin = ks * a.pairs_per_split;
+    const int k_end = min(a.K, k_begin + a.pairs_per_split);
+    const unsigned slab_bytes = (unsigned)a.nodes * kHalfRowBytes;
+    const unsigned base0 = __builtin_amdgcn_readfirstlane(lds_address(smem32));
+    const unsigned base1 = base0 + slab_bytes;
+    float *s_invh = reinterpret_cast<float *>(smem32 + ((2 * slab_bytes + 15) & ~15u));
+    for (int i = threadIdx.x; i < a.tab.G; i += blockDim.x) s_invh[i] = a.tab.inv_h[i];
+
+    // packed table: the rows of (pair, 64-output tile jt / 2) lie 128 bytes apart, this tile is
+    // their half jt & 1; a wave instruction moves 16 rows (four lanes x 16 bytes each)
+    const CT *half = static_cast<const CT *>(a.P) + (int64_t)(jt >> 1) * a.map.s_tile + (jt & 1) * kHalfTile + (lane & 3) * 8;
+    const int chunks = (a.nodes + 15) >> 4;
+    auto issue_fill = [&](unsigned lds_base, int k) {
+        const CT *src = half + (int64_t)k * a.map.s_pair;
+        for (int c = wave; c < chunks; c += WAVES) {
+            const int node = c * 16 + (lane >> 2);
+            if (node < a.nodes) lds_dma16(src + (int64_t)node * a.map.s_node, __builtin_amdgcn_readfirstlane(lds_base + c * 1024));
+        }
+    };
+
+    const int64_t n0 = (int64_t)btile * (WAVES * SETS * 64) + wave * (SETS * 64) + lane;
+    // register block j of a sample: gy of outputs jt*32 + 8 p .. + 7 with p = (j + l3) mod 4
+    float gyr[SETS][4][8];
+#pragma unroll
+    for (int s = 0; s < SETS; ++s) {
+        const int64_t n = n0 + s * 64;
+        const bool valid_s = n < a.B;
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const int col = jt * kHalfTile + ((j + l3) & 3) * 8;
+            const float *src = a.gy + (col >> 6) * a.gy_tile_stride + n * a.gy_row_stride + (col & 63);
+            float4 lo = make_float4(0.f, 0.f, 0.f, 0.f), hi = lo;
+            if (valid_s && col < a.n_out) lo = *reinterpret_cast<const float4 *>(src);
+            if (valid_s && col + 4 < a.n_out) hi = *reinterpret_cast<const float4 *>(src + 4);
+            gyr[s][j][0] = lo.x, gyr[s][j][1] = lo.y, gyr[s][j][2] = lo.z, gyr[s][j][3] = lo.w;
+            gyr[s][j][4] = hi.x, gyr[s][j][5] = hi.y, gyr[s][j][6] = hi.z, gyr[s][j][7] = hi.w;
+        }
+    }
+
+    int nx_node[SETS];
+    float nx_u[SETS], nx_v[SETS];
+    // (a sample past the end of the batch reads the records of the last one; the records of a pair
+    // start at a wave-uniform address, the sample is a 32-bit index into them)
+    unsigned n_rec[SETS];
+#pragma unroll
+    for (int s = 0; s < SETS; ++s) n_rec[s] = (unsigned)min(n0 + s * 64, a.B - 1);
+    auto fetch_records = [&](int k) {
+        const int32_t *r_node = a.rec_node + (int64_t)k * a.B;
+        const float *r_u = a.rec_u + (int64_t)k * a.B, *r_v = a.rec_v + (int64_t)k * a.B;
+#pragma unroll
+        for (int s = 0; s < SETS; ++s) {
+            nx_node[s] = r_node[n_rec[s]];
+            nx_u[s] = r_u[n_rec[s]];
+            nx_v[s] = r_v[n_rec[s]];
+        }
+    };
+    __syncthreads();  // s_invh in place
+    if (k_begin < k_end) {
+        issue_fill(base0, k_begin);
+        fetch_records(k_begin);
+    }
+
+    for (int k = k_begin; k < k_end; ++k) {
+        const unsigned cur = ((k - k_begin) & 1) ? base1 : base0;
+        const unsigned nxt = ((k - k_begin) & 1) ? base0 : base1;
+        int node[SETS];
+        float u[SETS], v[SETS];
+#pragma unroll
+        for (int s = 0; s < SETS; ++s) node[s] = nx_node[s], u[s] = nx_u[s], v[s] = nx_v[s];
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        __syncthreads();
+        if (k + 1 < k_end) {
+            issue_fill(nxt, k + 1);
+            fetch_records(k + 1);
+        }
+        // piece (j + l3) mod 4 of the row: from `first` for j < 4 - l3, one row back after the wrap
+        unsigned first[SETS];
+#pragma unroll
+        for (int s = 0; s < SETS; ++s) first[s] = cur + (unsigned)node[s] * kHalfRowBytes + (unsigned)l3 * 16;
+        float dif_a = 0.f, dif_b = 0.f, dif_c = 0.f;
+        CornersRaw ring[2];
+        auto request = [&](CornersRaw &c, int t) {
+            // (the empty statement ties the addresses to the sums so far: it keeps the reads of a
+            // piece between the multiply-adds of the pieces before it)
+            const int s = t >> 2, j = t & 3;
+            asm volatile("" : "+v"(first[s]), "+v"(dif_a), "+v"(dif_b), "+v"(dif_c));
+            const unsigned addr = (l3 + j >= 4 ? first[s] - kHalfRowBytes : first[s]) + j * 16;
+            c.c00 = lds_load_u4(addr);
+            c.c01 = lds_load_u4(addr + kHalfRowBytes);
+            c.c10 = lds_load_u4(addr + a.W * kHalfRowBytes);
+            c.c11 = lds_load_u4(addr + a.W * kHalfRowBytes + kHalfRowBytes);
+        };
+        request(ring[0], 0);
+        static_for(std::make_integer_sequence<int, SETS * 4>{}, [&](auto tc) {
+            constexpr int t = decltype(tc)::value;
+            constexpr int s = t >> 2, j = t & 3;
+            if constexpr (t + 1 < SETS * 4) request(ring[(t + 1) & 1], t + 1);
+            const CornersRaw &c = ring[t & 1];
+            float f[8];
+            float p00 = 0.f, p01 = 0.f;
+            widen8<CT>(c.c00, f);
+#pragma unroll
+            for (int i = 0; i < 8; ++i) p00 = fmaf(gyr[s][j][i], f[i], p00);
+            widen8<CT>(c.c01, f);
+#pragma unroll
+            for (int i = 0; i < 8; ++i) p01 = fmaf(gyr[s][j][i], f[i], p01);
+            widen8<CT>(c.c10, f);
+#pragma unroll
+            for (int i = 0; i < 8; ++i) dif_a = fmaf(gyr[s][j][i], f[i], dif_a);
+            widen8<CT>(c.c11, f);
+#pragma unroll
+            for (int i = 0; i < 8; ++i) dif_b = fmaf(gyr[s][j][i], f[i], dif_b);
+            dif_a -= p00;
+            dif_b -= p01;
+            dif_c += p01 - p00;
+            if constexpr (j == 3) {
+                const int i1 = node[s] / a.W;
+                const float rh1 = s_invh[i1], rh2 = s_invh[node[s] - i1 * a.W];
+                const float d1 = rh1 * (dif_a * (1.0f - v[s]) + dif_b * v[s]);
+                const float d2 = rh2 * (dif_c + u[s] * (dif_b - dif_a));
+                if (n0 + s * 64 < a.B) {
+                    float *dst = a.gx + (int64_t)(2 * k) * a.ld + n0 + s * 64;
+                    unsafeAtomicAdd(dst, d1);
+                    unsafeAtomicAdd(dst + a.ld, d2);
+                }
+                dif_a = dif_b = dif_c = 0.f;
+            }
+        });
+    }
+}
+
+// ---------------------------------------------------------------------------
 // Forward for grids whose 64-output slab does not fit LDS twice (17 <= G <= 34): the same
 // streaming with 16-output tiles.  A table row is then 64 bytes, read by four lanes, so a wave
 // takes 16 samples per step and the sample's weights reach its four lanes through the DPP
@@ -1409,6 +1598,14 @@ bool slab_backward_input_shape_ok(const LayerShape &s)
     return slab_batch_ok(s, false) && (slab_wide_fits(s) || slab_narrow_fits(s));
 }
 
+// 16-bit packed tables on the grids of the 16-output tiles: the input gradient runs on 32-output
+// tiles kept in LDS as they are stored (backward_input_lane32_kernel)
+bool slab_backward_input_keeps_table_16bit(const LayerShape &s)
+{
+    return slab_backward_input_shape_ok(s) && !slab_wide_fits(s) && s.dtype != LMKAN_F32 &&
+           s.layout == LMKAN_LAYOUT_PACKED;
+}
+
 bool slab_backward_input_applicable(const LayerShape &s, const void *coef, const float *gy, const float *gx)
 {
     if (!slab_backward_input_shape_ok(s)) return false;
@@ -1526,6 +1723,48 @@ void launch_backward_input_slab(const LayerShape &s, const GridTab &tab, const v
     constexpr int kTileB = WAVES * SETS * 64;
     typedef void (*Kernel)(GradInArgs);
     const bool narrow = !slab_wide_fits(s);
+    // 16-bit packed tables on the grids of the 16-output tiles: 32-output tiles kept as stored
+    const bool lane32 = slab_backward_input_keeps_table_16bit(s);
+    if (lane32) {
+        const Kernel k32 = s.dtype == LMKAN_F16 ? backward_input_lane32_kernel<_Float16> : backward_input_lane32_kernel<bf16_t>;
+        allow_large_lds(reinterpret_cast<const void *>(k32), 160 * 1024);
+        const size_t nrec = (size_t)s.pairs() * (size_t)s.batch;
+        GradInArgs a;
+        a.P = coef;
+        a.gy = gy;
+        a.gy_tile_stride = gy_tile_stride;
+        a.gy_row_stride = gy_row_stride;
+        a.gx = static_cast<float *>(scratch);
+        a.rec_node = static_cast<const int32_t *>(records);
+        a.rec_u = reinterpret_cast<const float *>(a.rec_node + nrec);
+        a.rec_v = a.rec_u + nrec;
+        a.map = coef_map(s);
+        a.tab = tab;
+        a.B = s.batch;
+        a.n_in = s.n_in;
+        a.n_out = s.n_out;
+        a.K = s.pairs();
+        a.W = s.G + 1;
+        a.nodes = s.nodes();
+        a.col_limit = s.out_tiles() * kTile;
+        a.packed = 1;
+        a.n_btiles = (int)((s.batch + 2047) / 2048);
+        a.n_jt = (s.n_out + kHalfTile - 1) / kHalfTile;
+        const int tiles32 = a.n_btiles * a.n_jt;
+        int split32 = 1;
+        while (tiles32 * split32 < 256 && a.K / (split32 * 2) >= 4) split32 *= 2;
+        a.n_split = split32;
+        a.pairs_per_split = (a.K + split32 - 1) / split32;
+        a.ld = scratch_row_stride(s.batch, kScratchPlain);
+        launch_fill_zero(a.gx, (size_t)a.ld * s.n_in, stream);
+        const size_t lds = (((size_t)2 * s.nodes() * kHalfRowBytes + 15) & ~(size_t)15) + LMKAN_MAX_GRID * sizeof(float);
+        {
+            KernelTiming timing(stream, kTimeGradInput);
+            k32<<<tiles32 * split32, 1024, lds, stream>>>(a);
+        }
+        launch_input_gradient_out(a.gx, gx, s, conv, stream, kScratchPlain);
+        return;
+    }
     constexpr int kNarrowSets = 8;
     constexpr int kWavesF32 = 16;  // float32 tables need no staging registers: 16 waves of 64 samples
     // (float32 tables on 64-output tiles: the kernel with a lane per sample)
