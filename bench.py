@@ -70,7 +70,7 @@ def kernel_names(w, n_out, B, storage, packed):
     elif ok and w.grid <= 34:
         fwd, gx, gp = "forward_slab_narrow_kernel", "backward_input_slab_narrow_kernel", "backward_coef_stream_kernel"
         if storage != "f32" and packed:      # 32-output tiles of the table as it is stored
-            gx = "backward_input_lane32_kernel"
+            fwd, gx = "forward_lane32_kernel", "backward_input_lane32_kernel"
         elif B >= 16 * w.grid * w.grid:
             both = "backward_fused_kernel"
     elif ok:

@@ -843,6 +843,144 @@ struct CornersRaw {
     uint4 c00, c01, c10, c11;
 };
 
+// Forward on the same tiles: the 32 outputs of a sample's tile in registers (two samples per lane),
+// the lane's own four weights, outputs kept and stored in the rotated order of the pieces.
+template <typename CT>
+__global__ __launch_bounds__(1024) __attribute__((amdgpu_waves_per_eu(4, 4))) void forward_lane32_kernel(SlabArgs a)
+{
+    extern __shared__ __align__(16) char smem32[];  // two slab buffers
+    constexpr int WAVES = 16, SETS = 2;
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int l3 = lane & 3;
+    int id = blockIdx.x;
+    const int total = gridDim.x;
+    if ((total & 7) == 0) id = (id & 7) * (total >> 3) + (id >> 3);
+    const int btile = id % a.n_btiles;
+    const int rest = id / a.n_btiles;
+    const int ks = rest % a.n_split;
+    const int jt = rest / a.n_split;   // 32-output tile
+
+    const int k_begin = ks * a.pairs_per_split;
+    const int k_end = min(a.K, k_begin + a.pairs_per_split);
+    const unsigned slab_bytes = (unsigned)a.nodes * kHalfRowBytes;
+    const unsigned base0 = __builtin_amdgcn_readfirstlane(lds_address(smem32));
+    const unsigned base1 = base0 + slab_bytes;
+
+    // packed table: the rows of (pair, 64-output tile jt / 2) lie 128 bytes apart, this tile is
+    // their half jt & 1; a wave instruction moves 16 rows (four lanes x 16 bytes each)
+    const CT *half = static_cast<const CT *>(a.P) + (int64_t)(jt >> 1) * a.map.s_tile + (jt & 1) * kHalfTile + (lane & 3) * 8;
+    const int chunks = (a.nodes + 15) >> 4;
+    auto issue_fill = [&](unsigned lds_base, int k) {
+        const CT *src = half + (int64_t)k * a.map.s_pair;
+        for (int c = wave; c < chunks; c += WAVES) {
+            const int node = c * 16 + (lane >> 2);
+            if (node < a.nodes) lds_dma16(src + (int64_t)node * a.map.s_node, __builtin_amdgcn_readfirstlane(lds_base + c * 1024));
+        }
+    };
+
+    const int64_t n0 = (int64_t)btile * (WAVES * SETS * 64) + wave * (SETS * 64) + lane;
+    // register block j of a sample: outputs jt*32 + 8 p .. + 7 with p = (j + l3) mod 4
+    float acc[SETS][4][8];
+#pragma unroll
+    for (int s = 0; s < SETS; ++s)
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+#pragma unroll
+            for (int i = 0; i < 8; ++i) acc[s][j][i] = 0.0f;
+
+    // (a sample past the end of the batch reads the records of the last one; the records of a pair
+    // start at a wave-uniform address, the sample is a 32-bit index into them)
+    unsigned n_rec[SETS];
+#pragma unroll
+    for (int s = 0; s < SETS; ++s) n_rec[s] = (unsigned)min(n0 + s * 64, a.B - 1);
+    int nx_node[SETS];
+    float nx_u[SETS], nx_v[SETS];
+    auto fetch_records = [&](int k) {
+        const int32_t *r_node = a.rec_node + (int64_t)k * a.B;
+        const float *r_u = a.rec_u + (int64_t)k * a.B, *r_v = a.rec_v + (int64_t)k * a.B;
+#pragma unroll
+        for (int s = 0; s < SETS; ++s) {
+            nx_node[s] = r_node[n_rec[s]];
+            nx_u[s] = r_u[n_rec[s]];
+            nx_v[s] = r_v[n_rec[s]];
+        }
+    };
+    if (k_begin < k_end) {
+        issue_fill(base0, k_begin);
+        fetch_records(k_begin);
+    }
+
+    for (int k = k_begin; k < k_end; ++k) {
+        const unsigned cur = ((k - k_begin) & 1) ? base1 : base0;
+        const unsigned nxt = ((k - k_begin) & 1) ? base0 : base1;
+        unsigned first[SETS];
+        float w00[SETS], w10[SETS], w01[SETS], w11[SETS];
+#pragma unroll
+        for (int s = 0; s < SETS; ++s) {
+            const float u = nx_u[s], v = nx_v[s];
+            const float a_lo = 1.0f - u, b_lo = 1.0f - v;
+            w00[s] = a_lo * b_lo, w10[s] = u * b_lo, w01[s] = a_lo * v, w11[s] = u * v;
+            // piece (j + l3) mod 4 of the row: from `first` for j < 4 - l3, one row back after the wrap
+            first[s] = cur + (unsigned)nx_node[s] * kHalfRowBytes + (unsigned)l3 * 16;
+        }
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        __syncthreads();
+        if (k + 1 < k_end) {
+            issue_fill(nxt, k + 1);
+            fetch_records(k + 1);
+        }
+        CornersRaw ring[2];
+        auto request = [&](CornersRaw &c, int t, float &tie) {
+            // (the empty statement ties the addresses to a sum of the piece before last: it keeps the
+            // reads of a piece between the multiply-adds of the pieces before it)
+            const int s = t >> 2, j = t & 3;
+            asm volatile("" : "+v"(first[s]), "+v"(tie));
+            const unsigned addr = (l3 + j >= 4 ? first[s] - kHalfRowBytes : first[s]) + j * 16;
+            c.c00 = lds_load_u4(addr);
+            c.c01 = lds_load_u4(addr + kHalfRowBytes);
+            c.c10 = lds_load_u4(addr + a.W * kHalfRowBytes);
+            c.c11 = lds_load_u4(addr + a.W * kHalfRowBytes + kHalfRowBytes);
+        };
+        request(ring[0], 0, acc[SETS - 1][3][7]);
+        static_for(std::make_integer_sequence<int, SETS * 4>{}, [&](auto tc) {
+            constexpr int t = decltype(tc)::value;
+            constexpr int s = t >> 2, j = t & 3;
+            constexpr int tp = t > 0 ? t - 1 : SETS * 4 - 1;   // the piece before this one
+            if constexpr (t + 1 < SETS * 4) request(ring[(t + 1) & 1], t + 1, acc[tp >> 2][tp & 3][7]);
+            const CornersRaw &c = ring[t & 1];
+            float f[8];
+            widen8<CT>(c.c00, f);
+#pragma unroll
+            for (int i = 0; i < 8; ++i) acc[s][j][i] = fmaf(w00[s], f[i], acc[s][j][i]);
+            widen8<CT>(c.c10, f);
+#pragma unroll
+            for (int i = 0; i < 8; ++i) acc[s][j][i] = fmaf(w10[s], f[i], acc[s][j][i]);
+            widen8<CT>(c.c01, f);
+#pragma unroll
+            for (int i = 0; i < 8; ++i) acc[s][j][i] = fmaf(w01[s], f[i], acc[s][j][i]);
+            widen8<CT>(c.c11, f);
+#pragma unroll
+            for (int i = 0; i < 8; ++i) acc[s][j][i] = fmaf(w11[s], f[i], acc[s][j][i]);
+        });
+    }
+
+    bool atomic;
+    float *ybase = forward_out_base(a, ks, atomic);
+#pragma unroll
+    for (int s = 0; s < SETS; ++s) {
+        const int64_t n = n0 + s * 64;
+        if (n < a.B) {
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                const int col = jt * kHalfTile + ((j + l3) & 3) * 8;
+                if (col < a.n_out) store_outputs(ybase + n * a.n_out + col, acc[s][j], a.n_out, col, atomic);
+                if (col + 4 < a.n_out) store_outputs(ybase + n * a.n_out + col + 4, acc[s][j] + 4, a.n_out, col + 4, atomic);
+            }
+        }
+    }
+}
+
 template <typename CT>
 __global__ __launch_bounds__(1024) __attribute__((amdgpu_waves_per_eu(4, 4))) void backward_input_lane32_kernel(GradInArgs a)
 {
@@ -1431,13 +1569,22 @@ bool slab_forward_shape_ok(const LayerShape &s)
 }
 bool slab_tile_is_wide(const LayerShape &s) { return slab_wide_fits(s); }
 
-// Samples per forward workgroup: 1024 with 64-output tiles, 4096 with 16-output tiles.
+// 16-bit packed tables on the grids that stream two 16-output slabs: 32-output tiles kept in LDS as
+// they are stored (forward_lane32_kernel)
+bool slab_forward_keeps_table_16bit(const LayerShape &s)
+{
+    return slab_batch_ok(s, true) && slab_narrow_fits(s) && s.dtype != LMKAN_F32 && s.layout == LMKAN_LAYOUT_PACKED;
+}
+
+// Samples per forward workgroup: 1024 with 64-output tiles, 4096 with 16-output tiles, 2048 with
+// 32-output tiles.
 int slab_forward_split(const LayerShape &s)
 {
     if (!slab_forward_shape_ok(s)) return 1;
     const bool wide = slab_wide_fits(s);
-    const int64_t tile_b = wide ? 1024 : 4096;
-    const int64_t n_jt = wide ? s.out_tiles() : (s.n_out + 15) / 16;
+    const bool half = slab_forward_keeps_table_16bit(s);
+    const int64_t tile_b = wide ? 1024 : half ? 2048 : 4096;
+    const int64_t n_jt = wide ? s.out_tiles() : half ? (s.n_out + 31) / 32 : (s.n_out + 15) / 16;
     return pair_split_count((int)(((s.batch + tile_b - 1) / tile_b) * n_jt), s.pairs());
 }
 
@@ -1496,6 +1643,38 @@ static void launch_forward_slab_narrow(const LayerShape &s, const void *coef, fl
     constexpr int WAVES = 8, SETS = 8;
     constexpr int kTileB = WAVES * SETS * 64;
     typedef void (*Kernel)(SlabArgs);
+    if (slab_forward_keeps_table_16bit(s)) {
+        const Kernel k32 = s.dtype == LMKAN_F16 ? forward_lane32_kernel<_Float16> : forward_lane32_kernel<bf16_t>;
+        allow_large_lds(reinterpret_cast<const void *>(k32), 160 * 1024);
+        const size_t nrec = (size_t)s.pairs() * (size_t)s.batch;
+        SlabArgs a;
+        a.P = coef;
+        a.y = y;
+        a.rec_node = static_cast<const int32_t *>(records);
+        a.rec_u = reinterpret_cast<const float *>(a.rec_node + nrec);
+        a.rec_v = a.rec_u + nrec;
+        a.map = coef_map(s);
+        a.B = s.batch;
+        a.n_out = s.n_out;
+        a.K = s.pairs();
+        a.W = s.G + 1;
+        a.nodes = s.nodes();
+        a.col_limit = s.out_tiles() * kTile;
+        a.packed = 1;
+        a.n_btiles = (int)((s.batch + 2047) / 2048);
+        a.n_jt = (s.n_out + kHalfTile - 1) / kHalfTile;
+        const int tiles32 = a.n_btiles * a.n_jt;
+        const int split32 = slab_forward_split(s);   // what the workspace was sized for
+        a.n_split = split32;
+        a.pairs_per_split = (a.K + split32 - 1) / split32;
+        finish_split_setup(a, s, y, partials, stream);
+        {
+            KernelTiming timing(stream, kTimeForward);
+            k32<<<tiles32 * split32, 1024, ((size_t)2 * s.nodes() * kHalfRowBytes + 15) & ~(size_t)15, stream>>>(a);
+        }
+        if (a.y_part) launch_sum_partials(y, a.y_part, split32 - 1, (int64_t)s.batch * s.n_out, stream);
+        return;
+    }
     // a float32 table needs no staging registers: 16 waves of 256 samples instead of 8 of 512
     const bool single = slab_narrow_single_fits(s);
     const Kernel kernels[6] = {forward_slab_narrow_kernel<float, 2 * WAVES, SETS / 2>,
