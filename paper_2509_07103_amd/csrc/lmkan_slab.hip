@@ -742,18 +742,19 @@ __global__ __launch_bounds__(1024) __attribute__((amdgpu_waves_per_eu(4, 4))) vo
         unsigned first = lds_address(slab) + (unsigned)node * kRowBytes + (unsigned)l15 * 16;
         // The derivative is made of differences between neighbouring corners, and on a smooth table
         // two dot products over all 64 outputs would agree in most of their digits before they are
-        // subtracted.  So the products with P00 and P01 are only summed over the four outputs of a
-        // piece and taken off at once: dif_a = sum gy (P10 - P00), dif_b = sum gy (P11 - P01),
-        // dif_c = sum gy (P01 - P00); the fourth difference is P11 - P10 = (P11 - P01) + (P01 - P00)
-        // - (P10 - P00), which turns d/dx2 into (dif_c + u (dif_b - dif_a)) / h2.
-        float dif_a = 0.f, dif_b = 0.f, dif_c = 0.f;
+        // subtracted.  So the four products are summed over the four outputs of a piece only and
+        // their differences taken at once: dif_a = sum gy (P10 - P00), dif_b = sum gy (P11 - P01),
+        // dif_c = sum gy (P01 - P00), dif_d = sum gy (P11 - P10).  (dif_d = dif_b + dif_c - dif_a
+        // would save a register and four instructions per piece, but far outside the grid, where the
+        // local coordinates are large, it costs accuracy: one more pair of roundings multiplied by u.)
+        float dif_a = 0.f, dif_b = 0.f, dif_c = 0.f, dif_d = 0.f;
         // the rows of piece j + 1 are requested before the multiply-adds of piece j are issued
         Corners ring[2];
         auto request = [&](Corners &c, int j) {
             // (the empty statement ties the addresses to the sums so far, so that the compiler keeps
             // that order: left to itself it issues all 64 reads of a pair first and spills them, or
             // walks one corner at a time with a single read in flight)
-            asm volatile("" : "+v"(first), "+v"(dif_a), "+v"(dif_b), "+v"(dif_c));
+            asm volatile("" : "+v"(first), "+v"(dif_a), "+v"(dif_b), "+v"(dif_c), "+v"(dif_d));
             const unsigned addr = (l15 + j >= 16 ? first - kRowBytes : first) + j * 16;
             c.c00 = lds_load4(addr);
             c.c01 = lds_load4(addr + kRowBytes);
@@ -766,24 +767,23 @@ __global__ __launch_bounds__(1024) __attribute__((amdgpu_waves_per_eu(4, 4))) vo
             if constexpr (j + 1 < 16) request(ring[(j + 1) & 1], j + 1);
             const Corners &c = ring[j & 1];
             const float4 g = gyr[j];
-            float p00 = g.x * c.c00.x, p01 = g.x * c.c01.x;
-            dif_a = fmaf(g.x, c.c10.x, dif_a);
-            dif_b = fmaf(g.x, c.c11.x, dif_b);
+            float p00 = g.x * c.c00.x, p01 = g.x * c.c01.x, p10 = g.x * c.c10.x, p11 = g.x * c.c11.x;
             p00 = fmaf(g.y, c.c00.y, p00);
             p01 = fmaf(g.y, c.c01.y, p01);
-            dif_a = fmaf(g.y, c.c10.y, dif_a);
-            dif_b = fmaf(g.y, c.c11.y, dif_b);
+            p10 = fmaf(g.y, c.c10.y, p10);
+            p11 = fmaf(g.y, c.c11.y, p11);
             p00 = fmaf(g.z, c.c00.z, p00);
             p01 = fmaf(g.z, c.c01.z, p01);
-            dif_a = fmaf(g.z, c.c10.z, dif_a);
-            dif_b = fmaf(g.z, c.c11.z, dif_b);
+            p10 = fmaf(g.z, c.c10.z, p10);
+            p11 = fmaf(g.z, c.c11.z, p11);
             p00 = fmaf(g.w, c.c00.w, p00);
             p01 = fmaf(g.w, c.c01.w, p01);
-            dif_a = fmaf(g.w, c.c10.w, dif_a);
-            dif_b = fmaf(g.w, c.c11.w, dif_b);
-            dif_a -= p00;
-            dif_b -= p01;
+            p10 = fmaf(g.w, c.c10.w, p10);
+            p11 = fmaf(g.w, c.c11.w, p11);
+            dif_a += p10 - p00;
+            dif_b += p11 - p01;
             dif_c += p01 - p00;
+            dif_d += p11 - p10;
             if constexpr (j == 7) {
                 if (k + 1 < k_end) {
                     fill.template commit<0>(sa, slab_next, wave, lane);
@@ -793,7 +793,7 @@ __global__ __launch_bounds__(1024) __attribute__((amdgpu_waves_per_eu(4, 4))) vo
         });
         if (k + 1 < k_end) fill.template commit<1>(sa, slab_next, wave, lane);
         const float d1 = rh1 * (dif_a * (1.0f - v) + dif_b * v);
-        const float d2 = rh2 * (dif_c + u * (dif_b - dif_a));
+        const float d2 = rh2 * (dif_c * (1.0f - u) + dif_d * u);
         if (valid) {
             unsafeAtomicAdd(gx_lane + (int64_t)(2 * k) * a.ld, d1);
             unsafeAtomicAdd(gx_lane + (int64_t)(2 * k + 1) * a.ld, d2);
@@ -1076,13 +1076,13 @@ __global__ __launch_bounds__(1024) __attribute__((amdgpu_waves_per_eu(4, 4))) vo
         unsigned first[SETS];
 #pragma unroll
         for (int s = 0; s < SETS; ++s) first[s] = cur + (unsigned)node[s] * kHalfRowBytes + (unsigned)l3 * 16;
-        float dif_a = 0.f, dif_b = 0.f, dif_c = 0.f;
+        float dif_a = 0.f, dif_b = 0.f, dif_c = 0.f, dif_d = 0.f;   // as in backward_input_lane_kernel
         CornersRaw ring[2];
         auto request = [&](CornersRaw &c, int t) {
             // (the empty statement ties the addresses to the sums so far: it keeps the reads of a
             // piece between the multiply-adds of the pieces before it)
             const int s = t >> 2, j = t & 3;
-            asm volatile("" : "+v"(first[s]), "+v"(dif_a), "+v"(dif_b), "+v"(dif_c));
+            asm volatile("" : "+v"(first[s]), "+v"(dif_a), "+v"(dif_b), "+v"(dif_c), "+v"(dif_d));
             const unsigned addr = (l3 + j >= 4 ? first[s] - kHalfRowBytes : first[s]) + j * 16;
             c.c00 = lds_load_u4(addr);
             c.c01 = lds_load_u4(addr + kHalfRowBytes);
@@ -1096,7 +1096,7 @@ __global__ __launch_bounds__(1024) __attribute__((amdgpu_waves_per_eu(4, 4))) vo
             if constexpr (t + 1 < SETS * 4) request(ring[(t + 1) & 1], t + 1);
             const CornersRaw &c = ring[t & 1];
             float f[8];
-            float p00 = 0.f, p01 = 0.f;
+            float p00 = 0.f, p01 = 0.f, p10 = 0.f, p11 = 0.f;
             widen8<CT>(c.c00, f);
 #pragma unroll
             for (int i = 0; i < 8; ++i) p00 = fmaf(gyr[s][j][i], f[i], p00);
@@ -1105,24 +1105,25 @@ __global__ __launch_bounds__(1024) __attribute__((amdgpu_waves_per_eu(4, 4))) vo
             for (int i = 0; i < 8; ++i) p01 = fmaf(gyr[s][j][i], f[i], p01);
             widen8<CT>(c.c10, f);
 #pragma unroll
-            for (int i = 0; i < 8; ++i) dif_a = fmaf(gyr[s][j][i], f[i], dif_a);
+            for (int i = 0; i < 8; ++i) p10 = fmaf(gyr[s][j][i], f[i], p10);
             widen8<CT>(c.c11, f);
 #pragma unroll
-            for (int i = 0; i < 8; ++i) dif_b = fmaf(gyr[s][j][i], f[i], dif_b);
-            dif_a -= p00;
-            dif_b -= p01;
+            for (int i = 0; i < 8; ++i) p11 = fmaf(gyr[s][j][i], f[i], p11);
+            dif_a += p10 - p00;
+            dif_b += p11 - p01;
             dif_c += p01 - p00;
+            dif_d += p11 - p10;
             if constexpr (j == 3) {
                 const int i1 = node[s] / a.W;
                 const float rh1 = s_invh[i1], rh2 = s_invh[node[s] - i1 * a.W];
                 const float d1 = rh1 * (dif_a * (1.0f - v[s]) + dif_b * v[s]);
-                const float d2 = rh2 * (dif_c + u[s] * (dif_b - dif_a));
+                const float d2 = rh2 * (dif_c * (1.0f - u[s]) + dif_d * u[s]);
                 if (n0 + s * 64 < a.B) {
                     float *dst = a.gx + (int64_t)(2 * k) * a.ld + n0 + s * 64;
                     unsafeAtomicAdd(dst, d1);
                     unsafeAtomicAdd(dst + a.ld, d2);
                 }
-                dif_a = dif_b = dif_c = 0.f;
+                dif_a = dif_b = dif_c = dif_d = 0.f;
             }
         });
     }

@@ -279,14 +279,15 @@ __global__ __launch_bounds__(kWaves * 64) __attribute__((amdgpu_waves_per_eu(4, 
         }
         // piece (j + l15) mod 16 of the row: from `first` for j < 16 - l15, one row back after the wrap
         unsigned first = cur + (unsigned)node * kRowBytesH + (unsigned)l15 * 8;
-        // dif_a = sum gy (P10 - P00), dif_b = sum gy (P11 - P01), dif_c = sum gy (P01 - P00), the
-        // products with P00 and P01 summed over the four outputs of a piece only and taken off at once
-        float dif_a = 0.f, dif_b = 0.f, dif_c = 0.f;
+        // dif_a = sum gy (P10 - P00), dif_b = sum gy (P11 - P01), dif_c = sum gy (P01 - P00),
+        // dif_d = sum gy (P11 - P10): the four products summed over the four outputs of a piece
+        // only, their differences taken at once
+        float dif_a = 0.f, dif_b = 0.f, dif_c = 0.f, dif_d = 0.f;
         CornersH ring[kAheadH + 1];
         auto request = [&](CornersH &c, int j) {
             // (the empty statement ties the addresses to the sums so far: it keeps the reads of a
             // piece between the multiply-adds of the pieces before it)
-            asm volatile("" : "+v"(first), "+v"(dif_a), "+v"(dif_b), "+v"(dif_c));
+            asm volatile("" : "+v"(first), "+v"(dif_a), "+v"(dif_b), "+v"(dif_c), "+v"(dif_d));
             const unsigned addr = (l15 + j >= 16 ? first - kRowBytesH : first) + j * 8;
             c.c00 = lds_load_h4(addr);
             c.c01 = lds_load_h4(addr + kRowBytesH);
@@ -300,12 +301,14 @@ __global__ __launch_bounds__(kWaves * 64) __attribute__((amdgpu_waves_per_eu(4, 
             if constexpr (j + kAheadH < 16) request(ring[(j + kAheadH) % (kAheadH + 1)], j + kAheadH);
             const CornersH &c = ring[j % (kAheadH + 1)];
             const float p00 = fma4_h(gyr[j], c.c00, 0.0f), p01 = fma4_h(gyr[j], c.c01, 0.0f);
-            dif_a = fma4_h(gyr[j], c.c10, dif_a) - p00;
-            dif_b = fma4_h(gyr[j], c.c11, dif_b) - p01;
+            const float p10 = fma4_h(gyr[j], c.c10, 0.0f), p11 = fma4_h(gyr[j], c.c11, 0.0f);
+            dif_a += p10 - p00;
+            dif_b += p11 - p01;
             dif_c += p01 - p00;
+            dif_d += p11 - p10;
         });
         const float d1 = rh1 * (dif_a * (1.0f - v) + dif_b * v);
-        const float d2 = rh2 * (dif_c + u * (dif_b - dif_a));
+        const float d2 = rh2 * (dif_c * (1.0f - u) + dif_d * u);
         if (valid) {
             unsafeAtomicAdd(gx_lane + (int64_t)(2 * k) * a.ld, d1);
             unsafeAtomicAdd(gx_lane + (int64_t)(2 * k + 1) * a.ld, d2);

@@ -89,7 +89,17 @@ def test_random_shape_matches_oracle(dev, oracle, draw):
             return rowwise_rel_err(got, want)
         return np.abs(got.astype(np.float64) - want).max() / np.abs(want).max()
 
-    assert rel_err(y.cpu().numpy(), oracle.forward(xh, bits(Ps), G, dtype=dt)) <= TOL_F32
+    want_y = oracle.forward(xh, bits(Ps), G, dtype=dt)
+    if B * n_out >= 8:
+        assert rel_err(y.cpu().numpy(), want_y) <= TOL_F32
+    else:
+        # a handful of outputs, each a sum over the pairs that may cancel to nothing (one row of one
+        # output is a single number): the scale is what float32 rounding acts on, the sum of the
+        # terms' magnitudes, which the oracle gives with |coefficients| (the weights are positive
+        # inside the grid; beyond the ghost points the bound is what the largest output needs anyway)
+        Pabs = wl.store(P.abs(), storage).contiguous()
+        scale = max(np.abs(oracle.forward(xh, bits(Pabs), G, dtype=dt)).max(), np.abs(want_y).max())
+        assert np.abs(y.cpu().numpy() - want_y).max() <= TOL_F32 * scale
     if grads != "coef":
         want = oracle.backward_input(xh, bits(Ps), gyh, G, dtype=dt)
         assert rel_err(gx.cpu().numpy(), want) <= TOL_F32
