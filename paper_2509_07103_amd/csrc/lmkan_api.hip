@@ -342,12 +342,13 @@ lmkan_status backward_impl(const lmkan_desc *desc, int64_t batch, const float *x
     // gradient alone.  The walk over the cell-sorted samples yields both gradients from one pass
     // over gy: it takes the grids too fine for any slab, and the 16-output slab range when both
     // gradients are wanted and cells hold enough samples for its chunks of four to fill (16 per
-    // cell on average), except for 16-bit packed tables, whose slab kernel is quicker than its
-    // share of the walk.  Whatever neither takes goes to the generic kernel.
+    // cell on average), except where the table is packed and two 32-output slabs fit LDS: that slab
+    // kernel is as quick as its share of the walk, or quicker.  Whatever neither takes goes to the
+    // generic kernel.
     const bool slab_ok = grad_x_dev && !small && slab_backward_input_applicable(s, coef_dev, grad_y_dev, grad_x_dev);
     const bool dense_cells = s.batch >= (int64_t)16 * s.G * s.G;
     const bool fused_pays = !slab_ok || (!slab_tile_is_wide(s) && grad_coef_dev && dense_cells &&
-                                         !slab_backward_input_keeps_table_16bit(s));
+                                         !slab_backward_input_takes_half_tiles(s));
     const bool enough_work = s.batch >= 256 || (int64_t)s.pairs() * s.n_out >= 8192;  // as for the slab kernels
     const bool gx_fused = grad_x_dev && !small && enough_work && fused_pays &&
                           fused_backward_applicable(s, coef_dev, grad_y_dev, grad_coef_dev);

@@ -79,7 +79,7 @@ void launch_forward_slab(const LayerShape &s, const void *coef, float *y, const 
                          hipStream_t stream);
 
 bool slab_backward_input_shape_ok(const LayerShape &s);
-bool slab_backward_input_keeps_table_16bit(const LayerShape &s);  // 32-output tiles of a 16-bit packed table
+bool slab_backward_input_takes_half_tiles(const LayerShape &s);  // 32-output tiles of a packed table kept as stored
 bool slab_backward_input_applicable(const LayerShape &s, const void *coef, const float *gy, const float *gx);
 size_t slab_backward_input_scratch_bytes(const LayerShape &s);
 // gy as [batch][n_out] (gy_tile_stride = 64, gy_row_stride = n_out, in floats), or its tile-by-tile
