@@ -70,8 +70,10 @@ def kernel_names(w, n_out, B, storage, packed):
     elif ok and w.grid <= 34:
         fwd, gx, gp = "forward_slab_narrow_kernel", "backward_input_slab_narrow_kernel", "backward_coef_stream_kernel"
         # 32-output tiles of a packed table as it is stored, where two such slabs fit LDS
-        if packed and 2 * (w.grid + 1) ** 2 * 32 * (4 if storage == "f32" else 2) + 256 <= 160 * 1024:
+        if packed and storage != "f32":
             fwd, gx = "forward_lane32_kernel", "backward_input_lane32_kernel"
+        elif packed and 2 * (w.grid + 1) ** 2 * 128 + 256 <= 160 * 1024:
+            gx = "backward_input_lane32_f32_kernel"
         elif B >= 16 * w.grid * w.grid:
             both = "backward_fused_kernel"
     elif ok:

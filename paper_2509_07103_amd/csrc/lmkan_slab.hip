@@ -802,33 +802,24 @@ __global__ __launch_bounds__(1024) __attribute__((amdgpu_waves_per_eu(4, 4))) vo
 }
 
 // ---------------------------------------------------------------------------
-// Packed tables on grids too fine for 64-output slabs (16-bit: 17 <= G <= 34, float32: 17 <= G <=
-// 24): 32-output tiles whose slab stays in LDS as it is stored (64 or 128 bytes per row, LDS-direct
-// fill, two buffers), a lane per sample as in backward_input_lane_kernel, two samples per lane
-// (2048 per workgroup, so that a slab serves twice as many).  A row is 16-byte pieces of eight
-// (float32: four) outputs; lane l reads piece (j + l) mod pieces at step j and holds its gy or its
-// outputs in that order.  16-bit values are widened in registers (a shift or a mask for
-// bfloat16), the differences of neighbouring corners are taken per piece.
+// Input gradient for 16-bit packed tables on grids too fine for 64-output slabs (17 <= G <= 34):
+// 32-output tiles whose slab stays in LDS as it is stored (64 bytes per row, LDS-direct fill, two
+// buffers), a lane per sample as in backward_input_lane_kernel, two samples per lane (2048 per
+// workgroup, so that a slab serves twice as many).  A row is four pieces of eight outputs; lane l
+// reads piece (j + l) mod 4 at step j and holds its gy in that order.  The stored values are
+// widened in registers (a shift or a mask for bfloat16), the differences of neighbouring corners
+// are taken per piece.
 // ---------------------------------------------------------------------------
 constexpr int kHalfTile = 32;
+constexpr int kHalfRowBytes = kHalfTile * 2;
 
 template <typename CT>
-struct HalfRow {
-    static constexpr int kBytes = kHalfTile * (int)sizeof(CT);   // a row of the slab
-    static constexpr int kPieces = kBytes / 16;                  // 16-byte pieces per row
-    static constexpr int kPer = 16 / (int)sizeof(CT);            // outputs per piece
-    static constexpr int kRowsPerFill = 64 / kPieces;            // rows one wave instruction moves
-};
-
-template <typename CT>
-__device__ __forceinline__ void widen_piece(const uint4 raw, float (&f)[16 / sizeof(CT)])
+__device__ __forceinline__ void widen8(const uint4 raw, float (&f)[8])
 {
     const unsigned d[4] = {raw.x, raw.y, raw.z, raw.w};
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
-        if constexpr (sizeof(CT) == 4) {
-            f[i] = __uint_as_float(d[i]);
-        } else if constexpr (is_bf16<CT>::value) {
+        if constexpr (is_bf16<CT>::value) {
             f[2 * i] = __uint_as_float(d[i] << 16);
             f[2 * i + 1] = __uint_as_float(d[i] & 0xffff0000u);
         } else {
@@ -858,11 +849,10 @@ template <typename CT>
 __global__ __launch_bounds__(1024) __attribute__((amdgpu_waves_per_eu(4, 4))) void forward_lane32_kernel(SlabArgs a)
 {
     extern __shared__ __align__(16) char smem32[];  // two slab buffers
-    typedef HalfRow<CT> Row;
-    constexpr int WAVES = 16, SETS = 2, PIECES = Row::kPieces, PER = Row::kPer, STEPS = SETS * PIECES;
+    constexpr int WAVES = 16, SETS = 2;
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-    const int lp = lane & (PIECES - 1);
+    const int l3 = lane & 3;
     int id = blockIdx.x;
     const int total = gridDim.x;
     if ((total & 7) == 0) id = (id & 7) * (total >> 3) + (id >> 3);
@@ -873,31 +863,31 @@ __global__ __launch_bounds__(1024) __attribute__((amdgpu_waves_per_eu(4, 4))) vo
 
     const int k_begin = ks * a.pairs_per_split;
     const int k_end = min(a.K, k_begin + a.pairs_per_split);
-    const unsigned slab_bytes = (unsigned)a.nodes * Row::kBytes;
+    const unsigned slab_bytes = (unsigned)a.nodes * kHalfRowBytes;
     const unsigned base0 = __builtin_amdgcn_readfirstlane(lds_address(smem32));
     const unsigned base1 = base0 + slab_bytes;
 
-    // packed table: the rows of (pair, 64-output tile jt / 2) lie 64 elements apart, this tile is
-    // their half jt & 1; a wave instruction moves 1024 bytes (PIECES lanes x 16 bytes per row)
-    const CT *half = static_cast<const CT *>(a.P) + (int64_t)(jt >> 1) * a.map.s_tile + (jt & 1) * kHalfTile + lp * PER;
-    const int chunks = (a.nodes + Row::kRowsPerFill - 1) / Row::kRowsPerFill;
+    // packed table: the rows of (pair, 64-output tile jt / 2) lie 128 bytes apart, this tile is
+    // their half jt & 1; a wave instruction moves 16 rows (four lanes x 16 bytes each)
+    const CT *half = static_cast<const CT *>(a.P) + (int64_t)(jt >> 1) * a.map.s_tile + (jt & 1) * kHalfTile + (lane & 3) * 8;
+    const int chunks = (a.nodes + 15) >> 4;
     auto issue_fill = [&](unsigned lds_base, int k) {
         const CT *src = half + (int64_t)k * a.map.s_pair;
         for (int c = wave; c < chunks; c += WAVES) {
-            const int node = c * Row::kRowsPerFill + lane / PIECES;
+            const int node = c * 16 + (lane >> 2);
             if (node < a.nodes) lds_dma16(src + (int64_t)node * a.map.s_node, __builtin_amdgcn_readfirstlane(lds_base + c * 1024));
         }
     };
 
     const int64_t n0 = (int64_t)btile * (WAVES * SETS * 64) + wave * (SETS * 64) + lane;
-    // register block j of a sample: outputs jt*32 + PER p .. + PER - 1 with p = (j + lp) mod PIECES
-    float acc[SETS][PIECES][PER];
+    // register block j of a sample: outputs jt*32 + 8 p .. + 7 with p = (j + l3) mod 4
+    float acc[SETS][4][8];
 #pragma unroll
     for (int s = 0; s < SETS; ++s)
 #pragma unroll
-        for (int j = 0; j < PIECES; ++j)
+        for (int j = 0; j < 4; ++j)
 #pragma unroll
-            for (int i = 0; i < PER; ++i) acc[s][j][i] = 0.0f;
+            for (int i = 0; i < 8; ++i) acc[s][j][i] = 0.0f;
 
     // (a sample past the end of the batch reads the records of the last one; the records of a pair
     // start at a wave-uniform address, the sample is a 32-bit index into them)
@@ -931,9 +921,8 @@ __global__ __launch_bounds__(1024) __attribute__((amdgpu_waves_per_eu(4, 4))) vo
             const float u = nx_u[s], v = nx_v[s];
             const float a_lo = 1.0f - u, b_lo = 1.0f - v;
             w00[s] = a_lo * b_lo, w10[s] = u * b_lo, w01[s] = a_lo * v, w11[s] = u * v;
-            // piece (j + lp) mod PIECES of the row: from `first` for j < PIECES - lp, one row back
-            // after the wrap
-            first[s] = cur + (unsigned)nx_node[s] * Row::kBytes + (unsigned)lp * 16;
+            // piece (j + l3) mod 4 of the row: from `first` for j < 4 - l3, one row back after the wrap
+            first[s] = cur + (unsigned)nx_node[s] * kHalfRowBytes + (unsigned)l3 * 16;
         }
         asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
         __syncthreads();
@@ -945,34 +934,34 @@ __global__ __launch_bounds__(1024) __attribute__((amdgpu_waves_per_eu(4, 4))) vo
         auto request = [&](CornersRaw &c, int t, float &tie) {
             // (the empty statement ties the addresses to a sum of the piece before last: it keeps the
             // reads of a piece between the multiply-adds of the pieces before it)
-            const int s = t / PIECES, j = t % PIECES;
+            const int s = t >> 2, j = t & 3;
             asm volatile("" : "+v"(first[s]), "+v"(tie));
-            const unsigned addr = (lp + j >= PIECES ? first[s] - Row::kBytes : first[s]) + j * 16;
+            const unsigned addr = (l3 + j >= 4 ? first[s] - kHalfRowBytes : first[s]) + j * 16;
             c.c00 = lds_load_u4(addr);
-            c.c01 = lds_load_u4(addr + Row::kBytes);
-            c.c10 = lds_load_u4(addr + a.W * Row::kBytes);
-            c.c11 = lds_load_u4(addr + a.W * Row::kBytes + Row::kBytes);
+            c.c01 = lds_load_u4(addr + kHalfRowBytes);
+            c.c10 = lds_load_u4(addr + a.W * kHalfRowBytes);
+            c.c11 = lds_load_u4(addr + a.W * kHalfRowBytes + kHalfRowBytes);
         };
-        request(ring[0], 0, acc[SETS - 1][PIECES - 1][PER - 1]);
-        static_for(std::make_integer_sequence<int, STEPS>{}, [&](auto tc) {
+        request(ring[0], 0, acc[SETS - 1][3][7]);
+        static_for(std::make_integer_sequence<int, SETS * 4>{}, [&](auto tc) {
             constexpr int t = decltype(tc)::value;
-            constexpr int s = t / PIECES, j = t % PIECES;
-            constexpr int tp = t > 0 ? t - 1 : STEPS - 1;   // the piece before this one
-            if constexpr (t + 1 < STEPS) request(ring[(t + 1) & 1], t + 1, acc[tp / PIECES][tp % PIECES][PER - 1]);
+            constexpr int s = t >> 2, j = t & 3;
+            constexpr int tp = t > 0 ? t - 1 : SETS * 4 - 1;   // the piece before this one
+            if constexpr (t + 1 < SETS * 4) request(ring[(t + 1) & 1], t + 1, acc[tp >> 2][tp & 3][7]);
             const CornersRaw &c = ring[t & 1];
-            float f[PER];
-            widen_piece<CT>(c.c00, f);
+            float f[8];
+            widen8<CT>(c.c00, f);
 #pragma unroll
-            for (int i = 0; i < PER; ++i) acc[s][j][i] = fmaf(w00[s], f[i], acc[s][j][i]);
-            widen_piece<CT>(c.c10, f);
+            for (int i = 0; i < 8; ++i) acc[s][j][i] = fmaf(w00[s], f[i], acc[s][j][i]);
+            widen8<CT>(c.c10, f);
 #pragma unroll
-            for (int i = 0; i < PER; ++i) acc[s][j][i] = fmaf(w10[s], f[i], acc[s][j][i]);
-            widen_piece<CT>(c.c01, f);
+            for (int i = 0; i < 8; ++i) acc[s][j][i] = fmaf(w10[s], f[i], acc[s][j][i]);
+            widen8<CT>(c.c01, f);
 #pragma unroll
-            for (int i = 0; i < PER; ++i) acc[s][j][i] = fmaf(w01[s], f[i], acc[s][j][i]);
-            widen_piece<CT>(c.c11, f);
+            for (int i = 0; i < 8; ++i) acc[s][j][i] = fmaf(w01[s], f[i], acc[s][j][i]);
+            widen8<CT>(c.c11, f);
 #pragma unroll
-            for (int i = 0; i < PER; ++i) acc[s][j][i] = fmaf(w11[s], f[i], acc[s][j][i]);
+            for (int i = 0; i < 8; ++i) acc[s][j][i] = fmaf(w11[s], f[i], acc[s][j][i]);
         });
     }
 
@@ -983,12 +972,10 @@ __global__ __launch_bounds__(1024) __attribute__((amdgpu_waves_per_eu(4, 4))) vo
         const int64_t n = n0 + s * 64;
         if (n < a.B) {
 #pragma unroll
-            for (int j = 0; j < PIECES; ++j) {
-#pragma unroll
-                for (int q = 0; q < PER; q += 4) {
-                    const int col = jt * kHalfTile + ((j + lp) & (PIECES - 1)) * PER + q;
-                    if (col < a.n_out) store_outputs(ybase + n * a.n_out + col, acc[s][j] + q, a.n_out, col, atomic);
-                }
+            for (int j = 0; j < 4; ++j) {
+                const int col = jt * kHalfTile + ((j + l3) & 3) * 8;
+                if (col < a.n_out) store_outputs(ybase + n * a.n_out + col, acc[s][j], a.n_out, col, atomic);
+                if (col + 4 < a.n_out) store_outputs(ybase + n * a.n_out + col + 4, acc[s][j] + 4, a.n_out, col + 4, atomic);
             }
         }
     }
@@ -998,7 +985,176 @@ template <typename CT>
 __global__ __launch_bounds__(1024) __attribute__((amdgpu_waves_per_eu(4, 4))) void backward_input_lane32_kernel(GradInArgs a)
 {
     extern __shared__ __align__(16) char smem32[];  // two slab buffers, then 1/h of the grid
-    typedef HalfRow<CT> Row;
+    constexpr int WAVES = 16, SETS = 2;
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int l3 = lane & 3;
+    int id = blockIdx.x;
+    const int total = gridDim.x;
+    if ((total & 7) == 0) id = (id & 7) * (total >> 3) + (id >> 3);
+    const int btile = id % a.n_btiles;
+    const int rest = id / a.n_btiles;
+    const int ks = rest % a.n_split;
+    const int jt = rest / a.n_split;   // 32-output tile
+
+    const int k_begin = ks * a.pairs_per_split;
+    const int k_end = min(a.K, k_begin + a.pairs_per_split);
+    const unsigned slab_bytes = (unsigned)a.nodes * kHalfRowBytes;
+    const unsigned base0 = __builtin_amdgcn_readfirstlane(lds_address(smem32));
+    const unsigned base1 = base0 + slab_bytes;
+    float *s_invh = reinterpret_cast<float *>(smem32 + ((2 * slab_bytes + 15) & ~15u));
+    for (int i = threadIdx.x; i < a.tab.G; i += blockDim.x) s_invh[i] = a.tab.inv_h[i];
+
+    // packed table: the rows of (pair, 64-output tile jt / 2) lie 128 bytes apart, this tile is
+    // their half jt & 1; a wave instruction moves 16 rows (four lanes x 16 bytes each)
+    const CT *half = static_cast<const CT *>(a.P) + (int64_t)(jt >> 1) * a.map.s_tile + (jt & 1) * kHalfTile + (lane & 3) * 8;
+    const int chunks = (a.nodes + 15) >> 4;
+    auto issue_fill = [&](unsigned lds_base, int k) {
+        const CT *src = half + (int64_t)k * a.map.s_pair;
+        for (int c = wave; c < chunks; c += WAVES) {
+            const int node = c * 16 + (lane >> 2);
+            if (node < a.nodes) lds_dma16(src + (int64_t)node * a.map.s_node, __builtin_amdgcn_readfirstlane(lds_base + c * 1024));
+        }
+    };
+
+    const int64_t n0 = (int64_t)btile * (WAVES * SETS * 64) + wave * (SETS * 64) + lane;
+    // register block j of a sample: gy of outputs jt*32 + 8 p .. + 7 with p = (j + l3) mod 4
+    float gyr[SETS][4][8];
+#pragma unroll
+    for (int s = 0; s < SETS; ++s) {
+        const int64_t n = n0 + s * 64;
+        const bool valid_s = n < a.B;
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const int col = jt * kHalfTile + ((j + l3) & 3) * 8;
+            const float *src = a.gy + (col >> 6) * a.gy_tile_stride + n * a.gy_row_stride + (col & 63);
+            float4 lo = make_float4(0.f, 0.f, 0.f, 0.f), hi = lo;
+            if (valid_s && col < a.n_out) lo = *reinterpret_cast<const float4 *>(src);
+            if (valid_s && col + 4 < a.n_out) hi = *reinterpret_cast<const float4 *>(src + 4);
+            gyr[s][j][0] = lo.x, gyr[s][j][1] = lo.y, gyr[s][j][2] = lo.z, gyr[s][j][3] = lo.w;
+            gyr[s][j][4] = hi.x, gyr[s][j][5] = hi.y, gyr[s][j][6] = hi.z, gyr[s][j][7] = hi.w;
+        }
+    }
+
+    int nx_node[SETS];
+    float nx_u[SETS], nx_v[SETS];
+    // (a sample past the end of the batch reads the records of the last one; the records of a pair
+    // start at a wave-uniform address, the sample is a 32-bit index into them)
+    unsigned n_rec[SETS];
+#pragma unroll
+    for (int s = 0; s < SETS; ++s) n_rec[s] = (unsigned)min(n0 + s * 64, a.B - 1);
+    auto fetch_records = [&](int k) {
+        const int32_t *r_node = a.rec_node + (int64_t)k * a.B;
+        const float *r_u = a.rec_u + (int64_t)k * a.B, *r_v = a.rec_v + (int64_t)k * a.B;
+#pragma unroll
+        for (int s = 0; s < SETS; ++s) {
+            nx_node[s] = r_node[n_rec[s]];
+            nx_u[s] = r_u[n_rec[s]];
+            nx_v[s] = r_v[n_rec[s]];
+        }
+    };
+    __syncthreads();  // s_invh in place
+    if (k_begin < k_end) {
+        issue_fill(base0, k_begin);
+        fetch_records(k_begin);
+    }
+
+    for (int k = k_begin; k < k_end; ++k) {
+        const unsigned cur = ((k - k_begin) & 1) ? base1 : base0;
+        const unsigned nxt = ((k - k_begin) & 1) ? base0 : base1;
+        int node[SETS];
+        float u[SETS], v[SETS];
+#pragma unroll
+        for (int s = 0; s < SETS; ++s) node[s] = nx_node[s], u[s] = nx_u[s], v[s] = nx_v[s];
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        __syncthreads();
+        if (k + 1 < k_end) {
+            issue_fill(nxt, k + 1);
+            fetch_records(k + 1);
+        }
+        // piece (j + l3) mod 4 of the row: from `first` for j < 4 - l3, one row back after the wrap
+        unsigned first[SETS];
+#pragma unroll
+        for (int s = 0; s < SETS; ++s) first[s] = cur + (unsigned)node[s] * kHalfRowBytes + (unsigned)l3 * 16;
+        float dif_a = 0.f, dif_b = 0.f, dif_c = 0.f, dif_d = 0.f;   // as in backward_input_lane_kernel
+        CornersRaw ring[2];
+        auto request = [&](CornersRaw &c, int t) {
+            // (the empty statement ties the addresses to the sums so far: it keeps the reads of a
+            // piece between the multiply-adds of the pieces before it)
+            const int s = t >> 2, j = t & 3;
+            asm volatile("" : "+v"(first[s]), "+v"(dif_a), "+v"(dif_b), "+v"(dif_c), "+v"(dif_d));
+            const unsigned addr = (l3 + j >= 4 ? first[s] - kHalfRowBytes : first[s]) + j * 16;
+            c.c00 = lds_load_u4(addr);
+            c.c01 = lds_load_u4(addr + kHalfRowBytes);
+            c.c10 = lds_load_u4(addr + a.W * kHalfRowBytes);
+            c.c11 = lds_load_u4(addr + a.W * kHalfRowBytes + kHalfRowBytes);
+        };
+        request(ring[0], 0);
+        static_for(std::make_integer_sequence<int, SETS * 4>{}, [&](auto tc) {
+            constexpr int t = decltype(tc)::value;
+            constexpr int s = t >> 2, j = t & 3;
+            if constexpr (t + 1 < SETS * 4) request(ring[(t + 1) & 1], t + 1);
+            const CornersRaw &c = ring[t & 1];
+            float f[8];
+            float p00 = 0.f, p01 = 0.f, p10 = 0.f, p11 = 0.f;
+            widen8<CT>(c.c00, f);
+#pragma unroll
+            for (int i = 0; i < 8; ++i) p00 = fmaf(gyr[s][j][i], f[i], p00);
+            widen8<CT>(c.c01, f);
+#pragma unroll
+            for (int i = 0; i < 8; ++i) p01 = fmaf(gyr[s][j][i], f[i], p01);
+            widen8<CT>(c.c10, f);
+#pragma unroll
+            for (int i = 0; i < 8; ++i) p10 = fmaf(gyr[s][j][i], f[i], p10);
+            widen8<CT>(c.c11, f);
+#pragma unroll
+            for (int i = 0; i < 8; ++i) p11 = fmaf(gyr[s][j][i], f[i], p11);
+            dif_a += p10 - p00;
+            dif_b += p11 - p01;
+            dif_c += p01 - p00;
+            dif_d += p11 - p10;
+            if constexpr (j == 3) {
+                const int i1 = node[s] / a.W;
+                const float rh1 = s_invh[i1], rh2 = s_invh[node[s] - i1 * a.W];
+                const float d1 = rh1 * (dif_a * (1.0f - v[s]) + dif_b * v[s]);
+                const float d2 = rh2 * (dif_c * (1.0f - u[s]) + dif_d * u[s]);
+                if (n0 + s * 64 < a.B) {
+                    float *dst = a.gx + (int64_t)(2 * k) * a.ld + n0 + s * 64;
+                    unsafeAtomicAdd(dst, d1);
+                    unsafeAtomicAdd(dst + a.ld, d2);
+                }
+                dif_a = dif_b = dif_c = dif_d = 0.f;
+            }
+        });
+    }
+}
+
+// ---------------------------------------------------------------------------
+// The same input gradient for float32 packed tables where two 32-output slabs of 128-byte rows fit
+// LDS (17 <= G <= 24): eight pieces of four outputs per row, read in the order (j + l) mod 8.
+// (The code below is written over the row's constants and would serve the 16-bit tables too; they
+// keep the kernel above, whose loop the compiler schedules about 8 % faster than this form.  A
+// forward kernel of this shape was no faster than forward_slab_narrow_kernel and is not kept.)
+// ---------------------------------------------------------------------------
+struct HalfRowF32 {
+    static constexpr int kBytes = kHalfTile * 4;         // a row of the slab
+    static constexpr int kPieces = kBytes / 16;          // 16-byte pieces per row
+    static constexpr int kPer = 4;                       // outputs per piece
+    static constexpr int kRowsPerFill = 64 / kPieces;    // rows one wave instruction moves
+    static constexpr int kPieceShift = 3;                // log2 of the two above
+    static constexpr int kFillShift = 3;
+};
+
+__device__ __forceinline__ void piece_as_floats(const uint4 raw, float (&f)[4])
+{
+    f[0] = __uint_as_float(raw.x), f[1] = __uint_as_float(raw.y), f[2] = __uint_as_float(raw.z),
+    f[3] = __uint_as_float(raw.w);
+}
+
+__global__ __launch_bounds__(1024) __attribute__((amdgpu_waves_per_eu(4, 4))) void backward_input_lane32_f32_kernel(GradInArgs a)
+{
+    extern __shared__ __align__(16) char smem32[];  // two slab buffers, then 1/h of the grid
+    typedef HalfRowF32 Row;
     constexpr int WAVES = 16, SETS = 2, PIECES = Row::kPieces, PER = Row::kPer, STEPS = SETS * PIECES;
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
@@ -1021,12 +1177,12 @@ __global__ __launch_bounds__(1024) __attribute__((amdgpu_waves_per_eu(4, 4))) vo
 
     // packed table: the rows of (pair, 64-output tile jt / 2) lie 64 elements apart, this tile is
     // their half jt & 1; a wave instruction moves 1024 bytes (PIECES lanes x 16 bytes per row)
-    const CT *half = static_cast<const CT *>(a.P) + (int64_t)(jt >> 1) * a.map.s_tile + (jt & 1) * kHalfTile + lp * PER;
-    const int chunks = (a.nodes + Row::kRowsPerFill - 1) / Row::kRowsPerFill;
+    const float *half = static_cast<const float *>(a.P) + (int64_t)(jt >> 1) * a.map.s_tile + (jt & 1) * kHalfTile + lp * PER;
+    const int chunks = (a.nodes + Row::kRowsPerFill - 1) >> Row::kFillShift;
     auto issue_fill = [&](unsigned lds_base, int k) {
-        const CT *src = half + (int64_t)k * a.map.s_pair;
+        const float *src = half + (int64_t)k * a.map.s_pair;
         for (int c = wave; c < chunks; c += WAVES) {
-            const int node = c * Row::kRowsPerFill + lane / PIECES;
+            const int node = c * Row::kRowsPerFill + (lane >> Row::kPieceShift);
             if (node < a.nodes) lds_dma16(src + (int64_t)node * a.map.s_node, __builtin_amdgcn_readfirstlane(lds_base + c * 1024));
         }
     };
@@ -1040,14 +1196,11 @@ __global__ __launch_bounds__(1024) __attribute__((amdgpu_waves_per_eu(4, 4))) vo
         const bool valid_s = n < a.B;
 #pragma unroll
         for (int j = 0; j < PIECES; ++j) {
-#pragma unroll
-            for (int q = 0; q < PER; q += 4) {
-                const int col = jt * kHalfTile + ((j + lp) & (PIECES - 1)) * PER + q;
-                const float *src = a.gy + (col >> 6) * a.gy_tile_stride + n * a.gy_row_stride + (col & 63);
-                float4 g = make_float4(0.f, 0.f, 0.f, 0.f);
-                if (valid_s && col < a.n_out) g = *reinterpret_cast<const float4 *>(src);
-                gyr[s][j][q] = g.x, gyr[s][j][q + 1] = g.y, gyr[s][j][q + 2] = g.z, gyr[s][j][q + 3] = g.w;
-            }
+            const int col = jt * kHalfTile + ((j + lp) & (PIECES - 1)) * PER;
+            const float *src = a.gy + (col >> 6) * a.gy_tile_stride + n * a.gy_row_stride + (col & 63);
+            float4 g = make_float4(0.f, 0.f, 0.f, 0.f);
+            if (valid_s && col < a.n_out) g = *reinterpret_cast<const float4 *>(src);
+            gyr[s][j][0] = g.x, gyr[s][j][1] = g.y, gyr[s][j][2] = g.z, gyr[s][j][3] = g.w;
         }
     }
 
@@ -1113,16 +1266,16 @@ __global__ __launch_bounds__(1024) __attribute__((amdgpu_waves_per_eu(4, 4))) vo
             const CornersRaw &c = ring[t & 1];
             float f[PER];
             float p00 = 0.f, p01 = 0.f, p10 = 0.f, p11 = 0.f;
-            widen_piece<CT>(c.c00, f);
+            piece_as_floats(c.c00, f);
 #pragma unroll
             for (int i = 0; i < PER; ++i) p00 = fmaf(gyr[s][j][i], f[i], p00);
-            widen_piece<CT>(c.c01, f);
+            piece_as_floats(c.c01, f);
 #pragma unroll
             for (int i = 0; i < PER; ++i) p01 = fmaf(gyr[s][j][i], f[i], p01);
-            widen_piece<CT>(c.c10, f);
+            piece_as_floats(c.c10, f);
 #pragma unroll
             for (int i = 0; i < PER; ++i) p10 = fmaf(gyr[s][j][i], f[i], p10);
-            widen_piece<CT>(c.c11, f);
+            piece_as_floats(c.c11, f);
 #pragma unroll
             for (int i = 0; i < PER; ++i) p11 = fmaf(gyr[s][j][i], f[i], p11);
             dif_a += p10 - p00;
@@ -1587,15 +1740,18 @@ bool slab_forward_shape_ok(const LayerShape &s)
 bool slab_tile_is_wide(const LayerShape &s) { return slab_wide_fits(s); }
 
 // Packed tables on the grids that stream two 16-output slabs, where two 32-output slabs as stored
-// fit LDS as well (16-bit: all of those grids, float32: G <= 24): forward_lane32_kernel and
-// backward_input_lane32_kernel
+// fit LDS as well (16-bit: all of those grids, float32: G <= 24): backward_input_lane32_kernel,
+// backward_input_lane32_f32_kernel and, for 16-bit tables, forward_lane32_kernel
 static size_t half_tile_row_bytes(const LayerShape &s) { return (size_t)kHalfTile * (s.dtype == LMKAN_F32 ? 4 : 2); }
 static bool slab_half_tiles_fit(const LayerShape &s)
 {
     return slab_narrow_fits(s) && s.layout == LMKAN_LAYOUT_PACKED &&
            (size_t)2 * s.nodes() * half_tile_row_bytes(s) + LMKAN_MAX_GRID * sizeof(float) <= 160 * 1024;
 }
-bool slab_forward_takes_half_tiles(const LayerShape &s) { return slab_batch_ok(s, true) && slab_half_tiles_fit(s); }
+bool slab_forward_takes_half_tiles(const LayerShape &s)
+{
+    return slab_batch_ok(s, true) && slab_half_tiles_fit(s) && s.dtype != LMKAN_F32;
+}
 
 // Samples per forward workgroup: 1024 with 64-output tiles, 4096 with 16-output tiles, 2048 with
 // 32-output tiles.
@@ -1665,9 +1821,7 @@ static void launch_forward_slab_narrow(const LayerShape &s, const void *coef, fl
     constexpr int kTileB = WAVES * SETS * 64;
     typedef void (*Kernel)(SlabArgs);
     if (slab_forward_takes_half_tiles(s)) {
-        const Kernel k32 = s.dtype == LMKAN_F32   ? forward_lane32_kernel<float>
-                           : s.dtype == LMKAN_F16 ? forward_lane32_kernel<_Float16>
-                                                  : forward_lane32_kernel<bf16_t>;
+        const Kernel k32 = s.dtype == LMKAN_F16 ? forward_lane32_kernel<_Float16> : forward_lane32_kernel<bf16_t>;
         allow_large_lds(reinterpret_cast<const void *>(k32), 160 * 1024);
         const size_t nrec = (size_t)s.pairs() * (size_t)s.batch;
         SlabArgs a;
@@ -1926,7 +2080,7 @@ void launch_backward_input_slab(const LayerShape &s, const GridTab &tab, const v
     // packed tables on the grids of the 16-output tiles: 32-output tiles kept as stored where two fit
     const bool lane32 = slab_backward_input_takes_half_tiles(s);
     if (lane32) {
-        const Kernel k32 = s.dtype == LMKAN_F32   ? backward_input_lane32_kernel<float>
+        const Kernel k32 = s.dtype == LMKAN_F32   ? backward_input_lane32_f32_kernel
                            : s.dtype == LMKAN_F16 ? backward_input_lane32_kernel<_Float16>
                                                   : backward_input_lane32_kernel<bf16_t>;
         allow_large_lds(reinterpret_cast<const void *>(k32), 160 * 1024);
