@@ -73,7 +73,7 @@ def kernel_names(w, n_out, B, storage, packed):
         if packed and storage != "f32":
             fwd, gx = "forward_lane32_kernel", "backward_input_lane32_kernel"
         elif packed and 2 * (w.grid + 1) ** 2 * 128 + 256 <= 160 * 1024:
-            gx = "backward_input_lane32_f32_kernel"
+            fwd, gx = "forward_lane32_f32_kernel", "backward_input_lane32_f32_kernel"
         elif B >= 16 * w.grid * w.grid:
             both = "backward_fused_kernel"
     elif ok:

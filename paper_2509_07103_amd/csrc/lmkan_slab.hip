@@ -1130,11 +1130,10 @@ __global__ __launch_bounds__(1024) __attribute__((amdgpu_waves_per_eu(4, 4))) vo
 }
 
 // ---------------------------------------------------------------------------
-// The same input gradient for float32 packed tables where two 32-output slabs of 128-byte rows fit
+// The same pair of kernels for float32 packed tables where two 32-output slabs of 128-byte rows fit
 // LDS (17 <= G <= 24): eight pieces of four outputs per row, read in the order (j + l) mod 8.
 // (The code below is written over the row's constants and would serve the 16-bit tables too; they
-// keep the kernel above, whose loop the compiler schedules about 8 % faster than this form.  A
-// forward kernel of this shape was no faster than forward_slab_narrow_kernel and is not kept.)
+// keep the kernels above, whose loops the compiler schedules about 8 % faster than this form.)
 // ---------------------------------------------------------------------------
 struct HalfRowF32 {
     static constexpr int kBytes = kHalfTile * 4;         // a row of the slab
@@ -1295,6 +1294,158 @@ __global__ __launch_bounds__(1024) __attribute__((amdgpu_waves_per_eu(4, 4))) vo
                 dif_a = dif_b = dif_c = dif_d = 0.f;
             }
         });
+    }
+}
+
+// Forward on the same tiles: the 32 outputs of a sample's tile in registers, stored in the rotated
+// order of the pieces.  Rows of 128 bytes alternate between the two halves of the LDS banks, and
+// lanes l and l + 8 of a 16-lane group read the same piece of their rows.  Lanes 0-7 therefore
+// start with whichever of their cell's rows r, r + 1 lies in the lower half and lanes 8-15 with
+// the one in the upper half (rows r + W, r + W + 1 follow suit: they flip both or neither), and the
+// four weights go to the rows as the lane reads them: no two lanes of a group meet on a bank.
+// (The input gradient above does not do this: it is bound by its vector instructions, and the two
+// extra address additions per piece cost it more than the conflicts do.)
+__global__ __launch_bounds__(1024) __attribute__((amdgpu_waves_per_eu(4, 4))) void forward_lane32_f32_kernel(SlabArgs a)
+{
+    extern __shared__ __align__(16) char smem32[];  // two slab buffers
+    typedef HalfRowF32 Row;
+    constexpr int WAVES = 16, SETS = 2, PIECES = Row::kPieces, PER = Row::kPer, STEPS = SETS * PIECES;
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int lp = lane & (PIECES - 1);
+    int id = blockIdx.x;
+    const int total = gridDim.x;
+    if ((total & 7) == 0) id = (id & 7) * (total >> 3) + (id >> 3);
+    const int btile = id % a.n_btiles;
+    const int rest = id / a.n_btiles;
+    const int ks = rest % a.n_split;
+    const int jt = rest / a.n_split;   // 32-output tile
+
+    const int k_begin = ks * a.pairs_per_split;
+    const int k_end = min(a.K, k_begin + a.pairs_per_split);
+    const unsigned slab_bytes = (unsigned)a.nodes * Row::kBytes;
+    const unsigned base0 = __builtin_amdgcn_readfirstlane(lds_address(smem32));
+    const unsigned base1 = base0 + slab_bytes;
+
+    // packed table: the rows of (pair, 64-output tile jt / 2) lie 64 elements apart, this tile is
+    // their half jt & 1; a wave instruction moves 1024 bytes (PIECES lanes x 16 bytes per row)
+    const float *half = static_cast<const float *>(a.P) + (int64_t)(jt >> 1) * a.map.s_tile + (jt & 1) * kHalfTile + lp * PER;
+    const int chunks = (a.nodes + Row::kRowsPerFill - 1) >> Row::kFillShift;
+    auto issue_fill = [&](unsigned lds_base, int k) {
+        const float *src = half + (int64_t)k * a.map.s_pair;
+        for (int c = wave; c < chunks; c += WAVES) {
+            const int node = c * Row::kRowsPerFill + (lane >> Row::kPieceShift);
+            if (node < a.nodes) lds_dma16(src + (int64_t)node * a.map.s_node, __builtin_amdgcn_readfirstlane(lds_base + c * 1024));
+        }
+    };
+
+    const int64_t n0 = (int64_t)btile * (WAVES * SETS * 64) + wave * (SETS * 64) + lane;
+    // register block j of a sample: outputs jt*32 + PER p .. + PER - 1 with p = (j + lp) mod PIECES
+    float acc[SETS][PIECES][PER];
+#pragma unroll
+    for (int s = 0; s < SETS; ++s)
+#pragma unroll
+        for (int j = 0; j < PIECES; ++j)
+#pragma unroll
+            for (int i = 0; i < PER; ++i) acc[s][j][i] = 0.0f;
+
+    // (a sample past the end of the batch reads the records of the last one; the records of a pair
+    // start at a wave-uniform address, the sample is a 32-bit index into them)
+    unsigned n_rec[SETS];
+#pragma unroll
+    for (int s = 0; s < SETS; ++s) n_rec[s] = (unsigned)min(n0 + s * 64, a.B - 1);
+    int nx_node[SETS];
+    float nx_u[SETS], nx_v[SETS];
+    auto fetch_records = [&](int k) {
+        const int32_t *r_node = a.rec_node + (int64_t)k * a.B;
+        const float *r_u = a.rec_u + (int64_t)k * a.B, *r_v = a.rec_v + (int64_t)k * a.B;
+#pragma unroll
+        for (int s = 0; s < SETS; ++s) {
+            nx_node[s] = r_node[n_rec[s]];
+            nx_u[s] = r_u[n_rec[s]];
+            nx_v[s] = r_v[n_rec[s]];
+        }
+    };
+    if (k_begin < k_end) {
+        issue_fill(base0, k_begin);
+        fetch_records(k_begin);
+    }
+
+    for (int k = k_begin; k < k_end; ++k) {
+        const unsigned cur = ((k - k_begin) & 1) ? base1 : base0;
+        const unsigned nxt = ((k - k_begin) & 1) ? base0 : base1;
+        // rows as the lane reads them (A, B = r, r + 1, or swapped where that keeps lanes l and
+        // l + 8 on different halves of the banks; C, D = A, B + W rows) and their weights
+        unsigned first[SETS];
+        int to_other[SETS];
+        float w_a[SETS], w_b[SETS], w_c[SETS], w_d[SETS];
+#pragma unroll
+        for (int s = 0; s < SETS; ++s) {
+            const float u = nx_u[s], v = nx_v[s];
+            const float a_lo = 1.0f - u, b_lo = 1.0f - v;
+            const float w00 = a_lo * b_lo, w10 = u * b_lo, w01 = a_lo * v, w11 = u * v;
+            const unsigned sw = ((unsigned)nx_node[s] ^ (unsigned)(lane >> 3)) & 1u;
+            w_a[s] = sw ? w01 : w00, w_b[s] = sw ? w00 : w01;
+            w_c[s] = sw ? w11 : w10, w_d[s] = sw ? w10 : w11;
+            // piece (j + lp) mod PIECES of the row: from `first` for j < PIECES - lp, one row back
+            // after the wrap
+            first[s] = cur + ((unsigned)nx_node[s] + sw) * Row::kBytes + (unsigned)lp * 16;
+            to_other[s] = sw ? -Row::kBytes : Row::kBytes;
+        }
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        __syncthreads();
+        if (k + 1 < k_end) {
+            issue_fill(nxt, k + 1);
+            fetch_records(k + 1);
+        }
+        CornersRaw ring[2];
+        auto request = [&](CornersRaw &c, int t, float &tie) {
+            // (the empty statement ties the addresses to a sum of the piece before last: it keeps the
+            // reads of a piece between the multiply-adds of the pieces before it)
+            const int s = t / PIECES, j = t % PIECES;
+            asm volatile("" : "+v"(first[s]), "+v"(tie));
+            const unsigned addr = (lp + j >= PIECES ? first[s] - Row::kBytes : first[s]) + j * 16;
+            const unsigned other = addr + to_other[s];
+            c.c00 = lds_load_u4(addr);
+            c.c01 = lds_load_u4(other);
+            c.c10 = lds_load_u4(addr + a.W * Row::kBytes);
+            c.c11 = lds_load_u4(other + a.W * Row::kBytes);
+        };
+        request(ring[0], 0, acc[SETS - 1][PIECES - 1][PER - 1]);
+        static_for(std::make_integer_sequence<int, STEPS>{}, [&](auto tc) {
+            constexpr int t = decltype(tc)::value;
+            constexpr int s = t / PIECES, j = t % PIECES;
+            constexpr int tp = t > 0 ? t - 1 : STEPS - 1;   // the piece before this one
+            if constexpr (t + 1 < STEPS) request(ring[(t + 1) & 1], t + 1, acc[tp / PIECES][tp % PIECES][PER - 1]);
+            const CornersRaw &c = ring[t & 1];
+            float f[PER];
+            piece_as_floats(c.c00, f);
+#pragma unroll
+            for (int i = 0; i < PER; ++i) acc[s][j][i] = fmaf(w_a[s], f[i], acc[s][j][i]);
+            piece_as_floats(c.c10, f);
+#pragma unroll
+            for (int i = 0; i < PER; ++i) acc[s][j][i] = fmaf(w_c[s], f[i], acc[s][j][i]);
+            piece_as_floats(c.c01, f);
+#pragma unroll
+            for (int i = 0; i < PER; ++i) acc[s][j][i] = fmaf(w_b[s], f[i], acc[s][j][i]);
+            piece_as_floats(c.c11, f);
+#pragma unroll
+            for (int i = 0; i < PER; ++i) acc[s][j][i] = fmaf(w_d[s], f[i], acc[s][j][i]);
+        });
+    }
+
+    bool atomic;
+    float *ybase = forward_out_base(a, ks, atomic);
+#pragma unroll
+    for (int s = 0; s < SETS; ++s) {
+        const int64_t n = n0 + s * 64;
+        if (n < a.B) {
+#pragma unroll
+            for (int j = 0; j < PIECES; ++j) {
+                const int col = jt * kHalfTile + ((j + lp) & (PIECES - 1)) * PER;
+                if (col < a.n_out) store_outputs(ybase + n * a.n_out + col, acc[s][j], a.n_out, col, atomic);
+            }
+        }
     }
 }
 
@@ -1740,8 +1891,7 @@ bool slab_forward_shape_ok(const LayerShape &s)
 bool slab_tile_is_wide(const LayerShape &s) { return slab_wide_fits(s); }
 
 // Packed tables on the grids that stream two 16-output slabs, where two 32-output slabs as stored
-// fit LDS as well (16-bit: all of those grids, float32: G <= 24): backward_input_lane32_kernel,
-// backward_input_lane32_f32_kernel and, for 16-bit tables, forward_lane32_kernel
+// fit LDS as well (16-bit: all of those grids, float32: G <= 24): the lane32 kernels
 static size_t half_tile_row_bytes(const LayerShape &s) { return (size_t)kHalfTile * (s.dtype == LMKAN_F32 ? 4 : 2); }
 static bool slab_half_tiles_fit(const LayerShape &s)
 {
@@ -1750,7 +1900,7 @@ static bool slab_half_tiles_fit(const LayerShape &s)
 }
 bool slab_forward_takes_half_tiles(const LayerShape &s)
 {
-    return slab_batch_ok(s, true) && slab_half_tiles_fit(s) && s.dtype != LMKAN_F32;
+    return slab_batch_ok(s, true) && slab_half_tiles_fit(s);
 }
 
 // Samples per forward workgroup: 1024 with 64-output tiles, 4096 with 16-output tiles, 2048 with
@@ -1821,7 +1971,9 @@ static void launch_forward_slab_narrow(const LayerShape &s, const void *coef, fl
     constexpr int kTileB = WAVES * SETS * 64;
     typedef void (*Kernel)(SlabArgs);
     if (slab_forward_takes_half_tiles(s)) {
-        const Kernel k32 = s.dtype == LMKAN_F16 ? forward_lane32_kernel<_Float16> : forward_lane32_kernel<bf16_t>;
+        const Kernel k32 = s.dtype == LMKAN_F32   ? forward_lane32_f32_kernel
+                           : s.dtype == LMKAN_F16 ? forward_lane32_kernel<_Float16>
+                                                  : forward_lane32_kernel<bf16_t>;
         allow_large_lds(reinterpret_cast<const void *>(k32), 160 * 1024);
         const size_t nrec = (size_t)s.pairs() * (size_t)s.batch;
         SlabArgs a;
