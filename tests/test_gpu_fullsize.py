@@ -6,6 +6,8 @@ outputs one by one: random rows for forward and the input gradient, random pair 
 (over all rows: a slice of the coefficient gradient depends on one pair only) for the
 coefficient gradient.  Cell indices are compared bit for bit on every element.
 Tolerances as in the small-shape parity tests (row-wise max norm)."""
+import dataclasses
+
 import numpy as np
 import pytest
 import torch
@@ -114,6 +116,15 @@ def test_cfg2_last_layer_backward(dev, oracle):
 @pytest.mark.parametrize("storage", ["f32", "f16"])
 def test_cfg3_headline(dev, oracle, storage):
     _check_layer(wl.CFG3, storage, dev, oracle, n_rows=256 if storage == "f32" else 128, n_pairs=8)
+
+
+@pytest.mark.parametrize("grid", [20, 24])
+def test_cfg3_shape_on_the_papers_finer_grids(dev, oracle, grid):
+    """The cfg3 layer on G = 20 (the grid of the paper's kernel benchmark, appendix on the CUDA
+    kernels) and on the largest grid whose float32 table still takes 32-output tiles, in the
+    launch configuration `bench.py --grid` times."""
+    w = dataclasses.replace(wl.CFG3, grid=grid, name=f"{wl.CFG3.name}@G={grid}")
+    _check_layer(w, "f32", dev, oracle, n_rows=128, n_pairs=4)
 
 
 def test_cfg3_hessian_regulariser(dev, oracle):
