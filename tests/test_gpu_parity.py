@@ -102,6 +102,8 @@ SHAPES = [
     (1100, 140, 66, 16),
     (300, 4, 8, 64),
     (300, 4, 3, 64),
+    # 32-output tiles with the pairs split over several workgroups (partial sums, atomics)
+    (2100, 64, 40, 22),
     # batches under 256 rows on layers wide enough for the slab kernels anyway (pairs x outputs
     # >= 8192), down to a single row; 16-output slabs, the single-slab forward, a ragged head
     (1, 128, 128, 16),
